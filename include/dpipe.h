@@ -1,0 +1,153 @@
+/*
+ * dpipe -- C ABI of the stage-compute hot path for MI355X (gfx950).
+ *
+ * What it computes: the per-micro-batch work of ONE pipeline stage of a diffusion
+ * backbone -- the forward and backward of a contiguous range of transformer blocks
+ * (the quantity sum_l P^f_l + sum_l P^b_l that defines a stage's time T_0(s), Sec. 4.1,
+ * equation for T_0) -- the additional no-grad forward of self-conditioning (Sec. 4.3,
+ * equation for T_{0,SC}: 2 sum P^f + sum P^b), and the frozen text encoder's forward on
+ * a partial batch (Sec. 5: partial-batch layer (component, layer, #samples); input split
+ * and output concatenation across pipeline bubbles), plus the per-layer timing export in
+ * the cost-profile form the partitioner consumes (Table "Notations": P^f_l(B), P^b_l(B),
+ * C^f, C^b, G_l, O_l).
+ *
+ * Conventions
+ *  - Every pointer marked [device] is HIP device memory owned by the caller; the library
+ *    never allocates, frees or synchronises in stage_fwd / stage_bwd /
+ *    encoder_fwd_partial.  `params` / `dparams` are HOST arrays of device pointers.
+ *  - `hip_stream` is a hipStream_t passed as void*; all work is enqueued on it in order.
+ *  - Tensors are row-major with the last dimension contiguous.  Storage dtype is the
+ *    descriptor's dtype (bf16 or fp32); parameter gradients are always fp32.
+ *  - Weights are [out_features, in_features] (y = x W^T).
+ *  - Every function returns DP_OK (0) or a negative error code; nothing throws or aborts.
+ *    Invalid descriptors, NULL or misaligned pointers (16 bytes), too-small workspaces and
+ *    unsupported shapes are rejected on the host before anything is launched.
+ *    dp_last_error() gives the calling thread's last message.
+ */
+#ifndef DPIPE_H
+#define DPIPE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct dp_stage dp_stage;     /* opaque, host memory */
+typedef struct dp_encoder dp_encoder; /* opaque, host memory */
+
+enum { DP_OK = 0, DP_EINVAL = -1, DP_EUNSUPPORTED = -2, DP_EWORKSPACE = -3, DP_EALIGN = -4, DP_EHIP = -5 };
+enum dp_block_kind { DP_BLOCK_UNET_XATTN_GEGLU = 0, DP_BLOCK_DIT_ADALN_ZERO = 1 };
+enum dp_dtype { DP_F32 = 0, DP_BF16 = 1 };
+
+/* A stage = n_blocks identical transformer blocks on a micro-batch of `batch` samples
+ * with `tokens` tokens of width d_model = n_heads * d_head.
+ *  DP_BLOCK_UNET_XATTN_GEGLU: pre-LN self-attention (no q/k/v bias), pre-LN cross-attention
+ *    to ctx [batch, ctx_tokens, ctx_dim] (frozen text-encoder states, Sec. 2.1; no gradient
+ *    to ctx), pre-LN GeGLU feed-forward with hidden width ff_inner (value half first, erf GELU).
+ *  DP_BLOCK_DIT_ADALN_ZERO: (shift,scale,gate)x2 = Linear(SiLU(cond)); modulated non-affine LN;
+ *    self-attention and a GELU MLP of width ff_inner, each gated into the residual.
+ *    gelu_tanh selects the tanh approximation.  ctx_tokens / ctx_dim are ignored.
+ * bf16 limits: d_model, ctx_dim, ff_inner multiples of 8; d_head multiple of 8, <= 96;
+ * d_model <= 2048.  fp32 limits: multiples of 4, d_model <= 1024, tokens <= 7500. */
+typedef struct {
+  int kind, dtype, n_blocks, batch, tokens, d_model, n_heads, d_head, ctx_tokens, ctx_dim, ff_inner;
+  float ln_eps;
+  int gelu_tanh;
+} dp_stage_desc;
+
+/* Validates desc and creates a host-side handle.  *out is untouched on error. */
+int dp_stage_create(const dp_stage_desc* desc, dp_stage** out);
+void dp_stage_destroy(dp_stage* st);
+
+/* Parameters are passed as a flat array in a fixed order: block 0's tensors, block 1's, ...
+ * U-Net block (17): ln1_g ln1_b attn1_wqkv[3d,d] attn1_wo attn1_bo ln2_g ln2_b attn2_wq
+ *   attn2_wkv[2d,ctx_dim] attn2_wo attn2_bo ln3_g ln3_b ff_w1[2*inner,d] ff_b1 ff_w2[d,inner] ff_b2
+ * DiT block (10): ada_w[6d,d] ada_b attn_wqkv[3d,d] attn_bqkv attn_wo attn_bo fc1_w fc1_b fc2_w fc2_b
+ * dp_stage_param_shape: shape[1] = 0 for vectors; *name points to static storage
+ * ("block<i>.<tensor>"). */
+int dp_stage_param_count(const dp_stage* st);
+int dp_stage_param_shape(const dp_stage* st, int idx, int64_t shape[2], const char** name);
+
+/* Bytes of caller-provided workspace [device].  save_for_bwd = 1: saved activations of all
+ * blocks plus backward scratch (pass the same workspace to stage_bwd).  0: scratch for a
+ * forward that keeps nothing (the self-conditioning pass).  The workspace must be
+ * 256-byte aligned. */
+size_t dp_stage_workspace_bytes(const dp_stage* st, int save_for_bwd);
+
+/* y = blocks(x).  x, y [device]: [batch, tokens, d_model].  ctx_or_cond [device]:
+ * ctx [batch, ctx_tokens, ctx_dim] (U-Net) or cond [batch, d_model] (DiT).
+ * save_for_bwd = 0 is the extra forward of self-conditioning (Sec. 4.3): it touches only
+ * the workspace it is given, so it may run between another workspace's forward and backward. */
+int stage_fwd(dp_stage* st, const void* const* params, const void* x, const void* ctx_or_cond, void* y,
+              void* workspace, size_t workspace_bytes, int save_for_bwd, void* hip_stream);
+
+/* Backward of the last stage_fwd(save_for_bwd = 1) on this workspace.  dy, dx [device]:
+ * [batch, tokens, d_model].  d_cond [device]: fp32 [batch, d_model], DiT only (else NULL),
+ * overwritten with the sum over blocks.  dparams: host array of fp32 device buffers, one per
+ * parameter, same order and shapes; accumulate = 1 adds to them (micro-batch accumulation
+ * before the pipeline flush), 0 overwrites. */
+int stage_bwd(dp_stage* st, const void* const* params, const void* dy, const void* ctx_or_cond, void* dx,
+              void* d_cond, void* const* dparams, int accumulate, void* workspace, size_t workspace_bytes,
+              void* hip_stream);
+
+/* Frozen text encoder (Sec. 2.1), forward only.  Pre-LN causal (causal = 1) transformer,
+ * biases on every projection, quick-GELU MLP, final LayerNorm.
+ * Parameter order: tok_emb[vocab,d] pos_emb[seq,d], then per layer (12 tensors): ln1_g ln1_b
+ * wqkv[3d,d] bqkv wo bo ln2_g ln2_b fc1_w[ff,d] fc1_b fc2_w[d,ff] fc2_b, then lnf_g lnf_b. */
+typedef struct {
+  int dtype, n_layers, d_model, n_heads, d_head, seq, vocab, ff_inner, causal;
+  float ln_eps;
+} dp_encoder_desc;
+
+int dp_encoder_create(const dp_encoder_desc* desc, dp_encoder** out);
+void dp_encoder_destroy(dp_encoder* enc);
+int dp_encoder_param_count(const dp_encoder* enc);
+int dp_encoder_param_shape(const dp_encoder* enc, int idx, int64_t shape[2], const char** name);
+/* Workspace bytes for a call on at most max_samples samples. */
+size_t dp_encoder_workspace_bytes(const dp_encoder* enc, int max_samples);
+
+/* Runs layers [layer_begin, layer_end) on samples [sample_offset, sample_offset + num_samples)
+ * of the global batch: the partial-batch layer tuple of Sec. 5.  Layer 0 = embedding
+ * (+ position), 1..n_layers = transformer layers, n_layers + 1 = final LayerNorm.
+ * ids [device]: int32 [global_batch, seq] (ids outside [0, vocab) are clamped).
+ * hidden [device]: [global_batch, seq, d_model], read (unless layer_begin = 0) and written
+ * in place for the selected samples only; other rows are untouched, so calls on disjoint
+ * sample ranges can be issued in any order or in different bubbles. */
+int encoder_fwd_partial(dp_encoder* enc, const void* const* params, const int32_t* ids, void* hidden,
+                        int global_batch, int layer_begin, int layer_end, int sample_offset, int num_samples,
+                        void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* One row of the cost profile (Table "Notations"): forward / backward time of layer `layer`
+ * of component `component` at batch size `batch` (ms, median of reps), its output size O_l
+ * (= the forward activation C^f_{l,l+1} sent to the next layer), the backward message
+ * C^b_{l+1,l} and the gradient size G_l, in bytes.  component 0 = backbone stage (layer =
+ * block index), 1 = text encoder (layer in the index space above; bwd_ms = 0, grad_bytes = 0). */
+typedef struct {
+  int component, layer, batch;
+  float fwd_ms, bwd_ms;
+  int64_t out_bytes, cf_bytes, cb_bytes, grad_bytes;
+} dp_layer_cost;
+
+/* Times every block's forward and backward (reps >= 1 repetitions each, hipEvents on the
+ * stream; this call synchronises).  Same buffers as stage_fwd / stage_bwd; dparams are
+ * overwritten.  Writes n_blocks rows. */
+int dp_stage_profile(dp_stage* st, const void* const* params, const void* x, const void* ctx_or_cond, void* y,
+                     const void* dy, void* dx, void* d_cond, void* const* dparams, void* workspace,
+                     size_t workspace_bytes, int reps, dp_layer_cost* rows, int max_rows, int* n_rows,
+                     void* hip_stream);
+
+/* Times every encoder layer at each requested partial-batch size (samples [0, b)).
+ * Writes (n_layers + 2) * n_batches rows. */
+int dp_encoder_profile(dp_encoder* enc, const void* const* params, const int32_t* ids, void* hidden,
+                       int global_batch, const int* batches, int n_batches, int reps, void* workspace,
+                       size_t workspace_bytes, dp_layer_cost* rows, int max_rows, int* n_rows, void* hip_stream);
+
+/* Thread-local description of the last error; never NULL. */
+const char* dp_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DPIPE_H */

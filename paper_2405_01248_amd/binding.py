@@ -1,0 +1,206 @@
+"""ctypes binding of libdpipe.so -- same names and arguments as include/dpipe.h.
+
+Argument marshalling only: tensors are passed as raw device pointers
+(``tensor.data_ptr()``), the stream as ``torch.cuda.current_stream().cuda_stream``.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Sequence
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB = None
+
+DP_F32, DP_BF16 = 0, 1
+KIND_UNET, KIND_DIT = 0, 1
+
+
+class DpipeError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__(f"dpipe error {code}: {msg}")
+        self.code = code
+
+
+class StageDesc(C.Structure):
+    _fields_ = [(n, C.c_int) for n in ("kind", "dtype", "n_blocks", "batch", "tokens", "d_model", "n_heads", "d_head",
+                                       "ctx_tokens", "ctx_dim", "ff_inner")] + [("ln_eps", C.c_float), ("gelu_tanh", C.c_int)]
+
+
+class EncoderDesc(C.Structure):
+    _fields_ = [(n, C.c_int) for n in ("dtype", "n_layers", "d_model", "n_heads", "d_head", "seq", "vocab", "ff_inner",
+                                       "causal")] + [("ln_eps", C.c_float)]
+
+
+class LayerCost(C.Structure):
+    _fields_ = [("component", C.c_int), ("layer", C.c_int), ("batch", C.c_int), ("fwd_ms", C.c_float), ("bwd_ms", C.c_float),
+                ("out_bytes", C.c_int64), ("cf_bytes", C.c_int64), ("cb_bytes", C.c_int64), ("grad_bytes", C.c_int64)]
+
+    def as_dict(self):
+        return {n: getattr(self, n) for n, _ in self._fields_}
+
+
+EXPORTS = ["dp_stage_create", "dp_stage_destroy", "dp_stage_param_count", "dp_stage_param_shape", "dp_stage_workspace_bytes",
+           "stage_fwd", "stage_bwd", "dp_encoder_create", "dp_encoder_destroy", "dp_encoder_param_count",
+           "dp_encoder_param_shape", "dp_encoder_workspace_bytes", "encoder_fwd_partial", "dp_stage_profile",
+           "dp_encoder_profile", "dp_last_error"]
+
+
+def library_path() -> str:
+    return os.path.join(_HERE, "libdpipe.so")
+
+
+def load_library():
+    """Loads libdpipe.so (built by paper_2405_01248_amd/build.py).  Raises if it is missing."""
+    global _LIB
+    if _LIB is not None:
+        return _LIB
+    path = library_path()
+    if not os.path.exists(path):
+        raise RuntimeError(f"{path} not found: build it with `python -m paper_2405_01248_amd.build` "
+                           "(there is no fallback path)")
+    lib = C.CDLL(path)
+    vp, pp, i, sz = C.c_void_p, C.POINTER(C.c_void_p), C.c_int, C.c_size_t
+    lib.dp_last_error.restype = C.c_char_p
+    lib.dp_stage_create.argtypes = [C.POINTER(StageDesc), pp]
+    lib.dp_stage_destroy.argtypes = [vp]; lib.dp_stage_destroy.restype = None
+    lib.dp_stage_param_count.argtypes = [vp]
+    lib.dp_stage_param_shape.argtypes = [vp, i, C.POINTER(C.c_int64), C.POINTER(C.c_char_p)]
+    lib.dp_stage_workspace_bytes.argtypes = [vp, i]; lib.dp_stage_workspace_bytes.restype = sz
+    lib.stage_fwd.argtypes = [vp, pp, vp, vp, vp, vp, sz, i, vp]
+    lib.stage_bwd.argtypes = [vp, pp, vp, vp, vp, vp, pp, i, vp, sz, vp]
+    lib.dp_encoder_create.argtypes = [C.POINTER(EncoderDesc), pp]
+    lib.dp_encoder_destroy.argtypes = [vp]; lib.dp_encoder_destroy.restype = None
+    lib.dp_encoder_param_count.argtypes = [vp]
+    lib.dp_encoder_param_shape.argtypes = [vp, i, C.POINTER(C.c_int64), C.POINTER(C.c_char_p)]
+    lib.dp_encoder_workspace_bytes.argtypes = [vp, i]; lib.dp_encoder_workspace_bytes.restype = sz
+    lib.encoder_fwd_partial.argtypes = [vp, pp, vp, vp, i, i, i, i, i, vp, sz, vp]
+    lib.dp_stage_profile.argtypes = [vp, pp, vp, vp, vp, vp, vp, vp, pp, vp, sz, i, C.POINTER(LayerCost), i, C.POINTER(i), vp]
+    lib.dp_encoder_profile.argtypes = [vp, pp, vp, vp, i, C.POINTER(i), i, i, vp, sz, C.POINTER(LayerCost), i, C.POINTER(i), vp]
+    _LIB = lib
+    return lib
+
+
+def _check(code: int):
+    if code != 0:
+        raise DpipeError(code, load_library().dp_last_error().decode())
+
+
+def _ptr(t):
+    if t is None:
+        return None
+    return C.c_void_p(t.data_ptr()) if hasattr(t, "data_ptr") else C.c_void_p(int(t))
+
+
+def _ptr_array(ts: Sequence):
+    arr = (C.c_void_p * len(ts))()
+    for k, t in enumerate(ts):
+        arr[k] = t.data_ptr() if hasattr(t, "data_ptr") else int(t)
+    return arr
+
+
+def _stream(stream):
+    if stream is None:
+        import torch
+        stream = torch.cuda.current_stream().cuda_stream
+    return C.c_void_p(int(stream))
+
+
+def _nbytes(t):
+    return t.numel() * t.element_size() if t is not None else 0
+
+
+class _Handle:
+    _destroy = None
+
+    def __init__(self):
+        self._h = C.c_void_p()
+
+    def close(self):
+        if self._h:
+            getattr(load_library(), self._destroy)(self._h)
+            self._h = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def _specs(self, count_fn, shape_fn):
+        lib = load_library()
+        n = getattr(lib, count_fn)(self._h)
+        out = []
+        for k in range(n):
+            shape = (C.c_int64 * 2)()
+            name = C.c_char_p()
+            _check(getattr(lib, shape_fn)(self._h, k, shape, C.byref(name)))
+            out.append((name.value.decode(), (shape[0],) if shape[1] == 0 else (shape[0], shape[1])))
+        return out
+
+
+class Stage(_Handle):
+    """dp_stage handle: stage_fwd / stage_bwd / dp_stage_profile."""
+    _destroy = "dp_stage_destroy"
+
+    def __init__(self, kind, dtype, n_blocks, batch, tokens, d_model, n_heads, d_head, ctx_tokens=0, ctx_dim=0,
+                 ff_inner=0, ln_eps=1e-5, gelu_tanh=0):
+        super().__init__()
+        self.desc = StageDesc(kind, dtype, n_blocks, batch, tokens, d_model, n_heads, d_head, ctx_tokens, ctx_dim, ff_inner,
+                              ln_eps, gelu_tanh)
+        _check(load_library().dp_stage_create(C.byref(self.desc), C.byref(self._h)))
+
+    def param_specs(self):
+        return self._specs("dp_stage_param_count", "dp_stage_param_shape")
+
+    def workspace_bytes(self, save_for_bwd: bool) -> int:
+        return load_library().dp_stage_workspace_bytes(self._h, int(save_for_bwd))
+
+    def fwd(self, params, x, ctx_or_cond, y, workspace, save_for_bwd, stream=None):
+        _check(load_library().stage_fwd(self._h, _ptr_array(params), _ptr(x), _ptr(ctx_or_cond), _ptr(y), _ptr(workspace),
+                                        _nbytes(workspace), int(save_for_bwd), _stream(stream)))
+
+    def bwd(self, params, dy, ctx_or_cond, dx, d_cond, dparams, accumulate, workspace, stream=None):
+        _check(load_library().stage_bwd(self._h, _ptr_array(params), _ptr(dy), _ptr(ctx_or_cond), _ptr(dx), _ptr(d_cond),
+                                        _ptr_array(dparams), int(accumulate), _ptr(workspace), _nbytes(workspace),
+                                        _stream(stream)))
+
+    def profile(self, params, x, ctx_or_cond, y, dy, dx, d_cond, dparams, workspace, reps=5, stream=None):
+        rows = (LayerCost * self.desc.n_blocks)()
+        n = C.c_int(0)
+        _check(load_library().dp_stage_profile(self._h, _ptr_array(params), _ptr(x), _ptr(ctx_or_cond), _ptr(y), _ptr(dy),
+                                               _ptr(dx), _ptr(d_cond), _ptr_array(dparams), _ptr(workspace),
+                                               _nbytes(workspace), reps, rows, len(rows), C.byref(n), _stream(stream)))
+        return [rows[k].as_dict() for k in range(n.value)]
+
+
+class Encoder(_Handle):
+    """dp_encoder handle: encoder_fwd_partial / dp_encoder_profile."""
+    _destroy = "dp_encoder_destroy"
+
+    def __init__(self, dtype, n_layers, d_model, n_heads, d_head, seq, vocab, ff_inner, causal=1, ln_eps=1e-5):
+        super().__init__()
+        self.desc = EncoderDesc(dtype, n_layers, d_model, n_heads, d_head, seq, vocab, ff_inner, causal, ln_eps)
+        _check(load_library().dp_encoder_create(C.byref(self.desc), C.byref(self._h)))
+
+    def param_specs(self):
+        return self._specs("dp_encoder_param_count", "dp_encoder_param_shape")
+
+    def workspace_bytes(self, max_samples: int) -> int:
+        return load_library().dp_encoder_workspace_bytes(self._h, max_samples)
+
+    def fwd_partial(self, params, ids, hidden, global_batch, layer_begin, layer_end, sample_offset, num_samples, workspace,
+                    stream=None):
+        _check(load_library().encoder_fwd_partial(self._h, _ptr_array(params), _ptr(ids), _ptr(hidden), global_batch,
+                                                  layer_begin, layer_end, sample_offset, num_samples, _ptr(workspace),
+                                                  _nbytes(workspace), _stream(stream)))
+
+    def profile(self, params, ids, hidden, global_batch, batches, workspace, reps=5, stream=None):
+        nl = self.desc.n_layers + 2
+        rows = (LayerCost * (nl * len(batches)))()
+        n = C.c_int(0)
+        arr = (C.c_int * len(batches))(*batches)
+        _check(load_library().dp_encoder_profile(self._h, _ptr_array(params), _ptr(ids), _ptr(hidden), global_batch, arr,
+                                                 len(batches), reps, _ptr(workspace), _nbytes(workspace), rows, len(rows),
+                                                 C.byref(n), _stream(stream)))
+        return [rows[k].as_dict() for k in range(n.value)]

@@ -1,0 +1,632 @@
+// Fused softmax attention, forward and backward, for self-attention (N keys),
+// cross-attention to the text context (77 keys) and the text encoder's causal attention.
+//
+// bf16 path (MFMA 32x32x16, wave64).  A wave owns 32 queries (forward, dQ) or 32 keys
+// (dK/dV) and keeps them in registers as the MFMA B operand; the other side streams
+// through LDS in 64-row tiles.  Scores are produced transposed (S^T = K Q^T) so that a
+// lane holds one query column: the online-softmax statistics are lane-local, and the
+// probability block, once rounded to bf16, already has the register layout of the B
+// operand of the second product (O^T = V^T P^T).  The operand that needs its
+// contraction index moved (V, and K/Q/dO in the backward) is read from its row-major
+// LDS tile with the transposing LDS load.  The backward is split into a dQ kernel and
+// a dK/dV kernel so that no floating-point atomics are needed (run-to-run identical).
+//
+// fp32 path: one wave per query (or key) row, plain FMA; used by the small fp32
+// configuration only.
+#include "dp_device.h"
+#include "dp_kernels.h"
+#include "dp_errors.h"
+#include <math.h>
+
+namespace dp {
+
+struct AttnK {
+  int B, H, Nq, Nk, dh;
+  float scale_log2;   // scale * log2(e)
+  float scale;
+  const void* q; int ldq;
+  const void* k; int ldk;
+  const void* v; int ldv;
+  void* o; int ldo;
+  float* lse;
+  const void* dout; int lddo;
+  float* delta;
+  void* dq; int lddq;
+  void* dk; int lddk;
+  void* dv; int lddv;
+};
+
+constexpr float LOG2E = 1.4426950408889634f;
+constexpr float LN2 = 0.6931471805599453f;
+
+// Copies a [64 x DHP] tile (rows row0.., zero-filled outside [0,nrows) x [0,dh)) into registers / LDS.
+template <int DHP, int NT>
+struct TileLoader {
+  static constexpr int CHUNKS = 64 * DHP / 8;
+  static constexpr int PER = (CHUNKS + NT - 1) / NT;
+  bf16x8 r[PER];
+  __device__ __forceinline__ void load(const bf16* base, int ld, int row0, int nrows, int dh, int tid) {
+#pragma unroll
+    for (int i = 0; i < PER; ++i) {
+      const int id = tid + i * NT;
+      const int row = id / (DHP / 8), c = (id % (DHP / 8)) * 8;
+      const bool ok = (CHUNKS % NT == 0 || id < CHUNKS) && row0 + row < nrows && c < dh;
+      r[i] = ld8(base + (size_t)(row0 + row) * ld + c, ok);
+    }
+  }
+  __device__ __forceinline__ void store(bf16* tile, int tld, int tid) const {
+#pragma unroll
+    for (int i = 0; i < PER; ++i) {
+      const int id = tid + i * NT;
+      const int row = id / (DHP / 8), c = (id % (DHP / 8)) * 8;
+      if (CHUNKS % NT == 0 || id < CHUNKS) *reinterpret_cast<bf16x8*>(tile + row * tld + c) = r[i];
+    }
+  }
+};
+
+__device__ __forceinline__ bf16x8 pack8(const f32x16& v, int off) {
+  bf16x8 o;
+#pragma unroll
+  for (int u = 0; u < 8; ++u) o[u] = (bf16)v[off + u];
+  return o;
+}
+
+// ------------------------------------------------------------------ forward (bf16)
+template <int DHP, bool CAUSAL>
+__global__ void __launch_bounds__(256) attn_fwd_bf16_kernel(const AttnK p) {
+  constexpr int KC = DHP / 16, DT = DHP / 32;
+  constexpr int K_LD = DHP + 8, V_LD = DHP + 16;
+  __shared__ __attribute__((aligned(16))) bf16 Ks[2][64 * K_LD];
+  __shared__ __attribute__((aligned(16))) bf16 Vs[2][64 * V_LD];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 5, l32 = lane & 31;
+  const int b = blockIdx.y / p.H, h = blockIdx.y % p.H;
+  const int qi = blockIdx.x * 128 + wave * 32 + l32;
+  const bf16* qb = (const bf16*)p.q + (size_t)b * p.Nq * p.ldq + h * p.dh;
+  const bf16* kb = (const bf16*)p.k + (size_t)b * p.Nk * p.ldk + h * p.dh;
+  const bf16* vb = (const bf16*)p.v + (size_t)b * p.Nk * p.ldv + h * p.dh;
+
+  bf16x8 qf[KC];
+#pragma unroll
+  for (int c = 0; c < KC; ++c) qf[c] = ld8(qb + (size_t)qi * p.ldq + 16 * c + 8 * g, qi < p.Nq && 16 * c + 8 * g < p.dh);
+
+  f32x16 oacc[DT];
+#pragma unroll
+  for (int i = 0; i < DT; ++i)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) oacc[i][r] = 0.f;
+  float m = -INFINITY, lsum = 0.f;
+
+  int nkt = (p.Nk + 63) / 64;
+  if (CAUSAL) nkt = min(nkt, (min(p.Nq, (int)blockIdx.x * 128 + 128) + 63) / 64);
+
+  TileLoader<DHP, 256> lk, lv;
+  lk.load(kb, p.ldk, 0, p.Nk, p.dh, tid);
+  lv.load(vb, p.ldv, 0, p.Nk, p.dh, tid);
+  lk.store(Ks[0], K_LD, tid);
+  lv.store(Vs[0], V_LD, tid);
+  __syncthreads();
+
+  for (int kt = 0; kt < nkt; ++kt) {
+    const int buf = kt & 1;
+    const bool more = kt + 1 < nkt;
+    if (more) {
+      lk.load(kb, p.ldk, (kt + 1) * 64, p.Nk, p.dh, tid);
+      lv.load(vb, p.ldv, (kt + 1) * 64, p.Nk, p.dh, tid);
+    }
+    f32x16 s[2];
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+#pragma unroll
+      for (int r = 0; r < 16; ++r) s[t][r] = 0.f;
+#pragma unroll
+      for (int c = 0; c < KC; ++c) {
+        bf16x8 a = *reinterpret_cast<const bf16x8*>(&Ks[buf][(32 * t + l32) * K_LD + 16 * c + 8 * g]);
+        s[t] = mfma32(a, qf[c], s[t]);
+      }
+    }
+    // online softmax over this lane's query column (shared with lane ^ 32)
+    float mx = m;
+    const bool edge = (kt * 64 + 64 > p.Nk) || (CAUSAL && kt * 64 + 63 > (int)blockIdx.x * 128 + wave * 32);
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        float v = s[t][r] * p.scale_log2;
+        if (edge) {
+          const int key = kt * 64 + 32 * t + acc_row(r, g);
+          if (key >= p.Nk || (CAUSAL && key > qi)) v = -INFINITY;
+        }
+        s[t][r] = v;
+        mx = fmaxf(mx, v);
+      }
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    const float mref = (mx == -INFINITY) ? 0.f : mx;
+    const float alpha = exp2f(m - mref);
+    float rs = 0.f;
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const float e = exp2f(s[t][r] - mref);
+        s[t][r] = e;
+        rs += e;
+      }
+    rs += __shfl_xor(rs, 32, 64);
+    lsum = lsum * alpha + rs;
+    m = mx;
+#pragma unroll
+    for (int i = 0; i < DT; ++i)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) oacc[i][r] *= alpha;
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+      for (int cc = 0; cc < 2; ++cc) {
+        const bf16x8 pf = pack8(s[t], 8 * cc);
+#pragma unroll
+        for (int i = 0; i < DT; ++i) {
+          bf16x8 a = frag_from_mc_accorder(&Vs[buf][(32 * t + 16 * cc) * V_LD + 32 * i], V_LD, lane);
+          oacc[i] = mfma32(a, pf, oacc[i]);
+        }
+      }
+    if (more) {
+      lk.store(Ks[buf ^ 1], K_LD, tid);
+      lv.store(Vs[buf ^ 1], V_LD, tid);
+    }
+    __syncthreads();
+  }
+
+  if (qi < p.Nq) {
+    const float inv = lsum > 0.f ? 1.0f / lsum : 0.f;
+    bf16* ob = (bf16*)p.o + ((size_t)b * p.Nq + qi) * p.ldo + h * p.dh;
+#pragma unroll
+    for (int i = 0; i < DT; ++i)
+#pragma unroll
+      for (int r4 = 0; r4 < 4; ++r4) {
+        const int col = 32 * i + 8 * r4 + 4 * g;
+        if (col < p.dh) {
+          bf16x4 o;
+#pragma unroll
+          for (int u = 0; u < 4; ++u) o[u] = (bf16)(oacc[i][4 * r4 + u] * inv);
+          *reinterpret_cast<bf16x4*>(ob + col) = o;
+        }
+      }
+    if (p.lse && g == 0) p.lse[((size_t)b * p.H + h) * p.Nq + qi] = m * LN2 + logf(lsum);
+  }
+}
+
+// ------------------------------------------------------------------ delta = rowsum(dO * O)
+// 8 lanes per (token, head) pair.
+template <typename T>
+__global__ void attn_delta_kernel(const T* __restrict__ o, int ldo, const T* __restrict__ dout, int lddo, float* __restrict__ delta,
+                                  int B, int H, int Nq, int dh) {
+  const size_t gid = (blockIdx.x * (size_t)blockDim.x + threadIdx.x) / 8;
+  const int sub = threadIdx.x & 7;
+  const size_t total = (size_t)B * Nq * H;
+  float s = 0.f;
+  if (gid < total) {
+    const int h = gid % H; const size_t row = gid / H;   // row = b * Nq + n
+    const T* po = o + row * ldo + h * dh;
+    const T* pd = dout + row * lddo + h * dh;
+    for (int t = sub; t < dh; t += 8) s += to_f<T>(po[t]) * to_f<T>(pd[t]);
+  }
+  s += __shfl_xor(s, 1, 64); s += __shfl_xor(s, 2, 64); s += __shfl_xor(s, 4, 64);
+  if (gid < total && sub == 0) {
+    const int h = gid % H; const size_t row = gid / H;
+    const size_t b = row / Nq, n = row % Nq;
+    delta[(b * H + h) * Nq + n] = s;
+  }
+}
+
+// ------------------------------------------------------------------ dQ (bf16)
+template <int DHP>
+__global__ void __launch_bounds__(256) attn_bwd_dq_bf16_kernel(const AttnK p) {
+  constexpr int KC = DHP / 16, DT = DHP / 32;
+  constexpr int LD = DHP + 8;
+  __shared__ __attribute__((aligned(16))) bf16 Ks[2][64 * LD];
+  __shared__ __attribute__((aligned(16))) bf16 Vs[2][64 * LD];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 5, l32 = lane & 31;
+  const int b = blockIdx.y / p.H, h = blockIdx.y % p.H;
+  const int qi = blockIdx.x * 128 + wave * 32 + l32;
+  const bool qok = qi < p.Nq;
+  const bf16* kb = (const bf16*)p.k + (size_t)b * p.Nk * p.ldk + h * p.dh;
+  const bf16* vb = (const bf16*)p.v + (size_t)b * p.Nk * p.ldv + h * p.dh;
+  const bf16* qrow = (const bf16*)p.q + ((size_t)b * p.Nq + qi) * p.ldq + h * p.dh;
+  const bf16* dorow = (const bf16*)p.dout + ((size_t)b * p.Nq + qi) * p.lddo + h * p.dh;
+
+  bf16x8 qf[KC], dof[KC];
+#pragma unroll
+  for (int c = 0; c < KC; ++c) {
+    const bool ok = qok && 16 * c + 8 * g < p.dh;
+    qf[c] = ld8(qrow + 16 * c + 8 * g, ok);
+    dof[c] = ld8(dorow + 16 * c + 8 * g, ok);
+  }
+  const size_t sidx = ((size_t)b * p.H + h) * p.Nq + qi;
+  const float lse2 = qok ? p.lse[sidx] * LOG2E : INFINITY;
+  const float dlt = qok ? p.delta[sidx] : 0.f;
+
+  f32x16 acc[DT];
+#pragma unroll
+  for (int i = 0; i < DT; ++i)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
+
+  const int nkt = (p.Nk + 63) / 64;
+  TileLoader<DHP, 256> lk, lv;
+  lk.load(kb, p.ldk, 0, p.Nk, p.dh, tid);
+  lv.load(vb, p.ldv, 0, p.Nk, p.dh, tid);
+  lk.store(Ks[0], LD, tid);
+  lv.store(Vs[0], LD, tid);
+  __syncthreads();
+
+  for (int kt = 0; kt < nkt; ++kt) {
+    const int buf = kt & 1;
+    const bool more = kt + 1 < nkt;
+    if (more) {
+      lk.load(kb, p.ldk, (kt + 1) * 64, p.Nk, p.dh, tid);
+      lv.load(vb, p.ldv, (kt + 1) * 64, p.Nk, p.dh, tid);
+    }
+    const bool edge = kt * 64 + 64 > p.Nk;
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+      f32x16 s, dp;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) { s[r] = 0.f; dp[r] = 0.f; }
+#pragma unroll
+      for (int c = 0; c < KC; ++c) {
+        bf16x8 ka = *reinterpret_cast<const bf16x8*>(&Ks[buf][(32 * t + l32) * LD + 16 * c + 8 * g]);
+        bf16x8 va = *reinterpret_cast<const bf16x8*>(&Vs[buf][(32 * t + l32) * LD + 16 * c + 8 * g]);
+        s = mfma32(ka, qf[c], s);
+        dp = mfma32(va, dof[c], dp);
+      }
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        float pr = exp2f(s[r] * p.scale_log2 - lse2);
+        if (edge && kt * 64 + 32 * t + acc_row(r, g) >= p.Nk) pr = 0.f;
+        s[r] = pr * (dp[r] - dlt);
+      }
+#pragma unroll
+      for (int cc = 0; cc < 2; ++cc) {
+        const bf16x8 dsf = pack8(s, 8 * cc);
+#pragma unroll
+        for (int i = 0; i < DT; ++i) {
+          bf16x8 a = frag_from_mc_accorder(&Ks[buf][(32 * t + 16 * cc) * LD + 32 * i], LD, lane);
+          acc[i] = mfma32(a, dsf, acc[i]);
+        }
+      }
+    }
+    if (more) {
+      lk.store(Ks[buf ^ 1], LD, tid);
+      lv.store(Vs[buf ^ 1], LD, tid);
+    }
+    __syncthreads();
+  }
+  if (qok) {
+    bf16* ob = (bf16*)p.dq + ((size_t)b * p.Nq + qi) * p.lddq + h * p.dh;
+#pragma unroll
+    for (int i = 0; i < DT; ++i)
+#pragma unroll
+      for (int r4 = 0; r4 < 4; ++r4) {
+        const int col = 32 * i + 8 * r4 + 4 * g;
+        if (col < p.dh) {
+          bf16x4 o;
+#pragma unroll
+          for (int u = 0; u < 4; ++u) o[u] = (bf16)(acc[i][4 * r4 + u] * p.scale);
+          *reinterpret_cast<bf16x4*>(ob + col) = o;
+        }
+      }
+  }
+}
+
+// ------------------------------------------------------------------ dK, dV (bf16)
+// grid.x = ceil(Nk / 128); each wave owns 32 keys and walks all query tiles.
+template <int DHP>
+__global__ void __launch_bounds__(256) attn_bwd_dkv_bf16_kernel(const AttnK p) {
+  constexpr int KC = DHP / 16, DT = DHP / 32;
+  constexpr int LD = DHP + 8;
+  __shared__ __attribute__((aligned(16))) bf16 Qs[2][64 * LD];
+  __shared__ __attribute__((aligned(16))) bf16 Ds[2][64 * LD];
+  __shared__ __attribute__((aligned(16))) float lse_s[2][64];
+  __shared__ __attribute__((aligned(16))) float dlt_s[2][64];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 5, l32 = lane & 31;
+  const int b = blockIdx.y / p.H, h = blockIdx.y % p.H;
+  const int ki = blockIdx.x * 128 + wave * 32 + l32;
+  const bool kok = ki < p.Nk;
+  const bf16* qb = (const bf16*)p.q + (size_t)b * p.Nq * p.ldq + h * p.dh;
+  const bf16* dob = (const bf16*)p.dout + (size_t)b * p.Nq * p.lddo + h * p.dh;
+  const bf16* krow = (const bf16*)p.k + ((size_t)b * p.Nk + ki) * p.ldk + h * p.dh;
+  const bf16* vrow = (const bf16*)p.v + ((size_t)b * p.Nk + ki) * p.ldv + h * p.dh;
+  const float* lse_b = p.lse + ((size_t)b * p.H + h) * p.Nq;
+  const float* dlt_b = p.delta + ((size_t)b * p.H + h) * p.Nq;
+
+  bf16x8 kf[KC], vf[KC];
+#pragma unroll
+  for (int c = 0; c < KC; ++c) {
+    const bool ok = kok && 16 * c + 8 * g < p.dh;
+    kf[c] = ld8(krow + 16 * c + 8 * g, ok);
+    vf[c] = ld8(vrow + 16 * c + 8 * g, ok);
+  }
+  f32x16 dkacc[DT], dvacc[DT];
+#pragma unroll
+  for (int i = 0; i < DT; ++i)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) { dkacc[i][r] = 0.f; dvacc[i][r] = 0.f; }
+
+  const int nqt = (p.Nq + 63) / 64;
+  TileLoader<DHP, 256> lq, ld_;
+  float r_lse = 0.f, r_dlt = 0.f;
+  auto load_stats = [&](int qt) {
+    if (tid < 64) {
+      const int qi = qt * 64 + tid;
+      r_lse = qi < p.Nq ? lse_b[qi] * LOG2E : INFINITY;
+      r_dlt = qi < p.Nq ? dlt_b[qi] : 0.f;
+    }
+  };
+  auto store_stats = [&](int buf) {
+    if (tid < 64) { lse_s[buf][tid] = r_lse; dlt_s[buf][tid] = r_dlt; }
+  };
+  lq.load(qb, p.ldq, 0, p.Nq, p.dh, tid);
+  ld_.load(dob, p.lddo, 0, p.Nq, p.dh, tid);
+  load_stats(0);
+  lq.store(Qs[0], LD, tid);
+  ld_.store(Ds[0], LD, tid);
+  store_stats(0);
+  __syncthreads();
+
+  for (int qt = 0; qt < nqt; ++qt) {
+    const int buf = qt & 1;
+    const bool more = qt + 1 < nqt;
+    if (more) {
+      lq.load(qb, p.ldq, (qt + 1) * 64, p.Nq, p.dh, tid);
+      ld_.load(dob, p.lddo, (qt + 1) * 64, p.Nq, p.dh, tid);
+      load_stats(qt + 1);
+    }
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+      f32x16 s, dp;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) { s[r] = 0.f; dp[r] = 0.f; }
+#pragma unroll
+      for (int c = 0; c < KC; ++c) {
+        bf16x8 qa = *reinterpret_cast<const bf16x8*>(&Qs[buf][(32 * t + l32) * LD + 16 * c + 8 * g]);
+        bf16x8 da = *reinterpret_cast<const bf16x8*>(&Ds[buf][(32 * t + l32) * LD + 16 * c + 8 * g]);
+        s = mfma32(qa, kf[c], s);
+        dp = mfma32(da, vf[c], dp);
+      }
+      f32x16 ds;
+#pragma unroll
+      for (int r4 = 0; r4 < 4; ++r4) {
+        const f32x4 l4 = *reinterpret_cast<const f32x4*>(&lse_s[buf][32 * t + 8 * r4 + 4 * g]);
+        const f32x4 d4 = *reinterpret_cast<const f32x4*>(&dlt_s[buf][32 * t + 8 * r4 + 4 * g]);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          const int r = 4 * r4 + u;
+          float pr = exp2f(s[r] * p.scale_log2 - l4[u]);
+          if (!kok) pr = 0.f;
+          s[r] = pr;
+          ds[r] = pr * (dp[r] - d4[u]);
+        }
+      }
+#pragma unroll
+      for (int cc = 0; cc < 2; ++cc) {
+        const bf16x8 pf = pack8(s, 8 * cc);
+        const bf16x8 dsf = pack8(ds, 8 * cc);
+#pragma unroll
+        for (int i = 0; i < DT; ++i) {
+          bf16x8 da = frag_from_mc_accorder(&Ds[buf][(32 * t + 16 * cc) * LD + 32 * i], LD, lane);
+          bf16x8 qa = frag_from_mc_accorder(&Qs[buf][(32 * t + 16 * cc) * LD + 32 * i], LD, lane);
+          dvacc[i] = mfma32(da, pf, dvacc[i]);
+          dkacc[i] = mfma32(qa, dsf, dkacc[i]);
+        }
+      }
+    }
+    if (more) {
+      lq.store(Qs[buf ^ 1], LD, tid);
+      ld_.store(Ds[buf ^ 1], LD, tid);
+      store_stats(buf ^ 1);
+    }
+    __syncthreads();
+  }
+  if (kok) {
+    bf16* dkb = (bf16*)p.dk + ((size_t)b * p.Nk + ki) * p.lddk + h * p.dh;
+    bf16* dvb = (bf16*)p.dv + ((size_t)b * p.Nk + ki) * p.lddv + h * p.dh;
+#pragma unroll
+    for (int i = 0; i < DT; ++i)
+#pragma unroll
+      for (int r4 = 0; r4 < 4; ++r4) {
+        const int col = 32 * i + 8 * r4 + 4 * g;
+        if (col < p.dh) {
+          bf16x4 ok_, ov;
+#pragma unroll
+          for (int u = 0; u < 4; ++u) { ok_[u] = (bf16)(dkacc[i][4 * r4 + u] * p.scale); ov[u] = (bf16)dvacc[i][4 * r4 + u]; }
+          *reinterpret_cast<bf16x4*>(dkb + col) = ok_;
+          *reinterpret_cast<bf16x4*>(dvb + col) = ov;
+        }
+      }
+  }
+}
+
+// ------------------------------------------------------------------ fp32 path (one wave per row)
+constexpr int F32_MAX_DH = 256;
+
+__global__ void __launch_bounds__(64) attn_fwd_f32_kernel(const AttnK p, int causal) {
+  extern __shared__ float sc[];        // [Nk]
+  __shared__ float qs[F32_MAX_DH];
+  const int lane = threadIdx.x, i = blockIdx.x, b = blockIdx.y / p.H, h = blockIdx.y % p.H;
+  const float* q = (const float*)p.q + ((size_t)b * p.Nq + i) * p.ldq + h * p.dh;
+  const float* kb = (const float*)p.k + (size_t)b * p.Nk * p.ldk + h * p.dh;
+  const float* vb = (const float*)p.v + (size_t)b * p.Nk * p.ldv + h * p.dh;
+  for (int t = lane; t < p.dh; t += 64) qs[t] = q[t];
+  __syncthreads();
+  float mx = -INFINITY;
+  for (int j = lane; j < p.Nk; j += 64) {
+    float s = 0.f;
+    for (int t = 0; t < p.dh; ++t) s = fmaf(qs[t], kb[(size_t)j * p.ldk + t], s);
+    s *= p.scale;
+    if (causal && j > i) s = -INFINITY;
+    sc[j] = s;
+    mx = fmaxf(mx, s);
+  }
+  mx = wave_max(mx);
+  float sum = 0.f;
+  for (int j = lane; j < p.Nk; j += 64) {
+    const float e = expf(sc[j] - mx);
+    sc[j] = e;
+    sum += e;
+  }
+  sum = wave_sum(sum);
+  __syncthreads();
+  float* o = (float*)p.o + ((size_t)b * p.Nq + i) * p.ldo + h * p.dh;
+  for (int t = lane; t < p.dh; t += 64) {
+    float a = 0.f;
+    for (int j = 0; j < p.Nk; ++j) a = fmaf(sc[j], vb[(size_t)j * p.ldv + t], a);
+    o[t] = a / sum;
+  }
+  if (p.lse && lane == 0) p.lse[((size_t)b * p.H + h) * p.Nq + i] = mx + logf(sum);
+}
+
+__global__ void __launch_bounds__(64) attn_bwd_dq_f32_kernel(const AttnK p) {
+  extern __shared__ float sc[];        // [Nk]
+  __shared__ float qs[F32_MAX_DH];
+  __shared__ float dos[F32_MAX_DH];
+  const int lane = threadIdx.x, i = blockIdx.x, b = blockIdx.y / p.H, h = blockIdx.y % p.H;
+  const float* q = (const float*)p.q + ((size_t)b * p.Nq + i) * p.ldq + h * p.dh;
+  const float* dor = (const float*)p.dout + ((size_t)b * p.Nq + i) * p.lddo + h * p.dh;
+  const float* kb = (const float*)p.k + (size_t)b * p.Nk * p.ldk + h * p.dh;
+  const float* vb = (const float*)p.v + (size_t)b * p.Nk * p.ldv + h * p.dh;
+  for (int t = lane; t < p.dh; t += 64) { qs[t] = q[t]; dos[t] = dor[t]; }
+  __syncthreads();
+  const size_t sidx = ((size_t)b * p.H + h) * p.Nq + i;
+  const float lse = p.lse[sidx], dlt = p.delta[sidx];
+  for (int j = lane; j < p.Nk; j += 64) {
+    float s = 0.f, dp = 0.f;
+    for (int t = 0; t < p.dh; ++t) {
+      s = fmaf(qs[t], kb[(size_t)j * p.ldk + t], s);
+      dp = fmaf(dos[t], vb[(size_t)j * p.ldv + t], dp);
+    }
+    sc[j] = expf(s * p.scale - lse) * (dp - dlt);
+  }
+  __syncthreads();
+  float* dq = (float*)p.dq + ((size_t)b * p.Nq + i) * p.lddq + h * p.dh;
+  for (int t = lane; t < p.dh; t += 64) {
+    float a = 0.f;
+    for (int j = 0; j < p.Nk; ++j) a = fmaf(sc[j], kb[(size_t)j * p.ldk + t], a);
+    dq[t] = a * p.scale;
+  }
+}
+
+__global__ void __launch_bounds__(64) attn_bwd_dkv_f32_kernel(const AttnK p) {
+  extern __shared__ float sc[];        // [2][Nq]: p, ds
+  __shared__ float ks[F32_MAX_DH];
+  __shared__ float vs[F32_MAX_DH];
+  const int lane = threadIdx.x, j = blockIdx.x, b = blockIdx.y / p.H, h = blockIdx.y % p.H;
+  const float* kr = (const float*)p.k + ((size_t)b * p.Nk + j) * p.ldk + h * p.dh;
+  const float* vr = (const float*)p.v + ((size_t)b * p.Nk + j) * p.ldv + h * p.dh;
+  const float* qb = (const float*)p.q + (size_t)b * p.Nq * p.ldq + h * p.dh;
+  const float* dob = (const float*)p.dout + (size_t)b * p.Nq * p.lddo + h * p.dh;
+  const float* lse_b = p.lse + ((size_t)b * p.H + h) * p.Nq;
+  const float* dlt_b = p.delta + ((size_t)b * p.H + h) * p.Nq;
+  for (int t = lane; t < p.dh; t += 64) { ks[t] = kr[t]; vs[t] = vr[t]; }
+  __syncthreads();
+  float* pp = sc; float* dsp = sc + p.Nq;
+  for (int i = lane; i < p.Nq; i += 64) {
+    float s = 0.f, dp = 0.f;
+    for (int t = 0; t < p.dh; ++t) {
+      s = fmaf(qb[(size_t)i * p.ldq + t], ks[t], s);
+      dp = fmaf(dob[(size_t)i * p.lddo + t], vs[t], dp);
+    }
+    const float pr = expf(s * p.scale - lse_b[i]);
+    pp[i] = pr;
+    dsp[i] = pr * (dp - dlt_b[i]);
+  }
+  __syncthreads();
+  float* dk = (float*)p.dk + ((size_t)b * p.Nk + j) * p.lddk + h * p.dh;
+  float* dv = (float*)p.dv + ((size_t)b * p.Nk + j) * p.lddv + h * p.dh;
+  for (int t = lane; t < p.dh; t += 64) {
+    float a = 0.f, c = 0.f;
+    for (int i = 0; i < p.Nq; ++i) {
+      a = fmaf(dsp[i], qb[(size_t)i * p.ldq + t], a);
+      c = fmaf(pp[i], dob[(size_t)i * p.lddo + t], c);
+    }
+    dk[t] = a * p.scale;
+    dv[t] = c;
+  }
+}
+
+// ------------------------------------------------------------------ host side
+static AttnK make_k(const AttnArgs& a) {
+  AttnK k;
+  k.B = a.B; k.H = a.H; k.Nq = a.Nq; k.Nk = a.Nk; k.dh = a.d_head;
+  k.scale = a.scale; k.scale_log2 = a.scale * LOG2E;
+  k.q = a.q; k.ldq = a.ldq; k.k = a.k; k.ldk = a.ldk; k.v = a.v; k.ldv = a.ldv; k.o = a.o; k.ldo = a.ldo; k.lse = a.lse;
+  k.dout = a.dout; k.lddo = a.lddo; k.delta = a.delta; k.dq = a.dq; k.lddq = a.lddq; k.dk = a.dk; k.lddk = a.lddk;
+  k.dv = a.dv; k.lddv = a.lddv;
+  return k;
+}
+
+static int check_attn(const AttnArgs& a, bool bwd) {
+  if (a.B <= 0 || a.H <= 0 || a.Nq <= 0 || a.Nk <= 0 || a.d_head <= 0) return set_error(DP_EINVAL, "attention: non-positive size");
+  if (!a.q || !a.k || !a.v || !a.o) return set_error(DP_EINVAL, "attention: null operand");
+  if ((size_t)a.B * a.H > 65535) return set_error(DP_EUNSUPPORTED, "attention: batch * heads exceeds 65535");
+  const int span = a.H * a.d_head;
+  if (a.ldq < span || a.ldk < span || a.ldv < span || a.ldo < span) return set_error(DP_EINVAL, "attention: leading dim smaller than heads * d_head");
+  if (bwd) {
+    if (!a.dout || !a.lse || !a.delta || !a.dq || !a.dk || !a.dv) return set_error(DP_EINVAL, "attention backward: null operand");
+    if (a.lddo < span || a.lddq < span || a.lddk < span || a.lddv < span) return set_error(DP_EINVAL, "attention backward: leading dim too small");
+    if (a.causal) return set_error(DP_EUNSUPPORTED, "attention backward: causal mask not supported (the causal encoder is frozen)");
+  }
+  if (a.dtype == BF16) {
+    if (a.d_head % 8 || a.d_head > 96) return set_error(DP_EUNSUPPORTED, "attention(bf16): d_head must be a multiple of 8, at most 96");
+    const int lds[] = {a.ldq, a.ldk, a.ldv, a.ldo, bwd ? a.lddo : 8, bwd ? a.lddq : 8, bwd ? a.lddk : 8, bwd ? a.lddv : 8};
+    for (int x : lds) if (x % 8) return set_error(DP_EUNSUPPORTED, "attention(bf16): leading dims must be multiples of 8");
+    const void* ps[] = {a.q, a.k, a.v, a.o, bwd ? a.dout : a.q, bwd ? a.dq : a.q, bwd ? a.dk : a.q, bwd ? a.dv : a.q};
+    for (const void* x : ps) if ((uintptr_t)x % 16) return set_error(DP_EALIGN, "attention(bf16): operands must be 16-byte aligned");
+  } else {
+    if (a.d_head > F32_MAX_DH) return set_error(DP_EUNSUPPORTED, "attention(fp32): d_head > 256");
+    if ((size_t)a.Nk * 4 > 60000 || (bwd && (size_t)a.Nq * 8 > 60000)) return set_error(DP_EUNSUPPORTED, "attention(fp32): sequence too long for the fp32 path");
+  }
+  return DP_OK;
+}
+
+int launch_attn_fwd(const AttnArgs& a, hipStream_t s) {
+  if (int e = check_attn(a, false)) return e;
+  const AttnK k = make_k(a);
+  if (a.dtype == BF16) {
+    dim3 grid((a.Nq + 127) / 128, a.B * a.H);
+    if (a.d_head <= 64) {
+      if (a.causal) hipLaunchKernelGGL((attn_fwd_bf16_kernel<64, true>), grid, dim3(256), 0, s, k);
+      else hipLaunchKernelGGL((attn_fwd_bf16_kernel<64, false>), grid, dim3(256), 0, s, k);
+    } else {
+      if (a.causal) hipLaunchKernelGGL((attn_fwd_bf16_kernel<96, true>), grid, dim3(256), 0, s, k);
+      else hipLaunchKernelGGL((attn_fwd_bf16_kernel<96, false>), grid, dim3(256), 0, s, k);
+    }
+  } else {
+    hipLaunchKernelGGL(attn_fwd_f32_kernel, dim3(a.Nq, a.B * a.H), dim3(64), (size_t)a.Nk * sizeof(float), s, k, a.causal);
+  }
+  return hipGetLastError() == hipSuccess ? DP_OK : set_error(DP_EHIP, "attention forward launch failed");
+}
+
+int launch_attn_bwd(const AttnArgs& a, hipStream_t s) {
+  if (int e = check_attn(a, true)) return e;
+  const AttnK k = make_k(a);
+  const size_t pairs = (size_t)a.B * a.Nq * a.H;
+  const dim3 dgrid((pairs * 8 + 255) / 256);
+  if (a.dtype == BF16) {
+    hipLaunchKernelGGL(attn_delta_kernel<bf16>, dgrid, dim3(256), 0, s, (const bf16*)a.o, a.ldo, (const bf16*)a.dout, a.lddo, a.delta, a.B, a.H, a.Nq, a.d_head);
+    dim3 gq((a.Nq + 127) / 128, a.B * a.H), gk((a.Nk + 127) / 128, a.B * a.H);
+    if (a.d_head <= 64) {
+      hipLaunchKernelGGL(attn_bwd_dq_bf16_kernel<64>, gq, dim3(256), 0, s, k);
+      hipLaunchKernelGGL(attn_bwd_dkv_bf16_kernel<64>, gk, dim3(256), 0, s, k);
+    } else {
+      hipLaunchKernelGGL(attn_bwd_dq_bf16_kernel<96>, gq, dim3(256), 0, s, k);
+      hipLaunchKernelGGL(attn_bwd_dkv_bf16_kernel<96>, gk, dim3(256), 0, s, k);
+    }
+  } else {
+    hipLaunchKernelGGL(attn_delta_kernel<float>, dgrid, dim3(256), 0, s, (const float*)a.o, a.ldo, (const float*)a.dout, a.lddo, a.delta, a.B, a.H, a.Nq, a.d_head);
+    hipLaunchKernelGGL(attn_bwd_dq_f32_kernel, dim3(a.Nq, a.B * a.H), dim3(64), (size_t)a.Nk * sizeof(float), s, k);
+    hipLaunchKernelGGL(attn_bwd_dkv_f32_kernel, dim3(a.Nk, a.B * a.H), dim3(64), (size_t)2 * a.Nq * sizeof(float), s, k);
+  }
+  return hipGetLastError() == hipSuccess ? DP_OK : set_error(DP_EHIP, "attention backward launch failed");
+}
+
+}  // namespace dp

@@ -1,0 +1,135 @@
+// Device-side helpers shared by the gfx950 kernels: vector types, MFMA and
+// transposing-LDS-read wrappers, guarded 16-byte global loads, wave reductions,
+// activation functions.  gfx950 (CDNA4) only; wave size is 64.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace dp {
+
+typedef __bf16 bf16;
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+
+#define DP_LDS __attribute__((address_space(3)))
+
+// D[32x32] += A[32x16] * B[16x32], bf16 in, fp32 accumulate.
+// Operand layout (lane l, g = l / 32): A: row l % 32, k = 8g..8g+7; B: column l % 32, k = 8g..8g+7;
+// D: column l % 32, register r holds row 8 * (r / 4) + 4g + (r % 4).
+__device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
+  return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
+
+// Row index inside a 32x32 accumulator tile held by register r of a lane in half g.
+__device__ __forceinline__ int acc_row(int r, int g) { return 8 * (r >> 2) + 4 * g + (r & 3); }
+
+// Transposing LDS read (ds_read_b64_tr_b16).  Inside each block of 16 lanes the 16
+// addresses describe a 4 x 16 tile (lanes 4r..4r+3 supply the four 4-element pieces of
+// row r); lane j of the block receives column j of that tile (4 values, rows 0..3).
+__device__ __forceinline__ bf16x4 lds_read_tr(const bf16* p) {
+  s16x4 v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((DP_LDS s16x4*)(p));
+  return __builtin_bit_cast(bf16x4, v);
+}
+
+// Fetch an MFMA A/B fragment (8 contraction values per lane) from an LDS tile stored
+// [k][mn] (the non-contracted index contiguous).  `tile` points at element (k0, mn0);
+// ld is the row stride in elements.  Slot u of the result is k = k0 + 8g + u.
+__device__ __forceinline__ bf16x8 frag_from_mc(const bf16* tile, int ld, int lane) {
+  const int b = lane >> 4, j = lane & 15;
+  const bf16* p = tile + (8 * (b >> 1) + (j >> 2)) * ld + 16 * (b & 1) + 4 * (j & 3);
+  bf16x4 lo = lds_read_tr(p);
+  bf16x4 hi = lds_read_tr(p + 4 * ld);
+  return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+}
+
+// Same, but the 8 contraction slots follow the accumulator row order of a 32x32 tile:
+// slot u is k = k0 + 8 * (u / 4) + 4g + (u % 4)  (16 k values: two groups of 8 per g).
+// This lets a C-layout register block (after conversion to bf16) act as the other operand.
+__device__ __forceinline__ bf16x8 frag_from_mc_accorder(const bf16* tile, int ld, int lane) {
+  const int b = lane >> 4, j = lane & 15;
+  const bf16* p = tile + (4 * (b >> 1) + (j >> 2)) * ld + 16 * (b & 1) + 4 * (j & 3);
+  bf16x4 lo = lds_read_tr(p);
+  bf16x4 hi = lds_read_tr(p + 8 * ld);
+  return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+}
+
+__device__ __forceinline__ bf16x8 zero8() {
+  u32x4 z = {0, 0, 0, 0};
+  return __builtin_bit_cast(bf16x8, z);
+}
+
+// 16-byte global load of 8 bf16, or zeros when !ok.
+__device__ __forceinline__ bf16x8 ld8(const bf16* p, bool ok) {
+  if (ok) return *reinterpret_cast<const bf16x8*>(p);
+  return zero8();
+}
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+  return v;
+}
+
+// ---- storage conversion -------------------------------------------------
+template <typename T> __device__ __forceinline__ float to_f(T v);
+template <> __device__ __forceinline__ float to_f<float>(float v) { return v; }
+template <> __device__ __forceinline__ float to_f<bf16>(bf16 v) { return (float)v; }
+template <typename T> __device__ __forceinline__ T from_f(float v);
+template <> __device__ __forceinline__ float from_f<float>(float v) { return v; }
+template <> __device__ __forceinline__ bf16 from_f<bf16>(float v) { return (bf16)v; }
+
+// ---- activations (fp32) ----------------------------------------------------
+enum Act { ACT_NONE = 0, ACT_GELU_ERF = 1, ACT_GELU_TANH = 2, ACT_QUICK_GELU = 3 };
+
+__device__ __forceinline__ float gelu_erf_f(float z) { return 0.5f * z * (1.0f + erff(z * 0.70710678118654752f)); }
+__device__ __forceinline__ float gelu_erf_grad_f(float z) {
+  return 0.5f * (1.0f + erff(z * 0.70710678118654752f)) + z * __expf(-0.5f * z * z) * 0.3989422804014327f;
+}
+__device__ __forceinline__ float tanh_fast(float x) {
+  // tanh(x) = 1 - 2 / (exp(2x) + 1); exact limits at +-inf, no cancellation issue at the tolerance used
+  float e = __expf(2.0f * x);
+  return 1.0f - 2.0f / (e + 1.0f);
+}
+__device__ __forceinline__ float gelu_tanh_f(float z) {
+  float t = tanh_fast(0.7978845608028654f * (z + 0.044715f * z * z * z));
+  return 0.5f * z * (1.0f + t);
+}
+__device__ __forceinline__ float gelu_tanh_grad_f(float z) {
+  float t = tanh_fast(0.7978845608028654f * (z + 0.044715f * z * z * z));
+  return 0.5f * (1.0f + t) + 0.5f * z * (1.0f - t * t) * 0.7978845608028654f * (1.0f + 0.134145f * z * z);
+}
+__device__ __forceinline__ float sigmoid_f(float z) { return 1.0f / (1.0f + __expf(-z)); }
+__device__ __forceinline__ float quick_gelu_f(float z) { return z * sigmoid_f(1.702f * z); }
+__device__ __forceinline__ float silu_f(float z) { return z * sigmoid_f(z); }
+__device__ __forceinline__ float silu_grad_f(float z) {
+  float s = sigmoid_f(z);
+  return s * (1.0f + z * (1.0f - s));
+}
+__device__ __forceinline__ float act_apply(int act, float z) {
+  switch (act) {
+    case ACT_GELU_ERF: return gelu_erf_f(z);
+    case ACT_GELU_TANH: return gelu_tanh_f(z);
+    case ACT_QUICK_GELU: return quick_gelu_f(z);
+    default: return z;
+  }
+}
+__device__ __forceinline__ float act_grad(int act, float z) {
+  switch (act) {
+    case ACT_GELU_ERF: return gelu_erf_grad_f(z);
+    case ACT_GELU_TANH: return gelu_tanh_grad_f(z);
+    default: return 1.0f;
+  }
+}
+
+}  // namespace dp

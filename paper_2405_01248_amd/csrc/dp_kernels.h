@@ -1,0 +1,128 @@
+// Host-side launch interface of the kernels (internal to the library).
+// Every launcher validates its operand shapes on the host before the launch and
+// returns a negative dpipe error code instead of launching when they do not fit.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace dp {
+
+enum DType { F32 = 0, BF16 = 1 };
+inline size_t dtype_size(int dt) { return dt == BF16 ? 2 : 4; }
+
+// ---------------------------------------------------------------- GEMM
+// C[M,N] = opA(A) * opB(B) with fp32 accumulation.
+//   a_mc = 0: A stored [M,K] (contraction index contiguous); 1: A stored [K,M].
+//   b_mc = 0: B stored [N,K] (a weight used as y = x W^T);   1: B stored [K,N].
+// Epilogue, in this order, all optional:
+//   v = acc + bias[n]; if (pre_out) pre_out[m,n] = v; v = act(v);
+//   if (dact_pre) v *= act'(dact_pre[m,n]); if (gate) v *= gate[(m / rows_per_batch) * gate_ld + n];
+//   if (residual) v += residual[m,n]; out[m,n] = v  (storage dtype)
+// or, when out_f32 is set, the raw product goes to fp32:
+//   out_f32[m,n] = (accumulate ? out_f32[m,n] : 0) + acc   (split-K partial sums are
+//   reduced in a fixed order through `splitk_ws`, so results are run-to-run identical).
+struct GemmArgs {
+  int dtype;                 // storage dtype of A, B, out, bias, residual, pre_out, dact_pre, gate
+  const void* A; const void* B;
+  int M, N, K;
+  int lda, ldb;              // row strides in elements
+  int a_mc, b_mc;
+  void* out; int ldo;        // storage-dtype output (or nullptr)
+  float* out_f32; int ldo32; int accumulate;
+  const void* bias;
+  void* pre_out; int ld_pre;
+  int act;
+  const void* dact_pre; int ld_dact; int dact_kind;
+  const void* gate; int gate_ld; int rows_per_batch;
+  const void* residual; int ld_res;
+  float* splitk_ws; size_t splitk_ws_bytes;
+};
+int launch_gemm(const GemmArgs& a, hipStream_t s);
+size_t gemm_splitk_ws_bytes(int M, int N, int K);   // upper bound for out_f32 GEMMs
+
+// ---------------------------------------------------------------- attention
+// Per (batch b, head h): O = softmax(Q K^T * scale [+ causal mask]) V.
+// Element (b, n, h, t) of X lives at X + (b * rows_X + n) * ld_X + h * d_head + t, so Q/K/V
+// may be column blocks of a fused projection output.  lse is [B, H, Nq] fp32 (natural log).
+struct AttnArgs {
+  int dtype;
+  int B, H, Nq, Nk, d_head;
+  int causal;
+  float scale;
+  const void* q; int ldq;
+  const void* k; int ldk;
+  const void* v; int ldv;
+  void* o; int ldo;
+  float* lse;               // may be nullptr in forward when nothing is saved
+  // backward only
+  const void* dout; int lddo;
+  float* delta;             // [B,H,Nq] scratch: rowsum(dO * O)
+  void* dq; int lddq;
+  void* dk; int lddk;
+  void* dv; int lddv;
+};
+int launch_attn_fwd(const AttnArgs& a, hipStream_t s);
+int launch_attn_bwd(const AttnArgs& a, hipStream_t s);
+
+// ---------------------------------------------------------------- norm / elementwise
+// LayerNorm over the last dim of x [rows, d]; gamma/beta (storage dtype) may be null.
+// If scale/shift are given (per batch, row b of a [B, mod_ld] matrix; batch = row / rows_per_batch)
+// the output is xhat * (1 + scale) + shift.  mean/rstd (fp32 [rows]) may be null.
+struct LnArgs {
+  int dtype; int rows, d; float eps;
+  const void* x; void* y;
+  const void* gamma; const void* beta;
+  const void* scale; const void* shift; int mod_ld; int rows_per_batch;
+  float* mean; float* rstd;
+};
+int launch_ln_fwd(const LnArgs& a, hipStream_t s);
+
+// dx = [dres +] LN backward of dy.  Affine: dgamma/dbeta (fp32 [d], accumulate flag).
+// Modulated: dscale/dshift rows written to fp32 [B, dmod_ld] (overwrite) and the
+// effective gain is (1 + scale).  partial is scratch of ln_bwd_partial_bytes().
+struct LnBwdArgs {
+  int dtype; int rows, d;
+  const void* dy; const void* x; const float* mean; const float* rstd;
+  const void* gamma;
+  const void* scale; int mod_ld; int rows_per_batch;
+  const void* dres;        // optional residual-stream gradient added to dx
+  void* dx;
+  float* dgamma; float* dbeta; int accumulate;
+  float* dscale; float* dshift; int dmod_ld;
+  float* partial; size_t partial_bytes;
+};
+int launch_ln_bwd(const LnBwdArgs& a, hipStream_t s);
+size_t ln_bwd_partial_bytes(int rows, int d, int rows_per_batch);
+
+// g[m, j] = u[m, j] * gelu_erf(u[m, inner + j])
+int launch_geglu_fwd(int dtype, const void* u, void* g, int rows, int inner, hipStream_t s);
+// du[m, j] = dg * gelu(gate); du[m, inner + j] = dg * val * gelu'(gate)
+int launch_geglu_bwd(int dtype, const void* dg, const void* u, void* du, int rows, int inner, hipStream_t s);
+
+// out[n] = (accumulate ? out[n] : 0) + sum_m x[m, n]   (fp32 out; deterministic two-stage)
+int launch_colsum(int dtype, const void* x, int ldx, int rows, int cols, float* out, int accumulate,
+                  float* partial, size_t partial_bytes, hipStream_t s);
+size_t colsum_partial_bytes(int rows, int cols);
+
+// out[i] = (accumulate ? out[i] : 0) + sum_z partial[z * n + i]
+int launch_reduce_partials(const float* partial, int nz, size_t n, float* out, int accumulate, hipStream_t s);
+
+// y = silu(x) elementwise (storage dtype), n elements
+int launch_silu(int dtype, const void* x, void* y, size_t n, hipStream_t s);
+// dc[i] (+)= dsilu_in[i] * silu'(c[i])   (fp32 in, storage-dtype c, fp32 out)
+int launch_silu_bwd(int dtype, const float* dz, const void* c, float* dc, int accumulate, size_t n, hipStream_t s);
+
+// Gated-branch backward helper: dbranch[m,n] = dres[m,n] * gate[b,n];
+// dgate[b,n] = sum_{rows of batch b} dres[m,n] * branch[m,n]   (fp32, overwrite)
+int launch_gate_bwd(int dtype, const void* dres, const void* branch, const void* gate, int gate_ld,
+                    void* dbranch, float* dgate, int dgate_ld, int B, int rows_per_batch, int d, hipStream_t s);
+
+// fp32 [rows, cols] -> storage dtype
+int launch_cast_from_f32(int dtype, const float* in, void* out, size_t n, hipStream_t s);
+
+// x[row, :] = tok[ids[row], :] + pos[row % seq, :]
+int launch_embed(int dtype, const int32_t* ids, const void* tok, const void* pos, void* x, int rows, int seq,
+                 int d, int vocab, hipStream_t s);
+
+}  // namespace dp

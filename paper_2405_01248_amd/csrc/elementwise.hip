@@ -1,0 +1,466 @@
+// Bandwidth-bound kernels of a stage: LayerNorm forward/backward (affine or adaLN
+// modulated), GeGLU, SiLU, gated-residual backward, column sums (bias gradients),
+// split-K partial reduction, embedding gather.  One wave per token row with 16-byte
+// accesses; all reductions are in a fixed order (no float atomics), so results are
+// run-to-run identical.  Templated on the storage type (bf16 or fp32); math is fp32.
+#include "dp_device.h"
+#include "dp_kernels.h"
+#include "dp_errors.h"
+
+namespace dp {
+
+template <typename T> struct Vec;
+template <> struct Vec<bf16> { static constexpr int N = 8; typedef bf16x8 type; };
+template <> struct Vec<float> { static constexpr int N = 4; typedef f32x4 type; };
+
+template <typename T> __device__ __forceinline__ void load_vec(const T* p, float* out) {
+  typename Vec<T>::type v = *reinterpret_cast<const typename Vec<T>::type*>(p);
+#pragma unroll
+  for (int i = 0; i < Vec<T>::N; ++i) out[i] = to_f<T>(v[i]);
+}
+template <typename T> __device__ __forceinline__ void store_vec(T* p, const float* in) {
+  typename Vec<T>::type v;
+#pragma unroll
+  for (int i = 0; i < Vec<T>::N; ++i) v[i] = from_f<T>(in[i]);
+  *reinterpret_cast<typename Vec<T>::type*>(p) = v;
+}
+
+constexpr int LN_MAXCH = 4;   // a lane holds up to 4 vectors of the row: d <= 64 * 4 * Vec::N
+
+// ------------------------------------------------------------------ LayerNorm forward
+template <typename T>
+__global__ void __launch_bounds__(256) ln_fwd_kernel(int rows, int d, float eps, const T* __restrict__ x, T* __restrict__ y,
+                                                     const T* __restrict__ gamma, const T* __restrict__ beta,
+                                                     const T* __restrict__ scale, const T* __restrict__ shift, int mod_ld,
+                                                     int rows_per_batch, float* __restrict__ mean, float* __restrict__ rstd) {
+  constexpr int V = Vec<T>::N;
+  const int lane = threadIdx.x & 63, row = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= rows) return;
+  const T* xr = x + (size_t)row * d;
+  float v[LN_MAXCH][V];
+  float s = 0.f;
+#pragma unroll
+  for (int c = 0; c < LN_MAXCH; ++c) {
+    const int col = (c * 64 + lane) * V;
+    if (col < d) {
+      load_vec<T>(xr + col, v[c]);
+#pragma unroll
+      for (int i = 0; i < V; ++i) s += v[c][i];
+    }
+  }
+  const float mu = wave_sum(s) / d;
+  float q = 0.f;
+#pragma unroll
+  for (int c = 0; c < LN_MAXCH; ++c) {
+    const int col = (c * 64 + lane) * V;
+    if (col < d) {
+#pragma unroll
+      for (int i = 0; i < V; ++i) { v[c][i] -= mu; q += v[c][i] * v[c][i]; }
+    }
+  }
+  const float rs = rsqrtf(wave_sum(q) / d + eps);
+  if (lane == 0) {
+    if (mean) mean[row] = mu;
+    if (rstd) rstd[row] = rs;
+  }
+  const size_t mrow = scale ? (size_t)(row / rows_per_batch) * mod_ld : 0;
+#pragma unroll
+  for (int c = 0; c < LN_MAXCH; ++c) {
+    const int col = (c * 64 + lane) * V;
+    if (col < d) {
+      float o[V], a[V], b[V];
+      if (scale) {
+        load_vec<T>(scale + mrow + col, a);
+        load_vec<T>(shift + mrow + col, b);
+#pragma unroll
+        for (int i = 0; i < V; ++i) o[i] = v[c][i] * rs * (1.0f + a[i]) + b[i];
+      } else if (gamma) {
+        load_vec<T>(gamma + col, a);
+        load_vec<T>(beta + col, b);
+#pragma unroll
+        for (int i = 0; i < V; ++i) o[i] = v[c][i] * rs * a[i] + b[i];
+      } else {
+#pragma unroll
+        for (int i = 0; i < V; ++i) o[i] = v[c][i] * rs;
+      }
+      store_vec<T>(y + (size_t)row * d + col, o);
+    }
+  }
+}
+
+template <typename T>
+static int ln_fwd_t(const LnArgs& a, hipStream_t s) {
+  hipLaunchKernelGGL(ln_fwd_kernel<T>, dim3((a.rows + 3) / 4), dim3(256), 0, s, a.rows, a.d, a.eps, (const T*)a.x, (T*)a.y,
+                     (const T*)a.gamma, (const T*)a.beta, (const T*)a.scale, (const T*)a.shift, a.mod_ld,
+                     a.rows_per_batch > 0 ? a.rows_per_batch : a.rows, a.mean, a.rstd);
+  return hipGetLastError() == hipSuccess ? DP_OK : set_error(DP_EHIP, "ln_fwd launch failed");
+}
+
+static int check_ln_dim(int dtype, int d) {
+  const int V = dtype == BF16 ? 8 : 4;
+  if (d <= 0 || d % V) return set_error(DP_EUNSUPPORTED, "layernorm: d must be a positive multiple of 8 (bf16) / 4 (fp32)");
+  if (d > 64 * LN_MAXCH * V) return set_error(DP_EUNSUPPORTED, "layernorm: d too large (max 2048 bf16 / 1024 fp32)");
+  return DP_OK;
+}
+
+int launch_ln_fwd(const LnArgs& a, hipStream_t s) {
+  if (a.rows <= 0 || !a.x || !a.y) return set_error(DP_EINVAL, "ln_fwd: bad arguments");
+  if (int e = check_ln_dim(a.dtype, a.d)) return e;
+  if ((a.gamma == nullptr) != (a.beta == nullptr) || (a.scale == nullptr) != (a.shift == nullptr))
+    return set_error(DP_EINVAL, "ln_fwd: gamma/beta and scale/shift come in pairs");
+  return a.dtype == BF16 ? ln_fwd_t<bf16>(a, s) : ln_fwd_t<float>(a, s);
+}
+
+// ------------------------------------------------------------------ LayerNorm backward
+constexpr int LNB_ROWS = 64;   // rows per workgroup (16 per wave)
+
+// grid = (chunks_per_batch, n_batches).  partial: [batch][chunk][2][d]
+template <typename T>
+__global__ void __launch_bounds__(256) ln_bwd_kernel(int d, int rows_per_batch, const T* __restrict__ dy, const T* __restrict__ x,
+                                                     const float* __restrict__ mean, const float* __restrict__ rstd,
+                                                     const T* __restrict__ gamma, const T* __restrict__ scale, int mod_ld,
+                                                     const T* __restrict__ dres, T* __restrict__ dx, float* __restrict__ partial) {
+  constexpr int V = Vec<T>::N;
+  __shared__ float red[4][2];
+  extern __shared__ float cols[];   // [4 waves][2][d]
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int b = blockIdx.y;
+  const int r_begin = blockIdx.x * LNB_ROWS, r_end = min(rows_per_batch, r_begin + LNB_ROWS);
+  (void)red;
+  float gsum[LN_MAXCH][V], bsum[LN_MAXCH][V], gain[LN_MAXCH][V];
+#pragma unroll
+  for (int c = 0; c < LN_MAXCH; ++c) {
+    const int col = (c * 64 + lane) * V;
+#pragma unroll
+    for (int i = 0; i < V; ++i) { gsum[c][i] = 0.f; bsum[c][i] = 0.f; gain[c][i] = 1.f; }
+    if (col < d) {
+      if (scale) {
+        load_vec<T>(scale + (size_t)b * mod_ld + col, gain[c]);
+#pragma unroll
+        for (int i = 0; i < V; ++i) gain[c][i] += 1.0f;
+      } else if (gamma) {
+        load_vec<T>(gamma + col, gain[c]);
+      }
+    }
+  }
+  for (int r = r_begin + wave; r < r_end; r += 4) {
+    const size_t row = (size_t)b * rows_per_batch + r;
+    const float mu = mean[row], rs = rstd[row];
+    float g[LN_MAXCH][V], xh[LN_MAXCH][V];
+    float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+    for (int c = 0; c < LN_MAXCH; ++c) {
+      const int col = (c * 64 + lane) * V;
+      if (col < d) {
+        float dyv[V];
+        load_vec<T>(dy + row * d + col, dyv);
+        load_vec<T>(x + row * d + col, xh[c]);
+#pragma unroll
+        for (int i = 0; i < V; ++i) {
+          xh[c][i] = (xh[c][i] - mu) * rs;
+          gsum[c][i] += dyv[i] * xh[c][i];
+          bsum[c][i] += dyv[i];
+          g[c][i] = dyv[i] * gain[c][i];
+          s1 += g[c][i];
+          s2 += g[c][i] * xh[c][i];
+        }
+      }
+    }
+    const float m1 = wave_sum(s1) / d, m2 = wave_sum(s2) / d;
+#pragma unroll
+    for (int c = 0; c < LN_MAXCH; ++c) {
+      const int col = (c * 64 + lane) * V;
+      if (col < d) {
+        float o[V];
+#pragma unroll
+        for (int i = 0; i < V; ++i) o[i] = rs * (g[c][i] - m1 - xh[c][i] * m2);
+        if (dres) {
+          float rr[V];
+          load_vec<T>(dres + row * d + col, rr);
+#pragma unroll
+          for (int i = 0; i < V; ++i) o[i] += rr[i];
+        }
+        store_vec<T>(dx + row * d + col, o);
+      }
+    }
+  }
+  if (!partial) return;
+  // fixed-order reduction of the four waves' column sums
+#pragma unroll
+  for (int c = 0; c < LN_MAXCH; ++c) {
+    const int col = (c * 64 + lane) * V;
+    if (col < d) {
+#pragma unroll
+      for (int i = 0; i < V; ++i) {
+        cols[(wave * 2 + 0) * d + col + i] = gsum[c][i];
+        cols[(wave * 2 + 1) * d + col + i] = bsum[c][i];
+      }
+    }
+  }
+  __syncthreads();
+  float* out = partial + ((size_t)b * gridDim.x + blockIdx.x) * 2 * d;
+  for (int i = threadIdx.x; i < 2 * d; i += 256)
+    out[i] = ((cols[i] + cols[2 * d + i]) + cols[4 * d + i]) + cols[6 * d + i];
+}
+
+// out_k[b * ld + col] = (acc ? old : 0) + sum_chunks partial[b][chunk][k][col], k = 0 (gain grad), 1 (shift grad)
+__global__ void ln_bwd_reduce_kernel(const float* __restrict__ partial, int nchunk, int d, float* out0, float* out1, int ld,
+                                     int accumulate) {
+  const int col = blockIdx.x * blockDim.x + threadIdx.x, b = blockIdx.y;
+  if (col >= d) return;
+  float s0 = 0.f, s1 = 0.f;
+  const float* p = partial + (size_t)b * nchunk * 2 * d;
+  for (int c = 0; c < nchunk; ++c) { s0 += p[(size_t)c * 2 * d + col]; s1 += p[(size_t)c * 2 * d + d + col]; }
+  float* o0 = out0 + (size_t)b * ld + col;
+  float* o1 = out1 + (size_t)b * ld + col;
+  *o0 = accumulate ? *o0 + s0 : s0;
+  *o1 = accumulate ? *o1 + s1 : s1;
+}
+
+size_t ln_bwd_partial_bytes(int rows, int d, int rows_per_batch) {
+  if (rows_per_batch <= 0) rows_per_batch = rows;
+  const int nb = rows / rows_per_batch;
+  const int nchunk = (rows_per_batch + LNB_ROWS - 1) / LNB_ROWS;
+  return (size_t)nb * nchunk * 2 * d * sizeof(float);
+}
+
+template <typename T>
+static int ln_bwd_t(const LnBwdArgs& a, int rpb, int nb, int nchunk, float* partial, hipStream_t s) {
+  hipLaunchKernelGGL(ln_bwd_kernel<T>, dim3(nchunk, nb), dim3(256), (size_t)8 * a.d * sizeof(float), s, a.d, rpb, (const T*)a.dy,
+                     (const T*)a.x, a.mean, a.rstd, (const T*)a.gamma, (const T*)a.scale, a.mod_ld, (const T*)a.dres, (T*)a.dx,
+                     partial);
+  return hipGetLastError() == hipSuccess ? DP_OK : set_error(DP_EHIP, "ln_bwd launch failed");
+}
+
+int launch_ln_bwd(const LnBwdArgs& a, hipStream_t s) {
+  if (a.rows <= 0 || !a.dy || !a.x || !a.mean || !a.rstd || !a.dx) return set_error(DP_EINVAL, "ln_bwd: bad arguments");
+  if (int e = check_ln_dim(a.dtype, a.d)) return e;
+  const bool modulated = a.scale != nullptr;
+  const int rpb = modulated ? a.rows_per_batch : a.rows;
+  if (rpb <= 0 || a.rows % rpb) return set_error(DP_EINVAL, "ln_bwd: rows must be a multiple of rows_per_batch");
+  const int nb = a.rows / rpb, nchunk = (rpb + LNB_ROWS - 1) / LNB_ROWS;
+  const bool want_cols = modulated ? (a.dscale && a.dshift) : (a.dgamma && a.dbeta);
+  float* partial = nullptr;
+  if (want_cols) {
+    if (!a.partial || a.partial_bytes < ln_bwd_partial_bytes(a.rows, a.d, rpb)) return set_error(DP_EWORKSPACE, "ln_bwd: partial buffer too small");
+    partial = a.partial;
+  }
+  int e = a.dtype == BF16 ? ln_bwd_t<bf16>(a, rpb, nb, nchunk, partial, s) : ln_bwd_t<float>(a, rpb, nb, nchunk, partial, s);
+  if (e || !want_cols) return e;
+  if (modulated)
+    hipLaunchKernelGGL(ln_bwd_reduce_kernel, dim3((a.d + 255) / 256, nb), dim3(256), 0, s, partial, nchunk, a.d, a.dscale, a.dshift, a.dmod_ld, 0);
+  else
+    hipLaunchKernelGGL(ln_bwd_reduce_kernel, dim3((a.d + 255) / 256, 1), dim3(256), 0, s, partial, nchunk, a.d, a.dgamma, a.dbeta, a.d, a.accumulate);
+  return hipGetLastError() == hipSuccess ? DP_OK : set_error(DP_EHIP, "ln_bwd_reduce launch failed");
+}
+
+// ------------------------------------------------------------------ GeGLU
+template <typename T>
+__global__ void geglu_fwd_kernel(const T* __restrict__ u, T* __restrict__ g, size_t rows, int inner) {
+  constexpr int V = Vec<T>::N;
+  const int per_row = inner / V;
+  const size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x;
+  if (i >= rows * per_row) return;
+  const size_t r = i / per_row; const int c = (int)(i % per_row) * V;
+  float a[V], b[V], o[V];
+  load_vec<T>(u + r * 2 * inner + c, a);
+  load_vec<T>(u + r * 2 * inner + inner + c, b);
+#pragma unroll
+  for (int k = 0; k < V; ++k) o[k] = a[k] * gelu_erf_f(b[k]);
+  store_vec<T>(g + r * inner + c, o);
+}
+template <typename T>
+__global__ void geglu_bwd_kernel(const T* __restrict__ dg, const T* __restrict__ u, T* __restrict__ du, size_t rows, int inner) {
+  constexpr int V = Vec<T>::N;
+  const int per_row = inner / V;
+  const size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x;
+  if (i >= rows * per_row) return;
+  const size_t r = i / per_row; const int c = (int)(i % per_row) * V;
+  float a[V], b[V], dgo[V], o1[V], o2[V];
+  load_vec<T>(u + r * 2 * inner + c, a);
+  load_vec<T>(u + r * 2 * inner + inner + c, b);
+  load_vec<T>(dg + r * inner + c, dgo);
+#pragma unroll
+  for (int k = 0; k < V; ++k) { o1[k] = dgo[k] * gelu_erf_f(b[k]); o2[k] = dgo[k] * a[k] * gelu_erf_grad_f(b[k]); }
+  store_vec<T>(du + r * 2 * inner + c, o1);
+  store_vec<T>(du + r * 2 * inner + inner + c, o2);
+}
+
+static int check_vec(int dtype, int n, const char* what) {
+  const int V = dtype == BF16 ? 8 : 4;
+  if (n <= 0 || n % V) return set_errorf(DP_EUNSUPPORTED, "%s: width must be a positive multiple of %d", what, V);
+  return DP_OK;
+}
+
+int launch_geglu_fwd(int dtype, const void* u, void* g, int rows, int inner, hipStream_t s) {
+  if (int e = check_vec(dtype, inner, "geglu")) return e;
+  const int V = dtype == BF16 ? 8 : 4;
+  const size_t n = (size_t)rows * (inner / V);
+  if (dtype == BF16) hipLaunchKernelGGL(geglu_fwd_kernel<bf16>, dim3((n + 255) / 256), dim3(256), 0, s, (const bf16*)u, (bf16*)g, (size_t)rows, inner);
+  else hipLaunchKernelGGL(geglu_fwd_kernel<float>, dim3((n + 255) / 256), dim3(256), 0, s, (const float*)u, (float*)g, (size_t)rows, inner);
+  return hipGetLastError() == hipSuccess ? DP_OK : set_error(DP_EHIP, "geglu_fwd launch failed");
+}
+int launch_geglu_bwd(int dtype, const void* dg, const void* u, void* du, int rows, int inner, hipStream_t s) {
+  if (int e = check_vec(dtype, inner, "geglu")) return e;
+  const int V = dtype == BF16 ? 8 : 4;
+  const size_t n = (size_t)rows * (inner / V);
+  if (dtype == BF16) hipLaunchKernelGGL(geglu_bwd_kernel<bf16>, dim3((n + 255) / 256), dim3(256), 0, s, (const bf16*)dg, (const bf16*)u, (bf16*)du, (size_t)rows, inner);
+  else hipLaunchKernelGGL(geglu_bwd_kernel<float>, dim3((n + 255) / 256), dim3(256), 0, s, (const float*)dg, (const float*)u, (float*)du, (size_t)rows, inner);
+  return hipGetLastError() == hipSuccess ? DP_OK : set_error(DP_EHIP, "geglu_bwd launch failed");
+}
+
+// ------------------------------------------------------------------ column sums
+constexpr int CS_ROWS = 256;   // rows per workgroup
+constexpr int CS_COLS = 128;   // columns per workgroup (2 per lane)
+
+template <typename T>
+__global__ void __launch_bounds__(256) colsum_kernel(const T* __restrict__ x, int ldx, int rows, int cols, float* __restrict__ partial) {
+  __shared__ float red[4][CS_COLS];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int col = blockIdx.x * CS_COLS + lane * 2;
+  const int r0 = blockIdx.y * CS_ROWS, r1 = min(rows, r0 + CS_ROWS);
+  float s0 = 0.f, s1 = 0.f;
+  if (col < cols) {
+    for (int r = r0 + wave; r < r1; r += 4) {
+      const T* p = x + (size_t)r * ldx + col;
+      s0 += to_f<T>(p[0]);
+      s1 += to_f<T>(p[1]);
+    }
+  }
+  red[wave][lane * 2] = s0; red[wave][lane * 2 + 1] = s1;
+  __syncthreads();
+  if (threadIdx.x < CS_COLS) {
+    const int c = blockIdx.x * CS_COLS + threadIdx.x;
+    if (c < cols) partial[(size_t)blockIdx.y * cols + c] = ((red[0][threadIdx.x] + red[1][threadIdx.x]) + red[2][threadIdx.x]) + red[3][threadIdx.x];
+  }
+}
+
+size_t colsum_partial_bytes(int rows, int cols) { return (size_t)((rows + CS_ROWS - 1) / CS_ROWS) * cols * sizeof(float); }
+
+int launch_colsum(int dtype, const void* x, int ldx, int rows, int cols, float* out, int accumulate, float* partial,
+                  size_t partial_bytes, hipStream_t s) {
+  if (rows <= 0 || cols <= 0 || cols % 2 || !x || !out) return set_error(DP_EINVAL, "colsum: bad arguments (cols must be even)");
+  if (!partial || partial_bytes < colsum_partial_bytes(rows, cols)) return set_error(DP_EWORKSPACE, "colsum: partial buffer too small");
+  dim3 grid((cols + CS_COLS - 1) / CS_COLS, (rows + CS_ROWS - 1) / CS_ROWS);
+  if (dtype == BF16) hipLaunchKernelGGL(colsum_kernel<bf16>, grid, dim3(256), 0, s, (const bf16*)x, ldx, rows, cols, partial);
+  else hipLaunchKernelGGL(colsum_kernel<float>, grid, dim3(256), 0, s, (const float*)x, ldx, rows, cols, partial);
+  if (hipGetLastError() != hipSuccess) return set_error(DP_EHIP, "colsum launch failed");
+  return launch_reduce_partials(partial, grid.y, (size_t)cols, out, accumulate, s);
+}
+
+__global__ void reduce_partials_kernel(const float* __restrict__ partial, int nz, size_t n, float* __restrict__ out, int accumulate) {
+  const size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x;
+  if (i >= n) return;
+  float s = 0.f;
+  for (int z = 0; z < nz; ++z) s += partial[(size_t)z * n + i];
+  out[i] = accumulate ? out[i] + s : s;
+}
+int launch_reduce_partials(const float* partial, int nz, size_t n, float* out, int accumulate, hipStream_t s) {
+  hipLaunchKernelGGL(reduce_partials_kernel, dim3((n + 255) / 256), dim3(256), 0, s, partial, nz, n, out, accumulate);
+  return hipGetLastError() == hipSuccess ? DP_OK : set_error(DP_EHIP, "reduce_partials launch failed");
+}
+
+// ------------------------------------------------------------------ SiLU and its backward
+template <typename T>
+__global__ void silu_kernel(const T* __restrict__ x, T* __restrict__ y, size_t n) {
+  const size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x;
+  if (i < n) y[i] = from_f<T>(silu_f(to_f<T>(x[i])));
+}
+template <typename T>
+__global__ void silu_bwd_kernel(const float* __restrict__ dz, const T* __restrict__ c, float* __restrict__ dc, int accumulate, size_t n) {
+  const size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x;
+  if (i >= n) return;
+  const float v = dz[i] * silu_grad_f(to_f<T>(c[i]));
+  dc[i] = accumulate ? dc[i] + v : v;
+}
+int launch_silu(int dtype, const void* x, void* y, size_t n, hipStream_t s) {
+  if (dtype == BF16) hipLaunchKernelGGL(silu_kernel<bf16>, dim3((n + 255) / 256), dim3(256), 0, s, (const bf16*)x, (bf16*)y, n);
+  else hipLaunchKernelGGL(silu_kernel<float>, dim3((n + 255) / 256), dim3(256), 0, s, (const float*)x, (float*)y, n);
+  return hipGetLastError() == hipSuccess ? DP_OK : set_error(DP_EHIP, "silu launch failed");
+}
+int launch_silu_bwd(int dtype, const float* dz, const void* c, float* dc, int accumulate, size_t n, hipStream_t s) {
+  if (dtype == BF16) hipLaunchKernelGGL(silu_bwd_kernel<bf16>, dim3((n + 255) / 256), dim3(256), 0, s, dz, (const bf16*)c, dc, accumulate, n);
+  else hipLaunchKernelGGL(silu_bwd_kernel<float>, dim3((n + 255) / 256), dim3(256), 0, s, dz, (const float*)c, dc, accumulate, n);
+  return hipGetLastError() == hipSuccess ? DP_OK : set_error(DP_EHIP, "silu_bwd launch failed");
+}
+
+// ------------------------------------------------------------------ gated branch backward
+// grid = (ceil(d / 128), B); each workgroup walks all rows of its batch.
+template <typename T>
+__global__ void __launch_bounds__(256) gate_bwd_kernel(const T* __restrict__ dres, const T* __restrict__ branch, const T* __restrict__ gate,
+                                                       int gate_ld, T* __restrict__ dbranch, float* __restrict__ dgate, int dgate_ld,
+                                                       int rows_per_batch, int d) {
+  __shared__ float red[4][CS_COLS];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int b = blockIdx.y, col = blockIdx.x * CS_COLS + lane * 2;
+  float s0 = 0.f, s1 = 0.f;
+  if (col < d) {
+    const float g0 = to_f<T>(gate[(size_t)b * gate_ld + col]), g1 = to_f<T>(gate[(size_t)b * gate_ld + col + 1]);
+    for (int r = wave; r < rows_per_batch; r += 4) {
+      const size_t o = ((size_t)b * rows_per_batch + r) * d + col;
+      const float d0 = to_f<T>(dres[o]), d1 = to_f<T>(dres[o + 1]);
+      s0 += d0 * to_f<T>(branch[o]);
+      s1 += d1 * to_f<T>(branch[o + 1]);
+      dbranch[o] = from_f<T>(d0 * g0);
+      dbranch[o + 1] = from_f<T>(d1 * g1);
+    }
+  }
+  red[wave][lane * 2] = s0; red[wave][lane * 2 + 1] = s1;
+  __syncthreads();
+  if (threadIdx.x < CS_COLS) {
+    const int c = blockIdx.x * CS_COLS + threadIdx.x;
+    if (c < d) dgate[(size_t)b * dgate_ld + c] = ((red[0][threadIdx.x] + red[1][threadIdx.x]) + red[2][threadIdx.x]) + red[3][threadIdx.x];
+  }
+}
+int launch_gate_bwd(int dtype, const void* dres, const void* branch, const void* gate, int gate_ld, void* dbranch, float* dgate,
+                    int dgate_ld, int B, int rows_per_batch, int d, hipStream_t s) {
+  if (B <= 0 || rows_per_batch <= 0 || d <= 0 || d % 2) return set_error(DP_EINVAL, "gate_bwd: bad sizes");
+  dim3 grid((d + CS_COLS - 1) / CS_COLS, B);
+  if (dtype == BF16) hipLaunchKernelGGL(gate_bwd_kernel<bf16>, grid, dim3(256), 0, s, (const bf16*)dres, (const bf16*)branch, (const bf16*)gate, gate_ld, (bf16*)dbranch, dgate, dgate_ld, rows_per_batch, d);
+  else hipLaunchKernelGGL(gate_bwd_kernel<float>, grid, dim3(256), 0, s, (const float*)dres, (const float*)branch, (const float*)gate, gate_ld, (float*)dbranch, dgate, dgate_ld, rows_per_batch, d);
+  return hipGetLastError() == hipSuccess ? DP_OK : set_error(DP_EHIP, "gate_bwd launch failed");
+}
+
+// ------------------------------------------------------------------ cast, embedding
+template <typename T>
+__global__ void cast_kernel(const float* __restrict__ in, T* __restrict__ out, size_t n) {
+  const size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x;
+  if (i < n) out[i] = from_f<T>(in[i]);
+}
+int launch_cast_from_f32(int dtype, const float* in, void* out, size_t n, hipStream_t s) {
+  if (dtype == BF16) hipLaunchKernelGGL(cast_kernel<bf16>, dim3((n + 255) / 256), dim3(256), 0, s, in, (bf16*)out, n);
+  else hipLaunchKernelGGL(cast_kernel<float>, dim3((n + 255) / 256), dim3(256), 0, s, in, (float*)out, n);
+  return hipGetLastError() == hipSuccess ? DP_OK : set_error(DP_EHIP, "cast launch failed");
+}
+
+// One wave per token row.  Token ids outside [0, vocab) are clamped (ids live on the device
+// and cannot be validated on the host); the sum is rounded once to the storage type.
+template <typename T>
+__global__ void __launch_bounds__(256) embed_kernel(const int32_t* __restrict__ ids, const T* __restrict__ tok, const T* __restrict__ pos,
+                                                    T* __restrict__ x, int rows, int seq, int d, int vocab) {
+  constexpr int V = Vec<T>::N;
+  const int lane = threadIdx.x & 63, row = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= rows) return;
+  int id = ids[row];
+  id = id < 0 ? 0 : (id >= vocab ? vocab - 1 : id);
+  const T* t = tok + (size_t)id * d;
+  const T* p = pos + (size_t)(row % seq) * d;
+  for (int col = lane * V; col < d; col += 64 * V) {
+    float a[V], b[V];
+    load_vec<T>(t + col, a);
+    load_vec<T>(p + col, b);
+#pragma unroll
+    for (int i = 0; i < V; ++i) a[i] += b[i];
+    store_vec<T>(x + (size_t)row * d + col, a);
+  }
+}
+int launch_embed(int dtype, const int32_t* ids, const void* tok, const void* pos, void* x, int rows, int seq, int d, int vocab,
+                 hipStream_t s) {
+  if (int e = check_vec(dtype, d, "embed")) return e;
+  if (rows <= 0 || seq <= 0 || vocab <= 0) return set_error(DP_EINVAL, "embed: bad sizes");
+  if (dtype == BF16) hipLaunchKernelGGL(embed_kernel<bf16>, dim3((rows + 3) / 4), dim3(256), 0, s, ids, (const bf16*)tok, (const bf16*)pos, (bf16*)x, rows, seq, d, vocab);
+  else hipLaunchKernelGGL(embed_kernel<float>, dim3((rows + 3) / 4), dim3(256), 0, s, ids, (const float*)tok, (const float*)pos, (float*)x, rows, seq, d, vocab);
+  return hipGetLastError() == hipSuccess ? DP_OK : set_error(DP_EHIP, "embed launch failed");
+}
+
+}  // namespace dp

@@ -1,0 +1,774 @@
+// Host side of the C ABI: descriptor validation, workspace planning, and the launch
+// sequences of stage_fwd / stage_bwd / encoder_fwd_partial and of the per-layer timing
+// export.  No allocation or synchronisation happens in the compute entry points.
+#include "../../include/dpipe.h"
+#include "dp_kernels.h"
+#include "dp_errors.h"
+
+#include <algorithm>
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <string>
+#include <vector>
+
+namespace dp {
+
+static thread_local char g_err[512] = "";
+int set_error(int code, const char* msg) {
+  snprintf(g_err, sizeof(g_err), "%s", msg);
+  return code;
+}
+int set_errorf(int code, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+  return code;
+}
+
+#define DP_TRY(expr) do { int _e = (expr); if (_e != DP_OK) return _e; } while (0)
+
+static inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+// Bump planner over the caller's workspace; the same code computes sizes (base = nullptr)
+// and pointers.
+struct Plan {
+  char* base; size_t off = 0;
+  explicit Plan(void* b) : base((char*)b) {}
+  void* take(size_t bytes) {
+    void* p = base ? base + off : nullptr;
+    off += align_up(bytes, 256);
+    return p;
+  }
+};
+
+struct ParamInfo { std::string name; int64_t rows, cols; };
+
+struct ProfileHooks {            // optional per-block event recording
+  std::vector<hipEvent_t>* ev = nullptr;
+};
+
+}  // namespace dp
+
+using namespace dp;
+
+struct dp_stage {
+  dp_stage_desc d;
+  std::vector<ParamInfo> params;
+  int per_block;
+  size_t es;      // element size of the storage dtype
+  int T, Tc;      // token rows, context rows
+};
+
+struct dp_encoder {
+  dp_encoder_desc d;
+  std::vector<ParamInfo> params;
+  size_t es;
+};
+
+namespace dp {
+
+// ============================================================ U-Net block plan
+enum { U_LN1_G, U_LN1_B, U_WQKV, U_WO1, U_BO1, U_LN2_G, U_LN2_B, U_WQ2, U_WKV2, U_WO2, U_BO2, U_LN3_G, U_LN3_B, U_W1, U_B1, U_W2, U_B2, U_COUNT };
+enum { D_ADA_W, D_ADA_B, D_WQKV, D_BQKV, D_WO, D_BO, D_FC1_W, D_FC1_B, D_FC2_W, D_FC2_B, D_COUNT };
+
+struct UnetBuf {
+  void *xin, *h1, *qkv, *a1, *x1, *h2, *q2, *kv2, *a2, *x2, *h3, *u, *g;
+  float *mean1, *rstd1, *lse1, *mean2, *rstd2, *lse2, *mean3, *rstd3;
+};
+struct DitBuf {
+  void *xin, *m, *h1, *qkv, *a, *o, *x1, *h2, *f1, *f, *f2;
+  float *mean1, *rstd1, *lse, *mean2, *rstd2;
+};
+struct BwdScratch {
+  void *r0, *r1, *dh, *da, *dqkv, *dq2, *dkv2, *dg, *du, *dm_t, *sc_in;
+  float *delta, *dm, *dcond_pre, *partial; size_t partial_bytes;
+};
+
+static void plan_unet_block(Plan& p, const dp_stage& s, UnetBuf& u, bool with_xin) {
+  const size_t T = s.T, Tc = s.Tc, d = s.d.d_model, inner = s.d.ff_inner, es = s.es;
+  const size_t stat = (size_t)s.d.batch * s.d.n_heads * s.d.tokens * sizeof(float);
+  u.xin = with_xin ? p.take(T * d * es) : nullptr;
+  u.h1 = p.take(T * d * es); u.qkv = p.take(T * 3 * d * es); u.a1 = p.take(T * d * es); u.x1 = p.take(T * d * es);
+  u.h2 = p.take(T * d * es); u.q2 = p.take(T * d * es); u.kv2 = p.take(Tc * 2 * d * es); u.a2 = p.take(T * d * es);
+  u.x2 = p.take(T * d * es); u.h3 = p.take(T * d * es); u.u = p.take(T * 2 * inner * es); u.g = p.take(T * inner * es);
+  u.mean1 = (float*)p.take(T * 4); u.rstd1 = (float*)p.take(T * 4); u.lse1 = (float*)p.take(stat);
+  u.mean2 = (float*)p.take(T * 4); u.rstd2 = (float*)p.take(T * 4); u.lse2 = (float*)p.take(stat);
+  u.mean3 = (float*)p.take(T * 4); u.rstd3 = (float*)p.take(T * 4);
+}
+static void plan_dit_block(Plan& p, const dp_stage& s, DitBuf& u, bool with_xin) {
+  const size_t T = s.T, d = s.d.d_model, ff = s.d.ff_inner, es = s.es, B = s.d.batch;
+  const size_t stat = (size_t)s.d.batch * s.d.n_heads * s.d.tokens * sizeof(float);
+  u.xin = with_xin ? p.take(T * d * es) : nullptr;
+  u.m = p.take(B * 6 * d * es);
+  u.h1 = p.take(T * d * es); u.qkv = p.take(T * 3 * d * es); u.a = p.take(T * d * es); u.o = p.take(T * d * es);
+  u.x1 = p.take(T * d * es); u.h2 = p.take(T * d * es); u.f1 = p.take(T * ff * es); u.f = p.take(T * ff * es);
+  u.f2 = p.take(T * d * es);
+  u.mean1 = (float*)p.take(T * 4); u.rstd1 = (float*)p.take(T * 4); u.lse = (float*)p.take(stat);
+  u.mean2 = (float*)p.take(T * 4); u.rstd2 = (float*)p.take(T * 4);
+}
+
+static size_t partial_need(const dp_stage& s) {
+  const int T = s.T, d = s.d.d_model, ff = s.d.ff_inner;
+  size_t n = 0;
+  auto mx = [&](size_t v) { n = std::max(n, v); };
+  const bool unet = s.d.kind == DP_BLOCK_UNET_XATTN_GEGLU;
+  const int wide = unet ? 2 * ff : ff;
+  // dW GEMMs (M = out features, N = in features, K = rows)
+  mx(gemm_splitk_ws_bytes(3 * d, d, T)); mx(gemm_splitk_ws_bytes(d, d, T));
+  mx(gemm_splitk_ws_bytes(wide, d, T)); mx(gemm_splitk_ws_bytes(d, ff, T));
+  if (unet) mx(gemm_splitk_ws_bytes(2 * d, s.d.ctx_dim, s.Tc));
+  else { mx(gemm_splitk_ws_bytes(6 * d, d, s.d.batch)); mx(gemm_splitk_ws_bytes(s.d.batch, d, 6 * d)); }
+  mx(colsum_partial_bytes(T, std::max(3 * d, wide)));
+  mx(colsum_partial_bytes(s.d.batch, 6 * d));
+  mx(ln_bwd_partial_bytes(T, d, unet ? T : s.d.tokens));
+  return n;
+}
+
+static void plan_bwd_scratch(Plan& p, const dp_stage& s, BwdScratch& b) {
+  const size_t T = s.T, Tc = s.Tc, d = s.d.d_model, ff = s.d.ff_inner, es = s.es, B = s.d.batch;
+  const bool unet = s.d.kind == DP_BLOCK_UNET_XATTN_GEGLU;
+  b.r0 = p.take(T * d * es); b.r1 = p.take(T * d * es); b.dh = p.take(T * d * es); b.da = p.take(T * d * es);
+  b.dqkv = p.take(T * 3 * d * es);
+  b.delta = (float*)p.take((size_t)s.d.batch * s.d.n_heads * s.d.tokens * sizeof(float));
+  if (unet) {
+    b.dq2 = p.take(T * d * es); b.dkv2 = p.take(Tc * 2 * d * es);
+    b.dg = p.take(T * ff * es); b.du = p.take(T * 2 * ff * es);
+    b.dm_t = nullptr; b.dm = nullptr; b.dcond_pre = nullptr;
+  } else {
+    b.dq2 = nullptr; b.dkv2 = nullptr;
+    b.dg = p.take(T * d * es);          // gated-branch gradient (df2 / do)
+    b.du = p.take(T * ff * es);         // df1
+    b.dm = (float*)p.take(B * 6 * d * 4); b.dm_t = p.take(B * 6 * d * es); b.dcond_pre = (float*)p.take(B * d * 4);
+  }
+  b.partial_bytes = partial_need(s);
+  b.partial = (float*)p.take(b.partial_bytes);
+}
+
+struct StagePlan {
+  std::vector<UnetBuf> ub; std::vector<DitBuf> db;
+  void *pp0 = nullptr, *pp1 = nullptr, *sc_in = nullptr;
+  BwdScratch bs{};
+  size_t bytes = 0;
+};
+
+static void make_plan(const dp_stage& s, void* base, bool save, StagePlan& sp) {
+  Plan p(base);
+  const bool unet = s.d.kind == DP_BLOCK_UNET_XATTN_GEGLU;
+  const int nb = save ? s.d.n_blocks : 1;
+  if (!unet) sp.sc_in = p.take((size_t)s.d.batch * s.d.d_model * s.es);
+  if (unet) { sp.ub.resize(nb); for (int i = 0; i < nb; ++i) plan_unet_block(p, s, sp.ub[i], save); }
+  else { sp.db.resize(nb); for (int i = 0; i < nb; ++i) plan_dit_block(p, s, sp.db[i], save); }
+  if (save) plan_bwd_scratch(p, s, sp.bs);
+  else { sp.pp0 = p.take((size_t)s.T * s.d.d_model * s.es); sp.pp1 = p.take((size_t)s.T * s.d.d_model * s.es); }
+  sp.bytes = p.off;
+}
+
+// ============================================================ small GEMM builders
+static GemmArgs gemm_base(int dtype) {
+  GemmArgs g;
+  memset(&g, 0, sizeof(g));
+  g.dtype = dtype;
+  return g;
+}
+// y[M,N] = x[M,K] W[N,K]^T (+ bias)
+static GemmArgs gemm_fwd(int dtype, const void* x, int M, int K, const void* W, int N, const void* bias, void* y) {
+  GemmArgs g = gemm_base(dtype);
+  g.A = x; g.B = W; g.M = M; g.N = N; g.K = K; g.lda = K; g.ldb = K; g.out = y; g.ldo = N; g.bias = bias;
+  return g;
+}
+// dx[M,K] = dy[M,N] W[N,K]
+static GemmArgs gemm_dx(int dtype, const void* dy, int M, int N, const void* W, int K, void* dx) {
+  GemmArgs g = gemm_base(dtype);
+  g.A = dy; g.B = W; g.M = M; g.N = K; g.K = N; g.lda = N; g.ldb = K; g.b_mc = 1; g.out = dx; g.ldo = K;
+  return g;
+}
+// dW[N,K] (+)= dy[M,N]^T x[M,K]   (fp32)
+static GemmArgs gemm_dw(int dtype, const void* dy, int M, int N, const void* x, int K, float* dW, int accumulate,
+                        const BwdScratch& bs) {
+  GemmArgs g = gemm_base(dtype);
+  g.A = dy; g.B = x; g.M = N; g.N = K; g.K = M; g.lda = N; g.ldb = K; g.a_mc = 1; g.b_mc = 1;
+  g.out_f32 = dW; g.ldo32 = K; g.accumulate = accumulate; g.splitk_ws = bs.partial; g.splitk_ws_bytes = bs.partial_bytes;
+  return g;
+}
+
+static AttnArgs attn_base(const dp_stage& s) {
+  AttnArgs a;
+  memset(&a, 0, sizeof(a));
+  a.dtype = s.d.dtype; a.B = s.d.batch; a.H = s.d.n_heads; a.Nq = s.d.tokens; a.d_head = s.d.d_head;
+  a.scale = 1.0f / sqrtf((float)s.d.d_head);
+  return a;
+}
+
+static inline char* at(void* p, size_t elems, size_t es) { return (char*)p + elems * es; }
+static inline const char* at(const void* p, size_t elems, size_t es) { return (const char*)p + elems * es; }
+
+static int record(ProfileHooks* ph, int idx, hipStream_t st) {
+  if (ph && ph->ev) {
+    if (hipEventRecord((*ph->ev)[idx], st) != hipSuccess) return set_error(DP_EHIP, "hipEventRecord failed");
+  }
+  return DP_OK;
+}
+
+// ============================================================ U-Net stage
+static int unet_block_fwd(const dp_stage& s, const void* const* P, const void* x, const void* ctx, void* y, UnetBuf& u,
+                          hipStream_t st) {
+  const int dt = s.d.dtype, T = s.T, Tc = s.Tc, d = s.d.d_model, inner = s.d.ff_inner, dc = s.d.ctx_dim;
+  const size_t es = s.es;
+  LnArgs ln; memset(&ln, 0, sizeof(ln));
+  ln.dtype = dt; ln.rows = T; ln.d = d; ln.eps = s.d.ln_eps;
+  // self-attention
+  ln.x = x; ln.y = u.h1; ln.gamma = P[U_LN1_G]; ln.beta = P[U_LN1_B]; ln.mean = u.mean1; ln.rstd = u.rstd1;
+  DP_TRY(launch_ln_fwd(ln, st));
+  DP_TRY(launch_gemm(gemm_fwd(dt, u.h1, T, d, P[U_WQKV], 3 * d, nullptr, u.qkv), st));
+  AttnArgs a = attn_base(s);
+  a.Nk = s.d.tokens; a.q = u.qkv; a.k = at(u.qkv, d, es); a.v = at(u.qkv, 2 * d, es); a.ldq = a.ldk = a.ldv = 3 * d;
+  a.o = u.a1; a.ldo = d; a.lse = u.lse1;
+  DP_TRY(launch_attn_fwd(a, st));
+  GemmArgs g = gemm_fwd(dt, u.a1, T, d, P[U_WO1], d, P[U_BO1], u.x1);
+  g.residual = x; g.ld_res = d;
+  DP_TRY(launch_gemm(g, st));
+  // cross-attention
+  ln.x = u.x1; ln.y = u.h2; ln.gamma = P[U_LN2_G]; ln.beta = P[U_LN2_B]; ln.mean = u.mean2; ln.rstd = u.rstd2;
+  DP_TRY(launch_ln_fwd(ln, st));
+  DP_TRY(launch_gemm(gemm_fwd(dt, u.h2, T, d, P[U_WQ2], d, nullptr, u.q2), st));
+  DP_TRY(launch_gemm(gemm_fwd(dt, ctx, Tc, dc, P[U_WKV2], 2 * d, nullptr, u.kv2), st));
+  a = attn_base(s);
+  a.Nk = s.d.ctx_tokens; a.q = u.q2; a.ldq = d; a.k = u.kv2; a.v = at(u.kv2, d, es); a.ldk = a.ldv = 2 * d;
+  a.o = u.a2; a.ldo = d; a.lse = u.lse2;
+  DP_TRY(launch_attn_fwd(a, st));
+  g = gemm_fwd(dt, u.a2, T, d, P[U_WO2], d, P[U_BO2], u.x2);
+  g.residual = u.x1; g.ld_res = d;
+  DP_TRY(launch_gemm(g, st));
+  // GeGLU feed-forward
+  ln.x = u.x2; ln.y = u.h3; ln.gamma = P[U_LN3_G]; ln.beta = P[U_LN3_B]; ln.mean = u.mean3; ln.rstd = u.rstd3;
+  DP_TRY(launch_ln_fwd(ln, st));
+  DP_TRY(launch_gemm(gemm_fwd(dt, u.h3, T, d, P[U_W1], 2 * inner, P[U_B1], u.u), st));
+  DP_TRY(launch_geglu_fwd(dt, u.u, u.g, T, inner, st));
+  g = gemm_fwd(dt, u.g, T, inner, P[U_W2], d, P[U_B2], y);
+  g.residual = u.x2; g.ld_res = d;
+  DP_TRY(launch_gemm(g, st));
+  return DP_OK;
+}
+
+static int unet_block_bwd(const dp_stage& s, const void* const* P, void* const* G, int acc, const void* ctx, const void* dy,
+                          void* dx, UnetBuf& u, BwdScratch& b, hipStream_t st) {
+  const int dt = s.d.dtype, T = s.T, Tc = s.Tc, d = s.d.d_model, inner = s.d.ff_inner, dc = s.d.ctx_dim;
+  const size_t es = s.es;
+  auto other = [&](const void* p) -> void* { return p == b.r0 ? b.r1 : b.r0; };
+  auto gf = [&](int i) { return (float*)G[i]; };
+  // ---- feed-forward
+  DP_TRY(launch_gemm(gemm_dx(dt, dy, T, d, P[U_W2], inner, b.dg), st));
+  DP_TRY(launch_gemm(gemm_dw(dt, dy, T, d, u.g, inner, gf(U_W2), acc, b), st));
+  DP_TRY(launch_colsum(dt, dy, d, T, d, gf(U_B2), acc, b.partial, b.partial_bytes, st));
+  DP_TRY(launch_geglu_bwd(dt, b.dg, u.u, b.du, T, inner, st));
+  DP_TRY(launch_gemm(gemm_dx(dt, b.du, T, 2 * inner, P[U_W1], d, b.dh), st));
+  DP_TRY(launch_gemm(gemm_dw(dt, b.du, T, 2 * inner, u.h3, d, gf(U_W1), acc, b), st));
+  DP_TRY(launch_colsum(dt, b.du, 2 * inner, T, 2 * inner, gf(U_B1), acc, b.partial, b.partial_bytes, st));
+  void* dx2 = other(dy);
+  LnBwdArgs lb; memset(&lb, 0, sizeof(lb));
+  lb.dtype = dt; lb.rows = T; lb.d = d; lb.accumulate = acc; lb.partial = b.partial; lb.partial_bytes = b.partial_bytes;
+  lb.dy = b.dh; lb.x = u.x2; lb.mean = u.mean3; lb.rstd = u.rstd3; lb.gamma = P[U_LN3_G]; lb.dres = dy; lb.dx = dx2;
+  lb.dgamma = gf(U_LN3_G); lb.dbeta = gf(U_LN3_B);
+  DP_TRY(launch_ln_bwd(lb, st));
+  // ---- cross-attention
+  DP_TRY(launch_gemm(gemm_dx(dt, dx2, T, d, P[U_WO2], d, b.da), st));
+  DP_TRY(launch_gemm(gemm_dw(dt, dx2, T, d, u.a2, d, gf(U_WO2), acc, b), st));
+  DP_TRY(launch_colsum(dt, dx2, d, T, d, gf(U_BO2), acc, b.partial, b.partial_bytes, st));
+  AttnArgs a = attn_base(s);
+  a.Nk = s.d.ctx_tokens; a.q = u.q2; a.ldq = d; a.k = u.kv2; a.v = at(u.kv2, d, es); a.ldk = a.ldv = 2 * d;
+  a.o = u.a2; a.ldo = d; a.lse = u.lse2; a.dout = b.da; a.lddo = d; a.delta = b.delta;
+  a.dq = b.dq2; a.lddq = d; a.dk = b.dkv2; a.dv = at(b.dkv2, d, es); a.lddk = a.lddv = 2 * d;
+  DP_TRY(launch_attn_bwd(a, st));
+  DP_TRY(launch_gemm(gemm_dx(dt, b.dq2, T, d, P[U_WQ2], d, b.dh), st));
+  DP_TRY(launch_gemm(gemm_dw(dt, b.dq2, T, d, u.h2, d, gf(U_WQ2), acc, b), st));
+  DP_TRY(launch_gemm(gemm_dw(dt, b.dkv2, Tc, 2 * d, ctx, dc, gf(U_WKV2), acc, b), st));
+  void* dx1 = other(dx2);
+  lb.dy = b.dh; lb.x = u.x1; lb.mean = u.mean2; lb.rstd = u.rstd2; lb.gamma = P[U_LN2_G]; lb.dres = dx2; lb.dx = dx1;
+  lb.dgamma = gf(U_LN2_G); lb.dbeta = gf(U_LN2_B);
+  DP_TRY(launch_ln_bwd(lb, st));
+  // ---- self-attention
+  DP_TRY(launch_gemm(gemm_dx(dt, dx1, T, d, P[U_WO1], d, b.da), st));
+  DP_TRY(launch_gemm(gemm_dw(dt, dx1, T, d, u.a1, d, gf(U_WO1), acc, b), st));
+  DP_TRY(launch_colsum(dt, dx1, d, T, d, gf(U_BO1), acc, b.partial, b.partial_bytes, st));
+  a = attn_base(s);
+  a.Nk = s.d.tokens; a.q = u.qkv; a.k = at(u.qkv, d, es); a.v = at(u.qkv, 2 * d, es); a.ldq = a.ldk = a.ldv = 3 * d;
+  a.o = u.a1; a.ldo = d; a.lse = u.lse1; a.dout = b.da; a.lddo = d; a.delta = b.delta;
+  a.dq = b.dqkv; a.dk = at(b.dqkv, d, es); a.dv = at(b.dqkv, 2 * d, es); a.lddq = a.lddk = a.lddv = 3 * d;
+  DP_TRY(launch_attn_bwd(a, st));
+  DP_TRY(launch_gemm(gemm_dx(dt, b.dqkv, T, 3 * d, P[U_WQKV], d, b.dh), st));
+  DP_TRY(launch_gemm(gemm_dw(dt, b.dqkv, T, 3 * d, u.h1, d, gf(U_WQKV), acc, b), st));
+  lb.dy = b.dh; lb.x = u.xin; lb.mean = u.mean1; lb.rstd = u.rstd1; lb.gamma = P[U_LN1_G]; lb.dres = dx1; lb.dx = dx;
+  lb.dgamma = gf(U_LN1_G); lb.dbeta = gf(U_LN1_B);
+  DP_TRY(launch_ln_bwd(lb, st));
+  return DP_OK;
+}
+
+// ============================================================ DiT stage
+static int dit_block_fwd(const dp_stage& s, const void* const* P, const void* x, const void* sc_in, void* y, DitBuf& u,
+                         hipStream_t st) {
+  const int dt = s.d.dtype, T = s.T, d = s.d.d_model, ff = s.d.ff_inner, B = s.d.batch, N = s.d.tokens;
+  const size_t es = s.es;
+  DP_TRY(launch_gemm(gemm_fwd(dt, sc_in, B, d, P[D_ADA_W], 6 * d, P[D_ADA_B], u.m), st));
+  LnArgs ln; memset(&ln, 0, sizeof(ln));
+  ln.dtype = dt; ln.rows = T; ln.d = d; ln.eps = s.d.ln_eps; ln.mod_ld = 6 * d; ln.rows_per_batch = N;
+  ln.x = x; ln.y = u.h1; ln.shift = u.m; ln.scale = at(u.m, d, es); ln.mean = u.mean1; ln.rstd = u.rstd1;
+  DP_TRY(launch_ln_fwd(ln, st));
+  DP_TRY(launch_gemm(gemm_fwd(dt, u.h1, T, d, P[D_WQKV], 3 * d, P[D_BQKV], u.qkv), st));
+  AttnArgs a = attn_base(s);
+  a.Nk = N; a.q = u.qkv; a.k = at(u.qkv, d, es); a.v = at(u.qkv, 2 * d, es); a.ldq = a.ldk = a.ldv = 3 * d;
+  a.o = u.a; a.ldo = d; a.lse = u.lse;
+  DP_TRY(launch_attn_fwd(a, st));
+  GemmArgs g = gemm_fwd(dt, u.a, T, d, P[D_WO], d, P[D_BO], u.x1);
+  g.pre_out = u.o; g.ld_pre = d; g.gate = at(u.m, 2 * d, es); g.gate_ld = 6 * d; g.rows_per_batch = N; g.residual = x; g.ld_res = d;
+  DP_TRY(launch_gemm(g, st));
+  ln.x = u.x1; ln.y = u.h2; ln.shift = at(u.m, 3 * d, es); ln.scale = at(u.m, 4 * d, es); ln.mean = u.mean2; ln.rstd = u.rstd2;
+  DP_TRY(launch_ln_fwd(ln, st));
+  g = gemm_fwd(dt, u.h2, T, d, P[D_FC1_W], ff, P[D_FC1_B], u.f);
+  g.pre_out = u.f1; g.ld_pre = ff; g.act = s.d.gelu_tanh ? 2 : 1;
+  DP_TRY(launch_gemm(g, st));
+  g = gemm_fwd(dt, u.f, T, ff, P[D_FC2_W], d, P[D_FC2_B], y);
+  g.pre_out = u.f2; g.ld_pre = d; g.gate = at(u.m, 5 * d, es); g.gate_ld = 6 * d; g.rows_per_batch = N; g.residual = u.x1; g.ld_res = d;
+  DP_TRY(launch_gemm(g, st));
+  return DP_OK;
+}
+
+static int dit_block_bwd(const dp_stage& s, const void* const* P, void* const* G, int acc, const void* cond, const void* sc_in,
+                         const void* dy, void* dx, float* d_cond, int dcond_acc, DitBuf& u, BwdScratch& b, hipStream_t st) {
+  const int dt = s.d.dtype, T = s.T, d = s.d.d_model, ff = s.d.ff_inner, B = s.d.batch, N = s.d.tokens;
+  const size_t es = s.es;
+  auto other = [&](const void* p) -> void* { return p == b.r0 ? b.r1 : b.r0; };
+  auto gf = [&](int i) { return (float*)G[i]; };
+  // ---- MLP branch
+  DP_TRY(launch_gate_bwd(dt, dy, u.f2, at(u.m, 5 * d, es), 6 * d, b.dg, b.dm + 5 * d, 6 * d, B, N, d, st));
+  GemmArgs g = gemm_dx(dt, b.dg, T, d, P[D_FC2_W], ff, b.du);
+  g.dact_pre = u.f1; g.ld_dact = ff; g.dact_kind = s.d.gelu_tanh ? 2 : 1;
+  DP_TRY(launch_gemm(g, st));
+  DP_TRY(launch_gemm(gemm_dw(dt, b.dg, T, d, u.f, ff, gf(D_FC2_W), acc, b), st));
+  DP_TRY(launch_colsum(dt, b.dg, d, T, d, gf(D_FC2_B), acc, b.partial, b.partial_bytes, st));
+  DP_TRY(launch_gemm(gemm_dx(dt, b.du, T, ff, P[D_FC1_W], d, b.dh), st));
+  DP_TRY(launch_gemm(gemm_dw(dt, b.du, T, ff, u.h2, d, gf(D_FC1_W), acc, b), st));
+  DP_TRY(launch_colsum(dt, b.du, ff, T, ff, gf(D_FC1_B), acc, b.partial, b.partial_bytes, st));
+  void* dx1 = other(dy);
+  LnBwdArgs lb; memset(&lb, 0, sizeof(lb));
+  lb.dtype = dt; lb.rows = T; lb.d = d; lb.partial = b.partial; lb.partial_bytes = b.partial_bytes;
+  lb.mod_ld = 6 * d; lb.rows_per_batch = N; lb.dmod_ld = 6 * d;
+  lb.dy = b.dh; lb.x = u.x1; lb.mean = u.mean2; lb.rstd = u.rstd2; lb.scale = at(u.m, 4 * d, es); lb.dres = dy; lb.dx = dx1;
+  lb.dscale = b.dm + 4 * d; lb.dshift = b.dm + 3 * d;
+  DP_TRY(launch_ln_bwd(lb, st));
+  // ---- attention branch
+  DP_TRY(launch_gate_bwd(dt, dx1, u.o, at(u.m, 2 * d, es), 6 * d, b.dg, b.dm + 2 * d, 6 * d, B, N, d, st));
+  DP_TRY(launch_gemm(gemm_dx(dt, b.dg, T, d, P[D_WO], d, b.da), st));
+  DP_TRY(launch_gemm(gemm_dw(dt, b.dg, T, d, u.a, d, gf(D_WO), acc, b), st));
+  DP_TRY(launch_colsum(dt, b.dg, d, T, d, gf(D_BO), acc, b.partial, b.partial_bytes, st));
+  AttnArgs a = attn_base(s);
+  a.Nk = N; a.q = u.qkv; a.k = at(u.qkv, d, es); a.v = at(u.qkv, 2 * d, es); a.ldq = a.ldk = a.ldv = 3 * d;
+  a.o = u.a; a.ldo = d; a.lse = u.lse; a.dout = b.da; a.lddo = d; a.delta = b.delta;
+  a.dq = b.dqkv; a.dk = at(b.dqkv, d, es); a.dv = at(b.dqkv, 2 * d, es); a.lddq = a.lddk = a.lddv = 3 * d;
+  DP_TRY(launch_attn_bwd(a, st));
+  DP_TRY(launch_gemm(gemm_dx(dt, b.dqkv, T, 3 * d, P[D_WQKV], d, b.dh), st));
+  DP_TRY(launch_gemm(gemm_dw(dt, b.dqkv, T, 3 * d, u.h1, d, gf(D_WQKV), acc, b), st));
+  DP_TRY(launch_colsum(dt, b.dqkv, 3 * d, T, 3 * d, gf(D_BQKV), acc, b.partial, b.partial_bytes, st));
+  lb.dy = b.dh; lb.x = u.xin; lb.mean = u.mean1; lb.rstd = u.rstd1; lb.scale = at(u.m, d, es); lb.dres = dx1; lb.dx = dx;
+  lb.dscale = b.dm + d; lb.dshift = b.dm;
+  DP_TRY(launch_ln_bwd(lb, st));
+  // ---- conditioning path: m = SiLU(cond) W_ada^T + b_ada
+  DP_TRY(launch_cast_from_f32(dt, b.dm, b.dm_t, (size_t)B * 6 * d, st));
+  DP_TRY(launch_gemm(gemm_dw(dt, b.dm_t, B, 6 * d, sc_in, d, gf(D_ADA_W), acc, b), st));
+  DP_TRY(launch_colsum(dt, b.dm_t, 6 * d, B, 6 * d, gf(D_ADA_B), acc, b.partial, b.partial_bytes, st));
+  g = gemm_base(dt);
+  g.A = b.dm_t; g.B = P[D_ADA_W]; g.M = B; g.N = d; g.K = 6 * d; g.lda = 6 * d; g.ldb = d; g.b_mc = 1;
+  g.out_f32 = b.dcond_pre; g.ldo32 = d; g.accumulate = 0; g.splitk_ws = b.partial; g.splitk_ws_bytes = b.partial_bytes;
+  DP_TRY(launch_gemm(g, st));
+  DP_TRY(launch_silu_bwd(dt, b.dcond_pre, cond, d_cond, dcond_acc, (size_t)B * d, st));
+  return DP_OK;
+}
+
+// ============================================================ stage drivers
+static int check_ptr(const void* p, const char* what, size_t align = 16) {
+  if (!p) return set_errorf(DP_EINVAL, "%s is NULL", what);
+  if ((uintptr_t)p % align) return set_errorf(DP_EALIGN, "%s is not %zu-byte aligned", what, align);
+  return DP_OK;
+}
+
+static int check_stage_call(const dp_stage* s, const void* const* params, const void* a, const void* b, const void* c,
+                            const void* ws, size_t ws_bytes, int save) {
+  if (!s) return set_error(DP_EINVAL, "stage handle is NULL");
+  if (!params) return set_error(DP_EINVAL, "params is NULL");
+  for (size_t i = 0; i < s->params.size(); ++i)
+    if (int e = check_ptr(params[i], s->params[i].name.c_str())) return e;
+  DP_TRY(check_ptr(a, "input tensor")); DP_TRY(check_ptr(b, "ctx_or_cond")); DP_TRY(check_ptr(c, "output tensor"));
+  DP_TRY(check_ptr(ws, "workspace", 256));
+  const size_t need = dp_stage_workspace_bytes(s, save);
+  if (ws_bytes < need) return set_errorf(DP_EWORKSPACE, "workspace too small: %zu bytes given, %zu needed", ws_bytes, need);
+  return DP_OK;
+}
+
+static int run_stage_fwd(dp_stage* s, const void* const* params, const void* x, const void* cc, void* y, void* ws, int save,
+                         hipStream_t st, ProfileHooks* ph) {
+  StagePlan sp;
+  make_plan(*s, ws, save != 0, sp);
+  const bool unet = s->d.kind == DP_BLOCK_UNET_XATTN_GEGLU;
+  const int nb = s->d.n_blocks;
+  const size_t act_bytes = (size_t)s->T * s->d.d_model * s->es;
+  if (!unet) DP_TRY(launch_silu(s->d.dtype, cc, sp.sc_in, (size_t)s->d.batch * s->d.d_model, st));
+  const void* cur = x;
+  for (int b = 0; b < nb; ++b) {
+    DP_TRY(record(ph, b, st));
+    const void* const* P = params + (size_t)b * s->per_block;
+    void* out;
+    if (save) {
+      void* xin = unet ? sp.ub[b].xin : sp.db[b].xin;
+      if (b == 0) {
+        if (hipMemcpyAsync(xin, x, act_bytes, hipMemcpyDeviceToDevice, st) != hipSuccess) return set_error(DP_EHIP, "hipMemcpyAsync failed");
+        cur = xin;
+      }
+      out = (b == nb - 1) ? y : (unet ? sp.ub[b + 1].xin : sp.db[b + 1].xin);
+      if (unet) DP_TRY(unet_block_fwd(*s, P, cur, cc, out, sp.ub[b], st));
+      else DP_TRY(dit_block_fwd(*s, P, cur, sp.sc_in, out, sp.db[b], st));
+    } else {
+      out = (b == nb - 1) ? y : ((b & 1) ? sp.pp1 : sp.pp0);
+      if (unet) DP_TRY(unet_block_fwd(*s, P, cur, cc, out, sp.ub[0], st));
+      else DP_TRY(dit_block_fwd(*s, P, cur, sp.sc_in, out, sp.db[0], st));
+    }
+    cur = out;
+  }
+  DP_TRY(record(ph, nb, st));
+  return DP_OK;
+}
+
+static int run_stage_bwd(dp_stage* s, const void* const* params, const void* dy, const void* cc, void* dx, void* d_cond,
+                         void* const* dparams, int acc, void* ws, hipStream_t st, ProfileHooks* ph) {
+  StagePlan sp;
+  make_plan(*s, ws, true, sp);
+  const bool unet = s->d.kind == DP_BLOCK_UNET_XATTN_GEGLU;
+  const int nb = s->d.n_blocks;
+  const void* cur = dy;
+  for (int b = nb - 1; b >= 0; --b) {
+    DP_TRY(record(ph, nb - 1 - b, st));
+    const void* const* P = params + (size_t)b * s->per_block;
+    void* const* G = dparams + (size_t)b * s->per_block;
+    // The block keeps its last residual-stream gradient (dx1) in one of the two scratch
+    // buffers; its dx goes to the other one.  U-Net: dx2 = other(cur), dx1 = other(dx2);
+    // DiT: dx1 = other(cur).
+    auto other = [&](const void* p) -> void* { return p == sp.bs.r0 ? sp.bs.r1 : sp.bs.r0; };
+    void* out;
+    if (b == 0) out = dx;
+    else out = unet ? other(other(other(cur))) : other(other(cur));
+    if (unet) DP_TRY(unet_block_bwd(*s, P, G, acc, cc, cur, out, sp.ub[b], sp.bs, st));
+    else DP_TRY(dit_block_bwd(*s, P, G, acc, cc, sp.sc_in, cur, out, (float*)d_cond, b != nb - 1, sp.db[b], sp.bs, st));
+    cur = out;
+  }
+  DP_TRY(record(ph, nb, st));
+  return DP_OK;
+}
+
+// ============================================================ encoder
+enum { E_LN1_G, E_LN1_B, E_WQKV, E_BQKV, E_WO, E_BO, E_LN2_G, E_LN2_B, E_FC1_W, E_FC1_B, E_FC2_W, E_FC2_B, E_PER_LAYER };
+
+struct EncBuf { void *h, *qkv, *a, *f; size_t bytes; };
+static void plan_encoder(const dp_encoder& e, void* base, int samples, EncBuf& b) {
+  Plan p(base);
+  const size_t R = (size_t)samples * e.d.seq, d = e.d.d_model, es = e.es;
+  b.h = p.take(R * d * es); b.qkv = p.take(R * 3 * d * es); b.a = p.take(R * d * es); b.f = p.take(R * e.d.ff_inner * es);
+  b.bytes = p.off;
+}
+
+static int encoder_layer(const dp_encoder& e, const void* const* params, int layer, const int32_t* ids, void* hidden,
+                         int sample_offset, int n, EncBuf& w, hipStream_t st) {
+  const int dt = e.d.dtype, d = e.d.d_model, seq = e.d.seq, ff = e.d.ff_inner, R = n * seq;
+  const size_t es = e.es;
+  void* x = at(hidden, (size_t)sample_offset * seq * d, es);
+  if (layer == 0)
+    return launch_embed(dt, ids + (size_t)sample_offset * seq, params[0], params[1], x, R, seq, d, e.d.vocab, st);
+  LnArgs ln; memset(&ln, 0, sizeof(ln));
+  ln.dtype = dt; ln.rows = R; ln.d = d; ln.eps = e.d.ln_eps;
+  if (layer == e.d.n_layers + 1) {
+    const void* const* P = params + 2 + (size_t)e.d.n_layers * E_PER_LAYER;
+    ln.x = x; ln.y = x; ln.gamma = P[0]; ln.beta = P[1];
+    return launch_ln_fwd(ln, st);
+  }
+  const void* const* P = params + 2 + (size_t)(layer - 1) * E_PER_LAYER;
+  ln.x = x; ln.y = w.h; ln.gamma = P[E_LN1_G]; ln.beta = P[E_LN1_B];
+  DP_TRY(launch_ln_fwd(ln, st));
+  DP_TRY(launch_gemm(gemm_fwd(dt, w.h, R, d, P[E_WQKV], 3 * d, P[E_BQKV], w.qkv), st));
+  AttnArgs a; memset(&a, 0, sizeof(a));
+  a.dtype = dt; a.B = n; a.H = e.d.n_heads; a.Nq = seq; a.Nk = seq; a.d_head = e.d.d_head; a.causal = e.d.causal;
+  a.scale = 1.0f / sqrtf((float)e.d.d_head);
+  a.q = w.qkv; a.k = at(w.qkv, d, es); a.v = at(w.qkv, 2 * d, es); a.ldq = a.ldk = a.ldv = 3 * d; a.o = w.a; a.ldo = d;
+  DP_TRY(launch_attn_fwd(a, st));
+  GemmArgs g = gemm_fwd(dt, w.a, R, d, P[E_WO], d, P[E_BO], x);
+  g.residual = x; g.ld_res = d;
+  DP_TRY(launch_gemm(g, st));
+  ln.x = x; ln.y = w.h; ln.gamma = P[E_LN2_G]; ln.beta = P[E_LN2_B];
+  DP_TRY(launch_ln_fwd(ln, st));
+  g = gemm_fwd(dt, w.h, R, d, P[E_FC1_W], ff, P[E_FC1_B], w.f);
+  g.act = 3;
+  DP_TRY(launch_gemm(g, st));
+  g = gemm_fwd(dt, w.f, R, ff, P[E_FC2_W], d, P[E_FC2_B], x);
+  g.residual = x; g.ld_res = d;
+  DP_TRY(launch_gemm(g, st));
+  return DP_OK;
+}
+
+static int check_encoder_call(const dp_encoder* e, const void* const* params, const int32_t* ids, const void* hidden,
+                              int global_batch, int lb, int le, int off, int n, const void* ws, size_t ws_bytes) {
+  if (!e) return set_error(DP_EINVAL, "encoder handle is NULL");
+  if (!params) return set_error(DP_EINVAL, "params is NULL");
+  for (size_t i = 0; i < e->params.size(); ++i)
+    if (int err = check_ptr(params[i], e->params[i].name.c_str())) return err;
+  DP_TRY(check_ptr(ids, "ids", 4)); DP_TRY(check_ptr(hidden, "hidden")); DP_TRY(check_ptr(ws, "workspace", 256));
+  if (global_batch <= 0 || off < 0 || n <= 0 || (long)off + n > global_batch)
+    return set_errorf(DP_EINVAL, "sample range [%d, %d) outside the global batch of %d", off, off + n, global_batch);
+  if (lb < 0 || le > e->d.n_layers + 2 || lb >= le) return set_errorf(DP_EINVAL, "layer range [%d, %d) invalid (0..%d)", lb, le, e->d.n_layers + 2);
+  if ((long)n * e->d.n_heads > 65535) return set_error(DP_EUNSUPPORTED, "num_samples * n_heads exceeds 65535");
+  const size_t need = dp_encoder_workspace_bytes(e, n);
+  if (ws_bytes < need) return set_errorf(DP_EWORKSPACE, "workspace too small: %zu bytes given, %zu needed", ws_bytes, need);
+  return DP_OK;
+}
+
+static float median(std::vector<float>& v) {
+  std::sort(v.begin(), v.end());
+  const size_t n = v.size();
+  return n % 2 ? v[n / 2] : 0.5f * (v[n / 2 - 1] + v[n / 2]);
+}
+
+}  // namespace dp
+
+// ============================================================ extern "C"
+extern "C" {
+
+const char* dp_last_error(void) { return dp::g_err; }
+
+int dp_stage_create(const dp_stage_desc* desc, dp_stage** out) {
+  if (!desc || !out) return set_error(DP_EINVAL, "dp_stage_create: NULL argument");
+  const dp_stage_desc& d = *desc;
+  if (d.kind != DP_BLOCK_UNET_XATTN_GEGLU && d.kind != DP_BLOCK_DIT_ADALN_ZERO) return set_error(DP_EINVAL, "unknown block kind");
+  if (d.dtype != DP_F32 && d.dtype != DP_BF16) return set_error(DP_EINVAL, "unknown dtype");
+  if (d.n_blocks <= 0 || d.batch <= 0 || d.tokens <= 0 || d.d_model <= 0 || d.n_heads <= 0 || d.d_head <= 0 || d.ff_inner <= 0)
+    return set_error(DP_EINVAL, "sizes must be positive");
+  if ((long)d.n_heads * d.d_head != d.d_model) return set_error(DP_EINVAL, "d_model must equal n_heads * d_head");
+  if (!(d.ln_eps > 0.f)) return set_error(DP_EINVAL, "ln_eps must be positive");
+  const bool unet = d.kind == DP_BLOCK_UNET_XATTN_GEGLU;
+  if (unet && (d.ctx_tokens <= 0 || d.ctx_dim <= 0)) return set_error(DP_EINVAL, "ctx_tokens and ctx_dim must be positive");
+  if ((long)d.batch * d.tokens > (1L << 30) || (long)d.batch * d.n_heads > 65535)
+    return set_error(DP_EUNSUPPORTED, "batch * tokens or batch * heads too large");
+  if (d.n_blocks > 4096) return set_error(DP_EUNSUPPORTED, "too many blocks");
+  const int V = d.dtype == DP_BF16 ? 8 : 4;
+  if (d.d_model % V || d.ff_inner % V || d.d_head % (d.dtype == DP_BF16 ? 8 : 1) || (unet && d.ctx_dim % V))
+    return set_errorf(DP_EUNSUPPORTED, "d_model, ff_inner, ctx_dim (and d_head for bf16) must be multiples of %d", V);
+  if (d.dtype == DP_BF16 && (d.d_head > 96 || d.d_model > 2048)) return set_error(DP_EUNSUPPORTED, "bf16 path: d_head <= 96, d_model <= 2048");
+  if (d.dtype == DP_F32 && (d.d_head > 256 || d.d_model > 1024 || d.tokens > 7500 || (unet && d.ctx_tokens > 7500)))
+    return set_error(DP_EUNSUPPORTED, "fp32 path: d_head <= 256, d_model <= 1024, tokens <= 7500");
+  dp_stage* s = new (std::nothrow) dp_stage();
+  if (!s) return set_error(DP_EINVAL, "out of host memory");
+  s->d = d;
+  s->es = dtype_size(d.dtype);
+  s->T = d.batch * d.tokens;
+  s->Tc = unet ? d.batch * d.ctx_tokens : 0;
+  const int64_t dm = d.d_model, inner = d.ff_inner, dc = d.ctx_dim;
+  struct Spec { const char* n; int64_t r, c; };
+  std::vector<Spec> per;
+  if (unet) {
+    per = {{"ln1_g", dm, 0}, {"ln1_b", dm, 0}, {"attn1_wqkv", 3 * dm, dm}, {"attn1_wo", dm, dm}, {"attn1_bo", dm, 0},
+           {"ln2_g", dm, 0}, {"ln2_b", dm, 0}, {"attn2_wq", dm, dm}, {"attn2_wkv", 2 * dm, dc}, {"attn2_wo", dm, dm},
+           {"attn2_bo", dm, 0}, {"ln3_g", dm, 0}, {"ln3_b", dm, 0}, {"ff_w1", 2 * inner, dm}, {"ff_b1", 2 * inner, 0},
+           {"ff_w2", dm, inner}, {"ff_b2", dm, 0}};
+  } else {
+    per = {{"ada_w", 6 * dm, dm}, {"ada_b", 6 * dm, 0}, {"attn_wqkv", 3 * dm, dm}, {"attn_bqkv", 3 * dm, 0}, {"attn_wo", dm, dm},
+           {"attn_bo", dm, 0}, {"fc1_w", inner, dm}, {"fc1_b", inner, 0}, {"fc2_w", dm, inner}, {"fc2_b", dm, 0}};
+  }
+  s->per_block = (int)per.size();
+  for (int b = 0; b < d.n_blocks; ++b)
+    for (auto& sp : per) s->params.push_back({"block" + std::to_string(b) + "." + sp.n, sp.r, sp.c});
+  *out = s;
+  return DP_OK;
+}
+
+void dp_stage_destroy(dp_stage* st) { delete st; }
+
+int dp_stage_param_count(const dp_stage* st) { return st ? (int)st->params.size() : set_error(DP_EINVAL, "stage handle is NULL"); }
+
+int dp_stage_param_shape(const dp_stage* st, int idx, int64_t shape[2], const char** name) {
+  if (!st || !shape) return set_error(DP_EINVAL, "dp_stage_param_shape: NULL argument");
+  if (idx < 0 || idx >= (int)st->params.size()) return set_error(DP_EINVAL, "parameter index out of range");
+  shape[0] = st->params[idx].rows; shape[1] = st->params[idx].cols;
+  if (name) *name = st->params[idx].name.c_str();
+  return DP_OK;
+}
+
+size_t dp_stage_workspace_bytes(const dp_stage* st, int save_for_bwd) {
+  if (!st) return 0;
+  StagePlan sp;
+  make_plan(*st, nullptr, save_for_bwd != 0, sp);
+  return sp.bytes;
+}
+
+int stage_fwd(dp_stage* st, const void* const* params, const void* x, const void* ctx_or_cond, void* y, void* workspace,
+              size_t workspace_bytes, int save_for_bwd, void* hip_stream) {
+  DP_TRY(check_stage_call(st, params, x, ctx_or_cond, y, workspace, workspace_bytes, save_for_bwd != 0));
+  return run_stage_fwd(st, params, x, ctx_or_cond, y, workspace, save_for_bwd != 0, (hipStream_t)hip_stream, nullptr);
+}
+
+int stage_bwd(dp_stage* st, const void* const* params, const void* dy, const void* ctx_or_cond, void* dx, void* d_cond,
+              void* const* dparams, int accumulate, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  DP_TRY(check_stage_call(st, params, dy, ctx_or_cond, dx, workspace, workspace_bytes, 1));
+  if (!dparams) return set_error(DP_EINVAL, "dparams is NULL");
+  for (size_t i = 0; i < st->params.size(); ++i)
+    if (int e = check_ptr(dparams[i], "parameter gradient")) return e;
+  if (st->d.kind == DP_BLOCK_DIT_ADALN_ZERO) DP_TRY(check_ptr(d_cond, "d_cond"));
+  return run_stage_bwd(st, params, dy, ctx_or_cond, dx, d_cond, dparams, accumulate != 0, workspace, (hipStream_t)hip_stream, nullptr);
+}
+
+int dp_encoder_create(const dp_encoder_desc* desc, dp_encoder** out) {
+  if (!desc || !out) return set_error(DP_EINVAL, "dp_encoder_create: NULL argument");
+  const dp_encoder_desc& d = *desc;
+  if (d.dtype != DP_F32 && d.dtype != DP_BF16) return set_error(DP_EINVAL, "unknown dtype");
+  if (d.n_layers <= 0 || d.d_model <= 0 || d.n_heads <= 0 || d.d_head <= 0 || d.seq <= 0 || d.vocab <= 0 || d.ff_inner <= 0)
+    return set_error(DP_EINVAL, "sizes must be positive");
+  if ((long)d.n_heads * d.d_head != d.d_model) return set_error(DP_EINVAL, "d_model must equal n_heads * d_head");
+  if (!(d.ln_eps > 0.f)) return set_error(DP_EINVAL, "ln_eps must be positive");
+  if (d.causal != 0 && d.causal != 1) return set_error(DP_EINVAL, "causal must be 0 or 1");
+  const int V = d.dtype == DP_BF16 ? 8 : 4;
+  if (d.d_model % V || d.ff_inner % V || d.d_head % (d.dtype == DP_BF16 ? 8 : 1))
+    return set_errorf(DP_EUNSUPPORTED, "d_model, ff_inner (and d_head for bf16) must be multiples of %d", V);
+  if (d.dtype == DP_BF16 && (d.d_head > 96 || d.d_model > 2048)) return set_error(DP_EUNSUPPORTED, "bf16 path: d_head <= 96, d_model <= 2048");
+  if (d.dtype == DP_F32 && (d.d_head > 256 || d.d_model > 1024 || d.seq > 7500)) return set_error(DP_EUNSUPPORTED, "fp32 path: d_head <= 256, d_model <= 1024, seq <= 7500");
+  if (d.n_layers > 4096) return set_error(DP_EUNSUPPORTED, "too many layers");
+  dp_encoder* e = new (std::nothrow) dp_encoder();
+  if (!e) return set_error(DP_EINVAL, "out of host memory");
+  e->d = d;
+  e->es = dtype_size(d.dtype);
+  const int64_t dm = d.d_model, ff = d.ff_inner;
+  e->params.push_back({"tok_emb", d.vocab, dm});
+  e->params.push_back({"pos_emb", d.seq, dm});
+  struct Spec { const char* n; int64_t r, c; };
+  const Spec per[] = {{"ln1_g", dm, 0}, {"ln1_b", dm, 0}, {"wqkv", 3 * dm, dm}, {"bqkv", 3 * dm, 0}, {"wo", dm, dm}, {"bo", dm, 0},
+                      {"ln2_g", dm, 0}, {"ln2_b", dm, 0}, {"fc1_w", ff, dm}, {"fc1_b", ff, 0}, {"fc2_w", dm, ff}, {"fc2_b", dm, 0}};
+  for (int l = 0; l < d.n_layers; ++l)
+    for (auto& sp : per) e->params.push_back({"layer" + std::to_string(l) + "." + sp.n, sp.r, sp.c});
+  e->params.push_back({"lnf_g", dm, 0});
+  e->params.push_back({"lnf_b", dm, 0});
+  *out = e;
+  return DP_OK;
+}
+
+void dp_encoder_destroy(dp_encoder* enc) { delete enc; }
+int dp_encoder_param_count(const dp_encoder* enc) { return enc ? (int)enc->params.size() : set_error(DP_EINVAL, "encoder handle is NULL"); }
+int dp_encoder_param_shape(const dp_encoder* enc, int idx, int64_t shape[2], const char** name) {
+  if (!enc || !shape) return set_error(DP_EINVAL, "dp_encoder_param_shape: NULL argument");
+  if (idx < 0 || idx >= (int)enc->params.size()) return set_error(DP_EINVAL, "parameter index out of range");
+  shape[0] = enc->params[idx].rows; shape[1] = enc->params[idx].cols;
+  if (name) *name = enc->params[idx].name.c_str();
+  return DP_OK;
+}
+size_t dp_encoder_workspace_bytes(const dp_encoder* enc, int max_samples) {
+  if (!enc || max_samples <= 0) return 0;
+  EncBuf b;
+  plan_encoder(*enc, nullptr, max_samples, b);
+  return b.bytes;
+}
+
+int encoder_fwd_partial(dp_encoder* enc, const void* const* params, const int32_t* ids, void* hidden, int global_batch,
+                        int layer_begin, int layer_end, int sample_offset, int num_samples, void* workspace,
+                        size_t workspace_bytes, void* hip_stream) {
+  DP_TRY(check_encoder_call(enc, params, ids, hidden, global_batch, layer_begin, layer_end, sample_offset, num_samples, workspace, workspace_bytes));
+  EncBuf w;
+  plan_encoder(*enc, workspace, num_samples, w);
+  for (int l = layer_begin; l < layer_end; ++l)
+    DP_TRY(encoder_layer(*enc, params, l, ids, hidden, sample_offset, num_samples, w, (hipStream_t)hip_stream));
+  return DP_OK;
+}
+
+int dp_stage_profile(dp_stage* st, const void* const* params, const void* x, const void* ctx_or_cond, void* y, const void* dy,
+                     void* dx, void* d_cond, void* const* dparams, void* workspace, size_t workspace_bytes, int reps,
+                     dp_layer_cost* rows, int max_rows, int* n_rows, void* hip_stream) {
+  DP_TRY(check_stage_call(st, params, x, ctx_or_cond, y, workspace, workspace_bytes, 1));
+  DP_TRY(check_ptr(dy, "dy")); DP_TRY(check_ptr(dx, "dx"));
+  if (!dparams || !rows || !n_rows) return set_error(DP_EINVAL, "dp_stage_profile: NULL argument");
+  for (size_t i = 0; i < st->params.size(); ++i)
+    if (int e = check_ptr(dparams[i], "parameter gradient")) return e;
+  if (st->d.kind == DP_BLOCK_DIT_ADALN_ZERO) DP_TRY(check_ptr(d_cond, "d_cond"));
+  const int nb = st->d.n_blocks;
+  if (reps < 1 || max_rows < nb) return set_error(DP_EINVAL, "dp_stage_profile: reps < 1 or too few rows");
+  hipStream_t s = (hipStream_t)hip_stream;
+  std::vector<hipEvent_t> ef(nb + 1), eb(nb + 1);
+  for (auto* v : {&ef, &eb})
+    for (auto& e : *v)
+      if (hipEventCreate(&e) != hipSuccess) return set_error(DP_EHIP, "hipEventCreate failed");
+  std::vector<std::vector<float>> tf(nb), tb(nb);
+  int rc = DP_OK;
+  for (int r = 0; r < reps && rc == DP_OK; ++r) {
+    ProfileHooks hf, hb;
+    hf.ev = &ef; hb.ev = &eb;
+    rc = run_stage_fwd(st, params, x, ctx_or_cond, y, workspace, 1, s, &hf);
+    if (rc == DP_OK) rc = run_stage_bwd(st, params, dy, ctx_or_cond, dx, d_cond, dparams, 0, workspace, s, &hb);
+    if (rc == DP_OK && hipStreamSynchronize(s) != hipSuccess) rc = set_error(DP_EHIP, "hipStreamSynchronize failed");
+    for (int b = 0; b < nb && rc == DP_OK; ++b) {
+      float ms = 0.f;
+      if (hipEventElapsedTime(&ms, ef[b], ef[b + 1]) != hipSuccess) rc = set_error(DP_EHIP, "hipEventElapsedTime failed");
+      tf[b].push_back(ms);
+      // backward runs blocks in reverse: event i brackets block nb-1-i
+      if (rc == DP_OK && hipEventElapsedTime(&ms, eb[nb - 1 - b], eb[nb - b]) != hipSuccess) rc = set_error(DP_EHIP, "hipEventElapsedTime failed");
+      tb[b].push_back(ms);
+    }
+  }
+  for (auto* v : {&ef, &eb})
+    for (auto& e : *v) (void)hipEventDestroy(e);
+  if (rc != DP_OK) return rc;
+  const int64_t act = (int64_t)st->T * st->d.d_model * st->es;
+  for (int b = 0; b < nb; ++b) {
+    int64_t gbytes = 0;
+    for (int i = 0; i < st->per_block; ++i) {
+      const ParamInfo& pi = st->params[(size_t)b * st->per_block + i];
+      gbytes += pi.rows * (pi.cols ? pi.cols : 1) * 4;
+    }
+    rows[b] = dp_layer_cost{0, b, st->d.batch, median(tf[b]), median(tb[b]), act, act, act, gbytes};
+  }
+  *n_rows = nb;
+  return DP_OK;
+}
+
+int dp_encoder_profile(dp_encoder* enc, const void* const* params, const int32_t* ids, void* hidden, int global_batch,
+                       const int* batches, int n_batches, int reps, void* workspace, size_t workspace_bytes,
+                       dp_layer_cost* rows, int max_rows, int* n_rows, void* hip_stream) {
+  if (!enc || !batches || !rows || !n_rows || n_batches <= 0 || reps < 1) return set_error(DP_EINVAL, "dp_encoder_profile: bad argument");
+  const int nl = enc->d.n_layers + 2;
+  if (max_rows < nl * n_batches) return set_error(DP_EINVAL, "dp_encoder_profile: too few rows");
+  for (int i = 0; i < n_batches; ++i)
+    DP_TRY(check_encoder_call(enc, params, ids, hidden, global_batch, 0, nl, 0, batches[i], workspace, workspace_bytes));
+  hipStream_t s = (hipStream_t)hip_stream;
+  std::vector<hipEvent_t> ev(nl + 1);
+  for (auto& e : ev)
+    if (hipEventCreate(&e) != hipSuccess) return set_error(DP_EHIP, "hipEventCreate failed");
+  int rc = DP_OK, out = 0;
+  for (int bi = 0; bi < n_batches && rc == DP_OK; ++bi) {
+    const int n = batches[bi];
+    EncBuf w;
+    plan_encoder(*enc, workspace, n, w);
+    std::vector<std::vector<float>> t(nl);
+    for (int r = 0; r < reps && rc == DP_OK; ++r) {
+      for (int l = 0; l < nl && rc == DP_OK; ++l) {
+        if (hipEventRecord(ev[l], s) != hipSuccess) rc = set_error(DP_EHIP, "hipEventRecord failed");
+        if (rc == DP_OK) rc = encoder_layer(*enc, params, l, ids, hidden, 0, n, w, s);
+      }
+      if (rc == DP_OK && hipEventRecord(ev[nl], s) != hipSuccess) rc = set_error(DP_EHIP, "hipEventRecord failed");
+      if (rc == DP_OK && hipStreamSynchronize(s) != hipSuccess) rc = set_error(DP_EHIP, "hipStreamSynchronize failed");
+      for (int l = 0; l < nl && rc == DP_OK; ++l) {
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, ev[l], ev[l + 1]) != hipSuccess) rc = set_error(DP_EHIP, "hipEventElapsedTime failed");
+        t[l].push_back(ms);
+      }
+    }
+    const int64_t act = (int64_t)n * enc->d.seq * enc->d.d_model * enc->es;
+    for (int l = 0; l < nl && rc == DP_OK; ++l) rows[out++] = dp_layer_cost{1, l, n, median(t[l]), 0.f, act, act, 0, 0};
+  }
+  for (auto& e : ev) (void)hipEventDestroy(e);
+  if (rc != DP_OK) return rc;
+  *n_rows = out;
+  return DP_OK;
+}
+
+}  // extern "C"

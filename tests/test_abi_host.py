@@ -1,0 +1,108 @@
+"""CPU-only checks of the C ABI: the library loads, exports every symbol the header
+declares, validates descriptors / pointers / workspaces on the host before any launch,
+and agrees with the input generator's parameter tables."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+import synth_inputs as si
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def dp():
+    import paper_2405_01248_amd as dp
+    if not os.path.exists(dp.library_path()):
+        from paper_2405_01248_amd import build
+        build.build(verbose=False)
+    dp.load_library()
+    return dp
+
+
+def _declared_functions():
+    text = open(os.path.join(ROOT, "include", "dpipe.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b([a-z_][a-z0-9_]*)\s*\([^;{]*\)\s*;", text)))
+
+
+def test_every_declared_symbol_is_exported(dp):
+    names = _declared_functions()
+    assert {"stage_fwd", "stage_bwd", "encoder_fwd_partial", "dp_stage_profile", "dp_encoder_profile"} <= set(names)
+    lib = dp.load_library()
+    for n in names:
+        assert hasattr(lib, n), n
+    from paper_2405_01248_amd.binding import EXPORTS
+    assert sorted(EXPORTS) == names
+
+
+def test_param_tables_agree_with_input_generator(dp):
+    for cfg in (si.CONFIG1, si.CONFIG2, si.CONFIG3, si.CONFIG4):
+        kind = dp.KIND_UNET if cfg.kind == si.UNET else dp.KIND_DIT
+        st = dp.Stage(kind, dp.DP_BF16 if cfg.dtype == "bf16" else dp.DP_F32, cfg.n_blocks, cfg.batch, cfg.tokens, cfg.d_model,
+                      cfg.n_heads, cfg.d_head, cfg.ctx_tokens, cfg.ctx_dim, cfg.ff_inner, cfg.ln_eps, cfg.gelu_tanh)
+        assert st.param_specs() == [(n, tuple(s)) for n, s, _ in si.stage_param_specs(cfg)]
+        assert st.workspace_bytes(True) > st.workspace_bytes(False) > 0
+    c = si.CONFIG5
+    enc = dp.Encoder(dp.DP_BF16, c.n_layers, c.d_model, c.n_heads, c.d_head, c.seq, c.vocab, c.ff_inner, c.causal, c.ln_eps)
+    assert enc.param_specs() == [(n, tuple(s)) for n, s, _ in si.encoder_param_specs(c)]
+    assert enc.workspace_bytes(64) > enc.workspace_bytes(1) > 0
+
+
+@pytest.mark.parametrize("bad, code", [
+    (dict(n_heads=9), -1),            # d_model != n_heads * d_head
+    (dict(batch=0), -1),
+    (dict(kind=7), -1),
+    (dict(dtype=5), -1),
+    (dict(ln_eps=0.0), -1),
+    (dict(ctx_tokens=0), -1),
+    (dict(ff_inner=2564), -2),        # not a multiple of 8 in bf16
+    (dict(d_model=1280, n_heads=10, d_head=128), -2),   # head dim beyond the MFMA attention kernels
+])
+def test_bad_descriptors_are_rejected(dp, bad, code):
+    base = dict(kind=0, dtype=1, n_blocks=2, batch=8, tokens=1024, d_model=640, n_heads=10, d_head=64, ctx_tokens=77,
+                ctx_dim=768, ff_inner=2560, ln_eps=1e-5, gelu_tanh=0)
+    base.update(bad)
+    with pytest.raises(dp.DpipeError) as ei:
+        dp.Stage(**base)
+    assert ei.value.code == code and str(ei.value)
+
+
+def test_null_misaligned_and_small_workspace_are_rejected_before_launch(dp):
+    lib = dp.load_library()
+    st = dp.Stage(0, 1, 1, 1, 64, 64, 1, 64, 8, 64, 64)
+    n = len(st.param_specs())
+    good = (C.c_void_p * n)(*([0x10000] * n))
+    x = C.c_void_p(0x20000)
+    ws_bytes = st.workspace_bytes(True)
+    assert lib.stage_fwd(st._h, None, x, x, x, x, ws_bytes, 1, None) == -1
+    assert lib.stage_fwd(None, good, x, x, x, x, ws_bytes, 1, None) == -1
+    assert lib.stage_fwd(st._h, good, None, x, x, x, ws_bytes, 1, None) == -1
+    assert b"NULL" in lib.dp_last_error()
+    assert lib.stage_fwd(st._h, good, C.c_void_p(0x20008), x, x, x, ws_bytes, 1, None) == -4
+    assert lib.stage_fwd(st._h, good, x, x, x, C.c_void_p(0x20010), ws_bytes, 1, None) == -4      # workspace needs 256
+    assert lib.stage_fwd(st._h, good, x, x, x, C.c_void_p(0x20100), ws_bytes - 1, 1, None) == -3
+    assert b"workspace too small" in lib.dp_last_error()
+    bad = (C.c_void_p * n)(*([0x10000] * (n - 1) + [0]))
+    assert lib.stage_fwd(st._h, bad, x, x, x, C.c_void_p(0x20100), ws_bytes, 1, None) == -1
+    assert lib.stage_bwd(st._h, good, x, x, x, None, None, 0, C.c_void_p(0x20100), ws_bytes, None) == -1
+
+    enc = dp.Encoder(1, 2, 64, 1, 64, 16, 100, 128)
+    m = len(enc.param_specs())
+    eg = (C.c_void_p * m)(*([0x10000] * m))
+    ws = C.c_void_p(0x20100)
+    wsb = enc.workspace_bytes(4)
+    call = lambda **k: lib.encoder_fwd_partial(enc._h, eg, x, x, k.get("gb", 8), k.get("lb", 0), k.get("le", 4), k.get("off", 0),
+                                               k.get("n", 4), ws, k.get("wsb", wsb), None)
+    assert call(off=6) == -1            # range leaves the global batch
+    assert call(n=0) == -1
+    assert call(le=5) == -1             # only layers 0..n_layers+1 exist
+    assert call(lb=3, le=3) == -1
+    assert call(wsb=wsb - 1) == -3
+    assert call(n=8, wsb=wsb) == -3     # workspace sized for 4 samples
+
+
+def test_last_error_is_never_null(dp):
+    assert dp.load_library().dp_last_error() is not None
