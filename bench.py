@@ -1,0 +1,243 @@
+#!/usr/bin/env python3
+"""Throughput of the stage-compute hot path on one MI355X.
+
+A step is one pass of the whole hot path over one micro-batch of synthetic input that is
+already resident in HBM: stage forward (saving activations) + stage backward, preceded by
+the extra no-grad forward for the self-conditioned DiT workload; for the text-encoder
+workload a step covers the 64-sample global batch with partial-batch calls.
+Prints ONE JSON line ("Measurement").
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+MFMA_PEAK = 2.5e15      # MI355X dense bf16 MFMA, FLOP/s
+HBM_PEAK = 8.0e12       # B/s
+
+
+def stage_flops(cfg):
+    """Algorithmic FLOPs of one step (2mnk per GEMM; backward = 2x forward except the context
+    K/V projection (weight gradient only); attention backward = 2x forward; no credit for
+    recomputation or padding)."""
+    B, N, d, H, dh = cfg.batch, cfg.tokens, cfg.d_model, cfg.n_heads, cfg.d_head
+    T = B * N
+    if cfg.kind == "unet_xattn_geglu":
+        Lc, dc, inner = cfg.ctx_tokens, cfg.ctx_dim, cfg.ff_inner
+        gemm = 2 * T * d * 3 * d + 2 * T * d * d            # qkv, out
+        gemm += 2 * T * d * d * 2                             # cross q, out
+        gemm += 2 * T * d * 2 * inner + 2 * T * inner * d     # ff
+        kv = 2 * B * Lc * dc * 2 * d
+        attn = 4 * B * H * N * N * dh + 4 * B * H * N * Lc * dh
+        fwd = gemm + kv + attn
+        bwd = 2 * gemm + kv + 2 * attn
+    else:
+        ff = cfg.ff_inner
+        gemm = 2 * T * d * 3 * d + 2 * T * d * d + 2 * T * d * ff * 2 + 2 * B * d * 6 * d
+        attn = 4 * B * H * N * N * dh
+        fwd = gemm + attn
+        bwd = 2 * (gemm + attn)
+    total = (fwd + bwd) * cfg.n_blocks
+    if cfg.self_cond:
+        total += fwd * cfg.n_blocks
+    return float(total)
+
+
+def encoder_flops_per_sample(c):
+    d, ff, S = c.d_model, c.ff_inner, c.seq
+    per_layer = 2 * S * d * 3 * d + 2 * S * d * d + 2 * S * d * ff * 2 + 4 * c.n_heads * S * S * c.d_head
+    return float(per_layer * c.n_layers)
+
+
+def timed(fn, steps, warmup):
+    import torch
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        fn()
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) / steps
+
+
+def cpu_baseline_stage(cfg):
+    """The fp64 oracle as it stands, timed on a bounded sample (a few samples of the workload)."""
+    import synth_inputs as si
+    from oracle import blocks
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+
+    def run(nb):
+        c = cfg.replace(batch=nb)
+        inp = si.make_stage_inputs(c, seed=0)
+        cc = inp["ctx"] if c.kind == si.UNET else inp["cond"]
+        t0 = time.perf_counter()
+        if c.self_cond:
+            blocks.stage_self_conditioned(c.kind, inp["params"], inp["x_sc"], inp["x"], cc, inp["dy"], c.n_blocks, c.n_heads,
+                                          c.ln_eps, bool(c.gelu_tanh))
+        else:
+            _, caches = blocks.stage_fwd(c.kind, inp["params"], inp["x"], cc, c.n_blocks, c.n_heads, c.ln_eps, bool(c.gelu_tanh))
+            blocks.stage_bwd(c.kind, inp["params"], caches, inp["dy"], c.n_heads)
+        return time.perf_counter() - t0
+
+    t1 = run(1)
+    nb, t = 1, t1
+    if t1 < 6.0 and cfg.batch > 1:
+        nb = int(min(cfg.batch, max(2, 12.0 // max(t1, 1e-3))))
+        t = run(nb)
+    return {"value": nb / t, "unit": "samples/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"{nb} of {cfg.batch} samples of {cfg.name}, one fp64 numpy fwd+bwd"
+                      + (" incl. the extra no-grad forward" if cfg.self_cond else "") + f", {t:.1f} s"}
+
+
+# HBM bytes per launch of the dominant kernel measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE),
+# scaled by a copy kernel of known size; see profiles/.  None until measured for the current kernels.
+PMC_TRAFFIC_BYTES = {}
+
+MFMA_KINDS = {"gemm_nt", "gemm_nn", "gemm_tn", "attn_fwd", "attn_bwd_dq", "attn_bwd_dkv"}
+KERNEL_NAMES = {"gemm_nt": "dp::gemm_bf16_kernel<..., A_MC=false, B_MC=false> (y = x W^T)",
+                "gemm_nn": "dp::gemm_bf16_kernel<..., A_MC=false, B_MC=true> (dx = dy W)",
+                "gemm_tn": "dp::gemm_bf16_kernel<..., A_MC=true, B_MC=true> (dW = dy^T x)",
+                "attn_fwd": "dp::attn_fwd_bf16_kernel", "attn_bwd_dq": "dp::attn_bwd_dq_bf16_kernel",
+                "attn_bwd_dkv": "dp::attn_bwd_dkv_bf16_kernel", "ln_fwd": "dp::ln_fwd_kernel", "ln_bwd": "dp::ln_bwd_kernel",
+                "geglu_fwd": "dp::geglu_fwd_kernel", "geglu_bwd": "dp::geglu_bwd_kernel", "reduce": "dp::colsum_kernel"}
+
+
+def kernel_roofline(workload, names, si, DeviceStage, DeviceEncoder, passes=3):
+    import torch
+    from paper_2405_01248_amd import binding
+    if workload == "cfg5":
+        obj = DeviceEncoder(si.CONFIG5, si.make_encoder_inputs(si.CONFIG5, seed=0))
+        run = lambda: obj.run_slices(si.CONFIG5.global_batch)
+    else:
+        obj = DeviceStage(names[workload], si.make_stage_inputs(names[workload], seed=0))
+        run = obj.step
+    run()
+    torch.cuda.synchronize()
+    binding.ktime_begin()
+    for _ in range(passes):
+        run()
+    recs = binding.ktime_end()
+    agg = {}
+    for r in recs:
+        a = agg.setdefault(r["kind"], {"launches": 0, "ms": 0.0, "flops": 0.0, "bytes": 0.0})
+        a["launches"] += 1; a["ms"] += r["ms"]; a["flops"] += r["flops"]; a["bytes"] += r["bytes"]
+    total = sum(a["ms"] for a in agg.values())
+    classes = {}
+    for k, a in sorted(agg.items(), key=lambda kv: -kv[1]["ms"]):
+        c = {"launches_per_step": a["launches"] / passes, "ms_per_step": a["ms"] / passes, "share": a["ms"] / total,
+             "avg_launch_us": 1e3 * a["ms"] / a["launches"]}
+        if k in MFMA_KINDS:
+            c["tflops"] = a["flops"] / (a["ms"] * 1e-3) / 1e12
+        else:
+            c["gbps"] = a["bytes"] / (a["ms"] * 1e-3) / 1e9
+        classes[k] = c
+    dom = max(agg, key=lambda k: agg[k]["ms"])
+    a = agg[dom]
+    if dom in MFMA_KINDS:
+        ach = a["flops"] / (a["ms"] * 1e-3) / 1e12
+        roof = {"bound": "mfma", "achieved": ach, "peak": MFMA_PEAK / 1e12, "unit": "TFLOP/s", "frac": ach / (MFMA_PEAK / 1e12)}
+    else:
+        ach = a["bytes"] / (a["ms"] * 1e-3) / 1e9
+        roof = {"bound": "hbm", "achieved": ach, "peak": HBM_PEAK / 1e9, "unit": "GB/s", "frac": ach / (HBM_PEAK / 1e9)}
+    roof.update(traffic=PMC_TRAFFIC_BYTES.get((workload, dom)), kernel=KERNEL_NAMES.get(dom, dom),
+                avg_launch_us=1e3 * a["ms"] / a["launches"], launches_per_step=a["launches"] / passes,
+                algorithmic_per_launch=(a["flops"] if dom in MFMA_KINDS else a["bytes"]) / a["launches"])
+    del obj
+    return roof, classes
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="cfg2", choices=["cfg2", "cfg3", "cfg4", "cfg5"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-others", action="store_true", help="skip the short runs of the other workloads")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives are part of it); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import synth_inputs as si
+    from paper_2405_01248_amd import load_library
+    from paper_2405_01248_amd.harness import DeviceEncoder, DeviceStage
+    load_library()        # fails loudly if the HIP library is missing
+    torch.cuda.set_device(0)
+
+    names = {"cfg2": si.CONFIG2, "cfg3": si.CONFIG3, "cfg4": si.CONFIG4}
+
+    def run_stage(cfg, steps, warmup):
+        ds = DeviceStage(cfg, si.make_stage_inputs(cfg, seed=0))
+        sec = timed(ds.step, steps, warmup)
+        fl = stage_flops(cfg)
+        return ds, {"samples_per_s": cfg.batch / sec, "ms_per_step": sec * 1e3, "tflops": fl / sec / 1e12,
+                    "mfma_peak_frac": fl / sec / MFMA_PEAK}
+
+    def run_encoder(steps, warmup):
+        c = si.CONFIG5
+        de = DeviceEncoder(c, si.make_encoder_inputs(c, seed=0))
+        out = {}
+        for b in c.slices:
+            sec = timed(lambda: de.run_slices(b), steps, warmup)
+            out[str(b)] = {"samples_per_s": c.global_batch / sec, "ms_per_global_batch": sec * 1e3,
+                           "ms_per_call": sec * 1e3 * b / c.global_batch,
+                           "mfma_peak_frac": encoder_flops_per_sample(c) * c.global_batch / sec / MFMA_PEAK}
+        return de, out
+
+    result = {"n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "higher_is_better": True, "scaling": "weak",
+              "vs_baseline": None, "dtype": "bf16", "data": "synthetic"}
+    if args.workload == "cfg5":
+        de, enc = run_encoder(args.steps, args.warmup)
+        full = enc[str(si.CONFIG5.global_batch)]
+        result.update(metric="encoder_fwd_samples_per_sec", value=full["samples_per_s"], unit="samples/s",
+                      ms_per_step=full["ms_per_global_batch"],
+                      config={"workload": si.CONFIG5.name, "global_batch": 64, "slice_sizes": enc})
+        del de
+    else:
+        cfg = names[args.workload]
+        ds, r = run_stage(cfg, args.steps, args.warmup)
+        result.update(metric="stage_fwd_bwd_samples_per_sec", value=r["samples_per_s"], unit="samples/s",
+                      ms_per_step=r["ms_per_step"], mfma_peak_frac=r["mfma_peak_frac"], achieved_tflops=r["tflops"],
+                      config={"workload": cfg.name, "micro_batch": cfg.batch, "tokens": cfg.tokens, "d_model": cfg.d_model,
+                              "n_blocks": cfg.n_blocks, "self_conditioning": cfg.self_cond,
+                              "algorithmic_tflop_per_step": stage_flops(cfg) / 1e12})
+        del ds
+    torch.cuda.empty_cache()
+
+    if not args.no_others:
+        others = {}
+        for k, c in names.items():
+            if k != args.workload:
+                ds, r = run_stage(c, max(3, args.steps // 3), 2)
+                others[c.name] = r
+                del ds
+                torch.cuda.empty_cache()
+        if args.workload != "cfg5":
+            de, enc = run_encoder(max(3, args.steps // 3), 2)
+            others[si.CONFIG5.name] = enc
+            del de
+        result["other_workloads"] = others
+
+    # Roofline of the dominant kernel: a separate instrumented pass of the same workload in the
+    # same launch configuration, with HIP events around every launch on the launch stream.
+    result["roofline"], result["kernel_classes"] = kernel_roofline(args.workload, names, si, DeviceStage, DeviceEncoder)
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline_stage(names.get(args.workload, si.CONFIG2))
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

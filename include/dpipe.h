@@ -144,6 +144,25 @@ int dp_encoder_profile(dp_encoder* enc, const void* const* params, const int32_t
                        int global_batch, const int* batches, int n_batches, int reps, void* workspace,
                        size_t workspace_bytes, dp_layer_cost* rows, int max_rows, int* n_rows, void* hip_stream);
 
+/* Measurement aid: per-launch kernel timing.  Between dp_ktime_begin and dp_ktime_end every
+ * kernel class the library launches is bracketed by hipEvents on the caller's stream; each
+ * record carries the kernel kind, the algorithmic FLOPs and bytes of that launch (the
+ * accounting used for the roofline figures: 2mnk per GEMM, 4 * B * H * Nq * Nk * d_head per
+ * attention forward, tensor bytes read + written once for the bandwidth-bound kernels) and
+ * its duration.  kind: 0 GEMM y = x W^T, 1 GEMM dx = dy W, 2 GEMM dW = dy^T x, 3 attention
+ * forward, 4 attention dQ, 5 attention dK/dV, 6 LayerNorm forward, 7 LayerNorm backward,
+ * 8 GeGLU forward, 9 GeGLU backward, 10 partial-sum reductions, 11 other, 12 fp32 GEMM,
+ * 13 fp32 attention.  dp_ktime_begin allocates host-side events (max_records pairs);
+ * dp_ktime_end synchronises the device, writes up to max records and frees them.  Not
+ * thread-safe; the recording adds launch overhead, so use it in a pass of its own. */
+typedef struct {
+  int kind, m, n, k;
+  float ms;
+  double flops, bytes;
+} dp_kernel_time;
+int dp_ktime_begin(int max_records);
+int dp_ktime_end(dp_kernel_time* out, int max, int* n);
+
 /* Thread-local description of the last error; never NULL. */
 const char* dp_last_error(void);
 

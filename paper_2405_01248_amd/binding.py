@@ -40,10 +40,18 @@ class LayerCost(C.Structure):
         return {n: getattr(self, n) for n, _ in self._fields_}
 
 
+class KernelTime(C.Structure):
+    _fields_ = [("kind", C.c_int), ("m", C.c_int), ("n", C.c_int), ("k", C.c_int), ("ms", C.c_float), ("flops", C.c_double),
+                ("bytes", C.c_double)]
+
+
+KERNEL_KINDS = {0: "gemm_nt", 1: "gemm_nn", 2: "gemm_tn", 3: "attn_fwd", 4: "attn_bwd_dq", 5: "attn_bwd_dkv", 6: "ln_fwd",
+                7: "ln_bwd", 8: "geglu_fwd", 9: "geglu_bwd", 10: "reduce", 11: "other", 12: "gemm_f32", 13: "attn_f32"}
+
 EXPORTS = ["dp_stage_create", "dp_stage_destroy", "dp_stage_param_count", "dp_stage_param_shape", "dp_stage_workspace_bytes",
            "stage_fwd", "stage_bwd", "dp_encoder_create", "dp_encoder_destroy", "dp_encoder_param_count",
            "dp_encoder_param_shape", "dp_encoder_workspace_bytes", "encoder_fwd_partial", "dp_stage_profile",
-           "dp_encoder_profile", "dp_last_error"]
+           "dp_encoder_profile", "dp_ktime_begin", "dp_ktime_end", "dp_last_error"]
 
 
 def library_path() -> str:
@@ -77,6 +85,8 @@ def load_library():
     lib.encoder_fwd_partial.argtypes = [vp, pp, vp, vp, i, i, i, i, i, vp, sz, vp]
     lib.dp_stage_profile.argtypes = [vp, pp, vp, vp, vp, vp, vp, vp, pp, vp, sz, i, C.POINTER(LayerCost), i, C.POINTER(i), vp]
     lib.dp_encoder_profile.argtypes = [vp, pp, vp, vp, i, C.POINTER(i), i, i, vp, sz, C.POINTER(LayerCost), i, C.POINTER(i), vp]
+    lib.dp_ktime_begin.argtypes = [i]
+    lib.dp_ktime_end.argtypes = [C.POINTER(KernelTime), i, C.POINTER(i)]
     _LIB = lib
     return lib
 
@@ -204,3 +214,16 @@ class Encoder(_Handle):
                                                  len(batches), reps, _ptr(workspace), _nbytes(workspace), rows, len(rows),
                                                  C.byref(n), _stream(stream)))
         return [rows[k].as_dict() for k in range(n.value)]
+
+
+def ktime_begin(max_records: int = 65536):
+    _check(load_library().dp_ktime_begin(max_records))
+
+
+def ktime_end(max_records: int = 65536):
+    """Returns a list of dicts (kind name, m, n, k, ms, flops, bytes), one per recorded launch."""
+    rows = (KernelTime * max_records)()
+    n = C.c_int(0)
+    _check(load_library().dp_ktime_end(rows, max_records, C.byref(n)))
+    return [{"kind": KERNEL_KINDS.get(rows[j].kind, str(rows[j].kind)), "m": rows[j].m, "n": rows[j].n, "k": rows[j].k,
+             "ms": rows[j].ms, "flops": rows[j].flops, "bytes": rows[j].bytes} for j in range(n.value)]

@@ -16,6 +16,7 @@
 #include "dp_device.h"
 #include "dp_kernels.h"
 #include "dp_errors.h"
+#include "dp_ktime.h"
 #include <math.h>
 
 namespace dp {
@@ -591,6 +592,9 @@ static int check_attn(const AttnArgs& a, bool bwd) {
 int launch_attn_fwd(const AttnArgs& a, hipStream_t s) {
   if (int e = check_attn(a, false)) return e;
   const AttnK k = make_k(a);
+  const double fl = 4.0 * a.B * a.H * (double)a.Nq * a.Nk * a.d_head;
+  const double by = dtype_size(a.dtype) * (double)a.B * a.H * a.d_head * (2.0 * a.Nq + 2.0 * a.Nk);
+  KScope ks(a.dtype == BF16 ? KK_ATTN_FWD : KK_ATTN_F32, fl, by, s, a.Nq, a.Nk, a.d_head);
   if (a.dtype == BF16) {
     dim3 grid((a.Nq + 127) / 128, a.B * a.H);
     if (a.d_head <= 64) {
@@ -614,12 +618,18 @@ int launch_attn_bwd(const AttnArgs& a, hipStream_t s) {
   if (a.dtype == BF16) {
     hipLaunchKernelGGL(attn_delta_kernel<bf16>, dgrid, dim3(256), 0, s, (const bf16*)a.o, a.ldo, (const bf16*)a.dout, a.lddo, a.delta, a.B, a.H, a.Nq, a.d_head);
     dim3 gq((a.Nq + 127) / 128, a.B * a.H), gk((a.Nk + 127) / 128, a.B * a.H);
-    if (a.d_head <= 64) {
-      hipLaunchKernelGGL(attn_bwd_dq_bf16_kernel<64>, gq, dim3(256), 0, s, k);
-      hipLaunchKernelGGL(attn_bwd_dkv_bf16_kernel<64>, gk, dim3(256), 0, s, k);
-    } else {
-      hipLaunchKernelGGL(attn_bwd_dq_bf16_kernel<96>, gq, dim3(256), 0, s, k);
-      hipLaunchKernelGGL(attn_bwd_dkv_bf16_kernel<96>, gk, dim3(256), 0, s, k);
+    // algorithmic backward work = 2x forward, split evenly between the two kernels for accounting
+    const double fl = 4.0 * a.B * a.H * (double)a.Nq * a.Nk * a.d_head;
+    const double by = 2.0 * (double)a.B * a.H * a.d_head * (3.0 * a.Nq + 2.0 * a.Nk);
+    {
+      KScope ks(KK_ATTN_BWD_DQ, fl, by, s, a.Nq, a.Nk, a.d_head);
+      if (a.d_head <= 64) hipLaunchKernelGGL(attn_bwd_dq_bf16_kernel<64>, gq, dim3(256), 0, s, k);
+      else hipLaunchKernelGGL(attn_bwd_dq_bf16_kernel<96>, gq, dim3(256), 0, s, k);
+    }
+    {
+      KScope ks(KK_ATTN_BWD_DKV, fl, by, s, a.Nq, a.Nk, a.d_head);
+      if (a.d_head <= 64) hipLaunchKernelGGL(attn_bwd_dkv_bf16_kernel<64>, gk, dim3(256), 0, s, k);
+      else hipLaunchKernelGGL(attn_bwd_dkv_bf16_kernel<96>, gk, dim3(256), 0, s, k);
     }
   } else {
     hipLaunchKernelGGL(attn_delta_kernel<float>, dgrid, dim3(256), 0, s, (const float*)a.o, a.ldo, (const float*)a.dout, a.lddo, a.delta, a.B, a.H, a.Nq, a.d_head);

@@ -18,7 +18,7 @@ inline size_t dtype_size(int dt) { return dt == BF16 ? 2 : 4; }
 // Epilogue, in this order, all optional:
 //   v = acc + bias[n]; if (pre_out) pre_out[m,n] = v; v = act(v);
 //   if (dact_pre) v *= act'(dact_pre[m,n]); if (gate) v *= gate[(m / rows_per_batch) * gate_ld + n];
-//   if (residual) v += residual[m,n]; out[m,n] = v  (storage dtype)
+//   if (residual) v += residual[m,n]; out[m,n] = v  (storage dtype, or fp32 if out_fused_f32)
 // or, when out_f32 is set, the raw product goes to fp32:
 //   out_f32[m,n] = (accumulate ? out_f32[m,n] : 0) + acc   (split-K partial sums are
 //   reduced in a fixed order through `splitk_ws`, so results are run-to-run identical).
@@ -36,6 +36,8 @@ struct GemmArgs {
   const void* dact_pre; int ld_dact; int dact_kind;
   const void* gate; int gate_ld; int rows_per_batch;
   const void* residual; int ld_res;
+  int residual_f32;          // residual is fp32 (the residual stream) although dtype is bf16
+  int out_fused_f32;         // `out` receives the fused-epilogue result as fp32 instead of the storage dtype
   float* splitk_ws; size_t splitk_ws_bytes;
 };
 int launch_gemm(const GemmArgs& a, hipStream_t s);
@@ -71,14 +73,16 @@ int launch_attn_bwd(const AttnArgs& a, hipStream_t s);
 // the output is xhat * (1 + scale) + shift.  mean/rstd (fp32 [rows]) may be null.
 struct LnArgs {
   int dtype; int rows, d; float eps;
-  const void* x; void* y;
+  const void* x; int x_f32;     // x_f32: x is fp32 (the residual stream) although dtype is bf16
+  void* y;
   const void* gamma; const void* beta;
   const void* scale; const void* shift; int mod_ld; int rows_per_batch;
   float* mean; float* rstd;
 };
 int launch_ln_fwd(const LnArgs& a, hipStream_t s);
 
-// dx = [dres +] LN backward of dy.  Affine: dgamma/dbeta (fp32 [d], accumulate flag).
+// dx = [dres +] LN backward of dy.  x (the LayerNorm input) and dres are fp32 residual-stream
+// tensors; the result is written to dx32 (fp32) and/or dx (storage dtype).  Affine: dgamma/dbeta (fp32 [d], accumulate flag).
 // Modulated: dscale/dshift rows written to fp32 [B, dmod_ld] (overwrite) and the
 // effective gain is (1 + scale).  partial is scratch of ln_bwd_partial_bytes().
 struct LnBwdArgs {
@@ -86,8 +90,8 @@ struct LnBwdArgs {
   const void* dy; const void* x; const float* mean; const float* rstd;
   const void* gamma;
   const void* scale; int mod_ld; int rows_per_batch;
-  const void* dres;        // optional residual-stream gradient added to dx
-  void* dx;
+  const void* dres;        // optional fp32 residual-stream gradient added to dx
+  void* dx; float* dx32;
   float* dgamma; float* dbeta; int accumulate;
   float* dscale; float* dshift; int dmod_ld;
   float* partial; size_t partial_bytes;
@@ -113,11 +117,13 @@ int launch_silu(int dtype, const void* x, void* y, size_t n, hipStream_t s);
 // dc[i] (+)= dsilu_in[i] * silu'(c[i])   (fp32 in, storage-dtype c, fp32 out)
 int launch_silu_bwd(int dtype, const float* dz, const void* c, float* dc, int accumulate, size_t n, hipStream_t s);
 
-// Gated-branch backward helper: dbranch[m,n] = dres[m,n] * gate[b,n];
+// Gated-branch backward helper (dres is the fp32 residual-stream gradient): dbranch[m,n] = dres[m,n] * gate[b,n];
 // dgate[b,n] = sum_{rows of batch b} dres[m,n] * branch[m,n]   (fp32, overwrite)
 int launch_gate_bwd(int dtype, const void* dres, const void* branch, const void* gate, int gate_ld,
                     void* dbranch, float* dgate, int dgate_ld, int B, int rows_per_batch, int d, hipStream_t s);
 
+// storage dtype -> fp32
+int launch_cast_to_f32(int dtype, const void* in, float* out, size_t n, hipStream_t s);
 // fp32 [rows, cols] -> storage dtype
 int launch_cast_from_f32(int dtype, const float* in, void* out, size_t n, hipStream_t s);
 

@@ -6,6 +6,7 @@
 #include "dp_device.h"
 #include "dp_kernels.h"
 #include "dp_errors.h"
+#include "dp_ktime.h"
 
 namespace dp {
 
@@ -25,25 +26,36 @@ template <typename T> __device__ __forceinline__ void store_vec(T* p, const floa
   *reinterpret_cast<typename Vec<T>::type*>(p) = v;
 }
 
+// V consecutive fp32 values (V = 4 or 8)
+template <int V> __device__ __forceinline__ void load_f32(const float* p, float* out) {
+#pragma unroll
+  for (int i = 0; i < V; i += 4) *reinterpret_cast<f32x4*>(out + i) = *reinterpret_cast<const f32x4*>(p + i);
+}
+template <int V> __device__ __forceinline__ void store_f32(float* p, const float* in) {
+#pragma unroll
+  for (int i = 0; i < V; i += 4) *reinterpret_cast<f32x4*>(p + i) = *reinterpret_cast<const f32x4*>(in + i);
+}
+
 constexpr int LN_MAXCH = 4;   // a lane holds up to 4 vectors of the row: d <= 64 * 4 * Vec::N
 
 // ------------------------------------------------------------------ LayerNorm forward
-template <typename T>
-__global__ void __launch_bounds__(256) ln_fwd_kernel(int rows, int d, float eps, const T* __restrict__ x, T* __restrict__ y,
+template <typename TX, typename T>
+__global__ void __launch_bounds__(256) ln_fwd_kernel(int rows, int d, float eps, const TX* __restrict__ x, T* __restrict__ y,
                                                      const T* __restrict__ gamma, const T* __restrict__ beta,
                                                      const T* __restrict__ scale, const T* __restrict__ shift, int mod_ld,
                                                      int rows_per_batch, float* __restrict__ mean, float* __restrict__ rstd) {
   constexpr int V = Vec<T>::N;
   const int lane = threadIdx.x & 63, row = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (row >= rows) return;
-  const T* xr = x + (size_t)row * d;
+  const TX* xr = x + (size_t)row * d;
   float v[LN_MAXCH][V];
   float s = 0.f;
 #pragma unroll
   for (int c = 0; c < LN_MAXCH; ++c) {
     const int col = (c * 64 + lane) * V;
     if (col < d) {
-      load_vec<T>(xr + col, v[c]);
+      if (sizeof(TX) == 4) load_f32<V>(reinterpret_cast<const float*>(xr + col), v[c]);
+      else load_vec<T>(reinterpret_cast<const T*>(xr + col), v[c]);
 #pragma unroll
       for (int i = 0; i < V; ++i) s += v[c][i];
     }
@@ -88,9 +100,9 @@ __global__ void __launch_bounds__(256) ln_fwd_kernel(int rows, int d, float eps,
   }
 }
 
-template <typename T>
+template <typename TX, typename T>
 static int ln_fwd_t(const LnArgs& a, hipStream_t s) {
-  hipLaunchKernelGGL(ln_fwd_kernel<T>, dim3((a.rows + 3) / 4), dim3(256), 0, s, a.rows, a.d, a.eps, (const T*)a.x, (T*)a.y,
+  hipLaunchKernelGGL((ln_fwd_kernel<TX, T>), dim3((a.rows + 3) / 4), dim3(256), 0, s, a.rows, a.d, a.eps, (const TX*)a.x, (T*)a.y,
                      (const T*)a.gamma, (const T*)a.beta, (const T*)a.scale, (const T*)a.shift, a.mod_ld,
                      a.rows_per_batch > 0 ? a.rows_per_batch : a.rows, a.mean, a.rstd);
   return hipGetLastError() == hipSuccess ? DP_OK : set_error(DP_EHIP, "ln_fwd launch failed");
@@ -108,25 +120,26 @@ int launch_ln_fwd(const LnArgs& a, hipStream_t s) {
   if (int e = check_ln_dim(a.dtype, a.d)) return e;
   if ((a.gamma == nullptr) != (a.beta == nullptr) || (a.scale == nullptr) != (a.shift == nullptr))
     return set_error(DP_EINVAL, "ln_fwd: gamma/beta and scale/shift come in pairs");
-  return a.dtype == BF16 ? ln_fwd_t<bf16>(a, s) : ln_fwd_t<float>(a, s);
+  KScope ks(KK_LN_FWD, 0.0, a.rows * (double)a.d * (dtype_size(a.dtype) + (a.x_f32 ? 4 : dtype_size(a.dtype))) + 8.0 * a.rows, s, a.rows, a.d);
+  if (a.dtype == BF16) return a.x_f32 ? ln_fwd_t<float, bf16>(a, s) : ln_fwd_t<bf16, bf16>(a, s);
+  return ln_fwd_t<float, float>(a, s);
 }
 
 // ------------------------------------------------------------------ LayerNorm backward
-constexpr int LNB_ROWS = 64;   // rows per workgroup (16 per wave)
+constexpr int LNB_ROWS = 16;   // rows per workgroup (4 per wave)
 
 // grid = (chunks_per_batch, n_batches).  partial: [batch][chunk][2][d]
 template <typename T>
-__global__ void __launch_bounds__(256) ln_bwd_kernel(int d, int rows_per_batch, const T* __restrict__ dy, const T* __restrict__ x,
+__global__ void __launch_bounds__(256) ln_bwd_kernel(int d, int rows_per_batch, const T* __restrict__ dy, const float* __restrict__ x,
                                                      const float* __restrict__ mean, const float* __restrict__ rstd,
                                                      const T* __restrict__ gamma, const T* __restrict__ scale, int mod_ld,
-                                                     const T* __restrict__ dres, T* __restrict__ dx, float* __restrict__ partial) {
+                                                     const float* __restrict__ dres, T* __restrict__ dx, float* __restrict__ dx32,
+                                                     float* __restrict__ partial) {
   constexpr int V = Vec<T>::N;
-  __shared__ float red[4][2];
   extern __shared__ float cols[];   // [4 waves][2][d]
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int b = blockIdx.y;
   const int r_begin = blockIdx.x * LNB_ROWS, r_end = min(rows_per_batch, r_begin + LNB_ROWS);
-  (void)red;
   float gsum[LN_MAXCH][V], bsum[LN_MAXCH][V], gain[LN_MAXCH][V];
 #pragma unroll
   for (int c = 0; c < LN_MAXCH; ++c) {
@@ -154,7 +167,7 @@ __global__ void __launch_bounds__(256) ln_bwd_kernel(int d, int rows_per_batch, 
       if (col < d) {
         float dyv[V];
         load_vec<T>(dy + row * d + col, dyv);
-        load_vec<T>(x + row * d + col, xh[c]);
+        load_f32<V>(x + row * d + col, xh[c]);
 #pragma unroll
         for (int i = 0; i < V; ++i) {
           xh[c][i] = (xh[c][i] - mu) * rs;
@@ -176,11 +189,12 @@ __global__ void __launch_bounds__(256) ln_bwd_kernel(int d, int rows_per_batch, 
         for (int i = 0; i < V; ++i) o[i] = rs * (g[c][i] - m1 - xh[c][i] * m2);
         if (dres) {
           float rr[V];
-          load_vec<T>(dres + row * d + col, rr);
+          load_f32<V>(dres + row * d + col, rr);
 #pragma unroll
           for (int i = 0; i < V; ++i) o[i] += rr[i];
         }
-        store_vec<T>(dx + row * d + col, o);
+        if (dx32) store_f32<V>(dx32 + row * d + col, o);
+        if (dx) store_vec<T>(dx + row * d + col, o);
       }
     }
   }
@@ -203,18 +217,28 @@ __global__ void __launch_bounds__(256) ln_bwd_kernel(int d, int rows_per_batch, 
     out[i] = ((cols[i] + cols[2 * d + i]) + cols[4 * d + i]) + cols[6 * d + i];
 }
 
-// out_k[b * ld + col] = (acc ? old : 0) + sum_chunks partial[b][chunk][k][col], k = 0 (gain grad), 1 (shift grad)
-__global__ void ln_bwd_reduce_kernel(const float* __restrict__ partial, int nchunk, int d, float* out0, float* out1, int ld,
-                                     int accumulate) {
-  const int col = blockIdx.x * blockDim.x + threadIdx.x, b = blockIdx.y;
-  if (col >= d) return;
+// out_k[b * ld + col] = (acc ? old : 0) + sum_chunks partial[b][chunk][k][col], k = 0 (gain grad), 1 (shift grad).
+// grid = (ceil(d / 64), n_batches); 64 columns x 4 chunk groups per workgroup, fixed summation order.
+__global__ void __launch_bounds__(256) ln_bwd_reduce_kernel(const float* __restrict__ partial, int nchunk, int d, float* out0,
+                                                            float* out1, int ld, int accumulate) {
+  __shared__ float red[2][4][64];
+  const int lc = threadIdx.x & 63, grp = threadIdx.x >> 6;
+  const int col = blockIdx.x * 64 + lc, b = blockIdx.y;
   float s0 = 0.f, s1 = 0.f;
-  const float* p = partial + (size_t)b * nchunk * 2 * d;
-  for (int c = 0; c < nchunk; ++c) { s0 += p[(size_t)c * 2 * d + col]; s1 += p[(size_t)c * 2 * d + d + col]; }
-  float* o0 = out0 + (size_t)b * ld + col;
-  float* o1 = out1 + (size_t)b * ld + col;
-  *o0 = accumulate ? *o0 + s0 : s0;
-  *o1 = accumulate ? *o1 + s1 : s1;
+  if (col < d) {
+    const float* p = partial + (size_t)b * nchunk * 2 * d;
+    for (int c = grp; c < nchunk; c += 4) { s0 += p[(size_t)c * 2 * d + col]; s1 += p[(size_t)c * 2 * d + d + col]; }
+  }
+  red[0][grp][lc] = s0; red[1][grp][lc] = s1;
+  __syncthreads();
+  if (grp == 0 && col < d) {
+    s0 = ((red[0][0][lc] + red[0][1][lc]) + red[0][2][lc]) + red[0][3][lc];
+    s1 = ((red[1][0][lc] + red[1][1][lc]) + red[1][2][lc]) + red[1][3][lc];
+    float* o0 = out0 + (size_t)b * ld + col;
+    float* o1 = out1 + (size_t)b * ld + col;
+    *o0 = accumulate ? *o0 + s0 : s0;
+    *o1 = accumulate ? *o1 + s1 : s1;
+  }
 }
 
 size_t ln_bwd_partial_bytes(int rows, int d, int rows_per_batch) {
@@ -227,13 +251,13 @@ size_t ln_bwd_partial_bytes(int rows, int d, int rows_per_batch) {
 template <typename T>
 static int ln_bwd_t(const LnBwdArgs& a, int rpb, int nb, int nchunk, float* partial, hipStream_t s) {
   hipLaunchKernelGGL(ln_bwd_kernel<T>, dim3(nchunk, nb), dim3(256), (size_t)8 * a.d * sizeof(float), s, a.d, rpb, (const T*)a.dy,
-                     (const T*)a.x, a.mean, a.rstd, (const T*)a.gamma, (const T*)a.scale, a.mod_ld, (const T*)a.dres, (T*)a.dx,
-                     partial);
+                     (const float*)a.x, a.mean, a.rstd, (const T*)a.gamma, (const T*)a.scale, a.mod_ld, (const float*)a.dres, (T*)a.dx,
+                     a.dx32, partial);
   return hipGetLastError() == hipSuccess ? DP_OK : set_error(DP_EHIP, "ln_bwd launch failed");
 }
 
 int launch_ln_bwd(const LnBwdArgs& a, hipStream_t s) {
-  if (a.rows <= 0 || !a.dy || !a.x || !a.mean || !a.rstd || !a.dx) return set_error(DP_EINVAL, "ln_bwd: bad arguments");
+  if (a.rows <= 0 || !a.dy || !a.x || !a.mean || !a.rstd || (!a.dx && !a.dx32)) return set_error(DP_EINVAL, "ln_bwd: bad arguments");
   if (int e = check_ln_dim(a.dtype, a.d)) return e;
   const bool modulated = a.scale != nullptr;
   const int rpb = modulated ? a.rows_per_batch : a.rows;
@@ -245,12 +269,13 @@ int launch_ln_bwd(const LnBwdArgs& a, hipStream_t s) {
     if (!a.partial || a.partial_bytes < ln_bwd_partial_bytes(a.rows, a.d, rpb)) return set_error(DP_EWORKSPACE, "ln_bwd: partial buffer too small");
     partial = a.partial;
   }
+  KScope ks(KK_LN_BWD, 0.0, a.rows * (double)a.d * (dtype_size(a.dtype) + 4.0 + (a.dres ? 4.0 : 0.0) + (a.dx ? dtype_size(a.dtype) : 0.0) + (a.dx32 ? 4.0 : 0.0)) + 8.0 * a.rows, s, a.rows, a.d);
   int e = a.dtype == BF16 ? ln_bwd_t<bf16>(a, rpb, nb, nchunk, partial, s) : ln_bwd_t<float>(a, rpb, nb, nchunk, partial, s);
   if (e || !want_cols) return e;
   if (modulated)
-    hipLaunchKernelGGL(ln_bwd_reduce_kernel, dim3((a.d + 255) / 256, nb), dim3(256), 0, s, partial, nchunk, a.d, a.dscale, a.dshift, a.dmod_ld, 0);
+    hipLaunchKernelGGL(ln_bwd_reduce_kernel, dim3((a.d + 63) / 64, nb), dim3(256), 0, s, partial, nchunk, a.d, a.dscale, a.dshift, a.dmod_ld, 0);
   else
-    hipLaunchKernelGGL(ln_bwd_reduce_kernel, dim3((a.d + 255) / 256, 1), dim3(256), 0, s, partial, nchunk, a.d, a.dgamma, a.dbeta, a.d, a.accumulate);
+    hipLaunchKernelGGL(ln_bwd_reduce_kernel, dim3((a.d + 63) / 64, 1), dim3(256), 0, s, partial, nchunk, a.d, a.dgamma, a.dbeta, a.d, a.accumulate);
   return hipGetLastError() == hipSuccess ? DP_OK : set_error(DP_EHIP, "ln_bwd_reduce launch failed");
 }
 
@@ -296,6 +321,7 @@ int launch_geglu_fwd(int dtype, const void* u, void* g, int rows, int inner, hip
   if (int e = check_vec(dtype, inner, "geglu")) return e;
   const int V = dtype == BF16 ? 8 : 4;
   const size_t n = (size_t)rows * (inner / V);
+  KScope ks(KK_GEGLU_FWD, 0.0, 3.0 * rows * (double)inner * dtype_size(dtype), s, rows, inner);
   if (dtype == BF16) hipLaunchKernelGGL(geglu_fwd_kernel<bf16>, dim3((n + 255) / 256), dim3(256), 0, s, (const bf16*)u, (bf16*)g, (size_t)rows, inner);
   else hipLaunchKernelGGL(geglu_fwd_kernel<float>, dim3((n + 255) / 256), dim3(256), 0, s, (const float*)u, (float*)g, (size_t)rows, inner);
   return hipGetLastError() == hipSuccess ? DP_OK : set_error(DP_EHIP, "geglu_fwd launch failed");
@@ -304,6 +330,7 @@ int launch_geglu_bwd(int dtype, const void* dg, const void* u, void* du, int row
   if (int e = check_vec(dtype, inner, "geglu")) return e;
   const int V = dtype == BF16 ? 8 : 4;
   const size_t n = (size_t)rows * (inner / V);
+  KScope ks(KK_GEGLU_BWD, 0.0, 5.0 * rows * (double)inner * dtype_size(dtype), s, rows, inner);
   if (dtype == BF16) hipLaunchKernelGGL(geglu_bwd_kernel<bf16>, dim3((n + 255) / 256), dim3(256), 0, s, (const bf16*)dg, (const bf16*)u, (bf16*)du, (size_t)rows, inner);
   else hipLaunchKernelGGL(geglu_bwd_kernel<float>, dim3((n + 255) / 256), dim3(256), 0, s, (const float*)dg, (const float*)u, (float*)du, (size_t)rows, inner);
   return hipGetLastError() == hipSuccess ? DP_OK : set_error(DP_EHIP, "geglu_bwd launch failed");
@@ -342,6 +369,7 @@ int launch_colsum(int dtype, const void* x, int ldx, int rows, int cols, float* 
   if (rows <= 0 || cols <= 0 || cols % 2 || !x || !out) return set_error(DP_EINVAL, "colsum: bad arguments (cols must be even)");
   if (!partial || partial_bytes < colsum_partial_bytes(rows, cols)) return set_error(DP_EWORKSPACE, "colsum: partial buffer too small");
   dim3 grid((cols + CS_COLS - 1) / CS_COLS, (rows + CS_ROWS - 1) / CS_ROWS);
+  KScope ks(KK_REDUCE, 0.0, (double)rows * cols * dtype_size(dtype), s, rows, cols);
   if (dtype == BF16) hipLaunchKernelGGL(colsum_kernel<bf16>, grid, dim3(256), 0, s, (const bf16*)x, ldx, rows, cols, partial);
   else hipLaunchKernelGGL(colsum_kernel<float>, grid, dim3(256), 0, s, (const float*)x, ldx, rows, cols, partial);
   if (hipGetLastError() != hipSuccess) return set_error(DP_EHIP, "colsum launch failed");
@@ -387,7 +415,7 @@ int launch_silu_bwd(int dtype, const float* dz, const void* c, float* dc, int ac
 // ------------------------------------------------------------------ gated branch backward
 // grid = (ceil(d / 128), B); each workgroup walks all rows of its batch.
 template <typename T>
-__global__ void __launch_bounds__(256) gate_bwd_kernel(const T* __restrict__ dres, const T* __restrict__ branch, const T* __restrict__ gate,
+__global__ void __launch_bounds__(256) gate_bwd_kernel(const float* __restrict__ dres, const T* __restrict__ branch, const T* __restrict__ gate,
                                                        int gate_ld, T* __restrict__ dbranch, float* __restrict__ dgate, int dgate_ld,
                                                        int rows_per_batch, int d) {
   __shared__ float red[4][CS_COLS];
@@ -398,7 +426,7 @@ __global__ void __launch_bounds__(256) gate_bwd_kernel(const T* __restrict__ dre
     const float g0 = to_f<T>(gate[(size_t)b * gate_ld + col]), g1 = to_f<T>(gate[(size_t)b * gate_ld + col + 1]);
     for (int r = wave; r < rows_per_batch; r += 4) {
       const size_t o = ((size_t)b * rows_per_batch + r) * d + col;
-      const float d0 = to_f<T>(dres[o]), d1 = to_f<T>(dres[o + 1]);
+      const float d0 = dres[o], d1 = dres[o + 1];
       s0 += d0 * to_f<T>(branch[o]);
       s1 += d1 * to_f<T>(branch[o + 1]);
       dbranch[o] = from_f<T>(d0 * g0);
@@ -416,7 +444,7 @@ int launch_gate_bwd(int dtype, const void* dres, const void* branch, const void*
                     int dgate_ld, int B, int rows_per_batch, int d, hipStream_t s) {
   if (B <= 0 || rows_per_batch <= 0 || d <= 0 || d % 2) return set_error(DP_EINVAL, "gate_bwd: bad sizes");
   dim3 grid((d + CS_COLS - 1) / CS_COLS, B);
-  if (dtype == BF16) hipLaunchKernelGGL(gate_bwd_kernel<bf16>, grid, dim3(256), 0, s, (const bf16*)dres, (const bf16*)branch, (const bf16*)gate, gate_ld, (bf16*)dbranch, dgate, dgate_ld, rows_per_batch, d);
+  if (dtype == BF16) hipLaunchKernelGGL(gate_bwd_kernel<bf16>, grid, dim3(256), 0, s, (const float*)dres, (const bf16*)branch, (const bf16*)gate, gate_ld, (bf16*)dbranch, dgate, dgate_ld, rows_per_batch, d);
   else hipLaunchKernelGGL(gate_bwd_kernel<float>, grid, dim3(256), 0, s, (const float*)dres, (const float*)branch, (const float*)gate, gate_ld, (float*)dbranch, dgate, dgate_ld, rows_per_batch, d);
   return hipGetLastError() == hipSuccess ? DP_OK : set_error(DP_EHIP, "gate_bwd launch failed");
 }
@@ -430,6 +458,17 @@ __global__ void cast_kernel(const float* __restrict__ in, T* __restrict__ out, s
 int launch_cast_from_f32(int dtype, const float* in, void* out, size_t n, hipStream_t s) {
   if (dtype == BF16) hipLaunchKernelGGL(cast_kernel<bf16>, dim3((n + 255) / 256), dim3(256), 0, s, in, (bf16*)out, n);
   else hipLaunchKernelGGL(cast_kernel<float>, dim3((n + 255) / 256), dim3(256), 0, s, in, (float*)out, n);
+  return hipGetLastError() == hipSuccess ? DP_OK : set_error(DP_EHIP, "cast launch failed");
+}
+
+template <typename T>
+__global__ void cast_to_f32_kernel(const T* __restrict__ in, float* __restrict__ out, size_t n) {
+  const size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x;
+  if (i < n) out[i] = to_f<T>(in[i]);
+}
+int launch_cast_to_f32(int dtype, const void* in, float* out, size_t n, hipStream_t s) {
+  if (dtype == BF16) hipLaunchKernelGGL(cast_to_f32_kernel<bf16>, dim3((n + 255) / 256), dim3(256), 0, s, (const bf16*)in, out, n);
+  else hipLaunchKernelGGL(cast_to_f32_kernel<float>, dim3((n + 255) / 256), dim3(256), 0, s, (const float*)in, out, n);
   return hipGetLastError() == hipSuccess ? DP_OK : set_error(DP_EHIP, "cast launch failed");
 }
 

@@ -10,6 +10,7 @@
 #include "dp_device.h"
 #include "dp_kernels.h"
 #include "dp_errors.h"
+#include "dp_ktime.h"
 
 namespace dp {
 
@@ -24,7 +25,7 @@ struct EpiParams {
   int act;
   const T* dact_pre; int ld_dact; int dact_kind;
   const T* gate; int gate_ld; int rows_per_batch;
-  const T* residual; int ld_res;
+  const void* residual; int ld_res; int residual_f32; int out_fused_f32;
 };
 
 // Epilogue of one accumulator element (bounds already checked by the caller).
@@ -35,7 +36,7 @@ __device__ __forceinline__ void epi_fused(const EpiParams<T>& e, int m, int n, f
   if (e.act) v = act_apply(e.act, v);
   if (e.dact_pre) v *= act_grad(e.dact_kind, to_f<T>(e.dact_pre[(size_t)m * e.ld_dact + n]));
   if (e.gate) v *= to_f<T>(e.gate[(size_t)(m / e.rows_per_batch) * e.gate_ld + n]);
-  if (e.residual) v += to_f<T>(e.residual[(size_t)m * e.ld_res + n]);
+  if (e.residual) v += to_f<T>(((const T*)e.residual)[(size_t)m * e.ld_res + n]);
   e.out[(size_t)m * e.ldo + n] = from_f<T>(v);
 }
 
@@ -237,14 +238,27 @@ gemm_bf16_kernel(const GemmBf16Params p) {
       for (int t = 0; t < 8; ++t) v[t] *= (float)gv[t];
     }
     if (e.residual) {
-      const bf16x8 rv = *reinterpret_cast<const bf16x8*>(e.residual + (size_t)m * e.ld_res + n);
+      if (e.residual_f32) {
+        const float* rp = (const float*)e.residual + (size_t)m * e.ld_res + n;
+        const f32x4 r0 = *reinterpret_cast<const f32x4*>(rp), r1 = *reinterpret_cast<const f32x4*>(rp + 4);
 #pragma unroll
-      for (int t = 0; t < 8; ++t) v[t] += (float)rv[t];
+        for (int t = 0; t < 4; ++t) { v[t] += r0[t]; v[4 + t] += r1[t]; }
+      } else {
+        const bf16x8 rv = *reinterpret_cast<const bf16x8*>((const bf16*)e.residual + (size_t)m * e.ld_res + n);
+#pragma unroll
+        for (int t = 0; t < 8; ++t) v[t] += (float)rv[t];
+      }
     }
-    bf16x8 o;
+    if (e.out_fused_f32) {
+      float* op = reinterpret_cast<float*>(e.out) + (size_t)m * e.ldo + n;
+      *reinterpret_cast<f32x4*>(op) = *reinterpret_cast<const f32x4*>(&v[0]);
+      *reinterpret_cast<f32x4*>(op + 4) = *reinterpret_cast<const f32x4*>(&v[4]);
+    } else {
+      bf16x8 o;
 #pragma unroll
-    for (int t = 0; t < 8; ++t) o[t] = (bf16)v[t];
-    *reinterpret_cast<bf16x8*>(e.out + (size_t)m * e.ldo + n) = o;
+      for (int t = 0; t < 8; ++t) o[t] = (bf16)v[t];
+      *reinterpret_cast<bf16x8*>(e.out + (size_t)m * e.ldo + n) = o;
+    }
   }
 }
 
@@ -310,7 +324,7 @@ static EpiParams<T> make_epi(const GemmArgs& a) {
   e.act = a.act;
   e.dact_pre = (const T*)a.dact_pre; e.ld_dact = a.ld_dact; e.dact_kind = a.dact_kind;
   e.gate = (const T*)a.gate; e.gate_ld = a.gate_ld; e.rows_per_batch = a.rows_per_batch > 0 ? a.rows_per_batch : 1;
-  e.residual = (const T*)a.residual; e.ld_res = a.ld_res;
+  e.residual = a.residual; e.ld_res = a.ld_res; e.residual_f32 = a.residual_f32; e.out_fused_f32 = a.out_fused_f32;
   return e;
 }
 
@@ -387,6 +401,8 @@ int launch_gemm(const GemmArgs& a, hipStream_t s) {
     for (int x : elds) if (x % 8 || x < 8) return set_error(DP_EUNSUPPORTED, "gemm(bf16): epilogue leading dims must be multiples of 8");
     const void* eps[] = {a.out, a.out_f32, a.bias, a.pre_out, a.dact_pre, a.gate, a.residual, a.splitk_ws};
     for (const void* x : eps) if ((uintptr_t)x % 16) return set_error(DP_EALIGN, "gemm(bf16): epilogue operands must be 16-byte aligned");
+    KScope ks(a.a_mc ? KK_GEMM_TN : (a.b_mc ? KK_GEMM_NN : KK_GEMM_NT), 2.0 * a.M * a.N * a.K,
+              2.0 * ((double)a.M * a.K + (double)a.N * a.K + (double)a.M * a.N), s, a.M, a.N, a.K);
     return launch_bf16_layout<128, 128, 64, 2, 2>(a, s);
   }
   GemmF32Params p;
@@ -394,6 +410,7 @@ int launch_gemm(const GemmArgs& a, hipStream_t s) {
   p.M = a.M; p.N = a.N; p.K = a.K; p.lda = a.lda; p.ldb = a.ldb; p.a_mc = a.a_mc; p.b_mc = a.b_mc;
   p.epi = make_epi<float>(a);
   dim3 grid((a.N + 63) / 64, (a.M + 63) / 64, 1);
+  KScope ks(KK_GEMM_F32, 2.0 * a.M * a.N * a.K, 4.0 * ((double)a.M * a.K + (double)a.N * a.K + (double)a.M * a.N), s, a.M, a.N, a.K);
   hipLaunchKernelGGL(gemm_f32_kernel, grid, dim3(256), 0, s, p);
   if (hipGetLastError() != hipSuccess) return set_error(DP_EHIP, "gemm(f32) launch failed");
   return DP_OK;

@@ -82,18 +82,23 @@ struct DitBuf {
   void *xin, *m, *h1, *qkv, *a, *o, *x1, *h2, *f1, *f, *f2;
   float *mean1, *rstd1, *lse, *mean2, *rstd2;
 };
+// A residual-stream gradient lives twice: fp32 (f) for the running sum and in the storage
+// dtype (h) as a GEMM operand.  For fp32 storage both point at the same buffer.
+struct GradPair { float* f; void* h; };
 struct BwdScratch {
-  void *r0, *r1, *dh, *da, *dqkv, *dq2, *dkv2, *dg, *du, *dm_t, *sc_in;
+  GradPair r[2];
+  void *dh, *da, *dqkv, *dq2, *dkv2, *dg, *du, *dm_t;
   float *delta, *dm, *dcond_pre, *partial; size_t partial_bytes;
 };
 
 static void plan_unet_block(Plan& p, const dp_stage& s, UnetBuf& u, bool with_xin) {
   const size_t T = s.T, Tc = s.Tc, d = s.d.d_model, inner = s.d.ff_inner, es = s.es;
   const size_t stat = (size_t)s.d.batch * s.d.n_heads * s.d.tokens * sizeof(float);
-  u.xin = with_xin ? p.take(T * d * es) : nullptr;
-  u.h1 = p.take(T * d * es); u.qkv = p.take(T * 3 * d * es); u.a1 = p.take(T * d * es); u.x1 = p.take(T * d * es);
+  // xin, x1, x2: the residual stream, kept in fp32 inside the stage
+  u.xin = with_xin ? p.take(T * d * 4) : nullptr;
+  u.h1 = p.take(T * d * es); u.qkv = p.take(T * 3 * d * es); u.a1 = p.take(T * d * es); u.x1 = p.take(T * d * 4);
   u.h2 = p.take(T * d * es); u.q2 = p.take(T * d * es); u.kv2 = p.take(Tc * 2 * d * es); u.a2 = p.take(T * d * es);
-  u.x2 = p.take(T * d * es); u.h3 = p.take(T * d * es); u.u = p.take(T * 2 * inner * es); u.g = p.take(T * inner * es);
+  u.x2 = p.take(T * d * 4); u.h3 = p.take(T * d * es); u.u = p.take(T * 2 * inner * es); u.g = p.take(T * inner * es);
   u.mean1 = (float*)p.take(T * 4); u.rstd1 = (float*)p.take(T * 4); u.lse1 = (float*)p.take(stat);
   u.mean2 = (float*)p.take(T * 4); u.rstd2 = (float*)p.take(T * 4); u.lse2 = (float*)p.take(stat);
   u.mean3 = (float*)p.take(T * 4); u.rstd3 = (float*)p.take(T * 4);
@@ -101,10 +106,10 @@ static void plan_unet_block(Plan& p, const dp_stage& s, UnetBuf& u, bool with_xi
 static void plan_dit_block(Plan& p, const dp_stage& s, DitBuf& u, bool with_xin) {
   const size_t T = s.T, d = s.d.d_model, ff = s.d.ff_inner, es = s.es, B = s.d.batch;
   const size_t stat = (size_t)s.d.batch * s.d.n_heads * s.d.tokens * sizeof(float);
-  u.xin = with_xin ? p.take(T * d * es) : nullptr;
+  u.xin = with_xin ? p.take(T * d * 4) : nullptr;
   u.m = p.take(B * 6 * d * es);
   u.h1 = p.take(T * d * es); u.qkv = p.take(T * 3 * d * es); u.a = p.take(T * d * es); u.o = p.take(T * d * es);
-  u.x1 = p.take(T * d * es); u.h2 = p.take(T * d * es); u.f1 = p.take(T * ff * es); u.f = p.take(T * ff * es);
+  u.x1 = p.take(T * d * 4); u.h2 = p.take(T * d * es); u.f1 = p.take(T * ff * es); u.f = p.take(T * ff * es);
   u.f2 = p.take(T * d * es);
   u.mean1 = (float*)p.take(T * 4); u.rstd1 = (float*)p.take(T * 4); u.lse = (float*)p.take(stat);
   u.mean2 = (float*)p.take(T * 4); u.rstd2 = (float*)p.take(T * 4);
@@ -130,7 +135,11 @@ static size_t partial_need(const dp_stage& s) {
 static void plan_bwd_scratch(Plan& p, const dp_stage& s, BwdScratch& b) {
   const size_t T = s.T, Tc = s.Tc, d = s.d.d_model, ff = s.d.ff_inner, es = s.es, B = s.d.batch;
   const bool unet = s.d.kind == DP_BLOCK_UNET_XATTN_GEGLU;
-  b.r0 = p.take(T * d * es); b.r1 = p.take(T * d * es); b.dh = p.take(T * d * es); b.da = p.take(T * d * es);
+  for (int i = 0; i < 2; ++i) {
+    b.r[i].f = (float*)p.take(T * d * 4);
+    b.r[i].h = es == 4 ? (void*)b.r[i].f : p.take(T * d * es);
+  }
+  b.dh = p.take(T * d * es); b.da = p.take(T * d * es);
   b.dqkv = p.take(T * 3 * d * es);
   b.delta = (float*)p.take((size_t)s.d.batch * s.d.n_heads * s.d.tokens * sizeof(float));
   if (unet) {
@@ -149,7 +158,7 @@ static void plan_bwd_scratch(Plan& p, const dp_stage& s, BwdScratch& b) {
 
 struct StagePlan {
   std::vector<UnetBuf> ub; std::vector<DitBuf> db;
-  void *pp0 = nullptr, *pp1 = nullptr, *sc_in = nullptr;
+  void *pp0 = nullptr, *pp1 = nullptr, *pp2 = nullptr, *sc_in = nullptr;   // pp*: fp32 block inputs of a no-save forward
   BwdScratch bs{};
   size_t bytes = 0;
 };
@@ -162,7 +171,10 @@ static void make_plan(const dp_stage& s, void* base, bool save, StagePlan& sp) {
   if (unet) { sp.ub.resize(nb); for (int i = 0; i < nb; ++i) plan_unet_block(p, s, sp.ub[i], save); }
   else { sp.db.resize(nb); for (int i = 0; i < nb; ++i) plan_dit_block(p, s, sp.db[i], save); }
   if (save) plan_bwd_scratch(p, s, sp.bs);
-  else { sp.pp0 = p.take((size_t)s.T * s.d.d_model * s.es); sp.pp1 = p.take((size_t)s.T * s.d.d_model * s.es); }
+  else {
+    const size_t rb = (size_t)s.T * s.d.d_model * 4;
+    sp.pp0 = p.take(rb); sp.pp1 = p.take(rb); sp.pp2 = p.take(rb);
+  }
   sp.bytes = p.off;
 }
 
@@ -213,12 +225,13 @@ static int record(ProfileHooks* ph, int idx, hipStream_t st) {
 }
 
 // ============================================================ U-Net stage
-static int unet_block_fwd(const dp_stage& s, const void* const* P, const void* x, const void* ctx, void* y, UnetBuf& u,
-                          hipStream_t st) {
+// x: fp32 block input.  y: fp32 (next block's input) unless y_is_out (storage dtype, the stage output).
+static int unet_block_fwd(const dp_stage& s, const void* const* P, const float* x, const void* ctx, void* y, bool y_is_out,
+                          UnetBuf& u, hipStream_t st) {
   const int dt = s.d.dtype, T = s.T, Tc = s.Tc, d = s.d.d_model, inner = s.d.ff_inner, dc = s.d.ctx_dim;
   const size_t es = s.es;
   LnArgs ln; memset(&ln, 0, sizeof(ln));
-  ln.dtype = dt; ln.rows = T; ln.d = d; ln.eps = s.d.ln_eps;
+  ln.dtype = dt; ln.rows = T; ln.d = d; ln.eps = s.d.ln_eps; ln.x_f32 = 1;
   // self-attention
   ln.x = x; ln.y = u.h1; ln.gamma = P[U_LN1_G]; ln.beta = P[U_LN1_B]; ln.mean = u.mean1; ln.rstd = u.rstd1;
   DP_TRY(launch_ln_fwd(ln, st));
@@ -228,7 +241,7 @@ static int unet_block_fwd(const dp_stage& s, const void* const* P, const void* x
   a.o = u.a1; a.ldo = d; a.lse = u.lse1;
   DP_TRY(launch_attn_fwd(a, st));
   GemmArgs g = gemm_fwd(dt, u.a1, T, d, P[U_WO1], d, P[U_BO1], u.x1);
-  g.residual = x; g.ld_res = d;
+  g.residual = x; g.ld_res = d; g.residual_f32 = 1; g.out_fused_f32 = 1;
   DP_TRY(launch_gemm(g, st));
   // cross-attention
   ln.x = u.x1; ln.y = u.h2; ln.gamma = P[U_LN2_G]; ln.beta = P[U_LN2_B]; ln.mean = u.mean2; ln.rstd = u.rstd2;
@@ -240,7 +253,7 @@ static int unet_block_fwd(const dp_stage& s, const void* const* P, const void* x
   a.o = u.a2; a.ldo = d; a.lse = u.lse2;
   DP_TRY(launch_attn_fwd(a, st));
   g = gemm_fwd(dt, u.a2, T, d, P[U_WO2], d, P[U_BO2], u.x2);
-  g.residual = u.x1; g.ld_res = d;
+  g.residual = u.x1; g.ld_res = d; g.residual_f32 = 1; g.out_fused_f32 = 1;
   DP_TRY(launch_gemm(g, st));
   // GeGLU feed-forward
   ln.x = u.x2; ln.y = u.h3; ln.gamma = P[U_LN3_G]; ln.beta = P[U_LN3_B]; ln.mean = u.mean3; ln.rstd = u.rstd3;
@@ -248,35 +261,36 @@ static int unet_block_fwd(const dp_stage& s, const void* const* P, const void* x
   DP_TRY(launch_gemm(gemm_fwd(dt, u.h3, T, d, P[U_W1], 2 * inner, P[U_B1], u.u), st));
   DP_TRY(launch_geglu_fwd(dt, u.u, u.g, T, inner, st));
   g = gemm_fwd(dt, u.g, T, inner, P[U_W2], d, P[U_B2], y);
-  g.residual = u.x2; g.ld_res = d;
+  g.residual = u.x2; g.ld_res = d; g.residual_f32 = 1; g.out_fused_f32 = y_is_out ? 0 : 1;
   DP_TRY(launch_gemm(g, st));
   return DP_OK;
 }
 
-static int unet_block_bwd(const dp_stage& s, const void* const* P, void* const* G, int acc, const void* ctx, const void* dy,
-                          void* dx, UnetBuf& u, BwdScratch& b, hipStream_t st) {
+// dy: gradient of the block output (fp32 running sum + storage-dtype copy).  The block's dx goes to
+// `out` (fp32 + storage dtype) or, for the first block of the stage, to dx_final (storage dtype only).
+static int unet_block_bwd(const dp_stage& s, const void* const* P, void* const* G, int acc, const void* ctx, GradPair dy,
+                          GradPair dx2, GradPair dx1, GradPair out, void* dx_final, UnetBuf& u, BwdScratch& b, hipStream_t st) {
   const int dt = s.d.dtype, T = s.T, Tc = s.Tc, d = s.d.d_model, inner = s.d.ff_inner, dc = s.d.ctx_dim;
   const size_t es = s.es;
-  auto other = [&](const void* p) -> void* { return p == b.r0 ? b.r1 : b.r0; };
   auto gf = [&](int i) { return (float*)G[i]; };
+  auto set_dx = [&](LnBwdArgs& lb, GradPair t) { lb.dx32 = t.f; lb.dx = (es == 4) ? nullptr : t.h; };
   // ---- feed-forward
-  DP_TRY(launch_gemm(gemm_dx(dt, dy, T, d, P[U_W2], inner, b.dg), st));
-  DP_TRY(launch_gemm(gemm_dw(dt, dy, T, d, u.g, inner, gf(U_W2), acc, b), st));
-  DP_TRY(launch_colsum(dt, dy, d, T, d, gf(U_B2), acc, b.partial, b.partial_bytes, st));
+  DP_TRY(launch_gemm(gemm_dx(dt, dy.h, T, d, P[U_W2], inner, b.dg), st));
+  DP_TRY(launch_gemm(gemm_dw(dt, dy.h, T, d, u.g, inner, gf(U_W2), acc, b), st));
+  DP_TRY(launch_colsum(dt, dy.h, d, T, d, gf(U_B2), acc, b.partial, b.partial_bytes, st));
   DP_TRY(launch_geglu_bwd(dt, b.dg, u.u, b.du, T, inner, st));
   DP_TRY(launch_gemm(gemm_dx(dt, b.du, T, 2 * inner, P[U_W1], d, b.dh), st));
   DP_TRY(launch_gemm(gemm_dw(dt, b.du, T, 2 * inner, u.h3, d, gf(U_W1), acc, b), st));
   DP_TRY(launch_colsum(dt, b.du, 2 * inner, T, 2 * inner, gf(U_B1), acc, b.partial, b.partial_bytes, st));
-  void* dx2 = other(dy);
   LnBwdArgs lb; memset(&lb, 0, sizeof(lb));
   lb.dtype = dt; lb.rows = T; lb.d = d; lb.accumulate = acc; lb.partial = b.partial; lb.partial_bytes = b.partial_bytes;
-  lb.dy = b.dh; lb.x = u.x2; lb.mean = u.mean3; lb.rstd = u.rstd3; lb.gamma = P[U_LN3_G]; lb.dres = dy; lb.dx = dx2;
+  lb.dy = b.dh; lb.x = u.x2; lb.mean = u.mean3; lb.rstd = u.rstd3; lb.gamma = P[U_LN3_G]; lb.dres = dy.f; set_dx(lb, dx2);
   lb.dgamma = gf(U_LN3_G); lb.dbeta = gf(U_LN3_B);
   DP_TRY(launch_ln_bwd(lb, st));
   // ---- cross-attention
-  DP_TRY(launch_gemm(gemm_dx(dt, dx2, T, d, P[U_WO2], d, b.da), st));
-  DP_TRY(launch_gemm(gemm_dw(dt, dx2, T, d, u.a2, d, gf(U_WO2), acc, b), st));
-  DP_TRY(launch_colsum(dt, dx2, d, T, d, gf(U_BO2), acc, b.partial, b.partial_bytes, st));
+  DP_TRY(launch_gemm(gemm_dx(dt, dx2.h, T, d, P[U_WO2], d, b.da), st));
+  DP_TRY(launch_gemm(gemm_dw(dt, dx2.h, T, d, u.a2, d, gf(U_WO2), acc, b), st));
+  DP_TRY(launch_colsum(dt, dx2.h, d, T, d, gf(U_BO2), acc, b.partial, b.partial_bytes, st));
   AttnArgs a = attn_base(s);
   a.Nk = s.d.ctx_tokens; a.q = u.q2; a.ldq = d; a.k = u.kv2; a.v = at(u.kv2, d, es); a.ldk = a.ldv = 2 * d;
   a.o = u.a2; a.ldo = d; a.lse = u.lse2; a.dout = b.da; a.lddo = d; a.delta = b.delta;
@@ -285,14 +299,13 @@ static int unet_block_bwd(const dp_stage& s, const void* const* P, void* const* 
   DP_TRY(launch_gemm(gemm_dx(dt, b.dq2, T, d, P[U_WQ2], d, b.dh), st));
   DP_TRY(launch_gemm(gemm_dw(dt, b.dq2, T, d, u.h2, d, gf(U_WQ2), acc, b), st));
   DP_TRY(launch_gemm(gemm_dw(dt, b.dkv2, Tc, 2 * d, ctx, dc, gf(U_WKV2), acc, b), st));
-  void* dx1 = other(dx2);
-  lb.dy = b.dh; lb.x = u.x1; lb.mean = u.mean2; lb.rstd = u.rstd2; lb.gamma = P[U_LN2_G]; lb.dres = dx2; lb.dx = dx1;
+  lb.dy = b.dh; lb.x = u.x1; lb.mean = u.mean2; lb.rstd = u.rstd2; lb.gamma = P[U_LN2_G]; lb.dres = dx2.f; set_dx(lb, dx1);
   lb.dgamma = gf(U_LN2_G); lb.dbeta = gf(U_LN2_B);
   DP_TRY(launch_ln_bwd(lb, st));
   // ---- self-attention
-  DP_TRY(launch_gemm(gemm_dx(dt, dx1, T, d, P[U_WO1], d, b.da), st));
-  DP_TRY(launch_gemm(gemm_dw(dt, dx1, T, d, u.a1, d, gf(U_WO1), acc, b), st));
-  DP_TRY(launch_colsum(dt, dx1, d, T, d, gf(U_BO1), acc, b.partial, b.partial_bytes, st));
+  DP_TRY(launch_gemm(gemm_dx(dt, dx1.h, T, d, P[U_WO1], d, b.da), st));
+  DP_TRY(launch_gemm(gemm_dw(dt, dx1.h, T, d, u.a1, d, gf(U_WO1), acc, b), st));
+  DP_TRY(launch_colsum(dt, dx1.h, d, T, d, gf(U_BO1), acc, b.partial, b.partial_bytes, st));
   a = attn_base(s);
   a.Nk = s.d.tokens; a.q = u.qkv; a.k = at(u.qkv, d, es); a.v = at(u.qkv, 2 * d, es); a.ldq = a.ldk = a.ldv = 3 * d;
   a.o = u.a1; a.ldo = d; a.lse = u.lse1; a.dout = b.da; a.lddo = d; a.delta = b.delta;
@@ -300,20 +313,21 @@ static int unet_block_bwd(const dp_stage& s, const void* const* P, void* const* 
   DP_TRY(launch_attn_bwd(a, st));
   DP_TRY(launch_gemm(gemm_dx(dt, b.dqkv, T, 3 * d, P[U_WQKV], d, b.dh), st));
   DP_TRY(launch_gemm(gemm_dw(dt, b.dqkv, T, 3 * d, u.h1, d, gf(U_WQKV), acc, b), st));
-  lb.dy = b.dh; lb.x = u.xin; lb.mean = u.mean1; lb.rstd = u.rstd1; lb.gamma = P[U_LN1_G]; lb.dres = dx1; lb.dx = dx;
+  lb.dy = b.dh; lb.x = u.xin; lb.mean = u.mean1; lb.rstd = u.rstd1; lb.gamma = P[U_LN1_G]; lb.dres = dx1.f;
+  if (dx_final) { lb.dx = dx_final; lb.dx32 = nullptr; } else set_dx(lb, out);
   lb.dgamma = gf(U_LN1_G); lb.dbeta = gf(U_LN1_B);
   DP_TRY(launch_ln_bwd(lb, st));
   return DP_OK;
 }
 
 // ============================================================ DiT stage
-static int dit_block_fwd(const dp_stage& s, const void* const* P, const void* x, const void* sc_in, void* y, DitBuf& u,
-                         hipStream_t st) {
+static int dit_block_fwd(const dp_stage& s, const void* const* P, const float* x, const void* sc_in, void* y, bool y_is_out,
+                         DitBuf& u, hipStream_t st) {
   const int dt = s.d.dtype, T = s.T, d = s.d.d_model, ff = s.d.ff_inner, B = s.d.batch, N = s.d.tokens;
   const size_t es = s.es;
   DP_TRY(launch_gemm(gemm_fwd(dt, sc_in, B, d, P[D_ADA_W], 6 * d, P[D_ADA_B], u.m), st));
   LnArgs ln; memset(&ln, 0, sizeof(ln));
-  ln.dtype = dt; ln.rows = T; ln.d = d; ln.eps = s.d.ln_eps; ln.mod_ld = 6 * d; ln.rows_per_batch = N;
+  ln.dtype = dt; ln.rows = T; ln.d = d; ln.eps = s.d.ln_eps; ln.mod_ld = 6 * d; ln.rows_per_batch = N; ln.x_f32 = 1;
   ln.x = x; ln.y = u.h1; ln.shift = u.m; ln.scale = at(u.m, d, es); ln.mean = u.mean1; ln.rstd = u.rstd1;
   DP_TRY(launch_ln_fwd(ln, st));
   DP_TRY(launch_gemm(gemm_fwd(dt, u.h1, T, d, P[D_WQKV], 3 * d, P[D_BQKV], u.qkv), st));
@@ -322,7 +336,8 @@ static int dit_block_fwd(const dp_stage& s, const void* const* P, const void* x,
   a.o = u.a; a.ldo = d; a.lse = u.lse;
   DP_TRY(launch_attn_fwd(a, st));
   GemmArgs g = gemm_fwd(dt, u.a, T, d, P[D_WO], d, P[D_BO], u.x1);
-  g.pre_out = u.o; g.ld_pre = d; g.gate = at(u.m, 2 * d, es); g.gate_ld = 6 * d; g.rows_per_batch = N; g.residual = x; g.ld_res = d;
+  g.pre_out = u.o; g.ld_pre = d; g.gate = at(u.m, 2 * d, es); g.gate_ld = 6 * d; g.rows_per_batch = N;
+  g.residual = x; g.ld_res = d; g.residual_f32 = 1; g.out_fused_f32 = 1;
   DP_TRY(launch_gemm(g, st));
   ln.x = u.x1; ln.y = u.h2; ln.shift = at(u.m, 3 * d, es); ln.scale = at(u.m, 4 * d, es); ln.mean = u.mean2; ln.rstd = u.rstd2;
   DP_TRY(launch_ln_fwd(ln, st));
@@ -330,19 +345,21 @@ static int dit_block_fwd(const dp_stage& s, const void* const* P, const void* x,
   g.pre_out = u.f1; g.ld_pre = ff; g.act = s.d.gelu_tanh ? 2 : 1;
   DP_TRY(launch_gemm(g, st));
   g = gemm_fwd(dt, u.f, T, ff, P[D_FC2_W], d, P[D_FC2_B], y);
-  g.pre_out = u.f2; g.ld_pre = d; g.gate = at(u.m, 5 * d, es); g.gate_ld = 6 * d; g.rows_per_batch = N; g.residual = u.x1; g.ld_res = d;
+  g.pre_out = u.f2; g.ld_pre = d; g.gate = at(u.m, 5 * d, es); g.gate_ld = 6 * d; g.rows_per_batch = N;
+  g.residual = u.x1; g.ld_res = d; g.residual_f32 = 1; g.out_fused_f32 = y_is_out ? 0 : 1;
   DP_TRY(launch_gemm(g, st));
   return DP_OK;
 }
 
 static int dit_block_bwd(const dp_stage& s, const void* const* P, void* const* G, int acc, const void* cond, const void* sc_in,
-                         const void* dy, void* dx, float* d_cond, int dcond_acc, DitBuf& u, BwdScratch& b, hipStream_t st) {
+                         GradPair dy, GradPair dx1, GradPair out, void* dx_final, float* d_cond, int dcond_acc, DitBuf& u,
+                         BwdScratch& b, hipStream_t st) {
   const int dt = s.d.dtype, T = s.T, d = s.d.d_model, ff = s.d.ff_inner, B = s.d.batch, N = s.d.tokens;
   const size_t es = s.es;
-  auto other = [&](const void* p) -> void* { return p == b.r0 ? b.r1 : b.r0; };
   auto gf = [&](int i) { return (float*)G[i]; };
+  auto set_dx = [&](LnBwdArgs& lb, GradPair t) { lb.dx32 = t.f; lb.dx = (es == 4) ? nullptr : t.h; };
   // ---- MLP branch
-  DP_TRY(launch_gate_bwd(dt, dy, u.f2, at(u.m, 5 * d, es), 6 * d, b.dg, b.dm + 5 * d, 6 * d, B, N, d, st));
+  DP_TRY(launch_gate_bwd(dt, dy.f, u.f2, at(u.m, 5 * d, es), 6 * d, b.dg, b.dm + 5 * d, 6 * d, B, N, d, st));
   GemmArgs g = gemm_dx(dt, b.dg, T, d, P[D_FC2_W], ff, b.du);
   g.dact_pre = u.f1; g.ld_dact = ff; g.dact_kind = s.d.gelu_tanh ? 2 : 1;
   DP_TRY(launch_gemm(g, st));
@@ -351,15 +368,14 @@ static int dit_block_bwd(const dp_stage& s, const void* const* P, void* const* G
   DP_TRY(launch_gemm(gemm_dx(dt, b.du, T, ff, P[D_FC1_W], d, b.dh), st));
   DP_TRY(launch_gemm(gemm_dw(dt, b.du, T, ff, u.h2, d, gf(D_FC1_W), acc, b), st));
   DP_TRY(launch_colsum(dt, b.du, ff, T, ff, gf(D_FC1_B), acc, b.partial, b.partial_bytes, st));
-  void* dx1 = other(dy);
   LnBwdArgs lb; memset(&lb, 0, sizeof(lb));
   lb.dtype = dt; lb.rows = T; lb.d = d; lb.partial = b.partial; lb.partial_bytes = b.partial_bytes;
   lb.mod_ld = 6 * d; lb.rows_per_batch = N; lb.dmod_ld = 6 * d;
-  lb.dy = b.dh; lb.x = u.x1; lb.mean = u.mean2; lb.rstd = u.rstd2; lb.scale = at(u.m, 4 * d, es); lb.dres = dy; lb.dx = dx1;
+  lb.dy = b.dh; lb.x = u.x1; lb.mean = u.mean2; lb.rstd = u.rstd2; lb.scale = at(u.m, 4 * d, es); lb.dres = dy.f; set_dx(lb, dx1);
   lb.dscale = b.dm + 4 * d; lb.dshift = b.dm + 3 * d;
   DP_TRY(launch_ln_bwd(lb, st));
   // ---- attention branch
-  DP_TRY(launch_gate_bwd(dt, dx1, u.o, at(u.m, 2 * d, es), 6 * d, b.dg, b.dm + 2 * d, 6 * d, B, N, d, st));
+  DP_TRY(launch_gate_bwd(dt, dx1.f, u.o, at(u.m, 2 * d, es), 6 * d, b.dg, b.dm + 2 * d, 6 * d, B, N, d, st));
   DP_TRY(launch_gemm(gemm_dx(dt, b.dg, T, d, P[D_WO], d, b.da), st));
   DP_TRY(launch_gemm(gemm_dw(dt, b.dg, T, d, u.a, d, gf(D_WO), acc, b), st));
   DP_TRY(launch_colsum(dt, b.dg, d, T, d, gf(D_BO), acc, b.partial, b.partial_bytes, st));
@@ -371,7 +387,8 @@ static int dit_block_bwd(const dp_stage& s, const void* const* P, void* const* G
   DP_TRY(launch_gemm(gemm_dx(dt, b.dqkv, T, 3 * d, P[D_WQKV], d, b.dh), st));
   DP_TRY(launch_gemm(gemm_dw(dt, b.dqkv, T, 3 * d, u.h1, d, gf(D_WQKV), acc, b), st));
   DP_TRY(launch_colsum(dt, b.dqkv, 3 * d, T, 3 * d, gf(D_BQKV), acc, b.partial, b.partial_bytes, st));
-  lb.dy = b.dh; lb.x = u.xin; lb.mean = u.mean1; lb.rstd = u.rstd1; lb.scale = at(u.m, d, es); lb.dres = dx1; lb.dx = dx;
+  lb.dy = b.dh; lb.x = u.xin; lb.mean = u.mean1; lb.rstd = u.rstd1; lb.scale = at(u.m, d, es); lb.dres = dx1.f;
+  if (dx_final) { lb.dx = dx_final; lb.dx32 = nullptr; } else set_dx(lb, out);
   lb.dscale = b.dm + d; lb.dshift = b.dm;
   DP_TRY(launch_ln_bwd(lb, st));
   // ---- conditioning path: m = SiLU(cond) W_ada^T + b_ada
@@ -412,28 +429,23 @@ static int run_stage_fwd(dp_stage* s, const void* const* params, const void* x, 
   make_plan(*s, ws, save != 0, sp);
   const bool unet = s->d.kind == DP_BLOCK_UNET_XATTN_GEGLU;
   const int nb = s->d.n_blocks;
-  const size_t act_bytes = (size_t)s->T * s->d.d_model * s->es;
+  const size_t act = (size_t)s->T * s->d.d_model;
   if (!unet) DP_TRY(launch_silu(s->d.dtype, cc, sp.sc_in, (size_t)s->d.batch * s->d.d_model, st));
-  const void* cur = x;
+  // the residual stream runs in fp32 inside the stage: widen the stage input once
+  float* cur = (float*)(save ? (unet ? sp.ub[0].xin : sp.db[0].xin) : sp.pp2);
+  DP_TRY(launch_cast_to_f32(s->d.dtype, x, cur, act, st));
   for (int b = 0; b < nb; ++b) {
     DP_TRY(record(ph, b, st));
     const void* const* P = params + (size_t)b * s->per_block;
+    const bool last = b == nb - 1;
     void* out;
-    if (save) {
-      void* xin = unet ? sp.ub[b].xin : sp.db[b].xin;
-      if (b == 0) {
-        if (hipMemcpyAsync(xin, x, act_bytes, hipMemcpyDeviceToDevice, st) != hipSuccess) return set_error(DP_EHIP, "hipMemcpyAsync failed");
-        cur = xin;
-      }
-      out = (b == nb - 1) ? y : (unet ? sp.ub[b + 1].xin : sp.db[b + 1].xin);
-      if (unet) DP_TRY(unet_block_fwd(*s, P, cur, cc, out, sp.ub[b], st));
-      else DP_TRY(dit_block_fwd(*s, P, cur, sp.sc_in, out, sp.db[b], st));
-    } else {
-      out = (b == nb - 1) ? y : ((b & 1) ? sp.pp1 : sp.pp0);
-      if (unet) DP_TRY(unet_block_fwd(*s, P, cur, cc, out, sp.ub[0], st));
-      else DP_TRY(dit_block_fwd(*s, P, cur, sp.sc_in, out, sp.db[0], st));
-    }
-    cur = out;
+    if (last) out = y;
+    else if (save) out = unet ? sp.ub[b + 1].xin : sp.db[b + 1].xin;
+    else out = (b & 1) ? sp.pp1 : sp.pp0;
+    const int slot = save ? b : 0;
+    if (unet) DP_TRY(unet_block_fwd(*s, P, cur, cc, out, last, sp.ub[slot], st));
+    else DP_TRY(dit_block_fwd(*s, P, cur, sp.sc_in, out, last, sp.db[slot], st));
+    cur = (float*)out;
   }
   DP_TRY(record(ph, nb, st));
   return DP_OK;
@@ -445,21 +457,26 @@ static int run_stage_bwd(dp_stage* s, const void* const* params, const void* dy,
   make_plan(*s, ws, true, sp);
   const bool unet = s->d.kind == DP_BLOCK_UNET_XATTN_GEGLU;
   const int nb = s->d.n_blocks;
-  const void* cur = dy;
+  BwdScratch& bs = sp.bs;
+  // dy as a gradient pair: fp32 copy in pair 1's fp32 buffer, the caller's tensor as the GEMM operand
+  DP_TRY(launch_cast_to_f32(s->d.dtype, dy, bs.r[1].f, (size_t)s->T * s->d.d_model, st));
+  GradPair cur{bs.r[1].f, const_cast<void*>(dy)};
+  int ci = 1;   // index of the pair whose fp32 buffer holds cur
   for (int b = nb - 1; b >= 0; --b) {
     DP_TRY(record(ph, nb - 1 - b, st));
     const void* const* P = params + (size_t)b * s->per_block;
     void* const* G = dparams + (size_t)b * s->per_block;
-    // The block keeps its last residual-stream gradient (dx1) in one of the two scratch
-    // buffers; its dx goes to the other one.  U-Net: dx2 = other(cur), dx1 = other(dx2);
-    // DiT: dx1 = other(cur).
-    auto other = [&](const void* p) -> void* { return p == sp.bs.r0 ? sp.bs.r1 : sp.bs.r0; };
-    void* out;
-    if (b == 0) out = dx;
-    else out = unet ? other(other(other(cur))) : other(other(cur));
-    if (unet) DP_TRY(unet_block_bwd(*s, P, G, acc, cc, cur, out, sp.ub[b], sp.bs, st));
-    else DP_TRY(dit_block_bwd(*s, P, G, acc, cc, sp.sc_in, cur, out, (float*)d_cond, b != nb - 1, sp.db[b], sp.bs, st));
-    cur = out;
+    void* dx_final = b == 0 ? dx : nullptr;
+    if (unet) {
+      // dx2 -> other pair, dx1 -> cur's pair (cur is dead by then), block dx -> other pair again
+      DP_TRY(unet_block_bwd(*s, P, G, acc, cc, cur, bs.r[ci ^ 1], bs.r[ci], bs.r[ci ^ 1], dx_final, sp.ub[b], bs, st));
+      cur = bs.r[ci ^ 1]; ci ^= 1;
+    } else {
+      // dx1 -> other pair, block dx -> cur's pair
+      DP_TRY(dit_block_bwd(*s, P, G, acc, cc, sp.sc_in, cur, bs.r[ci ^ 1], bs.r[ci], dx_final, (float*)d_cond, b != nb - 1,
+                           sp.db[b], bs, st));
+      cur = bs.r[ci];
+    }
   }
   DP_TRY(record(ph, nb, st));
   return DP_OK;
@@ -468,29 +485,21 @@ static int run_stage_bwd(dp_stage* s, const void* const* params, const void* dy,
 // ============================================================ encoder
 enum { E_LN1_G, E_LN1_B, E_WQKV, E_BQKV, E_WO, E_BO, E_LN2_G, E_LN2_B, E_FC1_W, E_FC1_B, E_FC2_W, E_FC2_B, E_PER_LAYER };
 
-struct EncBuf { void *h, *qkv, *a, *f; size_t bytes; };
+struct EncBuf { void *h, *qkv, *a, *f; float* res; size_t bytes; };
 static void plan_encoder(const dp_encoder& e, void* base, int samples, EncBuf& b) {
   Plan p(base);
   const size_t R = (size_t)samples * e.d.seq, d = e.d.d_model, es = e.es;
   b.h = p.take(R * d * es); b.qkv = p.take(R * 3 * d * es); b.a = p.take(R * d * es); b.f = p.take(R * e.d.ff_inner * es);
+  b.res = (float*)p.take(R * d * 4);
   b.bytes = p.off;
 }
 
-static int encoder_layer(const dp_encoder& e, const void* const* params, int layer, const int32_t* ids, void* hidden,
-                         int sample_offset, int n, EncBuf& w, hipStream_t st) {
+// One transformer layer on the fp32 residual stream `x` [R, d] (updated in place).
+static int encoder_block(const dp_encoder& e, const void* const* P, float* x, int n, EncBuf& w, hipStream_t st) {
   const int dt = e.d.dtype, d = e.d.d_model, seq = e.d.seq, ff = e.d.ff_inner, R = n * seq;
   const size_t es = e.es;
-  void* x = at(hidden, (size_t)sample_offset * seq * d, es);
-  if (layer == 0)
-    return launch_embed(dt, ids + (size_t)sample_offset * seq, params[0], params[1], x, R, seq, d, e.d.vocab, st);
   LnArgs ln; memset(&ln, 0, sizeof(ln));
-  ln.dtype = dt; ln.rows = R; ln.d = d; ln.eps = e.d.ln_eps;
-  if (layer == e.d.n_layers + 1) {
-    const void* const* P = params + 2 + (size_t)e.d.n_layers * E_PER_LAYER;
-    ln.x = x; ln.y = x; ln.gamma = P[0]; ln.beta = P[1];
-    return launch_ln_fwd(ln, st);
-  }
-  const void* const* P = params + 2 + (size_t)(layer - 1) * E_PER_LAYER;
+  ln.dtype = dt; ln.rows = R; ln.d = d; ln.eps = e.d.ln_eps; ln.x_f32 = 1;
   ln.x = x; ln.y = w.h; ln.gamma = P[E_LN1_G]; ln.beta = P[E_LN1_B];
   DP_TRY(launch_ln_fwd(ln, st));
   DP_TRY(launch_gemm(gemm_fwd(dt, w.h, R, d, P[E_WQKV], 3 * d, P[E_BQKV], w.qkv), st));
@@ -500,7 +509,7 @@ static int encoder_layer(const dp_encoder& e, const void* const* params, int lay
   a.q = w.qkv; a.k = at(w.qkv, d, es); a.v = at(w.qkv, 2 * d, es); a.ldq = a.ldk = a.ldv = 3 * d; a.o = w.a; a.ldo = d;
   DP_TRY(launch_attn_fwd(a, st));
   GemmArgs g = gemm_fwd(dt, w.a, R, d, P[E_WO], d, P[E_BO], x);
-  g.residual = x; g.ld_res = d;
+  g.residual = x; g.ld_res = d; g.residual_f32 = 1; g.out_fused_f32 = 1;
   DP_TRY(launch_gemm(g, st));
   ln.x = x; ln.y = w.h; ln.gamma = P[E_LN2_G]; ln.beta = P[E_LN2_B];
   DP_TRY(launch_ln_fwd(ln, st));
@@ -508,8 +517,49 @@ static int encoder_layer(const dp_encoder& e, const void* const* params, int lay
   g.act = 3;
   DP_TRY(launch_gemm(g, st));
   g = gemm_fwd(dt, w.f, R, ff, P[E_FC2_W], d, P[E_FC2_B], x);
-  g.residual = x; g.ld_res = d;
+  g.residual = x; g.ld_res = d; g.residual_f32 = 1; g.out_fused_f32 = 1;
   DP_TRY(launch_gemm(g, st));
+  return DP_OK;
+}
+
+// Layers [lb, le) on samples [off, off + n).  `hidden` holds the state in the storage dtype between
+// calls; inside a call the residual stream of consecutive transformer layers stays in fp32.
+// When ev is given, ev[l - lb] is recorded before layer l and ev[le - lb] at the end.
+static int encoder_run(const dp_encoder& e, const void* const* params, const int32_t* ids, void* hidden, int lb, int le, int off,
+                       int n, EncBuf& w, hipStream_t st, std::vector<hipEvent_t>* ev) {
+  const int dt = e.d.dtype, d = e.d.d_model, seq = e.d.seq, R = n * seq, nl = e.d.n_layers;
+  void* x = at(hidden, (size_t)off * seq * d, e.es);
+  auto mark = [&](int l) -> int {
+    if (ev && hipEventRecord((*ev)[l - lb], st) != hipSuccess) return set_error(DP_EHIP, "hipEventRecord failed");
+    return DP_OK;
+  };
+  int l = lb;
+  if (l == 0) {
+    DP_TRY(mark(0));
+    DP_TRY(launch_embed(dt, ids + (size_t)off * seq, params[0], params[1], x, R, seq, d, e.d.vocab, st));
+    ++l;
+  }
+  const int tl_end = std::min(le, nl + 1);
+  const bool blocks = l < tl_end;
+  const bool final_ln = le == nl + 2;
+  if (blocks) {
+    DP_TRY(mark(l));
+    DP_TRY(launch_cast_to_f32(dt, x, w.res, (size_t)R * d, st));
+    for (; l < tl_end; ++l) {
+      if (l != (lb == 0 ? 1 : lb)) DP_TRY(mark(l));
+      DP_TRY(encoder_block(e, params + 2 + (size_t)(l - 1) * E_PER_LAYER, w.res, n, w, st));
+    }
+    if (!final_ln) DP_TRY(launch_cast_from_f32(dt, w.res, x, (size_t)R * d, st));
+  }
+  if (final_ln) {
+    DP_TRY(mark(nl + 1));
+    const void* const* P = params + 2 + (size_t)nl * E_PER_LAYER;
+    LnArgs ln; memset(&ln, 0, sizeof(ln));
+    ln.dtype = dt; ln.rows = R; ln.d = d; ln.eps = e.d.ln_eps;
+    ln.x = blocks ? (const void*)w.res : (const void*)x; ln.x_f32 = blocks ? 1 : 0; ln.y = x; ln.gamma = P[0]; ln.beta = P[1];
+    DP_TRY(launch_ln_fwd(ln, st));
+  }
+  if (ev && hipEventRecord((*ev)[le - lb], st) != hipSuccess) return set_error(DP_EHIP, "hipEventRecord failed");
   return DP_OK;
 }
 
@@ -677,9 +727,7 @@ int encoder_fwd_partial(dp_encoder* enc, const void* const* params, const int32_
   DP_TRY(check_encoder_call(enc, params, ids, hidden, global_batch, layer_begin, layer_end, sample_offset, num_samples, workspace, workspace_bytes));
   EncBuf w;
   plan_encoder(*enc, workspace, num_samples, w);
-  for (int l = layer_begin; l < layer_end; ++l)
-    DP_TRY(encoder_layer(*enc, params, l, ids, hidden, sample_offset, num_samples, w, (hipStream_t)hip_stream));
-  return DP_OK;
+  return encoder_run(*enc, params, ids, hidden, layer_begin, layer_end, sample_offset, num_samples, w, (hipStream_t)hip_stream, nullptr);
 }
 
 int dp_stage_profile(dp_stage* st, const void* const* params, const void* x, const void* ctx_or_cond, void* y, const void* dy,
@@ -750,11 +798,7 @@ int dp_encoder_profile(dp_encoder* enc, const void* const* params, const int32_t
     plan_encoder(*enc, workspace, n, w);
     std::vector<std::vector<float>> t(nl);
     for (int r = 0; r < reps && rc == DP_OK; ++r) {
-      for (int l = 0; l < nl && rc == DP_OK; ++l) {
-        if (hipEventRecord(ev[l], s) != hipSuccess) rc = set_error(DP_EHIP, "hipEventRecord failed");
-        if (rc == DP_OK) rc = encoder_layer(*enc, params, l, ids, hidden, 0, n, w, s);
-      }
-      if (rc == DP_OK && hipEventRecord(ev[nl], s) != hipSuccess) rc = set_error(DP_EHIP, "hipEventRecord failed");
+      rc = encoder_run(*enc, params, ids, hidden, 0, nl, 0, n, w, s, &ev);
       if (rc == DP_OK && hipStreamSynchronize(s) != hipSuccess) rc = set_error(DP_EHIP, "hipStreamSynchronize failed");
       for (int l = 0; l < nl && rc == DP_OK; ++l) {
         float ms = 0.f;

@@ -138,7 +138,11 @@ def test_encoder_partial_batches_match_oracle_and_each_other(cfg):
     for off, n in ((0, 2), (2, gb - 2)):
         de.enc.fwd_partial(de.params, de.ids, de.hidden, gb, 2, nl, off, n, de.ws)
     torch.cuda.synchronize()
-    assert np.array_equal(de.output(), outs[gb])
+    # the state between calls is held in the storage dtype (one extra rounding at the split)
+    split = de.output()
+    e_split, e_ref = rel_err(split, outs[gb]), rel_err(split, ref)
+    assert e_split <= (1e-2 if cfg.dtype == "bf16" else 1e-6), e_split
+    assert e_ref <= TOL[cfg.dtype], e_ref
 
 
 def test_calls_interleave_without_interference():
