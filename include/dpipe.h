@@ -144,6 +144,31 @@ int dp_encoder_profile(dp_encoder* enc, const void* const* params, const int32_t
                        int global_batch, const int* batches, int n_batches, int reps, void* workspace,
                        size_t workspace_bytes, dp_layer_cost* rows, int max_rows, int* n_rows, void* hip_stream);
 
+/* Operator-level entry points: the same kernels the stage calls, exposed one by one for unit
+ * tests and per-kernel measurement (the cost profile of Sec. 4 is per layer; these go one
+ * level below it).  All pointers [device]; dtype as in dp_dtype.
+ *
+ * dp_op_gemm: C[M,N] = A * B with fp32 accumulation.  a_kmajor = 0: A is [M,K] row-major,
+ * 1: A is stored [K,M].  b_kmajor = 0: B is stored [N,K] (a weight applied as x W^T), 1: B is
+ * stored [K,N].  out_is_f32 = 0: C in the storage dtype (+ optional bias [N]); 1: C fp32, dense,
+ * overwritten or accumulated into, `workspace` (fp32 scratch of dp_op_gemm_workspace_bytes) may
+ * be used for a fixed-order split-K reduction.  tile_cfg = 0 picks the tile shape from (M,N,K);
+ * 1..4 force one (measurement only). */
+size_t dp_op_gemm_workspace_bytes(int M, int N, int K);
+int dp_op_gemm(int dtype, const void* A, int lda, int a_kmajor, const void* B, int ldb, int b_kmajor, int M, int N, int K,
+               const void* bias, void* C, int ldc, int out_is_f32, int accumulate, void* workspace, size_t workspace_bytes,
+               int tile_cfg, void* hip_stream);
+
+/* dp_op_attention_fwd / _bwd: per (batch, head) O = softmax(Q K^T * scale [causal]) V.
+ * Element (b, n, h, t) of a tensor X is X[(b * rows + n) * ldX + h * d_head + t], so Q, K, V may
+ * be column blocks of one fused projection output.  lse: fp32 [B, H, Nq] (written by fwd, read
+ * by bwd).  delta: fp32 [B, H, Nq] scratch.  The backward does not support the causal mask. */
+int dp_op_attention_fwd(int dtype, int B, int H, int Nq, int Nk, int d_head, int causal, float scale, const void* q, int ldq,
+                        const void* k, int ldk, const void* v, int ldv, void* o, int ldo, float* lse, void* hip_stream);
+int dp_op_attention_bwd(int dtype, int B, int H, int Nq, int Nk, int d_head, float scale, const void* q, int ldq, const void* k,
+                        int ldk, const void* v, int ldv, const void* o, int ldo, const float* lse, const void* d_o, int lddo,
+                        float* delta, void* dq, int lddq, void* dk, int lddk, void* dv, int lddv, void* hip_stream);
+
 /* Measurement aid: per-launch kernel timing.  Between dp_ktime_begin and dp_ktime_end every
  * kernel class the library launches is bracketed by hipEvents on the caller's stream; each
  * record carries the kernel kind, the algorithmic FLOPs and bytes of that launch (the

@@ -51,7 +51,8 @@ KERNEL_KINDS = {0: "gemm_nt", 1: "gemm_nn", 2: "gemm_tn", 3: "attn_fwd", 4: "att
 EXPORTS = ["dp_stage_create", "dp_stage_destroy", "dp_stage_param_count", "dp_stage_param_shape", "dp_stage_workspace_bytes",
            "stage_fwd", "stage_bwd", "dp_encoder_create", "dp_encoder_destroy", "dp_encoder_param_count",
            "dp_encoder_param_shape", "dp_encoder_workspace_bytes", "encoder_fwd_partial", "dp_stage_profile",
-           "dp_encoder_profile", "dp_ktime_begin", "dp_ktime_end", "dp_last_error"]
+           "dp_encoder_profile", "dp_ktime_begin", "dp_ktime_end", "dp_last_error", "dp_op_gemm", "dp_op_gemm_workspace_bytes",
+           "dp_op_attention_fwd", "dp_op_attention_bwd"]
 
 
 def library_path() -> str:
@@ -85,6 +86,11 @@ def load_library():
     lib.encoder_fwd_partial.argtypes = [vp, pp, vp, vp, i, i, i, i, i, vp, sz, vp]
     lib.dp_stage_profile.argtypes = [vp, pp, vp, vp, vp, vp, vp, vp, pp, vp, sz, i, C.POINTER(LayerCost), i, C.POINTER(i), vp]
     lib.dp_encoder_profile.argtypes = [vp, pp, vp, vp, i, C.POINTER(i), i, i, vp, sz, C.POINTER(LayerCost), i, C.POINTER(i), vp]
+    f = C.c_float
+    lib.dp_op_gemm_workspace_bytes.argtypes = [i, i, i]; lib.dp_op_gemm_workspace_bytes.restype = sz
+    lib.dp_op_gemm.argtypes = [i, vp, i, i, vp, i, i, i, i, i, vp, vp, i, i, i, vp, sz, i, vp]
+    lib.dp_op_attention_fwd.argtypes = [i, i, i, i, i, i, i, f, vp, i, vp, i, vp, i, vp, i, vp, vp]
+    lib.dp_op_attention_bwd.argtypes = [i, i, i, i, i, i, f, vp, i, vp, i, vp, i, vp, i, vp, vp, i, vp, vp, i, vp, i, vp, i, vp]
     lib.dp_ktime_begin.argtypes = [i]
     lib.dp_ktime_end.argtypes = [C.POINTER(KernelTime), i, C.POINTER(i)]
     _LIB = lib
@@ -227,3 +233,26 @@ def ktime_end(max_records: int = 65536):
     _check(load_library().dp_ktime_end(rows, max_records, C.byref(n)))
     return [{"kind": KERNEL_KINDS.get(rows[j].kind, str(rows[j].kind)), "m": rows[j].m, "n": rows[j].n, "k": rows[j].k,
              "ms": rows[j].ms, "flops": rows[j].flops, "bytes": rows[j].bytes} for j in range(n.value)]
+
+
+def op_gemm(dtype, A, lda, a_kmajor, B, ldb, b_kmajor, M, N, K, bias, Cout, ldc, out_is_f32=False, accumulate=False,
+            workspace=None, tile_cfg=0, stream=None):
+    _check(load_library().dp_op_gemm(dtype, _ptr(A), lda, int(a_kmajor), _ptr(B), ldb, int(b_kmajor), M, N, K, _ptr(bias),
+                                     _ptr(Cout), ldc, int(out_is_f32), int(accumulate), _ptr(workspace), _nbytes(workspace),
+                                     tile_cfg, _stream(stream)))
+
+
+def op_gemm_workspace_bytes(M, N, K):
+    return load_library().dp_op_gemm_workspace_bytes(M, N, K)
+
+
+def op_attention_fwd(dtype, B, H, Nq, Nk, d_head, causal, scale, q, ldq, k, ldk, v, ldv, o, ldo, lse, stream=None):
+    _check(load_library().dp_op_attention_fwd(dtype, B, H, Nq, Nk, d_head, int(causal), scale, _ptr(q), ldq, _ptr(k), ldk,
+                                              _ptr(v), ldv, _ptr(o), ldo, _ptr(lse), _stream(stream)))
+
+
+def op_attention_bwd(dtype, B, H, Nq, Nk, d_head, scale, q, ldq, k, ldk, v, ldv, o, ldo, lse, d_o, lddo, delta, dq, lddq, dk,
+                     lddk, dv, lddv, stream=None):
+    _check(load_library().dp_op_attention_bwd(dtype, B, H, Nq, Nk, d_head, scale, _ptr(q), ldq, _ptr(k), ldk, _ptr(v), ldv,
+                                              _ptr(o), ldo, _ptr(lse), _ptr(d_o), lddo, _ptr(delta), _ptr(dq), lddq,
+                                              _ptr(dk), lddk, _ptr(dv), lddv, _stream(stream)))

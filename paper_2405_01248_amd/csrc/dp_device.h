@@ -59,6 +59,24 @@ __device__ __forceinline__ bf16x8 frag_from_mc_accorder(const bf16* tile, int ld
   return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
 }
 
+// Asynchronous global -> LDS copy: every lane fetches 16 bytes from its own global address and the
+// wave's 64 x 16 bytes land contiguously at lds_base (wave-uniform).  Completion is tracked by vmcnt.
+__device__ __forceinline__ void async_copy_16B(const void* gptr, void* lds_base) {
+  __builtin_amdgcn_global_load_lds(gptr, (DP_LDS void*)lds_base, 16, 0, 0);
+}
+// Wait until at most N of this wave's vector-memory operations are outstanding (lgkmcnt / expcnt untouched).
+template <int N> __device__ __forceinline__ void wait_vmcnt() {
+  __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
+}
+// Workgroup barrier without the memory fence of __syncthreads() (which would also wait for every
+// outstanding asynchronous copy); the empty asm statements keep the compiler from moving memory
+// accesses across it.
+__device__ __forceinline__ void barrier_nofence() {
+  asm volatile("" ::: "memory");
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
+}
+
 __device__ __forceinline__ bf16x8 zero8() {
   u32x4 z = {0, 0, 0, 0};
   return __builtin_bit_cast(bf16x8, z);
@@ -68,6 +86,15 @@ __device__ __forceinline__ bf16x8 zero8() {
 __device__ __forceinline__ bf16x8 ld8(const bf16* p, bool ok) {
   if (ok) return *reinterpret_cast<const bf16x8*>(p);
   return zero8();
+}
+
+// Branch-free guarded load: p must be a valid address in any case (the caller clamps it);
+// the value is replaced by zeros when !ok.
+__device__ __forceinline__ bf16x8 ld8_sel(const bf16* p, bool ok) {
+  u32x4 v = *reinterpret_cast<const u32x4*>(p);
+  const u32x4 z = {0, 0, 0, 0};
+  v = ok ? v : z;
+  return __builtin_bit_cast(bf16x8, v);
 }
 
 __device__ __forceinline__ float wave_sum(float v) {

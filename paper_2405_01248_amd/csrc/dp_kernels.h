@@ -39,6 +39,7 @@ struct GemmArgs {
   int residual_f32;          // residual is fp32 (the residual stream) although dtype is bf16
   int out_fused_f32;         // `out` receives the fused-epilogue result as fp32 instead of the storage dtype
   float* splitk_ws; size_t splitk_ws_bytes;
+  int force_cfg;             // 0 = choose by shape; 1 + index forces a tile configuration (measurement only)
 };
 int launch_gemm(const GemmArgs& a, hipStream_t s);
 size_t gemm_splitk_ws_bytes(int M, int N, int K);   // upper bound for out_f32 GEMMs

@@ -218,26 +218,26 @@ __global__ void __launch_bounds__(256) ln_bwd_kernel(int d, int rows_per_batch, 
 }
 
 // out_k[b * ld + col] = (acc ? old : 0) + sum_chunks partial[b][chunk][k][col], k = 0 (gain grad), 1 (shift grad).
-// grid = (ceil(d / 64), n_batches); 64 columns x 4 chunk groups per workgroup, fixed summation order.
-__global__ void __launch_bounds__(256) ln_bwd_reduce_kernel(const float* __restrict__ partial, int nchunk, int d, float* out0,
-                                                            float* out1, int ld, int accumulate) {
-  __shared__ float red[2][4][64];
-  const int lc = threadIdx.x & 63, grp = threadIdx.x >> 6;
-  const int col = blockIdx.x * 64 + lc, b = blockIdx.y;
-  float s0 = 0.f, s1 = 0.f;
-  if (col < d) {
-    const float* p = partial + (size_t)b * nchunk * 2 * d;
-    for (int c = grp; c < nchunk; c += 4) { s0 += p[(size_t)c * 2 * d + col]; s1 += p[(size_t)c * 2 * d + d + col]; }
+// grid = (ceil(2d / 32), n_batches); 32 columns x 32 chunk groups per workgroup; every thread sums its
+// chunks in ascending order and the 32 group sums are added in ascending order (fixed order).
+__global__ void __launch_bounds__(1024) ln_bwd_reduce_kernel(const float* __restrict__ partial, int nchunk, int d, float* out0,
+                                                             float* out1, int ld, int accumulate) {
+  __shared__ float red[32][33];
+  const int lc = threadIdx.x & 31, grp = threadIdx.x >> 5;
+  const int col = blockIdx.x * 32 + lc, b = blockIdx.y;     // col indexes the [2][d] row of a chunk
+  float s = 0.f;
+  if (col < 2 * d) {
+    const float* p = partial + (size_t)b * nchunk * 2 * d + col;
+    for (int c = grp; c < nchunk; c += 32) s += p[(size_t)c * 2 * d];
   }
-  red[0][grp][lc] = s0; red[1][grp][lc] = s1;
+  red[grp][lc] = s;
   __syncthreads();
-  if (grp == 0 && col < d) {
-    s0 = ((red[0][0][lc] + red[0][1][lc]) + red[0][2][lc]) + red[0][3][lc];
-    s1 = ((red[1][0][lc] + red[1][1][lc]) + red[1][2][lc]) + red[1][3][lc];
-    float* o0 = out0 + (size_t)b * ld + col;
-    float* o1 = out1 + (size_t)b * ld + col;
-    *o0 = accumulate ? *o0 + s0 : s0;
-    *o1 = accumulate ? *o1 + s1 : s1;
+  if (grp == 0 && col < 2 * d) {
+    float t = 0.f;
+#pragma unroll
+    for (int g = 0; g < 32; ++g) t += red[g][lc];
+    float* o = (col < d ? out0 + col : out1 + (col - d)) + (size_t)b * ld;
+    *o = accumulate ? *o + t : t;
   }
 }
 
@@ -273,9 +273,9 @@ int launch_ln_bwd(const LnBwdArgs& a, hipStream_t s) {
   int e = a.dtype == BF16 ? ln_bwd_t<bf16>(a, rpb, nb, nchunk, partial, s) : ln_bwd_t<float>(a, rpb, nb, nchunk, partial, s);
   if (e || !want_cols) return e;
   if (modulated)
-    hipLaunchKernelGGL(ln_bwd_reduce_kernel, dim3((a.d + 63) / 64, nb), dim3(256), 0, s, partial, nchunk, a.d, a.dscale, a.dshift, a.dmod_ld, 0);
+    hipLaunchKernelGGL(ln_bwd_reduce_kernel, dim3((2 * a.d + 31) / 32, nb), dim3(1024), 0, s, partial, nchunk, a.d, a.dscale, a.dshift, a.dmod_ld, 0);
   else
-    hipLaunchKernelGGL(ln_bwd_reduce_kernel, dim3((a.d + 63) / 64, 1), dim3(256), 0, s, partial, nchunk, a.d, a.dgamma, a.dbeta, a.d, a.accumulate);
+    hipLaunchKernelGGL(ln_bwd_reduce_kernel, dim3((2 * a.d + 31) / 32, 1), dim3(1024), 0, s, partial, nchunk, a.d, a.dgamma, a.dbeta, a.d, a.accumulate);
   return hipGetLastError() == hipSuccess ? DP_OK : set_error(DP_EHIP, "ln_bwd_reduce launch failed");
 }
 

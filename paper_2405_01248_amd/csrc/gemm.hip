@@ -5,12 +5,15 @@
 // contiguous in memory is staged [rows][BK] and read with 16-byte LDS loads; an operand
 // whose contraction index is the slow one (weights in dx, both operands in dW) is staged
 // [BK][cols] exactly as it sits in HBM and read with the transposing LDS load, so no
-// transposed copy of a weight or activation is ever materialised.
+// transposed copy of a weight or activation is ever materialised.  Workgroup ids are
+// remapped so that the tiles running on one XCD (one L2) are neighbours in the output.
 // fp32 path: plain FMA tiles (used by the small fp32 configuration only).
 #include "dp_device.h"
 #include "dp_kernels.h"
 #include "dp_errors.h"
 #include "dp_ktime.h"
+
+#include <algorithm>
 
 namespace dp {
 
@@ -28,18 +31,7 @@ struct EpiParams {
   const void* residual; int ld_res; int residual_f32; int out_fused_f32;
 };
 
-// Epilogue of one accumulator element (bounds already checked by the caller).
-template <typename T>
-__device__ __forceinline__ void epi_fused(const EpiParams<T>& e, int m, int n, float v) {
-  if (e.bias) v += to_f<T>(e.bias[n]);
-  if (e.pre_out) e.pre_out[(size_t)m * e.ld_pre + n] = from_f<T>(v);
-  if (e.act) v = act_apply(e.act, v);
-  if (e.dact_pre) v *= act_grad(e.dact_kind, to_f<T>(e.dact_pre[(size_t)m * e.ld_dact + n]));
-  if (e.gate) v *= to_f<T>(e.gate[(size_t)(m / e.rows_per_batch) * e.gate_ld + n]);
-  if (e.residual) v += to_f<T>(((const T*)e.residual)[(size_t)m * e.ld_res + n]);
-  e.out[(size_t)m * e.ldo + n] = from_f<T>(v);
-}
-
+// Scalar epilogue (fp32 path).
 template <typename T>
 __device__ __forceinline__ void epi_store(const EpiParams<T>& e, int m, int n, float v) {
   if (m < e.M && n < e.N) {
@@ -47,7 +39,77 @@ __device__ __forceinline__ void epi_store(const EpiParams<T>& e, int m, int n, f
     else if (e.out32) {
       float* p = e.out32 + (size_t)m * e.ldo32 + n;
       *p = e.accumulate ? (*p + v) : v;
-    } else epi_fused<T>(e, m, n, v);
+    } else {
+      if (e.bias) v += to_f<T>(e.bias[n]);
+      if (e.pre_out) e.pre_out[(size_t)m * e.ld_pre + n] = from_f<T>(v);
+      if (e.act) v = act_apply(e.act, v);
+      if (e.dact_pre) v *= act_grad(e.dact_kind, to_f<T>(e.dact_pre[(size_t)m * e.ld_dact + n]));
+      if (e.gate) v *= to_f<T>(e.gate[(size_t)(m / e.rows_per_batch) * e.gate_ld + n]);
+      if (e.residual) v += to_f<T>(((const T*)e.residual)[(size_t)m * e.ld_res + n]);
+      e.out[(size_t)m * e.ldo + n] = from_f<T>(v);
+    }
+  }
+}
+
+// Vector epilogue (bf16 path): 8 consecutive columns of row m starting at column n, all in bounds.
+__device__ __forceinline__ void epi_vec8(const EpiParams<bf16>& e, int m, int n, float* v) {
+  if (e.partial || e.out32) {
+    float* o = e.partial ? e.partial + ((size_t)blockIdx.z * e.M + m) * e.N + n : e.out32 + (size_t)m * e.ldo32 + n;
+    if (!e.partial && e.accumulate) {
+      const f32x4 o0 = *reinterpret_cast<const f32x4*>(o), o1 = *reinterpret_cast<const f32x4*>(o + 4);
+#pragma unroll
+      for (int t = 0; t < 4; ++t) { v[t] += o0[t]; v[4 + t] += o1[t]; }
+    }
+    *reinterpret_cast<f32x4*>(o) = *reinterpret_cast<const f32x4*>(&v[0]);
+    *reinterpret_cast<f32x4*>(o + 4) = *reinterpret_cast<const f32x4*>(&v[4]);
+    return;
+  }
+  if (e.bias) {
+    const bf16x8 bv = *reinterpret_cast<const bf16x8*>(e.bias + n);
+#pragma unroll
+    for (int t = 0; t < 8; ++t) v[t] += (float)bv[t];
+  }
+  if (e.pre_out) {
+    bf16x8 o;
+#pragma unroll
+    for (int t = 0; t < 8; ++t) o[t] = (bf16)v[t];
+    *reinterpret_cast<bf16x8*>(e.pre_out + (size_t)m * e.ld_pre + n) = o;
+  }
+  if (e.act) {
+#pragma unroll
+    for (int t = 0; t < 8; ++t) v[t] = act_apply(e.act, v[t]);
+  }
+  if (e.dact_pre) {
+    const bf16x8 pv = *reinterpret_cast<const bf16x8*>(e.dact_pre + (size_t)m * e.ld_dact + n);
+#pragma unroll
+    for (int t = 0; t < 8; ++t) v[t] *= act_grad(e.dact_kind, (float)pv[t]);
+  }
+  if (e.gate) {
+    const bf16x8 gv = *reinterpret_cast<const bf16x8*>(e.gate + (size_t)(m / e.rows_per_batch) * e.gate_ld + n);
+#pragma unroll
+    for (int t = 0; t < 8; ++t) v[t] *= (float)gv[t];
+  }
+  if (e.residual) {
+    if (e.residual_f32) {
+      const float* rp = (const float*)e.residual + (size_t)m * e.ld_res + n;
+      const f32x4 r0 = *reinterpret_cast<const f32x4*>(rp), r1 = *reinterpret_cast<const f32x4*>(rp + 4);
+#pragma unroll
+      for (int t = 0; t < 4; ++t) { v[t] += r0[t]; v[4 + t] += r1[t]; }
+    } else {
+      const bf16x8 rv = *reinterpret_cast<const bf16x8*>((const bf16*)e.residual + (size_t)m * e.ld_res + n);
+#pragma unroll
+      for (int t = 0; t < 8; ++t) v[t] += (float)rv[t];
+    }
+  }
+  if (e.out_fused_f32) {
+    float* op = reinterpret_cast<float*>(e.out) + (size_t)m * e.ldo + n;
+    *reinterpret_cast<f32x4*>(op) = *reinterpret_cast<const f32x4*>(&v[0]);
+    *reinterpret_cast<f32x4*>(op + 4) = *reinterpret_cast<const f32x4*>(&v[4]);
+  } else {
+    bf16x8 o;
+#pragma unroll
+    for (int t = 0; t < 8; ++t) o[t] = (bf16)v[t];
+    *reinterpret_cast<bf16x8*>(e.out + (size_t)m * e.ldo + n) = o;
   }
 }
 
@@ -56,22 +118,43 @@ struct GemmBf16Params {
   const bf16* A; const bf16* B;
   int M, N, K, lda, ldb;
   int k_tiles_per_split;
+  int tiles_m, tiles_n;
   EpiParams<bf16> epi;
 };
 
-template <int BM, int BN, int BK, bool A_MC, bool B_MC>
+template <int BM, int BN, int BK, int WGM, int WGN, bool A_MC, bool B_MC>
 struct GemmSmem {
   // [rows][BK + 8] for contraction-contiguous operands; [BK][cols + 16] for the others
   static constexpr int A_LD = A_MC ? (BM + 16) : (BK + 8);
   static constexpr int B_LD = B_MC ? (BN + 16) : (BK + 8);
   static constexpr int A_ELEMS = A_MC ? BK * A_LD : BM * A_LD;
   static constexpr int B_ELEMS = B_MC ? BK * B_LD : BN * B_LD;
+  static constexpr int WN = BN / WGN;
+  static constexpr int C_LD = WN + 4;                                   // per-wave fp32 staging [32][WN + 4]
+  static constexpr size_t TILE_BYTES = 2 * (size_t)(A_ELEMS + B_ELEMS) * 2;
+  static constexpr size_t EPI_BYTES = (size_t)WGM * WGN * 32 * C_LD * 4;
+  static constexpr size_t BYTES = TILE_BYTES > EPI_BYTES ? TILE_BYTES : EPI_BYTES;
 };
+
+// Maps the linear workgroup id to an output tile.  Hardware deals consecutive ids round-robin
+// to the 8 XCDs; the remap gives each XCD a contiguous range of tiles, ordered in groups of 8
+// tile-rows so that concurrently running tiles share A and B panels in that XCD's L2.
+__device__ __forceinline__ void tile_of_block(int pid, int tiles_m, int tiles_n, int& tm, int& tn) {
+  const int n = tiles_m * tiles_n;
+  const int ppx = (n + 7) / 8, tall = n % 8;
+  const int xcd = pid % 8, local = pid / 8;
+  const int id = (tall == 0 || xcd < tall) ? xcd * ppx + local : tall * ppx + (xcd - tall) * (ppx - 1) + local;
+  const int in_group = 8 * tiles_n;
+  const int first_m = (id / in_group) * 8;
+  const int gsz = min(tiles_m - first_m, 8);
+  tm = first_m + (id % in_group) % gsz;
+  tn = (id % in_group) / gsz;
+}
 
 template <int BM, int BN, int BK, int WGM, int WGN, bool A_MC, bool B_MC>
 __global__ void __launch_bounds__(WGM * WGN * 64)
 gemm_bf16_kernel(const GemmBf16Params p) {
-  using S = GemmSmem<BM, BN, BK, A_MC, B_MC>;
+  using S = GemmSmem<BM, BN, BK, WGM, WGN, A_MC, B_MC>;
   constexpr int NT = WGM * WGN * 64;
   constexpr int WM = BM / WGM, WN = BN / WGN;
   constexpr int TM = WM / 32, TN = WN / 32;
@@ -86,26 +169,34 @@ gemm_bf16_kernel(const GemmBf16Params p) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int g = lane >> 5, l32 = lane & 31;
   const int wm0 = (wave / WGN) * WM, wn0 = (wave % WGN) * WN;
-  const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
+  int tile_m, tile_n;
+  tile_of_block(blockIdx.x, p.tiles_m, p.tiles_n, tile_m, tile_n);
+  const int m0 = tile_m * BM, n0 = tile_n * BN;
 
   const int total_kt = (p.K + BK - 1) / BK;
   const int kt_begin = blockIdx.z * p.k_tiles_per_split;
   const int kt_end = min(total_kt, kt_begin + p.k_tiles_per_split);
 
+  // staged tile chunks; out-of-range chunks are loaded from a clamped (valid) address and
+  // zeroed only when they are written to LDS, so nothing waits on the loads before the MFMAs
   bf16x8 ra[A_PER], rb[B_PER];
+  unsigned oka = 0, okb = 0;
 #define DP_GEMM_LOAD_GLOBAL(kt_)                                                              \
   {                                                                                           \
     const int k0_ = (kt_) * BK;                                                               \
+    oka = 0; okb = 0;                                                                         \
     _Pragma("unroll") for (int i = 0; i < A_PER; ++i) {                                       \
       const int id = tid + i * NT;                                                            \
       if (A_MC) {                                                                             \
         const int kk = id / (BM / 8), c = id % (BM / 8);                                      \
         const int gk = k0_ + kk, gm = m0 + c * 8;                                             \
-        ra[i] = ld8(p.A + (size_t)gk * p.lda + gm, gk < p.K && gm < p.M);                     \
+        ra[i] = *reinterpret_cast<const bf16x8*>(p.A + (size_t)min(gk, p.K - 1) * p.lda + min(gm, p.M - 8)); \
+        oka |= (unsigned)(gk < p.K && gm < p.M) << i;                                         \
       } else {                                                                                \
         const int r = id / (BK / 8), c = id % (BK / 8);                                       \
         const int gm = m0 + r, gk = k0_ + c * 8;                                              \
-        ra[i] = ld8(p.A + (size_t)gm * p.lda + gk, gm < p.M && gk < p.K);                     \
+        ra[i] = *reinterpret_cast<const bf16x8*>(p.A + (size_t)min(gm, p.M - 1) * p.lda + min(gk, p.K - 8)); \
+        oka |= (unsigned)(gm < p.M && gk < p.K) << i;                                         \
       }                                                                                       \
     }                                                                                         \
     _Pragma("unroll") for (int i = 0; i < B_PER; ++i) {                                       \
@@ -113,11 +204,13 @@ gemm_bf16_kernel(const GemmBf16Params p) {
       if (B_MC) {                                                                             \
         const int kk = id / (BN / 8), c = id % (BN / 8);                                      \
         const int gk = k0_ + kk, gn = n0 + c * 8;                                             \
-        rb[i] = ld8(p.B + (size_t)gk * p.ldb + gn, gk < p.K && gn < p.N);                     \
+        rb[i] = *reinterpret_cast<const bf16x8*>(p.B + (size_t)min(gk, p.K - 1) * p.ldb + min(gn, p.N - 8)); \
+        okb |= (unsigned)(gk < p.K && gn < p.N) << i;                                         \
       } else {                                                                                \
         const int r = id / (BK / 8), c = id % (BK / 8);                                       \
         const int gn = n0 + r, gk = k0_ + c * 8;                                              \
-        rb[i] = ld8(p.B + (size_t)gn * p.ldb + gk, gn < p.N && gk < p.K);                     \
+        rb[i] = *reinterpret_cast<const bf16x8*>(p.B + (size_t)min(gn, p.N - 1) * p.ldb + min(gk, p.K - 8)); \
+        okb |= (unsigned)(gn < p.N && gk < p.K) << i;                                         \
       }                                                                                       \
     }                                                                                         \
   }
@@ -127,13 +220,13 @@ gemm_bf16_kernel(const GemmBf16Params p) {
     bf16* bs_ = Bs + (buf_) * S::B_ELEMS;                                                     \
     _Pragma("unroll") for (int i = 0; i < A_PER; ++i) {                                       \
       const int id = tid + i * NT;                                                            \
-      if (A_MC) { const int kk = id / (BM / 8), c = id % (BM / 8); *reinterpret_cast<bf16x8*>(as_ + kk * S::A_LD + c * 8) = ra[i]; } \
-      else      { const int r = id / (BK / 8), c = id % (BK / 8);  *reinterpret_cast<bf16x8*>(as_ + r * S::A_LD + c * 8) = ra[i]; }  \
+      if (A_MC) { const int kk = id / (BM / 8), c = id % (BM / 8); *reinterpret_cast<bf16x8*>(as_ + kk * S::A_LD + c * 8) = ((oka >> i) & 1) ? ra[i] : zero8(); } \
+      else      { const int r = id / (BK / 8), c = id % (BK / 8);  *reinterpret_cast<bf16x8*>(as_ + r * S::A_LD + c * 8) = ((oka >> i) & 1) ? ra[i] : zero8(); }  \
     }                                                                                         \
     _Pragma("unroll") for (int i = 0; i < B_PER; ++i) {                                       \
       const int id = tid + i * NT;                                                            \
-      if (B_MC) { const int kk = id / (BN / 8), c = id % (BN / 8); *reinterpret_cast<bf16x8*>(bs_ + kk * S::B_LD + c * 8) = rb[i]; } \
-      else      { const int r = id / (BK / 8), c = id % (BK / 8);  *reinterpret_cast<bf16x8*>(bs_ + r * S::B_LD + c * 8) = rb[i]; }  \
+      if (B_MC) { const int kk = id / (BN / 8), c = id % (BN / 8); *reinterpret_cast<bf16x8*>(bs_ + kk * S::B_LD + c * 8) = ((okb >> i) & 1) ? rb[i] : zero8(); } \
+      else      { const int r = id / (BK / 8), c = id % (BK / 8);  *reinterpret_cast<bf16x8*>(bs_ + r * S::B_LD + c * 8) = ((okb >> i) & 1) ? rb[i] : zero8(); }  \
     }                                                                                         \
   }
 
@@ -157,113 +250,243 @@ gemm_bf16_kernel(const GemmBf16Params p) {
     if (more) DP_GEMM_LOAD_GLOBAL(kt + 1);
     const bf16* as = As + buf * S::A_ELEMS;
     const bf16* bs = Bs + buf * S::B_ELEMS;
+    // fragments of k-step ks + 1 are fetched from LDS before the MFMAs of k-step ks are issued
+    bf16x8 fa[2][TM], fb[2][TN];
+#define DP_GEMM_LOAD_FRAGS(ks_, set_)                                                                                   \
+    {                                                                                                                     \
+      _Pragma("unroll") for (int i = 0; i < TM; ++i) {                                                                   \
+        if (A_MC) fa[set_][i] = frag_from_mc(as + ((ks_) * 16) * S::A_LD + wm0 + i * 32, S::A_LD, lane);                 \
+        else      fa[set_][i] = *reinterpret_cast<const bf16x8*>(as + (wm0 + i * 32 + l32) * S::A_LD + (ks_) * 16 + 8 * g); \
+      }                                                                                                                   \
+      _Pragma("unroll") for (int j = 0; j < TN; ++j) {                                                                   \
+        if (B_MC) fb[set_][j] = frag_from_mc(bs + ((ks_) * 16) * S::B_LD + wn0 + j * 32, S::B_LD, lane);                 \
+        else      fb[set_][j] = *reinterpret_cast<const bf16x8*>(bs + (wn0 + j * 32 + l32) * S::B_LD + (ks_) * 16 + 8 * g); \
+      }                                                                                                                   \
+    }
+    DP_GEMM_LOAD_FRAGS(0, 0);
 #pragma unroll
     for (int ks = 0; ks < BK / 16; ++ks) {
-      bf16x8 fa[TM], fb[TN];
-#pragma unroll
-      for (int i = 0; i < TM; ++i) {
-        if (A_MC) fa[i] = frag_from_mc(as + (ks * 16) * S::A_LD + wm0 + i * 32, S::A_LD, lane);
-        else      fa[i] = *reinterpret_cast<const bf16x8*>(as + (wm0 + i * 32 + l32) * S::A_LD + ks * 16 + 8 * g);
-      }
-#pragma unroll
-      for (int j = 0; j < TN; ++j) {
-        if (B_MC) fb[j] = frag_from_mc(bs + (ks * 16) * S::B_LD + wn0 + j * 32, S::B_LD, lane);
-        else      fb[j] = *reinterpret_cast<const bf16x8*>(bs + (wn0 + j * 32 + l32) * S::B_LD + ks * 16 + 8 * g);
-      }
+      if (ks + 1 < BK / 16) DP_GEMM_LOAD_FRAGS(ks + 1, (ks + 1) & 1);
+      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int i = 0; i < TM; ++i)
 #pragma unroll
-        for (int j = 0; j < TN; ++j) acc[i][j] = mfma32(fa[i], fb[j], acc[i][j]);
+        for (int j = 0; j < TN; ++j) acc[i][j] = mfma32(fa[ks & 1][i], fb[ks & 1][j], acc[i][j]);
     }
+#undef DP_GEMM_LOAD_FRAGS
     if (more) DP_GEMM_STORE_LDS(buf ^ 1);
     __syncthreads();
   }
 
-  // Epilogue: accumulators -> LDS (fp32, reusing the operand tiles) -> 8 consecutive columns
-  // per thread, so that bias / residual / saved pre-activation loads and all stores are
-  // 16-byte accesses along the contiguous dimension.
-  constexpr int C_LD = BN + 4;
-  static_assert((size_t)BM * C_LD * sizeof(float) <= 2 * (size_t)(S::A_ELEMS + S::B_ELEMS) * sizeof(bf16), "C tile must fit");
-  float* Cs = reinterpret_cast<float*>(smem_raw);
+  // Epilogue.  Each wave stages one 32-row slab of its accumulators at a time through its own
+  // fp32 LDS region (reusing the operand tiles) and re-reads it as 8 consecutive columns per
+  // lane, so bias / residual / saved pre-activation loads and all stores are 16-byte accesses.
+  float* Cw = reinterpret_cast<float*>(smem_raw) + wave * 32 * S::C_LD;
 #pragma unroll
-  for (int i = 0; i < TM; ++i)
+  for (int i = 0; i < TM; ++i) {
 #pragma unroll
     for (int j = 0; j < TN; ++j)
 #pragma unroll
-      for (int r = 0; r < 16; ++r)
-        Cs[(wm0 + i * 32 + 8 * (r >> 2) + 4 * g + (r & 3)) * C_LD + wn0 + j * 32 + l32] = acc[i][j][r];
-  __syncthreads();
-  const EpiParams<bf16>& e = p.epi;
-  for (int idx = tid; idx < BM * BN / 8; idx += NT) {
-    const int lm = idx / (BN / 8), ln = (idx % (BN / 8)) * 8;
-    const int m = m0 + lm, n = n0 + ln;
-    if (m >= p.M || n >= p.N) continue;
-    float v[8];
-    *reinterpret_cast<f32x4*>(&v[0]) = *reinterpret_cast<const f32x4*>(&Cs[lm * C_LD + ln]);
-    *reinterpret_cast<f32x4*>(&v[4]) = *reinterpret_cast<const f32x4*>(&Cs[lm * C_LD + ln + 4]);
-    if (e.partial || e.out32) {
-      float* o = e.partial ? e.partial + ((size_t)blockIdx.z * p.M + m) * p.N + n : e.out32 + (size_t)m * e.ldo32 + n;
-      if (!e.partial && e.accumulate) {
-        const f32x4 o0 = *reinterpret_cast<const f32x4*>(o), o1 = *reinterpret_cast<const f32x4*>(o + 4);
+      for (int r = 0; r < 16; ++r) Cw[(8 * (r >> 2) + 4 * g + (r & 3)) * S::C_LD + j * 32 + l32] = acc[i][j][r];
+    __syncthreads();
 #pragma unroll
-        for (int t = 0; t < 4; ++t) { v[t] += o0[t]; v[4 + t] += o1[t]; }
-      }
-      *reinterpret_cast<f32x4*>(o) = *reinterpret_cast<const f32x4*>(&v[0]);
-      *reinterpret_cast<f32x4*>(o + 4) = *reinterpret_cast<const f32x4*>(&v[4]);
-      continue;
-    }
-    if (e.bias) {
-      const bf16x8 bv = *reinterpret_cast<const bf16x8*>(e.bias + n);
-#pragma unroll
-      for (int t = 0; t < 8; ++t) v[t] += (float)bv[t];
-    }
-    if (e.pre_out) {
-      bf16x8 o;
-#pragma unroll
-      for (int t = 0; t < 8; ++t) o[t] = (bf16)v[t];
-      *reinterpret_cast<bf16x8*>(e.pre_out + (size_t)m * e.ld_pre + n) = o;
-    }
-    if (e.act) {
-#pragma unroll
-      for (int t = 0; t < 8; ++t) v[t] = act_apply(e.act, v[t]);
-    }
-    if (e.dact_pre) {
-      const bf16x8 pv = *reinterpret_cast<const bf16x8*>(e.dact_pre + (size_t)m * e.ld_dact + n);
-#pragma unroll
-      for (int t = 0; t < 8; ++t) v[t] *= act_grad(e.dact_kind, (float)pv[t]);
-    }
-    if (e.gate) {
-      const bf16x8 gv = *reinterpret_cast<const bf16x8*>(e.gate + (size_t)(m / e.rows_per_batch) * e.gate_ld + n);
-#pragma unroll
-      for (int t = 0; t < 8; ++t) v[t] *= (float)gv[t];
-    }
-    if (e.residual) {
-      if (e.residual_f32) {
-        const float* rp = (const float*)e.residual + (size_t)m * e.ld_res + n;
-        const f32x4 r0 = *reinterpret_cast<const f32x4*>(rp), r1 = *reinterpret_cast<const f32x4*>(rp + 4);
-#pragma unroll
-        for (int t = 0; t < 4; ++t) { v[t] += r0[t]; v[4 + t] += r1[t]; }
-      } else {
-        const bf16x8 rv = *reinterpret_cast<const bf16x8*>((const bf16*)e.residual + (size_t)m * e.ld_res + n);
-#pragma unroll
-        for (int t = 0; t < 8; ++t) v[t] += (float)rv[t];
+    for (int it = 0; it < 32 * WN / 8 / 64; ++it) {
+      const int id = it * 64 + lane;
+      const int lr = id / (WN / 8), lc = (id % (WN / 8)) * 8;
+      const int m = m0 + wm0 + i * 32 + lr, n = n0 + wn0 + lc;
+      if (m < p.M && n < p.N) {
+        float v[8];
+        *reinterpret_cast<f32x4*>(&v[0]) = *reinterpret_cast<const f32x4*>(&Cw[lr * S::C_LD + lc]);
+        *reinterpret_cast<f32x4*>(&v[4]) = *reinterpret_cast<const f32x4*>(&Cw[lr * S::C_LD + lc + 4]);
+        epi_vec8(p.epi, m, n, v);
       }
     }
-    if (e.out_fused_f32) {
-      float* op = reinterpret_cast<float*>(e.out) + (size_t)m * e.ldo + n;
-      *reinterpret_cast<f32x4*>(op) = *reinterpret_cast<const f32x4*>(&v[0]);
-      *reinterpret_cast<f32x4*>(op + 4) = *reinterpret_cast<const f32x4*>(&v[4]);
-    } else {
-      bf16x8 o;
-#pragma unroll
-      for (int t = 0; t < 8; ++t) o[t] = (bf16)v[t];
-      *reinterpret_cast<bf16x8*>(e.out + (size_t)m * e.ldo + n) = o;
-    }
+    __syncthreads();
   }
 }
 
 #undef DP_GEMM_LOAD_GLOBAL
 #undef DP_GEMM_STORE_LDS
+
+// ------------------------------------------------------------------ bf16 MFMA kernel, direct-to-LDS pipeline
+// Same tiling and epilogue, but the operand tiles travel global -> LDS without passing through
+// registers (global_load_lds_dwordx4: every lane fetches 16 bytes, the wave's 1 KB lands
+// contiguously in LDS) in a four-stage ring, three k-tiles ahead of the MFMAs.  On MI355X a
+// k-tile's MFMA time is far shorter than the memory latency, so the depth of this prefetch,
+// not the instruction schedule, decides the speed.  LDS tiles are unpadded; bank conflicts
+// are avoided by permuting 16-byte chunks inside a row (the permutation is applied through
+// the per-lane global address, and undone when fragments are read).
+//   K-contiguous operand:  tile [rows][32], chunk c of row r stored at c ^ ((r >> 2) & 3).
+//   K-strided operand:     tile [32][cols], chunk c of k-row k stored at c ^ (2 * (k & 3)).
+// Requires K % 32 == 0.  Rows / columns beyond M / N are fetched from a clamped address; they
+// only feed accumulators whose outputs are never stored.
+constexpr int DTL_BK = 32, DTL_STAGES = 4;
+
+template <int BM, int BN, int WGM, int WGN>
+struct DtlSmem {
+  static constexpr int A_BYTES = BM * DTL_BK * 2, B_BYTES = BN * DTL_BK * 2, STAGE = A_BYTES + B_BYTES;
+  static constexpr int WN = BN / WGN;
+  static constexpr int C_LD = WN + 4;
+  static constexpr size_t TILE_BYTES = (size_t)DTL_STAGES * STAGE;
+  static constexpr size_t EPI_BYTES = (size_t)WGM * WGN * 32 * C_LD * 4;
+  static constexpr size_t BYTES = TILE_BYTES > EPI_BYTES ? TILE_BYTES : EPI_BYTES;
+};
+
+template <int BM, int BN, int WGM, int WGN, bool A_MC, bool B_MC>
+__global__ void __launch_bounds__(WGM * WGN * 64)
+gemm_bf16_dtl_kernel(const GemmBf16Params p) {
+  using S = DtlSmem<BM, BN, WGM, WGN>;
+  constexpr int NW = WGM * WGN, BK = DTL_BK;
+  constexpr int WM = BM / WGM, WN = BN / WGN;
+  constexpr int TM = WM / 32, TN = WN / 32;
+  constexpr int A_LOADS = S::A_BYTES / 1024 / NW, B_LOADS = S::B_BYTES / 1024 / NW, LOADS = A_LOADS + B_LOADS;
+  static_assert(S::A_BYTES % (1024 * NW) == 0 && S::B_BYTES % (1024 * NW) == 0, "tile/waves mismatch");
+
+  extern __shared__ __attribute__((aligned(1024))) unsigned char smem_raw[];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int g = lane >> 5, l32 = lane & 31;
+  const int wm0 = (wave / WGN) * WM, wn0 = (wave % WGN) * WN;
+  int tile_m, tile_n;
+  tile_of_block(blockIdx.x, p.tiles_m, p.tiles_n, tile_m, tile_n);
+  const int m0 = tile_m * BM, n0 = tile_n * BN;
+  const int kt_begin = blockIdx.z * p.k_tiles_per_split;
+  const int kt_end = min(p.K / BK, kt_begin + p.k_tiles_per_split);
+  const int nk = kt_end - kt_begin;
+
+  // per-lane global source of each of this wave's 1 KB pieces (k-tile 0); advancing by one
+  // k-tile adds a constant
+  const bf16* ga[A_LOADS]; const bf16* gb[B_LOADS];
+#pragma unroll
+  for (int j = 0; j < A_LOADS; ++j) {
+    const int blk = wave * A_LOADS + j;
+    if (A_MC) {
+      const int k = blk * (1024 / (BM * 2)) + lane / (BM / 8), pc = lane % (BM / 8), c = pc ^ (2 * (k & 3));
+      ga[j] = p.A + (size_t)(kt_begin * BK + k) * p.lda + min(m0 + c * 8, p.M - 8);
+    } else {
+      const int r = blk * 16 + (lane >> 2), pc = lane & 3, c = pc ^ ((r >> 2) & 3);
+      ga[j] = p.A + (size_t)min(m0 + r, p.M - 1) * p.lda + kt_begin * BK + c * 8;
+    }
+  }
+#pragma unroll
+  for (int j = 0; j < B_LOADS; ++j) {
+    const int blk = wave * B_LOADS + j;
+    if (B_MC) {
+      const int k = blk * (1024 / (BN * 2)) + lane / (BN / 8), pc = lane % (BN / 8), c = pc ^ (2 * (k & 3));
+      gb[j] = p.B + (size_t)(kt_begin * BK + k) * p.ldb + min(n0 + c * 8, p.N - 8);
+    } else {
+      const int r = blk * 16 + (lane >> 2), pc = lane & 3, c = pc ^ ((r >> 2) & 3);
+      gb[j] = p.B + (size_t)min(n0 + r, p.N - 1) * p.ldb + kt_begin * BK + c * 8;
+    }
+  }
+  const size_t a_step = A_MC ? (size_t)BK * p.lda : BK, b_step = B_MC ? (size_t)BK * p.ldb : BK;
+
+#define DP_DTL_ISSUE(t_)                                                                                              \
+  {                                                                                                                   \
+    unsigned char* st_ = smem_raw + ((t_) % DTL_STAGES) * S::STAGE;                                                   \
+    _Pragma("unroll") for (int j = 0; j < A_LOADS; ++j)                                                               \
+      async_copy_16B(ga[j] + (size_t)(t_) * a_step, st_ + (wave * A_LOADS + j) * 1024); \
+    _Pragma("unroll") for (int j = 0; j < B_LOADS; ++j)                                                               \
+      async_copy_16B(gb[j] + (size_t)(t_) * b_step, st_ + S::A_BYTES + (wave * B_LOADS + j) * 1024); \
+  }
+
+  f32x16 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  // Fragment fetch of k-step ks_ of the k-tile in stage st_ into register set set_.
+  bf16x8 fa[2][TM], fb[2][TN];
+#define DP_DTL_FRAGS(st_, ks_, set_)                                                                                  \
+  {                                                                                                                   \
+    const bf16* as = reinterpret_cast<const bf16*>(smem_raw + (st_) * S::STAGE);                                      \
+    const bf16* bs = reinterpret_cast<const bf16*>(smem_raw + (st_) * S::STAGE + S::A_BYTES);                         \
+    _Pragma("unroll") for (int i = 0; i < TM; ++i) {                                                                  \
+      if (A_MC) {                                                                                                     \
+        const int b = lane >> 4, j = lane & 15;                                                                       \
+        const int k = (ks_) * 16 + 8 * (b >> 1) + (j >> 2);                                                           \
+        const int c = (wm0 + i * 32) / 8 + 2 * (b & 1) + ((j & 3) >> 1);                                              \
+        const bf16* q = as + k * BM + ((c ^ (2 * (k & 3))) * 8) + 4 * (j & 1);                                        \
+        fa[set_][i] = __builtin_shufflevector(lds_read_tr(q), lds_read_tr(q + 4 * BM), 0, 1, 2, 3, 4, 5, 6, 7);       \
+      } else {                                                                                                        \
+        const int r = wm0 + i * 32 + l32;                                                                             \
+        fa[set_][i] = *reinterpret_cast<const bf16x8*>(as + r * BK + (((2 * (ks_) + g) ^ ((r >> 2) & 3)) * 8));       \
+      }                                                                                                               \
+    }                                                                                                                 \
+    _Pragma("unroll") for (int j2 = 0; j2 < TN; ++j2) {                                                               \
+      if (B_MC) {                                                                                                     \
+        const int b = lane >> 4, j = lane & 15;                                                                       \
+        const int k = (ks_) * 16 + 8 * (b >> 1) + (j >> 2);                                                           \
+        const int c = (wn0 + j2 * 32) / 8 + 2 * (b & 1) + ((j & 3) >> 1);                                             \
+        const bf16* q = bs + k * BN + ((c ^ (2 * (k & 3))) * 8) + 4 * (j & 1);                                        \
+        fb[set_][j2] = __builtin_shufflevector(lds_read_tr(q), lds_read_tr(q + 4 * BN), 0, 1, 2, 3, 4, 5, 6, 7);      \
+      } else {                                                                                                        \
+        const int r = wn0 + j2 * 32 + l32;                                                                            \
+        fb[set_][j2] = *reinterpret_cast<const bf16x8*>(bs + r * BK + (((2 * (ks_) + g) ^ ((r >> 2) & 3)) * 8));      \
+      }                                                                                                               \
+    }                                                                                                                 \
+  }
+#define DP_DTL_MFMAS(set_)                                                                                            \
+  _Pragma("unroll") for (int i = 0; i < TM; ++i)                                                                      \
+    _Pragma("unroll") for (int j2 = 0; j2 < TN; ++j2) acc[i][j2] = mfma32(fa[set_][i], fb[set_][j2], acc[i][j2]);
+
+  // Software pipeline.  Fragments are fetched one k-step ahead of the MFMAs that use them, also
+  // across the k-tile boundary: the wait + barrier that publishes k-tile t + 1 sits between the
+  // two MFMA groups of k-tile t.  Passing that barrier also means every wave has finished reading
+  // k-tile t - 1, so its stage is refilled with k-tile t + 3 right after it.
+  for (int t = 0; t < DTL_STAGES - 1 && t < nk; ++t) DP_DTL_ISSUE(t);
+  if (nk > 2) wait_vmcnt<2 * LOADS>();
+  else if (nk > 1) wait_vmcnt<LOADS>();
+  else wait_vmcnt<0>();
+  barrier_nofence();
+  DP_DTL_FRAGS(0, 0, 0);
+  for (int t = 0; t < nk; ++t) {
+    const int st = t % DTL_STAGES;
+    DP_DTL_FRAGS(st, 1, 1);
+    __builtin_amdgcn_sched_barrier(0);
+    DP_DTL_MFMAS(0);
+    __builtin_amdgcn_sched_barrier(0);
+    if (t + 1 < nk) {
+      if (t + 2 < nk) wait_vmcnt<LOADS>();
+      else wait_vmcnt<0>();
+      barrier_nofence();
+      if (t + DTL_STAGES - 1 < nk) DP_DTL_ISSUE(t + DTL_STAGES - 1);
+      DP_DTL_FRAGS((t + 1) % DTL_STAGES, 0, 0);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    DP_DTL_MFMAS(1);
+    __builtin_amdgcn_sched_barrier(0);
+  }
+#undef DP_DTL_FRAGS
+#undef DP_DTL_MFMAS
+#undef DP_DTL_ISSUE
+  __syncthreads();   // every wave is done with the operand tiles before they are reused below
+
+  float* Cw = reinterpret_cast<float*>(smem_raw) + wave * 32 * S::C_LD;
+#pragma unroll
+  for (int i = 0; i < TM; ++i) {
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) Cw[(8 * (r >> 2) + 4 * g + (r & 3)) * S::C_LD + j * 32 + l32] = acc[i][j][r];
+    __syncthreads();
+#pragma unroll
+    for (int it = 0; it < 32 * WN / 8 / 64; ++it) {
+      const int id = it * 64 + lane;
+      const int lr = id / (WN / 8), lc = (id % (WN / 8)) * 8;
+      const int m = m0 + wm0 + i * 32 + lr, n = n0 + wn0 + lc;
+      if (m < p.M && n < p.N) {
+        float v[8];
+        *reinterpret_cast<f32x4*>(&v[0]) = *reinterpret_cast<const f32x4*>(&Cw[lr * S::C_LD + lc]);
+        *reinterpret_cast<f32x4*>(&v[4]) = *reinterpret_cast<const f32x4*>(&Cw[lr * S::C_LD + lc + 4]);
+        epi_vec8(p.epi, m, n, v);
+      }
+    }
+    __syncthreads();
+  }
+}
 
 // ------------------------------------------------------------------ fp32 FMA kernel
 struct GemmF32Params {
@@ -328,31 +551,69 @@ static EpiParams<T> make_epi(const GemmArgs& a) {
   return e;
 }
 
-static int choose_splits(int M, int N, int K, int BM, int BN, int BK) {
-  const long tiles = (long)((M + BM - 1) / BM) * ((N + BN - 1) / BN);
-  const int kt = (K + BK - 1) / BK;
+// Tile configurations of the bf16 kernel.
+struct TileCfg { int bm, bn, bk, waves; };
+static const TileCfg kCfgs[] = {
+    {128, 128, 64, 4},   // 0: two workgroups per CU; small or ragged problems
+    {256, 128, 64, 8},   // 1
+    {256, 256, 64, 8},   // 2: least LDS and L2 traffic per FLOP; large problems
+    {128, 256, 64, 8},   // 3
+    {256, 128, 32, 8},   // 4: shallower k-tile, two workgroups per CU
+    {128, 128, 32, 4},   // 5
+};
+constexpr int kNumCfgs = sizeof(kCfgs) / sizeof(kCfgs[0]);
+constexpr int kCUs = 256;
+
+static int choose_splits(long tiles, int kt) {
   int s = 1;
-  // aim for >= 512 workgroups (two per CU) while keeping >= 8 k-tiles per split
-  while (tiles * s < 512 && kt / (s * 2) >= 8 && s < 64) s *= 2;
+  // split-K only for the fp32-output (weight-gradient) GEMMs: fill the 256 CUs while keeping
+  // at least 8 k-tiles per split
+  while (tiles * s < kCUs && kt / (s * 2) >= 8 && s < 64) s *= 2;
   return s;
 }
 
+// Picks the tile configuration (indices as in launch_gemm's switch) from a sweep of all GEMM
+// shapes of the five workloads on MI355X:
+//  - y = x W^T (both operands K-contiguous): the direct-to-LDS pipeline, 128x128 tiles, or
+//    256x128 tiles for very large outputs;
+//  - dx = dy W: register-staged kernel; 256x256 tiles when the contraction is long and there
+//    are enough tiles to fill the CUs, else 256x128, else 128x128;
+//  - dW = dy^T x (both operands read through the transposing LDS load): 128x128, two
+//    workgroups per CU.
+static int choose_cfg(int M, int N, int K, bool a_mc, bool b_mc) {
+  const long t256x256 = (long)((M + 255) / 256) * ((N + 255) / 256);
+  const long t256x128 = (long)((M + 255) / 256) * ((N + 127) / 128);
+  if (a_mc) return 0;
+  if (!b_mc) {
+    if (K % DTL_BK) return t256x128 >= 128 ? 1 : 0;
+    return (double)M * N >= 8192.0 * 4096.0 ? 7 : 8;
+  }
+  if (K >= 2 * N && t256x256 >= 128) return 2;
+  return t256x128 >= 128 ? 1 : 0;
+}
+
 size_t gemm_splitk_ws_bytes(int M, int N, int K) {
-  int s = choose_splits(M, N, K, 128, 128, 64);
-  return s > 1 ? (size_t)s * M * N * sizeof(float) : 0;
+  size_t worst = 0;
+  for (int c = 0; c < kNumCfgs; ++c) {
+    const long tiles = (long)((M + kCfgs[c].bm - 1) / kCfgs[c].bm) * ((N + kCfgs[c].bn - 1) / kCfgs[c].bn);
+    const int s = choose_splits(tiles, (K + kCfgs[c].bk - 1) / kCfgs[c].bk);
+    if (s > 1) worst = std::max(worst, (size_t)s * M * N * sizeof(float));
+  }
+  return worst;
 }
 
 template <int BM, int BN, int BK, int WGM, int WGN, bool A_MC, bool B_MC>
 static int launch_bf16_cfg(const GemmArgs& a, hipStream_t s) {
-  using S = GemmSmem<BM, BN, BK, A_MC, B_MC>;
+  using S = GemmSmem<BM, BN, BK, WGM, WGN, A_MC, B_MC>;
   GemmBf16Params p;
   p.A = (const bf16*)a.A; p.B = (const bf16*)a.B;
   p.M = a.M; p.N = a.N; p.K = a.K; p.lda = a.lda; p.ldb = a.ldb;
   p.epi = make_epi<bf16>(a);
+  p.tiles_m = (a.M + BM - 1) / BM; p.tiles_n = (a.N + BN - 1) / BN;
   const int kt = (a.K + BK - 1) / BK;
   int splits = 1;
   if (a.out_f32) {
-    splits = choose_splits(a.M, a.N, a.K, BM, BN, BK);
+    splits = choose_splits((long)p.tiles_m * p.tiles_n, kt);
     if (splits > 1) {
       const size_t need = (size_t)splits * a.M * a.N * sizeof(float);
       if (!a.splitk_ws || a.splitk_ws_bytes < need) splits = 1;
@@ -361,8 +622,8 @@ static int launch_bf16_cfg(const GemmArgs& a, hipStream_t s) {
   p.k_tiles_per_split = (kt + splits - 1) / splits;
   splits = (kt + p.k_tiles_per_split - 1) / p.k_tiles_per_split;
   if (splits > 1) p.epi.partial = a.splitk_ws;
-  dim3 grid((a.N + BN - 1) / BN, (a.M + BM - 1) / BM, splits);
-  const size_t smem = 2 * (size_t)(S::A_ELEMS + S::B_ELEMS) * sizeof(bf16);
+  dim3 grid(p.tiles_m * p.tiles_n, 1, splits);
+  const size_t smem = S::BYTES;
   auto kern = gemm_bf16_kernel<BM, BN, BK, WGM, WGN, A_MC, B_MC>;
   static bool attr_set = false;
   if (!attr_set) {
@@ -374,6 +635,49 @@ static int launch_bf16_cfg(const GemmArgs& a, hipStream_t s) {
   if (hipGetLastError() != hipSuccess) return set_error(DP_EHIP, "gemm launch failed");
   if (splits > 1) return launch_reduce_partials(a.splitk_ws, splits, (size_t)a.M * a.N, a.out_f32, a.accumulate, s);
   return DP_OK;
+}
+
+template <int BM, int BN, int WGM, int WGN, bool A_MC, bool B_MC>
+static int launch_dtl_cfg(const GemmArgs& a, hipStream_t s) {
+  using S = DtlSmem<BM, BN, WGM, WGN>;
+  GemmBf16Params p;
+  p.A = (const bf16*)a.A; p.B = (const bf16*)a.B;
+  p.M = a.M; p.N = a.N; p.K = a.K; p.lda = a.lda; p.ldb = a.ldb;
+  p.epi = make_epi<bf16>(a);
+  p.tiles_m = (a.M + BM - 1) / BM; p.tiles_n = (a.N + BN - 1) / BN;
+  const int kt = a.K / DTL_BK;
+  int splits = 1;
+  if (a.out_f32) {
+    splits = choose_splits((long)p.tiles_m * p.tiles_n, kt / 2);
+    if (splits > 1) {
+      const size_t need = (size_t)splits * a.M * a.N * sizeof(float);
+      if (!a.splitk_ws || a.splitk_ws_bytes < need) splits = 1;
+    }
+  }
+  p.k_tiles_per_split = (kt + splits - 1) / splits;
+  splits = (kt + p.k_tiles_per_split - 1) / p.k_tiles_per_split;
+  if (splits > 1) p.epi.partial = a.splitk_ws;
+  dim3 grid(p.tiles_m * p.tiles_n, 1, splits);
+  const size_t smem = S::BYTES;
+  auto kern = gemm_bf16_dtl_kernel<BM, BN, WGM, WGN, A_MC, B_MC>;
+  static bool attr_set = false;
+  if (!attr_set) {
+    if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) != hipSuccess)
+      return set_error(DP_EHIP, "hipFuncSetAttribute(gemm) failed");
+    attr_set = true;
+  }
+  hipLaunchKernelGGL(kern, grid, dim3(WGM * WGN * 64), smem, s, p);
+  if (hipGetLastError() != hipSuccess) return set_error(DP_EHIP, "gemm launch failed");
+  if (splits > 1) return launch_reduce_partials(a.splitk_ws, splits, (size_t)a.M * a.N, a.out_f32, a.accumulate, s);
+  return DP_OK;
+}
+
+template <int BM, int BN, int WGM, int WGN>
+static int launch_dtl_layout(const GemmArgs& a, hipStream_t s) {
+  if (!a.a_mc && !a.b_mc) return launch_dtl_cfg<BM, BN, WGM, WGN, false, false>(a, s);
+  if (!a.a_mc && a.b_mc) return launch_dtl_cfg<BM, BN, WGM, WGN, false, true>(a, s);
+  if (a.a_mc && a.b_mc) return launch_dtl_cfg<BM, BN, WGM, WGN, true, true>(a, s);
+  return launch_dtl_cfg<BM, BN, WGM, WGN, true, false>(a, s);
 }
 
 template <int BM, int BN, int BK, int WGM, int WGN>
@@ -397,12 +701,26 @@ int launch_gemm(const GemmArgs& a, hipStream_t s) {
     if (((uintptr_t)a.A % 16) || ((uintptr_t)a.B % 16)) return set_error(DP_EALIGN, "gemm(bf16): operands must be 16-byte aligned");
     if (a.lda < a_inner || a.ldb < b_inner) return set_error(DP_EINVAL, "gemm: leading dim too small");
     if (a.N % 8) return set_error(DP_EUNSUPPORTED, "gemm(bf16): N must be a multiple of 8");
+    if (a_inner < 8 || b_inner < 8) return set_error(DP_EUNSUPPORTED, "gemm(bf16): contiguous extents must be at least 8");
     const int elds[] = {a.out ? a.ldo : 8, a.pre_out ? a.ld_pre : 8, a.dact_pre ? a.ld_dact : 8, a.gate ? a.gate_ld : 8, a.residual ? a.ld_res : 8};
     for (int x : elds) if (x % 8 || x < 8) return set_error(DP_EUNSUPPORTED, "gemm(bf16): epilogue leading dims must be multiples of 8");
     const void* eps[] = {a.out, a.out_f32, a.bias, a.pre_out, a.dact_pre, a.gate, a.residual, a.splitk_ws};
     for (const void* x : eps) if ((uintptr_t)x % 16) return set_error(DP_EALIGN, "gemm(bf16): epilogue operands must be 16-byte aligned");
+    const int cfg = (a.force_cfg > 0 && a.force_cfg <= kNumCfgs + 4) ? a.force_cfg - 1 : choose_cfg(a.M, a.N, a.K, a.a_mc != 0, a.b_mc != 0);
     KScope ks(a.a_mc ? KK_GEMM_TN : (a.b_mc ? KK_GEMM_NN : KK_GEMM_NT), 2.0 * a.M * a.N * a.K,
               2.0 * ((double)a.M * a.K + (double)a.N * a.K + (double)a.M * a.N), s, a.M, a.N, a.K);
+    switch (cfg) {
+      case 1: return launch_bf16_layout<256, 128, 64, 4, 2>(a, s);
+      case 2: return launch_bf16_layout<256, 256, 64, 2, 4>(a, s);
+      case 3: return launch_bf16_layout<128, 256, 64, 2, 4>(a, s);
+      case 4: return launch_bf16_layout<256, 128, 32, 4, 2>(a, s);
+      case 5: return launch_bf16_layout<128, 128, 32, 2, 2>(a, s);
+      case 6: if (a.K % DTL_BK == 0) return launch_dtl_layout<256, 256, 2, 4>(a, s); break;
+      case 7: if (a.K % DTL_BK == 0) return launch_dtl_layout<256, 128, 4, 2>(a, s); break;
+      case 8: if (a.K % DTL_BK == 0) return launch_dtl_layout<128, 128, 2, 2>(a, s); break;
+      case 9: if (a.K % DTL_BK == 0) return launch_dtl_layout<256, 256, 2, 2>(a, s); break;
+      default: break;
+    }
     return launch_bf16_layout<128, 128, 64, 2, 2>(a, s);
   }
   GemmF32Params p;

@@ -815,4 +815,51 @@ int dp_encoder_profile(dp_encoder* enc, const void* const* params, const int32_t
   return DP_OK;
 }
 
+size_t dp_op_gemm_workspace_bytes(int M, int N, int K) {
+  if (M <= 0 || N <= 0 || K <= 0) return 0;
+  return gemm_splitk_ws_bytes(M, N, K);
+}
+
+int dp_op_gemm(int dtype, const void* A, int lda, int a_kmajor, const void* B, int ldb, int b_kmajor, int M, int N, int K,
+               const void* bias, void* C, int ldc, int out_is_f32, int accumulate, void* workspace, size_t workspace_bytes,
+               int tile_cfg, void* hip_stream) {
+  if (dtype != DP_F32 && dtype != DP_BF16) return set_error(DP_EINVAL, "unknown dtype");
+  DP_TRY(check_ptr(A, "A")); DP_TRY(check_ptr(B, "B")); DP_TRY(check_ptr(C, "C"));
+  GemmArgs g;
+  memset(&g, 0, sizeof(g));
+  g.dtype = dtype; g.A = A; g.B = B; g.M = M; g.N = N; g.K = K; g.lda = lda; g.ldb = ldb; g.a_mc = a_kmajor != 0; g.b_mc = b_kmajor != 0;
+  if (out_is_f32) {
+    if (bias) return set_error(DP_EUNSUPPORTED, "dp_op_gemm: bias with fp32 output is not supported");
+    g.out_f32 = (float*)C; g.ldo32 = ldc; g.accumulate = accumulate != 0;
+    g.splitk_ws = (float*)workspace; g.splitk_ws_bytes = workspace ? workspace_bytes : 0;
+  } else {
+    g.out = C; g.ldo = ldc; g.bias = bias;
+  }
+  g.force_cfg = tile_cfg;
+  return launch_gemm(g, (hipStream_t)hip_stream);
+}
+
+int dp_op_attention_fwd(int dtype, int B, int H, int Nq, int Nk, int d_head, int causal, float scale, const void* q, int ldq,
+                        const void* k, int ldk, const void* v, int ldv, void* o, int ldo, float* lse, void* hip_stream) {
+  if (dtype != DP_F32 && dtype != DP_BF16) return set_error(DP_EINVAL, "unknown dtype");
+  AttnArgs a;
+  memset(&a, 0, sizeof(a));
+  a.dtype = dtype; a.B = B; a.H = H; a.Nq = Nq; a.Nk = Nk; a.d_head = d_head; a.causal = causal != 0; a.scale = scale;
+  a.q = q; a.ldq = ldq; a.k = k; a.ldk = ldk; a.v = v; a.ldv = ldv; a.o = o; a.ldo = ldo; a.lse = lse;
+  return launch_attn_fwd(a, (hipStream_t)hip_stream);
+}
+
+int dp_op_attention_bwd(int dtype, int B, int H, int Nq, int Nk, int d_head, float scale, const void* q, int ldq, const void* k,
+                        int ldk, const void* v, int ldv, const void* o, int ldo, const float* lse, const void* d_o, int lddo,
+                        float* delta, void* dq, int lddq, void* dk, int lddk, void* dv, int lddv, void* hip_stream) {
+  if (dtype != DP_F32 && dtype != DP_BF16) return set_error(DP_EINVAL, "unknown dtype");
+  AttnArgs a;
+  memset(&a, 0, sizeof(a));
+  a.dtype = dtype; a.B = B; a.H = H; a.Nq = Nq; a.Nk = Nk; a.d_head = d_head; a.scale = scale;
+  a.q = q; a.ldq = ldq; a.k = k; a.ldk = ldk; a.v = v; a.ldv = ldv; a.o = const_cast<void*>(o); a.ldo = ldo;
+  a.lse = const_cast<float*>(lse); a.dout = d_o; a.lddo = lddo; a.delta = delta;
+  a.dq = dq; a.lddq = lddq; a.dk = dk; a.lddk = lddk; a.dv = dv; a.lddv = lddv;
+  return launch_attn_bwd(a, (hipStream_t)hip_stream);
+}
+
 }  // extern "C"
