@@ -72,6 +72,22 @@ __device__ __forceinline__ bf16x8 pack8(const f32x16& v, int off) {
   return o;
 }
 
+// Maps a linear workgroup id to (tile along the sequence, batch * head).  Hardware deals
+// consecutive ids round-robin to the 8 XCDs; with this map all tiles of one (batch, head) run
+// on the same XCD, so its K/V (or Q/dO) stream is fetched into one L2 only.
+__device__ __forceinline__ void attn_block_map(int id, int ntiles, int BH, int& tile, int& bh) {
+  const int full = (BH / 8) * 8;
+  if (id < full * ntiles) {
+    const int grp = id / (8 * ntiles), r = id % (8 * ntiles);
+    bh = grp * 8 + (r & 7);
+    tile = r >> 3;
+  } else {
+    const int r = id - full * ntiles;
+    bh = full + r / ntiles;
+    tile = r % ntiles;
+  }
+}
+
 // ------------------------------------------------------------------ forward (bf16)
 template <int DHP, bool CAUSAL>
 __global__ void __launch_bounds__(256) attn_fwd_bf16_kernel(const AttnK p) {
@@ -80,8 +96,10 @@ __global__ void __launch_bounds__(256) attn_fwd_bf16_kernel(const AttnK p) {
   __shared__ __attribute__((aligned(16))) bf16 Ks[2][64 * K_LD];
   __shared__ __attribute__((aligned(16))) bf16 Vs[2][64 * V_LD];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 5, l32 = lane & 31;
-  const int b = blockIdx.y / p.H, h = blockIdx.y % p.H;
-  const int qi = blockIdx.x * 128 + wave * 32 + l32;
+  int qtile, bh;
+  attn_block_map(blockIdx.x, (p.Nq + 127) / 128, p.B * p.H, qtile, bh);
+  const int b = bh / p.H, h = bh % p.H;
+  const int qi = qtile * 128 + wave * 32 + l32;
   const bf16* qb = (const bf16*)p.q + (size_t)b * p.Nq * p.ldq + h * p.dh;
   const bf16* kb = (const bf16*)p.k + (size_t)b * p.Nk * p.ldk + h * p.dh;
   const bf16* vb = (const bf16*)p.v + (size_t)b * p.Nk * p.ldv + h * p.dh;
@@ -98,7 +116,7 @@ __global__ void __launch_bounds__(256) attn_fwd_bf16_kernel(const AttnK p) {
   float m = -INFINITY, lsum = 0.f;
 
   int nkt = (p.Nk + 63) / 64;
-  if (CAUSAL) nkt = min(nkt, (min(p.Nq, (int)blockIdx.x * 128 + 128) + 63) / 64);
+  if (CAUSAL) nkt = min(nkt, (min(p.Nq, qtile * 128 + 128) + 63) / 64);
 
   TileLoader<DHP, 256> lk, lv;
   lk.load(kb, p.ldk, 0, p.Nk, p.dh, tid);
@@ -127,7 +145,7 @@ __global__ void __launch_bounds__(256) attn_fwd_bf16_kernel(const AttnK p) {
     }
     // online softmax over this lane's query column (shared with lane ^ 32)
     float mx = m;
-    const bool edge = (kt * 64 + 64 > p.Nk) || (CAUSAL && kt * 64 + 63 > (int)blockIdx.x * 128 + wave * 32);
+    const bool edge = (kt * 64 + 64 > p.Nk) || (CAUSAL && kt * 64 + 63 > qtile * 128 + wave * 32);
 #pragma unroll
     for (int t = 0; t < 2; ++t)
 #pragma unroll
@@ -227,8 +245,10 @@ __global__ void __launch_bounds__(256) attn_bwd_dq_bf16_kernel(const AttnK p) {
   __shared__ __attribute__((aligned(16))) bf16 Ks[2][64 * LD];
   __shared__ __attribute__((aligned(16))) bf16 Vs[2][64 * LD];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 5, l32 = lane & 31;
-  const int b = blockIdx.y / p.H, h = blockIdx.y % p.H;
-  const int qi = blockIdx.x * 128 + wave * 32 + l32;
+  int qtile, bh;
+  attn_block_map(blockIdx.x, (p.Nq + 127) / 128, p.B * p.H, qtile, bh);
+  const int b = bh / p.H, h = bh % p.H;
+  const int qi = qtile * 128 + wave * 32 + l32;
   const bool qok = qi < p.Nq;
   const bf16* kb = (const bf16*)p.k + (size_t)b * p.Nk * p.ldk + h * p.dh;
   const bf16* vb = (const bf16*)p.v + (size_t)b * p.Nk * p.ldv + h * p.dh;
@@ -322,7 +342,7 @@ __global__ void __launch_bounds__(256) attn_bwd_dq_bf16_kernel(const AttnK p) {
 // ------------------------------------------------------------------ dK, dV (bf16)
 // grid.x = ceil(Nk / 128); each wave owns 32 keys and walks all query tiles.
 template <int DHP>
-__global__ void __launch_bounds__(256) attn_bwd_dkv_bf16_kernel(const AttnK p) {
+__global__ void __launch_bounds__(256, DHP == 64 ? 2 : 1) attn_bwd_dkv_bf16_kernel(const AttnK p) {
   constexpr int KC = DHP / 16, DT = DHP / 32;
   constexpr int LD = DHP + 8;
   __shared__ __attribute__((aligned(16))) bf16 Qs[2][64 * LD];
@@ -330,8 +350,10 @@ __global__ void __launch_bounds__(256) attn_bwd_dkv_bf16_kernel(const AttnK p) {
   __shared__ __attribute__((aligned(16))) float lse_s[2][64];
   __shared__ __attribute__((aligned(16))) float dlt_s[2][64];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 5, l32 = lane & 31;
-  const int b = blockIdx.y / p.H, h = blockIdx.y % p.H;
-  const int ki = blockIdx.x * 128 + wave * 32 + l32;
+  int ktile, bh;
+  attn_block_map(blockIdx.x, (p.Nk + 127) / 128, p.B * p.H, ktile, bh);
+  const int b = bh / p.H, h = bh % p.H;
+  const int ki = ktile * 128 + wave * 32 + l32;
   const bool kok = ki < p.Nk;
   const bf16* qb = (const bf16*)p.q + (size_t)b * p.Nq * p.ldq + h * p.dh;
   const bf16* dob = (const bf16*)p.dout + (size_t)b * p.Nq * p.lddo + h * p.dh;
@@ -596,7 +618,7 @@ int launch_attn_fwd(const AttnArgs& a, hipStream_t s) {
   const double by = dtype_size(a.dtype) * (double)a.B * a.H * a.d_head * (2.0 * a.Nq + 2.0 * a.Nk);
   KScope ks(a.dtype == BF16 ? KK_ATTN_FWD : KK_ATTN_F32, fl, by, s, a.Nq, a.Nk, a.d_head);
   if (a.dtype == BF16) {
-    dim3 grid((a.Nq + 127) / 128, a.B * a.H);
+    dim3 grid(((a.Nq + 127) / 128) * a.B * a.H);
     if (a.d_head <= 64) {
       if (a.causal) hipLaunchKernelGGL((attn_fwd_bf16_kernel<64, true>), grid, dim3(256), 0, s, k);
       else hipLaunchKernelGGL((attn_fwd_bf16_kernel<64, false>), grid, dim3(256), 0, s, k);
@@ -617,7 +639,7 @@ int launch_attn_bwd(const AttnArgs& a, hipStream_t s) {
   const dim3 dgrid((pairs * 8 + 255) / 256);
   if (a.dtype == BF16) {
     hipLaunchKernelGGL(attn_delta_kernel<bf16>, dgrid, dim3(256), 0, s, (const bf16*)a.o, a.ldo, (const bf16*)a.dout, a.lddo, a.delta, a.B, a.H, a.Nq, a.d_head);
-    dim3 gq((a.Nq + 127) / 128, a.B * a.H), gk((a.Nk + 127) / 128, a.B * a.H);
+    dim3 gq(((a.Nq + 127) / 128) * a.B * a.H), gk(((a.Nk + 127) / 128) * a.B * a.H);
     // algorithmic backward work = 2x forward, split evenly between the two kernels for accounting
     const double fl = 4.0 * a.B * a.H * (double)a.Nq * a.Nk * a.d_head;
     const double by = 2.0 * (double)a.B * a.H * a.d_head * (3.0 * a.Nq + 2.0 * a.Nk);

@@ -337,28 +337,56 @@ int launch_geglu_bwd(int dtype, const void* dg, const void* u, void* du, int row
 }
 
 // ------------------------------------------------------------------ column sums
-constexpr int CS_ROWS = 256;   // rows per workgroup
-constexpr int CS_COLS = 128;   // columns per workgroup (2 per lane)
+constexpr int CS_ROWS = 64;    // rows per workgroup (16 per wave)
+constexpr int CS_COLS = 128;   // columns per workgroup in the gated-branch kernel (2 per lane)
 
+// Stage 1: partial[chunk][col] = sum of x over the chunk's rows.  A lane owns Vec::N consecutive
+// columns (16-byte loads); the four waves of a workgroup take rows round-robin and are added
+// in a fixed order.
 template <typename T>
 __global__ void __launch_bounds__(256) colsum_kernel(const T* __restrict__ x, int ldx, int rows, int cols, float* __restrict__ partial) {
-  __shared__ float red[4][CS_COLS];
+  constexpr int V = Vec<T>::N;
+  __shared__ float red[4][64 * V];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int col = blockIdx.x * CS_COLS + lane * 2;
+  const int col = (blockIdx.x * 64 + lane) * V;
   const int r0 = blockIdx.y * CS_ROWS, r1 = min(rows, r0 + CS_ROWS);
-  float s0 = 0.f, s1 = 0.f;
+  float s[V];
+#pragma unroll
+  for (int i = 0; i < V; ++i) s[i] = 0.f;
   if (col < cols) {
     for (int r = r0 + wave; r < r1; r += 4) {
-      const T* p = x + (size_t)r * ldx + col;
-      s0 += to_f<T>(p[0]);
-      s1 += to_f<T>(p[1]);
+      float v[V];
+      load_vec<T>(x + (size_t)r * ldx + col, v);
+#pragma unroll
+      for (int i = 0; i < V; ++i) s[i] += v[i];
     }
   }
-  red[wave][lane * 2] = s0; red[wave][lane * 2 + 1] = s1;
+#pragma unroll
+  for (int i = 0; i < V; ++i) red[wave][lane * V + i] = s[i];
   __syncthreads();
-  if (threadIdx.x < CS_COLS) {
-    const int c = blockIdx.x * CS_COLS + threadIdx.x;
-    if (c < cols) partial[(size_t)blockIdx.y * cols + c] = ((red[0][threadIdx.x] + red[1][threadIdx.x]) + red[2][threadIdx.x]) + red[3][threadIdx.x];
+  for (int t = threadIdx.x; t < 64 * V; t += 256) {
+    const int c = blockIdx.x * 64 * V + t;
+    if (c < cols) partial[(size_t)blockIdx.y * cols + c] = ((red[0][t] + red[1][t]) + red[2][t]) + red[3][t];
+  }
+}
+
+// Stage 2: out[c] = (accumulate ? out[c] : 0) + sum_r partial[r][c]; 32 columns x 32 row groups per
+// workgroup, each thread sums its rows in ascending order, the 32 group sums are added in ascending order.
+__global__ void __launch_bounds__(1024) rows_reduce_kernel(const float* __restrict__ partial, int nrows, int ncols,
+                                                           float* __restrict__ out, int accumulate) {
+  __shared__ float red[32][33];
+  const int lc = threadIdx.x & 31, grp = threadIdx.x >> 5;
+  const int col = blockIdx.x * 32 + lc;
+  float s = 0.f;
+  if (col < ncols)
+    for (int r = grp; r < nrows; r += 32) s += partial[(size_t)r * ncols + col];
+  red[grp][lc] = s;
+  __syncthreads();
+  if (grp == 0 && col < ncols) {
+    float t = 0.f;
+#pragma unroll
+    for (int g = 0; g < 32; ++g) t += red[g][lc];
+    out[col] = accumulate ? out[col] + t : t;
   }
 }
 
@@ -366,25 +394,30 @@ size_t colsum_partial_bytes(int rows, int cols) { return (size_t)((rows + CS_ROW
 
 int launch_colsum(int dtype, const void* x, int ldx, int rows, int cols, float* out, int accumulate, float* partial,
                   size_t partial_bytes, hipStream_t s) {
-  if (rows <= 0 || cols <= 0 || cols % 2 || !x || !out) return set_error(DP_EINVAL, "colsum: bad arguments (cols must be even)");
+  const int V = dtype == BF16 ? 8 : 4;
+  if (rows <= 0 || cols <= 0 || cols % V || ldx % V || !x || !out) return set_error(DP_EINVAL, "colsum: bad arguments (cols must be a multiple of 8 (bf16) / 4 (fp32))");
   if (!partial || partial_bytes < colsum_partial_bytes(rows, cols)) return set_error(DP_EWORKSPACE, "colsum: partial buffer too small");
-  dim3 grid((cols + CS_COLS - 1) / CS_COLS, (rows + CS_ROWS - 1) / CS_ROWS);
+  dim3 grid((cols + 64 * V - 1) / (64 * V), (rows + CS_ROWS - 1) / CS_ROWS);
   KScope ks(KK_REDUCE, 0.0, (double)rows * cols * dtype_size(dtype), s, rows, cols);
   if (dtype == BF16) hipLaunchKernelGGL(colsum_kernel<bf16>, grid, dim3(256), 0, s, (const bf16*)x, ldx, rows, cols, partial);
   else hipLaunchKernelGGL(colsum_kernel<float>, grid, dim3(256), 0, s, (const float*)x, ldx, rows, cols, partial);
   if (hipGetLastError() != hipSuccess) return set_error(DP_EHIP, "colsum launch failed");
-  return launch_reduce_partials(partial, grid.y, (size_t)cols, out, accumulate, s);
+  hipLaunchKernelGGL(rows_reduce_kernel, dim3((cols + 31) / 32), dim3(1024), 0, s, partial, (int)grid.y, cols, out, accumulate);
+  return hipGetLastError() == hipSuccess ? DP_OK : set_error(DP_EHIP, "rows_reduce launch failed");
 }
 
-__global__ void reduce_partials_kernel(const float* __restrict__ partial, int nz, size_t n, float* __restrict__ out, int accumulate) {
+// out[i] = (accumulate ? out[i] : 0) + sum_z partial[z * n + i], four elements per thread (n % 4 == 0)
+__global__ void reduce_partials_kernel(const float* __restrict__ partial, int nz, size_t n4, float* __restrict__ out, int accumulate) {
   const size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x;
-  if (i >= n) return;
-  float s = 0.f;
-  for (int z = 0; z < nz; ++z) s += partial[(size_t)z * n + i];
-  out[i] = accumulate ? out[i] + s : s;
+  if (i >= n4) return;
+  f32x4 s = {0.f, 0.f, 0.f, 0.f};
+  for (int z = 0; z < nz; ++z) s += reinterpret_cast<const f32x4*>(partial)[(size_t)z * n4 + i];
+  f32x4* o = reinterpret_cast<f32x4*>(out) + i;
+  *o = accumulate ? *o + s : s;
 }
 int launch_reduce_partials(const float* partial, int nz, size_t n, float* out, int accumulate, hipStream_t s) {
-  hipLaunchKernelGGL(reduce_partials_kernel, dim3((n + 255) / 256), dim3(256), 0, s, partial, nz, n, out, accumulate);
+  if (n % 4) return set_error(DP_EUNSUPPORTED, "reduce_partials: element count must be a multiple of 4");
+  hipLaunchKernelGGL(reduce_partials_kernel, dim3((n / 4 + 255) / 256), dim3(256), 0, s, partial, nz, n / 4, out, accumulate);
   return hipGetLastError() == hipSuccess ? DP_OK : set_error(DP_EHIP, "reduce_partials launch failed");
 }
 

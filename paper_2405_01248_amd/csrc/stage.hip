@@ -321,8 +321,9 @@ static int unet_block_bwd(const dp_stage& s, const void* const* P, void* const* 
 }
 
 // ============================================================ DiT stage
+// save = false (the self-conditioning pass) skips the tensors only the backward reads.
 static int dit_block_fwd(const dp_stage& s, const void* const* P, const float* x, const void* sc_in, void* y, bool y_is_out,
-                         DitBuf& u, hipStream_t st) {
+                         bool save, DitBuf& u, hipStream_t st) {
   const int dt = s.d.dtype, T = s.T, d = s.d.d_model, ff = s.d.ff_inner, B = s.d.batch, N = s.d.tokens;
   const size_t es = s.es;
   DP_TRY(launch_gemm(gemm_fwd(dt, sc_in, B, d, P[D_ADA_W], 6 * d, P[D_ADA_B], u.m), st));
@@ -336,16 +337,16 @@ static int dit_block_fwd(const dp_stage& s, const void* const* P, const float* x
   a.o = u.a; a.ldo = d; a.lse = u.lse;
   DP_TRY(launch_attn_fwd(a, st));
   GemmArgs g = gemm_fwd(dt, u.a, T, d, P[D_WO], d, P[D_BO], u.x1);
-  g.pre_out = u.o; g.ld_pre = d; g.gate = at(u.m, 2 * d, es); g.gate_ld = 6 * d; g.rows_per_batch = N;
+  g.pre_out = save ? u.o : nullptr; g.ld_pre = d; g.gate = at(u.m, 2 * d, es); g.gate_ld = 6 * d; g.rows_per_batch = N;
   g.residual = x; g.ld_res = d; g.residual_f32 = 1; g.out_fused_f32 = 1;
   DP_TRY(launch_gemm(g, st));
   ln.x = u.x1; ln.y = u.h2; ln.shift = at(u.m, 3 * d, es); ln.scale = at(u.m, 4 * d, es); ln.mean = u.mean2; ln.rstd = u.rstd2;
   DP_TRY(launch_ln_fwd(ln, st));
   g = gemm_fwd(dt, u.h2, T, d, P[D_FC1_W], ff, P[D_FC1_B], u.f);
-  g.pre_out = u.f1; g.ld_pre = ff; g.act = s.d.gelu_tanh ? 2 : 1;
+  g.pre_out = save ? u.f1 : nullptr; g.ld_pre = ff; g.act = s.d.gelu_tanh ? 2 : 1;
   DP_TRY(launch_gemm(g, st));
   g = gemm_fwd(dt, u.f, T, ff, P[D_FC2_W], d, P[D_FC2_B], y);
-  g.pre_out = u.f2; g.ld_pre = d; g.gate = at(u.m, 5 * d, es); g.gate_ld = 6 * d; g.rows_per_batch = N;
+  g.pre_out = save ? u.f2 : nullptr; g.ld_pre = d; g.gate = at(u.m, 5 * d, es); g.gate_ld = 6 * d; g.rows_per_batch = N;
   g.residual = u.x1; g.ld_res = d; g.residual_f32 = 1; g.out_fused_f32 = y_is_out ? 0 : 1;
   DP_TRY(launch_gemm(g, st));
   return DP_OK;
@@ -444,7 +445,7 @@ static int run_stage_fwd(dp_stage* s, const void* const* params, const void* x, 
     else out = (b & 1) ? sp.pp1 : sp.pp0;
     const int slot = save ? b : 0;
     if (unet) DP_TRY(unet_block_fwd(*s, P, cur, cc, out, last, sp.ub[slot], st));
-    else DP_TRY(dit_block_fwd(*s, P, cur, sp.sc_in, out, last, sp.db[slot], st));
+    else DP_TRY(dit_block_fwd(*s, P, cur, sp.sc_in, out, last, save != 0, sp.db[slot], st));
     cur = (float*)out;
   }
   DP_TRY(record(ph, nb, st));
