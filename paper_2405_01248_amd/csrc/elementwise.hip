@@ -269,9 +269,13 @@ int launch_ln_bwd(const LnBwdArgs& a, hipStream_t s) {
     if (!a.partial || a.partial_bytes < ln_bwd_partial_bytes(a.rows, a.d, rpb)) return set_error(DP_EWORKSPACE, "ln_bwd: partial buffer too small");
     partial = a.partial;
   }
-  KScope ks(KK_LN_BWD, 0.0, a.rows * (double)a.d * (dtype_size(a.dtype) + 4.0 + (a.dres ? 4.0 : 0.0) + (a.dx ? dtype_size(a.dtype) : 0.0) + (a.dx32 ? 4.0 : 0.0)) + 8.0 * a.rows, s, a.rows, a.d);
-  int e = a.dtype == BF16 ? ln_bwd_t<bf16>(a, rpb, nb, nchunk, partial, s) : ln_bwd_t<float>(a, rpb, nb, nchunk, partial, s);
+  int e;
+  {
+    KScope ks(KK_LN_BWD, 0.0, a.rows * (double)a.d * (dtype_size(a.dtype) + 4.0 + (a.dres ? 4.0 : 0.0) + (a.dx ? dtype_size(a.dtype) : 0.0) + (a.dx32 ? 4.0 : 0.0)) + 8.0 * a.rows, s, a.rows, a.d);
+    e = a.dtype == BF16 ? ln_bwd_t<bf16>(a, rpb, nb, nchunk, partial, s) : ln_bwd_t<float>(a, rpb, nb, nchunk, partial, s);
+  }
   if (e || !want_cols) return e;
+  KScope ks(KK_REDUCE, 0.0, (double)nb * nchunk * 2 * a.d * 4, s, nchunk, 2 * a.d);
   if (modulated)
     hipLaunchKernelGGL(ln_bwd_reduce_kernel, dim3((2 * a.d + 31) / 32, nb), dim3(1024), 0, s, partial, nchunk, a.d, a.dscale, a.dshift, a.dmod_ld, 0);
   else

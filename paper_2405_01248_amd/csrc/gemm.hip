@@ -631,9 +631,17 @@ static int launch_bf16_cfg(const GemmArgs& a, hipStream_t s) {
       return set_error(DP_EHIP, "hipFuncSetAttribute(gemm) failed");
     attr_set = true;
   }
-  hipLaunchKernelGGL(kern, grid, dim3(WGM * WGN * 64), smem, s, p);
+  {
+    // the timing scope brackets the GEMM kernel alone (the split-K reduction is its own class)
+    KScope ks(a.a_mc ? KK_GEMM_TN : (a.b_mc ? KK_GEMM_NN : KK_GEMM_NT), 2.0 * a.M * a.N * a.K,
+              2.0 * ((double)a.M * a.K + (double)a.N * a.K + (double)a.M * a.N), s, a.M, a.N, a.K);
+    hipLaunchKernelGGL(kern, grid, dim3(WGM * WGN * 64), smem, s, p);
+  }
   if (hipGetLastError() != hipSuccess) return set_error(DP_EHIP, "gemm launch failed");
-  if (splits > 1) return launch_reduce_partials(a.splitk_ws, splits, (size_t)a.M * a.N, a.out_f32, a.accumulate, s);
+  if (splits > 1) {
+    KScope ks(KK_REDUCE, 0.0, 4.0 * (splits + 1.0) * a.M * a.N, s, a.M, a.N, splits);
+    return launch_reduce_partials(a.splitk_ws, splits, (size_t)a.M * a.N, a.out_f32, a.accumulate, s);
+  }
   return DP_OK;
 }
 
@@ -666,9 +674,17 @@ static int launch_dtl_cfg(const GemmArgs& a, hipStream_t s) {
       return set_error(DP_EHIP, "hipFuncSetAttribute(gemm) failed");
     attr_set = true;
   }
-  hipLaunchKernelGGL(kern, grid, dim3(WGM * WGN * 64), smem, s, p);
+  {
+    // the timing scope brackets the GEMM kernel alone (the split-K reduction is its own class)
+    KScope ks(a.a_mc ? KK_GEMM_TN : (a.b_mc ? KK_GEMM_NN : KK_GEMM_NT), 2.0 * a.M * a.N * a.K,
+              2.0 * ((double)a.M * a.K + (double)a.N * a.K + (double)a.M * a.N), s, a.M, a.N, a.K);
+    hipLaunchKernelGGL(kern, grid, dim3(WGM * WGN * 64), smem, s, p);
+  }
   if (hipGetLastError() != hipSuccess) return set_error(DP_EHIP, "gemm launch failed");
-  if (splits > 1) return launch_reduce_partials(a.splitk_ws, splits, (size_t)a.M * a.N, a.out_f32, a.accumulate, s);
+  if (splits > 1) {
+    KScope ks(KK_REDUCE, 0.0, 4.0 * (splits + 1.0) * a.M * a.N, s, a.M, a.N, splits);
+    return launch_reduce_partials(a.splitk_ws, splits, (size_t)a.M * a.N, a.out_f32, a.accumulate, s);
+  }
   return DP_OK;
 }
 
@@ -707,8 +723,6 @@ int launch_gemm(const GemmArgs& a, hipStream_t s) {
     const void* eps[] = {a.out, a.out_f32, a.bias, a.pre_out, a.dact_pre, a.gate, a.residual, a.splitk_ws};
     for (const void* x : eps) if ((uintptr_t)x % 16) return set_error(DP_EALIGN, "gemm(bf16): epilogue operands must be 16-byte aligned");
     const int cfg = (a.force_cfg > 0 && a.force_cfg <= kNumCfgs + 4) ? a.force_cfg - 1 : choose_cfg(a.M, a.N, a.K, a.a_mc != 0, a.b_mc != 0);
-    KScope ks(a.a_mc ? KK_GEMM_TN : (a.b_mc ? KK_GEMM_NN : KK_GEMM_NT), 2.0 * a.M * a.N * a.K,
-              2.0 * ((double)a.M * a.K + (double)a.N * a.K + (double)a.M * a.N), s, a.M, a.N, a.K);
     switch (cfg) {
       case 1: return launch_bf16_layout<256, 128, 64, 4, 2>(a, s);
       case 2: return launch_bf16_layout<256, 256, 64, 2, 4>(a, s);
