@@ -60,6 +60,12 @@ struct dp_stage {
   int per_block;
   size_t es;      // element size of the storage dtype
   int T, Tc;      // token rows, context rows
+  // The backward runs the weight-gradient GEMMs and bias-gradient reductions (off the critical
+  // path) on a second stream, forked from and joined to the caller's stream with events.  Created
+  // lazily on the first stage_bwd (host objects only; no device memory).
+  hipStream_t side = nullptr;
+  std::vector<hipEvent_t> events;
+  bool overlap = true;
 };
 
 struct dp_encoder {
@@ -87,8 +93,8 @@ struct DitBuf {
 struct GradPair { float* f; void* h; };
 struct BwdScratch {
   GradPair r[2];
-  void *dh, *da, *dqkv, *dq2, *dkv2, *dg, *du, *dm_t;
-  float *delta, *dm, *dcond_pre, *partial; size_t partial_bytes;
+  void *dh, *da, *dqkv, *dq2, *dkv2, *dg, *dg2, *du, *dm_t;
+  float *delta, *dm, *dcond_pre, *partial, *partial_side; size_t partial_bytes;
 };
 
 static void plan_unet_block(Plan& p, const dp_stage& s, UnetBuf& u, bool with_xin) {
@@ -144,16 +150,18 @@ static void plan_bwd_scratch(Plan& p, const dp_stage& s, BwdScratch& b) {
   b.delta = (float*)p.take((size_t)s.d.batch * s.d.n_heads * s.d.tokens * sizeof(float));
   if (unet) {
     b.dq2 = p.take(T * d * es); b.dkv2 = p.take(Tc * 2 * d * es);
-    b.dg = p.take(T * ff * es); b.du = p.take(T * 2 * ff * es);
+    b.dg = p.take(T * ff * es); b.du = p.take(T * 2 * ff * es); b.dg2 = nullptr;
     b.dm_t = nullptr; b.dm = nullptr; b.dcond_pre = nullptr;
   } else {
     b.dq2 = nullptr; b.dkv2 = nullptr;
-    b.dg = p.take(T * d * es);          // gated-branch gradient (df2 / do)
+    b.dg = p.take(T * d * es);          // gated-branch gradients: df2 ...
+    b.dg2 = p.take(T * d * es);         // ... and do (separate, so the side stream can still read df2)
     b.du = p.take(T * ff * es);         // df1
     b.dm = (float*)p.take(B * 6 * d * 4); b.dm_t = p.take(B * 6 * d * es); b.dcond_pre = (float*)p.take(B * d * 4);
   }
   b.partial_bytes = partial_need(s);
   b.partial = (float*)p.take(b.partial_bytes);
+  b.partial_side = (float*)p.take(b.partial_bytes);   // split-K / column-sum partials of the side stream
 }
 
 struct StagePlan {
@@ -199,12 +207,49 @@ static GemmArgs gemm_dx(int dtype, const void* dy, int M, int N, const void* W, 
 }
 // dW[N,K] (+)= dy[M,N]^T x[M,K]   (fp32)
 static GemmArgs gemm_dw(int dtype, const void* dy, int M, int N, const void* x, int K, float* dW, int accumulate,
-                        const BwdScratch& bs) {
+                        float* partial, size_t partial_bytes) {
   GemmArgs g = gemm_base(dtype);
   g.A = dy; g.B = x; g.M = N; g.N = K; g.K = M; g.lda = N; g.ldb = K; g.a_mc = 1; g.b_mc = 1;
-  g.out_f32 = dW; g.ldo32 = K; g.accumulate = accumulate; g.splitk_ws = bs.partial; g.splitk_ws_bytes = bs.partial_bytes;
+  g.out_f32 = dW; g.ldo32 = K; g.accumulate = accumulate; g.splitk_ws = partial; g.splitk_ws_bytes = partial_bytes;
   return g;
 }
+
+// Fork/join bookkeeping between the caller's stream and the stage's side stream.  A "batch" is a
+// group of launches on the side stream that starts after the main stream's current position
+// (fork) and ends with an event; before the main stream overwrites a buffer that a batch reads,
+// it waits for that batch (the side stream runs in order, so this also covers earlier batches).
+struct Side {
+  hipStream_t main, side;
+  std::vector<hipEvent_t>* ev;
+  size_t next_ev = 0;
+  int issued = 0, waited = 0;
+  std::vector<hipEvent_t> done;
+  bool on;
+  int err = DP_OK;
+
+  hipEvent_t take() { return (*ev)[next_ev++ % ev->size()]; }
+  hipStream_t begin() {                       // returns the stream the batch is launched on
+    if (!on) return main;
+    hipEvent_t e = take();
+    if (hipEventRecord(e, main) != hipSuccess || hipStreamWaitEvent(side, e, 0) != hipSuccess) err = set_error(DP_EHIP, "stream fork failed");
+    return side;
+  }
+  int end() {                                 // returns the batch id
+    if (!on) return 0;
+    hipEvent_t e = take();
+    if (hipEventRecord(e, side) != hipSuccess) err = set_error(DP_EHIP, "hipEventRecord failed");
+    done.push_back(e);
+    return ++issued;
+  }
+  void wait(int batch) {                      // main stream waits for batch (and all before it)
+    if (!on || batch <= waited) return;
+    if (hipStreamWaitEvent(main, done[batch - 1], 0) != hipSuccess) err = set_error(DP_EHIP, "stream join failed");
+    waited = batch;
+  }
+};
+
+// Last side batch that reads each reusable backward buffer.
+struct SideReads { int pair[2] = {0, 0}; int du = 0, dq2 = 0, dqkv = 0, dg = 0, dg2 = 0, dm_t = 0; };
 
 static AttnArgs attn_base(const dp_stage& s) {
   AttnArgs a;
@@ -266,58 +311,98 @@ static int unet_block_fwd(const dp_stage& s, const void* const* P, const float* 
   return DP_OK;
 }
 
-// dy: gradient of the block output (fp32 running sum + storage-dtype copy).  The block's dx goes to
-// `out` (fp32 + storage dtype) or, for the first block of the stage, to dx_final (storage dtype only).
-static int unet_block_bwd(const dp_stage& s, const void* const* P, void* const* G, int acc, const void* ctx, GradPair dy,
-                          GradPair dx2, GradPair dx1, GradPair out, void* dx_final, UnetBuf& u, BwdScratch& b, hipStream_t st) {
+// dy: gradient of the block output (fp32 running sum in pair `c`'s fp32 buffer + a storage-dtype
+// copy).  dx2 goes to pair c ^ 1, dx1 to pair c, the block's dx to pair c ^ 1 again or, for the
+// first block of the stage, to dx_final (storage dtype only).  Weight- and bias-gradient work runs
+// in side-stream batches.
+static int unet_block_bwd(const dp_stage& s, const void* const* P, void* const* G, int acc, const void* ctx, GradPair dy, int c,
+                          void* dx_final, UnetBuf& u, BwdScratch& b, Side& sd, SideReads& rd) {
   const int dt = s.d.dtype, T = s.T, Tc = s.Tc, d = s.d.d_model, inner = s.d.ff_inner, dc = s.d.ctx_dim;
   const size_t es = s.es;
+  hipStream_t st = sd.main;
+  const GradPair dx2 = b.r[c ^ 1], dx1 = b.r[c], out = b.r[c ^ 1];
   auto gf = [&](int i) { return (float*)G[i]; };
   auto set_dx = [&](LnBwdArgs& lb, GradPair t) { lb.dx32 = t.f; lb.dx = (es == 4) ? nullptr : t.h; };
+  auto dw = [&](const void* gy, int M, int N, const void* x, int K, int pidx, hipStream_t q) {
+    return launch_gemm(gemm_dw(dt, gy, M, N, x, K, gf(pidx), acc, b.partial_side, b.partial_bytes), q);
+  };
+  auto db = [&](const void* gy, int cols, int rows, int pidx, hipStream_t q) {
+    return launch_colsum(dt, gy, cols, rows, cols, gf(pidx), acc, b.partial_side, b.partial_bytes, q);
+  };
   // ---- feed-forward
+  {
+    hipStream_t q = sd.begin();
+    DP_TRY(dw(dy.h, T, d, u.g, inner, U_W2, q));
+    DP_TRY(db(dy.h, d, T, U_B2, q));
+    rd.pair[c] = sd.end();
+  }
   DP_TRY(launch_gemm(gemm_dx(dt, dy.h, T, d, P[U_W2], inner, b.dg), st));
-  DP_TRY(launch_gemm(gemm_dw(dt, dy.h, T, d, u.g, inner, gf(U_W2), acc, b), st));
-  DP_TRY(launch_colsum(dt, dy.h, d, T, d, gf(U_B2), acc, b.partial, b.partial_bytes, st));
+  sd.wait(rd.du);
   DP_TRY(launch_geglu_bwd(dt, b.dg, u.u, b.du, T, inner, st));
+  {
+    hipStream_t q = sd.begin();
+    DP_TRY(dw(b.du, T, 2 * inner, u.h3, d, U_W1, q));
+    DP_TRY(db(b.du, 2 * inner, T, U_B1, q));
+    rd.du = sd.end();
+  }
   DP_TRY(launch_gemm(gemm_dx(dt, b.du, T, 2 * inner, P[U_W1], d, b.dh), st));
-  DP_TRY(launch_gemm(gemm_dw(dt, b.du, T, 2 * inner, u.h3, d, gf(U_W1), acc, b), st));
-  DP_TRY(launch_colsum(dt, b.du, 2 * inner, T, 2 * inner, gf(U_B1), acc, b.partial, b.partial_bytes, st));
   LnBwdArgs lb; memset(&lb, 0, sizeof(lb));
   lb.dtype = dt; lb.rows = T; lb.d = d; lb.accumulate = acc; lb.partial = b.partial; lb.partial_bytes = b.partial_bytes;
   lb.dy = b.dh; lb.x = u.x2; lb.mean = u.mean3; lb.rstd = u.rstd3; lb.gamma = P[U_LN3_G]; lb.dres = dy.f; set_dx(lb, dx2);
   lb.dgamma = gf(U_LN3_G); lb.dbeta = gf(U_LN3_B);
+  sd.wait(rd.pair[c ^ 1]);
   DP_TRY(launch_ln_bwd(lb, st));
   // ---- cross-attention
+  {
+    hipStream_t q = sd.begin();
+    DP_TRY(dw(dx2.h, T, d, u.a2, d, U_WO2, q));
+    DP_TRY(db(dx2.h, d, T, U_BO2, q));
+    rd.pair[c ^ 1] = sd.end();
+  }
   DP_TRY(launch_gemm(gemm_dx(dt, dx2.h, T, d, P[U_WO2], d, b.da), st));
-  DP_TRY(launch_gemm(gemm_dw(dt, dx2.h, T, d, u.a2, d, gf(U_WO2), acc, b), st));
-  DP_TRY(launch_colsum(dt, dx2.h, d, T, d, gf(U_BO2), acc, b.partial, b.partial_bytes, st));
   AttnArgs a = attn_base(s);
   a.Nk = s.d.ctx_tokens; a.q = u.q2; a.ldq = d; a.k = u.kv2; a.v = at(u.kv2, d, es); a.ldk = a.ldv = 2 * d;
   a.o = u.a2; a.ldo = d; a.lse = u.lse2; a.dout = b.da; a.lddo = d; a.delta = b.delta;
   a.dq = b.dq2; a.lddq = d; a.dk = b.dkv2; a.dv = at(b.dkv2, d, es); a.lddk = a.lddv = 2 * d;
+  sd.wait(rd.dq2);
   DP_TRY(launch_attn_bwd(a, st));
+  {
+    hipStream_t q = sd.begin();
+    DP_TRY(dw(b.dq2, T, d, u.h2, d, U_WQ2, q));
+    DP_TRY(dw(b.dkv2, Tc, 2 * d, ctx, dc, U_WKV2, q));
+    rd.dq2 = sd.end();
+  }
   DP_TRY(launch_gemm(gemm_dx(dt, b.dq2, T, d, P[U_WQ2], d, b.dh), st));
-  DP_TRY(launch_gemm(gemm_dw(dt, b.dq2, T, d, u.h2, d, gf(U_WQ2), acc, b), st));
-  DP_TRY(launch_gemm(gemm_dw(dt, b.dkv2, Tc, 2 * d, ctx, dc, gf(U_WKV2), acc, b), st));
   lb.dy = b.dh; lb.x = u.x1; lb.mean = u.mean2; lb.rstd = u.rstd2; lb.gamma = P[U_LN2_G]; lb.dres = dx2.f; set_dx(lb, dx1);
   lb.dgamma = gf(U_LN2_G); lb.dbeta = gf(U_LN2_B);
+  sd.wait(rd.pair[c]);
   DP_TRY(launch_ln_bwd(lb, st));
   // ---- self-attention
+  {
+    hipStream_t q = sd.begin();
+    DP_TRY(dw(dx1.h, T, d, u.a1, d, U_WO1, q));
+    DP_TRY(db(dx1.h, d, T, U_BO1, q));
+    rd.pair[c] = sd.end();
+  }
   DP_TRY(launch_gemm(gemm_dx(dt, dx1.h, T, d, P[U_WO1], d, b.da), st));
-  DP_TRY(launch_gemm(gemm_dw(dt, dx1.h, T, d, u.a1, d, gf(U_WO1), acc, b), st));
-  DP_TRY(launch_colsum(dt, dx1.h, d, T, d, gf(U_BO1), acc, b.partial, b.partial_bytes, st));
   a = attn_base(s);
   a.Nk = s.d.tokens; a.q = u.qkv; a.k = at(u.qkv, d, es); a.v = at(u.qkv, 2 * d, es); a.ldq = a.ldk = a.ldv = 3 * d;
   a.o = u.a1; a.ldo = d; a.lse = u.lse1; a.dout = b.da; a.lddo = d; a.delta = b.delta;
   a.dq = b.dqkv; a.dk = at(b.dqkv, d, es); a.dv = at(b.dqkv, 2 * d, es); a.lddq = a.lddk = a.lddv = 3 * d;
+  sd.wait(rd.dqkv);
   DP_TRY(launch_attn_bwd(a, st));
+  {
+    hipStream_t q = sd.begin();
+    DP_TRY(dw(b.dqkv, T, 3 * d, u.h1, d, U_WQKV, q));
+    rd.dqkv = sd.end();
+  }
   DP_TRY(launch_gemm(gemm_dx(dt, b.dqkv, T, 3 * d, P[U_WQKV], d, b.dh), st));
-  DP_TRY(launch_gemm(gemm_dw(dt, b.dqkv, T, 3 * d, u.h1, d, gf(U_WQKV), acc, b), st));
   lb.dy = b.dh; lb.x = u.xin; lb.mean = u.mean1; lb.rstd = u.rstd1; lb.gamma = P[U_LN1_G]; lb.dres = dx1.f;
   if (dx_final) { lb.dx = dx_final; lb.dx32 = nullptr; } else set_dx(lb, out);
   lb.dgamma = gf(U_LN1_G); lb.dbeta = gf(U_LN1_B);
+  sd.wait(rd.pair[c ^ 1]);
   DP_TRY(launch_ln_bwd(lb, st));
-  return DP_OK;
+  return sd.err;
 }
 
 // ============================================================ DiT stage
@@ -352,23 +437,42 @@ static int dit_block_fwd(const dp_stage& s, const void* const* P, const float* x
   return DP_OK;
 }
 
+// dy lives in pair c; dx1 goes to pair c ^ 1 and the block's dx back to pair c (or dx_final).
 static int dit_block_bwd(const dp_stage& s, const void* const* P, void* const* G, int acc, const void* cond, const void* sc_in,
-                         GradPair dy, GradPair dx1, GradPair out, void* dx_final, float* d_cond, int dcond_acc, DitBuf& u,
-                         BwdScratch& b, hipStream_t st) {
+                         GradPair dy, int c, void* dx_final, float* d_cond, int dcond_acc, DitBuf& u, BwdScratch& b, Side& sd,
+                         SideReads& rd) {
   const int dt = s.d.dtype, T = s.T, d = s.d.d_model, ff = s.d.ff_inner, B = s.d.batch, N = s.d.tokens;
   const size_t es = s.es;
+  hipStream_t st = sd.main;
+  const GradPair dx1 = b.r[c ^ 1], out = b.r[c];
   auto gf = [&](int i) { return (float*)G[i]; };
   auto set_dx = [&](LnBwdArgs& lb, GradPair t) { lb.dx32 = t.f; lb.dx = (es == 4) ? nullptr : t.h; };
+  auto dw = [&](const void* gy, int M, int Nn, const void* x, int K, int pidx, hipStream_t q) {
+    return launch_gemm(gemm_dw(dt, gy, M, Nn, x, K, gf(pidx), acc, b.partial_side, b.partial_bytes), q);
+  };
+  auto db = [&](const void* gy, int cols, int rows, int pidx, hipStream_t q) {
+    return launch_colsum(dt, gy, cols, rows, cols, gf(pidx), acc, b.partial_side, b.partial_bytes, q);
+  };
   // ---- MLP branch
+  sd.wait(rd.dg);
   DP_TRY(launch_gate_bwd(dt, dy.f, u.f2, at(u.m, 5 * d, es), 6 * d, b.dg, b.dm + 5 * d, 6 * d, B, N, d, st));
+  {
+    hipStream_t q = sd.begin();
+    DP_TRY(dw(b.dg, T, d, u.f, ff, D_FC2_W, q));
+    DP_TRY(db(b.dg, d, T, D_FC2_B, q));
+    rd.dg = sd.end();
+  }
   GemmArgs g = gemm_dx(dt, b.dg, T, d, P[D_FC2_W], ff, b.du);
   g.dact_pre = u.f1; g.ld_dact = ff; g.dact_kind = s.d.gelu_tanh ? 2 : 1;
+  sd.wait(rd.du);
   DP_TRY(launch_gemm(g, st));
-  DP_TRY(launch_gemm(gemm_dw(dt, b.dg, T, d, u.f, ff, gf(D_FC2_W), acc, b), st));
-  DP_TRY(launch_colsum(dt, b.dg, d, T, d, gf(D_FC2_B), acc, b.partial, b.partial_bytes, st));
+  {
+    hipStream_t q = sd.begin();
+    DP_TRY(dw(b.du, T, ff, u.h2, d, D_FC1_W, q));
+    DP_TRY(db(b.du, ff, T, D_FC1_B, q));
+    rd.du = sd.end();
+  }
   DP_TRY(launch_gemm(gemm_dx(dt, b.du, T, ff, P[D_FC1_W], d, b.dh), st));
-  DP_TRY(launch_gemm(gemm_dw(dt, b.du, T, ff, u.h2, d, gf(D_FC1_W), acc, b), st));
-  DP_TRY(launch_colsum(dt, b.du, ff, T, ff, gf(D_FC1_B), acc, b.partial, b.partial_bytes, st));
   LnBwdArgs lb; memset(&lb, 0, sizeof(lb));
   lb.dtype = dt; lb.rows = T; lb.d = d; lb.partial = b.partial; lb.partial_bytes = b.partial_bytes;
   lb.mod_ld = 6 * d; lb.rows_per_batch = N; lb.dmod_ld = 6 * d;
@@ -376,32 +480,47 @@ static int dit_block_bwd(const dp_stage& s, const void* const* P, void* const* G
   lb.dscale = b.dm + 4 * d; lb.dshift = b.dm + 3 * d;
   DP_TRY(launch_ln_bwd(lb, st));
   // ---- attention branch
-  DP_TRY(launch_gate_bwd(dt, dx1.f, u.o, at(u.m, 2 * d, es), 6 * d, b.dg, b.dm + 2 * d, 6 * d, B, N, d, st));
-  DP_TRY(launch_gemm(gemm_dx(dt, b.dg, T, d, P[D_WO], d, b.da), st));
-  DP_TRY(launch_gemm(gemm_dw(dt, b.dg, T, d, u.a, d, gf(D_WO), acc, b), st));
-  DP_TRY(launch_colsum(dt, b.dg, d, T, d, gf(D_BO), acc, b.partial, b.partial_bytes, st));
+  sd.wait(rd.dg2);
+  DP_TRY(launch_gate_bwd(dt, dx1.f, u.o, at(u.m, 2 * d, es), 6 * d, b.dg2, b.dm + 2 * d, 6 * d, B, N, d, st));
+  {
+    hipStream_t q = sd.begin();
+    DP_TRY(dw(b.dg2, T, d, u.a, d, D_WO, q));
+    DP_TRY(db(b.dg2, d, T, D_BO, q));
+    rd.dg2 = sd.end();
+  }
+  DP_TRY(launch_gemm(gemm_dx(dt, b.dg2, T, d, P[D_WO], d, b.da), st));
   AttnArgs a = attn_base(s);
   a.Nk = N; a.q = u.qkv; a.k = at(u.qkv, d, es); a.v = at(u.qkv, 2 * d, es); a.ldq = a.ldk = a.ldv = 3 * d;
   a.o = u.a; a.ldo = d; a.lse = u.lse; a.dout = b.da; a.lddo = d; a.delta = b.delta;
   a.dq = b.dqkv; a.dk = at(b.dqkv, d, es); a.dv = at(b.dqkv, 2 * d, es); a.lddq = a.lddk = a.lddv = 3 * d;
+  sd.wait(rd.dqkv);
   DP_TRY(launch_attn_bwd(a, st));
+  {
+    hipStream_t q = sd.begin();
+    DP_TRY(dw(b.dqkv, T, 3 * d, u.h1, d, D_WQKV, q));
+    DP_TRY(db(b.dqkv, 3 * d, T, D_BQKV, q));
+    rd.dqkv = sd.end();
+  }
   DP_TRY(launch_gemm(gemm_dx(dt, b.dqkv, T, 3 * d, P[D_WQKV], d, b.dh), st));
-  DP_TRY(launch_gemm(gemm_dw(dt, b.dqkv, T, 3 * d, u.h1, d, gf(D_WQKV), acc, b), st));
-  DP_TRY(launch_colsum(dt, b.dqkv, 3 * d, T, 3 * d, gf(D_BQKV), acc, b.partial, b.partial_bytes, st));
   lb.dy = b.dh; lb.x = u.xin; lb.mean = u.mean1; lb.rstd = u.rstd1; lb.scale = at(u.m, d, es); lb.dres = dx1.f;
   if (dx_final) { lb.dx = dx_final; lb.dx32 = nullptr; } else set_dx(lb, out);
   lb.dscale = b.dm + d; lb.dshift = b.dm;
   DP_TRY(launch_ln_bwd(lb, st));
   // ---- conditioning path: m = SiLU(cond) W_ada^T + b_ada
+  sd.wait(rd.dm_t);
   DP_TRY(launch_cast_from_f32(dt, b.dm, b.dm_t, (size_t)B * 6 * d, st));
-  DP_TRY(launch_gemm(gemm_dw(dt, b.dm_t, B, 6 * d, sc_in, d, gf(D_ADA_W), acc, b), st));
-  DP_TRY(launch_colsum(dt, b.dm_t, 6 * d, B, 6 * d, gf(D_ADA_B), acc, b.partial, b.partial_bytes, st));
+  {
+    hipStream_t q = sd.begin();
+    DP_TRY(dw(b.dm_t, B, 6 * d, sc_in, d, D_ADA_W, q));
+    DP_TRY(db(b.dm_t, 6 * d, B, D_ADA_B, q));
+    rd.dm_t = sd.end();
+  }
   g = gemm_base(dt);
   g.A = b.dm_t; g.B = P[D_ADA_W]; g.M = B; g.N = d; g.K = 6 * d; g.lda = 6 * d; g.ldb = d; g.b_mc = 1;
   g.out_f32 = b.dcond_pre; g.ldo32 = d; g.accumulate = 0; g.splitk_ws = b.partial; g.splitk_ws_bytes = b.partial_bytes;
   DP_TRY(launch_gemm(g, st));
   DP_TRY(launch_silu_bwd(dt, b.dcond_pre, cond, d_cond, dcond_acc, (size_t)B * d, st));
-  return DP_OK;
+  return sd.err;
 }
 
 // ============================================================ stage drivers
@@ -452,6 +571,15 @@ static int run_stage_fwd(dp_stage* s, const void* const* params, const void* x, 
   return DP_OK;
 }
 
+static int ensure_side_stream(dp_stage* s) {
+  if (s->side) return DP_OK;
+  if (hipStreamCreateWithFlags(&s->side, hipStreamNonBlocking) != hipSuccess) { s->side = nullptr; return set_error(DP_EHIP, "hipStreamCreate failed"); }
+  s->events.resize((size_t)s->d.n_blocks * 16 + 8);
+  for (auto& e : s->events)
+    if (hipEventCreateWithFlags(&e, hipEventDisableTiming) != hipSuccess) return set_error(DP_EHIP, "hipEventCreate failed");
+  return DP_OK;
+}
+
 static int run_stage_bwd(dp_stage* s, const void* const* params, const void* dy, const void* cc, void* dx, void* d_cond,
                          void* const* dparams, int acc, void* ws, hipStream_t st, ProfileHooks* ph) {
   StagePlan sp;
@@ -459,6 +587,13 @@ static int run_stage_bwd(dp_stage* s, const void* const* params, const void* dy,
   const bool unet = s->d.kind == DP_BLOCK_UNET_XATTN_GEGLU;
   const int nb = s->d.n_blocks;
   BwdScratch& bs = sp.bs;
+  Side sd;
+  sd.main = st; sd.on = s->overlap;
+  if (sd.on) {
+    DP_TRY(ensure_side_stream(s));
+    sd.side = s->side; sd.ev = &s->events;
+  }
+  SideReads rd;
   // dy as a gradient pair: fp32 copy in pair 1's fp32 buffer, the caller's tensor as the GEMM operand
   DP_TRY(launch_cast_to_f32(s->d.dtype, dy, bs.r[1].f, (size_t)s->T * s->d.d_model, st));
   GradPair cur{bs.r[1].f, const_cast<void*>(dy)};
@@ -469,18 +604,18 @@ static int run_stage_bwd(dp_stage* s, const void* const* params, const void* dy,
     void* const* G = dparams + (size_t)b * s->per_block;
     void* dx_final = b == 0 ? dx : nullptr;
     if (unet) {
-      // dx2 -> other pair, dx1 -> cur's pair (cur is dead by then), block dx -> other pair again
-      DP_TRY(unet_block_bwd(*s, P, G, acc, cc, cur, bs.r[ci ^ 1], bs.r[ci], bs.r[ci ^ 1], dx_final, sp.ub[b], bs, st));
-      cur = bs.r[ci ^ 1]; ci ^= 1;
+      DP_TRY(unet_block_bwd(*s, P, G, acc, cc, cur, ci, dx_final, sp.ub[b], bs, sd, rd));
+      ci ^= 1;
+      cur = bs.r[ci];
     } else {
-      // dx1 -> other pair, block dx -> cur's pair
-      DP_TRY(dit_block_bwd(*s, P, G, acc, cc, sp.sc_in, cur, bs.r[ci ^ 1], bs.r[ci], dx_final, (float*)d_cond, b != nb - 1,
-                           sp.db[b], bs, st));
+      DP_TRY(dit_block_bwd(*s, P, G, acc, cc, sp.sc_in, cur, ci, dx_final, (float*)d_cond, b != nb - 1, sp.db[b], bs, sd, rd));
       cur = bs.r[ci];
     }
+    if (ph && ph->ev) sd.wait(sd.issued);      // per-block timing: charge a block's side work to that block
   }
+  sd.wait(sd.issued);                          // join: everything is ordered before later work on the caller's stream
   DP_TRY(record(ph, nb, st));
-  return DP_OK;
+  return sd.err;
 }
 
 // ============================================================ encoder
@@ -638,7 +773,12 @@ int dp_stage_create(const dp_stage_desc* desc, dp_stage** out) {
   return DP_OK;
 }
 
-void dp_stage_destroy(dp_stage* st) { delete st; }
+void dp_stage_destroy(dp_stage* st) {
+  if (!st) return;
+  for (auto& e : st->events) (void)hipEventDestroy(e);
+  if (st->side) (void)hipStreamDestroy(st->side);
+  delete st;
+}
 
 int dp_stage_param_count(const dp_stage* st) { return st ? (int)st->params.size() : set_error(DP_EINVAL, "stage handle is NULL"); }
 
