@@ -121,6 +121,8 @@ def kernel_roofline(workload, names, si, DeviceStage, DeviceEncoder, passes=3):
         run = lambda: obj.run_slices(si.CONFIG5.global_batch)
     else:
         obj = DeviceStage(names[workload], si.make_stage_inputs(names[workload], seed=0))
+        # single-kernel durations: issue the backward's side-stream work in program order
+        obj.stage.set_overlap(False)
         run = obj.step
     run()
     torch.cuda.synchronize()
@@ -151,6 +153,7 @@ def kernel_roofline(workload, names, si, DeviceStage, DeviceEncoder, passes=3):
         ach = a["bytes"] / (a["ms"] * 1e-3) / 1e9
         roof = {"bound": "hbm", "achieved": ach, "peak": HBM_PEAK / 1e9, "unit": "GB/s", "frac": ach / (HBM_PEAK / 1e9)}
     roof.update(traffic=PMC_TRAFFIC_BYTES.get((workload, dom)), kernel=KERNEL_NAMES.get(dom, dom),
+                note="durations from a pass with the backward's side stream disabled (kernels run one at a time)",
                 avg_launch_us=1e3 * a["ms"] / a["launches"], launches_per_step=a["launches"] / passes,
                 algorithmic_per_launch=(a["flops"] if dom in MFMA_KINDS else a["bytes"]) / a["launches"])
     del obj
@@ -165,6 +168,9 @@ def main():
     ap.add_argument("--workload", default="cfg2", choices=["cfg2", "cfg3", "cfg4", "cfg5"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-others", action="store_true", help="skip the short runs of the other workloads")
+    ap.add_argument("--serial", action="store_true",
+                    help="issue the backward's weight-gradient kernels in program order instead of on the side stream "
+                         "(per-kernel profiling; the default overlaps them)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives are part of it); use --gpus 1", file=sys.stderr)
@@ -181,6 +187,8 @@ def main():
 
     def run_stage(cfg, steps, warmup):
         ds = DeviceStage(cfg, si.make_stage_inputs(cfg, seed=0))
+        if args.serial:
+            ds.stage.set_overlap(False)
         sec = timed(ds.step, steps, warmup)
         fl = stage_flops(cfg)
         return ds, {"samples_per_s": cfg.batch / sec, "ms_per_step": sec * 1e3, "tflops": fl / sec / 1e12,

@@ -18,6 +18,7 @@
 #include "dp_errors.h"
 #include "dp_ktime.h"
 #include <math.h>
+#include <algorithm>
 
 namespace dp {
 
@@ -35,6 +36,7 @@ struct AttnK {
   void* dq; int lddq;
   void* dk; int lddk;
   void* dv; int lddv;
+  int qsplits; float* dkv_partial;   // dK/dV kernel: query range split + fp32 partial outputs [2][qsplits][B * Nk][H * dh]
 };
 
 constexpr float LOG2E = 1.4426950408889634f;
@@ -89,34 +91,46 @@ __device__ __forceinline__ void attn_block_map(int id, int ntiles, int BH, int& 
 }
 
 // ------------------------------------------------------------------ forward (bf16)
-template <int DHP, bool CAUSAL>
-__global__ void __launch_bounds__(256) attn_fwd_bf16_kernel(const AttnK p) {
-  constexpr int KC = DHP / 16, DT = DHP / 32;
+// A wave owns QT tiles of 32 queries; every K / V fragment fetched from LDS is used for all of
+// them (QT = 2 halves the LDS traffic per FLOP, and the MFMAs of one query tile can overlap the
+// softmax arithmetic of the other).  A workgroup covers 128 * QT queries.
+template <int DHP, bool CAUSAL, int QT>
+__global__ void __launch_bounds__(256, (QT == 1 && DHP == 64) ? 3 : 2) attn_fwd_bf16_kernel(const AttnK p) {
+  constexpr int KC = DHP / 16, DT = DHP / 32, BQ = 128 * QT;
   constexpr int K_LD = DHP + 8, V_LD = DHP + 16;
   __shared__ __attribute__((aligned(16))) bf16 Ks[2][64 * K_LD];
   __shared__ __attribute__((aligned(16))) bf16 Vs[2][64 * V_LD];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 5, l32 = lane & 31;
   int qtile, bh;
-  attn_block_map(blockIdx.x, (p.Nq + 127) / 128, p.B * p.H, qtile, bh);
+  attn_block_map(blockIdx.x, (p.Nq + BQ - 1) / BQ, p.B * p.H, qtile, bh);
   const int b = bh / p.H, h = bh % p.H;
-  const int qi = qtile * 128 + wave * 32 + l32;
+  const int q0 = qtile * BQ + wave * 32 * QT;          // first query of this wave
   const bf16* qb = (const bf16*)p.q + (size_t)b * p.Nq * p.ldq + h * p.dh;
   const bf16* kb = (const bf16*)p.k + (size_t)b * p.Nk * p.ldk + h * p.dh;
   const bf16* vb = (const bf16*)p.v + (size_t)b * p.Nk * p.ldv + h * p.dh;
 
-  bf16x8 qf[KC];
+  bf16x8 qf[QT][KC];
 #pragma unroll
-  for (int c = 0; c < KC; ++c) qf[c] = ld8(qb + (size_t)qi * p.ldq + 16 * c + 8 * g, qi < p.Nq && 16 * c + 8 * g < p.dh);
+  for (int j = 0; j < QT; ++j)
+#pragma unroll
+    for (int c = 0; c < KC; ++c) {
+      const int qi = q0 + 32 * j + l32;
+      qf[j][c] = ld8(qb + (size_t)qi * p.ldq + 16 * c + 8 * g, qi < p.Nq && 16 * c + 8 * g < p.dh);
+    }
 
-  f32x16 oacc[DT];
+  f32x16 oacc[QT][DT];
+  float m[QT], lsum[QT];
 #pragma unroll
-  for (int i = 0; i < DT; ++i)
+  for (int j = 0; j < QT; ++j) {
+    m[j] = -INFINITY; lsum[j] = 0.f;
 #pragma unroll
-    for (int r = 0; r < 16; ++r) oacc[i][r] = 0.f;
-  float m = -INFINITY, lsum = 0.f;
+    for (int i = 0; i < DT; ++i)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) oacc[j][i][r] = 0.f;
+  }
 
   int nkt = (p.Nk + 63) / 64;
-  if (CAUSAL) nkt = min(nkt, (min(p.Nq, qtile * 128 + 128) + 63) / 64);
+  if (CAUSAL) nkt = min(nkt, (min(p.Nq, qtile * BQ + BQ) + 63) / 64);
 
   TileLoader<DHP, 256> lk, lv;
   lk.load(kb, p.ldk, 0, p.Nk, p.dh, tid);
@@ -132,60 +146,79 @@ __global__ void __launch_bounds__(256) attn_fwd_bf16_kernel(const AttnK p) {
       lk.load(kb, p.ldk, (kt + 1) * 64, p.Nk, p.dh, tid);
       lv.load(vb, p.ldv, (kt + 1) * 64, p.Nk, p.dh, tid);
     }
-    f32x16 s[2];
+    // S^T = K Q^T for the wave's QT query tiles: K fragments are fetched once
+    f32x16 s[QT][2];
 #pragma unroll
-    for (int t = 0; t < 2; ++t) {
+    for (int j = 0; j < QT; ++j)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) s[t][r] = 0.f;
+      for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) s[j][t][r] = 0.f;
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
 #pragma unroll
       for (int c = 0; c < KC; ++c) {
-        bf16x8 a = *reinterpret_cast<const bf16x8*>(&Ks[buf][(32 * t + l32) * K_LD + 16 * c + 8 * g]);
-        s[t] = mfma32(a, qf[c], s[t]);
+        const bf16x8 a = *reinterpret_cast<const bf16x8*>(&Ks[buf][(32 * t + l32) * K_LD + 16 * c + 8 * g]);
+#pragma unroll
+        for (int j = 0; j < QT; ++j) s[j][t] = mfma32(a, qf[j][c], s[j][t]);
       }
-    }
-    // online softmax over this lane's query column (shared with lane ^ 32)
-    float mx = m;
-    const bool edge = (kt * 64 + 64 > p.Nk) || (CAUSAL && kt * 64 + 63 > qtile * 128 + wave * 32);
+    // online softmax, one query column per lane (shared with lane ^ 32)
+    const bool key_edge = kt * 64 + 64 > p.Nk;
 #pragma unroll
-    for (int t = 0; t < 2; ++t)
+    for (int j = 0; j < QT; ++j) {
+      const int qi = q0 + 32 * j + l32;
+      const bool edge = key_edge || (CAUSAL && kt * 64 + 63 > q0 + 32 * j);
+      // running maximum over raw scores (the scale is positive, so it commutes with max)
+      float mx = -INFINITY;
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        float v = s[t][r] * p.scale_log2;
-        if (edge) {
-          const int key = kt * 64 + 32 * t + acc_row(r, g);
-          if (key >= p.Nk || (CAUSAL && key > qi)) v = -INFINITY;
+      for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          float v = s[j][t][r];
+          if (edge) {
+            const int key = kt * 64 + 32 * t + acc_row(r, g);
+            if (key >= p.Nk || (CAUSAL && key > qi)) v = -INFINITY;
+            s[j][t][r] = v;
+          }
+          mx = fmaxf(mx, v);
         }
-        s[t][r] = v;
-        mx = fmaxf(mx, v);
+      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+      mx = fmaxf(m[j], mx * p.scale_log2);                 // m[j] is kept in the scaled (log2) domain
+      const float mref = (mx == -INFINITY) ? 0.f : mx;
+      float rs = 0.f;
+#pragma unroll
+      for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const float e = __builtin_amdgcn_exp2f(fmaf(s[j][t][r], p.scale_log2, -mref));
+          s[j][t][r] = e;
+          rs += e;
+        }
+      rs += __shfl_xor(rs, 32, 64);
+      if (__any(mx != m[j])) {                              // wave-uniform: skip the rescale once the maxima settle
+        const float alpha = __builtin_amdgcn_exp2f(m[j] - mref);
+        lsum[j] *= alpha;
+#pragma unroll
+        for (int i = 0; i < DT; ++i)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) oacc[j][i][r] *= alpha;
       }
-    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-    const float mref = (mx == -INFINITY) ? 0.f : mx;
-    const float alpha = exp2f(m - mref);
-    float rs = 0.f;
-#pragma unroll
-    for (int t = 0; t < 2; ++t)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const float e = exp2f(s[t][r] - mref);
-        s[t][r] = e;
-        rs += e;
-      }
-    rs += __shfl_xor(rs, 32, 64);
-    lsum = lsum * alpha + rs;
-    m = mx;
-#pragma unroll
-    for (int i = 0; i < DT; ++i)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) oacc[i][r] *= alpha;
+      lsum[j] += rs;
+      m[j] = mx;
+    }
+    // O^T += V^T P^T: V fragments are fetched once for all query tiles
 #pragma unroll
     for (int t = 0; t < 2; ++t)
 #pragma unroll
       for (int cc = 0; cc < 2; ++cc) {
-        const bf16x8 pf = pack8(s[t], 8 * cc);
+        bf16x8 pf[QT];
+#pragma unroll
+        for (int j = 0; j < QT; ++j) pf[j] = pack8(s[j][t], 8 * cc);
 #pragma unroll
         for (int i = 0; i < DT; ++i) {
-          bf16x8 a = frag_from_mc_accorder(&Vs[buf][(32 * t + 16 * cc) * V_LD + 32 * i], V_LD, lane);
-          oacc[i] = mfma32(a, pf, oacc[i]);
+          const bf16x8 a = frag_from_mc_accorder(&Vs[buf][(32 * t + 16 * cc) * V_LD + 32 * i], V_LD, lane);
+#pragma unroll
+          for (int j = 0; j < QT; ++j) oacc[j][i] = mfma32(a, pf[j], oacc[j][i]);
         }
       }
     if (more) {
@@ -195,22 +228,26 @@ __global__ void __launch_bounds__(256) attn_fwd_bf16_kernel(const AttnK p) {
     __syncthreads();
   }
 
-  if (qi < p.Nq) {
-    const float inv = lsum > 0.f ? 1.0f / lsum : 0.f;
-    bf16* ob = (bf16*)p.o + ((size_t)b * p.Nq + qi) * p.ldo + h * p.dh;
 #pragma unroll
-    for (int i = 0; i < DT; ++i)
+  for (int j = 0; j < QT; ++j) {
+    const int qi = q0 + 32 * j + l32;
+    if (qi < p.Nq) {
+      const float inv = lsum[j] > 0.f ? 1.0f / lsum[j] : 0.f;
+      bf16* ob = (bf16*)p.o + ((size_t)b * p.Nq + qi) * p.ldo + h * p.dh;
 #pragma unroll
-      for (int r4 = 0; r4 < 4; ++r4) {
-        const int col = 32 * i + 8 * r4 + 4 * g;
-        if (col < p.dh) {
-          bf16x4 o;
+      for (int i = 0; i < DT; ++i)
 #pragma unroll
-          for (int u = 0; u < 4; ++u) o[u] = (bf16)(oacc[i][4 * r4 + u] * inv);
-          *reinterpret_cast<bf16x4*>(ob + col) = o;
+        for (int r4 = 0; r4 < 4; ++r4) {
+          const int col = 32 * i + 8 * r4 + 4 * g;
+          if (col < p.dh) {
+            bf16x4 o;
+#pragma unroll
+            for (int u = 0; u < 4; ++u) o[u] = (bf16)(oacc[j][i][4 * r4 + u] * inv);
+            *reinterpret_cast<bf16x4*>(ob + col) = o;
+          }
         }
-      }
-    if (p.lse && g == 0) p.lse[((size_t)b * p.H + h) * p.Nq + qi] = m * LN2 + logf(lsum);
+      if (p.lse && g == 0) p.lse[((size_t)b * p.H + h) * p.Nq + qi] = m[j] * LN2 + logf(lsum[j]);
+    }
   }
 }
 
@@ -239,7 +276,7 @@ __global__ void attn_delta_kernel(const T* __restrict__ o, int ldo, const T* __r
 
 // ------------------------------------------------------------------ dQ (bf16)
 template <int DHP>
-__global__ void __launch_bounds__(256) attn_bwd_dq_bf16_kernel(const AttnK p) {
+__global__ void __launch_bounds__(256, DHP == 64 ? 3 : 2) attn_bwd_dq_bf16_kernel(const AttnK p) {
   constexpr int KC = DHP / 16, DT = DHP / 32;
   constexpr int LD = DHP + 8;
   __shared__ __attribute__((aligned(16))) bf16 Ks[2][64 * LD];
@@ -302,7 +339,7 @@ __global__ void __launch_bounds__(256) attn_bwd_dq_bf16_kernel(const AttnK p) {
       }
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        float pr = exp2f(s[r] * p.scale_log2 - lse2);
+        float pr = __builtin_amdgcn_exp2f(s[r] * p.scale_log2 - lse2);
         if (edge && kt * 64 + 32 * t + acc_row(r, g) >= p.Nk) pr = 0.f;
         s[r] = pr * (dp[r] - dlt);
       }
@@ -351,7 +388,8 @@ __global__ void __launch_bounds__(256, DHP == 64 ? 2 : 1) attn_bwd_dkv_bf16_kern
   __shared__ __attribute__((aligned(16))) float dlt_s[2][64];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 5, l32 = lane & 31;
   int ktile, bh;
-  attn_block_map(blockIdx.x, (p.Nk + 127) / 128, p.B * p.H, ktile, bh);
+  const int qs = blockIdx.x % p.qsplits;
+  attn_block_map(blockIdx.x / p.qsplits, (p.Nk + 127) / 128, p.B * p.H, ktile, bh);
   const int b = bh / p.H, h = bh % p.H;
   const int ki = ktile * 128 + wave * 32 + l32;
   const bool kok = ki < p.Nk;
@@ -375,7 +413,9 @@ __global__ void __launch_bounds__(256, DHP == 64 ? 2 : 1) attn_bwd_dkv_bf16_kern
 #pragma unroll
     for (int r = 0; r < 16; ++r) { dkacc[i][r] = 0.f; dvacc[i][r] = 0.f; }
 
-  const int nqt = (p.Nq + 63) / 64;
+  // this workgroup's share of the 64-query tiles
+  const int nqt_all = (p.Nq + 63) / 64, tps = (nqt_all + p.qsplits - 1) / p.qsplits;
+  const int qt0 = qs * tps, nqt = min(nqt_all, qt0 + tps);
   TileLoader<DHP, 256> lq, ld_;
   float r_lse = 0.f, r_dlt = 0.f;
   auto load_stats = [&](int qt) {
@@ -388,16 +428,16 @@ __global__ void __launch_bounds__(256, DHP == 64 ? 2 : 1) attn_bwd_dkv_bf16_kern
   auto store_stats = [&](int buf) {
     if (tid < 64) { lse_s[buf][tid] = r_lse; dlt_s[buf][tid] = r_dlt; }
   };
-  lq.load(qb, p.ldq, 0, p.Nq, p.dh, tid);
-  ld_.load(dob, p.lddo, 0, p.Nq, p.dh, tid);
-  load_stats(0);
+  lq.load(qb, p.ldq, qt0 * 64, p.Nq, p.dh, tid);
+  ld_.load(dob, p.lddo, qt0 * 64, p.Nq, p.dh, tid);
+  load_stats(qt0);
   lq.store(Qs[0], LD, tid);
   ld_.store(Ds[0], LD, tid);
   store_stats(0);
   __syncthreads();
 
-  for (int qt = 0; qt < nqt; ++qt) {
-    const int buf = qt & 1;
+  for (int qt = qt0; qt < nqt; ++qt) {
+    const int buf = (qt - qt0) & 1;
     const bool more = qt + 1 < nqt;
     if (more) {
       lq.load(qb, p.ldq, (qt + 1) * 64, p.Nq, p.dh, tid);
@@ -424,7 +464,7 @@ __global__ void __launch_bounds__(256, DHP == 64 ? 2 : 1) attn_bwd_dkv_bf16_kern
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
           const int r = 4 * r4 + u;
-          float pr = exp2f(s[r] * p.scale_log2 - l4[u]);
+          float pr = __builtin_amdgcn_exp2f(s[r] * p.scale_log2 - l4[u]);
           if (!kok) pr = 0.f;
           s[r] = pr;
           ds[r] = pr * (dp[r] - d4[u]);
@@ -450,7 +490,25 @@ __global__ void __launch_bounds__(256, DHP == 64 ? 2 : 1) attn_bwd_dkv_bf16_kern
     }
     __syncthreads();
   }
-  if (kok) {
+  if (kok && p.qsplits > 1) {
+    // fp32 partial sums of this query range; reduced in a fixed order by attn_dkv_reduce_kernel
+    const size_t hd = (size_t)p.H * p.dh, rows = (size_t)p.B * p.Nk;
+    float* pk = p.dkv_partial + ((size_t)qs * rows + (size_t)b * p.Nk + ki) * hd + h * p.dh;
+    float* pv = pk + (size_t)p.qsplits * rows * hd;
+#pragma unroll
+    for (int i = 0; i < DT; ++i)
+#pragma unroll
+      for (int r4 = 0; r4 < 4; ++r4) {
+        const int col = 32 * i + 8 * r4 + 4 * g;
+        if (col < p.dh) {
+          f32x4 ok_, ov;
+#pragma unroll
+          for (int u = 0; u < 4; ++u) { ok_[u] = dkacc[i][4 * r4 + u] * p.scale; ov[u] = dvacc[i][4 * r4 + u]; }
+          *reinterpret_cast<f32x4*>(pk + col) = ok_;
+          *reinterpret_cast<f32x4*>(pv + col) = ov;
+        }
+      }
+  } else if (kok) {
     bf16* dkb = (bf16*)p.dk + ((size_t)b * p.Nk + ki) * p.lddk + h * p.dh;
     bf16* dvb = (bf16*)p.dv + ((size_t)b * p.Nk + ki) * p.lddv + h * p.dh;
 #pragma unroll
@@ -467,6 +525,26 @@ __global__ void __launch_bounds__(256, DHP == 64 ? 2 : 1) attn_bwd_dkv_bf16_kern
         }
       }
   }
+}
+
+// dk[row, col] = sum_qs partial_k[qs][row][col] (ascending qs), same for dv; 4 columns per thread.
+__global__ void attn_dkv_reduce_kernel(const float* __restrict__ partial, int qsplits, size_t rows, int hd, bf16* __restrict__ dk, int lddk,
+                                       bf16* __restrict__ dv, int lddv) {
+  const size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x;
+  const int per_row = hd / 4;
+  if (i >= rows * per_row) return;
+  const size_t row = i / per_row; const int col = (int)(i % per_row) * 4;
+  f32x4 sk = {0.f, 0.f, 0.f, 0.f}, sv = sk;
+  const size_t plane = rows * hd;
+  for (int q = 0; q < qsplits; ++q) {
+    sk += *reinterpret_cast<const f32x4*>(partial + (size_t)q * plane + row * hd + col);
+    sv += *reinterpret_cast<const f32x4*>(partial + ((size_t)qsplits + q) * plane + row * hd + col);
+  }
+  bf16x4 ok_, ov;
+#pragma unroll
+  for (int u = 0; u < 4; ++u) { ok_[u] = (bf16)sk[u]; ov[u] = (bf16)sv[u]; }
+  *reinterpret_cast<bf16x4*>(dk + row * lddk + col) = ok_;
+  *reinterpret_cast<bf16x4*>(dv + row * lddv + col) = ov;
 }
 
 // ------------------------------------------------------------------ fp32 path (one wave per row)
@@ -584,6 +662,7 @@ static AttnK make_k(const AttnArgs& a) {
   k.q = a.q; k.ldq = a.ldq; k.k = a.k; k.ldk = a.ldk; k.v = a.v; k.ldv = a.ldv; k.o = a.o; k.ldo = a.ldo; k.lse = a.lse;
   k.dout = a.dout; k.lddo = a.lddo; k.delta = a.delta; k.dq = a.dq; k.lddq = a.lddq; k.dk = a.dk; k.lddk = a.lddk;
   k.dv = a.dv; k.lddv = a.lddv;
+  k.qsplits = 1; k.dkv_partial = nullptr;
   return k;
 }
 
@@ -611,6 +690,8 @@ static int check_attn(const AttnArgs& a, bool bwd) {
   return DP_OK;
 }
 
+size_t attn_dkv_ws_bytes(int B, int H, int Nk, int d_head) { return 2 * (size_t)16 * B * Nk * H * d_head * sizeof(float); }
+
 int launch_attn_fwd(const AttnArgs& a, hipStream_t s) {
   if (int e = check_attn(a, false)) return e;
   const AttnK k = make_k(a);
@@ -618,13 +699,21 @@ int launch_attn_fwd(const AttnArgs& a, hipStream_t s) {
   const double by = dtype_size(a.dtype) * (double)a.B * a.H * a.d_head * (2.0 * a.Nq + 2.0 * a.Nk);
   KScope ks(a.dtype == BF16 ? KK_ATTN_FWD : KK_ATTN_F32, fl, by, s, a.Nq, a.Nk, a.d_head);
   if (a.dtype == BF16) {
-    dim3 grid(((a.Nq + 127) / 128) * a.B * a.H);
+    // two query tiles per wave halve the LDS traffic but cost occupancy; measured slower on MI355X
+    // (the kernel is bound by the softmax arithmetic, not by LDS), so one tile per wave is used
+    const bool qt2 = false;
+    dim3 grid(((a.Nq + (qt2 ? 255 : 127)) / (qt2 ? 256 : 128)) * a.B * a.H);
     if (a.d_head <= 64) {
-      if (a.causal) hipLaunchKernelGGL((attn_fwd_bf16_kernel<64, true>), grid, dim3(256), 0, s, k);
-      else hipLaunchKernelGGL((attn_fwd_bf16_kernel<64, false>), grid, dim3(256), 0, s, k);
+      if (qt2) {
+        if (a.causal) hipLaunchKernelGGL((attn_fwd_bf16_kernel<64, true, 2>), grid, dim3(256), 0, s, k);
+        else hipLaunchKernelGGL((attn_fwd_bf16_kernel<64, false, 2>), grid, dim3(256), 0, s, k);
+      } else {
+        if (a.causal) hipLaunchKernelGGL((attn_fwd_bf16_kernel<64, true, 1>), grid, dim3(256), 0, s, k);
+        else hipLaunchKernelGGL((attn_fwd_bf16_kernel<64, false, 1>), grid, dim3(256), 0, s, k);
+      }
     } else {
-      if (a.causal) hipLaunchKernelGGL((attn_fwd_bf16_kernel<96, true>), grid, dim3(256), 0, s, k);
-      else hipLaunchKernelGGL((attn_fwd_bf16_kernel<96, false>), grid, dim3(256), 0, s, k);
+      if (a.causal) hipLaunchKernelGGL((attn_fwd_bf16_kernel<96, true, 1>), grid, dim3(256), 0, s, k);
+      else hipLaunchKernelGGL((attn_fwd_bf16_kernel<96, false, 1>), grid, dim3(256), 0, s, k);
     }
   } else {
     hipLaunchKernelGGL(attn_fwd_f32_kernel, dim3(a.Nq, a.B * a.H), dim3(64), (size_t)a.Nk * sizeof(float), s, k, a.causal);
@@ -649,9 +738,27 @@ int launch_attn_bwd(const AttnArgs& a, hipStream_t s) {
       else hipLaunchKernelGGL(attn_bwd_dq_bf16_kernel<96>, gq, dim3(256), 0, s, k);
     }
     {
-      KScope ks(KK_ATTN_BWD_DKV, fl, by, s, a.Nq, a.Nk, a.d_head);
-      if (a.d_head <= 64) hipLaunchKernelGGL(attn_bwd_dkv_bf16_kernel<64>, gk, dim3(256), 0, s, k);
-      else hipLaunchKernelGGL(attn_bwd_dkv_bf16_kernel<96>, gk, dim3(256), 0, s, k);
+      // few key tiles (cross-attention to 77 keys): split the query range over more workgroups
+      AttnK k2 = k;
+      const long base_blocks = (long)((a.Nk + 127) / 128) * a.B * a.H;
+      const int nqt = (a.Nq + 63) / 64;
+      int qsplit = 1;
+      if (base_blocks < 256) qsplit = (int)std::min<long>(std::min<long>(16, nqt / 2 > 0 ? nqt / 2 : 1), (512 + base_blocks - 1) / base_blocks);
+      const size_t need = 2 * (size_t)qsplit * a.B * a.Nk * a.H * a.d_head * sizeof(float);
+      if (qsplit > 1 && (!a.dkv_ws || a.dkv_ws_bytes < need || ((uintptr_t)a.dkv_ws % 16))) qsplit = 1;
+      k2.qsplits = qsplit; k2.dkv_partial = a.dkv_ws;
+      dim3 gk2(gk.x * qsplit);
+      {
+        KScope ks(KK_ATTN_BWD_DKV, fl, by, s, a.Nq, a.Nk, a.d_head);
+        if (a.d_head <= 64) hipLaunchKernelGGL(attn_bwd_dkv_bf16_kernel<64>, gk2, dim3(256), 0, s, k2);
+        else hipLaunchKernelGGL(attn_bwd_dkv_bf16_kernel<96>, gk2, dim3(256), 0, s, k2);
+      }
+      if (qsplit > 1) {
+        const size_t rows = (size_t)a.B * a.Nk; const int hd = a.H * a.d_head;
+        KScope ks(KK_REDUCE, 0.0, (double)need + 4.0 * rows * hd, s, (int)rows, hd, qsplit);
+        hipLaunchKernelGGL(attn_dkv_reduce_kernel, dim3((rows * (hd / 4) + 255) / 256), dim3(256), 0, s, a.dkv_ws, qsplit, rows, hd,
+                           (bf16*)a.dk, a.lddk, (bf16*)a.dv, a.lddv);
+      }
     }
   } else {
     hipLaunchKernelGGL(attn_delta_kernel<float>, dgrid, dim3(256), 0, s, (const float*)a.o, a.ldo, (const float*)a.dout, a.lddo, a.delta, a.B, a.H, a.Nq, a.d_head);

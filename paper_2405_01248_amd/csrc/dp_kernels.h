@@ -64,7 +64,9 @@ struct AttnArgs {
   void* dq; int lddq;
   void* dk; int lddk;
   void* dv; int lddv;
+  float* dkv_ws; size_t dkv_ws_bytes;   // optional fp32 scratch: lets the dK/dV kernel split the query range when there are few key tiles
 };
+size_t attn_dkv_ws_bytes(int B, int H, int Nk, int d_head);   // enough for any split the launcher may choose
 int launch_attn_fwd(const AttnArgs& a, hipStream_t s);
 int launch_attn_bwd(const AttnArgs& a, hipStream_t s);
 

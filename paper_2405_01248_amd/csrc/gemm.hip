@@ -320,27 +320,32 @@ gemm_bf16_kernel(const GemmBf16Params p) {
 //   K-strided operand:     tile [32][cols], chunk c of k-row k stored at c ^ (2 * (k & 3)).
 // Requires K % 32 == 0.  Rows / columns beyond M / N are fetched from a clamped address; they
 // only feed accumulators whose outputs are never stored.
-constexpr int DTL_BK = 32, DTL_STAGES = 4;
+constexpr int DTL_BK = 32;   // every k-tile depth used by this kernel is a multiple of this
 
-template <int BM, int BN, int WGM, int WGN>
+template <int BM, int BN, int BK, int STAGES, int WGM, int WGN>
 struct DtlSmem {
-  static constexpr int A_BYTES = BM * DTL_BK * 2, B_BYTES = BN * DTL_BK * 2, STAGE = A_BYTES + B_BYTES;
+  static constexpr int A_BYTES = BM * BK * 2, B_BYTES = BN * BK * 2, STAGE = A_BYTES + B_BYTES;
   static constexpr int WN = BN / WGN;
   static constexpr int C_LD = WN + 4;
-  static constexpr size_t TILE_BYTES = (size_t)DTL_STAGES * STAGE;
+  static constexpr size_t TILE_BYTES = (size_t)STAGES * STAGE;
   static constexpr size_t EPI_BYTES = (size_t)WGM * WGN * 32 * C_LD * 4;
   static constexpr size_t BYTES = TILE_BYTES > EPI_BYTES ? TILE_BYTES : EPI_BYTES;
 };
 
-template <int BM, int BN, int WGM, int WGN, bool A_MC, bool B_MC>
+// Chunk permutation of a K-contiguous tile row r (BK / 8 chunks per row): conflict-free 16-byte
+// reads by 16 consecutive rows.  BK = 32: 4 chunks, key (r >> 2) & 3; BK = 64: 8 chunks, key (r >> 1) & 7.
+template <int BK> __device__ __forceinline__ int kc_key(int r) { return BK == 32 ? ((r >> 2) & 3) : ((r >> 1) & 7); }
+
+template <int BM, int BN, int BK, int STAGES, int WGM, int WGN, bool A_MC, bool B_MC>
 __global__ void __launch_bounds__(WGM * WGN * 64)
 gemm_bf16_dtl_kernel(const GemmBf16Params p) {
-  using S = DtlSmem<BM, BN, WGM, WGN>;
-  constexpr int NW = WGM * WGN, BK = DTL_BK;
+  using S = DtlSmem<BM, BN, BK, STAGES, WGM, WGN>;
+  constexpr int NW = WGM * WGN, KS = BK / 16, CPR = BK / 8;      // k-steps per tile, chunks per K-contiguous row
   constexpr int WM = BM / WGM, WN = BN / WGN;
   constexpr int TM = WM / 32, TN = WN / 32;
   constexpr int A_LOADS = S::A_BYTES / 1024 / NW, B_LOADS = S::B_BYTES / 1024 / NW, LOADS = A_LOADS + B_LOADS;
   static_assert(S::A_BYTES % (1024 * NW) == 0 && S::B_BYTES % (1024 * NW) == 0, "tile/waves mismatch");
+  static_assert(KS % 2 == 0 && STAGES >= 3, "pipeline shape");
 
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem_raw[];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -363,7 +368,7 @@ gemm_bf16_dtl_kernel(const GemmBf16Params p) {
       const int k = blk * (1024 / (BM * 2)) + lane / (BM / 8), pc = lane % (BM / 8), c = pc ^ (2 * (k & 3));
       ga[j] = p.A + (size_t)(kt_begin * BK + k) * p.lda + min(m0 + c * 8, p.M - 8);
     } else {
-      const int r = blk * 16 + (lane >> 2), pc = lane & 3, c = pc ^ ((r >> 2) & 3);
+      const int r = blk * (512 / BK) + lane / CPR, pc = lane % CPR, c = pc ^ kc_key<BK>(r);
       ga[j] = p.A + (size_t)min(m0 + r, p.M - 1) * p.lda + kt_begin * BK + c * 8;
     }
   }
@@ -374,7 +379,7 @@ gemm_bf16_dtl_kernel(const GemmBf16Params p) {
       const int k = blk * (1024 / (BN * 2)) + lane / (BN / 8), pc = lane % (BN / 8), c = pc ^ (2 * (k & 3));
       gb[j] = p.B + (size_t)(kt_begin * BK + k) * p.ldb + min(n0 + c * 8, p.N - 8);
     } else {
-      const int r = blk * 16 + (lane >> 2), pc = lane & 3, c = pc ^ ((r >> 2) & 3);
+      const int r = blk * (512 / BK) + lane / CPR, pc = lane % CPR, c = pc ^ kc_key<BK>(r);
       gb[j] = p.B + (size_t)min(n0 + r, p.N - 1) * p.ldb + kt_begin * BK + c * 8;
     }
   }
@@ -382,11 +387,11 @@ gemm_bf16_dtl_kernel(const GemmBf16Params p) {
 
 #define DP_DTL_ISSUE(t_)                                                                                              \
   {                                                                                                                   \
-    unsigned char* st_ = smem_raw + ((t_) % DTL_STAGES) * S::STAGE;                                                   \
+    unsigned char* st_ = smem_raw + ((t_) % STAGES) * S::STAGE;                                                       \
     _Pragma("unroll") for (int j = 0; j < A_LOADS; ++j)                                                               \
-      async_copy_16B(ga[j] + (size_t)(t_) * a_step, st_ + (wave * A_LOADS + j) * 1024); \
+      async_copy_16B(ga[j] + (size_t)(t_) * a_step, st_ + (wave * A_LOADS + j) * 1024);                               \
     _Pragma("unroll") for (int j = 0; j < B_LOADS; ++j)                                                               \
-      async_copy_16B(gb[j] + (size_t)(t_) * b_step, st_ + S::A_BYTES + (wave * B_LOADS + j) * 1024); \
+      async_copy_16B(gb[j] + (size_t)(t_) * b_step, st_ + S::A_BYTES + (wave * B_LOADS + j) * 1024);                  \
   }
 
   f32x16 acc[TM][TN];
@@ -412,7 +417,7 @@ gemm_bf16_dtl_kernel(const GemmBf16Params p) {
         fa[set_][i] = __builtin_shufflevector(lds_read_tr(q), lds_read_tr(q + 4 * BM), 0, 1, 2, 3, 4, 5, 6, 7);       \
       } else {                                                                                                        \
         const int r = wm0 + i * 32 + l32;                                                                             \
-        fa[set_][i] = *reinterpret_cast<const bf16x8*>(as + r * BK + (((2 * (ks_) + g) ^ ((r >> 2) & 3)) * 8));       \
+        fa[set_][i] = *reinterpret_cast<const bf16x8*>(as + r * BK + (((2 * (ks_) + g) ^ kc_key<BK>(r)) * 8));        \
       }                                                                                                               \
     }                                                                                                                 \
     _Pragma("unroll") for (int j2 = 0; j2 < TN; ++j2) {                                                               \
@@ -424,7 +429,7 @@ gemm_bf16_dtl_kernel(const GemmBf16Params p) {
         fb[set_][j2] = __builtin_shufflevector(lds_read_tr(q), lds_read_tr(q + 4 * BN), 0, 1, 2, 3, 4, 5, 6, 7);      \
       } else {                                                                                                        \
         const int r = wn0 + j2 * 32 + l32;                                                                            \
-        fb[set_][j2] = *reinterpret_cast<const bf16x8*>(bs + r * BK + (((2 * (ks_) + g) ^ ((r >> 2) & 3)) * 8));      \
+        fb[set_][j2] = *reinterpret_cast<const bf16x8*>(bs + r * BK + (((2 * (ks_) + g) ^ kc_key<BK>(r)) * 8));       \
       }                                                                                                               \
     }                                                                                                                 \
   }
@@ -433,31 +438,37 @@ gemm_bf16_dtl_kernel(const GemmBf16Params p) {
     _Pragma("unroll") for (int j2 = 0; j2 < TN; ++j2) acc[i][j2] = mfma32(fa[set_][i], fb[set_][j2], acc[i][j2]);
 
   // Software pipeline.  Fragments are fetched one k-step ahead of the MFMAs that use them, also
-  // across the k-tile boundary: the wait + barrier that publishes k-tile t + 1 sits between the
-  // two MFMA groups of k-tile t.  Passing that barrier also means every wave has finished reading
-  // k-tile t - 1, so its stage is refilled with k-tile t + 3 right after it.
-  for (int t = 0; t < DTL_STAGES - 1 && t < nk; ++t) DP_DTL_ISSUE(t);
-  if (nk > 2) wait_vmcnt<2 * LOADS>();
-  else if (nk > 1) wait_vmcnt<LOADS>();
-  else wait_vmcnt<0>();
+  // across the k-tile boundary: the wait + barrier that publishes k-tile t + 1 sits before the
+  // last MFMA group of k-tile t.  Passing that barrier also means every wave has finished reading
+  // k-tile t - 1, so its stage is refilled with k-tile t + STAGES - 1 right after it.  At the wait,
+  // the k-tiles t + 2 .. t + STAGES - 2 may still be in flight.
+  for (int t = 0; t < STAGES - 1 && t < nk; ++t) DP_DTL_ISSUE(t);
+  {
+    const int younger = min(nk - 1, STAGES - 2);
+    if (younger >= 2) wait_vmcnt<2 * LOADS>();
+    else if (younger == 1) wait_vmcnt<LOADS>();
+    else wait_vmcnt<0>();
+  }
   barrier_nofence();
   DP_DTL_FRAGS(0, 0, 0);
   for (int t = 0; t < nk; ++t) {
-    const int st = t % DTL_STAGES;
-    DP_DTL_FRAGS(st, 1, 1);
-    __builtin_amdgcn_sched_barrier(0);
-    DP_DTL_MFMAS(0);
-    __builtin_amdgcn_sched_barrier(0);
-    if (t + 1 < nk) {
-      if (t + 2 < nk) wait_vmcnt<LOADS>();
-      else wait_vmcnt<0>();
-      barrier_nofence();
-      if (t + DTL_STAGES - 1 < nk) DP_DTL_ISSUE(t + DTL_STAGES - 1);
-      DP_DTL_FRAGS((t + 1) % DTL_STAGES, 0, 0);
+    const int st = t % STAGES;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      if (ks + 1 < KS) {
+        DP_DTL_FRAGS(st, ks + 1, (ks + 1) & 1);
+      } else if (t + 1 < nk) {
+        const int younger = min(nk - 2 - t, STAGES - 3);
+        if (younger >= 1) wait_vmcnt<LOADS>();
+        else wait_vmcnt<0>();
+        barrier_nofence();
+        if (t + STAGES - 1 < nk) DP_DTL_ISSUE(t + STAGES - 1);
+        DP_DTL_FRAGS((t + 1) % STAGES, 0, 0);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+      DP_DTL_MFMAS(ks & 1);
+      __builtin_amdgcn_sched_barrier(0);
     }
-    __builtin_amdgcn_sched_barrier(0);
-    DP_DTL_MFMAS(1);
-    __builtin_amdgcn_sched_barrier(0);
   }
 #undef DP_DTL_FRAGS
 #undef DP_DTL_MFMAS
@@ -574,8 +585,8 @@ static int choose_splits(long tiles, int kt) {
 
 // Picks the tile configuration (indices as in launch_gemm's switch) from a sweep of all GEMM
 // shapes of the five workloads on MI355X:
-//  - y = x W^T (both operands K-contiguous): the direct-to-LDS pipeline, 128x128 tiles, or
-//    256x128 tiles for very large outputs;
+//  - y = x W^T (both operands K-contiguous): the direct-to-LDS pipeline, 256x128x64 tiles when
+//    they fill the CUs, else 128x128x32 tiles (two workgroups per CU);
 //  - dx = dy W: register-staged kernel; 256x256 tiles when the contraction is long and there
 //    are enough tiles to fill the CUs, else 256x128, else 128x128;
 //  - dW = dy^T x (both operands read through the transposing LDS load): 128x128, two
@@ -586,7 +597,8 @@ static int choose_cfg(int M, int N, int K, bool a_mc, bool b_mc) {
   if (a_mc) return 0;
   if (!b_mc) {
     if (K % DTL_BK) return t256x128 >= 128 ? 1 : 0;
-    return (double)M * N >= 8192.0 * 4096.0 ? 7 : 8;
+    if (t256x128 >= 96 && K % 64 == 0) return 9;     // 256x128 tiles, 64-deep k-tiles, three stages
+    return 8;                                        // 128x128 tiles, 32-deep k-tiles, four stages
   }
   if (K >= 2 * N && t256x256 >= 128) return 2;
   return t256x128 >= 128 ? 1 : 0;
@@ -645,18 +657,18 @@ static int launch_bf16_cfg(const GemmArgs& a, hipStream_t s) {
   return DP_OK;
 }
 
-template <int BM, int BN, int WGM, int WGN, bool A_MC, bool B_MC>
+template <int BM, int BN, int BK, int STAGES, int WGM, int WGN, bool A_MC, bool B_MC>
 static int launch_dtl_cfg(const GemmArgs& a, hipStream_t s) {
-  using S = DtlSmem<BM, BN, WGM, WGN>;
+  using S = DtlSmem<BM, BN, BK, STAGES, WGM, WGN>;
   GemmBf16Params p;
   p.A = (const bf16*)a.A; p.B = (const bf16*)a.B;
   p.M = a.M; p.N = a.N; p.K = a.K; p.lda = a.lda; p.ldb = a.ldb;
   p.epi = make_epi<bf16>(a);
   p.tiles_m = (a.M + BM - 1) / BM; p.tiles_n = (a.N + BN - 1) / BN;
-  const int kt = a.K / DTL_BK;
+  const int kt = a.K / BK;
   int splits = 1;
   if (a.out_f32) {
-    splits = choose_splits((long)p.tiles_m * p.tiles_n, kt / 2);
+    splits = choose_splits((long)p.tiles_m * p.tiles_n, kt * BK / 64);
     if (splits > 1) {
       const size_t need = (size_t)splits * a.M * a.N * sizeof(float);
       if (!a.splitk_ws || a.splitk_ws_bytes < need) splits = 1;
@@ -667,7 +679,7 @@ static int launch_dtl_cfg(const GemmArgs& a, hipStream_t s) {
   if (splits > 1) p.epi.partial = a.splitk_ws;
   dim3 grid(p.tiles_m * p.tiles_n, 1, splits);
   const size_t smem = S::BYTES;
-  auto kern = gemm_bf16_dtl_kernel<BM, BN, WGM, WGN, A_MC, B_MC>;
+  auto kern = gemm_bf16_dtl_kernel<BM, BN, BK, STAGES, WGM, WGN, A_MC, B_MC>;
   static bool attr_set = false;
   if (!attr_set) {
     if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) != hipSuccess)
@@ -688,12 +700,13 @@ static int launch_dtl_cfg(const GemmArgs& a, hipStream_t s) {
   return DP_OK;
 }
 
-template <int BM, int BN, int WGM, int WGN>
+template <int BM, int BN, int BK, int STAGES, int WGM, int WGN>
 static int launch_dtl_layout(const GemmArgs& a, hipStream_t s) {
-  if (!a.a_mc && !a.b_mc) return launch_dtl_cfg<BM, BN, WGM, WGN, false, false>(a, s);
-  if (!a.a_mc && a.b_mc) return launch_dtl_cfg<BM, BN, WGM, WGN, false, true>(a, s);
-  if (a.a_mc && a.b_mc) return launch_dtl_cfg<BM, BN, WGM, WGN, true, true>(a, s);
-  return launch_dtl_cfg<BM, BN, WGM, WGN, true, false>(a, s);
+  if (a.K % BK) return set_error(DP_EUNSUPPORTED, "gemm: K is not a multiple of the k-tile of the forced configuration");
+  if (!a.a_mc && !a.b_mc) return launch_dtl_cfg<BM, BN, BK, STAGES, WGM, WGN, false, false>(a, s);
+  if (!a.a_mc && a.b_mc) return launch_dtl_cfg<BM, BN, BK, STAGES, WGM, WGN, false, true>(a, s);
+  if (a.a_mc && a.b_mc) return launch_dtl_cfg<BM, BN, BK, STAGES, WGM, WGN, true, true>(a, s);
+  return launch_dtl_cfg<BM, BN, BK, STAGES, WGM, WGN, true, false>(a, s);
 }
 
 template <int BM, int BN, int BK, int WGM, int WGN>
@@ -722,17 +735,18 @@ int launch_gemm(const GemmArgs& a, hipStream_t s) {
     for (int x : elds) if (x % 8 || x < 8) return set_error(DP_EUNSUPPORTED, "gemm(bf16): epilogue leading dims must be multiples of 8");
     const void* eps[] = {a.out, a.out_f32, a.bias, a.pre_out, a.dact_pre, a.gate, a.residual, a.splitk_ws};
     for (const void* x : eps) if ((uintptr_t)x % 16) return set_error(DP_EALIGN, "gemm(bf16): epilogue operands must be 16-byte aligned");
-    const int cfg = (a.force_cfg > 0 && a.force_cfg <= kNumCfgs + 4) ? a.force_cfg - 1 : choose_cfg(a.M, a.N, a.K, a.a_mc != 0, a.b_mc != 0);
+    const int cfg = (a.force_cfg > 0 && a.force_cfg <= kNumCfgs + 5) ? a.force_cfg - 1 : choose_cfg(a.M, a.N, a.K, a.a_mc != 0, a.b_mc != 0);
     switch (cfg) {
       case 1: return launch_bf16_layout<256, 128, 64, 4, 2>(a, s);
       case 2: return launch_bf16_layout<256, 256, 64, 2, 4>(a, s);
       case 3: return launch_bf16_layout<128, 256, 64, 2, 4>(a, s);
       case 4: return launch_bf16_layout<256, 128, 32, 4, 2>(a, s);
       case 5: return launch_bf16_layout<128, 128, 32, 2, 2>(a, s);
-      case 6: if (a.K % DTL_BK == 0) return launch_dtl_layout<256, 256, 2, 4>(a, s); break;
-      case 7: if (a.K % DTL_BK == 0) return launch_dtl_layout<256, 128, 4, 2>(a, s); break;
-      case 8: if (a.K % DTL_BK == 0) return launch_dtl_layout<128, 128, 2, 2>(a, s); break;
-      case 9: if (a.K % DTL_BK == 0) return launch_dtl_layout<256, 256, 2, 2>(a, s); break;
+      case 6: return launch_dtl_layout<256, 256, 32, 4, 2, 4>(a, s);
+      case 7: return launch_dtl_layout<256, 128, 32, 4, 4, 2>(a, s);
+      case 8: return launch_dtl_layout<128, 128, 32, 4, 2, 2>(a, s);
+      case 9: return launch_dtl_layout<256, 128, 64, 3, 4, 2>(a, s);
+      case 10: return launch_dtl_layout<128, 128, 64, 3, 2, 2>(a, s);
       default: break;
     }
     return launch_bf16_layout<128, 128, 64, 2, 2>(a, s);

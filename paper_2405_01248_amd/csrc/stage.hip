@@ -95,6 +95,7 @@ struct BwdScratch {
   GradPair r[2];
   void *dh, *da, *dqkv, *dq2, *dkv2, *dg, *dg2, *du, *dm_t;
   float *delta, *dm, *dcond_pre, *partial, *partial_side; size_t partial_bytes;
+  float* dkv_ws; size_t dkv_ws_bytes;     // query-split partials of the cross-attention dK/dV kernel
 };
 
 static void plan_unet_block(Plan& p, const dp_stage& s, UnetBuf& u, bool with_xin) {
@@ -150,10 +151,12 @@ static void plan_bwd_scratch(Plan& p, const dp_stage& s, BwdScratch& b) {
   b.delta = (float*)p.take((size_t)s.d.batch * s.d.n_heads * s.d.tokens * sizeof(float));
   if (unet) {
     b.dq2 = p.take(T * d * es); b.dkv2 = p.take(Tc * 2 * d * es);
+    b.dkv_ws_bytes = attn_dkv_ws_bytes(s.d.batch, s.d.n_heads, s.d.ctx_tokens, s.d.d_head);
+    b.dkv_ws = (float*)p.take(b.dkv_ws_bytes);
     b.dg = p.take(T * ff * es); b.du = p.take(T * 2 * ff * es); b.dg2 = nullptr;
     b.dm_t = nullptr; b.dm = nullptr; b.dcond_pre = nullptr;
   } else {
-    b.dq2 = nullptr; b.dkv2 = nullptr;
+    b.dq2 = nullptr; b.dkv2 = nullptr; b.dkv_ws = nullptr; b.dkv_ws_bytes = 0;
     b.dg = p.take(T * d * es);          // gated-branch gradients: df2 ...
     b.dg2 = p.take(T * d * es);         // ... and do (separate, so the side stream can still read df2)
     b.du = p.take(T * ff * es);         // df1
@@ -364,6 +367,7 @@ static int unet_block_bwd(const dp_stage& s, const void* const* P, void* const* 
   a.Nk = s.d.ctx_tokens; a.q = u.q2; a.ldq = d; a.k = u.kv2; a.v = at(u.kv2, d, es); a.ldk = a.ldv = 2 * d;
   a.o = u.a2; a.ldo = d; a.lse = u.lse2; a.dout = b.da; a.lddo = d; a.delta = b.delta;
   a.dq = b.dq2; a.lddq = d; a.dk = b.dkv2; a.dv = at(b.dkv2, d, es); a.lddk = a.lddv = 2 * d;
+  a.dkv_ws = b.dkv_ws; a.dkv_ws_bytes = b.dkv_ws_bytes;
   sd.wait(rd.dq2);
   DP_TRY(launch_attn_bwd(a, st));
   {
@@ -778,6 +782,12 @@ void dp_stage_destroy(dp_stage* st) {
   for (auto& e : st->events) (void)hipEventDestroy(e);
   if (st->side) (void)hipStreamDestroy(st->side);
   delete st;
+}
+
+int dp_stage_set_overlap(dp_stage* st, int enabled) {
+  if (!st) return set_error(DP_EINVAL, "stage handle is NULL");
+  st->overlap = enabled != 0;
+  return DP_OK;
 }
 
 int dp_stage_param_count(const dp_stage* st) { return st ? (int)st->params.size() : set_error(DP_EINVAL, "stage handle is NULL"); }
