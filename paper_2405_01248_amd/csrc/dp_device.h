@@ -64,10 +64,23 @@ __device__ __forceinline__ bf16x8 frag_from_mc_accorder(const bf16* tile, int ld
 __device__ __forceinline__ void async_copy_16B(const void* gptr, void* lds_base) {
   __builtin_amdgcn_global_load_lds(gptr, (DP_LDS void*)lds_base, 16, 0, 0);
 }
+// The same copy through a buffer descriptor: the source is base + lane_off + wave_off (bytes; wave_off
+// wave-uniform).  Preferred over the flat-address form inside pipelined loops: with a flat-address LDS
+// copy in flight the compiler treats the LDS counter as unordered and turns every wait for an LDS read
+// into a wait for all of them, which defeats fragment prefetching.
+typedef __amdgpu_buffer_rsrc_t rsrc_t;
+__device__ __forceinline__ rsrc_t make_rsrc(const void* base, uint32_t bytes) {
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, bytes, 0x00020000);
+}
+__device__ __forceinline__ void async_copy_16B_buf(rsrc_t r, uint32_t lane_off, uint32_t wave_off, void* lds_base) {
+  __builtin_amdgcn_raw_ptr_buffer_load_lds(r, (DP_LDS void*)lds_base, 16, lane_off, wave_off, 0, 0);
+}
 // Wait until at most N of this wave's vector-memory operations are outstanding (lgkmcnt / expcnt untouched).
 template <int N> __device__ __forceinline__ void wait_vmcnt() {
   __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
 }
+// Wait for all of this wave's LDS / scalar-memory operations (vmcnt / expcnt untouched).
+__device__ __forceinline__ void wait_lgkmcnt0() { __builtin_amdgcn_s_waitcnt(0xC07F); }
 // Workgroup barrier without the memory fence of __syncthreads() (which would also wait for every
 // outstanding asynchronous copy); the empty asm statements keep the compiler from moving memory
 // accesses across it.

@@ -17,6 +17,15 @@
 
 namespace dp {
 
+// Optional phase tracing of the direct-to-LDS kernel (development builds only): thread 0 of each
+// workgroup stores the 100 MHz wall clock at a few points of its life.
+#ifdef DP_GEMM_TRACE
+__device__ unsigned long long g_gemm_trace[2048 * 32];
+#define DP_TRACE(i_) { if (threadIdx.x == 0 && blockIdx.x < 2048 && (i_) < 32) g_gemm_trace[blockIdx.x * 32 + (i_)] = wall_clock64(); }
+#else
+#define DP_TRACE(i_)
+#endif
+
 template <typename T>
 struct EpiParams {
   int M, N;
@@ -113,14 +122,61 @@ __device__ __forceinline__ void epi_vec8(const EpiParams<bf16>& e, int m, int n,
   }
 }
 
+// Epilogue shared by the MFMA kernels.  A wave stages one 32-row slab of its accumulators at a time
+// through its own fp32 LDS region Cw ([32][C_LD], reusing the operand tiles once every wave of the
+// workgroup is past its last fragment read) and re-reads it as 8 consecutive columns per lane, so
+// bias / residual / saved pre-activation loads and all stores are 16-byte accesses.  LDS requests
+// of one wave are served in order, so no barrier is needed between a slab's writes and reads; the
+// empty asm statements only stop the compiler from reordering them.  The store loop is kept rolled:
+// unrolled, the activation and gradient variants would be replicated per 8-column group and the
+// kernel would outgrow the instruction cache.
+template <int TM, int TN, int WN, int C_LD>
+__device__ __forceinline__ void wave_epilogue(const f32x16 (&acc)[TM][TN], float* Cw, const EpiParams<bf16>& e, int row0,
+                                              int col0, int lane) {
+  const int g = lane >> 5, l32 = lane & 31;
+#pragma unroll
+  for (int i = 0; i < TM; ++i) {
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) Cw[(8 * (r >> 2) + 4 * g + (r & 3)) * C_LD + j * 32 + l32] = acc[i][j][r];
+    asm volatile("" ::: "memory");
+    DP_TRACE(20 + 2 * i);
+#pragma unroll 1
+    for (int it = 0; it < 32 * WN / 8 / 64; ++it) {
+      const int id = it * 64 + lane;
+      const int lr = id / (WN / 8), lc = (id % (WN / 8)) * 8;
+      const int m = row0 + i * 32 + lr, n = col0 + lc;
+      if (m < e.M && n < e.N) {
+        float v[8];
+        *reinterpret_cast<f32x4*>(&v[0]) = *reinterpret_cast<const f32x4*>(&Cw[lr * C_LD + lc]);
+        *reinterpret_cast<f32x4*>(&v[4]) = *reinterpret_cast<const f32x4*>(&Cw[lr * C_LD + lc + 4]);
+        epi_vec8(e, m, n, v);
+      }
+    }
+    asm volatile("" ::: "memory");
+    DP_TRACE(21 + 2 * i);
+  }
+}
+
 // ------------------------------------------------------------------ bf16 MFMA kernel
 struct GemmBf16Params {
   const bf16* A; const bf16* B;
   int M, N, K, lda, ldb;
   int k_tiles_per_split;
   int tiles_m, tiles_n;
+  uint32_t a_bytes, b_bytes;   // extent of each operand in bytes (direct-to-LDS kernels address it with 32-bit offsets)
   EpiParams<bf16> epi;
 };
+
+// Bytes from the first to one past the last element of an operand; rows x inner elements, row stride ld.
+static inline size_t operand_extent_bytes(int rows, int inner, int ld) { return 2 * ((size_t)(rows - 1) * ld + inner); }
+// The direct-to-LDS kernels need both operands below 4 GiB.
+static inline bool dtl_addressable(const GemmArgs& a) {
+  const size_t ab = a.a_mc ? operand_extent_bytes(a.K, a.M, a.lda) : operand_extent_bytes(a.M, a.K, a.lda);
+  const size_t bb = a.b_mc ? operand_extent_bytes(a.K, a.N, a.ldb) : operand_extent_bytes(a.N, a.K, a.ldb);
+  return ab < (1ull << 32) && bb < (1ull << 32);
+}
 
 template <int BM, int BN, int BK, int WGM, int WGN, bool A_MC, bool B_MC>
 struct GemmSmem {
@@ -278,31 +334,8 @@ gemm_bf16_kernel(const GemmBf16Params p) {
     __syncthreads();
   }
 
-  // Epilogue.  Each wave stages one 32-row slab of its accumulators at a time through its own
-  // fp32 LDS region (reusing the operand tiles) and re-reads it as 8 consecutive columns per
-  // lane, so bias / residual / saved pre-activation loads and all stores are 16-byte accesses.
   float* Cw = reinterpret_cast<float*>(smem_raw) + wave * 32 * S::C_LD;
-#pragma unroll
-  for (int i = 0; i < TM; ++i) {
-#pragma unroll
-    for (int j = 0; j < TN; ++j)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) Cw[(8 * (r >> 2) + 4 * g + (r & 3)) * S::C_LD + j * 32 + l32] = acc[i][j][r];
-    __syncthreads();
-#pragma unroll
-    for (int it = 0; it < 32 * WN / 8 / 64; ++it) {
-      const int id = it * 64 + lane;
-      const int lr = id / (WN / 8), lc = (id % (WN / 8)) * 8;
-      const int m = m0 + wm0 + i * 32 + lr, n = n0 + wn0 + lc;
-      if (m < p.M && n < p.N) {
-        float v[8];
-        *reinterpret_cast<f32x4*>(&v[0]) = *reinterpret_cast<const f32x4*>(&Cw[lr * S::C_LD + lc]);
-        *reinterpret_cast<f32x4*>(&v[4]) = *reinterpret_cast<const f32x4*>(&Cw[lr * S::C_LD + lc + 4]);
-        epi_vec8(p.epi, m, n, v);
-      }
-    }
-    __syncthreads();
-  }
+  wave_epilogue<TM, TN, WN, S::C_LD>(acc, Cw, p.epi, m0 + wm0, n0 + wn0, lane);
 }
 
 #undef DP_GEMM_LOAD_GLOBAL
@@ -310,17 +343,20 @@ gemm_bf16_kernel(const GemmBf16Params p) {
 
 // ------------------------------------------------------------------ bf16 MFMA kernel, direct-to-LDS pipeline
 // Same tiling and epilogue, but the operand tiles travel global -> LDS without passing through
-// registers (global_load_lds_dwordx4: every lane fetches 16 bytes, the wave's 1 KB lands
-// contiguously in LDS) in a four-stage ring, three k-tiles ahead of the MFMAs.  On MI355X a
-// k-tile's MFMA time is far shorter than the memory latency, so the depth of this prefetch,
-// not the instruction schedule, decides the speed.  LDS tiles are unpadded; bank conflicts
+// registers (buffer_load_dwordx4 ... lds: every lane fetches 16 bytes, the wave's 1 KB lands
+// contiguously in LDS) in a ring of three or four buffers, two or three k-tiles ahead of the
+// MFMAs.  What bounds this loop on MI355X is not one pipe but three at once: per k-tile a
+// 256x128 workgroup needs about as many LDS cycles (fragment reads plus the incoming copies) and
+// three quarters as many L1 address cycles as MFMA cycles, so copies, fragment reads and MFMAs
+// are interleaved finely and every wait names exactly the data it needs.  The copies use the
+// buffer-descriptor form because a flat-address LDS copy in flight makes the compiler treat the
+// LDS counter as unordered (every wait for one fragment becomes a wait for all).  LDS tiles are unpadded; bank conflicts
 // are avoided by permuting 16-byte chunks inside a row (the permutation is applied through
 // the per-lane global address, and undone when fragments are read).
 //   K-contiguous operand:  tile [rows][32], chunk c of row r stored at c ^ ((r >> 2) & 3).
 //   K-strided operand:     tile [32][cols], chunk c of k-row k stored at c ^ (2 * (k & 3)).
 // Requires K % 32 == 0.  Rows / columns beyond M / N are fetched from a clamped address; they
 // only feed accumulators whose outputs are never stored.
-constexpr int DTL_BK = 32;   // every k-tile depth used by this kernel is a multiple of this
 
 template <int BM, int BN, int BK, int STAGES, int WGM, int WGN>
 struct DtlSmem {
@@ -345,7 +381,7 @@ gemm_bf16_dtl_kernel(const GemmBf16Params p) {
   constexpr int TM = WM / 32, TN = WN / 32;
   constexpr int A_LOADS = S::A_BYTES / 1024 / NW, B_LOADS = S::B_BYTES / 1024 / NW, LOADS = A_LOADS + B_LOADS;
   static_assert(S::A_BYTES % (1024 * NW) == 0 && S::B_BYTES % (1024 * NW) == 0, "tile/waves mismatch");
-  static_assert(KS % 2 == 0 && STAGES >= 3, "pipeline shape");
+  static_assert(KS % 2 == 0 && STAGES >= 2, "pipeline shape");
 
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem_raw[];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -357,19 +393,22 @@ gemm_bf16_dtl_kernel(const GemmBf16Params p) {
   const int kt_begin = blockIdx.z * p.k_tiles_per_split;
   const int kt_end = min(p.K / BK, kt_begin + p.k_tiles_per_split);
   const int nk = kt_end - kt_begin;
+  DP_TRACE(0);
 
-  // per-lane global source of each of this wave's 1 KB pieces (k-tile 0); advancing by one
-  // k-tile adds a constant
-  const bf16* ga[A_LOADS]; const bf16* gb[B_LOADS];
+  // per-lane byte offset (inside the operand) of each of this wave's 1 KB pieces at k-tile 0;
+  // advancing by one k-tile adds a wave-uniform constant.  Rows / column chunks past the matrix edge
+  // are clamped to the last valid one (they only feed outputs that are never stored).
+  const rsrc_t ra = make_rsrc(p.A, p.a_bytes), rb = make_rsrc(p.B, p.b_bytes);
+  uint32_t va[A_LOADS], vb[B_LOADS];
 #pragma unroll
   for (int j = 0; j < A_LOADS; ++j) {
     const int blk = wave * A_LOADS + j;
     if (A_MC) {
       const int k = blk * (1024 / (BM * 2)) + lane / (BM / 8), pc = lane % (BM / 8), c = pc ^ (2 * (k & 3));
-      ga[j] = p.A + (size_t)(kt_begin * BK + k) * p.lda + min(m0 + c * 8, p.M - 8);
+      va[j] = 2u * ((uint32_t)(kt_begin * BK + k) * p.lda + min(m0 + c * 8, p.M - 8));
     } else {
       const int r = blk * (512 / BK) + lane / CPR, pc = lane % CPR, c = pc ^ kc_key<BK>(r);
-      ga[j] = p.A + (size_t)min(m0 + r, p.M - 1) * p.lda + kt_begin * BK + c * 8;
+      va[j] = 2u * ((uint32_t)min(m0 + r, p.M - 1) * p.lda + kt_begin * BK + c * 8);
     }
   }
 #pragma unroll
@@ -377,22 +416,26 @@ gemm_bf16_dtl_kernel(const GemmBf16Params p) {
     const int blk = wave * B_LOADS + j;
     if (B_MC) {
       const int k = blk * (1024 / (BN * 2)) + lane / (BN / 8), pc = lane % (BN / 8), c = pc ^ (2 * (k & 3));
-      gb[j] = p.B + (size_t)(kt_begin * BK + k) * p.ldb + min(n0 + c * 8, p.N - 8);
+      vb[j] = 2u * ((uint32_t)(kt_begin * BK + k) * p.ldb + min(n0 + c * 8, p.N - 8));
     } else {
       const int r = blk * (512 / BK) + lane / CPR, pc = lane % CPR, c = pc ^ kc_key<BK>(r);
-      gb[j] = p.B + (size_t)min(n0 + r, p.N - 1) * p.ldb + kt_begin * BK + c * 8;
+      vb[j] = 2u * ((uint32_t)min(n0 + r, p.N - 1) * p.ldb + kt_begin * BK + c * 8);
     }
   }
-  const size_t a_step = A_MC ? (size_t)BK * p.lda : BK, b_step = B_MC ? (size_t)BK * p.ldb : BK;
+  const uint32_t a_step = 2u * (A_MC ? (uint32_t)BK * p.lda : BK), b_step = 2u * (B_MC ? (uint32_t)BK * p.ldb : BK);
 
-#define DP_DTL_ISSUE(t_)                                                                                              \
+  // Copies of k-tile t_ whose index j (A pieces first, then B) satisfies j % parts_ == part_.
+#define DP_DTL_ISSUE_PART(t_, part_, parts_)                                                                          \
   {                                                                                                                   \
     unsigned char* st_ = smem_raw + ((t_) % STAGES) * S::STAGE;                                                       \
     _Pragma("unroll") for (int j = 0; j < A_LOADS; ++j)                                                               \
-      async_copy_16B(ga[j] + (size_t)(t_) * a_step, st_ + (wave * A_LOADS + j) * 1024);                               \
+      if (j % (parts_) == (part_))                                                                                    \
+        async_copy_16B_buf(ra, va[j], (uint32_t)(t_) * a_step, st_ + (wave * A_LOADS + j) * 1024);                    \
     _Pragma("unroll") for (int j = 0; j < B_LOADS; ++j)                                                               \
-      async_copy_16B(gb[j] + (size_t)(t_) * b_step, st_ + S::A_BYTES + (wave * B_LOADS + j) * 1024);                  \
+      if ((A_LOADS + j) % (parts_) == (part_))                                                                        \
+        async_copy_16B_buf(rb, vb[j], (uint32_t)(t_) * b_step, st_ + S::A_BYTES + (wave * B_LOADS + j) * 1024);       \
   }
+#define DP_DTL_ISSUE(t_) DP_DTL_ISSUE_PART(t_, 0, 1)
 
   f32x16 acc[TM][TN];
 #pragma unroll
@@ -437,34 +480,63 @@ gemm_bf16_dtl_kernel(const GemmBf16Params p) {
   _Pragma("unroll") for (int i = 0; i < TM; ++i)                                                                      \
     _Pragma("unroll") for (int j2 = 0; j2 < TN; ++j2) acc[i][j2] = mfma32(fa[set_][i], fb[set_][j2], acc[i][j2]);
 
-  // Software pipeline.  Fragments are fetched one k-step ahead of the MFMAs that use them, also
-  // across the k-tile boundary: the wait + barrier that publishes k-tile t + 1 sits before the
-  // last MFMA group of k-tile t.  Passing that barrier also means every wave has finished reading
-  // k-tile t - 1, so its stage is refilled with k-tile t + STAGES - 1 right after it.  At the wait,
-  // the k-tiles t + 2 .. t + STAGES - 2 may still be in flight.
-  for (int t = 0; t < STAGES - 1 && t < nk; ++t) DP_DTL_ISSUE(t);
+  // Software pipeline.  All STAGES buffers are filled up front.  Fragments are fetched one k-step
+  // ahead of the MFMAs that use them, also across the k-tile boundary: before the last MFMA group
+  // of k-tile t every wave waits for its own fragment reads of that tile and for its share of
+  // k-tile t + 1 to land, then meets the others at a barrier.  Past it, k-tile t + 1 is visible to
+  // all and nobody reads k-tile t from LDS any more, so its buffer is free for k-tile t + STAGES.
+  // Those copies are not issued in one burst behind the barrier (all waves would queue up at the
+  // texture addresser together while the MFMA pipes drain) but spread over the k-steps of
+  // k-tile t + 1, a few per MFMA group; they still run STAGES - 2 k-tiles ahead of their use.
+  constexpr int PART_LAST = LOADS / KS;   // number of copies with index % KS == KS - 1
+  static_assert(STAGES >= 3 && STAGES <= 4 && 3 * LOADS < 64, "pipeline shape");
+  for (int t = 0; t < STAGES && t < nk; ++t) DP_DTL_ISSUE(t);
+  DP_TRACE(1);
   {
-    const int younger = min(nk - 1, STAGES - 2);
-    if (younger >= 2) wait_vmcnt<2 * LOADS>();
-    else if (younger == 1) wait_vmcnt<LOADS>();
+    const int y = min(nk, STAGES) - 1;
+    if (y >= 3) wait_vmcnt<3 * LOADS>();
+    else if (y == 2) wait_vmcnt<2 * LOADS>();
+    else if (y == 1) wait_vmcnt<LOADS>();
     else wait_vmcnt<0>();
   }
   barrier_nofence();
+  DP_TRACE(2);
   DP_DTL_FRAGS(0, 0, 0);
-  for (int t = 0; t < nk; ++t) {
+  // all k-tiles but the last: no branch between the fragment reads and the MFMAs, so the waits for
+  // LDS data stay exact (a merge of paths with different numbers of reads in flight would make the
+  // compiler wait for all of them)
+  for (int t = 0; t + 1 < nk; ++t) {
     const int st = t % STAGES;
+    const bool refill = t >= 1 && t - 1 + STAGES < nk;   // k-tile t - 1 + STAGES goes into the buffer k-tile t - 1 left
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
       if (ks + 1 < KS) {
         DP_DTL_FRAGS(st, ks + 1, (ks + 1) & 1);
-      } else if (t + 1 < nk) {
-        const int younger = min(nk - 2 - t, STAGES - 3);
-        if (younger >= 1) wait_vmcnt<LOADS>();
+      } else {
+        wait_lgkmcnt0();
+        // copies younger than k-tile t + 1 that may stay in flight: whole k-tiles t + 2 .. t - 2 + STAGES
+        // and the parts of k-tile t - 1 + STAGES issued so far (never more than are really there)
+        const int avail = nk - 2 - t;
+        if (STAGES == 4 && avail >= 2) wait_vmcnt<2 * LOADS - PART_LAST>();
+        else if (STAGES == 4 && avail == 1) wait_vmcnt<LOADS>();
+        else if (STAGES == 3 && avail >= 1) wait_vmcnt<LOADS - PART_LAST>();
         else wait_vmcnt<0>();
         barrier_nofence();
-        if (t + STAGES - 1 < nk) DP_DTL_ISSUE(t + STAGES - 1);
+        DP_TRACE(6 + t);
         DP_DTL_FRAGS((t + 1) % STAGES, 0, 0);
       }
+      __builtin_amdgcn_sched_barrier(0);
+      DP_DTL_MFMAS(ks & 1);
+      __builtin_amdgcn_sched_barrier(0);
+      if (refill) DP_DTL_ISSUE_PART(t - 1 + STAGES, ks, KS);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  }
+  {
+    const int st = (nk - 1) % STAGES;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      if (ks + 1 < KS) DP_DTL_FRAGS(st, ks + 1, (ks + 1) & 1);
       __builtin_amdgcn_sched_barrier(0);
       DP_DTL_MFMAS(ks & 1);
       __builtin_amdgcn_sched_barrier(0);
@@ -473,30 +545,14 @@ gemm_bf16_dtl_kernel(const GemmBf16Params p) {
 #undef DP_DTL_FRAGS
 #undef DP_DTL_MFMAS
 #undef DP_DTL_ISSUE
+#undef DP_DTL_ISSUE_PART
+  DP_TRACE(3);
   __syncthreads();   // every wave is done with the operand tiles before they are reused below
+  DP_TRACE(5);
 
   float* Cw = reinterpret_cast<float*>(smem_raw) + wave * 32 * S::C_LD;
-#pragma unroll
-  for (int i = 0; i < TM; ++i) {
-#pragma unroll
-    for (int j = 0; j < TN; ++j)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) Cw[(8 * (r >> 2) + 4 * g + (r & 3)) * S::C_LD + j * 32 + l32] = acc[i][j][r];
-    __syncthreads();
-#pragma unroll
-    for (int it = 0; it < 32 * WN / 8 / 64; ++it) {
-      const int id = it * 64 + lane;
-      const int lr = id / (WN / 8), lc = (id % (WN / 8)) * 8;
-      const int m = m0 + wm0 + i * 32 + lr, n = n0 + wn0 + lc;
-      if (m < p.M && n < p.N) {
-        float v[8];
-        *reinterpret_cast<f32x4*>(&v[0]) = *reinterpret_cast<const f32x4*>(&Cw[lr * S::C_LD + lc]);
-        *reinterpret_cast<f32x4*>(&v[4]) = *reinterpret_cast<const f32x4*>(&Cw[lr * S::C_LD + lc + 4]);
-        epi_vec8(p.epi, m, n, v);
-      }
-    }
-    __syncthreads();
-  }
+  wave_epilogue<TM, TN, WN, S::C_LD>(acc, Cw, p.epi, m0 + wm0, n0 + wn0, lane);
+  DP_TRACE(4);
 }
 
 // ------------------------------------------------------------------ fp32 FMA kernel
@@ -591,15 +647,23 @@ static int choose_splits(long tiles, int kt) {
 //    are enough tiles to fill the CUs, else 256x128, else 128x128;
 //  - dW = dy^T x (both operands read through the transposing LDS load): 128x128, two
 //    workgroups per CU.
-static int choose_cfg(int M, int N, int K, bool a_mc, bool b_mc) {
+static int choose_cfg(int M, int N, int K, bool a_mc, bool b_mc, bool dtl_ok) {
+  // Measured on MI355X over the GEMM shapes of the five workloads.  256x256 direct-to-LDS tiles
+  // (least LDS and L1 traffic per FLOP) whenever they still give every CU work; otherwise smaller
+  // tiles, direct-to-LDS for short contractions and for operands read without transposition.
   const long t256x256 = (long)((M + 255) / 256) * ((N + 255) / 256);
   const long t256x128 = (long)((M + 255) / 256) * ((N + 127) / 128);
-  if (a_mc) return 0;
+  const bool dtl32 = dtl_ok && K % 32 == 0, dtl64 = dtl_ok && K % 64 == 0;
+  if (a_mc) return (dtl32 && b_mc && t256x256 >= 80) ? 6 : 0;
   if (!b_mc) {
-    if (K % DTL_BK) return t256x128 >= 128 ? 1 : 0;
-    if (t256x128 >= 96 && K % 64 == 0) return 9;     // 256x128 tiles, 64-deep k-tiles, three stages
-    return 8;                                        // 128x128 tiles, 32-deep k-tiles, four stages
+    if (dtl32 && t256x256 >= 128) return (K <= 320 && N >= 512) ? 2 : 6;
+    if (dtl64 && t256x128 >= 128) return 9;
+    if (dtl64) return 10;
+    if (dtl32) return 8;
+    return t256x128 >= 128 ? 1 : 0;
   }
+  if (dtl32 && t256x256 >= 128) return 6;
+  if (dtl32 && K <= 1024) return 8;
   if (K >= 2 * N && t256x256 >= 128) return 2;
   return t256x128 >= 128 ? 1 : 0;
 }
@@ -665,6 +729,9 @@ static int launch_dtl_cfg(const GemmArgs& a, hipStream_t s) {
   p.M = a.M; p.N = a.N; p.K = a.K; p.lda = a.lda; p.ldb = a.ldb;
   p.epi = make_epi<bf16>(a);
   p.tiles_m = (a.M + BM - 1) / BM; p.tiles_n = (a.N + BN - 1) / BN;
+  if (!dtl_addressable(a)) return set_error(DP_EUNSUPPORTED, "gemm: operand too large for the forced direct-to-LDS configuration");
+  p.a_bytes = (uint32_t)(A_MC ? operand_extent_bytes(a.K, a.M, a.lda) : operand_extent_bytes(a.M, a.K, a.lda));
+  p.b_bytes = (uint32_t)(B_MC ? operand_extent_bytes(a.K, a.N, a.ldb) : operand_extent_bytes(a.N, a.K, a.ldb));
   const int kt = a.K / BK;
   int splits = 1;
   if (a.out_f32) {
@@ -735,7 +802,7 @@ int launch_gemm(const GemmArgs& a, hipStream_t s) {
     for (int x : elds) if (x % 8 || x < 8) return set_error(DP_EUNSUPPORTED, "gemm(bf16): epilogue leading dims must be multiples of 8");
     const void* eps[] = {a.out, a.out_f32, a.bias, a.pre_out, a.dact_pre, a.gate, a.residual, a.splitk_ws};
     for (const void* x : eps) if ((uintptr_t)x % 16) return set_error(DP_EALIGN, "gemm(bf16): epilogue operands must be 16-byte aligned");
-    const int cfg = (a.force_cfg > 0 && a.force_cfg <= kNumCfgs + 5) ? a.force_cfg - 1 : choose_cfg(a.M, a.N, a.K, a.a_mc != 0, a.b_mc != 0);
+    const int cfg = (a.force_cfg > 0 && a.force_cfg <= kNumCfgs + 7) ? a.force_cfg - 1 : choose_cfg(a.M, a.N, a.K, a.a_mc != 0, a.b_mc != 0, dtl_addressable(a));
     switch (cfg) {
       case 1: return launch_bf16_layout<256, 128, 64, 4, 2>(a, s);
       case 2: return launch_bf16_layout<256, 256, 64, 2, 4>(a, s);
@@ -747,6 +814,8 @@ int launch_gemm(const GemmArgs& a, hipStream_t s) {
       case 8: return launch_dtl_layout<128, 128, 32, 4, 2, 2>(a, s);
       case 9: return launch_dtl_layout<256, 128, 64, 3, 4, 2>(a, s);
       case 10: return launch_dtl_layout<128, 128, 64, 3, 2, 2>(a, s);
+      case 11: return launch_dtl_layout<256, 128, 64, 3, 2, 2>(a, s);   // one wave per SIMD, 128x64 per wave
+      case 12: return launch_dtl_layout<256, 256, 32, 4, 2, 2>(a, s);   // one wave per SIMD, 128x128 per wave
       default: break;
     }
     return launch_bf16_layout<128, 128, 64, 2, 2>(a, s);
