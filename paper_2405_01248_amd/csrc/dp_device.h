@@ -48,6 +48,22 @@ __device__ __forceinline__ bf16x8 frag_from_mc(const bf16* tile, int ld, int lan
   return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
 }
 
+// Fragment fetch from an unpadded [k][mn] tile (row length ld elements, a multiple of 128) whose
+// 16-byte chunks are permuted inside each k-row: chunk c of row k sits at chunk position
+// c ^ (4 * (k & 3)).  The four k-rows a 32-lane half of the transposing read touches then fall
+// into four different 64-byte bank groups, so the read is conflict-free without padding.
+// col0 (a multiple of 32) is the first column of the fragment, k0 (a multiple of 16) its first k.
+__device__ __forceinline__ int mc_swizzle(int chunk, int k) { return chunk ^ (4 * (k & 3)); }
+__device__ __forceinline__ bf16x8 frag_from_mc_swz(const bf16* tile, int ld, int k0, int col0, int lane) {
+  const int b = lane >> 4, j = lane & 15;
+  const int k = k0 + 8 * (b >> 1) + (j >> 2);
+  const int c = col0 / 8 + 2 * (b & 1) + ((j & 3) >> 1);
+  const bf16* q = tile + k * ld + mc_swizzle(c, k) * 8 + 4 * (j & 1);
+  bf16x4 lo = lds_read_tr(q);
+  bf16x4 hi = lds_read_tr(q + 4 * ld);
+  return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+}
+
 // Same, but the 8 contraction slots follow the accumulator row order of a 32x32 tile:
 // slot u is k = k0 + 8 * (u / 4) + 4g + (u % 4)  (16 k values: two groups of 8 per g).
 // This lets a C-layout register block (after conversion to bf16) act as the other operand.

@@ -134,4 +134,21 @@ int launch_cast_from_f32(int dtype, const float* in, void* out, size_t n, hipStr
 int launch_embed(int dtype, const int32_t* ids, const void* tok, const void* pos, void* x, int rows, int seq,
                  int d, int vocab, hipStream_t s);
 
+// dst[c, r] = src[r, c] for up to kTransposeMax dense row-major 16-bit matrices in one launch.
+// tile_start[i] is the number of 64 x 64 tiles of the matrices before matrix i (tile_start[n] = total).
+constexpr int kTransposeMax = 16;
+struct TransposeBatch {
+  int n;
+  const void* src[kTransposeMax]; void* dst[kTransposeMax];
+  int rows[kTransposeMax], cols[kTransposeMax];
+  int tile_start[kTransposeMax + 1];
+};
+inline void transpose_batch_add(TransposeBatch& tb, const void* src, void* dst, int rows, int cols) {
+  const int i = tb.n++;
+  tb.src[i] = src; tb.dst[i] = dst; tb.rows[i] = rows; tb.cols[i] = cols;
+  if (i == 0) tb.tile_start[0] = 0;
+  tb.tile_start[i + 1] = tb.tile_start[i] + ((rows + 63) / 64) * ((cols + 63) / 64);
+}
+int launch_transpose16_batch(const TransposeBatch& tb, hipStream_t s);
+
 }  // namespace dp

@@ -539,4 +539,56 @@ int launch_embed(int dtype, const int32_t* ids, const void* tok, const void* pos
   return hipGetLastError() == hipSuccess ? DP_OK : set_error(DP_EHIP, "embed launch failed");
 }
 
+// ---------------------------------------------------------------- batched 16-bit transpose
+// dst[c, r] = src[r, c] for up to kTransposeMax dense row-major matrices in one launch (the weight
+// matrices of a block, transposed once per backward pass so that dx = dy W runs as y = x W'^T on
+// contraction-contiguous operands).  One workgroup moves a 64 x 64 tile through LDS.
+__global__ void __launch_bounds__(256) transpose16_batch_kernel(const TransposeBatch tb) {
+  __shared__ uint16_t tile[64][66];
+  int mi = 0;
+  while (mi + 1 < tb.n && (int)blockIdx.x >= tb.tile_start[mi + 1]) ++mi;
+  const uint16_t* src = (const uint16_t*)tb.src[mi];
+  uint16_t* dst = (uint16_t*)tb.dst[mi];
+  const int R = tb.rows[mi], C = tb.cols[mi];
+  const int tcols = (C + 63) / 64;
+  const int t = blockIdx.x - tb.tile_start[mi];
+  const int r0 = (t / tcols) * 64, c0 = (t % tcols) * 64;
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int id = threadIdx.x + i * 256, r = id >> 3, c = (id & 7) * 8;
+    if (r0 + r < R && c0 + c < C) {
+      const u32x4 v = *reinterpret_cast<const u32x4*>(src + (size_t)(r0 + r) * C + c0 + c);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) { tile[r][c + 2 * e] = (uint16_t)(v[e] & 0xffff); tile[r][c + 2 * e + 1] = (uint16_t)(v[e] >> 16); }
+    }
+  }
+  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int id = threadIdx.x + i * 256, c = id >> 3, r = (id & 7) * 8;   // output row c0 + c, output columns r0 + r .. + 7
+    if (c0 + c < C && r0 + r < R) {
+      u32x4 v;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) v[e] = (uint32_t)tile[r + 2 * e][c] | ((uint32_t)tile[r + 2 * e + 1][c] << 16);
+      *reinterpret_cast<u32x4*>(dst + (size_t)(c0 + c) * R + r0 + r) = v;
+    }
+  }
+}
+int launch_transpose16_batch(const TransposeBatch& tb, hipStream_t s) {
+  if (tb.n <= 0 || tb.n > kTransposeMax) return set_error(DP_EINVAL, "transpose: bad matrix count");
+  for (int i = 0; i < tb.n; ++i) {
+    if (!tb.src[i] || !tb.dst[i] || tb.rows[i] <= 0 || tb.cols[i] <= 0) return set_error(DP_EINVAL, "transpose: bad matrix");
+    if ((tb.rows[i] % 8) || (tb.cols[i] % 8)) return set_error(DP_EUNSUPPORTED, "transpose: dims must be multiples of 8");
+    if (((uintptr_t)tb.src[i] % 16) || ((uintptr_t)tb.dst[i] % 16)) return set_error(DP_EALIGN, "transpose: operands must be 16-byte aligned");
+    const int tiles = ((tb.rows[i] + 63) / 64) * ((tb.cols[i] + 63) / 64);
+    if (tb.tile_start[i + 1] - tb.tile_start[i] != tiles || (i == 0 && tb.tile_start[0] != 0))
+      return set_error(DP_EINVAL, "transpose: tile table does not match the shapes");
+  }
+  double bytes = 0.0;
+  for (int i = 0; i < tb.n; ++i) bytes += 4.0 * tb.rows[i] * tb.cols[i];
+  KScope ks(KK_OTHER, 0.0, bytes, s, tb.n, 0, 0);
+  hipLaunchKernelGGL(transpose16_batch_kernel, dim3(tb.tile_start[tb.n]), dim3(256), 0, s, tb);
+  return hipGetLastError() == hipSuccess ? DP_OK : set_error(DP_EHIP, "transpose launch failed");
+}
+
 }  // namespace dp

@@ -180,9 +180,10 @@ static inline bool dtl_addressable(const GemmArgs& a) {
 
 template <int BM, int BN, int BK, int WGM, int WGN, bool A_MC, bool B_MC>
 struct GemmSmem {
-  // [rows][BK + 8] for contraction-contiguous operands; [BK][cols + 16] for the others
-  static constexpr int A_LD = A_MC ? (BM + 16) : (BK + 8);
-  static constexpr int B_LD = B_MC ? (BN + 16) : (BK + 8);
+  // [rows][BK + 8] for contraction-contiguous operands; [BK][cols], unpadded with permuted 16-byte
+  // chunks (mc_swizzle), for the others
+  static constexpr int A_LD = A_MC ? BM : (BK + 8);
+  static constexpr int B_LD = B_MC ? BN : (BK + 8);
   static constexpr int A_ELEMS = A_MC ? BK * A_LD : BM * A_LD;
   static constexpr int B_ELEMS = B_MC ? BK * B_LD : BN * B_LD;
   static constexpr int WN = BN / WGN;
@@ -276,12 +277,12 @@ gemm_bf16_kernel(const GemmBf16Params p) {
     bf16* bs_ = Bs + (buf_) * S::B_ELEMS;                                                     \
     _Pragma("unroll") for (int i = 0; i < A_PER; ++i) {                                       \
       const int id = tid + i * NT;                                                            \
-      if (A_MC) { const int kk = id / (BM / 8), c = id % (BM / 8); *reinterpret_cast<bf16x8*>(as_ + kk * S::A_LD + c * 8) = ((oka >> i) & 1) ? ra[i] : zero8(); } \
+      if (A_MC) { const int kk = id / (BM / 8), c = id % (BM / 8); *reinterpret_cast<bf16x8*>(as_ + kk * S::A_LD + mc_swizzle(c, kk) * 8) = ((oka >> i) & 1) ? ra[i] : zero8(); } \
       else      { const int r = id / (BK / 8), c = id % (BK / 8);  *reinterpret_cast<bf16x8*>(as_ + r * S::A_LD + c * 8) = ((oka >> i) & 1) ? ra[i] : zero8(); }  \
     }                                                                                         \
     _Pragma("unroll") for (int i = 0; i < B_PER; ++i) {                                       \
       const int id = tid + i * NT;                                                            \
-      if (B_MC) { const int kk = id / (BN / 8), c = id % (BN / 8); *reinterpret_cast<bf16x8*>(bs_ + kk * S::B_LD + c * 8) = ((okb >> i) & 1) ? rb[i] : zero8(); } \
+      if (B_MC) { const int kk = id / (BN / 8), c = id % (BN / 8); *reinterpret_cast<bf16x8*>(bs_ + kk * S::B_LD + mc_swizzle(c, kk) * 8) = ((okb >> i) & 1) ? rb[i] : zero8(); } \
       else      { const int r = id / (BK / 8), c = id % (BK / 8);  *reinterpret_cast<bf16x8*>(bs_ + r * S::B_LD + c * 8) = ((okb >> i) & 1) ? rb[i] : zero8(); }  \
     }                                                                                         \
   }
@@ -311,11 +312,11 @@ gemm_bf16_kernel(const GemmBf16Params p) {
 #define DP_GEMM_LOAD_FRAGS(ks_, set_)                                                                                   \
     {                                                                                                                     \
       _Pragma("unroll") for (int i = 0; i < TM; ++i) {                                                                   \
-        if (A_MC) fa[set_][i] = frag_from_mc(as + ((ks_) * 16) * S::A_LD + wm0 + i * 32, S::A_LD, lane);                 \
+        if (A_MC) fa[set_][i] = frag_from_mc_swz(as, S::A_LD, (ks_) * 16, wm0 + i * 32, lane);                 \
         else      fa[set_][i] = *reinterpret_cast<const bf16x8*>(as + (wm0 + i * 32 + l32) * S::A_LD + (ks_) * 16 + 8 * g); \
       }                                                                                                                   \
       _Pragma("unroll") for (int j = 0; j < TN; ++j) {                                                                   \
-        if (B_MC) fb[set_][j] = frag_from_mc(bs + ((ks_) * 16) * S::B_LD + wn0 + j * 32, S::B_LD, lane);                 \
+        if (B_MC) fb[set_][j] = frag_from_mc_swz(bs, S::B_LD, (ks_) * 16, wn0 + j * 32, lane);                 \
         else      fb[set_][j] = *reinterpret_cast<const bf16x8*>(bs + (wn0 + j * 32 + l32) * S::B_LD + (ks_) * 16 + 8 * g); \
       }                                                                                                                   \
     }
@@ -354,7 +355,7 @@ gemm_bf16_kernel(const GemmBf16Params p) {
 // are avoided by permuting 16-byte chunks inside a row (the permutation is applied through
 // the per-lane global address, and undone when fragments are read).
 //   K-contiguous operand:  tile [rows][32], chunk c of row r stored at c ^ ((r >> 2) & 3).
-//   K-strided operand:     tile [32][cols], chunk c of k-row k stored at c ^ (2 * (k & 3)).
+//   K-strided operand:     tile [BK][cols], chunk c of k-row k stored at c ^ (4 * (k & 3)).
 // Requires K % 32 == 0.  Rows / columns beyond M / N are fetched from a clamped address; they
 // only feed accumulators whose outputs are never stored.
 
@@ -404,7 +405,7 @@ gemm_bf16_dtl_kernel(const GemmBf16Params p) {
   for (int j = 0; j < A_LOADS; ++j) {
     const int blk = wave * A_LOADS + j;
     if (A_MC) {
-      const int k = blk * (1024 / (BM * 2)) + lane / (BM / 8), pc = lane % (BM / 8), c = pc ^ (2 * (k & 3));
+      const int k = blk * (1024 / (BM * 2)) + lane / (BM / 8), pc = lane % (BM / 8), c = mc_swizzle(pc, k);
       va[j] = 2u * ((uint32_t)(kt_begin * BK + k) * p.lda + min(m0 + c * 8, p.M - 8));
     } else {
       const int r = blk * (512 / BK) + lane / CPR, pc = lane % CPR, c = pc ^ kc_key<BK>(r);
@@ -415,7 +416,7 @@ gemm_bf16_dtl_kernel(const GemmBf16Params p) {
   for (int j = 0; j < B_LOADS; ++j) {
     const int blk = wave * B_LOADS + j;
     if (B_MC) {
-      const int k = blk * (1024 / (BN * 2)) + lane / (BN / 8), pc = lane % (BN / 8), c = pc ^ (2 * (k & 3));
+      const int k = blk * (1024 / (BN * 2)) + lane / (BN / 8), pc = lane % (BN / 8), c = mc_swizzle(pc, k);
       vb[j] = 2u * ((uint32_t)(kt_begin * BK + k) * p.ldb + min(n0 + c * 8, p.N - 8));
     } else {
       const int r = blk * (512 / BK) + lane / CPR, pc = lane % CPR, c = pc ^ kc_key<BK>(r);
@@ -453,11 +454,7 @@ gemm_bf16_dtl_kernel(const GemmBf16Params p) {
     const bf16* bs = reinterpret_cast<const bf16*>(smem_raw + (st_) * S::STAGE + S::A_BYTES);                         \
     _Pragma("unroll") for (int i = 0; i < TM; ++i) {                                                                  \
       if (A_MC) {                                                                                                     \
-        const int b = lane >> 4, j = lane & 15;                                                                       \
-        const int k = (ks_) * 16 + 8 * (b >> 1) + (j >> 2);                                                           \
-        const int c = (wm0 + i * 32) / 8 + 2 * (b & 1) + ((j & 3) >> 1);                                              \
-        const bf16* q = as + k * BM + ((c ^ (2 * (k & 3))) * 8) + 4 * (j & 1);                                        \
-        fa[set_][i] = __builtin_shufflevector(lds_read_tr(q), lds_read_tr(q + 4 * BM), 0, 1, 2, 3, 4, 5, 6, 7);       \
+        fa[set_][i] = frag_from_mc_swz(as, BM, (ks_) * 16, wm0 + i * 32, lane);                                       \
       } else {                                                                                                        \
         const int r = wm0 + i * 32 + l32;                                                                             \
         fa[set_][i] = *reinterpret_cast<const bf16x8*>(as + r * BK + (((2 * (ks_) + g) ^ kc_key<BK>(r)) * 8));        \
@@ -465,11 +462,7 @@ gemm_bf16_dtl_kernel(const GemmBf16Params p) {
     }                                                                                                                 \
     _Pragma("unroll") for (int j2 = 0; j2 < TN; ++j2) {                                                               \
       if (B_MC) {                                                                                                     \
-        const int b = lane >> 4, j = lane & 15;                                                                       \
-        const int k = (ks_) * 16 + 8 * (b >> 1) + (j >> 2);                                                           \
-        const int c = (wn0 + j2 * 32) / 8 + 2 * (b & 1) + ((j & 3) >> 1);                                             \
-        const bf16* q = bs + k * BN + ((c ^ (2 * (k & 3))) * 8) + 4 * (j & 1);                                        \
-        fb[set_][j2] = __builtin_shufflevector(lds_read_tr(q), lds_read_tr(q + 4 * BN), 0, 1, 2, 3, 4, 5, 6, 7);      \
+        fb[set_][j2] = frag_from_mc_swz(bs, BN, (ks_) * 16, wn0 + j2 * 32, lane);                                     \
       } else {                                                                                                        \
         const int r = wn0 + j2 * 32 + l32;                                                                            \
         fb[set_][j2] = *reinterpret_cast<const bf16x8*>(bs + r * BK + (((2 * (ks_) + g) ^ kc_key<BK>(r)) * 8));       \

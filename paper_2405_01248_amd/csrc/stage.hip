@@ -96,6 +96,7 @@ struct BwdScratch {
   void *dh, *da, *dqkv, *dq2, *dkv2, *dg, *dg2, *du, *dm_t;
   float *delta, *dm, *dcond_pre, *partial, *partial_side; size_t partial_bytes;
   float* dkv_ws; size_t dkv_ws_bytes;     // query-split partials of the cross-attention dK/dV kernel
+  void* wt;                               // transposed copies of every block's weight matrices (bf16 stages only)
 };
 
 static void plan_unet_block(Plan& p, const dp_stage& s, UnetBuf& u, bool with_xin) {
@@ -139,6 +140,28 @@ static size_t partial_need(const dp_stage& s) {
   return n;
 }
 
+// Weight matrices whose activation-gradient GEMM (dx = dy W) reads a transposed copy: for each, the
+// index in the block's parameter list and its shape [out features, in features].
+struct WtEntry { int param, rows, cols; };
+static int wt_entries(const dp_stage& s, WtEntry* e) {
+  const int d = s.d.d_model, ff = s.d.ff_inner;
+  if (s.d.kind == DP_BLOCK_UNET_XATTN_GEGLU) {
+    const WtEntry t[] = {{U_WQKV, 3 * d, d}, {U_WO1, d, d}, {U_WQ2, d, d}, {U_WO2, d, d}, {U_W1, 2 * ff, d}, {U_W2, d, ff}};
+    memcpy(e, t, sizeof(t));
+    return 6;
+  }
+  const WtEntry t[] = {{D_WQKV, 3 * d, d}, {D_WO, d, d}, {D_FC1_W, ff, d}, {D_FC2_W, d, ff}};
+  memcpy(e, t, sizeof(t));
+  return 4;
+}
+static size_t wt_block_elems(const dp_stage& s) {
+  WtEntry e[8];
+  const int n = wt_entries(s, e);
+  size_t t = 0;
+  for (int i = 0; i < n; ++i) t += ((size_t)e[i].rows * e[i].cols + 127) / 128 * 128;
+  return t;
+}
+
 static void plan_bwd_scratch(Plan& p, const dp_stage& s, BwdScratch& b) {
   const size_t T = s.T, Tc = s.Tc, d = s.d.d_model, ff = s.d.ff_inner, es = s.es, B = s.d.batch;
   const bool unet = s.d.kind == DP_BLOCK_UNET_XATTN_GEGLU;
@@ -162,6 +185,7 @@ static void plan_bwd_scratch(Plan& p, const dp_stage& s, BwdScratch& b) {
     b.du = p.take(T * ff * es);         // df1
     b.dm = (float*)p.take(B * 6 * d * 4); b.dm_t = p.take(B * 6 * d * es); b.dcond_pre = (float*)p.take(B * d * 4);
   }
+  b.wt = s.es == 2 ? p.take((size_t)s.d.n_blocks * wt_block_elems(s) * s.es) : nullptr;
   b.partial_bytes = partial_need(s);
   b.partial = (float*)p.take(b.partial_bytes);
   b.partial_side = (float*)p.take(b.partial_bytes);   // split-K / column-sum partials of the side stream
@@ -202,10 +226,13 @@ static GemmArgs gemm_fwd(int dtype, const void* x, int M, int K, const void* W, 
   g.A = x; g.B = W; g.M = M; g.N = N; g.K = K; g.lda = K; g.ldb = K; g.out = y; g.ldo = N; g.bias = bias;
   return g;
 }
-// dx[M,K] = dy[M,N] W[N,K]
-static GemmArgs gemm_dx(int dtype, const void* dy, int M, int N, const void* W, int K, void* dx) {
+// dx[M,K] = dy[M,N] W[N,K]; when a transposed copy Wt[K,N] exists the product runs on it, with both
+// operands contraction-contiguous (no transposing LDS reads, which are the slow ones)
+static GemmArgs gemm_dx(int dtype, const void* dy, int M, int N, const void* W, const void* Wt, int K, void* dx) {
   GemmArgs g = gemm_base(dtype);
-  g.A = dy; g.B = W; g.M = M; g.N = K; g.K = N; g.lda = N; g.ldb = K; g.b_mc = 1; g.out = dx; g.ldo = K;
+  g.A = dy; g.M = M; g.N = K; g.K = N; g.lda = N; g.out = dx; g.ldo = K;
+  if (Wt) { g.B = Wt; g.ldb = N; g.b_mc = 0; }
+  else { g.B = W; g.ldb = K; g.b_mc = 1; }
   return g;
 }
 // dW[N,K] (+)= dy[M,N]^T x[M,K]   (fp32)
@@ -318,7 +345,7 @@ static int unet_block_fwd(const dp_stage& s, const void* const* P, const float* 
 // copy).  dx2 goes to pair c ^ 1, dx1 to pair c, the block's dx to pair c ^ 1 again or, for the
 // first block of the stage, to dx_final (storage dtype only).  Weight- and bias-gradient work runs
 // in side-stream batches.
-static int unet_block_bwd(const dp_stage& s, const void* const* P, void* const* G, int acc, const void* ctx, GradPair dy, int c,
+static int unet_block_bwd(const dp_stage& s, const void* const* P, const void* const* WT, void* const* G, int acc, const void* ctx, GradPair dy, int c,
                           void* dx_final, UnetBuf& u, BwdScratch& b, Side& sd, SideReads& rd) {
   const int dt = s.d.dtype, T = s.T, Tc = s.Tc, d = s.d.d_model, inner = s.d.ff_inner, dc = s.d.ctx_dim;
   const size_t es = s.es;
@@ -339,7 +366,7 @@ static int unet_block_bwd(const dp_stage& s, const void* const* P, void* const* 
     DP_TRY(db(dy.h, d, T, U_B2, q));
     rd.pair[c] = sd.end();
   }
-  DP_TRY(launch_gemm(gemm_dx(dt, dy.h, T, d, P[U_W2], inner, b.dg), st));
+  DP_TRY(launch_gemm(gemm_dx(dt, dy.h, T, d, P[U_W2], WT[U_W2], inner, b.dg), st));
   sd.wait(rd.du);
   DP_TRY(launch_geglu_bwd(dt, b.dg, u.u, b.du, T, inner, st));
   {
@@ -348,7 +375,7 @@ static int unet_block_bwd(const dp_stage& s, const void* const* P, void* const* 
     DP_TRY(db(b.du, 2 * inner, T, U_B1, q));
     rd.du = sd.end();
   }
-  DP_TRY(launch_gemm(gemm_dx(dt, b.du, T, 2 * inner, P[U_W1], d, b.dh), st));
+  DP_TRY(launch_gemm(gemm_dx(dt, b.du, T, 2 * inner, P[U_W1], WT[U_W1], d, b.dh), st));
   LnBwdArgs lb; memset(&lb, 0, sizeof(lb));
   lb.dtype = dt; lb.rows = T; lb.d = d; lb.accumulate = acc; lb.partial = b.partial; lb.partial_bytes = b.partial_bytes;
   lb.dy = b.dh; lb.x = u.x2; lb.mean = u.mean3; lb.rstd = u.rstd3; lb.gamma = P[U_LN3_G]; lb.dres = dy.f; set_dx(lb, dx2);
@@ -362,7 +389,7 @@ static int unet_block_bwd(const dp_stage& s, const void* const* P, void* const* 
     DP_TRY(db(dx2.h, d, T, U_BO2, q));
     rd.pair[c ^ 1] = sd.end();
   }
-  DP_TRY(launch_gemm(gemm_dx(dt, dx2.h, T, d, P[U_WO2], d, b.da), st));
+  DP_TRY(launch_gemm(gemm_dx(dt, dx2.h, T, d, P[U_WO2], WT[U_WO2], d, b.da), st));
   AttnArgs a = attn_base(s);
   a.Nk = s.d.ctx_tokens; a.q = u.q2; a.ldq = d; a.k = u.kv2; a.v = at(u.kv2, d, es); a.ldk = a.ldv = 2 * d;
   a.o = u.a2; a.ldo = d; a.lse = u.lse2; a.dout = b.da; a.lddo = d; a.delta = b.delta;
@@ -376,7 +403,7 @@ static int unet_block_bwd(const dp_stage& s, const void* const* P, void* const* 
     DP_TRY(dw(b.dkv2, Tc, 2 * d, ctx, dc, U_WKV2, q));
     rd.dq2 = sd.end();
   }
-  DP_TRY(launch_gemm(gemm_dx(dt, b.dq2, T, d, P[U_WQ2], d, b.dh), st));
+  DP_TRY(launch_gemm(gemm_dx(dt, b.dq2, T, d, P[U_WQ2], WT[U_WQ2], d, b.dh), st));
   lb.dy = b.dh; lb.x = u.x1; lb.mean = u.mean2; lb.rstd = u.rstd2; lb.gamma = P[U_LN2_G]; lb.dres = dx2.f; set_dx(lb, dx1);
   lb.dgamma = gf(U_LN2_G); lb.dbeta = gf(U_LN2_B);
   sd.wait(rd.pair[c]);
@@ -388,7 +415,7 @@ static int unet_block_bwd(const dp_stage& s, const void* const* P, void* const* 
     DP_TRY(db(dx1.h, d, T, U_BO1, q));
     rd.pair[c] = sd.end();
   }
-  DP_TRY(launch_gemm(gemm_dx(dt, dx1.h, T, d, P[U_WO1], d, b.da), st));
+  DP_TRY(launch_gemm(gemm_dx(dt, dx1.h, T, d, P[U_WO1], WT[U_WO1], d, b.da), st));
   a = attn_base(s);
   a.Nk = s.d.tokens; a.q = u.qkv; a.k = at(u.qkv, d, es); a.v = at(u.qkv, 2 * d, es); a.ldq = a.ldk = a.ldv = 3 * d;
   a.o = u.a1; a.ldo = d; a.lse = u.lse1; a.dout = b.da; a.lddo = d; a.delta = b.delta;
@@ -400,7 +427,7 @@ static int unet_block_bwd(const dp_stage& s, const void* const* P, void* const* 
     DP_TRY(dw(b.dqkv, T, 3 * d, u.h1, d, U_WQKV, q));
     rd.dqkv = sd.end();
   }
-  DP_TRY(launch_gemm(gemm_dx(dt, b.dqkv, T, 3 * d, P[U_WQKV], d, b.dh), st));
+  DP_TRY(launch_gemm(gemm_dx(dt, b.dqkv, T, 3 * d, P[U_WQKV], WT[U_WQKV], d, b.dh), st));
   lb.dy = b.dh; lb.x = u.xin; lb.mean = u.mean1; lb.rstd = u.rstd1; lb.gamma = P[U_LN1_G]; lb.dres = dx1.f;
   if (dx_final) { lb.dx = dx_final; lb.dx32 = nullptr; } else set_dx(lb, out);
   lb.dgamma = gf(U_LN1_G); lb.dbeta = gf(U_LN1_B);
@@ -442,7 +469,7 @@ static int dit_block_fwd(const dp_stage& s, const void* const* P, const float* x
 }
 
 // dy lives in pair c; dx1 goes to pair c ^ 1 and the block's dx back to pair c (or dx_final).
-static int dit_block_bwd(const dp_stage& s, const void* const* P, void* const* G, int acc, const void* cond, const void* sc_in,
+static int dit_block_bwd(const dp_stage& s, const void* const* P, const void* const* WT, void* const* G, int acc, const void* cond, const void* sc_in,
                          GradPair dy, int c, void* dx_final, float* d_cond, int dcond_acc, DitBuf& u, BwdScratch& b, Side& sd,
                          SideReads& rd) {
   const int dt = s.d.dtype, T = s.T, d = s.d.d_model, ff = s.d.ff_inner, B = s.d.batch, N = s.d.tokens;
@@ -466,7 +493,7 @@ static int dit_block_bwd(const dp_stage& s, const void* const* P, void* const* G
     DP_TRY(db(b.dg, d, T, D_FC2_B, q));
     rd.dg = sd.end();
   }
-  GemmArgs g = gemm_dx(dt, b.dg, T, d, P[D_FC2_W], ff, b.du);
+  GemmArgs g = gemm_dx(dt, b.dg, T, d, P[D_FC2_W], WT[D_FC2_W], ff, b.du);
   g.dact_pre = u.f1; g.ld_dact = ff; g.dact_kind = s.d.gelu_tanh ? 2 : 1;
   sd.wait(rd.du);
   DP_TRY(launch_gemm(g, st));
@@ -476,7 +503,7 @@ static int dit_block_bwd(const dp_stage& s, const void* const* P, void* const* G
     DP_TRY(db(b.du, ff, T, D_FC1_B, q));
     rd.du = sd.end();
   }
-  DP_TRY(launch_gemm(gemm_dx(dt, b.du, T, ff, P[D_FC1_W], d, b.dh), st));
+  DP_TRY(launch_gemm(gemm_dx(dt, b.du, T, ff, P[D_FC1_W], WT[D_FC1_W], d, b.dh), st));
   LnBwdArgs lb; memset(&lb, 0, sizeof(lb));
   lb.dtype = dt; lb.rows = T; lb.d = d; lb.partial = b.partial; lb.partial_bytes = b.partial_bytes;
   lb.mod_ld = 6 * d; lb.rows_per_batch = N; lb.dmod_ld = 6 * d;
@@ -492,7 +519,7 @@ static int dit_block_bwd(const dp_stage& s, const void* const* P, void* const* G
     DP_TRY(db(b.dg2, d, T, D_BO, q));
     rd.dg2 = sd.end();
   }
-  DP_TRY(launch_gemm(gemm_dx(dt, b.dg2, T, d, P[D_WO], d, b.da), st));
+  DP_TRY(launch_gemm(gemm_dx(dt, b.dg2, T, d, P[D_WO], WT[D_WO], d, b.da), st));
   AttnArgs a = attn_base(s);
   a.Nk = N; a.q = u.qkv; a.k = at(u.qkv, d, es); a.v = at(u.qkv, 2 * d, es); a.ldq = a.ldk = a.ldv = 3 * d;
   a.o = u.a; a.ldo = d; a.lse = u.lse; a.dout = b.da; a.lddo = d; a.delta = b.delta;
@@ -505,7 +532,7 @@ static int dit_block_bwd(const dp_stage& s, const void* const* P, void* const* G
     DP_TRY(db(b.dqkv, 3 * d, T, D_BQKV, q));
     rd.dqkv = sd.end();
   }
-  DP_TRY(launch_gemm(gemm_dx(dt, b.dqkv, T, 3 * d, P[D_WQKV], d, b.dh), st));
+  DP_TRY(launch_gemm(gemm_dx(dt, b.dqkv, T, 3 * d, P[D_WQKV], WT[D_WQKV], d, b.dh), st));
   lb.dy = b.dh; lb.x = u.xin; lb.mean = u.mean1; lb.rstd = u.rstd1; lb.scale = at(u.m, d, es); lb.dres = dx1.f;
   if (dx_final) { lb.dx = dx_final; lb.dx32 = nullptr; } else set_dx(lb, out);
   lb.dscale = b.dm + d; lb.dshift = b.dm;
@@ -578,7 +605,7 @@ static int run_stage_fwd(dp_stage* s, const void* const* params, const void* x, 
 static int ensure_side_stream(dp_stage* s) {
   if (s->side) return DP_OK;
   if (hipStreamCreateWithFlags(&s->side, hipStreamNonBlocking) != hipSuccess) { s->side = nullptr; return set_error(DP_EHIP, "hipStreamCreate failed"); }
-  s->events.resize((size_t)s->d.n_blocks * 16 + 8);
+  s->events.resize((size_t)s->d.n_blocks * 24 + 8);
   for (auto& e : s->events)
     if (hipEventCreateWithFlags(&e, hipEventDisableTiming) != hipSuccess) return set_error(DP_EHIP, "hipEventCreate failed");
   return DP_OK;
@@ -602,17 +629,43 @@ static int run_stage_bwd(dp_stage* s, const void* const* params, const void* dy,
   DP_TRY(launch_cast_to_f32(s->d.dtype, dy, bs.r[1].f, (size_t)s->T * s->d.d_model, st));
   GradPair cur{bs.r[1].f, const_cast<void*>(dy)};
   int ci = 1;   // index of the pair whose fp32 buffer holds cur
+  // Transposed weight copies: one launch per block on the side stream, issued one block ahead of
+  // the block that uses them; the main stream waits for a block's copies right before that block.
+  std::vector<const void*> wt_ptrs((size_t)nb * s->per_block, nullptr);
+  std::vector<int> wt_batch(nb, 0);
+  auto transpose_block = [&](int b) -> int {
+    WtEntry we[8];
+    const int nw = wt_entries(*s, we);
+    TransposeBatch tb; tb.n = 0;
+    size_t off = (size_t)b * wt_block_elems(*s);
+    for (int i = 0; i < nw; ++i) {
+      void* dst = at(bs.wt, off, s->es);
+      transpose_batch_add(tb, params[(size_t)b * s->per_block + we[i].param], dst, we[i].rows, we[i].cols);
+      wt_ptrs[(size_t)b * s->per_block + we[i].param] = dst;
+      off += ((size_t)we[i].rows * we[i].cols + 127) / 128 * 128;
+    }
+    hipStream_t q = sd.begin();
+    DP_TRY(launch_transpose16_batch(tb, q));
+    wt_batch[b] = sd.end();
+    return DP_OK;
+  };
+  if (bs.wt) DP_TRY(transpose_block(nb - 1));
   for (int b = nb - 1; b >= 0; --b) {
     DP_TRY(record(ph, nb - 1 - b, st));
+    if (bs.wt) {
+      if (b > 0) DP_TRY(transpose_block(b - 1));
+      sd.wait(wt_batch[b]);
+    }
     const void* const* P = params + (size_t)b * s->per_block;
+    const void* const* WT = wt_ptrs.data() + (size_t)b * s->per_block;
     void* const* G = dparams + (size_t)b * s->per_block;
     void* dx_final = b == 0 ? dx : nullptr;
     if (unet) {
-      DP_TRY(unet_block_bwd(*s, P, G, acc, cc, cur, ci, dx_final, sp.ub[b], bs, sd, rd));
+      DP_TRY(unet_block_bwd(*s, P, WT, G, acc, cc, cur, ci, dx_final, sp.ub[b], bs, sd, rd));
       ci ^= 1;
       cur = bs.r[ci];
     } else {
-      DP_TRY(dit_block_bwd(*s, P, G, acc, cc, sp.sc_in, cur, ci, dx_final, (float*)d_cond, b != nb - 1, sp.db[b], bs, sd, rd));
+      DP_TRY(dit_block_bwd(*s, P, WT, G, acc, cc, sp.sc_in, cur, ci, dx_final, (float*)d_cond, b != nb - 1, sp.db[b], bs, sd, rd));
       cur = bs.r[ci];
     }
     if (ph && ph->ev) sd.wait(sd.issued);      // per-block timing: charge a block's side work to that block
