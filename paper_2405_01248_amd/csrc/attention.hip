@@ -168,20 +168,24 @@ __global__ void __launch_bounds__(256, (QT == 1 && DHP == 64) ? 3 : 2) attn_fwd_
     for (int j = 0; j < QT; ++j) {
       const int qi = q0 + 32 * j + l32;
       const bool edge = key_edge || (CAUSAL && kt * 64 + 63 > q0 + 32 * j);
+      // masking only in tiles that cross the end of the keys or the causal diagonal (one wave-uniform
+      // branch around a block of selects; a test per element would be compiled into a branch per element)
+      if (edge) {
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const int key = kt * 64 + 32 * t + acc_row(r, g);
+            const bool dead = key >= p.Nk || (CAUSAL && key > qi);
+            s[j][t][r] = dead ? -INFINITY : s[j][t][r];
+          }
+      }
       // running maximum over raw scores (the scale is positive, so it commutes with max)
       float mx = -INFINITY;
 #pragma unroll
       for (int t = 0; t < 2; ++t)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          float v = s[j][t][r];
-          if (edge) {
-            const int key = kt * 64 + 32 * t + acc_row(r, g);
-            if (key >= p.Nk || (CAUSAL && key > qi)) v = -INFINITY;
-            s[j][t][r] = v;
-          }
-          mx = fmaxf(mx, v);
-        }
+        for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[j][t][r]);
       mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
       mx = fmaxf(m[j], mx * p.scale_log2);                 // m[j] is kept in the scaled (log2) domain
       const float mref = (mx == -INFINITY) ? 0.f : mx;
@@ -301,7 +305,21 @@ __global__ void __launch_bounds__(256, DHP == 64 ? 3 : 2) attn_bwd_dq_bf16_kerne
   }
   const size_t sidx = ((size_t)b * p.H + h) * p.Nq + qi;
   const float lse2 = qok ? p.lse[sidx] * LOG2E : INFINITY;
-  const float dlt = qok ? p.delta[sidx] : 0.f;
+  // delta = rowsum(dO * O), computed here from the dO fragments the lane already holds (its half of
+  // the head dimension; lane ^ 32 holds the other half) and stored for the dK/dV kernel, which runs
+  // after this one on the same stream
+  float dlt = 0.f;
+  {
+    const bf16* orow = (const bf16*)p.o + ((size_t)b * p.Nq + qi) * p.ldo + h * p.dh;
+#pragma unroll
+    for (int c = 0; c < KC; ++c) {
+      const bf16x8 of = ld8(orow + 16 * c + 8 * g, qok && 16 * c + 8 * g < p.dh);
+#pragma unroll
+      for (int u = 0; u < 8; ++u) dlt = fmaf((float)of[u], (float)dof[c][u], dlt);
+    }
+    dlt += __shfl_xor(dlt, 32, 64);
+    if (qok && g == 0) p.delta[sidx] = dlt;
+  }
 
   f32x16 acc[DT];
 #pragma unroll
@@ -324,7 +342,8 @@ __global__ void __launch_bounds__(256, DHP == 64 ? 3 : 2) attn_bwd_dq_bf16_kerne
       lk.load(kb, p.ldk, (kt + 1) * 64, p.Nk, p.dh, tid);
       lv.load(vb, p.ldv, (kt + 1) * 64, p.Nk, p.dh, tid);
     }
-    const bool edge = kt * 64 + 64 > p.Nk;
+    // Keys past Nk need no masking here: their K and V rows are zero in LDS, so dP = 0 and the
+    // finite dS they get multiplies a zero K row in the dQ product.
 #pragma unroll
     for (int t = 0; t < 2; ++t) {
       f32x16 s, dp;
@@ -339,8 +358,7 @@ __global__ void __launch_bounds__(256, DHP == 64 ? 3 : 2) attn_bwd_dq_bf16_kerne
       }
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        float pr = __builtin_amdgcn_exp2f(s[r] * p.scale_log2 - lse2);
-        if (edge && kt * 64 + 32 * t + acc_row(r, g) >= p.Nk) pr = 0.f;
+        const float pr = __builtin_amdgcn_exp2f(fmaf(s[r], p.scale_log2, -lse2));
         s[r] = pr * (dp[r] - dlt);
       }
 #pragma unroll
@@ -464,8 +482,9 @@ __global__ void __launch_bounds__(256, DHP == 64 ? 2 : 1) attn_bwd_dkv_bf16_kern
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
           const int r = 4 * r4 + u;
-          float pr = __builtin_amdgcn_exp2f(s[r] * p.scale_log2 - l4[u]);
-          if (!kok) pr = 0.f;
+          // a lane whose key is past Nk computes garbage that stays in its own accumulator columns,
+          // which are never stored; queries past Nq have lse = +inf, hence pr = 0
+          const float pr = __builtin_amdgcn_exp2f(fmaf(s[r], p.scale_log2, -l4[u]));
           s[r] = pr;
           ds[r] = pr * (dp[r] - d4[u]);
         }
@@ -727,7 +746,6 @@ int launch_attn_bwd(const AttnArgs& a, hipStream_t s) {
   const size_t pairs = (size_t)a.B * a.Nq * a.H;
   const dim3 dgrid((pairs * 8 + 255) / 256);
   if (a.dtype == BF16) {
-    hipLaunchKernelGGL(attn_delta_kernel<bf16>, dgrid, dim3(256), 0, s, (const bf16*)a.o, a.ldo, (const bf16*)a.dout, a.lddo, a.delta, a.B, a.H, a.Nq, a.d_head);
     dim3 gq(((a.Nq + 127) / 128) * a.B * a.H), gk(((a.Nk + 127) / 128) * a.B * a.H);
     // algorithmic backward work = 2x forward, split evenly between the two kernels for accounting
     const double fl = 4.0 * a.B * a.H * (double)a.Nq * a.Nk * a.d_head;
