@@ -177,6 +177,8 @@ def main():
     ap.add_argument("--serial", action="store_true",
                     help="issue the backward's weight-gradient kernels in program order instead of on the side stream "
                          "(per-kernel profiling; the default overlaps them)")
+    ap.add_argument("--fusion", type=int, default=None, choices=[0, 1, 2, 3],
+                    help="GeGLU epilogue-fusion mask of the stage (library default when omitted); for A/B timing")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives are part of it); use --gpus 1", file=sys.stderr)
@@ -195,6 +197,8 @@ def main():
         ds = DeviceStage(cfg, si.make_stage_inputs(cfg, seed=0))
         if args.serial:
             ds.stage.set_overlap(False)
+        if args.fusion is not None:
+            ds.stage.set_fusion(args.fusion)
         sec = timed(ds.step, steps, warmup)
         fl = stage_flops(cfg)
         return ds, {"samples_per_s": cfg.batch / sec, "ms_per_step": sec * 1e3, "tflops": fl / sec / 1e12,

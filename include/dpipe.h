@@ -76,6 +76,14 @@ int dp_stage_param_shape(const dp_stage* st, int idx, int64_t shape[2], const ch
  * (used when single kernels are to be timed); results are bit-identical either way.  Default 1. */
 int dp_stage_set_overlap(dp_stage* st, int enabled);
 
+/* Epilogue fusions of the U-Net block's GeGLU feed-forward (bf16 stages; the fp32 path never fuses).
+ * mask bit 0: the gated activation is applied in the epilogue of the projection GEMM (forward);
+ * bit 1: its backward is applied in the epilogue of the activation-gradient GEMM of the second
+ * feed-forward layer, whose raw product then never reaches memory.  Unfused, the same arithmetic
+ * runs as separate elementwise kernels; forward results are bit-identical, backward results
+ * differ by the rounding of the raw product to bf16 that the fused path skips.  Default 3. */
+int dp_stage_set_fusion(dp_stage* st, int mask);
+
 /* Bytes of caller-provided workspace [device].  save_for_bwd = 1: saved activations of all
  * blocks plus backward scratch (pass the same workspace to stage_bwd).  0: scratch for a
  * forward that keeps nothing (the self-conditioning pass).  The workspace must be

@@ -48,7 +48,7 @@ class KernelTime(C.Structure):
 KERNEL_KINDS = {0: "gemm_nt", 1: "gemm_nn", 2: "gemm_tn", 3: "attn_fwd", 4: "attn_bwd_dq", 5: "attn_bwd_dkv", 6: "ln_fwd",
                 7: "ln_bwd", 8: "geglu_fwd", 9: "geglu_bwd", 10: "reduce", 11: "other", 12: "gemm_f32", 13: "attn_f32"}
 
-EXPORTS = ["dp_stage_create", "dp_stage_destroy", "dp_stage_set_overlap", "dp_stage_param_count", "dp_stage_param_shape", "dp_stage_workspace_bytes",
+EXPORTS = ["dp_stage_create", "dp_stage_destroy", "dp_stage_set_overlap", "dp_stage_set_fusion", "dp_stage_param_count", "dp_stage_param_shape", "dp_stage_workspace_bytes",
            "stage_fwd", "stage_bwd", "dp_encoder_create", "dp_encoder_destroy", "dp_encoder_param_count",
            "dp_encoder_param_shape", "dp_encoder_workspace_bytes", "encoder_fwd_partial", "dp_stage_profile",
            "dp_encoder_profile", "dp_ktime_begin", "dp_ktime_end", "dp_last_error", "dp_op_gemm", "dp_op_gemm_workspace_bytes",
@@ -74,6 +74,7 @@ def load_library():
     lib.dp_stage_create.argtypes = [C.POINTER(StageDesc), pp]
     lib.dp_stage_destroy.argtypes = [vp]; lib.dp_stage_destroy.restype = None
     lib.dp_stage_set_overlap.argtypes = [vp, i]
+    lib.dp_stage_set_fusion.argtypes = [vp, i]
     lib.dp_stage_param_count.argtypes = [vp]
     lib.dp_stage_param_shape.argtypes = [vp, i, C.POINTER(C.c_int64), C.POINTER(C.c_char_p)]
     lib.dp_stage_workspace_bytes.argtypes = [vp, i]; lib.dp_stage_workspace_bytes.restype = sz
@@ -169,6 +170,9 @@ class Stage(_Handle):
 
     def set_overlap(self, enabled: bool):
         _check(load_library().dp_stage_set_overlap(self._h, int(enabled)))
+
+    def set_fusion(self, mask: int):
+        _check(load_library().dp_stage_set_fusion(self._h, int(mask)))
 
     def param_specs(self):
         return self._specs("dp_stage_param_count", "dp_stage_param_shape")

@@ -148,9 +148,29 @@ template <> __device__ __forceinline__ bf16 from_f<bf16>(float v) { return (bf16
 // ---- activations (fp32) ----------------------------------------------------
 enum Act { ACT_NONE = 0, ACT_GELU_ERF = 1, ACT_GELU_TANH = 2, ACT_QUICK_GELU = 3 };
 
-__device__ __forceinline__ float gelu_erf_f(float z) { return 0.5f * z * (1.0f + erff(z * 0.70710678118654752f)); }
+// erf by the rational-times-Gaussian formula 7.1.26 of Abramowitz & Stegun (absolute error below 1.5e-7,
+// i.e. about one fp32 ulp of the values it is added to here): one reciprocal, one exponential and a
+// degree-5 Horner chain instead of the library routine's branches.  ex2 receives exp(-x^2) for callers
+// that need the Gaussian as well.
+__device__ __forceinline__ float erf_fast(float x, float& ex2) {
+  const float ax = fabsf(x);
+  const float t = __builtin_amdgcn_rcpf(fmaf(0.3275911f, ax, 1.0f));
+  float poly = fmaf(1.061405429f, t, -1.453152027f);
+  poly = fmaf(poly, t, 1.421413741f);
+  poly = fmaf(poly, t, -0.284496736f);
+  poly = fmaf(poly, t, 0.254829592f);
+  ex2 = __builtin_amdgcn_exp2f(-1.4426950408889634f * ax * ax);
+  const float r = fmaf(-poly * t, ex2, 1.0f);
+  return copysignf(r, x);
+}
+__device__ __forceinline__ float gelu_erf_f(float z) {
+  float e;
+  return 0.5f * z * (1.0f + erf_fast(z * 0.70710678118654752f, e));
+}
 __device__ __forceinline__ float gelu_erf_grad_f(float z) {
-  return 0.5f * (1.0f + erff(z * 0.70710678118654752f)) + z * __expf(-0.5f * z * z) * 0.3989422804014327f;
+  float e;   // exp(-z^2 / 2), the Gaussian of the density term
+  const float erfv = erf_fast(z * 0.70710678118654752f, e);
+  return 0.5f * (1.0f + erfv) + z * e * 0.3989422804014327f;
 }
 __device__ __forceinline__ float tanh_fast(float x) {
   // tanh(x) = 1 - 2 / (exp(2x) + 1); exact limits at +-inf, no cancellation issue at the tolerance used

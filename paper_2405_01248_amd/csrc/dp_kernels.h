@@ -40,8 +40,17 @@ struct GemmArgs {
   int out_fused_f32;         // `out` receives the fused-epilogue result as fp32 instead of the storage dtype
   float* splitk_ws; size_t splitk_ws_bytes;
   int force_cfg;             // 0 = choose by shape; 1 + index forces a tile configuration (measurement only)
+  // GeGLU fused into the epilogue (bf16 only; bias is the only other epilogue term allowed):
+  //   geglu = 1 (forward): B [2 * geglu_inner, K] and bias are the [value | gate] projection, N = 2 * geglu_inner.
+  //     pre_out [M, N] (optional) receives the projection u, out [M, geglu_inner] = value * gelu(gate), both taken
+  //     from u as rounded to the storage dtype.  Needs gemm_geglu_fwd_supported().
+  //   geglu = 2 (backward): N = geglu_inner, the product is dg; out [M, 2 * geglu_inner] =
+  //     [dg * gelu(gate) | dg * value * gelu'(gate)] with value / gate read from geglu_u [M, 2 * geglu_inner].
+  int geglu, geglu_inner;
+  const void* geglu_u; int ld_geglu;
 };
 int launch_gemm(const GemmArgs& a, hipStream_t s);
+bool gemm_geglu_fwd_supported(const GemmArgs& a);
 size_t gemm_splitk_ws_bytes(int M, int N, int K);   // upper bound for out_f32 GEMMs
 
 // ---------------------------------------------------------------- attention

@@ -38,6 +38,7 @@ struct EpiParams {
   const T* dact_pre; int ld_dact; int dact_kind;
   const T* gate; int gate_ld; int rows_per_batch;
   const void* residual; int ld_res; int residual_f32; int out_fused_f32;
+  int geglu, geglu_inner; const T* geglu_u; int ld_geglu;
 };
 
 // Scalar epilogue (fp32 path).
@@ -77,6 +78,22 @@ __device__ __forceinline__ void epi_vec8(const EpiParams<bf16>& e, int m, int n,
     const bf16x8 bv = *reinterpret_cast<const bf16x8*>(e.bias + n);
 #pragma unroll
     for (int t = 0; t < 8; ++t) v[t] += (float)bv[t];
+  }
+  if (e.geglu == 2) {
+    // v is dg[m, n .. n + 7]; the two halves of du come from the saved projection u = [value | gate]
+    const bf16* up = e.geglu_u + (size_t)m * e.ld_geglu + n;
+    const bf16x8 uv = *reinterpret_cast<const bf16x8*>(up), ug = *reinterpret_cast<const bf16x8*>(up + e.geglu_inner);
+    bf16x8 o0, o1;
+#pragma unroll
+    for (int t = 0; t < 8; ++t) {
+      const float gt = (float)ug[t];
+      o0[t] = (bf16)(v[t] * gelu_erf_f(gt));
+      o1[t] = (bf16)(v[t] * (float)uv[t] * gelu_erf_grad_f(gt));
+    }
+    bf16* op = e.out + (size_t)m * e.ldo + n;
+    *reinterpret_cast<bf16x8*>(op) = o0;
+    *reinterpret_cast<bf16x8*>(op + e.geglu_inner) = o1;
+    return;
   }
   if (e.pre_out) {
     bf16x8 o;
@@ -142,6 +159,43 @@ __device__ __forceinline__ void wave_epilogue(const f32x16 (&acc)[TM][TN], float
       for (int r = 0; r < 16; ++r) Cw[(8 * (r >> 2) + 4 * g + (r & 3)) * C_LD + j * 32 + l32] = acc[i][j][r];
     asm volatile("" ::: "memory");
     DP_TRACE(20 + 2 * i);
+    if (WN == 64 && e.geglu == 1) {
+      // Forward GeGLU: the tile's columns are permuted so that this wave's first 32 columns are values
+      // and its last 32 the gates of the same outputs j0 .. j0 + 31 (see the B loader).
+      const int j0 = col0 / 2;
+#pragma unroll 1
+      for (int it = 0; it < 2; ++it) {
+        const int id = it * 64 + lane;
+        const int lr = id >> 2, lc = (id & 3) * 8;
+        const int m = row0 + i * 32 + lr, j = j0 + lc;
+        if (m < e.M && j < e.geglu_inner) {
+          float va[8], ga[8];
+          *reinterpret_cast<f32x4*>(&va[0]) = *reinterpret_cast<const f32x4*>(&Cw[lr * C_LD + lc]);
+          *reinterpret_cast<f32x4*>(&va[4]) = *reinterpret_cast<const f32x4*>(&Cw[lr * C_LD + lc + 4]);
+          *reinterpret_cast<f32x4*>(&ga[0]) = *reinterpret_cast<const f32x4*>(&Cw[lr * C_LD + 32 + lc]);
+          *reinterpret_cast<f32x4*>(&ga[4]) = *reinterpret_cast<const f32x4*>(&Cw[lr * C_LD + 32 + lc + 4]);
+          if (e.bias) {
+            const bf16x8 bv = *reinterpret_cast<const bf16x8*>(e.bias + j), bg = *reinterpret_cast<const bf16x8*>(e.bias + e.geglu_inner + j);
+#pragma unroll
+            for (int t = 0; t < 8; ++t) { va[t] += (float)bv[t]; ga[t] += (float)bg[t]; }
+          }
+          bf16x8 uv, ug, o;
+#pragma unroll
+          for (int t = 0; t < 8; ++t) {
+            uv[t] = (bf16)va[t]; ug[t] = (bf16)ga[t];
+            o[t] = (bf16)((float)uv[t] * gelu_erf_f((float)ug[t]));
+          }
+          if (e.pre_out) {
+            bf16* up = e.pre_out + (size_t)m * e.ld_pre + j;
+            *reinterpret_cast<bf16x8*>(up) = uv;
+            *reinterpret_cast<bf16x8*>(up + e.geglu_inner) = ug;
+          }
+          *reinterpret_cast<bf16x8*>(e.out + (size_t)m * e.ldo + j) = o;
+        }
+      }
+      asm volatile("" ::: "memory");
+      continue;
+    }
 #pragma unroll 1
     for (int it = 0; it < 32 * WN / 8 / 64; ++it) {
       const int id = it * 64 + lane;
@@ -420,7 +474,10 @@ gemm_bf16_dtl_kernel(const GemmBf16Params p) {
       vb[j] = 2u * ((uint32_t)(kt_begin * BK + k) * p.ldb + min(n0 + c * 8, p.N - 8));
     } else {
       const int r = blk * (512 / BK) + lane / CPR, pc = lane % CPR, c = pc ^ kc_key<BK>(r);
-      vb[j] = 2u * ((uint32_t)min(n0 + r, p.N - 1) * p.ldb + kt_begin * BK + c * 8);
+      int brow = min(n0 + r, p.N - 1);
+      if (p.epi.geglu == 1)   // tile row r: 32-row blocks alternate value / gate rows of the same outputs
+        brow = ((r >> 5) & 1) * p.epi.geglu_inner + min(n0 / 2 + (r >> 6) * 32 + (r & 31), p.epi.geglu_inner - 1);
+      vb[j] = 2u * ((uint32_t)brow * p.ldb + kt_begin * BK + c * 8);
     }
   }
   const uint32_t a_step = 2u * (A_MC ? (uint32_t)BK * p.lda : BK), b_step = 2u * (B_MC ? (uint32_t)BK * p.ldb : BK);
@@ -608,6 +665,7 @@ static EpiParams<T> make_epi(const GemmArgs& a) {
   e.dact_pre = (const T*)a.dact_pre; e.ld_dact = a.ld_dact; e.dact_kind = a.dact_kind;
   e.gate = (const T*)a.gate; e.gate_ld = a.gate_ld; e.rows_per_batch = a.rows_per_batch > 0 ? a.rows_per_batch : 1;
   e.residual = a.residual; e.ld_res = a.ld_res; e.residual_f32 = a.residual_f32; e.out_fused_f32 = a.out_fused_f32;
+  e.geglu = a.geglu; e.geglu_inner = a.geglu_inner; e.geglu_u = (const T*)a.geglu_u; e.ld_geglu = a.ld_geglu;
   return e;
 }
 
@@ -777,6 +835,11 @@ static int launch_bf16_layout(const GemmArgs& a, hipStream_t s) {
   return launch_bf16_cfg<BM, BN, BK, WGM, WGN, true, false>(a, s);
 }
 
+bool gemm_geglu_fwd_supported(const GemmArgs& a) {
+  return a.dtype == BF16 && !a.a_mc && !a.b_mc && a.K % 32 == 0 && a.geglu_inner > 0 && a.geglu_inner % 32 == 0 &&
+         a.N == 2 * a.geglu_inner && a.ldo >= a.geglu_inner && (!a.pre_out || a.ld_pre >= a.N) && dtl_addressable(a);
+}
+
 int launch_gemm(const GemmArgs& a, hipStream_t s) {
   if (a.M <= 0 || a.N <= 0 || a.K <= 0) return set_error(DP_EINVAL, "gemm: non-positive size");
   if (!a.A || !a.B || (!a.out && !a.out_f32)) return set_error(DP_EINVAL, "gemm: null operand");
@@ -795,7 +858,23 @@ int launch_gemm(const GemmArgs& a, hipStream_t s) {
     for (int x : elds) if (x % 8 || x < 8) return set_error(DP_EUNSUPPORTED, "gemm(bf16): epilogue leading dims must be multiples of 8");
     const void* eps[] = {a.out, a.out_f32, a.bias, a.pre_out, a.dact_pre, a.gate, a.residual, a.splitk_ws};
     for (const void* x : eps) if ((uintptr_t)x % 16) return set_error(DP_EALIGN, "gemm(bf16): epilogue operands must be 16-byte aligned");
-    const int cfg = (a.force_cfg > 0 && a.force_cfg <= kNumCfgs + 7) ? a.force_cfg - 1 : choose_cfg(a.M, a.N, a.K, a.a_mc != 0, a.b_mc != 0, dtl_addressable(a));
+    if (a.geglu) {
+      if (a.geglu != 1 && a.geglu != 2) return set_error(DP_EINVAL, "gemm: bad geglu mode");
+      if (!a.out || a.out_f32 || a.act || a.dact_pre || a.gate || a.residual || a.out_fused_f32)
+        return set_error(DP_EUNSUPPORTED, "gemm: a GeGLU epilogue combines with a bias only");
+      if (a.geglu == 1 && !gemm_geglu_fwd_supported(a)) return set_error(DP_EUNSUPPORTED, "gemm: fused GeGLU forward not available for this problem");
+      if (a.geglu == 2) {
+        if (a.N != a.geglu_inner || a.geglu_inner % 8 || !a.geglu_u || a.ld_geglu % 8 || a.ld_geglu < 2 * a.geglu_inner ||
+            a.ldo < 2 * a.geglu_inner || a.pre_out || ((uintptr_t)a.geglu_u % 16))
+          return set_error(DP_EINVAL, "gemm: bad fused GeGLU backward arguments");
+      }
+    }
+    int cfg = (a.force_cfg > 0 && a.force_cfg <= kNumCfgs + 7) ? a.force_cfg - 1 : choose_cfg(a.M, a.N, a.K, a.a_mc != 0, a.b_mc != 0, dtl_addressable(a));
+    if (a.geglu == 1 && (cfg < 6 || cfg > 10)) {
+      // the column permutation lives in the direct-to-LDS loader
+      const long t256x256 = (long)((a.M + 255) / 256) * ((a.N + 255) / 256);
+      cfg = t256x256 >= 128 ? 6 : 8;
+    }
     switch (cfg) {
       case 1: return launch_bf16_layout<256, 128, 64, 4, 2>(a, s);
       case 2: return launch_bf16_layout<256, 256, 64, 2, 4>(a, s);

@@ -66,6 +66,7 @@ struct dp_stage {
   hipStream_t side = nullptr;
   std::vector<hipEvent_t> events;
   bool overlap = true;
+  int fuse = 3;   // bit 0: GeGLU forward in the projection GEMM's epilogue; bit 1: its backward in the dx GEMM's
 };
 
 struct dp_encoder {
@@ -333,8 +334,17 @@ static int unet_block_fwd(const dp_stage& s, const void* const* P, const float* 
   // GeGLU feed-forward
   ln.x = u.x2; ln.y = u.h3; ln.gamma = P[U_LN3_G]; ln.beta = P[U_LN3_B]; ln.mean = u.mean3; ln.rstd = u.rstd3;
   DP_TRY(launch_ln_fwd(ln, st));
-  DP_TRY(launch_gemm(gemm_fwd(dt, u.h3, T, d, P[U_W1], 2 * inner, P[U_B1], u.u), st));
-  DP_TRY(launch_geglu_fwd(dt, u.u, u.g, T, inner, st));
+  {
+    // u = h3 W1^T + b1 and g = value * gelu(gate) in one kernel where the GEMM supports it
+    GemmArgs f = gemm_fwd(dt, u.h3, T, d, P[U_W1], 2 * inner, P[U_B1], u.g);
+    f.ldo = inner; f.pre_out = u.u; f.ld_pre = 2 * inner; f.geglu = 1; f.geglu_inner = inner;
+    if ((s.fuse & 1) && gemm_geglu_fwd_supported(f)) {
+      DP_TRY(launch_gemm(f, st));
+    } else {
+      DP_TRY(launch_gemm(gemm_fwd(dt, u.h3, T, d, P[U_W1], 2 * inner, P[U_B1], u.u), st));
+      DP_TRY(launch_geglu_fwd(dt, u.u, u.g, T, inner, st));
+    }
+  }
   g = gemm_fwd(dt, u.g, T, inner, P[U_W2], d, P[U_B2], y);
   g.residual = u.x2; g.ld_res = d; g.residual_f32 = 1; g.out_fused_f32 = y_is_out ? 0 : 1;
   DP_TRY(launch_gemm(g, st));
@@ -366,9 +376,16 @@ static int unet_block_bwd(const dp_stage& s, const void* const* P, const void* c
     DP_TRY(db(dy.h, d, T, U_B2, q));
     rd.pair[c] = sd.end();
   }
-  DP_TRY(launch_gemm(gemm_dx(dt, dy.h, T, d, P[U_W2], WT[U_W2], inner, b.dg), st));
   sd.wait(rd.du);
-  DP_TRY(launch_geglu_bwd(dt, b.dg, u.u, b.du, T, inner, st));
+  if (dt == BF16 && (s.fuse & 2)) {
+    // dg = dy W2 never reaches memory: the GEMM epilogue turns it into du = [dg gelu(gate) | dg value gelu'(gate)]
+    GemmArgs f = gemm_dx(dt, dy.h, T, d, P[U_W2], WT[U_W2], inner, b.du);
+    f.ldo = 2 * inner; f.geglu = 2; f.geglu_inner = inner; f.geglu_u = u.u; f.ld_geglu = 2 * inner;
+    DP_TRY(launch_gemm(f, st));
+  } else {
+    DP_TRY(launch_gemm(gemm_dx(dt, dy.h, T, d, P[U_W2], WT[U_W2], inner, b.dg), st));
+    DP_TRY(launch_geglu_bwd(dt, b.dg, u.u, b.du, T, inner, st));
+  }
   {
     hipStream_t q = sd.begin();
     DP_TRY(dw(b.du, T, 2 * inner, u.h3, d, U_W1, q));
@@ -840,6 +857,13 @@ void dp_stage_destroy(dp_stage* st) {
 int dp_stage_set_overlap(dp_stage* st, int enabled) {
   if (!st) return set_error(DP_EINVAL, "stage handle is NULL");
   st->overlap = enabled != 0;
+  return DP_OK;
+}
+
+int dp_stage_set_fusion(dp_stage* st, int mask) {
+  if (!st) return set_error(DP_EINVAL, "stage handle is NULL");
+  if (mask < 0 || mask > 3) return set_error(DP_EINVAL, "fusion mask out of range");
+  st->fuse = mask;
   return DP_OK;
 }
 

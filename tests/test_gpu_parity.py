@@ -55,13 +55,14 @@ def _run(cfg, seed=0, **kw):
 
 # ------------------------------------------------------------------ small shapes, several tiles + ragged tails
 SMALL_UNET = si.StageConfig("small_unet_bf16", si.UNET, "bf16", 2, 2, 200, 192, 3, 64, 77, 64, 264)
+SMALL_UNET_FUSE = si.StageConfig("small_unet_bf16_inner288", si.UNET, "bf16", 2, 2, 200, 192, 3, 64, 77, 64, 288)   # inner % 32 == 0: fused GeGLU forward
 SMALL_UNET_DH32 = si.StageConfig("small_unet_bf16_dh32", si.UNET, "bf16", 1, 1, 130, 64, 2, 32, 5, 24, 40)
 SMALL_DIT = si.StageConfig("small_dit_bf16", si.DIT, "bf16", 2, 3, 72, 144, 2, 72, 0, 0, 296, 1e-6, 1, self_cond=True)
 SMALL_DIT_ERF = si.StageConfig("small_dit_bf16_erf", si.DIT, "bf16", 1, 2, 257, 128, 2, 64, 0, 0, 128, 1e-6, 0)
 SMALL_DIT_F32 = si.StageConfig("small_dit_f32", si.DIT, "f32", 2, 2, 40, 48, 2, 24, 0, 0, 96, 1e-6, 1, self_cond=True)
 
 
-@pytest.mark.parametrize("cfg", [si.CONFIG1, SMALL_UNET, SMALL_UNET_DH32, SMALL_DIT, SMALL_DIT_ERF, SMALL_DIT_F32],
+@pytest.mark.parametrize("cfg", [si.CONFIG1, SMALL_UNET, SMALL_UNET_FUSE, SMALL_UNET_DH32, SMALL_DIT, SMALL_DIT_ERF, SMALL_DIT_F32],
                          ids=lambda c: c.name)
 def test_stage_matches_oracle_small(cfg):
     ds, inp = _run(cfg, randomize_ln=(cfg.name != si.CONFIG1.name))
@@ -101,6 +102,32 @@ def test_deterministic_and_accumulate_and_selfcond_isolation():
     for k in r1["grads"]:
         assert np.array_equal(r3["grads"][k], 2.0 * r1["grads"][k]), k
     assert np.array_equal(r3["dcond"], r1["dcond"])   # d_cond is overwritten, not accumulated
+
+
+def test_geglu_epilogue_fusion_matches_separate_kernels():
+    """The GeGLU fused into the GEMM epilogues computes what the separate elementwise kernels compute:
+    the forward bit for bit, the backward up to the bf16 rounding of dg that the fused path skips."""
+    import torch
+    from paper_2405_01248_amd.harness import DeviceStage, rel_err
+    cfg = SMALL_UNET_FUSE
+    inp = si.make_stage_inputs(cfg, seed=5, randomize_ln=True)
+    ref = _oracle_stage(cfg, inp)
+    ds = DeviceStage(cfg, inp)
+    res = {}
+    for mask in (0, 3, 1, 2):
+        ds.stage.set_fusion(mask)
+        ds.step()
+        torch.cuda.synchronize()
+        res[mask] = ds.results()
+        _compare(cfg, res[mask], ref)
+    for mask in (1, 2, 3):
+        assert np.array_equal(res[0]["y"], res[mask]["y"]), mask
+    for k in res[0]["grads"]:
+        assert np.array_equal(res[0]["grads"][k], res[1]["grads"][k]), k        # forward fusion alone changes nothing
+        assert rel_err(res[3]["grads"][k], res[0]["grads"][k]) < 5e-3, k
+    assert rel_err(res[3]["dx"], res[0]["dx"]) < 5e-3
+    with pytest.raises(Exception):
+        ds.stage.set_fusion(4)
 
 
 # ------------------------------------------------------------------ text encoder, partial batches
