@@ -103,15 +103,13 @@ def cpu_baseline_stage(cfg):
 # HBM bytes per launch of the dominant kernel measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE),
 # scaled by kernels of known size in the same run (FETCH_SIZE x 2.0, WRITE_SIZE x 1.0); the counter runs and the
 # per-kernel table are in profiles/hbm_traffic_cfg2.md.  Average over the launches of the class in one step.
-_KIB = 1024.0
 PMC_TRAFFIC_BYTES = {
-    ("cfg2", "gemm_nt"): ((84 * 33968 + 14 * 5463) * 2.0 + (84 * 29867 + 14 * 1540) * 1.0) / 98 * _KIB,
-    ("cfg2", "gemm_nn"): (34393 * 2.0 + 15360 * 1.0) * _KIB,
-    ("cfg2", "gemm_tn"): (59023 * 2.0 + 21577 * 1.0) * _KIB,
+    ("cfg2", "gemm_nt"): 94.0e6,    # 26 launches per step: forward projections and dx = dy W on transposed weight copies
+    ("cfg2", "gemm_tn"): 139.6e6,   # 14 launches per step: dW = dy^T x, split-K partial sums included
 }
 
 MFMA_KINDS = {"gemm_nt", "gemm_nn", "gemm_tn", "attn_fwd", "attn_bwd_dq", "attn_bwd_dkv"}
-KERNEL_NAMES = {"gemm_nt": "dp::gemm_bf16_kernel<..., A_MC=false, B_MC=false> (y = x W^T)",
+KERNEL_NAMES = {"gemm_nt": "dp::gemm_bf16_dtl_kernel<..., A_MC=false, B_MC=false> (y = x W^T; dx = dy W on transposed weight copies)",
                 "gemm_nn": "dp::gemm_bf16_kernel<..., A_MC=false, B_MC=true> (dx = dy W)",
                 "gemm_tn": "dp::gemm_bf16_kernel<..., A_MC=true, B_MC=true> (dW = dy^T x)",
                 "attn_fwd": "dp::attn_fwd_bf16_kernel", "attn_bwd_dq": "dp::attn_bwd_dq_bf16_kernel",
