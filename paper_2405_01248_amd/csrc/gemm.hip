@@ -605,6 +605,176 @@ gemm_bf16_dtl_kernel(const GemmBf16Params p) {
   DP_TRACE(4);
 }
 
+// ------------------------------------------------------------------ bf16 MFMA kernel, 16x16x32 tiles (flexible tile shapes)
+// The same direct-to-LDS pipeline with v_mfma_f32_16x16x32_bf16, whose 16-row / 16-column granularity
+// allows workgroup tiles such as 256x160 (wave tile 64x80: 9 fragment reads per 20 MFMAs).  It exists
+// for output widths that leave 256x128 / 256x256 tiles with padded columns or a badly filled last round
+// (N = 320: 256 tiles of 256x160 instead of 256 half-empty 256x256 tiles; N = 1152: 256 tiles, 10 % padding).
+// Contraction-contiguous operands only (y = x W^T), 64-deep k-tiles, 8 waves.
+// Register layout of the instruction (lane l): A row l % 16, B column l % 16, both k = 8 * (l / 16) .. + 7 of
+// the 32-deep step; D column l % 16, rows 4 * (l / 16) + r.
+typedef __attribute__((ext_vector_type(4))) float f32x4_acc;
+
+template <int BM, int BN, int STAGES, int WGM, int WGN>
+struct Dtl16Smem {
+  static constexpr int BK = 64;
+  static constexpr int A_BYTES = BM * BK * 2, B_BYTES = BN * BK * 2, STAGE = A_BYTES + B_BYTES;
+  static constexpr int WN = BN / WGN;
+  static constexpr int C_LD = WN + 4;
+  static constexpr size_t TILE_BYTES = (size_t)STAGES * STAGE;
+  static constexpr size_t EPI_BYTES = (size_t)WGM * WGN * 16 * C_LD * 4;
+  static constexpr size_t BYTES = TILE_BYTES > EPI_BYTES ? TILE_BYTES : EPI_BYTES;
+};
+
+template <int BM, int BN, int STAGES, int WGM, int WGN>
+__global__ void __launch_bounds__(WGM * WGN * 64)
+gemm_bf16_dtl16_kernel(const GemmBf16Params p) {
+  using S = Dtl16Smem<BM, BN, STAGES, WGM, WGN>;
+  constexpr int BK = 64, NW = WGM * WGN, KS = 2, CPR = 8;        // two 32-deep k-steps per k-tile, 8 chunks per tile row
+  constexpr int WM = BM / WGM, WN = BN / WGN;
+  constexpr int TM = WM / 16, TN = WN / 16;
+  constexpr int PIECES = (S::A_BYTES + S::B_BYTES) / 1024, A_PIECES = S::A_BYTES / 1024;
+  constexpr int LOADS = (PIECES + NW - 1) / NW;                   // copies per wave and k-tile; surplus slots repeat the last piece
+  static_assert(WM % 16 == 0 && WN % 16 == 0 && S::A_BYTES % 1024 == 0 && S::B_BYTES % 1024 == 0, "tile shape");
+  static_assert(STAGES == 3 && 2 * LOADS < 64, "pipeline shape");
+
+  extern __shared__ __attribute__((aligned(1024))) unsigned char smem_raw[];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int l16 = lane & 15, q = lane >> 4;
+  const int wm0 = (wave / WGN) * WM, wn0 = (wave % WGN) * WN;
+  int tile_m, tile_n;
+  tile_of_block(blockIdx.x, p.tiles_m, p.tiles_n, tile_m, tile_n);
+  const int m0 = tile_m * BM, n0 = tile_n * BN;
+  const int nk = p.K / BK;
+
+  // Piece j of this wave: 8 tile rows x 128 bytes of A (pieces 0 .. A_PIECES - 1) or B.  A wave-uniform
+  // choice of descriptor per slot is made with two issue paths below; the per-lane byte offset is fixed.
+  const rsrc_t ra = make_rsrc(p.A, p.a_bytes), rb = make_rsrc(p.B, p.b_bytes);
+  uint32_t vo[LOADS];
+  int ldsoff[LOADS];
+  bool isa[LOADS];
+#pragma unroll
+  for (int j = 0; j < LOADS; ++j) {
+    const int piece = min(wave * LOADS + j, PIECES - 1);
+    isa[j] = piece < A_PIECES;
+    const int blk = isa[j] ? piece : piece - A_PIECES;
+    const int r = blk * 8 + lane / CPR, pc = lane % CPR, c = pc ^ kc_key<BK>(r);
+    if (isa[j]) vo[j] = 2u * ((uint32_t)min(m0 + r, p.M - 1) * p.lda + c * 8);
+    else vo[j] = 2u * ((uint32_t)min(n0 + r, p.N - 1) * p.ldb + c * 8);
+    ldsoff[j] = (isa[j] ? 0 : S::A_BYTES) + blk * 1024;
+  }
+#define DP16_ISSUE_PART(t_, part_, parts_)                                                                            \
+  {                                                                                                                   \
+    unsigned char* st_ = smem_raw + ((t_) % STAGES) * S::STAGE;                                                       \
+    _Pragma("unroll") for (int j = 0; j < LOADS; ++j)                                                                 \
+      if (j % (parts_) == (part_)) {                                                                                  \
+        if (isa[j]) async_copy_16B_buf(ra, vo[j], (uint32_t)(t_) * (2u * BK), st_ + ldsoff[j]);                       \
+        else async_copy_16B_buf(rb, vo[j], (uint32_t)(t_) * (2u * BK), st_ + ldsoff[j]);                              \
+      }                                                                                                               \
+  }
+
+  f32x4_acc acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) acc[i][j][r] = 0.f;
+
+  bf16x8 fa[2][TM], fb[2][TN];
+#define DP16_FRAGS(st_, ks_, set_)                                                                                    \
+  {                                                                                                                   \
+    const bf16* as = reinterpret_cast<const bf16*>(smem_raw + (st_) * S::STAGE);                                      \
+    const bf16* bs = reinterpret_cast<const bf16*>(smem_raw + (st_) * S::STAGE + S::A_BYTES);                         \
+    _Pragma("unroll") for (int i = 0; i < TM; ++i) {                                                                  \
+      const int r = wm0 + i * 16 + l16;                                                                               \
+      fa[set_][i] = *reinterpret_cast<const bf16x8*>(as + r * BK + (((4 * (ks_) + q) ^ kc_key<BK>(r)) * 8));          \
+    }                                                                                                                 \
+    _Pragma("unroll") for (int j2 = 0; j2 < TN; ++j2) {                                                               \
+      const int r = wn0 + j2 * 16 + l16;                                                                              \
+      fb[set_][j2] = *reinterpret_cast<const bf16x8*>(bs + r * BK + (((4 * (ks_) + q) ^ kc_key<BK>(r)) * 8));         \
+    }                                                                                                                 \
+  }
+#define DP16_MFMAS(set_)                                                                                              \
+  _Pragma("unroll") for (int i = 0; i < TM; ++i)                                                                      \
+    _Pragma("unroll") for (int j2 = 0; j2 < TN; ++j2)                                                                 \
+      acc[i][j2] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa[set_][i], fb[set_][j2], acc[i][j2], 0, 0, 0);
+
+  // pipeline: identical in structure to gemm_bf16_dtl_kernel (three buffers, copies two k-tiles ahead,
+  // spread over the k-steps; exact waits)
+  constexpr int PART_LAST = LOADS / KS;
+#pragma unroll
+  for (int t = 0; t < STAGES; ++t)
+    if (t < nk) DP16_ISSUE_PART(t, 0, 1);
+  {
+    const int y = min(nk, STAGES) - 1;
+    if (y == 2) wait_vmcnt<2 * LOADS>();
+    else if (y == 1) wait_vmcnt<LOADS>();
+    else wait_vmcnt<0>();
+  }
+  barrier_nofence();
+  DP16_FRAGS(0, 0, 0);
+  for (int t = 0; t + 1 < nk; ++t) {
+    const int st = t % STAGES;
+    const bool refill = t >= 1 && t - 1 + STAGES < nk;
+    // k-step 0: fetch the fragments of k-step 1, MFMAs of k-step 0
+    DP16_FRAGS(st, 1, 1);
+    __builtin_amdgcn_sched_barrier(0);
+    DP16_MFMAS(0);
+    __builtin_amdgcn_sched_barrier(0);
+    if (refill) DP16_ISSUE_PART(t - 1 + STAGES, 0, KS);
+    __builtin_amdgcn_sched_barrier(0);
+    // k-step 1: publish k-tile t + 1, fetch its first fragments, MFMAs of k-step 1
+    wait_lgkmcnt0();
+    if (nk - 2 - t >= 1) wait_vmcnt<LOADS - PART_LAST>();
+    else wait_vmcnt<0>();
+    barrier_nofence();
+    DP16_FRAGS((t + 1) % STAGES, 0, 0);
+    __builtin_amdgcn_sched_barrier(0);
+    DP16_MFMAS(1);
+    __builtin_amdgcn_sched_barrier(0);
+    if (refill) DP16_ISSUE_PART(t - 1 + STAGES, 1, KS);
+    __builtin_amdgcn_sched_barrier(0);
+  }
+  {
+    const int st = (nk - 1) % STAGES;
+    DP16_FRAGS(st, 1, 1);
+    __builtin_amdgcn_sched_barrier(0);
+    DP16_MFMAS(0);
+    __builtin_amdgcn_sched_barrier(0);
+    DP16_MFMAS(1);
+  }
+#undef DP16_FRAGS
+#undef DP16_MFMAS
+#undef DP16_ISSUE_PART
+  __syncthreads();   // every wave is done with the operand tiles before they are reused below
+
+  // Epilogue: 16-row slabs through the wave's own fp32 LDS region, then 8 consecutive columns per lane.
+  float* Cw = reinterpret_cast<float*>(smem_raw) + wave * 16 * S::C_LD;
+#pragma unroll
+  for (int i = 0; i < TM; ++i) {
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) Cw[(4 * q + r) * S::C_LD + j * 16 + l16] = acc[i][j][r];
+    asm volatile("" ::: "memory");
+    constexpr int CHUNKS = 16 * WN / 8;
+#pragma unroll 1
+    for (int it = 0; it < (CHUNKS + 63) / 64; ++it) {
+      const int id = it * 64 + lane;
+      const int lr = id / (WN / 8), lc = (id % (WN / 8)) * 8;
+      const int m = m0 + wm0 + i * 16 + lr, n = n0 + wn0 + lc;
+      if (id < CHUNKS && m < p.M && n < p.N) {
+        float v[8];
+        *reinterpret_cast<f32x4*>(&v[0]) = *reinterpret_cast<const f32x4*>(&Cw[lr * S::C_LD + lc]);
+        *reinterpret_cast<f32x4*>(&v[4]) = *reinterpret_cast<const f32x4*>(&Cw[lr * S::C_LD + lc + 4]);
+        epi_vec8(p.epi, m, n, v);
+      }
+    }
+    asm volatile("" ::: "memory");
+  }
+}
+
 // ------------------------------------------------------------------ fp32 FMA kernel
 struct GemmF32Params {
   const float* A; const float* B;
@@ -699,18 +869,29 @@ static int choose_splits(long tiles, int kt) {
 //  - dW = dy^T x (both operands read through the transposing LDS load): 128x128, two
 //    workgroups per CU.
 static int choose_cfg(int M, int N, int K, bool a_mc, bool b_mc, bool dtl_ok) {
-  // Measured on MI355X over the GEMM shapes of the five workloads.  256x256 direct-to-LDS tiles
-  // (least LDS and L1 traffic per FLOP) whenever they still give every CU work; otherwise smaller
-  // tiles, direct-to-LDS for short contractions and for operands read without transposition.
   const long t256x256 = (long)((M + 255) / 256) * ((N + 255) / 256);
   const long t256x128 = (long)((M + 255) / 256) * ((N + 127) / 128);
   const bool dtl32 = dtl_ok && K % 32 == 0, dtl64 = dtl_ok && K % 64 == 0;
   if (a_mc) return (dtl32 && b_mc && t256x256 >= 80) ? 6 : 0;
   if (!b_mc) {
-    if (dtl32 && t256x256 >= 128) return (K <= 320 && N >= 512) ? 2 : 6;
-    if (dtl64 && t256x128 >= 128) return 9;
-    if (dtl64) return 10;
-    if (dtl32) return 8;
+    // y = x W^T on contraction-contiguous operands: pick the direct-to-LDS tile with the least
+    // (rounds over the 256 CUs) x (tile area / measured relative efficiency).  The efficiencies were
+    // fitted on MI355X over the GEMM shapes of the five workloads: 256x256 tiles move the fewest LDS
+    // and L1 bytes per FLOP; 256x160 (16x16x32 MFMA tiles) exists for widths that leave the others
+    // with padded columns or a badly filled last round (N = 320, 1152, 2560).  A 192x128 tile for
+    // N = 640 (215 instead of 160 workgroups) won 5 % on bare GEMMs and lost 2 % inside the stage.
+    struct Cand { int idx, bm, bn; float eff; bool need64; };
+    static const Cand cands[] = {{6, 256, 256, 1.27f, false}, {11, 256, 160, 1.01f, true}, {9, 256, 128, 1.00f, true},
+                                 {10, 128, 128, 0.90f, true}, {8, 128, 128, 0.85f, false}};
+    int best = -1;
+    float best_cost = 0.f;
+    for (const Cand& c : cands) {
+      if (c.need64 ? !dtl64 : !dtl32) continue;
+      const long tiles = (long)((M + c.bm - 1) / c.bm) * ((N + c.bn - 1) / c.bn);
+      const float cost = (float)((tiles + kCUs - 1) / kCUs) * (float)(c.bm * c.bn) / c.eff;
+      if (best < 0 || cost < best_cost) { best = c.idx; best_cost = cost; }
+    }
+    if (best >= 0) return best;
     return t256x128 >= 128 ? 1 : 0;
   }
   if (dtl32 && t256x256 >= 128) return 6;
@@ -818,6 +999,31 @@ static int launch_dtl_cfg(const GemmArgs& a, hipStream_t s) {
   return DP_OK;
 }
 
+template <int BM, int BN, int WGM, int WGN>
+static int launch_dtl16(const GemmArgs& a, hipStream_t s) {
+  using S = Dtl16Smem<BM, BN, 3, WGM, WGN>;
+  if (a.a_mc || a.b_mc || a.out_f32 || a.K % 64) return set_error(DP_EUNSUPPORTED, "gemm: forced 16x16-tile configuration needs contraction-contiguous operands, a storage-dtype output and K % 64 == 0");
+  if (!dtl_addressable(a)) return set_error(DP_EUNSUPPORTED, "gemm: operand too large for the forced direct-to-LDS configuration");
+  GemmBf16Params p;
+  p.A = (const bf16*)a.A; p.B = (const bf16*)a.B;
+  p.M = a.M; p.N = a.N; p.K = a.K; p.lda = a.lda; p.ldb = a.ldb;
+  p.epi = make_epi<bf16>(a);
+  p.tiles_m = (a.M + BM - 1) / BM; p.tiles_n = (a.N + BN - 1) / BN;
+  p.a_bytes = (uint32_t)operand_extent_bytes(a.M, a.K, a.lda);
+  p.b_bytes = (uint32_t)operand_extent_bytes(a.N, a.K, a.ldb);
+  p.k_tiles_per_split = a.K / 64;
+  auto kern = gemm_bf16_dtl16_kernel<BM, BN, 3, WGM, WGN>;
+  static bool attr_set = false;
+  if (!attr_set) {
+    if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)S::BYTES) != hipSuccess)
+      return set_error(DP_EHIP, "hipFuncSetAttribute(gemm) failed");
+    attr_set = true;
+  }
+  KScope ks(KK_GEMM_NT, 2.0 * a.M * a.N * a.K, 2.0 * ((double)a.M * a.K + (double)a.N * a.K + (double)a.M * a.N), s, a.M, a.N, a.K);
+  hipLaunchKernelGGL(kern, dim3(p.tiles_m * p.tiles_n), dim3(WGM * WGN * 64), S::BYTES, s, p);
+  return hipGetLastError() == hipSuccess ? DP_OK : set_error(DP_EHIP, "gemm launch failed");
+}
+
 template <int BM, int BN, int BK, int STAGES, int WGM, int WGN>
 static int launch_dtl_layout(const GemmArgs& a, hipStream_t s) {
   if (a.K % BK) return set_error(DP_EUNSUPPORTED, "gemm: K is not a multiple of the k-tile of the forced configuration");
@@ -869,8 +1075,8 @@ int launch_gemm(const GemmArgs& a, hipStream_t s) {
           return set_error(DP_EINVAL, "gemm: bad fused GeGLU backward arguments");
       }
     }
-    int cfg = (a.force_cfg > 0 && a.force_cfg <= kNumCfgs + 7) ? a.force_cfg - 1 : choose_cfg(a.M, a.N, a.K, a.a_mc != 0, a.b_mc != 0, dtl_addressable(a));
-    if (a.geglu == 1 && (cfg < 6 || cfg > 10)) {
+    int cfg = (a.force_cfg > 0 && a.force_cfg <= kNumCfgs + 6) ? a.force_cfg - 1 : choose_cfg(a.M, a.N, a.K, a.a_mc != 0, a.b_mc != 0, dtl_addressable(a));
+    if (a.geglu == 1 && (cfg < 6 || cfg > 10)) {   // cfg 11 has no column permutation in its loader either
       // the column permutation lives in the direct-to-LDS loader
       const long t256x256 = (long)((a.M + 255) / 256) * ((a.N + 255) / 256);
       cfg = t256x256 >= 128 ? 6 : 8;
@@ -886,8 +1092,7 @@ int launch_gemm(const GemmArgs& a, hipStream_t s) {
       case 8: return launch_dtl_layout<128, 128, 32, 4, 2, 2>(a, s);
       case 9: return launch_dtl_layout<256, 128, 64, 3, 4, 2>(a, s);
       case 10: return launch_dtl_layout<128, 128, 64, 3, 2, 2>(a, s);
-      case 11: return launch_dtl_layout<256, 128, 64, 3, 2, 2>(a, s);   // one wave per SIMD, 128x64 per wave
-      case 12: return launch_dtl_layout<256, 256, 32, 4, 2, 2>(a, s);   // one wave per SIMD, 128x128 per wave
+      case 11: return launch_dtl16<256, 160, 4, 2>(a, s);
       default: break;
     }
     return launch_bf16_layout<128, 128, 64, 2, 2>(a, s);
