@@ -70,9 +70,10 @@ void dp_stage_destroy(dp_stage* st);
 int dp_stage_param_count(const dp_stage* st);
 int dp_stage_param_shape(const dp_stage* st, int idx, int64_t shape[2], const char** name);
 
-/* stage_bwd runs the weight- and bias-gradient kernels (off the critical path) on a second,
- * library-owned stream forked from and joined to hip_stream with events, so that they overlap the
- * activation-gradient chain.  enabled = 0 issues everything on hip_stream in program order
+/* stage_bwd runs the weight- and bias-gradient kernels and the per-call weight transposes (all off the
+ * critical path) on a second, library-owned stream forked from and joined to hip_stream with events,
+ * so that they overlap the activation-gradient chain; a saving stage_fwd of U-Net blocks runs the
+ * context K/V projections of all blocks there.  enabled = 0 issues everything on hip_stream in program order
  * (used when single kernels are to be timed); results are bit-identical either way.  Default 1. */
 int dp_stage_set_overlap(dp_stage* st, int enabled);
 

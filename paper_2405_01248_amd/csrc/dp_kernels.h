@@ -107,8 +107,10 @@ struct LnBwdArgs {
   float* dgamma; float* dbeta; int accumulate;
   float* dscale; float* dshift; int dmod_ld;
   float* partial; size_t partial_bytes;
+  int defer_reduce;        // 1: only write the column partials; the caller runs launch_ln_bwd_reduce (maybe on another stream)
 };
 int launch_ln_bwd(const LnBwdArgs& a, hipStream_t s);
+int launch_ln_bwd_reduce(const LnBwdArgs& a, hipStream_t s);
 size_t ln_bwd_partial_bytes(int rows, int d, int rows_per_batch);
 
 // g[m, j] = u[m, j] * gelu_erf(u[m, inner + j])

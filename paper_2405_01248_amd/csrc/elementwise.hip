@@ -274,12 +274,22 @@ int launch_ln_bwd(const LnBwdArgs& a, hipStream_t s) {
     KScope ks(KK_LN_BWD, 0.0, a.rows * (double)a.d * (dtype_size(a.dtype) + 4.0 + (a.dres ? 4.0 : 0.0) + (a.dx ? dtype_size(a.dtype) : 0.0) + (a.dx32 ? 4.0 : 0.0)) + 8.0 * a.rows, s, a.rows, a.d);
     e = a.dtype == BF16 ? ln_bwd_t<bf16>(a, rpb, nb, nchunk, partial, s) : ln_bwd_t<float>(a, rpb, nb, nchunk, partial, s);
   }
-  if (e || !want_cols) return e;
+  if (e || !want_cols || a.defer_reduce) return e;
+  return launch_ln_bwd_reduce(a, s);
+}
+
+// Second half of launch_ln_bwd: fixed-order sum of the per-workgroup column partials into the parameter
+// (or modulation) gradients.  Separate so that a caller can put it on another stream (defer_reduce).
+int launch_ln_bwd_reduce(const LnBwdArgs& a, hipStream_t s) {
+  const bool modulated = a.scale != nullptr;
+  const int rpb = modulated ? a.rows_per_batch : a.rows;
+  if (rpb <= 0 || a.rows % rpb || !a.partial) return set_error(DP_EINVAL, "ln_bwd_reduce: bad arguments");
+  const int nb = a.rows / rpb, nchunk = (rpb + LNB_ROWS - 1) / LNB_ROWS;
   KScope ks(KK_REDUCE, 0.0, (double)nb * nchunk * 2 * a.d * 4, s, nchunk, 2 * a.d);
   if (modulated)
-    hipLaunchKernelGGL(ln_bwd_reduce_kernel, dim3((2 * a.d + 31) / 32, nb), dim3(1024), 0, s, partial, nchunk, a.d, a.dscale, a.dshift, a.dmod_ld, 0);
+    hipLaunchKernelGGL(ln_bwd_reduce_kernel, dim3((2 * a.d + 31) / 32, nb), dim3(1024), 0, s, a.partial, nchunk, a.d, a.dscale, a.dshift, a.dmod_ld, 0);
   else
-    hipLaunchKernelGGL(ln_bwd_reduce_kernel, dim3((2 * a.d + 31) / 32, 1), dim3(1024), 0, s, partial, nchunk, a.d, a.dgamma, a.dbeta, a.d, a.accumulate);
+    hipLaunchKernelGGL(ln_bwd_reduce_kernel, dim3((2 * a.d + 31) / 32, 1), dim3(1024), 0, s, a.partial, nchunk, a.d, a.dgamma, a.dbeta, a.d, a.accumulate);
   return hipGetLastError() == hipSuccess ? DP_OK : set_error(DP_EHIP, "ln_bwd_reduce launch failed");
 }
 

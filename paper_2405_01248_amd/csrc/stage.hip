@@ -98,6 +98,7 @@ struct BwdScratch {
   float *delta, *dm, *dcond_pre, *partial, *partial_side; size_t partial_bytes;
   float* dkv_ws; size_t dkv_ws_bytes;     // query-split partials of the cross-attention dK/dV kernel
   void* wt;                               // transposed copies of every block's weight matrices (bf16 stages only)
+  float* ln_partial[3]; size_t ln_partial_bytes;   // U-Net: column partials of the three LayerNorm backward kernels (reduced on the side stream)
 };
 
 static void plan_unet_block(Plan& p, const dp_stage& s, UnetBuf& u, bool with_xin) {
@@ -179,8 +180,11 @@ static void plan_bwd_scratch(Plan& p, const dp_stage& s, BwdScratch& b) {
     b.dkv_ws = (float*)p.take(b.dkv_ws_bytes);
     b.dg = p.take(T * ff * es); b.du = p.take(T * 2 * ff * es); b.dg2 = nullptr;
     b.dm_t = nullptr; b.dm = nullptr; b.dcond_pre = nullptr;
+    b.ln_partial_bytes = ln_bwd_partial_bytes((int)T, (int)d, (int)T);
+    for (int i = 0; i < 3; ++i) b.ln_partial[i] = (float*)p.take(b.ln_partial_bytes);
   } else {
     b.dq2 = nullptr; b.dkv2 = nullptr; b.dkv_ws = nullptr; b.dkv_ws_bytes = 0;
+    b.ln_partial_bytes = 0; b.ln_partial[0] = b.ln_partial[1] = b.ln_partial[2] = nullptr;
     b.dg = p.take(T * d * es);          // gated-branch gradients: df2 ...
     b.dg2 = p.take(T * d * es);         // ... and do (separate, so the side stream can still read df2)
     b.du = p.take(T * ff * es);         // df1
@@ -280,7 +284,7 @@ struct Side {
 };
 
 // Last side batch that reads each reusable backward buffer.
-struct SideReads { int pair[2] = {0, 0}; int du = 0, dq2 = 0, dqkv = 0, dg = 0, dg2 = 0, dm_t = 0; };
+struct SideReads { int pair[2] = {0, 0}; int du = 0, dq2 = 0, dqkv = 0, dg = 0, dg2 = 0, dm_t = 0; int lnp[3] = {0, 0, 0}; };
 
 static AttnArgs attn_base(const dp_stage& s) {
   AttnArgs a;
@@ -302,8 +306,10 @@ static int record(ProfileHooks* ph, int idx, hipStream_t st) {
 
 // ============================================================ U-Net stage
 // x: fp32 block input.  y: fp32 (next block's input) unless y_is_out (storage dtype, the stage output).
+// kv_side: the context K/V projection of this block was issued on the side stream as batch kv_batch
+// of *kv_side (it depends on the context and the weights only); otherwise it is computed here.
 static int unet_block_fwd(const dp_stage& s, const void* const* P, const float* x, const void* ctx, void* y, bool y_is_out,
-                          UnetBuf& u, hipStream_t st) {
+                          UnetBuf& u, hipStream_t st, Side* kv_side = nullptr, int kv_batch = 0) {
   const int dt = s.d.dtype, T = s.T, Tc = s.Tc, d = s.d.d_model, inner = s.d.ff_inner, dc = s.d.ctx_dim;
   const size_t es = s.es;
   LnArgs ln; memset(&ln, 0, sizeof(ln));
@@ -323,7 +329,8 @@ static int unet_block_fwd(const dp_stage& s, const void* const* P, const float* 
   ln.x = u.x1; ln.y = u.h2; ln.gamma = P[U_LN2_G]; ln.beta = P[U_LN2_B]; ln.mean = u.mean2; ln.rstd = u.rstd2;
   DP_TRY(launch_ln_fwd(ln, st));
   DP_TRY(launch_gemm(gemm_fwd(dt, u.h2, T, d, P[U_WQ2], d, nullptr, u.q2), st));
-  DP_TRY(launch_gemm(gemm_fwd(dt, ctx, Tc, dc, P[U_WKV2], 2 * d, nullptr, u.kv2), st));
+  if (kv_side) kv_side->wait(kv_batch);
+  else DP_TRY(launch_gemm(gemm_fwd(dt, ctx, Tc, dc, P[U_WKV2], 2 * d, nullptr, u.kv2), st));
   a = attn_base(s);
   a.Nk = s.d.ctx_tokens; a.q = u.q2; a.ldq = d; a.k = u.kv2; a.v = at(u.kv2, d, es); a.ldk = a.ldv = 2 * d;
   a.o = u.a2; a.ldo = d; a.lse = u.lse2;
@@ -369,6 +376,17 @@ static int unet_block_bwd(const dp_stage& s, const void* const* P, const void* c
   auto db = [&](const void* gy, int cols, int rows, int pidx, hipStream_t q) {
     return launch_colsum(dt, gy, cols, rows, cols, gf(pidx), acc, b.partial_side, b.partial_bytes, q);
   };
+  // LayerNorm backward: dx on the main stream; the sum of the column partials into d gamma / d beta
+  // (parameter gradients, nothing downstream waits for them) on the side stream, from a buffer of its own
+  auto ln_bwd = [&](LnBwdArgs& lb, int k) -> int {
+    sd.wait(rd.lnp[k]);
+    lb.partial = b.ln_partial[k]; lb.partial_bytes = b.ln_partial_bytes; lb.defer_reduce = 1;
+    DP_TRY(launch_ln_bwd(lb, st));
+    hipStream_t q = sd.begin();
+    DP_TRY(launch_ln_bwd_reduce(lb, q));
+    rd.lnp[k] = sd.end();
+    return DP_OK;
+  };
   // ---- feed-forward
   {
     hipStream_t q = sd.begin();
@@ -398,7 +416,7 @@ static int unet_block_bwd(const dp_stage& s, const void* const* P, const void* c
   lb.dy = b.dh; lb.x = u.x2; lb.mean = u.mean3; lb.rstd = u.rstd3; lb.gamma = P[U_LN3_G]; lb.dres = dy.f; set_dx(lb, dx2);
   lb.dgamma = gf(U_LN3_G); lb.dbeta = gf(U_LN3_B);
   sd.wait(rd.pair[c ^ 1]);
-  DP_TRY(launch_ln_bwd(lb, st));
+  DP_TRY(ln_bwd(lb, 2));
   // ---- cross-attention
   {
     hipStream_t q = sd.begin();
@@ -424,7 +442,7 @@ static int unet_block_bwd(const dp_stage& s, const void* const* P, const void* c
   lb.dy = b.dh; lb.x = u.x1; lb.mean = u.mean2; lb.rstd = u.rstd2; lb.gamma = P[U_LN2_G]; lb.dres = dx2.f; set_dx(lb, dx1);
   lb.dgamma = gf(U_LN2_G); lb.dbeta = gf(U_LN2_B);
   sd.wait(rd.pair[c]);
-  DP_TRY(launch_ln_bwd(lb, st));
+  DP_TRY(ln_bwd(lb, 1));
   // ---- self-attention
   {
     hipStream_t q = sd.begin();
@@ -449,7 +467,7 @@ static int unet_block_bwd(const dp_stage& s, const void* const* P, const void* c
   if (dx_final) { lb.dx = dx_final; lb.dx32 = nullptr; } else set_dx(lb, out);
   lb.dgamma = gf(U_LN1_G); lb.dbeta = gf(U_LN1_B);
   sd.wait(rd.pair[c ^ 1]);
-  DP_TRY(launch_ln_bwd(lb, st));
+  DP_TRY(ln_bwd(lb, 0));
   return sd.err;
 }
 
@@ -591,6 +609,15 @@ static int check_stage_call(const dp_stage* s, const void* const* params, const 
   return DP_OK;
 }
 
+static int ensure_side_stream(dp_stage* s) {
+  if (s->side) return DP_OK;
+  if (hipStreamCreateWithFlags(&s->side, hipStreamNonBlocking) != hipSuccess) { s->side = nullptr; return set_error(DP_EHIP, "hipStreamCreate failed"); }
+  s->events.resize((size_t)s->d.n_blocks * 32 + 8);
+  for (auto& e : s->events)
+    if (hipEventCreateWithFlags(&e, hipEventDisableTiming) != hipSuccess) return set_error(DP_EHIP, "hipEventCreate failed");
+  return DP_OK;
+}
+
 static int run_stage_fwd(dp_stage* s, const void* const* params, const void* x, const void* cc, void* y, void* ws, int save,
                          hipStream_t st, ProfileHooks* ph) {
   StagePlan sp;
@@ -601,6 +628,20 @@ static int run_stage_fwd(dp_stage* s, const void* const* params, const void* x, 
   if (!unet) DP_TRY(launch_silu(s->d.dtype, cc, sp.sc_in, (size_t)s->d.batch * s->d.d_model, st));
   // the residual stream runs in fp32 inside the stage: widen the stage input once
   float* cur = (float*)(save ? (unet ? sp.ub[0].xin : sp.db[0].xin) : sp.pp2);
+  // U-Net, saving pass (one K/V buffer per block): the context projections of all blocks run on the
+  // side stream while the main stream works through block 0's self-attention
+  Side sd;
+  sd.main = st; sd.on = s->overlap && unet && save;
+  int kv_batch = 0;
+  if (sd.on) {
+    DP_TRY(ensure_side_stream(s));
+    sd.side = s->side; sd.ev = &s->events;
+    hipStream_t q = sd.begin();
+    for (int b = 0; b < nb; ++b)
+      DP_TRY(launch_gemm(gemm_fwd(s->d.dtype, cc, s->Tc, s->d.ctx_dim, params[(size_t)b * s->per_block + U_WKV2], 2 * s->d.d_model, nullptr,
+                                  sp.ub[b].kv2), q));
+    kv_batch = sd.end();
+  }
   DP_TRY(launch_cast_to_f32(s->d.dtype, x, cur, act, st));
   for (int b = 0; b < nb; ++b) {
     DP_TRY(record(ph, b, st));
@@ -611,21 +652,13 @@ static int run_stage_fwd(dp_stage* s, const void* const* params, const void* x, 
     else if (save) out = unet ? sp.ub[b + 1].xin : sp.db[b + 1].xin;
     else out = (b & 1) ? sp.pp1 : sp.pp0;
     const int slot = save ? b : 0;
-    if (unet) DP_TRY(unet_block_fwd(*s, P, cur, cc, out, last, sp.ub[slot], st));
+    if (unet) DP_TRY(unet_block_fwd(*s, P, cur, cc, out, last, sp.ub[slot], st, sd.on ? &sd : nullptr, kv_batch));
     else DP_TRY(dit_block_fwd(*s, P, cur, sp.sc_in, out, last, save != 0, sp.db[slot], st));
     cur = (float*)out;
   }
+  sd.wait(sd.issued);
   DP_TRY(record(ph, nb, st));
-  return DP_OK;
-}
-
-static int ensure_side_stream(dp_stage* s) {
-  if (s->side) return DP_OK;
-  if (hipStreamCreateWithFlags(&s->side, hipStreamNonBlocking) != hipSuccess) { s->side = nullptr; return set_error(DP_EHIP, "hipStreamCreate failed"); }
-  s->events.resize((size_t)s->d.n_blocks * 24 + 8);
-  for (auto& e : s->events)
-    if (hipEventCreateWithFlags(&e, hipEventDisableTiming) != hipSuccess) return set_error(DP_EHIP, "hipEventCreate failed");
-  return DP_OK;
+  return sd.err;
 }
 
 static int run_stage_bwd(dp_stage* s, const void* const* params, const void* dy, const void* cc, void* dx, void* d_cond,
