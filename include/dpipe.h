@@ -12,9 +12,10 @@
  * C^f, C^b, G_l, O_l).
  *
  * Conventions
- *  - Every pointer marked [device] is HIP device memory owned by the caller; the library
- *    never allocates, frees or synchronises in stage_fwd / stage_bwd /
- *    encoder_fwd_partial.  `params` / `dparams` are HOST arrays of device pointers.
+ *  - Every pointer marked [device] is HIP device memory owned by the caller; stage_fwd,
+ *    stage_bwd and encoder_fwd_partial never allocate or free device memory and never
+ *    synchronise (the first call that uses the side stream, see dp_stage_set_overlap, creates
+ *    that stream and a pool of events: host objects, released by dp_stage_destroy).  `params` / `dparams` are HOST arrays of device pointers.
  *  - `hip_stream` is a hipStream_t passed as void*; all work is enqueued on it in order.
  *  - Tensors are row-major with the last dimension contiguous.  Storage dtype is the
  *    descriptor's dtype (bf16 or fp32); parameter gradients are always fp32.
@@ -129,7 +130,8 @@ size_t dp_encoder_workspace_bytes(const dp_encoder* enc, int max_samples);
  * ids [device]: int32 [global_batch, seq] (ids outside [0, vocab) are clamped).
  * hidden [device]: [global_batch, seq, d_model], read (unless layer_begin = 0) and written
  * in place for the selected samples only; other rows are untouched, so calls on disjoint
- * sample ranges can be issued in any order or in different bubbles. */
+ * sample ranges can be issued in any order or in different bubbles.  num_samples = 0 is a valid
+ * empty slice: arguments are still checked, nothing is launched. */
 int encoder_fwd_partial(dp_encoder* enc, const void* const* params, const int32_t* ids, void* hidden,
                         int global_batch, int layer_begin, int layer_end, int sample_offset, int num_samples,
                         void* workspace, size_t workspace_bytes, void* hip_stream);

@@ -813,7 +813,7 @@ static int check_encoder_call(const dp_encoder* e, const void* const* params, co
   for (size_t i = 0; i < e->params.size(); ++i)
     if (int err = check_ptr(params[i], e->params[i].name.c_str())) return err;
   DP_TRY(check_ptr(ids, "ids", 4)); DP_TRY(check_ptr(hidden, "hidden")); DP_TRY(check_ptr(ws, "workspace", 256));
-  if (global_batch <= 0 || off < 0 || n <= 0 || (long)off + n > global_batch)
+  if (global_batch <= 0 || off < 0 || n < 0 || (long)off + n > global_batch)
     return set_errorf(DP_EINVAL, "sample range [%d, %d) outside the global batch of %d", off, off + n, global_batch);
   if (lb < 0 || le > e->d.n_layers + 2 || lb >= le) return set_errorf(DP_EINVAL, "layer range [%d, %d) invalid (0..%d)", lb, le, e->d.n_layers + 2);
   if ((long)n * e->d.n_heads > 65535) return set_error(DP_EUNSUPPORTED, "num_samples * n_heads exceeds 65535");
@@ -986,6 +986,7 @@ int encoder_fwd_partial(dp_encoder* enc, const void* const* params, const int32_
                         int layer_begin, int layer_end, int sample_offset, int num_samples, void* workspace,
                         size_t workspace_bytes, void* hip_stream) {
   DP_TRY(check_encoder_call(enc, params, ids, hidden, global_batch, layer_begin, layer_end, sample_offset, num_samples, workspace, workspace_bytes));
+  if (num_samples == 0) return DP_OK;   // an empty slice is valid and touches nothing
   EncBuf w;
   plan_encoder(*enc, workspace, num_samples, w);
   return encoder_run(*enc, params, ids, hidden, layer_begin, layer_end, sample_offset, num_samples, w, (hipStream_t)hip_stream, nullptr);
@@ -1046,8 +1047,10 @@ int dp_encoder_profile(dp_encoder* enc, const void* const* params, const int32_t
   if (!enc || !batches || !rows || !n_rows || n_batches <= 0 || reps < 1) return set_error(DP_EINVAL, "dp_encoder_profile: bad argument");
   const int nl = enc->d.n_layers + 2;
   if (max_rows < nl * n_batches) return set_error(DP_EINVAL, "dp_encoder_profile: too few rows");
-  for (int i = 0; i < n_batches; ++i)
+  for (int i = 0; i < n_batches; ++i) {
+    if (batches[i] < 1) return set_error(DP_EINVAL, "dp_encoder_profile: batch sizes must be positive");
     DP_TRY(check_encoder_call(enc, params, ids, hidden, global_batch, 0, nl, 0, batches[i], workspace, workspace_bytes));
+  }
   hipStream_t s = (hipStream_t)hip_stream;
   std::vector<hipEvent_t> ev(nl + 1);
   for (auto& e : ev)

@@ -97,11 +97,23 @@ def test_null_misaligned_and_small_workspace_are_rejected_before_launch(dp):
     call = lambda **k: lib.encoder_fwd_partial(enc._h, eg, x, x, k.get("gb", 8), k.get("lb", 0), k.get("le", 4), k.get("off", 0),
                                                k.get("n", 4), ws, k.get("wsb", wsb), None)
     assert call(off=6) == -1            # range leaves the global batch
-    assert call(n=0) == -1
+    assert call(n=0) == 0               # an empty slice is valid: checked, then nothing is launched (no GPU needed)
+    assert call(n=0, off=8) == 0        # ... also at the very end of the batch
+    assert call(n=0, off=9) == -1
+    assert call(n=-1) == -1
     assert call(le=5) == -1             # only layers 0..n_layers+1 exist
     assert call(lb=3, le=3) == -1
     assert call(wsb=wsb - 1) == -3
     assert call(n=8, wsb=wsb) == -3     # workspace sized for 4 samples
+
+
+def test_fusion_mask_range(dp):
+    st = dp.Stage(0, 1, 1, 1, 64, 64, 1, 64, 8, 64, 64)
+    for m in (0, 1, 2, 3):
+        st.set_fusion(m)
+    for m in (-1, 4):
+        with pytest.raises(dp.DpipeError):
+            st.set_fusion(m)
 
 
 def test_last_error_is_never_null(dp):
