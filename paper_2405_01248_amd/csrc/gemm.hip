@@ -881,8 +881,11 @@ static int choose_cfg(int M, int N, int K, bool a_mc, bool b_mc, bool dtl_ok) {
     // with padded columns or a badly filled last round (N = 320, 1152, 2560).  A 192x128 tile for
     // N = 640 (215 instead of 160 workgroups) won 5 % on bare GEMMs and lost 2 % inside the stage.
     struct Cand { int idx, bm, bn; float eff; bool need64; };
-    static const Cand cands[] = {{6, 256, 256, 1.27f, false}, {11, 256, 160, 1.01f, true}, {9, 256, 128, 1.00f, true},
-                                 {10, 128, 128, 0.90f, true}, {8, 128, 128, 0.85f, false}};
+    // Two 256x128 workgroups per CU (configuration 12, three 32-deep buffers) hide each other's prologue,
+    // epilogue and barrier stalls: the shorter the contraction and the more tiles per CU, the more it pays.
+    const float eff12 = t256x128 <= kCUs ? 0.95f : (K <= 384 ? 1.6f : (K <= 768 ? 1.25f : (K <= 1536 ? 1.15f : 0.9f)));
+    const Cand cands[] = {{6, 256, 256, 1.27f, false}, {11, 256, 160, 1.01f, true}, {12, 256, 128, eff12, false},
+                          {9, 256, 128, 1.00f, true}, {10, 128, 128, 0.90f, true}, {8, 128, 128, 0.85f, false}};
     int best = -1;
     float best_cost = 0.f;
     for (const Cand& c : cands) {
@@ -1075,8 +1078,8 @@ int launch_gemm(const GemmArgs& a, hipStream_t s) {
           return set_error(DP_EINVAL, "gemm: bad fused GeGLU backward arguments");
       }
     }
-    int cfg = (a.force_cfg > 0 && a.force_cfg <= kNumCfgs + 6) ? a.force_cfg - 1 : choose_cfg(a.M, a.N, a.K, a.a_mc != 0, a.b_mc != 0, dtl_addressable(a));
-    if (a.geglu == 1 && (cfg < 6 || cfg > 10)) {   // cfg 11 has no column permutation in its loader either
+    int cfg = (a.force_cfg > 0 && a.force_cfg <= kNumCfgs + 7) ? a.force_cfg - 1 : choose_cfg(a.M, a.N, a.K, a.a_mc != 0, a.b_mc != 0, dtl_addressable(a));
+    if (a.geglu == 1 && (cfg < 6 || cfg > 12 || cfg == 11)) {   // cfg 11 has no column permutation in its loader either
       // the column permutation lives in the direct-to-LDS loader
       const long t256x256 = (long)((a.M + 255) / 256) * ((a.N + 255) / 256);
       cfg = t256x256 >= 128 ? 6 : 8;
@@ -1093,6 +1096,7 @@ int launch_gemm(const GemmArgs& a, hipStream_t s) {
       case 9: return launch_dtl_layout<256, 128, 64, 3, 4, 2>(a, s);
       case 10: return launch_dtl_layout<128, 128, 64, 3, 2, 2>(a, s);
       case 11: return launch_dtl16<256, 160, 4, 2>(a, s);
+      case 12: return launch_dtl_layout<256, 128, 32, 3, 4, 2>(a, s);   // 72 KB of LDS: two workgroups per CU
       default: break;
     }
     return launch_bf16_layout<128, 128, 64, 2, 2>(a, s);
