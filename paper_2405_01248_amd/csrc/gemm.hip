@@ -860,14 +860,14 @@ static int choose_splits(long tiles, int kt) {
   return s;
 }
 
-// Picks the tile configuration (indices as in launch_gemm's switch) from a sweep of all GEMM
-// shapes of the five workloads on MI355X:
-//  - y = x W^T (both operands K-contiguous): the direct-to-LDS pipeline, 256x128x64 tiles when
-//    they fill the CUs, else 128x128x32 tiles (two workgroups per CU);
-//  - dx = dy W: register-staged kernel; 256x256 tiles when the contraction is long and there
-//    are enough tiles to fill the CUs, else 256x128, else 128x128;
-//  - dW = dy^T x (both operands read through the transposing LDS load): 128x128, two
-//    workgroups per CU.
+// Picks the tile configuration (indices as in launch_gemm's switch), from sweeps of all GEMM shapes of
+// the five workloads on MI355X:
+//  - y = x W^T (both operands K-contiguous; also dx = dy W on transposed weight copies): the
+//    direct-to-LDS kernels, tile chosen by the cost model below;
+//  - dx = dy W with W as stored (fp32-free fallback when no transposed copy exists): 256x256
+//    direct-to-LDS tiles when they fill the CUs, else the register-staged kernel;
+//  - dW = dy^T x (both operands read through the transposing LDS load): register-staged 128x128 tiles,
+//    two workgroups per CU; 256x256 direct-to-LDS tiles for large M and N.
 static int choose_cfg(int M, int N, int K, bool a_mc, bool b_mc, bool dtl_ok) {
   const long t256x256 = (long)((M + 255) / 256) * ((N + 255) / 256);
   const long t256x128 = (long)((M + 255) / 256) * ((N + 127) / 128);
