@@ -102,7 +102,8 @@ struct LnBwdArgs {
   const void* dy; const void* x; const float* mean; const float* rstd;
   const void* gamma;
   const void* scale; int mod_ld; int rows_per_batch;
-  const void* dres;        // optional fp32 residual-stream gradient added to dx
+  const void* dres;        // optional residual-stream gradient added to dx: fp32, or the storage dtype if dres_storage
+  int dres_storage;
   void* dx; float* dx32;
   float* dgamma; float* dbeta; int accumulate;
   float* dscale; float* dshift; int dmod_ld;

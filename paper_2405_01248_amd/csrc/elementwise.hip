@@ -133,8 +133,8 @@ template <typename T>
 __global__ void __launch_bounds__(256) ln_bwd_kernel(int d, int rows_per_batch, const T* __restrict__ dy, const float* __restrict__ x,
                                                      const float* __restrict__ mean, const float* __restrict__ rstd,
                                                      const T* __restrict__ gamma, const T* __restrict__ scale, int mod_ld,
-                                                     const float* __restrict__ dres, T* __restrict__ dx, float* __restrict__ dx32,
-                                                     float* __restrict__ partial) {
+                                                     const float* __restrict__ dres, const T* __restrict__ dres_t,
+                                                     T* __restrict__ dx, float* __restrict__ dx32, float* __restrict__ partial) {
   constexpr int V = Vec<T>::N;
   extern __shared__ float cols[];   // [4 waves][2][d]
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -190,6 +190,11 @@ __global__ void __launch_bounds__(256) ln_bwd_kernel(int d, int rows_per_batch, 
         if (dres) {
           float rr[V];
           load_f32<V>(dres + row * d + col, rr);
+#pragma unroll
+          for (int i = 0; i < V; ++i) o[i] += rr[i];
+        } else if (dres_t) {
+          float rr[V];
+          load_vec<T>(dres_t + row * d + col, rr);
 #pragma unroll
           for (int i = 0; i < V; ++i) o[i] += rr[i];
         }
@@ -251,8 +256,8 @@ size_t ln_bwd_partial_bytes(int rows, int d, int rows_per_batch) {
 template <typename T>
 static int ln_bwd_t(const LnBwdArgs& a, int rpb, int nb, int nchunk, float* partial, hipStream_t s) {
   hipLaunchKernelGGL(ln_bwd_kernel<T>, dim3(nchunk, nb), dim3(256), (size_t)8 * a.d * sizeof(float), s, a.d, rpb, (const T*)a.dy,
-                     (const float*)a.x, a.mean, a.rstd, (const T*)a.gamma, (const T*)a.scale, a.mod_ld, (const float*)a.dres, (T*)a.dx,
-                     a.dx32, partial);
+                     (const float*)a.x, a.mean, a.rstd, (const T*)a.gamma, (const T*)a.scale, a.mod_ld,
+                     a.dres_storage ? nullptr : (const float*)a.dres, a.dres_storage ? (const T*)a.dres : nullptr, (T*)a.dx, a.dx32, partial);
   return hipGetLastError() == hipSuccess ? DP_OK : set_error(DP_EHIP, "ln_bwd launch failed");
 }
 
@@ -271,7 +276,7 @@ int launch_ln_bwd(const LnBwdArgs& a, hipStream_t s) {
   }
   int e;
   {
-    KScope ks(KK_LN_BWD, 0.0, a.rows * (double)a.d * (dtype_size(a.dtype) + 4.0 + (a.dres ? 4.0 : 0.0) + (a.dx ? dtype_size(a.dtype) : 0.0) + (a.dx32 ? 4.0 : 0.0)) + 8.0 * a.rows, s, a.rows, a.d);
+    KScope ks(KK_LN_BWD, 0.0, a.rows * (double)a.d * (dtype_size(a.dtype) + 4.0 + (a.dres ? (a.dres_storage ? dtype_size(a.dtype) : 4.0) : 0.0) + (a.dx ? dtype_size(a.dtype) : 0.0) + (a.dx32 ? 4.0 : 0.0)) + 8.0 * a.rows, s, a.rows, a.d);
     e = a.dtype == BF16 ? ln_bwd_t<bf16>(a, rpb, nb, nchunk, partial, s) : ln_bwd_t<float>(a, rpb, nb, nchunk, partial, s);
   }
   if (e || !want_cols || a.defer_reduce) return e;

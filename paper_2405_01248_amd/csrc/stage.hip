@@ -362,6 +362,7 @@ static int unet_block_fwd(const dp_stage& s, const void* const* P, const float* 
 // copy).  dx2 goes to pair c ^ 1, dx1 to pair c, the block's dx to pair c ^ 1 again or, for the
 // first block of the stage, to dx_final (storage dtype only).  Weight- and bias-gradient work runs
 // in side-stream batches.
+// dy.f == nullptr: the upstream gradient exists in the storage dtype only (dy.h, the caller's tensor)
 static int unet_block_bwd(const dp_stage& s, const void* const* P, const void* const* WT, void* const* G, int acc, const void* ctx, GradPair dy, int c,
                           void* dx_final, UnetBuf& u, BwdScratch& b, Side& sd, SideReads& rd) {
   const int dt = s.d.dtype, T = s.T, Tc = s.Tc, d = s.d.d_model, inner = s.d.ff_inner, dc = s.d.ctx_dim;
@@ -413,7 +414,8 @@ static int unet_block_bwd(const dp_stage& s, const void* const* P, const void* c
   DP_TRY(launch_gemm(gemm_dx(dt, b.du, T, 2 * inner, P[U_W1], WT[U_W1], d, b.dh), st));
   LnBwdArgs lb; memset(&lb, 0, sizeof(lb));
   lb.dtype = dt; lb.rows = T; lb.d = d; lb.accumulate = acc; lb.partial = b.partial; lb.partial_bytes = b.partial_bytes;
-  lb.dy = b.dh; lb.x = u.x2; lb.mean = u.mean3; lb.rstd = u.rstd3; lb.gamma = P[U_LN3_G]; lb.dres = dy.f; set_dx(lb, dx2);
+  lb.dy = b.dh; lb.x = u.x2; lb.mean = u.mean3; lb.rstd = u.rstd3; lb.gamma = P[U_LN3_G]; set_dx(lb, dx2);
+  if (dy.f) lb.dres = dy.f; else { lb.dres = dy.h; lb.dres_storage = 1; }
   lb.dgamma = gf(U_LN3_G); lb.dbeta = gf(U_LN3_B);
   sd.wait(rd.pair[c ^ 1]);
   DP_TRY(ln_bwd(lb, 2));
@@ -439,7 +441,7 @@ static int unet_block_bwd(const dp_stage& s, const void* const* P, const void* c
     rd.dq2 = sd.end();
   }
   DP_TRY(launch_gemm(gemm_dx(dt, b.dq2, T, d, P[U_WQ2], WT[U_WQ2], d, b.dh), st));
-  lb.dy = b.dh; lb.x = u.x1; lb.mean = u.mean2; lb.rstd = u.rstd2; lb.gamma = P[U_LN2_G]; lb.dres = dx2.f; set_dx(lb, dx1);
+  lb.dy = b.dh; lb.x = u.x1; lb.mean = u.mean2; lb.rstd = u.rstd2; lb.gamma = P[U_LN2_G]; lb.dres = dx2.f; lb.dres_storage = 0; set_dx(lb, dx1);
   lb.dgamma = gf(U_LN2_G); lb.dbeta = gf(U_LN2_B);
   sd.wait(rd.pair[c]);
   DP_TRY(ln_bwd(lb, 1));
@@ -675,9 +677,10 @@ static int run_stage_bwd(dp_stage* s, const void* const* params, const void* dy,
     sd.side = s->side; sd.ev = &s->events;
   }
   SideReads rd;
-  // dy as a gradient pair: fp32 copy in pair 1's fp32 buffer, the caller's tensor as the GEMM operand
-  DP_TRY(launch_cast_to_f32(s->d.dtype, dy, bs.r[1].f, (size_t)s->T * s->d.d_model, st));
-  GradPair cur{bs.r[1].f, const_cast<void*>(dy)};
+  // dy as a gradient pair: the caller's tensor as GEMM operand; an fp32 copy only where a kernel of the
+  // last block wants one (the U-Net block reads dy in the storage dtype everywhere)
+  if (!unet || s->es == 4) DP_TRY(launch_cast_to_f32(s->d.dtype, dy, bs.r[1].f, (size_t)s->T * s->d.d_model, st));
+  GradPair cur{(!unet || s->es == 4) ? bs.r[1].f : nullptr, const_cast<void*>(dy)};
   int ci = 1;   // index of the pair whose fp32 buffer holds cur
   // Transposed weight copies: one launch per block on the side stream, issued one block ahead of
   // the block that uses them; the main stream waits for a block's copies right before that block.
