@@ -357,7 +357,6 @@ int launch_geglu_bwd(int dtype, const void* dg, const void* u, void* du, int row
 
 // ------------------------------------------------------------------ column sums
 constexpr int CS_ROWS = 64;    // rows per workgroup (16 per wave)
-constexpr int CS_COLS = 128;   // columns per workgroup in the gated-branch kernel (2 per lane)
 
 // Stage 1: partial[chunk][col] = sum of x over the chunk's rows.  A lane owns Vec::N consecutive
 // columns (16-byte loads); the four waves of a workgroup take rows round-robin and are added
@@ -465,39 +464,66 @@ int launch_silu_bwd(int dtype, const float* dz, const void* c, float* dc, int ac
 }
 
 // ------------------------------------------------------------------ gated branch backward
-// grid = (ceil(d / 128), B); each workgroup walks all rows of its batch.
+// grid = (ceil(d / (16 V)), B), 16 waves per workgroup.  A workgroup owns 16 V columns (V = 8 bf16 / 4 fp32
+// per lane, 16-byte accesses) of one batch; a wave covers 4 rows at a time (lane = row-in-group * 16 +
+// column chunk), the 16 waves 64 rows.  Column sums: over a wave's 4 row lanes by shuffles, over the
+// waves through LDS in wave order (fixed order).
+constexpr int GB_WAVES = 16;
 template <typename T>
-__global__ void __launch_bounds__(256) gate_bwd_kernel(const float* __restrict__ dres, const T* __restrict__ branch, const T* __restrict__ gate,
-                                                       int gate_ld, T* __restrict__ dbranch, float* __restrict__ dgate, int dgate_ld,
-                                                       int rows_per_batch, int d) {
-  __shared__ float red[4][CS_COLS];
+__global__ void __launch_bounds__(64 * GB_WAVES) gate_bwd_kernel(const float* __restrict__ dres, const T* __restrict__ branch,
+                                                                 const T* __restrict__ gate, int gate_ld, T* __restrict__ dbranch,
+                                                                 float* __restrict__ dgate, int dgate_ld, int rows_per_batch, int d) {
+  constexpr int V = Vec<T>::N;
+  __shared__ float red[GB_WAVES][16 * V];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int b = blockIdx.y, col = blockIdx.x * CS_COLS + lane * 2;
-  float s0 = 0.f, s1 = 0.f;
+  const int cl = lane & 15, rl = lane >> 4;
+  const int b = blockIdx.y, col = (blockIdx.x * 16 + cl) * V;
+  float s[V], g[V];
+#pragma unroll
+  for (int i = 0; i < V; ++i) s[i] = 0.f;
   if (col < d) {
-    const float g0 = to_f<T>(gate[(size_t)b * gate_ld + col]), g1 = to_f<T>(gate[(size_t)b * gate_ld + col + 1]);
-    for (int r = wave; r < rows_per_batch; r += 4) {
+    load_vec<T>(gate + (size_t)b * gate_ld + col, g);
+#pragma unroll 2
+    for (int r = wave * 4 + rl; r < rows_per_batch; r += 4 * GB_WAVES) {
       const size_t o = ((size_t)b * rows_per_batch + r) * d + col;
-      const float d0 = dres[o], d1 = dres[o + 1];
-      s0 += d0 * to_f<T>(branch[o]);
-      s1 += d1 * to_f<T>(branch[o + 1]);
-      dbranch[o] = from_f<T>(d0 * g0);
-      dbranch[o + 1] = from_f<T>(d1 * g1);
+      float dr[V], br[V], ob[V];
+      load_f32<V>(dres + o, dr);
+      load_vec<T>(branch + o, br);
+#pragma unroll
+      for (int i = 0; i < V; ++i) { s[i] = fmaf(dr[i], br[i], s[i]); ob[i] = dr[i] * g[i]; }
+      store_vec<T>(dbranch + o, ob);
     }
   }
-  red[wave][lane * 2] = s0; red[wave][lane * 2 + 1] = s1;
+#pragma unroll
+  for (int i = 0; i < V; ++i) {
+    s[i] += __shfl_xor(s[i], 16, 64);
+    s[i] += __shfl_xor(s[i], 32, 64);
+  }
+  if (rl == 0) {
+#pragma unroll
+    for (int i = 0; i < V; ++i) red[wave][cl * V + i] = s[i];
+  }
   __syncthreads();
-  if (threadIdx.x < CS_COLS) {
-    const int c = blockIdx.x * CS_COLS + threadIdx.x;
-    if (c < d) dgate[(size_t)b * dgate_ld + c] = ((red[0][threadIdx.x] + red[1][threadIdx.x]) + red[2][threadIdx.x]) + red[3][threadIdx.x];
+  if (threadIdx.x < 16 * V) {
+    const int gc = blockIdx.x * 16 * V + threadIdx.x;
+    if (gc < d) {
+      float t = 0.f;
+#pragma unroll
+      for (int w = 0; w < GB_WAVES; ++w) t += red[w][threadIdx.x];
+      dgate[(size_t)b * dgate_ld + gc] = t;
+    }
   }
 }
 int launch_gate_bwd(int dtype, const void* dres, const void* branch, const void* gate, int gate_ld, void* dbranch, float* dgate,
                     int dgate_ld, int B, int rows_per_batch, int d, hipStream_t s) {
-  if (B <= 0 || rows_per_batch <= 0 || d <= 0 || d % 2) return set_error(DP_EINVAL, "gate_bwd: bad sizes");
-  dim3 grid((d + CS_COLS - 1) / CS_COLS, B);
-  if (dtype == BF16) hipLaunchKernelGGL(gate_bwd_kernel<bf16>, grid, dim3(256), 0, s, (const float*)dres, (const bf16*)branch, (const bf16*)gate, gate_ld, (bf16*)dbranch, dgate, dgate_ld, rows_per_batch, d);
-  else hipLaunchKernelGGL(gate_bwd_kernel<float>, grid, dim3(256), 0, s, (const float*)dres, (const float*)branch, (const float*)gate, gate_ld, (float*)dbranch, dgate, dgate_ld, rows_per_batch, d);
+  const int V = dtype == BF16 ? 8 : 4;
+  if (B <= 0 || rows_per_batch <= 0 || d <= 0 || d % V || gate_ld % V) return set_error(DP_EINVAL, "gate_bwd: bad sizes");
+  const void* ptrs[] = {dres, branch, gate, dbranch};
+  for (const void* q : ptrs) if (!q || ((uintptr_t)q % 16)) return set_error(DP_EALIGN, "gate_bwd: operands must be non-null and 16-byte aligned");
+  if (!dgate) return set_error(DP_EINVAL, "gate_bwd: dgate is NULL");
+  dim3 grid((d + 16 * V - 1) / (16 * V), B);
+  if (dtype == BF16) hipLaunchKernelGGL(gate_bwd_kernel<bf16>, grid, dim3(64 * GB_WAVES), 0, s, (const float*)dres, (const bf16*)branch, (const bf16*)gate, gate_ld, (bf16*)dbranch, dgate, dgate_ld, rows_per_batch, d);
+  else hipLaunchKernelGGL(gate_bwd_kernel<float>, grid, dim3(64 * GB_WAVES), 0, s, (const float*)dres, (const float*)branch, (const float*)gate, gate_ld, (float*)dbranch, dgate, dgate_ld, rows_per_batch, d);
   return hipGetLastError() == hipSuccess ? DP_OK : set_error(DP_EHIP, "gate_bwd launch failed");
 }
 
