@@ -172,20 +172,23 @@ __device__ __forceinline__ float gelu_erf_grad_f(float z) {
   const float erfv = erf_fast(z * 0.70710678118654752f, e);
   return 0.5f * (1.0f + erfv) + z * e * 0.3989422804014327f;
 }
-__device__ __forceinline__ float tanh_fast(float x) {
-  // tanh(x) = 1 - 2 / (exp(2x) + 1); exact limits at +-inf, no cancellation issue at the tolerance used
-  float e = __expf(2.0f * x);
-  return 1.0f - 2.0f / (e + 1.0f);
+// Logistic function through the hardware exp2 and reciprocal (1 ulp each): the division of the
+// textbook form costs ten instructions in IEEE mode and these functions sit in GEMM epilogues.
+__device__ __forceinline__ float sigmoid_f(float z) {
+  return __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.4426950408889634f * z));
 }
+// tanh-form GELU: 0.5 z (1 + tanh(u)) = z sigmoid(2u), u = sqrt(2/pi) (z + 0.044715 z^3)
 __device__ __forceinline__ float gelu_tanh_f(float z) {
-  float t = tanh_fast(0.7978845608028654f * (z + 0.044715f * z * z * z));
-  return 0.5f * z * (1.0f + t);
+  const float u2 = z * fmaf(0.0713548162726f, z * z, 1.5957691216057308f);   // 2u
+  return z * sigmoid_f(u2);
 }
 __device__ __forceinline__ float gelu_tanh_grad_f(float z) {
-  float t = tanh_fast(0.7978845608028654f * (z + 0.044715f * z * z * z));
-  return 0.5f * (1.0f + t) + 0.5f * z * (1.0f - t * t) * 0.7978845608028654f * (1.0f + 0.134145f * z * z);
+  const float z2 = z * z;
+  const float u2 = z * fmaf(0.0713548162726f, z2, 1.5957691216057308f);
+  const float r = sigmoid_f(u2);
+  const float du2 = fmaf(0.2140644488178f, z2, 1.5957691216057308f);          // d(2u)/dz
+  return fmaf(z * r * (1.0f - r), du2, r);
 }
-__device__ __forceinline__ float sigmoid_f(float z) { return 1.0f / (1.0f + __expf(-z)); }
 __device__ __forceinline__ float quick_gelu_f(float z) { return z * sigmoid_f(1.702f * z); }
 __device__ __forceinline__ float silu_f(float z) { return z * sigmoid_f(z); }
 __device__ __forceinline__ float silu_grad_f(float z) {
