@@ -130,6 +130,54 @@ def test_geglu_epilogue_fusion_matches_separate_kernels():
         ds.stage.set_fusion(4)
 
 
+# ------------------------------------------------------------------ cost-profile export (Sec. 4.1, Table "Notations")
+@pytest.mark.parametrize("cfg", [SMALL_UNET, SMALL_DIT], ids=lambda c: c.name)
+def test_stage_cost_profile_rows(cfg):
+    """dp_stage_profile: one row per block with positive P^f, P^b, the activation / gradient message sizes
+    O_l = C^f = C^b = batch * tokens * d * element size and G_l = 4 bytes per parameter of the block; the
+    timed passes leave exactly the results of an ordinary step behind."""
+    import torch
+    from paper_2405_01248_amd.harness import DeviceStage
+    inp = si.make_stage_inputs(cfg, seed=2, randomize_ln=True)
+    ds = DeviceStage(cfg, inp)
+    ds.step(self_cond=False)
+    torch.cuda.synchronize()
+    want = ds.results()
+    rows = ds.stage.profile(ds.params, ds.x, ds.cc, ds.y, ds.dy, ds.dx, ds.d_cond, ds.dparams, ds.ws, reps=3)
+    torch.cuda.synchronize()
+    assert len(rows) == cfg.n_blocks
+    act = cfg.batch * cfg.tokens * cfg.d_model * (2 if cfg.dtype == "bf16" else 4)
+    per_block = len(ds.specs) // cfg.n_blocks
+    for i, r in enumerate(rows):
+        assert (r["component"], r["layer"], r["batch"]) == (0, i, cfg.batch)
+        assert 0.0 < r["fwd_ms"] < 1e3 and 0.0 < r["bwd_ms"] < 1e3
+        assert r["out_bytes"] == act and r["cf_bytes"] == act and r["cb_bytes"] == act
+        n_par = sum(int(np.prod(shape)) for _, shape in ds.specs[i * per_block:(i + 1) * per_block])
+        assert r["grad_bytes"] == 4 * n_par
+    got = ds.results()
+    assert np.array_equal(got["y"], want["y"]) and np.array_equal(got["dx"], want["dx"])
+    for k in want["grads"]:
+        assert np.array_equal(got["grads"][k], want["grads"][k]), k
+
+
+def test_encoder_cost_profile_rows():
+    import torch
+    from paper_2405_01248_amd.harness import DeviceEncoder
+    cfg = SMALL_ENC
+    de = DeviceEncoder(cfg, si.make_encoder_inputs(cfg, seed=0))
+    batches = [1, 3]
+    rows = de.enc.profile(de.params, de.ids, de.hidden, de.gb, batches, de.ws, reps=2)
+    torch.cuda.synchronize()
+    nl = cfg.n_layers + 2
+    assert len(rows) == nl * len(batches)
+    for j, b in enumerate(batches):
+        for l in range(nl):
+            r = rows[j * nl + l]
+            assert (r["component"], r["layer"], r["batch"]) == (1, l, b)
+            assert 0.0 < r["fwd_ms"] < 1e3 and r["bwd_ms"] == 0.0 and r["grad_bytes"] == 0 and r["cb_bytes"] == 0
+            assert r["out_bytes"] == b * cfg.seq * cfg.d_model * 2 and r["cf_bytes"] == r["out_bytes"]
+
+
 # ------------------------------------------------------------------ text encoder, partial batches
 SMALL_ENC = si.EncoderConfig("small_enc_bf16", "bf16", 2, 128, 2, 64, 77, 1000, 256, 6)
 SMALL_ENC_F32 = si.EncoderConfig("small_enc_f32", "f32", 2, 32, 2, 16, 9, 100, 64, 5)
