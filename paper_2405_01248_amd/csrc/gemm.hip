@@ -852,11 +852,17 @@ static const TileCfg kCfgs[] = {
 constexpr int kNumCfgs = sizeof(kCfgs) / sizeof(kCfgs[0]);
 constexpr int kCUs = 256;
 
-static int choose_splits(long tiles, int kt) {
+// Split-K factor of the fp32-output (weight-gradient) GEMMs: the largest power of two that keeps every
+// workgroup of the launch resident at once (`slots` = CUs x workgroups per CU of the configuration), with
+// at least 8 64-deep k-tiles per split and at most 32 partial sums to reduce.  A launch that spills into a
+// second round loses what the extra splits gained (90 tiles of 256x256, one per CU: 2 splits run 10 %
+// faster than 4 on the bare GEMM).  Inside the stage these GEMMs run on the side stream under the main
+// stream's kernels and every policy tried, a split count that is not a power of two included, stays
+// within 0.5 % of the step time.
+static int choose_splits(long tiles, int kt, int slots) {
+  const long cap = std::min<long>(std::min<long>(slots / std::max<long>(tiles, 1), kt / 8), 32);
   int s = 1;
-  // split-K only for the fp32-output (weight-gradient) GEMMs: fill the 256 CUs while keeping
-  // at least 8 k-tiles per split
-  while (tiles * s < kCUs && kt / (s * 2) >= 8 && s < 64) s *= 2;
+  while (2 * s <= cap) s *= 2;
   return s;
 }
 
@@ -907,7 +913,7 @@ size_t gemm_splitk_ws_bytes(int M, int N, int K) {
   size_t worst = 0;
   for (int c = 0; c < kNumCfgs; ++c) {
     const long tiles = (long)((M + kCfgs[c].bm - 1) / kCfgs[c].bm) * ((N + kCfgs[c].bn - 1) / kCfgs[c].bn);
-    const int s = choose_splits(tiles, (K + kCfgs[c].bk - 1) / kCfgs[c].bk);
+    const int s = choose_splits(tiles, (K + kCfgs[c].bk - 1) / kCfgs[c].bk, 2 * kCUs);
     if (s > 1) worst = std::max(worst, (size_t)s * M * N * sizeof(float));
   }
   return worst;
@@ -924,7 +930,7 @@ static int launch_bf16_cfg(const GemmArgs& a, hipStream_t s) {
   const int kt = (a.K + BK - 1) / BK;
   int splits = 1;
   if (a.out_f32) {
-    splits = choose_splits((long)p.tiles_m * p.tiles_n, kt);
+    splits = choose_splits((long)p.tiles_m * p.tiles_n, kt, S::BYTES <= 80 * 1024 ? 2 * kCUs : kCUs);
     if (splits > 1) {
       const size_t need = (size_t)splits * a.M * a.N * sizeof(float);
       if (!a.splitk_ws || a.splitk_ws_bytes < need) splits = 1;
@@ -970,7 +976,7 @@ static int launch_dtl_cfg(const GemmArgs& a, hipStream_t s) {
   const int kt = a.K / BK;
   int splits = 1;
   if (a.out_f32) {
-    splits = choose_splits((long)p.tiles_m * p.tiles_n, kt * BK / 64);
+    splits = choose_splits((long)p.tiles_m * p.tiles_n, kt * BK / 64, S::BYTES <= 80 * 1024 ? 2 * kCUs : kCUs);
     if (splits > 1) {
       const size_t need = (size_t)splits * a.M * a.N * sizeof(float);
       if (!a.splitk_ws || a.splitk_ws_bytes < need) splits = 1;
