@@ -52,6 +52,7 @@ struct GemmArgs {
 int launch_gemm(const GemmArgs& a, hipStream_t s);
 bool gemm_geglu_fwd_supported(const GemmArgs& a);
 size_t gemm_splitk_ws_bytes(int M, int N, int K);   // upper bound for out_f32 GEMMs
+size_t gemm_epi_splitk_ws_bytes(int M, int N, int K);   // same for storage-dtype outputs (0: such a GEMM is never split)
 
 // ---------------------------------------------------------------- attention
 // Per (batch b, head h): O = softmax(Q K^T * scale [+ causal mask]) V.

@@ -821,6 +821,27 @@ __global__ void __launch_bounds__(256) gemm_f32_kernel(const GemmF32Params p) {
     for (int j = 0; j < 4; ++j) epi_store<float>(p.epi, m0 + tm + i, n0 + tn + j, acc[i][j]);
 }
 
+// Second pass of a split-K GEMM with a storage-dtype output: sums the fp32 partial tiles in ascending
+// split order (fixed order, run-to-run identical) and applies the GEMM's epilogue to the sums.  One thread
+// per 8 consecutive columns of a row.
+__global__ void __launch_bounds__(256) reduce_epilogue_kernel(EpiParams<bf16> e, const float* __restrict__ partial, int splits) {
+  const int per_row = e.N / 8;
+  const size_t idx = blockIdx.x * (size_t)256 + threadIdx.x;
+  if (idx >= (size_t)e.M * per_row) return;
+  const int m = (int)(idx / per_row), n = (int)(idx % per_row) * 8;
+  const float* p = partial + (size_t)m * e.N + n;
+  const size_t plane = (size_t)e.M * e.N;
+  float v[8];
+  *reinterpret_cast<f32x4*>(&v[0]) = *reinterpret_cast<const f32x4*>(p);
+  *reinterpret_cast<f32x4*>(&v[4]) = *reinterpret_cast<const f32x4*>(p + 4);
+  for (int z = 1; z < splits; ++z) {
+    const f32x4 a = *reinterpret_cast<const f32x4*>(p + z * plane), b = *reinterpret_cast<const f32x4*>(p + z * plane + 4);
+#pragma unroll
+    for (int t = 0; t < 4; ++t) { v[t] += a[t]; v[4 + t] += b[t]; }
+  }
+  epi_vec8(e, m, n, v);
+}
+
 // ------------------------------------------------------------------ host side
 template <typename T>
 static EpiParams<T> make_epi(const GemmArgs& a) {
@@ -864,6 +885,31 @@ static int choose_splits(long tiles, int kt, int slots) {
   int s = 1;
   while (2 * s <= cap) s *= 2;
   return s;
+}
+
+// Split-K factor of a GEMM with a storage-dtype output (second pass: reduce_epilogue_kernel).  It pays
+// where a few tiles would each walk the contraction alone while most CUs idle: the frozen encoder's
+// projections on a partial batch (6 to 72 tiles of 128x128, K = 768 or 3072).  Measured on MI355X, encoder
+// forward in samples/s without and with it: 889 -> 1322 (slices of 1 sample), 3374 -> 4555 (4), 12971 -> 16249
+// (16); at 120 tiles (64 samples) the partial sums' traffic cancels the gain, so tile counts above 96 are
+// left alone.  At least 6 64-deep k-tiles per split; a finer split (3 per split) measured no better.
+static int choose_splits_epi(long tiles, int kt) {
+  if (tiles > 96 || kt < 12) return 1;
+  const long cap = std::min<long>(std::min<long>(kCUs / std::max<long>(tiles, 1), kt / 6), 16);
+  int s = 1;
+  while (2 * s <= cap) s *= 2;
+  return s;
+}
+
+size_t gemm_epi_splitk_ws_bytes(int M, int N, int K) {
+  size_t worst = 0;
+  const int shapes[][2] = {{128, 128}, {256, 128}, {256, 256}};
+  for (const auto& t : shapes) {
+    const long tiles = (long)((M + t[0] - 1) / t[0]) * ((N + t[1] - 1) / t[1]);
+    const int sp = choose_splits_epi(tiles, K / 64);
+    if (sp > 1) worst = std::max(worst, (size_t)sp * M * N * sizeof(float));
+  }
+  return worst;
 }
 
 // Picks the tile configuration (indices as in launch_gemm's switch), from sweeps of all GEMM shapes of
@@ -977,10 +1023,12 @@ static int launch_dtl_cfg(const GemmArgs& a, hipStream_t s) {
   int splits = 1;
   if (a.out_f32) {
     splits = choose_splits((long)p.tiles_m * p.tiles_n, kt * BK / 64, S::BYTES <= 80 * 1024 ? 2 * kCUs : kCUs);
-    if (splits > 1) {
-      const size_t need = (size_t)splits * a.M * a.N * sizeof(float);
-      if (!a.splitk_ws || a.splitk_ws_bytes < need) splits = 1;
-    }
+  } else if (a.splitk_ws && a.geglu != 1) {
+    splits = choose_splits_epi((long)p.tiles_m * p.tiles_n, kt * BK / 64);
+  }
+  if (splits > 1) {
+    const size_t need = (size_t)splits * a.M * a.N * sizeof(float);
+    if (!a.splitk_ws || a.splitk_ws_bytes < need) splits = 1;
   }
   p.k_tiles_per_split = (kt + splits - 1) / splits;
   splits = (kt + p.k_tiles_per_split - 1) / p.k_tiles_per_split;
@@ -1001,6 +1049,12 @@ static int launch_dtl_cfg(const GemmArgs& a, hipStream_t s) {
     hipLaunchKernelGGL(kern, grid, dim3(WGM * WGN * 64), smem, s, p);
   }
   if (hipGetLastError() != hipSuccess) return set_error(DP_EHIP, "gemm launch failed");
+  if (splits > 1 && !a.out_f32) {
+    KScope ks(KK_REDUCE, 0.0, 4.0 * splits * a.M * a.N + 2.0 * a.M * a.N, s, a.M, a.N, splits);
+    const size_t groups = (size_t)a.M * (a.N / 8);
+    hipLaunchKernelGGL(reduce_epilogue_kernel, dim3((unsigned)((groups + 255) / 256)), dim3(256), 0, s, make_epi<bf16>(a), a.splitk_ws, splits);
+    return hipGetLastError() == hipSuccess ? DP_OK : set_error(DP_EHIP, "gemm split-K epilogue launch failed");
+  }
   if (splits > 1) {
     KScope ks(KK_REDUCE, 0.0, 4.0 * (splits + 1.0) * a.M * a.N, s, a.M, a.N, splits);
     return launch_reduce_partials(a.splitk_ws, splits, (size_t)a.M * a.N, a.out_f32, a.accumulate, s);

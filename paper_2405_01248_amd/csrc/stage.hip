@@ -731,12 +731,17 @@ static int run_stage_bwd(dp_stage* s, const void* const* params, const void* dy,
 // ============================================================ encoder
 enum { E_LN1_G, E_LN1_B, E_WQKV, E_BQKV, E_WO, E_BO, E_LN2_G, E_LN2_B, E_FC1_W, E_FC1_B, E_FC2_W, E_FC2_B, E_PER_LAYER };
 
-struct EncBuf { void *h, *qkv, *a, *f; float* res; size_t bytes; };
+struct EncBuf { void *h, *qkv, *a, *f; float* res; float* splitk; size_t splitk_bytes; size_t bytes; };
 static void plan_encoder(const dp_encoder& e, void* base, int samples, EncBuf& b) {
   Plan p(base);
   const size_t R = (size_t)samples * e.d.seq, d = e.d.d_model, es = e.es;
   b.h = p.take(R * d * es); b.qkv = p.take(R * 3 * d * es); b.a = p.take(R * d * es); b.f = p.take(R * e.d.ff_inner * es);
   b.res = (float*)p.take(R * d * 4);
+  // partial sums of the projections that are split along the contraction on small batches
+  const int Ri = (int)R, di = e.d.d_model, ff = e.d.ff_inner;
+  b.splitk_bytes = std::max(std::max(gemm_epi_splitk_ws_bytes(Ri, 3 * di, di), gemm_epi_splitk_ws_bytes(Ri, di, di)),
+                            std::max(gemm_epi_splitk_ws_bytes(Ri, ff, di), gemm_epi_splitk_ws_bytes(Ri, di, ff)));
+  b.splitk = b.splitk_bytes ? (float*)p.take(b.splitk_bytes) : nullptr;
   b.bytes = p.off;
 }
 
@@ -748,21 +753,26 @@ static int encoder_block(const dp_encoder& e, const void* const* P, float* x, in
   ln.dtype = dt; ln.rows = R; ln.d = d; ln.eps = e.d.ln_eps; ln.x_f32 = 1;
   ln.x = x; ln.y = w.h; ln.gamma = P[E_LN1_G]; ln.beta = P[E_LN1_B];
   DP_TRY(launch_ln_fwd(ln, st));
-  DP_TRY(launch_gemm(gemm_fwd(dt, w.h, R, d, P[E_WQKV], 3 * d, P[E_BQKV], w.qkv), st));
+  GemmArgs g = gemm_fwd(dt, w.h, R, d, P[E_WQKV], 3 * d, P[E_BQKV], w.qkv);
+  g.splitk_ws = w.splitk; g.splitk_ws_bytes = w.splitk_bytes;
+  DP_TRY(launch_gemm(g, st));
   AttnArgs a; memset(&a, 0, sizeof(a));
   a.dtype = dt; a.B = n; a.H = e.d.n_heads; a.Nq = seq; a.Nk = seq; a.d_head = e.d.d_head; a.causal = e.d.causal;
   a.scale = 1.0f / sqrtf((float)e.d.d_head);
   a.q = w.qkv; a.k = at(w.qkv, d, es); a.v = at(w.qkv, 2 * d, es); a.ldq = a.ldk = a.ldv = 3 * d; a.o = w.a; a.ldo = d;
   DP_TRY(launch_attn_fwd(a, st));
-  GemmArgs g = gemm_fwd(dt, w.a, R, d, P[E_WO], d, P[E_BO], x);
+  g = gemm_fwd(dt, w.a, R, d, P[E_WO], d, P[E_BO], x);
+  g.splitk_ws = w.splitk; g.splitk_ws_bytes = w.splitk_bytes;
   g.residual = x; g.ld_res = d; g.residual_f32 = 1; g.out_fused_f32 = 1;
   DP_TRY(launch_gemm(g, st));
   ln.x = x; ln.y = w.h; ln.gamma = P[E_LN2_G]; ln.beta = P[E_LN2_B];
   DP_TRY(launch_ln_fwd(ln, st));
   g = gemm_fwd(dt, w.h, R, d, P[E_FC1_W], ff, P[E_FC1_B], w.f);
+  g.splitk_ws = w.splitk; g.splitk_ws_bytes = w.splitk_bytes;
   g.act = 3;
   DP_TRY(launch_gemm(g, st));
   g = gemm_fwd(dt, w.f, R, ff, P[E_FC2_W], d, P[E_FC2_B], x);
+  g.splitk_ws = w.splitk; g.splitk_ws_bytes = w.splitk_bytes;
   g.residual = x; g.ld_res = d; g.residual_f32 = 1; g.out_fused_f32 = 1;
   DP_TRY(launch_gemm(g, st));
   return DP_OK;
@@ -1084,7 +1094,7 @@ int dp_encoder_profile(dp_encoder* enc, const void* const* params, const int32_t
 
 size_t dp_op_gemm_workspace_bytes(int M, int N, int K) {
   if (M <= 0 || N <= 0 || K <= 0) return 0;
-  return gemm_splitk_ws_bytes(M, N, K);
+  return std::max(gemm_splitk_ws_bytes(M, N, K), gemm_epi_splitk_ws_bytes(M, N, K));
 }
 
 int dp_op_gemm(int dtype, const void* A, int lda, int a_kmajor, const void* B, int ldb, int b_kmajor, int M, int N, int K,

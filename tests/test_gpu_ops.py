@@ -1,0 +1,137 @@
+"""GPU parity one level below the stage: the operator entry points of the C ABI (the kernels the
+stage and the encoder launch, one at a time) against the fp64 oracle of the same operation.
+
+The GEMM cases force every tile configuration of the bf16 MFMA kernels on every operand layout the
+stage uses (y = x W^T, dx = dy W, dW = dy^T x), at sizes that span several tiles and leave ragged
+tails in both output dimensions, and the two split-K paths (fp32 output, storage-dtype output with
+the epilogue applied by the reduction pass)."""
+import numpy as np
+import pytest
+
+import synth_inputs as si
+from oracle import ops
+
+pytestmark = pytest.mark.gpu
+
+TOL_BF16, TOL_F32OUT = 2e-2, 1e-4
+
+# tile_cfg value -> contraction multiple it needs (0 = chosen from the shape; 1..6 register-staged
+# tiles; 7..13 direct-to-LDS tiles, 12 being the 16x16-MFMA tile for y = x W^T only)
+K_MULTIPLE = {0: 8, 1: 8, 2: 8, 3: 8, 4: 8, 5: 8, 6: 8, 7: 32, 8: 32, 9: 32, 10: 64, 11: 64, 12: 64, 13: 32}
+LAYOUTS = {"nt": (0, 0), "nn": (0, 1), "tn": (1, 1)}
+
+
+def _gemm_case(layout, M, N, K, tile_cfg, seed, bias=True, accumulate=False):
+    import torch
+    from paper_2405_01248_amd import binding as B
+    from paper_2405_01248_amd.harness import _np_to_dev, _dev_to_np, rel_err
+    a_k, b_k = LAYOUTS[layout]
+    rng = np.random.default_rng(seed)
+    A = si.round_bf16(rng.standard_normal((M, K)))           # A_eff [M, K]
+    Bm = si.round_bf16(rng.standard_normal((K, N)) * 0.05)    # B_eff [K, N]
+    bv = si.round_bf16(rng.standard_normal(N)) if bias else None
+    f32 = layout == "tn"                                       # the weight-gradient product has an fp32 output
+    dA = _np_to_dev(A.T if a_k else A, "bf16")
+    dB = _np_to_dev(Bm if b_k else Bm.T, "bf16")
+    dbias = _np_to_dev(bv, "bf16") if (bias and not f32) else None
+    ref = ops.linear_fwd(A, Bm.T, bv if (bias and not f32) else None)
+    if f32:
+        C0 = rng.standard_normal((M, N)) if accumulate else np.zeros((M, N))
+        C0 = C0.astype(np.float32).astype(np.float64)
+        dC = torch.from_numpy(C0.astype(np.float32)).to("cuda:0")
+        ref = ref + C0
+    else:
+        dC = torch.zeros((M, N), dtype=torch.bfloat16, device="cuda:0")
+    ws = torch.empty(max(B.op_gemm_workspace_bytes(M, N, K), 256), dtype=torch.uint8, device="cuda:0")
+    B.op_gemm(B.DP_BF16, dA, dA.shape[1], a_k, dB, dB.shape[1], b_k, M, N, K, dbias, dC, N, f32, accumulate, ws, tile_cfg)
+    torch.cuda.synchronize()
+    return rel_err(_dev_to_np(dC), ref)
+
+
+@pytest.mark.parametrize("layout", list(LAYOUTS))
+def test_gemm_every_tile_configuration_ragged(layout):
+    # 333 x 392 output: 2-3 tiles of 128 / 256 per side with ragged tails (tn needs M % 8 == 0: 328)
+    M, N = (328 if layout == "tn" else 333), 392
+    for tile_cfg, mult in K_MULTIPLE.items():
+        if tile_cfg == 12 and layout != "nt":
+            continue
+        for K in (448, 200):
+            if K % mult:
+                continue
+            e = _gemm_case(layout, M, N, K, tile_cfg, seed=tile_cfg * 7 + K)
+            print(f"\n[gemm {layout} cfg {tile_cfg} {M}x{N}x{K}] rel err {e:.2e}", flush=True)
+            assert e <= (TOL_F32OUT if layout == "tn" else TOL_BF16)
+
+
+def test_gemm_unsupported_forced_configuration_is_an_error_not_a_launch():
+    from paper_2405_01248_amd import binding as B
+    for layout, tile_cfg, K in (("nt", 10, 96), ("nn", 12, 448), ("nt", 7, 200)):
+        with pytest.raises(B.DpipeError) as ei:
+            _gemm_case(layout, 136, 136, K, tile_cfg, seed=1)
+        assert ei.value.code == -2
+
+
+@pytest.mark.parametrize("M,N,K", [(77, 768, 3072), (308, 768, 768), (1232, 2304, 768), (40, 6912, 1152)])
+def test_gemm_split_k_with_epilogue_in_the_reduction(M, N, K):
+    # few tiles and a long contraction: the storage-dtype GEMM is split along K (encoder projections
+    # on a partial batch, the adaLN modulation GEMM); bias is applied by the reduction pass
+    e = _gemm_case("nt", M, N, K, 0, seed=M)
+    print(f"\n[gemm nt split-K {M}x{N}x{K}] rel err {e:.2e}", flush=True)
+    assert e <= TOL_BF16
+
+
+@pytest.mark.parametrize("M,N,K,acc", [(640, 640, 8192, False), (1152, 4608, 2048, True), (320, 328, 4104, True)])
+def test_gemm_weight_gradient_split_k(M, N, K, acc):
+    e = _gemm_case("tn", M, N, K, 0, seed=N, accumulate=acc)
+    print(f"\n[gemm tn split-K {M}x{N}x{K} acc={acc}] rel err {e:.2e}", flush=True)
+    assert e <= TOL_F32OUT
+
+
+ATTN_CASES = [
+    # B, H, Nq, Nk, dh, causal
+    (2, 3, 200, 200, 64, False),      # self-attention, ragged query and key tiles
+    (2, 3, 200, 77, 64, False),       # cross-attention to the 77-token context
+    (2, 2, 256, 256, 72, False),      # DiT head width (not a multiple of the MFMA depth)
+    (1, 2, 130, 130, 32, False),
+    (3, 4, 77, 77, 64, True),         # text encoder: causal, forward only
+]
+
+
+@pytest.mark.parametrize("case", ATTN_CASES, ids=lambda c: "B{}H{}q{}k{}d{}{}".format(*c[:5], "c" if c[5] else ""))
+def test_attention_forward_and_backward(case):
+    import torch
+    from paper_2405_01248_amd import binding as B
+    from paper_2405_01248_amd.harness import _np_to_dev, _dev_to_np, rel_err
+    Bt, H, Nq, Nk, dh, causal = case
+    d = H * dh
+    rng = np.random.default_rng(Nq * 31 + Nk)
+    q, k, v, do = (si.round_bf16(rng.standard_normal((Bt, n, d))) for n in (Nq, Nk, Nk, Nq))
+    dq_, dk_, dv_, ddo = (_np_to_dev(t, "bf16") for t in (q, k, v, do))
+    o = torch.zeros((Bt, Nq, d), dtype=torch.bfloat16, device="cuda:0")
+    lse = torch.zeros((Bt, H, Nq), dtype=torch.float32, device="cuda:0")
+    scale = 1.0 / np.sqrt(dh)
+    B.op_attention_fwd(B.DP_BF16, Bt, H, Nq, Nk, dh, causal, scale, dq_, d, dk_, d, dv_, d, o, d, lse)
+    torch.cuda.synchronize()
+    ref_o = ops.attention_fwd(q, k, v, H, causal)
+    e = rel_err(_dev_to_np(o), ref_o)
+    print(f"\n[attention fwd {case}] rel err {e:.2e}", flush=True)
+    assert e <= TOL_BF16
+    # the log-sum-exp the backward re-derives the probabilities from
+    qh = q.reshape(Bt, Nq, H, dh); kh = k.reshape(Bt, Nk, H, dh)
+    s = np.einsum("bqhd,bkhd->bhqk", qh, kh) * scale
+    if causal:
+        s = np.where(np.arange(Nk)[None, :] > np.arange(Nq)[:, None], -np.inf, s)
+    m = s.max(axis=-1)
+    ref_lse = m + np.log(np.exp(s - m[..., None]).sum(axis=-1))
+    e_lse = float(np.max(np.abs(_dev_to_np(lse) - ref_lse)))
+    assert e_lse <= 1e-3 * max(1.0, float(np.max(np.abs(ref_lse)))), e_lse
+    if causal:
+        return                      # the frozen encoder has no backward
+    gq, gk, gv = (torch.zeros_like(t) for t in (dq_, dk_, dv_))
+    delta = torch.zeros((Bt, H, Nq), dtype=torch.float32, device="cuda:0")
+    B.op_attention_bwd(B.DP_BF16, Bt, H, Nq, Nk, dh, scale, dq_, d, dk_, d, dv_, d, o, d, lse, ddo, d, delta, gq, d, gk, d, gv, d)
+    torch.cuda.synchronize()
+    rq, rk, rv = ops.attention_bwd(do, q, k, v, H, False)
+    errs = {"dq": rel_err(_dev_to_np(gq), rq), "dk": rel_err(_dev_to_np(gk), rk), "dv": rel_err(_dev_to_np(gv), rv)}
+    print(f"[attention bwd {case}] {errs}", flush=True)
+    assert max(errs.values()) <= TOL_BF16, errs

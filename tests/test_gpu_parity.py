@@ -272,6 +272,13 @@ def test_encoder_full_size_all_slice_sizes():
         e = rel_err(out, ref)
         print(f"\n[{cfg.name}] slice {b}: rel err {e:.3e}", flush=True)
         assert e <= TOL[cfg.dtype]
+        # run-to-run identical for a given slice size (split-K partial sums are reduced in a fixed order)
+        de.hidden.zero_()
+        de.run_slices(b)
+        torch.cuda.synchronize()
+        assert np.array_equal(de.output(), out)
+        # across slice sizes the results agree to rounding only: the projections of small slices are
+        # split along the contraction, which changes the order of the fp32 sums
         if first is None:
             first = out
-        assert np.array_equal(out, first)
+        assert rel_err(out, first) <= 1e-2
