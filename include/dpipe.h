@@ -171,9 +171,9 @@ int dp_encoder_profile(dp_encoder* enc, const void* const* params, const int32_t
  * overwritten or accumulated into.  `workspace` (fp32 scratch of dp_op_gemm_workspace_bytes; may be
  * NULL, then nothing is split) serves a fixed-order split-K reduction: of the fp32 output, and of a
  * storage-dtype output with few tiles and a long contraction, whose bias is then applied by the
- * reduction pass.  tile_cfg = 0 picks the tile shape from (M,N,K); 1..13 force one (measurement and
- * tests only): 1..6 register-staged tiles, 7..13 direct-to-LDS tiles, which need K % 32 == 0
- * (7, 8, 9, 13) or K % 64 == 0 (10, 11, 12); 12 exists for a_kmajor = b_kmajor = 0 only.  A forced
+ * reduction pass.  tile_cfg = 0 picks the tile shape from (M,N,K); 1..15 force one (measurement and
+ * tests only): 1..6 register-staged tiles, 7..15 direct-to-LDS tiles, which need K % 32 == 0
+ * (7, 8, 9, 13, 15) or K % 64 == 0 (10, 11, 12, 14); 12 exists for a_kmajor = b_kmajor = 0 only.  A forced
  * configuration that does not fit the problem returns DP_EUNSUPPORTED without launching. */
 size_t dp_op_gemm_workspace_bytes(int M, int N, int K);
 int dp_op_gemm(int dtype, const void* A, int lda, int a_kmajor, const void* B, int ldb, int b_kmajor, int M, int N, int K,

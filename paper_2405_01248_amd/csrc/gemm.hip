@@ -890,11 +890,12 @@ static int choose_splits(long tiles, int kt, int slots) {
 // Split-K factor of a GEMM with a storage-dtype output (second pass: reduce_epilogue_kernel).  It pays
 // where a few tiles would each walk the contraction alone while most CUs idle: the frozen encoder's
 // projections on a partial batch (6 to 72 tiles of 128x128, K = 768 or 3072).  Measured on MI355X, encoder
-// forward in samples/s without and with it: 889 -> 1322 (slices of 1 sample), 3374 -> 4555 (4), 12971 -> 16249
-// (16); at 120 tiles (64 samples) the partial sums' traffic cancels the gain, so tile counts above 96 are
-// left alone.  At least 6 64-deep k-tiles per split; a finer split (3 per split) measured no better.
+// forward in samples/s without and with it: 1074 -> 1450 (slices of 1 sample), 4118 -> 5224 (4), 15881 ->
+// 18057 (16).  The second pass costs a launch and the partial sums' traffic, so a short contraction
+// (K < 2048) is split only up to 48 tiles (at 54 and 72 tiles it lost 9 %), a long one up to 96 (at 120
+// tiles, 64 samples, the gain is cancelled).  At least 6 64-deep k-tiles per split; 3 or 12 measured no better.
 static int choose_splits_epi(long tiles, int kt) {
-  if (tiles > 96 || kt < 12) return 1;
+  if (kt < 12 || tiles > (kt >= 32 ? 96 : 48)) return 1;
   const long cap = std::min<long>(std::min<long>(kCUs / std::max<long>(tiles, 1), kt / 6), 16);
   int s = 1;
   while (2 * s <= cap) s *= 2;
@@ -937,7 +938,7 @@ static int choose_cfg(int M, int N, int K, bool a_mc, bool b_mc, bool dtl_ok) {
     // epilogue and barrier stalls: the shorter the contraction and the more tiles per CU, the more it pays.
     const float eff12 = t256x128 <= kCUs ? 0.95f : (K <= 384 ? 1.6f : (K <= 768 ? 1.25f : (K <= 1536 ? 1.15f : 0.9f)));
     const Cand cands[] = {{6, 256, 256, 1.27f, false}, {11, 256, 160, 1.01f, true}, {12, 256, 128, eff12, false},
-                          {9, 256, 128, 1.00f, true}, {10, 128, 128, 0.90f, true}, {8, 128, 128, 0.85f, false}};
+                          {9, 256, 128, 1.00f, true}, {13, 128, 128, 0.98f, true}, {8, 128, 128, 0.85f, false}};
     int best = -1;
     float best_cost = 0.f;
     for (const Cand& c : cands) {
@@ -1138,8 +1139,8 @@ int launch_gemm(const GemmArgs& a, hipStream_t s) {
           return set_error(DP_EINVAL, "gemm: bad fused GeGLU backward arguments");
       }
     }
-    int cfg = (a.force_cfg > 0 && a.force_cfg <= kNumCfgs + 7) ? a.force_cfg - 1 : choose_cfg(a.M, a.N, a.K, a.a_mc != 0, a.b_mc != 0, dtl_addressable(a));
-    if (a.geglu == 1 && (cfg < 6 || cfg > 12 || cfg == 11)) {   // cfg 11 has no column permutation in its loader either
+    int cfg = (a.force_cfg > 0 && a.force_cfg <= kNumCfgs + 9) ? a.force_cfg - 1 : choose_cfg(a.M, a.N, a.K, a.a_mc != 0, a.b_mc != 0, dtl_addressable(a));
+    if (a.geglu == 1 && (cfg < 6 || cfg > 14 || cfg == 11)) {   // cfg 11 has no column permutation in its loader either
       // the column permutation lives in the direct-to-LDS loader
       const long t256x256 = (long)((a.M + 255) / 256) * ((a.N + 255) / 256);
       cfg = t256x256 >= 128 ? 6 : 8;
@@ -1157,6 +1158,8 @@ int launch_gemm(const GemmArgs& a, hipStream_t s) {
       case 10: return launch_dtl_layout<128, 128, 64, 3, 2, 2>(a, s);
       case 11: return launch_dtl16<256, 160, 4, 2>(a, s);
       case 12: return launch_dtl_layout<256, 128, 32, 3, 4, 2>(a, s);   // 72 KB of LDS: two workgroups per CU
+      case 13: return launch_dtl_layout<128, 128, 64, 3, 4, 2>(a, s);   // eight waves on a 128x128 tile
+      case 14: return launch_dtl_layout<128, 128, 32, 4, 4, 2>(a, s);
       default: break;
     }
     return launch_bf16_layout<128, 128, 64, 2, 2>(a, s);

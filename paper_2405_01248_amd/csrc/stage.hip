@@ -1108,10 +1108,10 @@ int dp_op_gemm(int dtype, const void* A, int lda, int a_kmajor, const void* B, i
   if (out_is_f32) {
     if (bias) return set_error(DP_EUNSUPPORTED, "dp_op_gemm: bias with fp32 output is not supported");
     g.out_f32 = (float*)C; g.ldo32 = ldc; g.accumulate = accumulate != 0;
-    g.splitk_ws = (float*)workspace; g.splitk_ws_bytes = workspace ? workspace_bytes : 0;
   } else {
     g.out = C; g.ldo = ldc; g.bias = bias;
   }
+  g.splitk_ws = (float*)workspace; g.splitk_ws_bytes = workspace ? workspace_bytes : 0;
   g.force_cfg = tile_cfg;
   return launch_gemm(g, (hipStream_t)hip_stream);
 }
