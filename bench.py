@@ -164,6 +164,52 @@ def kernel_roofline(workload, names, si, DeviceStage, DeviceEncoder, passes=3):
     return roof, classes
 
 
+def partition_report(si, DeviceStage):
+    """Partitioner (Sec. 4.1 / 4.3) on cost rows measured here: the 7 identical-shape DiT blocks of cfg4 are profiled at
+    local batch 32 / r for r = 1, 2, 4, 8 and tiled 4x to the 28 layers of the whole backbone; link figures are one xGMI
+    link for p2p and a 7-link reduce-scatter + all-gather for the gradient all-reduce."""
+    import torch
+    from paper_2405_01248_amd import binding
+    from oracle import partition as P      # timed beside the library as the CPU baseline of this row
+    base = si.CONFIG4
+    rows = []
+    for b in (32, 16, 8, 4):
+        cfg = base.replace(batch=b, name=f"{base.name}_b{b}")
+        ds = DeviceStage(cfg, si.make_stage_inputs(cfg, seed=0))
+        ds.step()
+        blk = ds.stage.profile(ds.params, ds.x, ds.cc, ds.y, ds.dy, ds.dx, ds.d_cond, ds.dparams, ds.ws, reps=10)
+        torch.cuda.synchronize()
+        for rep in range(4):
+            rows += [dict(r, layer=r["layer"] + rep * cfg.n_blocks) for r in blk]
+        del ds
+        torch.cuda.empty_cache()
+    L = 4 * base.n_blocks
+    prof = P.Profile(L, {}, {}, {}, {}, [0] * L, {})
+    for r in rows:
+        for name, tab in (("fwd_ms", prof.fwd_ms), ("bwd_ms", prof.bwd_ms), ("cf_bytes", prof.cf_bytes), ("cb_bytes", prof.cb_bytes)):
+            tab.setdefault(r["batch"], [0] * L)[r["layer"]] = r[name]
+        prof.grad_bytes[r["layer"]] = r["grad_bytes"]
+        if r["layer"] == L - 1:
+            prof.out_bytes[r["batch"]] = r["out_bytes"]
+    link = dict(p2p_gbps=153.0, p2p_latency_ms=0.01, ar_gbps=7 * 153.0 / 2, ar_latency_ms=0.05)
+    out = {"workload": "cfg4 blocks tiled to 28 layers, B=32, M=8, D=8", "links": link,
+           "per_layer_ms": {str(b): {"fwd": prof.fwd_ms[b][0], "bwd": prof.bwd_ms[b][0]} for b in sorted(prof.fwd_ms)}, "plans": []}
+    for p, uni in ((0.0, False), (0.5, False), (0.5, True)):
+        t0 = time.perf_counter()
+        for _ in range(20):
+            got = binding.partition_solve(rows, 32, 8, 8, self_cond_prob=p, uniform_replication=uni, **link)
+        t_lib = (time.perf_counter() - t0) / 20
+        o = P.Options(micro_batch=32, n_micro_batches=8, n_devices=8, self_cond_prob=p, uniform_replication=uni, **link)
+        t0 = time.perf_counter()
+        ref = P.solve(prof, o)
+        t_or = time.perf_counter() - t0
+        same = (got["first_layer"], got["replicas"]) == (ref.first_layer, ref.replicas) and abs(got["t_max_ms"] - ref.t_max_ms) <= 1e-9 * ref.t_max_ms
+        out["plans"].append({"self_cond_prob": p, "uniform_replication": uni, "layers_per_stage": got["n_layers"], "replicas": got["replicas"],
+                             "t0_ms": got["t0_ms"], "gap_ms": got["gap_ms"], "t_max_ms": got["t_max_ms"], "solve_ms_library": t_lib * 1e3,
+                             "solve_ms_oracle": t_or * 1e3, "matches_oracle": same})
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -177,6 +223,9 @@ def main():
                          "(per-kernel profiling; the default overlaps them)")
     ap.add_argument("--fusion", type=int, default=None, choices=[0, 1, 2, 3],
                     help="GeGLU epilogue-fusion mask of the stage (library default when omitted); for A/B timing")
+    ap.add_argument("--partition", action="store_true",
+                    help="instead of the step benchmark: profile the DiT stage's blocks at local batch sizes 32, 16, 8, 4 on this "
+                         "GPU, tile them to a 28-layer backbone and run the partitioner (library and oracle) for 8 devices")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives are part of it); use --gpus 1", file=sys.stderr)
@@ -212,6 +261,10 @@ def main():
                            "ms_per_call": sec * 1e3 * b / c.global_batch,
                            "mfma_peak_frac": encoder_flops_per_sample(c) * c.global_batch / sec / MFMA_PEAK}
         return de, out
+
+    if args.partition:
+        print(json.dumps(partition_report(si, DeviceStage)))
+        return
 
     result = {"n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "higher_is_better": True, "scaling": "weak",
               "vs_baseline": None, "dtype": "bf16", "data": "synthetic"}

@@ -161,6 +161,41 @@ int dp_encoder_profile(dp_encoder* enc, const void* const* params, const int32_t
                        int global_batch, const int* batches, int n_batches, int reps, void* workspace,
                        size_t workspace_bytes, dp_layer_cost* rows, int max_rows, int* n_rows, void* hip_stream);
 
+/* Backbone partitioner (Sec. 4.1, Eq. 1-9; self-conditioning Sec. 4.3, Eq. 17-18), host only: no
+ * GPU call is made.  Input is the cost profile of the backbone, rows [host] of component 0 (other
+ * components are ignored): one row per (layer, batch) with layers 0..L-1 complete for every batch
+ * size that appears.  A stage replicated on r devices runs at local batch micro_batch / r: r must
+ * divide micro_batch and that batch size must be in the profile, otherwise that replication is
+ * infeasible.  The dynamic programme keeps, for the first l layers in s stages on devices 1..d with
+ * the last stage on the last r devices, W = T_0 (Eq. 3, 7), W_SC (Eq. 17) and Y = T_0^{S-C} (Eq. 4-6,
+ * 8; clamped at zero) of the candidate that minimises (M + 2S - 2)(p W_SC + (1 - p) W) + Y, and
+ * returns the minimum over the replication r of the last stage (Eq. 2), over S = 1..min(L, D,
+ * max_stages), plus p T_F with T_F = O_L(micro_batch) / R_p2p + L_p2p.  The first stage has no incoming
+ * transfer.  Ties go to fewer stages, then smaller r, earlier cut, smaller replication of the stage
+ * before.  Units: ms, bytes, GB/s = 1e9 bytes per second.
+ * Errors: DP_EINVAL for null arguments, incomplete or duplicate rows, non-positive sizes or
+ * bandwidths, p outside [0, 1], p > 0 without rows at batch = micro_batch; DP_EUNSUPPORTED when no
+ * replication vector is feasible or stages x devices^2 x layers exceeds 64M.  `plan` [host] is
+ * written on success only; entries past n_stages are zero. */
+#define DP_MAX_STAGES 64
+typedef struct {
+  int micro_batch;          /* B */
+  int n_micro_batches;      /* M */
+  int n_devices;            /* D, devices of one pipeline-parallel group, <= DP_MAX_STAGES */
+  int max_stages;           /* 0: no limit beyond min(L, D) */
+  int uniform_replication;  /* 1: every stage on the same number of devices (the setting of Sec. 6) */
+  double p2p_gbps, p2p_latency_ms;   /* R_p2p, L_p2p */
+  double ar_gbps, ar_latency_ms;     /* R_ar, L_ar */
+  double self_cond_prob;             /* p; 0 = Eq. 1 alone */
+} dp_partition_opts;
+typedef struct {
+  int n_stages;
+  int first_layer[DP_MAX_STAGES], n_layers[DP_MAX_STAGES], replicas[DP_MAX_STAGES];
+  double t0_ms, t0_sc_ms, gap_ms, tf_ms;   /* W, W_SC, Y, T_F of the chosen partition */
+  double t_max_ms;                         /* the bound of Eq. 1 / Eq. 18 in expectation */
+} dp_partition_plan;
+int dp_partition_solve(const dp_layer_cost* rows, int n_rows, const dp_partition_opts* opts, dp_partition_plan* plan);
+
 /* Operator-level entry points: the same kernels the stage calls, exposed one by one for unit
  * tests and per-kernel measurement (the cost profile of Sec. 4 is per layer; these go one
  * level below it).  All pointers [device]; dtype as in dp_dtype.

@@ -40,6 +40,20 @@ class LayerCost(C.Structure):
         return {n: getattr(self, n) for n, _ in self._fields_}
 
 
+DP_MAX_STAGES = 64
+
+
+class PartitionOpts(C.Structure):
+    _fields_ = [(n, C.c_int) for n in ("micro_batch", "n_micro_batches", "n_devices", "max_stages", "uniform_replication")] + \
+               [(n, C.c_double) for n in ("p2p_gbps", "p2p_latency_ms", "ar_gbps", "ar_latency_ms", "self_cond_prob")]
+
+
+class PartitionPlan(C.Structure):
+    _fields_ = [("n_stages", C.c_int), ("first_layer", C.c_int * DP_MAX_STAGES), ("n_layers", C.c_int * DP_MAX_STAGES),
+                ("replicas", C.c_int * DP_MAX_STAGES)] + \
+               [(n, C.c_double) for n in ("t0_ms", "t0_sc_ms", "gap_ms", "tf_ms", "t_max_ms")]
+
+
 class KernelTime(C.Structure):
     _fields_ = [("kind", C.c_int), ("m", C.c_int), ("n", C.c_int), ("k", C.c_int), ("ms", C.c_float), ("flops", C.c_double),
                 ("bytes", C.c_double)]
@@ -52,7 +66,7 @@ EXPORTS = ["dp_stage_create", "dp_stage_destroy", "dp_stage_set_overlap", "dp_st
            "stage_fwd", "stage_bwd", "dp_encoder_create", "dp_encoder_destroy", "dp_encoder_param_count",
            "dp_encoder_param_shape", "dp_encoder_workspace_bytes", "encoder_fwd_partial", "dp_stage_profile",
            "dp_encoder_profile", "dp_ktime_begin", "dp_ktime_end", "dp_last_error", "dp_op_gemm", "dp_op_gemm_workspace_bytes",
-           "dp_op_attention_fwd", "dp_op_attention_bwd"]
+           "dp_op_attention_fwd", "dp_op_attention_bwd", "dp_partition_solve"]
 
 
 def library_path() -> str:
@@ -93,6 +107,7 @@ def load_library():
     lib.dp_op_gemm.argtypes = [i, vp, i, i, vp, i, i, i, i, i, vp, vp, i, i, i, vp, sz, i, vp]
     lib.dp_op_attention_fwd.argtypes = [i, i, i, i, i, i, i, f, vp, i, vp, i, vp, i, vp, i, vp, vp]
     lib.dp_op_attention_bwd.argtypes = [i, i, i, i, i, i, f, vp, i, vp, i, vp, i, vp, i, vp, vp, i, vp, vp, i, vp, i, vp, i, vp]
+    lib.dp_partition_solve.argtypes = [C.POINTER(LayerCost), i, C.POINTER(PartitionOpts), C.POINTER(PartitionPlan)]
     lib.dp_ktime_begin.argtypes = [i]
     lib.dp_ktime_end.argtypes = [C.POINTER(KernelTime), i, C.POINTER(i)]
     _LIB = lib
@@ -241,6 +256,25 @@ def ktime_end(max_records: int = 65536):
     _check(load_library().dp_ktime_end(rows, max_records, C.byref(n)))
     return [{"kind": KERNEL_KINDS.get(rows[j].kind, str(rows[j].kind)), "m": rows[j].m, "n": rows[j].n, "k": rows[j].k,
              "ms": rows[j].ms, "flops": rows[j].flops, "bytes": rows[j].bytes} for j in range(n.value)]
+
+
+def partition_solve(rows, micro_batch, n_micro_batches, n_devices, p2p_gbps, p2p_latency_ms, ar_gbps, ar_latency_ms,
+                    self_cond_prob=0.0, max_stages=0, uniform_replication=False):
+    """rows: sequence of LayerCost or of dicts with its fields (host data).  Returns a dict with the plan."""
+    arr = (LayerCost * len(rows))()
+    for i, r in enumerate(rows):
+        d = r if isinstance(r, dict) else r.as_dict()
+        for n, _ in LayerCost._fields_:
+            setattr(arr[i], n, d[n])
+    opts = PartitionOpts(micro_batch, n_micro_batches, n_devices, max_stages, int(uniform_replication), p2p_gbps, p2p_latency_ms,
+                         ar_gbps, ar_latency_ms, self_cond_prob)
+    plan = PartitionPlan()
+    lib = load_library()
+    _check(lib.dp_partition_solve(arr, len(rows), C.byref(opts), C.byref(plan)))
+    n = plan.n_stages
+    return {"n_stages": n, "first_layer": list(plan.first_layer[:n]), "n_layers": list(plan.n_layers[:n]),
+            "replicas": list(plan.replicas[:n]), "t0_ms": plan.t0_ms, "t0_sc_ms": plan.t0_sc_ms, "gap_ms": plan.gap_ms,
+            "tf_ms": plan.tf_ms, "t_max_ms": plan.t_max_ms}
 
 
 def op_gemm(dtype, A, lda, a_kmajor, B, ldb, b_kmajor, M, N, K, bias, Cout, ldc, out_is_f32=False, accumulate=False,

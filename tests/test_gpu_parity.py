@@ -160,6 +160,42 @@ def test_stage_cost_profile_rows(cfg):
         assert np.array_equal(got["grads"][k], want["grads"][k]), k
 
 
+def test_partitioner_on_measured_stage_profiles():
+    """Closes the loop of Sec. 4: cost rows measured on the GPU at the local batch sizes B / r feed the library's
+    partitioner, whose plan must be the oracle's plan for the same rows (host arithmetic, compared exactly)."""
+    import dataclasses
+    import torch
+    from oracle import partition as P
+    from paper_2405_01248_amd import binding as B
+    from paper_2405_01248_amd.harness import DeviceStage
+    base = dataclasses.replace(SMALL_DIT, n_blocks=4, self_cond=False)
+    rows = []
+    for b in (4, 2, 1):
+        cfg = dataclasses.replace(base, batch=b, name=f"{base.name}_b{b}")
+        ds = DeviceStage(cfg, si.make_stage_inputs(cfg, seed=b))
+        ds.step(self_cond=False)
+        rows += ds.stage.profile(ds.params, ds.x, ds.cc, ds.y, ds.dy, ds.dx, ds.d_cond, ds.dparams, ds.ws, reps=3)
+        torch.cuda.synchronize()
+        del ds
+    assert len(rows) == 12
+    prof = P.Profile(4, {}, {}, {}, {}, [0] * 4, {})
+    for r in rows:
+        for name, tab in (("fwd_ms", prof.fwd_ms), ("bwd_ms", prof.bwd_ms), ("cf_bytes", prof.cf_bytes), ("cb_bytes", prof.cb_bytes)):
+            tab.setdefault(r["batch"], [0] * 4)[r["layer"]] = r[name]
+        prof.grad_bytes[r["layer"]] = r["grad_bytes"]
+        if r["layer"] == 3:
+            prof.out_bytes[r["batch"]] = r["out_bytes"]
+    for D, p, uni in ((4, 0.0, False), (4, 0.5, False), (2, 1.0, True), (3, 0.5, False)):
+        o = P.Options(micro_batch=4, n_micro_batches=8, n_devices=D, p2p_gbps=50.0, p2p_latency_ms=0.01, ar_gbps=100.0,
+                      ar_latency_ms=0.05, self_cond_prob=p, uniform_replication=uni)
+        ref = P.solve(prof, o)
+        got = B.partition_solve(rows, 4, 8, D, 50.0, 0.01, 100.0, 0.05, p, 0, uni)
+        print(f"\n[partition D={D} p={p}] stages {got['n_layers']} x replicas {got['replicas']}: T_max {got['t_max_ms']:.3f} ms", flush=True)
+        assert (got["n_stages"], got["first_layer"], got["replicas"]) == (ref.n_stages, ref.first_layer, ref.replicas)
+        assert abs(got["t_max_ms"] - ref.t_max_ms) <= 1e-9 * ref.t_max_ms
+        assert sum(got["replicas"]) == D and sum(got["n_layers"]) == 4
+
+
 def test_encoder_cost_profile_rows():
     import torch
     from paper_2405_01248_amd.harness import DeviceEncoder
