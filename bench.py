@@ -207,7 +207,55 @@ def partition_report(si, DeviceStage):
         out["plans"].append({"self_cond_prob": p, "uniform_replication": uni, "layers_per_stage": got["n_layers"], "replicas": got["replicas"],
                              "t0_ms": got["t0_ms"], "gap_ms": got["gap_ms"], "t_max_ms": got["t_max_ms"], "solve_ms_library": t_lib * 1e3,
                              "solve_ms_oracle": t_or * 1e3, "matches_oracle": same})
-    return out
+    return out, prof, rows
+
+
+def bubble_report(si, DeviceStage, DeviceEncoder):
+    """Bubble filling (Sec. 5) on measured profiles: the partition of --partition (self-conditioning off), one 1F1B
+    iteration simulated from the measured stage times, and the frozen text encoder (profiled here at local batch 4..64,
+    training batch = M x B = 256) placed into its bubbles.  The paper's 10 ms floor for a bubble assumes stages of
+    hundreds of ms; these stages take 8 ms per micro-batch, so the floor is scaled to 0.1 ms."""
+    import torch
+    from paper_2405_01248_amd import binding
+    from oracle import bubbles as Bu
+    part, prof, _ = partition_report(si, DeviceStage)
+    plan = part["plans"][0]
+    S, reps, M, Bm = len(plan["replicas"]), plan["replicas"], 8, 32
+    f, bw, cf = [], [], []
+    lo = 0
+    for s in range(S):
+        b = Bm // reps[s]
+        hi = lo + plan["layers_per_stage"][s]
+        f.append(sum(prof.fwd_ms[b][lo:hi])); bw.append(sum(prof.bwd_ms[b][lo:hi]))
+        if s:
+            cf.append(prof.cf_bytes[b][lo - 1] / (part["links"]["p2p_gbps"] * 1e9) * 1e3 + part["links"]["p2p_latency_ms"])
+        lo = hi
+    cfg = si.CONFIG5
+    de = DeviceEncoder(cfg, si.make_encoder_inputs(cfg, seed=0))
+    batches = [4, 8, 12, 16, 24, 32, 48, 64]
+    rows = de.enc.profile(de.params, de.ids, de.hidden, de.gb, batches, de.ws, reps=5)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    bubbles, t_iter = binding.bubbles_1f1b(f, bw, reps, M, cf or None, cf or None, None, 0.1)
+    fills, summ = binding.bubbles_fill(bubbles, rows, M * Bm, sum(reps))
+    t_lib = time.perf_counter() - t0
+    nl = cfg.n_layers + 2
+    comp = Bu.Component(nl, {b: [r["fwd_ms"] for r in rows if r["batch"] == b] for b in batches})
+    t0 = time.perf_counter()
+    busy, t = Bu.simulate_1f1b(f, bw, M, cf or None, cf or None)
+    ref_b = Bu.find_bubbles(busy, t, reps, 0.1)
+    ref = Bu.fill_all(ref_b, [comp], M * Bm, sum(reps))
+    t_or = time.perf_counter() - t0
+    same = len(bubbles) == len(ref_b) and abs(summ["filled_device_ms"] - ref.filled_device_ms) <= 1e-9 * max(ref.filled_device_ms, 1e-9) \
+        and abs(summ["leftover_ms"] - ref.leftover_ms) <= 1e-9 * max(ref.leftover_ms, 1e-9)
+    D = sum(reps)
+    return {"workload": part["workload"], "stages": {"layers": plan["layers_per_stage"], "replicas": reps, "fwd_ms": f, "bwd_ms": bw, "comm_ms": cf},
+            "iteration_ms": t_iter, "n_bubbles": len(bubbles), "bubble_ratio": summ["bubble_device_ms"] / (D * t_iter),
+            "bubble_ratio_after_filling": (summ["bubble_device_ms"] - summ["filled_device_ms"]) / (D * (t_iter + summ["leftover_ms"])),
+            "encoder_ms_at_local_batch": {str(b): sum(comp.fwd_ms[b]) for b in batches},
+            "filled_device_ms": summ["filled_device_ms"], "bubble_device_ms": summ["bubble_device_ms"], "leftover_ms": summ["leftover_ms"],
+            "placements": [(r["bubble"], r["first_layer"], r["n_layers"], r["samples"], r["partial"]) for r in fills],
+            "solve_ms_library": t_lib * 1e3, "solve_ms_oracle": t_or * 1e3, "matches_oracle": same}
 
 
 def main():
@@ -223,6 +271,9 @@ def main():
                          "(per-kernel profiling; the default overlaps them)")
     ap.add_argument("--fusion", type=int, default=None, choices=[0, 1, 2, 3],
                     help="GeGLU epilogue-fusion mask of the stage (library default when omitted); for A/B timing")
+    ap.add_argument("--bubbles", action="store_true",
+                    help="instead of the step benchmark: --partition's plan for cfg4, its 1F1B bubbles, and their filling with "
+                         "the text encoder profiled here at the regular partial-batch sizes (library and oracle)")
     ap.add_argument("--partition", action="store_true",
                     help="instead of the step benchmark: profile the DiT stage's blocks at local batch sizes 32, 16, 8, 4 on this "
                          "GPU, tile them to a 28-layer backbone and run the partitioner (library and oracle) for 8 devices")
@@ -263,7 +314,10 @@ def main():
         return de, out
 
     if args.partition:
-        print(json.dumps(partition_report(si, DeviceStage)))
+        print(json.dumps(partition_report(si, DeviceStage)[0]))
+        return
+    if args.bubbles:
+        print(json.dumps(bubble_report(si, DeviceStage, DeviceEncoder)))
         return
 
     result = {"n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "higher_is_better": True, "scaling": "weak",

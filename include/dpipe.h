@@ -196,6 +196,60 @@ typedef struct {
 } dp_partition_plan;
 int dp_partition_solve(const dp_layer_cost* rows, int n_rows, const dp_partition_opts* opts, dp_partition_plan* plan);
 
+/* Pipeline bubbles and their filling (Sec. 5, Algorithms 1 and 2), host only: no GPU call is made.
+ *
+ * dp_bubbles_1f1b simulates one iteration of the FIFO-1F1B schedule of n_stages stages and
+ * n_micro_batches micro-batches: stage s runs min(S - 1 - s, M) warm-up forwards, then alternates one
+ * forward and one backward, then drains its backwards, micro-batches in order; an operation starts when
+ * its stage is free and its input has arrived (forward of the stage before, backward of the stage
+ * after, plus comm_fwd_ms[s] / comm_bwd_ms[s] between stages s and s + 1; NULL = 0).  tail_ms[s]
+ * (NULL = 0) is busy time after the stage's last backward (gradient synchronisation not overlapped).
+ * All arrays [host]: fwd_ms, bwd_ms, replicas, tail_ms have n_stages entries, the comm arrays
+ * n_stages - 1.  A bubble is a maximal time span over which the set of idle stages is constant and not
+ * empty; n_devices = sum of the replicas of those stages, stage_mask bit s = stage s idle.  Bubbles
+ * shorter than min_ms are dropped (the paper uses 10 ms).  They are written in chronological order;
+ * *n_out is their number, also when it exceeds max_out (then DP_EWORKSPACE and the first max_out are
+ * written); *iteration_ms (may be NULL) is the length of the iteration. */
+typedef struct {
+  double start_ms, end_ms;
+  int n_devices;
+  uint64_t stage_mask;
+} dp_bubble;
+int dp_bubbles_1f1b(int n_stages, const double* fwd_ms, const double* bwd_ms, const int* replicas, int n_micro_batches,
+                    const double* comm_fwd_ms, const double* comm_bwd_ms, const double* tail_ms, double min_ms,
+                    dp_bubble* out, int max_out, int* n_out, double* iteration_ms);
+
+/* dp_bubbles_fill fills the bubbles, in the order given (chronological), with the layers of the
+ * non-trainable components described by the cost rows with component >= 1 (fwd_ms at the local batch
+ * sizes profiled; layers 0..L-1 complete for every batch size of a component; components are taken in
+ * ascending id).  dep_pairs [2 * n_dep_pairs]: (component, component it depends on); a component is
+ * ready in a bubble when all layers of its dependencies were placed in earlier bubbles.  `batch` is the
+ * training batch size: a whole-batch layer on the d idle devices of a bubble runs at local batch
+ * ceil(batch / d); a local batch size between two profiled ones is interpolated linearly, below the
+ * smallest it costs as the smallest, above the largest proportionally.  Per bubble: Algorithm 2 lists
+ * the ways to pack whole-batch layers of the ready components; Algorithm 1 adds to each at most one
+ * partial-batch layer, the next layer of one component on b samples, b / d one of 4, 8, 12, 16, 24, 32,
+ * 48, 64, 96, b smaller than what is left of that layer and as large as fits; the candidate that runs
+ * longest is kept.  A layer begun on part of the batch is the first ready layer of its component in the
+ * following bubbles and counts as a whole-batch layer on its remaining samples.  Output: one dp_fill
+ * row per run of whole-batch layers of a component in a bubble (partial = 0: layers first_layer ..
+ * first_layer + n_layers - 1, `samples` = samples of the first of them, the others take the whole
+ * batch) and one per partial-batch layer (partial = 1, n_layers = 1, `samples` = b); fill_ms is the
+ * run time of the bubble's whole filling.  The summary holds the idle device-time offered, the
+ * device-time filled, and leftover_ms: the time of the layers that fit no bubble, run after the
+ * pipeline on all n_devices devices.  summary.n_fills is the number of rows, also when it exceeds
+ * max_fills (then DP_EWORKSPACE). */
+typedef struct {
+  int bubble, component, first_layer, n_layers, samples, partial;
+  double fill_ms;
+} dp_fill;
+typedef struct {
+  double bubble_device_ms, filled_device_ms, leftover_ms;
+  int n_fills;
+} dp_fill_summary;
+int dp_bubbles_fill(const dp_bubble* bubbles, int n_bubbles, const dp_layer_cost* rows, int n_rows, const int* dep_pairs,
+                    int n_dep_pairs, int batch, int n_devices, dp_fill* fills, int max_fills, dp_fill_summary* summary);
+
 /* Operator-level entry points: the same kernels the stage calls, exposed one by one for unit
  * tests and per-kernel measurement (the cost profile of Sec. 4 is per layer; these go one
  * level below it).  All pointers [device]; dtype as in dp_dtype.

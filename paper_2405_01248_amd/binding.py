@@ -54,6 +54,18 @@ class PartitionPlan(C.Structure):
                [(n, C.c_double) for n in ("t0_ms", "t0_sc_ms", "gap_ms", "tf_ms", "t_max_ms")]
 
 
+class Bubble(C.Structure):
+    _fields_ = [("start_ms", C.c_double), ("end_ms", C.c_double), ("n_devices", C.c_int), ("stage_mask", C.c_uint64)]
+
+
+class FillRow(C.Structure):
+    _fields_ = [(n, C.c_int) for n in ("bubble", "component", "first_layer", "n_layers", "samples", "partial")] + [("fill_ms", C.c_double)]
+
+
+class FillSummary(C.Structure):
+    _fields_ = [("bubble_device_ms", C.c_double), ("filled_device_ms", C.c_double), ("leftover_ms", C.c_double), ("n_fills", C.c_int)]
+
+
 class KernelTime(C.Structure):
     _fields_ = [("kind", C.c_int), ("m", C.c_int), ("n", C.c_int), ("k", C.c_int), ("ms", C.c_float), ("flops", C.c_double),
                 ("bytes", C.c_double)]
@@ -66,7 +78,7 @@ EXPORTS = ["dp_stage_create", "dp_stage_destroy", "dp_stage_set_overlap", "dp_st
            "stage_fwd", "stage_bwd", "dp_encoder_create", "dp_encoder_destroy", "dp_encoder_param_count",
            "dp_encoder_param_shape", "dp_encoder_workspace_bytes", "encoder_fwd_partial", "dp_stage_profile",
            "dp_encoder_profile", "dp_ktime_begin", "dp_ktime_end", "dp_last_error", "dp_op_gemm", "dp_op_gemm_workspace_bytes",
-           "dp_op_attention_fwd", "dp_op_attention_bwd", "dp_partition_solve"]
+           "dp_op_attention_fwd", "dp_op_attention_bwd", "dp_partition_solve", "dp_bubbles_1f1b", "dp_bubbles_fill"]
 
 
 def library_path() -> str:
@@ -108,6 +120,9 @@ def load_library():
     lib.dp_op_attention_fwd.argtypes = [i, i, i, i, i, i, i, f, vp, i, vp, i, vp, i, vp, i, vp, vp]
     lib.dp_op_attention_bwd.argtypes = [i, i, i, i, i, i, f, vp, i, vp, i, vp, i, vp, i, vp, vp, i, vp, vp, i, vp, i, vp, i, vp]
     lib.dp_partition_solve.argtypes = [C.POINTER(LayerCost), i, C.POINTER(PartitionOpts), C.POINTER(PartitionPlan)]
+    dptr = C.POINTER(C.c_double)
+    lib.dp_bubbles_1f1b.argtypes = [i, dptr, dptr, C.POINTER(i), i, dptr, dptr, dptr, C.c_double, C.POINTER(Bubble), i, C.POINTER(i), dptr]
+    lib.dp_bubbles_fill.argtypes = [C.POINTER(Bubble), i, C.POINTER(LayerCost), i, C.POINTER(i), i, i, i, C.POINTER(FillRow), i, C.POINTER(FillSummary)]
     lib.dp_ktime_begin.argtypes = [i]
     lib.dp_ktime_end.argtypes = [C.POINTER(KernelTime), i, C.POINTER(i)]
     _LIB = lib
@@ -275,6 +290,45 @@ def partition_solve(rows, micro_batch, n_micro_batches, n_devices, p2p_gbps, p2p
     return {"n_stages": n, "first_layer": list(plan.first_layer[:n]), "n_layers": list(plan.n_layers[:n]),
             "replicas": list(plan.replicas[:n]), "t0_ms": plan.t0_ms, "t0_sc_ms": plan.t0_sc_ms, "gap_ms": plan.gap_ms,
             "tf_ms": plan.tf_ms, "t_max_ms": plan.t_max_ms}
+
+
+def _darr(v):
+    return None if v is None else (C.c_double * len(v))(*v)
+
+
+def bubbles_1f1b(fwd_ms, bwd_ms, replicas, n_micro_batches, comm_fwd_ms=None, comm_bwd_ms=None, tail_ms=None, min_ms=0.0,
+                 max_out=4096):
+    """Returns (list of bubble dicts, iteration_ms)."""
+    S = len(fwd_ms)
+    out = (Bubble * max_out)()
+    n, t = C.c_int(0), C.c_double(0.0)
+    _check(load_library().dp_bubbles_1f1b(S, _darr(fwd_ms), _darr(bwd_ms), (C.c_int * S)(*replicas), n_micro_batches,
+                                          _darr(comm_fwd_ms), _darr(comm_bwd_ms), _darr(tail_ms), min_ms, out, max_out,
+                                          C.byref(n), C.byref(t)))
+    return [{"start_ms": out[i].start_ms, "end_ms": out[i].end_ms, "n_devices": out[i].n_devices,
+             "stages": tuple(s for s in range(S) if out[i].stage_mask >> s & 1)} for i in range(n.value)], t.value
+
+
+def bubbles_fill(bubbles, rows, batch, n_devices, deps=(), max_fills=4096):
+    """bubbles: dicts as returned by bubbles_1f1b (start_ms, end_ms, n_devices); rows: LayerCost dicts of the
+    non-trainable components; deps: (component, depends_on) pairs.  Returns (fill row dicts, summary dict)."""
+    barr = (Bubble * max(len(bubbles), 1))()
+    for i, b in enumerate(bubbles):
+        barr[i].start_ms, barr[i].end_ms, barr[i].n_devices = b["start_ms"], b["end_ms"], b["n_devices"]
+        barr[i].stage_mask = sum(1 << s for s in b.get("stages", ()))
+    arr = (LayerCost * len(rows))()
+    for i, r in enumerate(rows):
+        for n, _ in LayerCost._fields_:
+            setattr(arr[i], n, r[n])
+    flat = [x for pair in deps for x in pair]
+    darr = (C.c_int * max(len(flat), 1))(*flat)
+    fills = (FillRow * max_fills)()
+    summ = FillSummary()
+    _check(load_library().dp_bubbles_fill(barr, len(bubbles), arr, len(rows), darr, len(deps), batch, n_devices, fills, max_fills,
+                                          C.byref(summ)))
+    names = [n for n, _ in FillRow._fields_]
+    return ([{n: getattr(fills[i], n) for n in names} for i in range(summ.n_fills)],
+            {"bubble_device_ms": summ.bubble_device_ms, "filled_device_ms": summ.filled_device_ms, "leftover_ms": summ.leftover_ms})
 
 
 def op_gemm(dtype, A, lda, a_kmajor, B, ldb, b_kmajor, M, N, K, bias, Cout, ldc, out_is_f32=False, accumulate=False,

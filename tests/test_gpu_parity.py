@@ -214,6 +214,42 @@ def test_encoder_cost_profile_rows():
             assert r["out_bytes"] == b * cfg.seq * cfg.d_model * 2 and r["cf_bytes"] == r["out_bytes"]
 
 
+def test_bubble_filling_on_measured_encoder_profile():
+    """Closes the loop of Sec. 5: the encoder's per-layer times measured on the GPU at several partial-batch sizes
+    feed the library's bubble filler, whose placement must be the oracle's for the same rows and bubbles."""
+    import torch
+    from oracle import bubbles as Bu
+    from paper_2405_01248_amd import binding as B
+    from paper_2405_01248_amd.harness import DeviceEncoder
+    cfg = SMALL_ENC.replace(global_batch=32)
+    de = DeviceEncoder(cfg, si.make_encoder_inputs(cfg, seed=0))
+    batches = [4, 8, 16, 32]
+    rows = de.enc.profile(de.params, de.ids, de.hidden, de.gb, batches, de.ws, reps=3)
+    torch.cuda.synchronize()
+    nl = cfg.n_layers + 2
+    comp = Bu.Component(nl, {b: [r["fwd_ms"] for r in rows if r["batch"] == b] for b in batches})
+    per_layer = sum(comp.fwd_ms[16]) / nl
+    # a 3-stage pipeline whose bubbles are of the order of a few encoder layers at local batch 16
+    f, bw, rep, M = [3 * per_layer] * 3, [6 * per_layer] * 3, [2, 2, 2], 4
+    got_b, t_iter = B.bubbles_1f1b(f, bw, rep, M)
+    busy, t = Bu.simulate_1f1b(f, bw, M)
+    ref_b = Bu.find_bubbles(busy, t, rep)
+    assert t_iter == t and [(x["start_ms"], x["end_ms"], x["n_devices"]) for x in got_b] == [(x.start, x.end, x.devices) for x in ref_b]
+    fills, summ = B.bubbles_fill(got_b, rows, 64, 6)
+    ref = Bu.fill_all(ref_b, [comp], 64, 6)
+    want = []
+    for fl in ref.fills:
+        want += [(fl.bubble, first, cnt, smp, 0) for _, first, cnt, smp in fl.full]
+        if fl.partial:
+            want.append((fl.bubble, fl.partial[1], 1, fl.partial[2], 1))
+    assert [(r["bubble"], r["first_layer"], r["n_layers"], r["samples"], r["partial"]) for r in fills] == want
+    assert abs(summ["filled_device_ms"] - ref.filled_device_ms) <= 1e-9 * max(ref.filled_device_ms, 1e-9)
+    assert abs(summ["leftover_ms"] - ref.leftover_ms) <= 1e-9 * max(ref.leftover_ms, 1e-9)
+    print(f"\n[bubbles] {len(got_b)} bubbles, {summ['bubble_device_ms']:.3f} idle device-ms, {summ['filled_device_ms']:.3f} filled, "
+          f"leftover {summ['leftover_ms']:.3f} ms; {len(fills)} placements", flush=True)
+    assert summ["filled_device_ms"] > 0.0
+
+
 # ------------------------------------------------------------------ text encoder, partial batches
 SMALL_ENC = si.EncoderConfig("small_enc_bf16", "bf16", 2, 128, 2, 64, 77, 1000, 256, 6)
 SMALL_ENC_F32 = si.EncoderConfig("small_enc_f32", "f32", 2, 32, 2, 16, 9, 100, 64, 5)
