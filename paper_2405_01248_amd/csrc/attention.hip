@@ -188,6 +188,12 @@ __global__ void __launch_bounds__(256, (QT == 1 && DHP == 64) ? 3 : 2) attn_fwd_
         for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[j][t][r]);
       mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
       mx = fmaxf(m[j], mx * p.scale_log2);                 // m[j] is kept in the scaled (log2) domain
+      // The reference point only has to bound the exponents, not equal the maximum: it is moved (and the
+      // accumulators rescaled) when some query of the wave has outgrown it by 2^8; until then the
+      // probabilities of this tile are taken relative to the old one (at most 256, exact in the final
+      // O = acc / sum and LSE = ref + log sum).  Wave-uniform, so the rescale is skipped for most tiles.
+      const bool bump = __any(mx > m[j] + 8.0f);
+      mx = bump ? mx : m[j];
       const float mref = (mx == -INFINITY) ? 0.f : mx;
       float rs = 0.f;
 #pragma unroll
@@ -199,7 +205,7 @@ __global__ void __launch_bounds__(256, (QT == 1 && DHP == 64) ? 3 : 2) attn_fwd_
           rs += e;
         }
       rs += __shfl_xor(rs, 32, 64);
-      if (__any(mx != m[j])) {                              // wave-uniform: skip the rescale once the maxima settle
+      if (bump) {
         const float alpha = __builtin_amdgcn_exp2f(m[j] - mref);
         lsum[j] *= alpha;
 #pragma unroll
