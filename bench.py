@@ -134,6 +134,7 @@ def kernel_roofline(workload, names, si, DeviceStage, DeviceEncoder, passes=3):
     for _ in range(passes):
         run()
     recs = binding.ktime_end()
+    event_overhead_us = 1e3 * binding.ktime_event_overhead_ms()
     agg = {}
     for r in recs:
         a = agg.setdefault(r["kind"], {"launches": 0, "ms": 0.0, "flops": 0.0, "bytes": 0.0})
@@ -157,7 +158,10 @@ def kernel_roofline(workload, names, si, DeviceStage, DeviceEncoder, passes=3):
         ach = a["bytes"] / (a["ms"] * 1e-3) / 1e9
         roof = {"bound": "hbm", "achieved": ach, "peak": HBM_PEAK / 1e9, "unit": "GB/s", "frac": ach / (HBM_PEAK / 1e9)}
     roof.update(traffic=PMC_TRAFFIC_BYTES.get((workload, dom)), kernel=KERNEL_NAMES.get(dom, dom),
-                note="durations from a pass with the backward's side stream disabled (kernels run one at a time)",
+                note="durations from a pass with the backward's side stream disabled (kernels run one at a time); "
+                     "HIP events around every launch, dispatch gap included (rocprofv3's kernel-only averages are in "
+                     "profiles/kernels_cfg2_serial.md; an empty event pair reads event_pair_overhead_us)",
+                event_pair_overhead_us=event_overhead_us,
                 avg_launch_us=1e3 * a["ms"] / a["launches"], launches_per_step=a["launches"] / passes,
                 algorithmic_per_launch=(a["flops"] if dom in MFMA_KINDS else a["bytes"]) / a["launches"])
     del obj

@@ -288,8 +288,12 @@ int dp_op_attention_bwd(int dtype, int B, int H, int Nq, int Nk, int d_head, flo
  * forward, 4 attention dQ, 5 attention dK/dV, 6 LayerNorm forward, 7 LayerNorm backward,
  * 8 GeGLU forward, 9 GeGLU backward, 10 partial-sum reductions, 11 other, 12 fp32 GEMM,
  * 13 fp32 attention.  dp_ktime_begin allocates host-side events (max_records pairs);
- * dp_ktime_end synchronises the device, writes up to max records and frees them.  Not
- * thread-safe; the recording adds launch overhead, so use it in a pass of its own. */
+ * dp_ktime_end synchronises the device, writes up to max records and frees them.  `ms` is the
+ * time between a record's two events, which includes the dispatch gap around the kernel (an upper
+ * bound of the kernel's duration: a few microseconds above what a kernel trace shows).  For scale,
+ * dp_ktime_end also records up to 33 empty event pairs on the same stream when the pool has spare
+ * events; dp_ktime_event_overhead_ms returns their median reading (0 if none was taken).
+ * Not thread-safe; the recording adds launch overhead, so use it in a pass of its own. */
 typedef struct {
   int kind, m, n, k;
   float ms;
@@ -297,6 +301,7 @@ typedef struct {
 } dp_kernel_time;
 int dp_ktime_begin(int max_records);
 int dp_ktime_end(dp_kernel_time* out, int max, int* n);
+float dp_ktime_event_overhead_ms(void);
 
 /* Thread-local description of the last error; never NULL. */
 const char* dp_last_error(void);

@@ -77,7 +77,7 @@ KERNEL_KINDS = {0: "gemm_nt", 1: "gemm_nn", 2: "gemm_tn", 3: "attn_fwd", 4: "att
 EXPORTS = ["dp_stage_create", "dp_stage_destroy", "dp_stage_set_overlap", "dp_stage_set_fusion", "dp_stage_param_count", "dp_stage_param_shape", "dp_stage_workspace_bytes",
            "stage_fwd", "stage_bwd", "dp_encoder_create", "dp_encoder_destroy", "dp_encoder_param_count",
            "dp_encoder_param_shape", "dp_encoder_workspace_bytes", "encoder_fwd_partial", "dp_stage_profile",
-           "dp_encoder_profile", "dp_ktime_begin", "dp_ktime_end", "dp_last_error", "dp_op_gemm", "dp_op_gemm_workspace_bytes",
+           "dp_encoder_profile", "dp_ktime_begin", "dp_ktime_end", "dp_ktime_event_overhead_ms", "dp_last_error", "dp_op_gemm", "dp_op_gemm_workspace_bytes",
            "dp_op_attention_fwd", "dp_op_attention_bwd", "dp_partition_solve", "dp_bubbles_1f1b", "dp_bubbles_fill"]
 
 
@@ -124,6 +124,7 @@ def load_library():
     lib.dp_bubbles_1f1b.argtypes = [i, dptr, dptr, C.POINTER(i), i, dptr, dptr, dptr, C.c_double, C.POINTER(Bubble), i, C.POINTER(i), dptr]
     lib.dp_bubbles_fill.argtypes = [C.POINTER(Bubble), i, C.POINTER(LayerCost), i, C.POINTER(i), i, i, i, C.POINTER(FillRow), i, C.POINTER(FillSummary)]
     lib.dp_ktime_begin.argtypes = [i]
+    lib.dp_ktime_event_overhead_ms.restype = C.c_float
     lib.dp_ktime_end.argtypes = [C.POINTER(KernelTime), i, C.POINTER(i)]
     _LIB = lib
     return lib
@@ -271,6 +272,11 @@ def ktime_end(max_records: int = 65536):
     _check(load_library().dp_ktime_end(rows, max_records, C.byref(n)))
     return [{"kind": KERNEL_KINDS.get(rows[j].kind, str(rows[j].kind)), "m": rows[j].m, "n": rows[j].n, "k": rows[j].k,
              "ms": rows[j].ms, "flops": rows[j].flops, "bytes": rows[j].bytes} for j in range(n.value)]
+
+
+def ktime_event_overhead_ms() -> float:
+    """What an empty pair of events read in the last ktime_end (for scale; the records are not corrected by it)."""
+    return float(load_library().dp_ktime_event_overhead_ms())
 
 
 def partition_solve(rows, micro_batch, n_micro_batches, n_devices, p2p_gbps, p2p_latency_ms, ar_gbps, ar_latency_ms,
