@@ -104,6 +104,39 @@ def test_deterministic_and_accumulate_and_selfcond_isolation():
     assert np.array_equal(r3["dcond"], r1["dcond"])   # d_cond is overwritten, not accumulated
 
 
+@pytest.mark.parametrize("cfg", [SMALL_UNET_FUSE, SMALL_DIT], ids=lambda c: c.name)
+def test_step_can_be_captured_in_a_hip_graph_and_replayed(cfg):
+    """The compute entry points allocate nothing, never synchronise and clear memory with kernels only, and the
+    side stream forks from and joins the caller's stream through events: a whole step (extra no-grad forward
+    included) records into one HIP graph.  Every replay, with eager steps and synchronisations in between, must
+    give the eager result bit for bit."""
+    import torch
+    ds, _ = _run(cfg)
+    want = ds.results()
+    s = torch.cuda.Stream()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(s):
+        ds.step()
+        torch.cuda.synchronize()
+        with torch.cuda.graph(g, stream=s):
+            ds.step()
+    torch.cuda.synchronize()
+    for rep in range(3):
+        for t in ds.dparams:
+            t.fill_(7.0)
+        ds.y.zero_(); ds.dx.zero_()
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        got = ds.results()
+        assert np.array_equal(got["y"], want["y"]) and np.array_equal(got["dx"], want["dx"]), rep
+        for k in want["grads"]:
+            assert np.array_equal(got["grads"][k], want["grads"][k]), (rep, k)
+        ds.step()                              # eager work between replays
+        torch.cuda.synchronize()
+    del g
+
+
 def test_geglu_epilogue_fusion_matches_separate_kernels():
     """The GeGLU fused into the GEMM epilogues computes what the separate elementwise kernels compute:
     the forward bit for bit, the backward up to the bf16 rounding of dg that the fused path skips."""
