@@ -57,12 +57,13 @@ def _run(cfg, seed=0, **kw):
 SMALL_UNET = si.StageConfig("small_unet_bf16", si.UNET, "bf16", 2, 2, 200, 192, 3, 64, 77, 64, 264)
 SMALL_UNET_FUSE = si.StageConfig("small_unet_bf16_inner288", si.UNET, "bf16", 2, 2, 200, 192, 3, 64, 77, 64, 288)   # inner % 32 == 0: fused GeGLU forward
 SMALL_UNET_DH32 = si.StageConfig("small_unet_bf16_dh32", si.UNET, "bf16", 1, 1, 130, 64, 2, 32, 5, 24, 40)
+SMALL_UNET_SC = SMALL_UNET.replace(name="small_unet_bf16_selfcond", self_cond=True)     # Sec. 4.3 on the U-Net-style stage
 SMALL_DIT = si.StageConfig("small_dit_bf16", si.DIT, "bf16", 2, 3, 72, 144, 2, 72, 0, 0, 296, 1e-6, 1, self_cond=True)
 SMALL_DIT_ERF = si.StageConfig("small_dit_bf16_erf", si.DIT, "bf16", 1, 2, 257, 128, 2, 64, 0, 0, 128, 1e-6, 0)
 SMALL_DIT_F32 = si.StageConfig("small_dit_f32", si.DIT, "f32", 2, 2, 40, 48, 2, 24, 0, 0, 96, 1e-6, 1, self_cond=True)
 
 
-@pytest.mark.parametrize("cfg", [si.CONFIG1, SMALL_UNET, SMALL_UNET_FUSE, SMALL_UNET_DH32, SMALL_DIT, SMALL_DIT_ERF, SMALL_DIT_F32],
+@pytest.mark.parametrize("cfg", [si.CONFIG1, SMALL_UNET, SMALL_UNET_SC, SMALL_UNET_FUSE, SMALL_UNET_DH32, SMALL_DIT, SMALL_DIT_ERF, SMALL_DIT_F32],
                          ids=lambda c: c.name)
 def test_stage_matches_oracle_small(cfg):
     ds, inp = _run(cfg, randomize_ln=(cfg.name != si.CONFIG1.name))
