@@ -48,6 +48,12 @@ struct GemmArgs {
   //     [dg * gelu(gate) | dg * value * gelu'(gate)] with value / gate read from geglu_u [M, 2 * geglu_inner].
   int geglu, geglu_inner;
   const void* geglu_u; int ld_geglu;
+  // LayerNorm of the result rows folded into the split-K reduction pass (bf16, fp32 residual stream updated
+  // in place: out == residual, out_fused_f32, dense rows, bias optional, nothing else in the epilogue).  Only
+  // when the GEMM happens to be split along K: *ln_applied (must be given with ln_out) is then set to 1 and
+  // ln_out [M, N] holds LN(out; ln_gamma, ln_beta, ln_eps) in the storage dtype; otherwise it is set to 0 and
+  // the caller runs the LayerNorm itself.
+  const void* ln_gamma; const void* ln_beta; void* ln_out; float ln_eps; int* ln_applied;
 };
 int launch_gemm(const GemmArgs& a, hipStream_t s);
 bool gemm_geglu_fwd_supported(const GemmArgs& a);
@@ -93,6 +99,11 @@ struct LnArgs {
   float* mean; float* rstd;
 };
 int launch_ln_fwd(const LnArgs& a, hipStream_t s);
+// x[r, :] += sum_z partial[z][r, :] (+ bias), then y[r, :] = LN(x[r, :]; gamma, beta, eps) in bf16: the split-K
+// reduction of a projection onto the fp32 residual stream and the LayerNorm that follows it, one wave per row.
+// partial: [splits][rows][d] fp32; d a multiple of 8, at most 2048.
+int launch_reduce_residual_ln(const float* partial, int splits, int rows, int d, const void* bias, float* x, void* y,
+                              const void* gamma, const void* beta, float eps, hipStream_t s);
 
 // dx = [dres +] LN backward of dy.  x (the LayerNorm input) and dres are fp32 residual-stream
 // tensors; the result is written to dx32 (fp32) and/or dx (storage dtype).  Affine: dgamma/dbeta (fp32 [d], accumulate flag).

@@ -108,6 +108,76 @@ static int ln_fwd_t(const LnArgs& a, hipStream_t s) {
   return hipGetLastError() == hipSuccess ? DP_OK : set_error(DP_EHIP, "ln_fwd launch failed");
 }
 
+// Split-K reduction onto the fp32 residual stream fused with the LayerNorm that follows (bf16 storage).
+__global__ void __launch_bounds__(256) reduce_residual_ln_kernel(int rows, int d, float eps, const float* __restrict__ partial, int splits,
+                                                                 const bf16* __restrict__ bias, float* __restrict__ x, bf16* __restrict__ y,
+                                                                 const bf16* __restrict__ gamma, const bf16* __restrict__ beta) {
+  constexpr int V = 8;
+  const int lane = threadIdx.x & 63, row = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= rows) return;
+  const size_t plane = (size_t)rows * d;
+  float v[LN_MAXCH][V];
+  float s = 0.f;
+#pragma unroll
+  for (int c = 0; c < LN_MAXCH; ++c) {
+    const int col = (c * 64 + lane) * V;
+    if (col < d) {
+      float* xr = x + (size_t)row * d + col;
+      load_f32<V>(xr, v[c]);
+      float acc[V];
+      load_f32<V>(partial + (size_t)row * d + col, acc);
+      for (int z = 1; z < splits; ++z) {                  // ascending split order: fixed summation order
+        float t[V];
+        load_f32<V>(partial + z * plane + (size_t)row * d + col, t);
+#pragma unroll
+        for (int i = 0; i < V; ++i) acc[i] += t[i];
+      }
+      if (bias) {
+        float b[V];
+        load_vec<bf16>(bias + col, b);
+#pragma unroll
+        for (int i = 0; i < V; ++i) acc[i] += b[i];
+      }
+#pragma unroll
+      for (int i = 0; i < V; ++i) { v[c][i] += acc[i]; s += v[c][i]; }
+      store_f32<V>(xr, v[c]);
+    }
+  }
+  const float mu = wave_sum(s) / d;
+  float q = 0.f;
+#pragma unroll
+  for (int c = 0; c < LN_MAXCH; ++c) {
+    const int col = (c * 64 + lane) * V;
+    if (col < d) {
+#pragma unroll
+      for (int i = 0; i < V; ++i) { v[c][i] -= mu; q += v[c][i] * v[c][i]; }
+    }
+  }
+  const float rs = rsqrtf(wave_sum(q) / d + eps);
+#pragma unroll
+  for (int c = 0; c < LN_MAXCH; ++c) {
+    const int col = (c * 64 + lane) * V;
+    if (col < d) {
+      float o[V], a[V], b[V];
+      load_vec<bf16>(gamma + col, a);
+      load_vec<bf16>(beta + col, b);
+#pragma unroll
+      for (int i = 0; i < V; ++i) o[i] = v[c][i] * rs * a[i] + b[i];
+      store_vec<bf16>(y + (size_t)row * d + col, o);
+    }
+  }
+}
+
+int launch_reduce_residual_ln(const float* partial, int splits, int rows, int d, const void* bias, float* x, void* y,
+                              const void* gamma, const void* beta, float eps, hipStream_t s) {
+  if (!partial || splits < 1 || rows <= 0 || !x || !y || !gamma || !beta) return set_error(DP_EINVAL, "reduce_residual_ln: bad arguments");
+  if (d <= 0 || d % 8 || d > 64 * LN_MAXCH * 8) return set_error(DP_EUNSUPPORTED, "reduce_residual_ln: d must be a multiple of 8, at most 2048");
+  KScope ks(KK_REDUCE, 0.0, (double)rows * d * (4.0 * splits + 8.0 + 2.0), s, rows, d, splits);
+  hipLaunchKernelGGL(reduce_residual_ln_kernel, dim3((rows + 3) / 4), dim3(256), 0, s, rows, d, eps, partial, splits, (const bf16*)bias, x,
+                     (bf16*)y, (const bf16*)gamma, (const bf16*)beta);
+  return hipGetLastError() == hipSuccess ? DP_OK : set_error(DP_EHIP, "reduce_residual_ln launch failed");
+}
+
 static int check_ln_dim(int dtype, int d) {
   const int V = dtype == BF16 ? 8 : 4;
   if (d <= 0 || d % V) return set_error(DP_EUNSUPPORTED, "layernorm: d must be a positive multiple of 8 (bf16) / 4 (fp32)");

@@ -1050,6 +1050,13 @@ static int launch_dtl_cfg(const GemmArgs& a, hipStream_t s) {
     hipLaunchKernelGGL(kern, grid, dim3(WGM * WGN * 64), smem, s, p);
   }
   if (hipGetLastError() != hipSuccess) return set_error(DP_EHIP, "gemm launch failed");
+  if (a.ln_applied) *a.ln_applied = 0;
+  if (splits > 1 && !a.out_f32 && a.ln_out && a.ln_applied && a.ln_gamma && a.ln_beta && a.residual && a.residual_f32 && a.out_fused_f32 &&
+      a.out == a.residual && a.ldo == a.N && a.ld_res == a.N && !a.act && !a.dact_pre && !a.gate && !a.pre_out && !a.geglu && a.N <= 2048) {
+    // the reduction pass also normalises the rows it completes (one launch less per projection onto the residual stream)
+    *a.ln_applied = 1;
+    return launch_reduce_residual_ln(a.splitk_ws, splits, a.M, a.N, a.bias, (float*)a.out, a.ln_out, a.ln_gamma, a.ln_beta, a.ln_eps, s);
+  }
   if (splits > 1 && !a.out_f32) {
     KScope ks(KK_REDUCE, 0.0, 4.0 * splits * a.M * a.N + 2.0 * a.M * a.N, s, a.M, a.N, splits);
     const size_t groups = (size_t)a.M * (a.N / 8);
@@ -1111,6 +1118,7 @@ bool gemm_geglu_fwd_supported(const GemmArgs& a) {
 }
 
 int launch_gemm(const GemmArgs& a, hipStream_t s) {
+  if (a.ln_applied) *a.ln_applied = 0;
   if (a.M <= 0 || a.N <= 0 || a.K <= 0) return set_error(DP_EINVAL, "gemm: non-positive size");
   if (!a.A || !a.B || (!a.out && !a.out_f32)) return set_error(DP_EINVAL, "gemm: null operand");
   if (a.out_f32 && a.ldo32 < a.N) return set_error(DP_EINVAL, "gemm: ldo32 < N");

@@ -745,14 +745,19 @@ static void plan_encoder(const dp_encoder& e, void* base, int samples, EncBuf& b
   b.bytes = p.off;
 }
 
-// One transformer layer on the fp32 residual stream `x` [R, d] (updated in place).
-static int encoder_block(const dp_encoder& e, const void* const* P, float* x, int n, EncBuf& w, hipStream_t st) {
+// One transformer layer on the fp32 residual stream `x` [R, d] (updated in place).  h_ready: w.h already
+// holds LN1(x) (written by the previous layer's last reduction pass).  When next_gamma is given, the LayerNorm
+// that follows this layer (the next layer's first, or the final one) is handed to the last projection's
+// split-K reduction pass with output next_out; *next_done tells whether that pass existed and did it.
+static int encoder_block(const dp_encoder& e, const void* const* P, float* x, int n, EncBuf& w, hipStream_t st, bool h_ready,
+                         const void* next_gamma, const void* next_beta, void* next_out, bool* next_done) {
   const int dt = e.d.dtype, d = e.d.d_model, seq = e.d.seq, ff = e.d.ff_inner, R = n * seq;
   const size_t es = e.es;
+  const bool fuse_ln = dt == DP_BF16;
   LnArgs ln; memset(&ln, 0, sizeof(ln));
   ln.dtype = dt; ln.rows = R; ln.d = d; ln.eps = e.d.ln_eps; ln.x_f32 = 1;
   ln.x = x; ln.y = w.h; ln.gamma = P[E_LN1_G]; ln.beta = P[E_LN1_B];
-  DP_TRY(launch_ln_fwd(ln, st));
+  if (!h_ready) DP_TRY(launch_ln_fwd(ln, st));
   GemmArgs g = gemm_fwd(dt, w.h, R, d, P[E_WQKV], 3 * d, P[E_BQKV], w.qkv);
   g.splitk_ws = w.splitk; g.splitk_ws_bytes = w.splitk_bytes;
   DP_TRY(launch_gemm(g, st));
@@ -761,20 +766,27 @@ static int encoder_block(const dp_encoder& e, const void* const* P, float* x, in
   a.scale = 1.0f / sqrtf((float)e.d.d_head);
   a.q = w.qkv; a.k = at(w.qkv, d, es); a.v = at(w.qkv, 2 * d, es); a.ldq = a.ldk = a.ldv = 3 * d; a.o = w.a; a.ldo = d;
   DP_TRY(launch_attn_fwd(a, st));
+  int ln_applied = 0;
   g = gemm_fwd(dt, w.a, R, d, P[E_WO], d, P[E_BO], x);
   g.splitk_ws = w.splitk; g.splitk_ws_bytes = w.splitk_bytes;
   g.residual = x; g.ld_res = d; g.residual_f32 = 1; g.out_fused_f32 = 1;
+  if (fuse_ln) { g.ln_gamma = P[E_LN2_G]; g.ln_beta = P[E_LN2_B]; g.ln_out = w.h; g.ln_eps = e.d.ln_eps; g.ln_applied = &ln_applied; }
   DP_TRY(launch_gemm(g, st));
-  ln.x = x; ln.y = w.h; ln.gamma = P[E_LN2_G]; ln.beta = P[E_LN2_B];
-  DP_TRY(launch_ln_fwd(ln, st));
+  if (!ln_applied) {
+    ln.x = x; ln.y = w.h; ln.gamma = P[E_LN2_G]; ln.beta = P[E_LN2_B];
+    DP_TRY(launch_ln_fwd(ln, st));
+  }
   g = gemm_fwd(dt, w.h, R, d, P[E_FC1_W], ff, P[E_FC1_B], w.f);
   g.splitk_ws = w.splitk; g.splitk_ws_bytes = w.splitk_bytes;
   g.act = 3;
   DP_TRY(launch_gemm(g, st));
+  ln_applied = 0;
   g = gemm_fwd(dt, w.f, R, ff, P[E_FC2_W], d, P[E_FC2_B], x);
   g.splitk_ws = w.splitk; g.splitk_ws_bytes = w.splitk_bytes;
   g.residual = x; g.ld_res = d; g.residual_f32 = 1; g.out_fused_f32 = 1;
+  if (fuse_ln && next_gamma) { g.ln_gamma = next_gamma; g.ln_beta = next_beta; g.ln_out = next_out; g.ln_eps = e.d.ln_eps; g.ln_applied = &ln_applied; }
   DP_TRY(launch_gemm(g, st));
+  if (next_done) *next_done = ln_applied != 0;
   return DP_OK;
 }
 
@@ -798,16 +810,28 @@ static int encoder_run(const dp_encoder& e, const void* const* params, const int
   const int tl_end = std::min(le, nl + 1);
   const bool blocks = l < tl_end;
   const bool final_ln = le == nl + 2;
+  bool final_done = false;
   if (blocks) {
     DP_TRY(mark(l));
     DP_TRY(launch_cast_to_f32(dt, x, w.res, (size_t)R * d, st));
+    // A layer's last reduction pass may also compute the LayerNorm that follows it (the next layer's first, or
+    // the final one straight into `hidden`); not while layers are being timed one by one.
+    bool h_ready = false;
     for (; l < tl_end; ++l) {
       if (l != (lb == 0 ? 1 : lb)) DP_TRY(mark(l));
-      DP_TRY(encoder_block(e, params + 2 + (size_t)(l - 1) * E_PER_LAYER, w.res, n, w, st));
+      const void* const* P = params + 2 + (size_t)(l - 1) * E_PER_LAYER;
+      const void *ng = nullptr, *nb = nullptr;
+      void* nout = nullptr;
+      if (!ev && l + 1 < tl_end) { ng = P[E_PER_LAYER + E_LN1_G]; nb = P[E_PER_LAYER + E_LN1_B]; nout = w.h; }
+      else if (!ev && l == nl && final_ln) { ng = params[2 + (size_t)nl * E_PER_LAYER]; nb = params[2 + (size_t)nl * E_PER_LAYER + 1]; nout = x; }
+      bool done = false;
+      DP_TRY(encoder_block(e, P, w.res, n, w, st, h_ready, ng, nb, nout, &done));
+      h_ready = done && l + 1 < tl_end;
+      final_done = done && l == nl && final_ln;
     }
     if (!final_ln) DP_TRY(launch_cast_from_f32(dt, w.res, x, (size_t)R * d, st));
   }
-  if (final_ln) {
+  if (final_ln && !final_done) {
     DP_TRY(mark(nl + 1));
     const void* const* P = params + 2 + (size_t)nl * E_PER_LAYER;
     LnArgs ln; memset(&ln, 0, sizeof(ln));
