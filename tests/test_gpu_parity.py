@@ -70,6 +70,18 @@ def test_stage_matches_oracle_small(cfg):
     _compare(cfg, ds.results(), _oracle_stage(cfg, inp))
 
 
+# degenerate sizes: a single token attending to a single context token; a batch of one; three tokens
+EDGE_UNET_1TOKEN = si.StageConfig("edge_unet_bf16_1token", si.UNET, "bf16", 1, 1, 1, 64, 1, 64, 1, 8, 32)
+EDGE_UNET_F32_1TOKEN = si.StageConfig("edge_unet_f32_1token", si.UNET, "f32", 1, 1, 1, 32, 2, 16, 1, 4, 16)
+EDGE_DIT_3TOKENS = si.StageConfig("edge_dit_bf16_3tokens", si.DIT, "bf16", 2, 1, 3, 72, 1, 72, 0, 0, 72, 1e-6, 1, self_cond=True)
+
+
+@pytest.mark.parametrize("cfg", [EDGE_UNET_1TOKEN, EDGE_UNET_F32_1TOKEN, EDGE_DIT_3TOKENS], ids=lambda c: c.name)
+def test_stage_degenerate_sizes(cfg):
+    ds, inp = _run(cfg, randomize_ln=True)
+    _compare(cfg, ds.results(), _oracle_stage(cfg, inp))
+
+
 @pytest.mark.parametrize("cfg", [SMALL_UNET, SMALL_DIT], ids=lambda c: c.name)
 def test_stage_sharp_softmax_stress(cfg):
     """Query/key projections scaled up so that softmax rows are far from uniform and the
