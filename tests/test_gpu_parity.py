@@ -338,6 +338,22 @@ def test_encoder_partial_batches_match_oracle_and_each_other(cfg):
     assert e_ref <= TOL[cfg.dtype], e_ref
 
 
+@pytest.mark.parametrize("cfg", [si.EncoderConfig("edge_enc_bf16_seq1", "bf16", 1, 64, 1, 64, 1, 50, 64, 1),
+                                 si.EncoderConfig("edge_enc_bf16_noncausal", "bf16", 2, 64, 2, 32, 5, 50, 72, 3, causal=0)], ids=lambda c: c.name)
+def test_encoder_degenerate_sizes(cfg):
+    """A one-token sequence in a batch of one; a non-causal encoder with an odd sequence length."""
+    import torch
+    from paper_2405_01248_amd.harness import DeviceEncoder, rel_err
+    inp = si.make_encoder_inputs(cfg, seed=3, randomize_ln=True)
+    ref = _oracle_encoder(cfg, inp)
+    de = DeviceEncoder(cfg, inp)
+    de.run_slices(cfg.global_batch)
+    torch.cuda.synchronize()
+    e = rel_err(de.output(), ref)
+    print(f"\n[{cfg.name}] rel err {e:.3e}", flush=True)
+    assert e <= TOL[cfg.dtype]
+
+
 def test_calls_interleave_without_interference():
     """Encoder partial-batch calls issued between a stage's forward and backward (what
     bubble filling does) change neither result."""
