@@ -163,7 +163,9 @@ def kernel_roofline(workload, names, si, DeviceStage, DeviceEncoder, passes=3):
                      "profiles/kernels_cfg2_serial.md; an empty event pair reads event_pair_overhead_us)",
                 event_pair_overhead_us=event_overhead_us,
                 avg_launch_us=1e3 * a["ms"] / a["launches"], launches_per_step=a["launches"] / passes,
-                algorithmic_per_launch=(a["flops"] if dom in MFMA_KINDS else a["bytes"]) / a["launches"])
+                algorithmic_per_launch=(a["flops"] if dom in MFMA_KINDS else a["bytes"]) / a["launches"],
+                # what `traffic` compares with: operands, result and every tensor the fused epilogue reads or writes, once
+                tensor_bytes_per_launch=a["bytes"] / a["launches"])
     del obj
     return roof, classes
 
