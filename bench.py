@@ -104,8 +104,8 @@ def cpu_baseline_stage(cfg):
 # scaled by kernels of known size in the same run (FETCH_SIZE x 2.0, WRITE_SIZE x 1.0); the counter runs and the
 # per-kernel table are in profiles/hbm_traffic_cfg2.md.  Average over the launches of the class in one step.
 PMC_TRAFFIC_BYTES = {
-    ("cfg2", "gemm_nt"): 94.6e6,    # 26 launches per step: forward projections and dx = dy W on transposed weight copies
-    ("cfg2", "gemm_tn"): 139.5e6,   # 14 launches per step: dW = dy^T x, split-K partial sums included
+    ("cfg2", "gemm_nt"): 81.8e6,    # 26 launches per step: forward projections and dx = dy W on transposed weight copies
+    ("cfg2", "gemm_tn"): 116.6e6,   # 14 launches per step: dW = dy^T x, split-K partial sums included
 }
 
 MFMA_KINDS = {"gemm_nt", "gemm_nn", "gemm_tn", "attn_fwd", "attn_bwd_dq", "attn_bwd_dkv"}
