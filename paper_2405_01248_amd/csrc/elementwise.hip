@@ -199,20 +199,25 @@ int launch_ln_fwd(const LnArgs& a, hipStream_t s) {
 constexpr int LNB_ROWS = 16;   // rows per workgroup (4 per wave)
 
 // grid = (chunks_per_batch, n_batches).  partial: [batch][chunk][2][d]
-template <typename T>
+// NCH = number of 64-lane vector chunks a row spans (d <= 64 * V * NCH).  A wave owns every fourth row of the
+// workgroup's 16.  All loads of a row (dy, x, the residual gradient) are issued before the first is used; rows
+// of a single chunk (d <= 512 in bf16) are taken two at a time, which doubles the bytes in flight per wave --
+// the kernel moves ~16 bytes per element and is bound by how much of that is outstanding, not by arithmetic.
+template <typename T, int NCH>
 __global__ void __launch_bounds__(256) ln_bwd_kernel(int d, int rows_per_batch, const T* __restrict__ dy, const float* __restrict__ x,
                                                      const float* __restrict__ mean, const float* __restrict__ rstd,
                                                      const T* __restrict__ gamma, const T* __restrict__ scale, int mod_ld,
                                                      const float* __restrict__ dres, const T* __restrict__ dres_t,
                                                      T* __restrict__ dx, float* __restrict__ dx32, float* __restrict__ partial) {
   constexpr int V = Vec<T>::N;
+  using VT = typename Vec<T>::type;
   extern __shared__ float cols[];   // [4 waves][2][d]
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int b = blockIdx.y;
   const int r_begin = blockIdx.x * LNB_ROWS, r_end = min(rows_per_batch, r_begin + LNB_ROWS);
-  float gsum[LN_MAXCH][V], bsum[LN_MAXCH][V], gain[LN_MAXCH][V];
+  float gsum[NCH][V], bsum[NCH][V], gain[NCH][V];
 #pragma unroll
-  for (int c = 0; c < LN_MAXCH; ++c) {
+  for (int c = 0; c < NCH; ++c) {
     const int col = (c * 64 + lane) * V;
 #pragma unroll
     for (int i = 0; i < V; ++i) { gsum[c][i] = 0.f; bsum[c][i] = 0.f; gain[c][i] = 1.f; }
@@ -226,57 +231,90 @@ __global__ void __launch_bounds__(256) ln_bwd_kernel(int d, int rows_per_batch, 
       }
     }
   }
-  for (int r = r_begin + wave; r < r_end; r += 4) {
-    const size_t row = (size_t)b * rows_per_batch + r;
-    const float mu = mean[row], rs = rstd[row];
-    float g[LN_MAXCH][V], xh[LN_MAXCH][V];
-    float s1 = 0.f, s2 = 0.f;
+  struct Row {
+    size_t row; float mu, rs, s1, s2;
+    VT dyr[NCH], drt[NCH];            // raw loads
+    float xr[NCH][V], drf[NCH][V];
+    float g[NCH][V], xh[NCH][V];
+  };
+  auto issue = [&](Row& R, int r) {
+    R.row = (size_t)b * rows_per_batch + r;
+    R.mu = mean[R.row]; R.rs = rstd[R.row];
 #pragma unroll
-    for (int c = 0; c < LN_MAXCH; ++c) {
+    for (int c = 0; c < NCH; ++c) {
       const int col = (c * 64 + lane) * V;
       if (col < d) {
-        float dyv[V];
-        load_vec<T>(dy + row * d + col, dyv);
-        load_f32<V>(x + row * d + col, xh[c]);
+        R.dyr[c] = *reinterpret_cast<const VT*>(dy + R.row * d + col);
+        load_f32<V>(x + R.row * d + col, R.xr[c]);
+        if (dres) load_f32<V>(dres + R.row * d + col, R.drf[c]);
+        else if (dres_t) R.drt[c] = *reinterpret_cast<const VT*>(dres_t + R.row * d + col);
+      }
+    }
+  };
+  auto reduce_in = [&](Row& R) {
+    R.s1 = 0.f; R.s2 = 0.f;
+#pragma unroll
+    for (int c = 0; c < NCH; ++c) {
+      const int col = (c * 64 + lane) * V;
+      if (col < d) {
 #pragma unroll
         for (int i = 0; i < V; ++i) {
-          xh[c][i] = (xh[c][i] - mu) * rs;
-          gsum[c][i] += dyv[i] * xh[c][i];
-          bsum[c][i] += dyv[i];
-          g[c][i] = dyv[i] * gain[c][i];
-          s1 += g[c][i];
-          s2 += g[c][i] * xh[c][i];
+          const float dyv = to_f<T>(R.dyr[c][i]);
+          R.xh[c][i] = (R.xr[c][i] - R.mu) * R.rs;
+          gsum[c][i] += dyv * R.xh[c][i];
+          bsum[c][i] += dyv;
+          R.g[c][i] = dyv * gain[c][i];
+          R.s1 += R.g[c][i];
+          R.s2 += R.g[c][i] * R.xh[c][i];
         }
       }
     }
-    const float m1 = wave_sum(s1) / d, m2 = wave_sum(s2) / d;
+  };
+  auto finish = [&](Row& R) {
+    const float m1 = wave_sum(R.s1) / d, m2 = wave_sum(R.s2) / d;
 #pragma unroll
-    for (int c = 0; c < LN_MAXCH; ++c) {
+    for (int c = 0; c < NCH; ++c) {
       const int col = (c * 64 + lane) * V;
       if (col < d) {
         float o[V];
 #pragma unroll
-        for (int i = 0; i < V; ++i) o[i] = rs * (g[c][i] - m1 - xh[c][i] * m2);
+        for (int i = 0; i < V; ++i) o[i] = R.rs * (R.g[c][i] - m1 - R.xh[c][i] * m2);
         if (dres) {
-          float rr[V];
-          load_f32<V>(dres + row * d + col, rr);
 #pragma unroll
-          for (int i = 0; i < V; ++i) o[i] += rr[i];
+          for (int i = 0; i < V; ++i) o[i] += R.drf[c][i];
         } else if (dres_t) {
-          float rr[V];
-          load_vec<T>(dres_t + row * d + col, rr);
 #pragma unroll
-          for (int i = 0; i < V; ++i) o[i] += rr[i];
+          for (int i = 0; i < V; ++i) o[i] += to_f<T>(R.drt[c][i]);
         }
-        if (dx32) store_f32<V>(dx32 + row * d + col, o);
-        if (dx) store_vec<T>(dx + row * d + col, o);
+        if (dx32) store_f32<V>(dx32 + R.row * d + col, o);
+        if (dx) store_vec<T>(dx + R.row * d + col, o);
       }
+    }
+  };
+  if (NCH == 1) {
+    for (int r = r_begin + wave; r < r_end; r += 8) {
+      const bool two = r + 4 < r_end;                        // wave-uniform
+      Row A, B;
+      issue(A, r);
+      if (two) issue(B, r + 4);
+      reduce_in(A);
+      if (two) reduce_in(B);
+      finish(A);
+      if (two) finish(B);
+    }
+  } else {
+    // wider rows: a second row's registers would cost occupancy (measured slower at d = 640 and 1152)
+    for (int r = r_begin + wave; r < r_end; r += 4) {
+      Row A;
+      issue(A, r);
+      reduce_in(A);
+      finish(A);
     }
   }
   if (!partial) return;
   // fixed-order reduction of the four waves' column sums
 #pragma unroll
-  for (int c = 0; c < LN_MAXCH; ++c) {
+  for (int c = 0; c < NCH; ++c) {
     const int col = (c * 64 + lane) * V;
     if (col < d) {
 #pragma unroll
@@ -323,11 +361,21 @@ size_t ln_bwd_partial_bytes(int rows, int d, int rows_per_batch) {
   return (size_t)nb * nchunk * 2 * d * sizeof(float);
 }
 
-template <typename T>
-static int ln_bwd_t(const LnBwdArgs& a, int rpb, int nb, int nchunk, float* partial, hipStream_t s) {
-  hipLaunchKernelGGL(ln_bwd_kernel<T>, dim3(nchunk, nb), dim3(256), (size_t)8 * a.d * sizeof(float), s, a.d, rpb, (const T*)a.dy,
+template <typename T, int NCH>
+static void ln_bwd_launch(const LnBwdArgs& a, int rpb, int nb, int nchunk, float* partial, hipStream_t s) {
+  hipLaunchKernelGGL((ln_bwd_kernel<T, NCH>), dim3(nchunk, nb), dim3(256), (size_t)8 * a.d * sizeof(float), s, a.d, rpb, (const T*)a.dy,
                      (const float*)a.x, a.mean, a.rstd, (const T*)a.gamma, (const T*)a.scale, a.mod_ld,
                      a.dres_storage ? nullptr : (const float*)a.dres, a.dres_storage ? (const T*)a.dres : nullptr, (T*)a.dx, a.dx32, partial);
+}
+template <typename T>
+static int ln_bwd_t(const LnBwdArgs& a, int rpb, int nb, int nchunk, float* partial, hipStream_t s) {
+  const int nch = (a.d + 64 * Vec<T>::N - 1) / (64 * Vec<T>::N);
+  switch (nch) {
+    case 1: ln_bwd_launch<T, 1>(a, rpb, nb, nchunk, partial, s); break;
+    case 2: ln_bwd_launch<T, 2>(a, rpb, nb, nchunk, partial, s); break;
+    case 3: ln_bwd_launch<T, 3>(a, rpb, nb, nchunk, partial, s); break;
+    default: ln_bwd_launch<T, LN_MAXCH>(a, rpb, nb, nchunk, partial, s); break;
+  }
   return hipGetLastError() == hipSuccess ? DP_OK : set_error(DP_EHIP, "ln_bwd launch failed");
 }
 
