@@ -39,6 +39,9 @@ struct GemmArgs {
   int residual_f32;          // residual is fp32 (the residual stream) although dtype is bf16
   int out_fused_f32;         // `out` receives the fused-epilogue result as fp32 instead of the storage dtype
   float* splitk_ws; size_t splitk_ws_bytes;
+  // with out_f32 and a_mc (a weight gradient dy^T x): also colsum_out[m] = (accumulate ? old : 0) + sum_k A[k, m], the
+  // bias gradient, from the tiles the kernel stages anyway.  Only where gemm_colsum_supported() says so.
+  float* colsum_out;
   int force_cfg;             // 0 = choose by shape; 1 + index forces a tile configuration (measurement only)
   // GeGLU fused into the epilogue (bf16 only; bias is the only other epilogue term allowed):
   //   geglu = 1 (forward): B [2 * geglu_inner, K] and bias are the [value | gate] projection, N = 2 * geglu_inner.
@@ -57,6 +60,7 @@ struct GemmArgs {
 };
 int launch_gemm(const GemmArgs& a, hipStream_t s);
 bool gemm_geglu_fwd_supported(const GemmArgs& a);
+bool gemm_colsum_supported(const GemmArgs& a);
 size_t gemm_splitk_ws_bytes(int M, int N, int K);   // upper bound for out_f32 GEMMs
 size_t gemm_epi_splitk_ws_bytes(int M, int N, int K);   // same for storage-dtype outputs (0: such a GEMM is never split)
 
@@ -138,6 +142,9 @@ size_t colsum_partial_bytes(int rows, int cols);
 
 // out[i] = (accumulate ? out[i] : 0) + sum_z partial[z * n + i]
 int launch_reduce_partials(const float* partial, int nz, size_t n, float* out, int accumulate, hipStream_t s);
+// the same for two tensors in one launch (the second may be absent: n_b = 0)
+int launch_reduce_partials2(const float* partial, int nz, size_t n, float* out, const float* partial_b, size_t n_b, float* out_b,
+                            int accumulate, hipStream_t s);
 
 // y = silu(x) elementwise (storage dtype), n elements
 int launch_silu(int dtype, const void* x, void* y, size_t n, hipStream_t s);

@@ -557,6 +557,30 @@ int launch_reduce_partials(const float* partial, int nz, size_t n, float* out, i
   return hipGetLastError() == hipSuccess ? DP_OK : set_error(DP_EHIP, "reduce_partials launch failed");
 }
 
+// Two tensors in one launch: out (n4 vectors of 4) and out_b (nb4 vectors), each summed over nz planes in plane order.
+__global__ void reduce_partials2_kernel(const float* __restrict__ partial, int nz, size_t n4, float* __restrict__ out,
+                                        const float* __restrict__ partial_b, size_t nb4, float* __restrict__ out_b, int accumulate) {
+  size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x;
+  const float* src = partial; float* dst = out; size_t plane = n4;
+  if (i >= n4) {
+    i -= n4;
+    if (i >= nb4) return;
+    src = partial_b; dst = out_b; plane = nb4;
+  }
+  f32x4 s = {0.f, 0.f, 0.f, 0.f};
+  for (int z = 0; z < nz; ++z) s += reinterpret_cast<const f32x4*>(src)[(size_t)z * plane + i];
+  f32x4* o = reinterpret_cast<f32x4*>(dst) + i;
+  *o = accumulate ? *o + s : s;
+}
+int launch_reduce_partials2(const float* partial, int nz, size_t n, float* out, const float* partial_b, size_t n_b, float* out_b,
+                            int accumulate, hipStream_t s) {
+  if (n % 4 || n_b % 4) return set_error(DP_EUNSUPPORTED, "reduce_partials: element counts must be multiples of 4");
+  if (n_b && (!partial_b || !out_b)) return set_error(DP_EINVAL, "reduce_partials: second tensor missing");
+  const size_t total = n / 4 + n_b / 4;
+  hipLaunchKernelGGL(reduce_partials2_kernel, dim3((total + 255) / 256), dim3(256), 0, s, partial, nz, n / 4, out, partial_b, n_b / 4, out_b, accumulate);
+  return hipGetLastError() == hipSuccess ? DP_OK : set_error(DP_EHIP, "reduce_partials launch failed");
+}
+
 // ------------------------------------------------------------------ SiLU and its backward
 template <typename T>
 __global__ void silu_kernel(const T* __restrict__ x, T* __restrict__ y, size_t n) {

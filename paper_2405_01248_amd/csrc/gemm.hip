@@ -221,6 +221,9 @@ struct GemmBf16Params {
   int k_tiles_per_split;
   int tiles_m, tiles_n;
   int group_m;                 // tile-rows per group of the workgroup-to-tile map (choose_group_m)
+  // Column sums of the A operand over the contraction (register-staged kernel, contraction-strided A only: the
+  // bias gradient next to a weight gradient).  colsum[blockIdx.z * colsum_stride + m]; colsum_acc: add to what is there.
+  float* colsum; int colsum_stride; int colsum_acc;
   uint32_t a_bytes, b_bytes;   // extent of each operand in bytes (direct-to-LDS kernels address it with 32-bit offsets)
   EpiParams<bf16> epi;
 };
@@ -295,6 +298,10 @@ gemm_bf16_kernel(const GemmBf16Params p) {
   // zeroed only when they are written to LDS, so nothing waits on the loads before the MFMAs
   bf16x8 ra[A_PER], rb[B_PER];
   unsigned oka = 0, okb = 0;
+  // bias gradient: every thread always stages the same 8 columns of A (NT is a multiple of BM / 8), so it keeps
+  // their running sums; only the workgroups of the first tile column do
+  const bool do_colsum = A_MC && p.colsum != nullptr && tile_n == 0;
+  float csum[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 #define DP_GEMM_LOAD_GLOBAL(kt_)                                                              \
   {                                                                                           \
     const int k0_ = (kt_) * BK;                                                               \
@@ -334,7 +341,9 @@ gemm_bf16_kernel(const GemmBf16Params p) {
     bf16* bs_ = Bs + (buf_) * S::B_ELEMS;                                                     \
     _Pragma("unroll") for (int i = 0; i < A_PER; ++i) {                                       \
       const int id = tid + i * NT;                                                            \
-      if (A_MC) { const int kk = id / (BM / 8), c = id % (BM / 8); *reinterpret_cast<bf16x8*>(as_ + kk * S::A_LD + mc_swizzle(c, kk) * 8) = ((oka >> i) & 1) ? ra[i] : zero8(); } \
+      if (A_MC) { const int kk = id / (BM / 8), c = id % (BM / 8); const bf16x8 v_ = ((oka >> i) & 1) ? ra[i] : zero8(); \
+                  *reinterpret_cast<bf16x8*>(as_ + kk * S::A_LD + mc_swizzle(c, kk) * 8) = v_;                \
+                  if (do_colsum) { _Pragma("unroll") for (int t_ = 0; t_ < 8; ++t_) csum[t_] += (float)v_[t_]; } } \
       else      { const int r = id / (BK / 8), c = id % (BK / 8);  *reinterpret_cast<bf16x8*>(as_ + r * S::A_LD + c * 8) = ((oka >> i) & 1) ? ra[i] : zero8(); }  \
     }                                                                                         \
     _Pragma("unroll") for (int i = 0; i < B_PER; ++i) {                                       \
@@ -392,6 +401,22 @@ gemm_bf16_kernel(const GemmBf16Params p) {
     __syncthreads();
   }
 
+  if (A_MC && do_colsum) {      // workgroup-uniform
+    // fixed order: a thread's rows in k order (above), then the NT / (BM / 8) row groups in ascending order
+    constexpr int GROUPS = NT / (BM / 8);
+    float* red = reinterpret_cast<float*>(smem_raw);
+    const int c = tid % (BM / 8), grp = tid / (BM / 8);
+#pragma unroll
+    for (int t = 0; t < 8; ++t) red[grp * BM + c * 8 + t] = csum[t];
+    __syncthreads();
+    if (tid < BM && m0 + tid < p.M) {
+      float sum = 0.f;
+      for (int g2 = 0; g2 < GROUPS; ++g2) sum += red[g2 * BM + tid];
+      float* o = p.colsum + (size_t)blockIdx.z * p.colsum_stride + m0 + tid;
+      *o = p.colsum_acc ? *o + sum : sum;
+    }
+    __syncthreads();
+  }
   float* Cw = reinterpret_cast<float*>(smem_raw) + wave * 32 * S::C_LD;
   wave_epilogue<TM, TN, WN, S::C_LD>(acc, Cw, p.epi, m0 + wm0, n0 + wn0, lane);
 }
@@ -996,7 +1021,7 @@ size_t gemm_splitk_ws_bytes(int M, int N, int K) {
   for (int c = 0; c < kNumCfgs; ++c) {
     const long tiles = (long)((M + kCfgs[c].bm - 1) / kCfgs[c].bm) * ((N + kCfgs[c].bn - 1) / kCfgs[c].bn);
     const int s = choose_splits(tiles, (K + kCfgs[c].bk - 1) / kCfgs[c].bk, 2 * kCUs);
-    if (s > 1) worst = std::max(worst, (size_t)s * M * N * sizeof(float));
+    if (s > 1) worst = std::max(worst, (size_t)s * ((size_t)M * N + M) * sizeof(float));   // + the column sums of A per split
   }
   return worst;
 }
@@ -1015,13 +1040,20 @@ static int launch_bf16_cfg(const GemmArgs& a, hipStream_t s) {
   if (a.out_f32) {
     splits = choose_splits((long)p.tiles_m * p.tiles_n, kt, S::BYTES <= 80 * 1024 ? 2 * kCUs : kCUs);
     if (splits > 1) {
-      const size_t need = (size_t)splits * a.M * a.N * sizeof(float);
+      const size_t need = (size_t)splits * ((size_t)a.M * a.N + (a.colsum_out ? a.M : 0)) * sizeof(float);
       if (!a.splitk_ws || a.splitk_ws_bytes < need) splits = 1;
     }
   }
   p.k_tiles_per_split = (kt + splits - 1) / splits;
   splits = (kt + p.k_tiles_per_split - 1) / p.k_tiles_per_split;
   if (splits > 1) p.epi.partial = a.splitk_ws;
+  float* colsum_ws = nullptr;
+  p.colsum = nullptr; p.colsum_stride = 0; p.colsum_acc = 0;
+  if (A_MC && a.colsum_out) {
+    if (!a.out_f32) return set_error(DP_EUNSUPPORTED, "gemm: column sums come with an fp32 output only");
+    if (splits > 1) { colsum_ws = a.splitk_ws + (size_t)splits * a.M * a.N; p.colsum = colsum_ws; p.colsum_stride = a.M; }
+    else { p.colsum = a.colsum_out; p.colsum_acc = a.accumulate; }
+  }
   dim3 grid(p.tiles_m * p.tiles_n, 1, splits);
   const size_t smem = S::BYTES;
   auto kern = gemm_bf16_kernel<BM, BN, BK, WGM, WGN, A_MC, B_MC>;
@@ -1040,7 +1072,8 @@ static int launch_bf16_cfg(const GemmArgs& a, hipStream_t s) {
   if (hipGetLastError() != hipSuccess) return set_error(DP_EHIP, "gemm launch failed");
   if (splits > 1) {
     KScope ks(KK_REDUCE, 0.0, 4.0 * (splits + 1.0) * a.M * a.N, s, a.M, a.N, splits);
-    return launch_reduce_partials(a.splitk_ws, splits, (size_t)a.M * a.N, a.out_f32, a.accumulate, s);
+    return launch_reduce_partials2(a.splitk_ws, splits, (size_t)a.M * a.N, a.out_f32, colsum_ws, colsum_ws ? (size_t)a.M : 0,
+                                   a.colsum_out, a.accumulate, s);
   }
   return DP_OK;
 }
@@ -1150,6 +1183,13 @@ static int launch_bf16_layout(const GemmArgs& a, hipStream_t s) {
   return launch_bf16_cfg<BM, BN, BK, WGM, WGN, true, false>(a, s);
 }
 
+// The bias gradient can ride in a weight-gradient GEMM when that GEMM runs on the register-staged kernel.
+bool gemm_colsum_supported(const GemmArgs& a) {
+  if (a.dtype != BF16 || !a.a_mc || !a.b_mc || !a.out_f32 || a.M % 8) return false;
+  const int cfg = (a.force_cfg > 0) ? a.force_cfg - 1 : choose_cfg(a.M, a.N, a.K, true, true, dtl_addressable(a));
+  return cfg >= 0 && cfg <= 5;
+}
+
 bool gemm_geglu_fwd_supported(const GemmArgs& a) {
   return a.dtype == BF16 && !a.a_mc && !a.b_mc && a.K % 32 == 0 && a.geglu_inner > 0 && a.geglu_inner % 32 == 0 &&
          a.N == 2 * a.geglu_inner && a.ldo >= a.geglu_inner && (!a.pre_out || a.ld_pre >= a.N) && dtl_addressable(a);
@@ -1161,6 +1201,7 @@ int launch_gemm(const GemmArgs& a, hipStream_t s) {
   if (!a.A || !a.B || (!a.out && !a.out_f32)) return set_error(DP_EINVAL, "gemm: null operand");
   if (a.out_f32 && a.ldo32 < a.N) return set_error(DP_EINVAL, "gemm: ldo32 < N");
   if (a.out_f32 && a.ldo32 != a.N) return set_error(DP_EUNSUPPORTED, "gemm: fp32 output must be dense");
+  if (a.colsum_out && !gemm_colsum_supported(a)) return set_error(DP_EUNSUPPORTED, "gemm: column sums are not available for this problem");
   if (a.dtype == BF16) {
     // 16-byte vector loads: every row start and the contiguous extent must be multiples of 8 elements
     const int a_inner = a.a_mc ? a.M : a.K, b_inner = a.b_mc ? a.N : a.K;

@@ -377,6 +377,13 @@ static int unet_block_bwd(const dp_stage& s, const void* const* P, const void* c
   auto db = [&](const void* gy, int cols, int rows, int pidx, hipStream_t q) {
     return launch_colsum(dt, gy, cols, rows, cols, gf(pidx), acc, b.partial_side, b.partial_bytes, q);
   };
+  // weight gradient and bias gradient of one projection: the column sums of dy ride in the dW GEMM where it can take them
+  auto dwb = [&](const void* gy, int M, int N, const void* x, int K, int pw, int pb, hipStream_t q) -> int {
+    GemmArgs g = gemm_dw(dt, gy, M, N, x, K, gf(pw), acc, b.partial_side, b.partial_bytes);
+    if (gemm_colsum_supported(g)) { g.colsum_out = gf(pb); return launch_gemm(g, q); }
+    DP_TRY(launch_gemm(g, q));
+    return db(gy, N, M, pb, q);
+  };
   // LayerNorm backward: dx on the main stream; the sum of the column partials into d gamma / d beta
   // (parameter gradients, nothing downstream waits for them) on the side stream, from a buffer of its own
   auto ln_bwd = [&](LnBwdArgs& lb, int k) -> int {
@@ -391,8 +398,7 @@ static int unet_block_bwd(const dp_stage& s, const void* const* P, const void* c
   // ---- feed-forward
   {
     hipStream_t q = sd.begin();
-    DP_TRY(dw(dy.h, T, d, u.g, inner, U_W2, q));
-    DP_TRY(db(dy.h, d, T, U_B2, q));
+    DP_TRY(dwb(dy.h, T, d, u.g, inner, U_W2, U_B2, q));
     rd.pair[c] = sd.end();
   }
   sd.wait(rd.du);
@@ -407,8 +413,7 @@ static int unet_block_bwd(const dp_stage& s, const void* const* P, const void* c
   }
   {
     hipStream_t q = sd.begin();
-    DP_TRY(dw(b.du, T, 2 * inner, u.h3, d, U_W1, q));
-    DP_TRY(db(b.du, 2 * inner, T, U_B1, q));
+    DP_TRY(dwb(b.du, T, 2 * inner, u.h3, d, U_W1, U_B1, q));
     rd.du = sd.end();
   }
   DP_TRY(launch_gemm(gemm_dx(dt, b.du, T, 2 * inner, P[U_W1], WT[U_W1], d, b.dh), st));
@@ -422,8 +427,7 @@ static int unet_block_bwd(const dp_stage& s, const void* const* P, const void* c
   // ---- cross-attention
   {
     hipStream_t q = sd.begin();
-    DP_TRY(dw(dx2.h, T, d, u.a2, d, U_WO2, q));
-    DP_TRY(db(dx2.h, d, T, U_BO2, q));
+    DP_TRY(dwb(dx2.h, T, d, u.a2, d, U_WO2, U_BO2, q));
     rd.pair[c ^ 1] = sd.end();
   }
   DP_TRY(launch_gemm(gemm_dx(dt, dx2.h, T, d, P[U_WO2], WT[U_WO2], d, b.da), st));
@@ -448,8 +452,7 @@ static int unet_block_bwd(const dp_stage& s, const void* const* P, const void* c
   // ---- self-attention
   {
     hipStream_t q = sd.begin();
-    DP_TRY(dw(dx1.h, T, d, u.a1, d, U_WO1, q));
-    DP_TRY(db(dx1.h, d, T, U_BO1, q));
+    DP_TRY(dwb(dx1.h, T, d, u.a1, d, U_WO1, U_BO1, q));
     rd.pair[c] = sd.end();
   }
   DP_TRY(launch_gemm(gemm_dx(dt, dx1.h, T, d, P[U_WO1], WT[U_WO1], d, b.da), st));
@@ -515,19 +518,22 @@ static int dit_block_bwd(const dp_stage& s, const void* const* P, const void* co
   const GradPair dx1 = b.r[c ^ 1], out = b.r[c];
   auto gf = [&](int i) { return (float*)G[i]; };
   auto set_dx = [&](LnBwdArgs& lb, GradPair t) { lb.dx32 = t.f; lb.dx = (es == 4) ? nullptr : t.h; };
-  auto dw = [&](const void* gy, int M, int Nn, const void* x, int K, int pidx, hipStream_t q) {
-    return launch_gemm(gemm_dw(dt, gy, M, Nn, x, K, gf(pidx), acc, b.partial_side, b.partial_bytes), q);
-  };
   auto db = [&](const void* gy, int cols, int rows, int pidx, hipStream_t q) {
     return launch_colsum(dt, gy, cols, rows, cols, gf(pidx), acc, b.partial_side, b.partial_bytes, q);
+  };
+  // weight gradient and bias gradient of one projection: the column sums of dy ride in the dW GEMM where it can take them
+  auto dwb = [&](const void* gy, int M, int N, const void* x, int K, int pw, int pb, hipStream_t q) -> int {
+    GemmArgs g = gemm_dw(dt, gy, M, N, x, K, gf(pw), acc, b.partial_side, b.partial_bytes);
+    if (gemm_colsum_supported(g)) { g.colsum_out = gf(pb); return launch_gemm(g, q); }
+    DP_TRY(launch_gemm(g, q));
+    return db(gy, N, M, pb, q);
   };
   // ---- MLP branch
   sd.wait(rd.dg);
   DP_TRY(launch_gate_bwd(dt, dy.f, u.f2, at(u.m, 5 * d, es), 6 * d, b.dg, b.dm + 5 * d, 6 * d, B, N, d, st));
   {
     hipStream_t q = sd.begin();
-    DP_TRY(dw(b.dg, T, d, u.f, ff, D_FC2_W, q));
-    DP_TRY(db(b.dg, d, T, D_FC2_B, q));
+    DP_TRY(dwb(b.dg, T, d, u.f, ff, D_FC2_W, D_FC2_B, q));
     rd.dg = sd.end();
   }
   GemmArgs g = gemm_dx(dt, b.dg, T, d, P[D_FC2_W], WT[D_FC2_W], ff, b.du);
@@ -536,8 +542,7 @@ static int dit_block_bwd(const dp_stage& s, const void* const* P, const void* co
   DP_TRY(launch_gemm(g, st));
   {
     hipStream_t q = sd.begin();
-    DP_TRY(dw(b.du, T, ff, u.h2, d, D_FC1_W, q));
-    DP_TRY(db(b.du, ff, T, D_FC1_B, q));
+    DP_TRY(dwb(b.du, T, ff, u.h2, d, D_FC1_W, D_FC1_B, q));
     rd.du = sd.end();
   }
   DP_TRY(launch_gemm(gemm_dx(dt, b.du, T, ff, P[D_FC1_W], WT[D_FC1_W], d, b.dh), st));
@@ -552,8 +557,7 @@ static int dit_block_bwd(const dp_stage& s, const void* const* P, const void* co
   DP_TRY(launch_gate_bwd(dt, dx1.f, u.o, at(u.m, 2 * d, es), 6 * d, b.dg2, b.dm + 2 * d, 6 * d, B, N, d, st));
   {
     hipStream_t q = sd.begin();
-    DP_TRY(dw(b.dg2, T, d, u.a, d, D_WO, q));
-    DP_TRY(db(b.dg2, d, T, D_BO, q));
+    DP_TRY(dwb(b.dg2, T, d, u.a, d, D_WO, D_BO, q));
     rd.dg2 = sd.end();
   }
   DP_TRY(launch_gemm(gemm_dx(dt, b.dg2, T, d, P[D_WO], WT[D_WO], d, b.da), st));
@@ -565,8 +569,7 @@ static int dit_block_bwd(const dp_stage& s, const void* const* P, const void* co
   DP_TRY(launch_attn_bwd(a, st));
   {
     hipStream_t q = sd.begin();
-    DP_TRY(dw(b.dqkv, T, 3 * d, u.h1, d, D_WQKV, q));
-    DP_TRY(db(b.dqkv, 3 * d, T, D_BQKV, q));
+    DP_TRY(dwb(b.dqkv, T, 3 * d, u.h1, d, D_WQKV, D_BQKV, q));
     rd.dqkv = sd.end();
   }
   DP_TRY(launch_gemm(gemm_dx(dt, b.dqkv, T, 3 * d, P[D_WQKV], WT[D_WQKV], d, b.dh), st));
@@ -579,8 +582,7 @@ static int dit_block_bwd(const dp_stage& s, const void* const* P, const void* co
   DP_TRY(launch_cast_from_f32(dt, b.dm, b.dm_t, (size_t)B * 6 * d, st));
   {
     hipStream_t q = sd.begin();
-    DP_TRY(dw(b.dm_t, B, 6 * d, sc_in, d, D_ADA_W, q));
-    DP_TRY(db(b.dm_t, 6 * d, B, D_ADA_B, q));
+    DP_TRY(dwb(b.dm_t, B, 6 * d, sc_in, d, D_ADA_W, D_ADA_B, q));
     rd.dm_t = sd.end();
   }
   g = gemm_base(dt);
