@@ -105,3 +105,10 @@ def rel_err(gpu: np.ndarray, ref: np.ndarray) -> float:
     den = float(np.max(np.abs(ref)))
     num = float(np.max(np.abs(gpu - ref)))
     return num / den if den > 0 else num
+
+
+def rel_l2(gpu: np.ndarray, ref: np.ndarray) -> float:
+    """||gpu - ref||_2 / ||ref||_2 over one tensor (reported beside rel_err; not a pass criterion)."""
+    den = float(np.sqrt(np.sum(np.square(ref))))
+    num = float(np.sqrt(np.sum(np.square(gpu - ref))))
+    return num / den if den > 0 else num

@@ -234,6 +234,28 @@ def make_stage_inputs(c: StageConfig, seed: int = 0, randomize_ln: bool = False,
     return out
 
 
+def make_attention_inputs(B, H, Nq, Nk, dh, seed, gain=1.0, row_shift=0.0):
+    """q [B,Nq,H*dh], k, v [B,Nk,H*dh], do [B,Nq,H*dh] for the attention operator, bf16-representable.
+
+    gain = 1, row_shift = 0: plain N(0,1) tensors.  Otherwise a stress input for a tiled online
+    softmax: queries are scaled by ``gain`` (logit spread), key j is scaled by a ramp rising from
+    0.5 to 1.5 along the key index (the extreme logits, hence the row maxima, tend to arrive in late
+    key tiles), and the first coordinate of every head carries a per-row constant: keys hold 4 there
+    and query i holds r_i sqrt(dh) / 4 with r_i ~ U(-row_shift, row_shift), which adds r_i to every
+    logit of row i (a shift that an exact softmax cancels)."""
+    rng = np.random.default_rng(seed)
+    d = H * dh
+    q, k, v, do = (rng.standard_normal((B, n, d)) for n in (Nq, Nk, Nk, Nq))
+    if gain != 1.0 or row_shift != 0.0:
+        q *= gain
+        k *= np.linspace(0.5, 1.5, Nk)[None, :, None]
+        r = rng.uniform(-row_shift, row_shift, size=(B, Nq))
+        for h in range(H):
+            k[:, :, h * dh] = 4.0
+            q[:, :, h * dh] = r * math.sqrt(dh) / 4.0
+    return tuple(round_bf16(t) for t in (q, k, v, do))
+
+
 def make_encoder_inputs(c: EncoderConfig, seed: int = 0, randomize_ln: bool = False):
     rng = np.random.default_rng(seed)
     params = _draw_params(rng, encoder_param_specs(c), c.dtype, randomize_ln)

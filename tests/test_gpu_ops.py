@@ -88,24 +88,48 @@ def test_gemm_weight_gradient_split_k(M, N, K, acc):
 
 
 ATTN_CASES = [
-    # B, H, Nq, Nk, dh, causal
-    (2, 3, 200, 200, 64, False),      # self-attention, ragged query and key tiles
-    (2, 3, 200, 77, 64, False),       # cross-attention to the 77-token context
-    (2, 2, 256, 256, 72, False),      # DiT head width (not a multiple of the MFMA depth)
-    (1, 2, 130, 130, 32, False),
-    (3, 4, 77, 77, 64, True),         # text encoder: causal, forward only
+    # B, H, Nq, Nk, dh, causal, gain, row_shift
+    (2, 3, 200, 200, 64, False, 1.0, 0.0),      # self-attention, ragged query and key tiles
+    (2, 3, 200, 77, 64, False, 1.0, 0.0),       # cross-attention to the 77-token context
+    (2, 2, 256, 256, 72, False, 1.0, 0.0),      # DiT head width (not a multiple of the MFMA depth)
+    (1, 2, 130, 130, 32, False, 1.0, 0.0),
+    (3, 4, 77, 77, 64, True, 1.0, 0.0),         # text encoder: causal, forward only
+    (2, 2, 200, 200, 64, True, 1.0, 0.0),       # causal over several key tiles: the diagonal mask meets full tiles
+    # sharp softmax: logits spread over tens of log2 units, a per-row shift of up to +-80, row maxima
+    # arriving in late key tiles -- the running reference of the online softmax has to move after the
+    # first tile (gain 16: at almost every tile; gain 4: at some tiles and not at others)
+    (2, 3, 200, 200, 64, False, 16.0, 80.0),
+    (2, 3, 200, 200, 64, False, 4.0, 80.0),
+    (2, 3, 200, 77, 64, False, 16.0, 80.0),
+    (2, 2, 256, 256, 72, False, 16.0, 80.0),
+    (2, 2, 256, 256, 72, False, 4.0, 30.0),
+    (3, 4, 77, 77, 64, True, 16.0, 80.0),
+    (2, 2, 200, 200, 64, True, 8.0, 80.0),      # the causal edge mask and the moving reference together
 ]
 
 
-@pytest.mark.parametrize("case", ATTN_CASES, ids=lambda c: "B{}H{}q{}k{}d{}{}".format(*c[:5], "c" if c[5] else ""))
+def _attn_id(c):
+    return "B{}H{}q{}k{}d{}{}{}".format(*c[:5], "c" if c[5] else "", f"_gain{c[6]:g}_shift{c[7]:g}" if c[6] != 1.0 else "")
+
+
+@pytest.mark.parametrize("case", ATTN_CASES, ids=_attn_id)
 def test_attention_forward_and_backward(case):
     import torch
     from paper_2405_01248_amd import binding as B
-    from paper_2405_01248_amd.harness import _np_to_dev, _dev_to_np, rel_err
-    Bt, H, Nq, Nk, dh, causal = case
+    from paper_2405_01248_amd.harness import _np_to_dev, _dev_to_np, rel_err, rel_l2
+    from softmax_schedule import head_logits, rescale_stats
+    Bt, H, Nq, Nk, dh, causal, gain, row_shift = case
     d = H * dh
-    rng = np.random.default_rng(Nq * 31 + Nk)
-    q, k, v, do = (si.round_bf16(rng.standard_normal((Bt, n, d))) for n in (Nq, Nk, Nk, Nq))
+    q, k, v, do = si.make_attention_inputs(Bt, H, Nq, Nk, dh, seed=Nq * 31 + Nk, gain=gain, row_shift=row_shift)
+    s = head_logits(q, k, H, causal)
+    if gain != 1.0:
+        # the stress must really be a stress: replay the kernel's rule for moving the softmax reference on
+        # the oracle's logits and require that it fires after the first key tile, on peaked rows
+        st = rescale_stats(s)
+        print(f"\n[attention stress {_attn_id(case)}] {st}", flush=True)
+        assert st["moves_late"] > 0 and st["max_rise_log2"] > 8.0 and st["mean_max_prob"] > 0.5, st
+        if gain <= 4.0:
+            assert st["moves_late"] < st["steps_late"], st          # ... and also does not fire at some tiles
     dq_, dk_, dv_, ddo = (_np_to_dev(t, "bf16") for t in (q, k, v, do))
     o = torch.zeros((Bt, Nq, d), dtype=torch.bfloat16, device="cuda:0")
     lse = torch.zeros((Bt, H, Nq), dtype=torch.float32, device="cuda:0")
@@ -114,13 +138,9 @@ def test_attention_forward_and_backward(case):
     torch.cuda.synchronize()
     ref_o = ops.attention_fwd(q, k, v, H, causal)
     e = rel_err(_dev_to_np(o), ref_o)
-    print(f"\n[attention fwd {case}] rel err {e:.2e}", flush=True)
+    print(f"\n[attention fwd {_attn_id(case)}] rel err {e:.2e}, rel L2 {rel_l2(_dev_to_np(o), ref_o):.2e}", flush=True)
     assert e <= TOL_BF16
     # the log-sum-exp the backward re-derives the probabilities from
-    qh = q.reshape(Bt, Nq, H, dh); kh = k.reshape(Bt, Nk, H, dh)
-    s = np.einsum("bqhd,bkhd->bhqk", qh, kh) * scale
-    if causal:
-        s = np.where(np.arange(Nk)[None, :] > np.arange(Nq)[:, None], -np.inf, s)
     m = s.max(axis=-1)
     ref_lse = m + np.log(np.exp(s - m[..., None]).sum(axis=-1))
     e_lse = float(np.max(np.abs(_dev_to_np(lse) - ref_lse)))
@@ -133,5 +153,5 @@ def test_attention_forward_and_backward(case):
     torch.cuda.synchronize()
     rq, rk, rv = ops.attention_bwd(do, q, k, v, H, False)
     errs = {"dq": rel_err(_dev_to_np(gq), rq), "dk": rel_err(_dev_to_np(gk), rk), "dv": rel_err(_dev_to_np(gv), rv)}
-    print(f"[attention bwd {case}] {errs}", flush=True)
+    print(f"[attention bwd {_attn_id(case)}] {errs}", flush=True)
     assert max(errs.values()) <= TOL_BF16, errs

@@ -25,7 +25,7 @@ def _oracle_stage(cfg, inp):
 
 
 def _compare(cfg, got, ref, tol=None):
-    from paper_2405_01248_amd.harness import rel_err
+    from paper_2405_01248_amd.harness import rel_err, rel_l2
     tol = TOL[cfg.dtype] if tol is None else tol
     errs = {"y": rel_err(got["y"], ref["y"]), "dx": rel_err(got["dx"], ref["dx"])}
     if ref["y_sc"] is not None:
@@ -35,7 +35,10 @@ def _compare(cfg, got, ref, tol=None):
     for k, g in ref["grads"].items():
         errs["d" + k] = rel_err(got["grads"][k], g)
     worst = max(errs, key=errs.get)
-    print(f"\n[{cfg.name}] worst {worst} = {errs[worst]:.3e}; y {errs['y']:.2e} dx {errs['dx']:.2e}", flush=True)
+    l2 = {"y": rel_l2(got["y"], ref["y"]), "dx": rel_l2(got["dx"], ref["dx"])}
+    l2.update({"d" + k: rel_l2(got["grads"][k], g) for k, g in ref["grads"].items()})
+    print(f"\n[{cfg.name}] worst {worst} = {errs[worst]:.3e}; y {errs['y']:.2e} dx {errs['dx']:.2e}; "
+          f"relative L2: y {l2['y']:.2e} dx {l2['dx']:.2e} mean over tensors {np.mean(list(l2.values())):.2e}", flush=True)
     bad = {k: v for k, v in errs.items() if not (v <= tol)}
     assert not bad, bad
     for k in ("y", "dx"):
@@ -84,12 +87,23 @@ def test_stage_degenerate_sizes(cfg):
 
 @pytest.mark.parametrize("cfg", [SMALL_UNET, SMALL_DIT], ids=lambda c: c.name)
 def test_stage_sharp_softmax_stress(cfg):
-    """Query/key projections scaled up so that softmax rows are far from uniform and the
-    running maximum of the online softmax moves between key tiles."""
-    ds, inp = _run(cfg, seed=3, randomize_ln=True, logit_gain=4.0)
+    """Query/key projections scaled up so that softmax rows are peaked and the reference point of the
+    online softmax has to move between key tiles.  The gain is bounded by the storage format, not by the
+    kernel: q and k are stored in bf16, and a logit error of |logit| 2^-9 turns into a relative error of the
+    same size in every probability, so beyond a logit spread of ~10 natural units the 2e-2 bar is crossed by
+    the rounding of q and k alone (the operator-level stress cases, whose inputs are exact, go to 16x that)."""
+    from softmax_schedule import head_logits, rescale_stats
+    ds, inp = _run(cfg, seed=3, randomize_ln=True, logit_gain=8.0)
     ref = _oracle_stage(cfg, inp)
-    # the stress must really be a stress: the oracle's attention rows are peaked
-    p = inp["params"]
+    # the stress must really be a stress: replay the kernel's rule for moving the softmax reference on the
+    # oracle's own self-attention logits of every block
+    cc = inp["ctx"] if cfg.kind == si.UNET else inp["cond"]
+    _, caches = blocks.stage_fwd(cfg.kind, inp["params"], inp["x"], cc, cfg.n_blocks, cfg.n_heads, cfg.ln_eps, bool(cfg.gelu_tanh))
+    qn, kn = ("q1", "k1") if cfg.kind == si.UNET else ("q", "k")
+    for i, c in enumerate(caches):
+        st = rescale_stats(head_logits(c[qn], c[kn], cfg.n_heads))
+        print(f"\n[{cfg.name} block {i} self-attention] {st}", flush=True)
+        assert st["moves_late"] > 0 and st["max_rise_log2"] > 8.0 and st["mean_max_prob"] > 0.5, st
     _compare(cfg, ds.results(), ref)
 
 
@@ -301,6 +315,15 @@ SMALL_ENC = si.EncoderConfig("small_enc_bf16", "bf16", 2, 128, 2, 64, 77, 1000, 
 SMALL_ENC_F32 = si.EncoderConfig("small_enc_f32", "f32", 2, 32, 2, 16, 9, 100, 64, 5)
 
 
+def _encoder_output(cfg, inp):
+    import torch
+    from paper_2405_01248_amd.harness import DeviceEncoder
+    de = DeviceEncoder(cfg, inp)
+    de.run_slices(cfg.global_batch)
+    torch.cuda.synchronize()
+    return de.output()
+
+
 def _oracle_encoder(cfg, inp):
     return text_encoder.encoder_fwd(inp["params"], inp["ids"], cfg.n_layers, cfg.n_heads, cfg.ln_eps, bool(cfg.causal))
 
@@ -331,11 +354,36 @@ def test_encoder_partial_batches_match_oracle_and_each_other(cfg):
     for off, n in ((0, 2), (2, gb - 2)):
         de.enc.fwd_partial(de.params, de.ids, de.hidden, gb, 2, nl, off, n, de.ws)
     torch.cuda.synchronize()
-    # the state between calls is held in the storage dtype (one extra rounding at the split)
+    # the state between calls is held in the storage dtype: one extra rounding of the hidden state at the
+    # split (relative 2^-9 per element in bf16), carried through the remaining layers and the final rounding.
+    # Bound: two bf16 ulps of the largest output element (2^-7) for the worst element, and a relative L2
+    # distance of the order of the rounding itself -- a wrong row, sample or layer would break both by far
+    from paper_2405_01248_amd.harness import rel_l2
     split = de.output()
-    e_split, e_ref = rel_err(split, outs[gb]), rel_err(split, ref)
-    assert e_split <= (1e-2 if cfg.dtype == "bf16" else 1e-6), e_split
+    e_split, l2_split, e_ref = rel_err(split, outs[gb]), rel_l2(split, outs[gb]), rel_err(split, ref)
+    print(f"[{cfg.name}] layer-range split vs one call: max {e_split:.2e}, rel L2 {l2_split:.2e}", flush=True)
+    assert e_split <= (2.0 ** -7 if cfg.dtype == "bf16" else 1e-6), e_split
+    assert l2_split <= (3e-3 if cfg.dtype == "bf16" else 1e-6), l2_split
     assert e_ref <= TOL[cfg.dtype], e_ref
+
+
+def test_encoder_token_ids_outside_the_vocabulary_are_clamped():
+    """ids below 0 or at / above vocab read the first / last row of the token table (documented behaviour
+    of encoder_fwd_partial): the result is bit for bit that of the clamped ids."""
+    import torch
+    from paper_2405_01248_amd.harness import DeviceEncoder
+    cfg = SMALL_ENC
+    inp = si.make_encoder_inputs(cfg, seed=4)
+    bad = inp["ids"].copy()
+    bad[0, 0], bad[1, 5], bad[2, 76], bad[5, 40] = -1, cfg.vocab, -(2 ** 31), 2 ** 31 - 1
+    outs = []
+    for ids in (bad, np.clip(bad, 0, cfg.vocab - 1)):
+        de = DeviceEncoder(cfg, {"params": inp["params"], "ids": ids.astype(np.int32)})
+        de.run_slices(cfg.global_batch)
+        torch.cuda.synchronize()
+        outs.append(de.output())
+    assert np.isfinite(outs[0]).all() and np.array_equal(outs[0], outs[1])
+    assert not np.array_equal(outs[0][0], _encoder_output(cfg, inp)[0])     # and the bad ids did matter
 
 
 @pytest.mark.parametrize("cfg", [si.EncoderConfig("edge_enc_bf16_seq1", "bf16", 1, 64, 1, 64, 1, 50, 64, 1),
@@ -412,7 +460,14 @@ def test_encoder_full_size_all_slice_sizes():
         torch.cuda.synchronize()
         assert np.array_equal(de.output(), out)
         # across slice sizes the results agree to rounding only: the projections of small slices are
-        # split along the contraction, which changes the order of the fp32 sums
+        # split along the contraction, which changes the order of the fp32 sums (relative 1e-6), which
+        # flips the bf16 rounding of a few elements per layer by one ulp (relative 2^-8 of that element).
+        # Bound: two ulps of the largest element for the worst element; the relative L2 distance stays an
+        # order of magnitude below one rounding of every element (2^-9), since most elements agree exactly
+        from paper_2405_01248_amd.harness import rel_l2
         if first is None:
             first = out
-        assert rel_err(out, first) <= 1e-2
+        e_sl, l2_sl = rel_err(out, first), rel_l2(out, first)
+        print(f"[{cfg.name}] slice {b} vs slice {cfg.slices[0]}: max {e_sl:.2e}, rel L2 {l2_sl:.2e}, "
+              f"{100.0 * np.mean(out == first):.1f} % of elements identical", flush=True)
+        assert e_sl <= 2.0 ** -7 and l2_sl <= 2e-3, (e_sl, l2_sl)
