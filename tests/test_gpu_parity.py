@@ -356,14 +356,18 @@ def test_encoder_partial_batches_match_oracle_and_each_other(cfg):
     torch.cuda.synchronize()
     # the state between calls is held in the storage dtype: one extra rounding of the hidden state at the
     # split (relative 2^-9 per element in bf16), carried through the remaining layers and the final rounding.
-    # Bound: two bf16 ulps of the largest output element (2^-7) for the worst element, and a relative L2
-    # distance of the order of the rounding itself -- a wrong row, sample or layer would break both by far
+    # Bound: two bf16 ulps of the largest output element (2^-7) for the worst element.  In relative L2: the
+    # extra rounding perturbs an element by delta ~ 2^-9 / sqrt(3) = 1.1e-3 (rms, relative); both outputs are
+    # then rounded to bf16 again (ulp 2^-8 .. 2^-7 relative, 5.6e-3 on average), and two roundings of values
+    # delta apart differ by one ulp with probability delta / ulp, i.e. by sqrt(delta * ulp) = 2.5e-3 rms; the
+    # layers in between amplify a little (3.0e-3 measured).  6e-3 leaves a factor of two; a wrong row, sample
+    # or layer is off by O(1)
     from paper_2405_01248_amd.harness import rel_l2
     split = de.output()
     e_split, l2_split, e_ref = rel_err(split, outs[gb]), rel_l2(split, outs[gb]), rel_err(split, ref)
     print(f"[{cfg.name}] layer-range split vs one call: max {e_split:.2e}, rel L2 {l2_split:.2e}", flush=True)
     assert e_split <= (2.0 ** -7 if cfg.dtype == "bf16" else 1e-6), e_split
-    assert l2_split <= (3e-3 if cfg.dtype == "bf16" else 1e-6), l2_split
+    assert l2_split <= (6e-3 if cfg.dtype == "bf16" else 1e-6), l2_split
     assert e_ref <= TOL[cfg.dtype], e_ref
 
 
@@ -460,14 +464,16 @@ def test_encoder_full_size_all_slice_sizes():
         torch.cuda.synchronize()
         assert np.array_equal(de.output(), out)
         # across slice sizes the results agree to rounding only: the projections of small slices are
-        # split along the contraction, which changes the order of the fp32 sums (relative 1e-6), which
-        # flips the bf16 rounding of a few elements per layer by one ulp (relative 2^-8 of that element).
-        # Bound: two ulps of the largest element for the worst element; the relative L2 distance stays an
-        # order of magnitude below one rounding of every element (2^-9), since most elements agree exactly
+        # split along the contraction, which changes the order of the fp32 sums (relative 1e-6) and so
+        # flips the bf16 rounding of a few stored elements per layer; a flipped element (one ulp, 2^-8 ..
+        # 2^-7 relative) perturbs everything downstream of it a little, which flips more roundings, and after
+        # 12 layers of 5 stored tensors each most output elements sit one ulp apart (39 % identical measured).
+        # Bound: two ulps of the largest element for the worst element, and a relative L2 distance of one
+        # average ulp on every element (5.6e-3; 4.2e-3 measured) -- a wrong row or sample is off by O(1)
         from paper_2405_01248_amd.harness import rel_l2
         if first is None:
             first = out
         e_sl, l2_sl = rel_err(out, first), rel_l2(out, first)
         print(f"[{cfg.name}] slice {b} vs slice {cfg.slices[0]}: max {e_sl:.2e}, rel L2 {l2_sl:.2e}, "
               f"{100.0 * np.mean(out == first):.1f} % of elements identical", flush=True)
-        assert e_sl <= 2.0 ** -7 and l2_sl <= 2e-3, (e_sl, l2_sl)
+        assert e_sl <= 2.0 ** -7 and l2_sl <= 6e-3, (e_sl, l2_sl)
