@@ -269,6 +269,21 @@ int dp_op_gemm(int dtype, const void* A, int lda, int a_kmajor, const void* B, i
                const void* bias, void* C, int ldc, int out_is_f32, int accumulate, void* workspace, size_t workspace_bytes,
                int tile_cfg, void* hip_stream);
 
+/* dp_op_gemm for callers that cannot allocate device memory: code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc.  Same operation, arguments and results as dp_op_gemm (bit for bit
+ * those of dp_op_gemm given a workspace of dp_op_gemm_workspace_bytes), but the split-K partial sums live in
+ * a device array of DP_STATIC_SCRATCH_BYTES that is part of the library image: every GPU the library runs on
+ * holds its own copy until the process ends.  The call allocates and frees nothing, on the host's heap or
+ * the device.  A problem for which dp_op_gemm_workspace_bytes(M, N, K) exceeds DP_STATIC_SCRATCH_BYTES is
+ * rejected with DP_EWORKSPACE before anything is launched.  The device of hip_stream must be the calling
+ * thread's current device (the array's address is looked up per device, on the first call on that device).
+ * All calls on one GPU share that GPU's array: calls that may overlap on one GPU (different streams, or
+ * different threads) race on it; issue them on one stream.  Nothing in the array has to be cleared
+ * between calls: a call overwrites every partial sum it later reads. */
+#define DP_STATIC_SCRATCH_BYTES (64u << 20)
+int dp_op_gemm_static(int dtype, const void* A, int lda, int a_kmajor, const void* B, int ldb, int b_kmajor, int M, int N, int K,
+                      const void* bias, void* C, int ldc, int out_is_f32, int accumulate, int tile_cfg, void* hip_stream);
+
 /* dp_op_attention_fwd / _bwd: per (batch, head) O = softmax(Q K^T * scale [causal]) V.
  * Element (b, n, h, t) of a tensor X is X[(b * rows + n) * ldX + h * d_head + t], so Q, K, V may
  * be column blocks of one fused projection output.  lse: fp32 [B, H, Nq] (written by fwd, read

@@ -77,7 +77,7 @@ KERNEL_KINDS = {0: "gemm_nt", 1: "gemm_nn", 2: "gemm_tn", 3: "attn_fwd", 4: "att
 EXPORTS = ["dp_stage_create", "dp_stage_destroy", "dp_stage_set_overlap", "dp_stage_set_fusion", "dp_stage_param_count", "dp_stage_param_shape", "dp_stage_workspace_bytes",
            "stage_fwd", "stage_bwd", "dp_encoder_create", "dp_encoder_destroy", "dp_encoder_param_count",
            "dp_encoder_param_shape", "dp_encoder_workspace_bytes", "encoder_fwd_partial", "dp_stage_profile",
-           "dp_encoder_profile", "dp_ktime_begin", "dp_ktime_end", "dp_ktime_event_overhead_ms", "dp_last_error", "dp_op_gemm", "dp_op_gemm_workspace_bytes",
+           "dp_encoder_profile", "dp_ktime_begin", "dp_ktime_end", "dp_ktime_event_overhead_ms", "dp_last_error", "dp_op_gemm", "dp_op_gemm_static", "dp_op_gemm_workspace_bytes",
            "dp_op_attention_fwd", "dp_op_attention_bwd", "dp_partition_solve", "dp_bubbles_1f1b", "dp_bubbles_fill"]
 
 
@@ -117,6 +117,7 @@ def load_library():
     f = C.c_float
     lib.dp_op_gemm_workspace_bytes.argtypes = [i, i, i]; lib.dp_op_gemm_workspace_bytes.restype = sz
     lib.dp_op_gemm.argtypes = [i, vp, i, i, vp, i, i, i, i, i, vp, vp, i, i, i, vp, sz, i, vp]
+    lib.dp_op_gemm_static.argtypes = [i, vp, i, i, vp, i, i, i, i, i, vp, vp, i, i, i, i, vp]
     lib.dp_op_attention_fwd.argtypes = [i, i, i, i, i, i, i, f, vp, i, vp, i, vp, i, vp, i, vp, vp]
     lib.dp_op_attention_bwd.argtypes = [i, i, i, i, i, i, f, vp, i, vp, i, vp, i, vp, i, vp, vp, i, vp, vp, i, vp, i, vp, i, vp]
     lib.dp_partition_solve.argtypes = [C.POINTER(LayerCost), i, C.POINTER(PartitionOpts), C.POINTER(PartitionPlan)]
@@ -342,6 +343,15 @@ def op_gemm(dtype, A, lda, a_kmajor, B, ldb, b_kmajor, M, N, K, bias, Cout, ldc,
     _check(load_library().dp_op_gemm(dtype, _ptr(A), lda, int(a_kmajor), _ptr(B), ldb, int(b_kmajor), M, N, K, _ptr(bias),
                                      _ptr(Cout), ldc, int(out_is_f32), int(accumulate), _ptr(workspace), _nbytes(workspace),
                                      tile_cfg, _stream(stream)))
+
+
+STATIC_SCRATCH_BYTES = 64 << 20
+
+
+def op_gemm_static(dtype, A, lda, a_kmajor, B, ldb, b_kmajor, M, N, K, bias, Cout, ldc, out_is_f32=False, accumulate=False,
+                   tile_cfg=0, stream=None):
+    _check(load_library().dp_op_gemm_static(dtype, _ptr(A), lda, int(a_kmajor), _ptr(B), ldb, int(b_kmajor), M, N, K, _ptr(bias),
+                                            _ptr(Cout), ldc, int(out_is_f32), int(accumulate), tile_cfg, _stream(stream)))
 
 
 def op_gemm_workspace_bytes(M, N, K):
