@@ -115,6 +115,61 @@ CONFIG5 = EncoderConfig("cfg5_clip_l_text", "bf16", 12, 768, 12, 64, 77, 49408, 
 STAGE_CONFIGS = {c.name: c for c in (CONFIG1, CONFIG2, CONFIG3, CONFIG4)}
 
 
+@dataclass(frozen=True)
+class ImageEncoderConfig:
+    """A frozen convolutional image encoder (the auto-encoder's encoder of a latent diffusion model):
+    `layers` is a tuple of (kind, c_in, c_out, stride) with kind in conv / resnet / attn / norm_conv."""
+    name: str
+    dtype: str
+    height: int
+    width: int
+    in_ch: int
+    groups: int
+    layers: tuple
+    global_batch: int
+    gn_eps: float = 1e-6
+    slices: tuple = (1, 2, 4, 8)
+
+    def replace(self, **kw) -> "ImageEncoderConfig":
+        d = {f: getattr(self, f) for f in self.__dataclass_fields__}
+        d.update(kw)
+        return ImageEncoderConfig(**d)
+
+    def layer_dicts(self):
+        return [{"kind": k, "cin": ci, "cout": co, "stride": st} for (k, ci, co, st) in self.layers]
+
+    def out_shape(self, upto=None):
+        """(H, W, C) after layer `upto - 1` (all layers when None); upto = 0 is the input."""
+        h, w, c = self.height, self.width, self.in_ch
+        for (k, ci, co, st) in self.layers[:len(self.layers) if upto is None else upto]:
+            if k == "conv" and st == 2:
+                h, w = (h - 1) // 2 + 1, (w - 1) // 2 + 1
+            c = co
+        return h, w, c
+
+
+def vae_encoder_layers(ch=128, mult=(1, 2, 4, 4), in_ch=8, out_ch=8):
+    """The encoder of the latent-diffusion auto-encoder: input convolution, per resolution two
+    residual blocks and (but for the last) a stride-2 convolution, a middle of residual block /
+    attention / residual block, and the GroupNorm + SiLU + convolution head.  in_ch = 8: the three
+    image channels padded with zero channels to a 16-byte pixel."""
+    L = [("conv", in_ch, ch, 1)]
+    c = ch
+    for i, m in enumerate(mult):
+        for _ in range(2):
+            L.append(("resnet", c, ch * m, 1))
+            c = ch * m
+        if i != len(mult) - 1:
+            L.append(("conv", c, c, 2))
+    L += [("resnet", c, c, 1), ("attn", c, c, 1), ("resnet", c, c, 1), ("norm_conv", c, out_ch, 1)]
+    return tuple(L)
+
+
+# Stable Diffusion's image encoder at the paper's 512 x 512 training resolution (Sec. "Evaluation"): 16 layers,
+# 128..512 channels, 64 x 64 x 8 output (mean and log-variance of the 4-channel latent).
+CONFIG6 = ImageEncoderConfig("cfg6_vae_encoder_512", "bf16", 512, 512, 8, 32, vae_encoder_layers(), 8)
+
+
 # --------------------------------------------------------------------------
 # parameter tables: (name, shape, init) in the order the C ABI takes them
 # init: "w" -> N(0, 0.02), "one" -> 1, "zero" -> 0
@@ -254,6 +309,53 @@ def make_attention_inputs(B, H, Nq, Nk, dh, seed, gain=1.0, row_shift=0.0):
             k[:, :, h * dh] = 4.0
             q[:, :, h * dh] = r * math.sqrt(dh) / 4.0
     return tuple(round_bf16(t) for t in (q, k, v, do))
+
+
+def image_encoder_param_specs(c: ImageEncoderConfig):
+    """(name, shape, init) in the order the C ABI takes them.  Convolution weights are [C_out, 9 * C_in]
+    (taps row-major, channels last), 1x1 convolutions [C_out, C_in]."""
+    out = []
+    for l, (kind, ci, co, st) in enumerate(c.layers):
+        pre = f"layer{l}."
+        if kind == "conv":
+            per = [("w", (co, 9 * ci), "w"), ("b", (co,), "w")]
+        elif kind == "resnet":
+            per = [("norm1_g", (ci,), "one"), ("norm1_b", (ci,), "zero"), ("conv1_w", (co, 9 * ci), "w"), ("conv1_b", (co,), "w"),
+                   ("norm2_g", (co,), "one"), ("norm2_b", (co,), "zero"), ("conv2_w", (co, 9 * co), "w"), ("conv2_b", (co,), "w")]
+            if ci != co:
+                per += [("skip_w", (co, ci), "w"), ("skip_b", (co,), "w")]
+        elif kind == "attn":
+            per = [("norm_g", (ci,), "one"), ("norm_b", (ci,), "zero")]
+            for n in ("q", "k", "v", "proj"):
+                per += [(n + "_w", (ci, ci), "w"), (n + "_b", (ci,), "w")]
+        elif kind == "norm_conv":
+            per = [("norm_g", (ci,), "one"), ("norm_b", (ci,), "zero"), ("w", (co, 9 * ci), "w"), ("b", (co,), "w")]
+        else:
+            raise ValueError(kind)
+        out += [(pre + n, s, i) for (n, s, i) in per]
+    return out
+
+
+def make_image_encoder_inputs(c: ImageEncoderConfig, seed: int = 0, randomize_norm: bool = False, weight_std: float = 0.02):
+    """params in table order, then images [global_batch, H, W, in_ch] ~ N(0, 1) (a normalised image; when
+    in_ch = 8 the channels 3..7 are the zero padding).  weight_std: the N(0, 0.02) of the other workloads
+    makes a 3x3 convolution shrink its input by an order of magnitude per layer; tests may pass
+    1 / sqrt(fan_in)-like values to keep activations O(1) through 16 layers."""
+    rng = np.random.default_rng(seed)
+    params = {}
+    for name, shape, init in image_encoder_param_specs(c):
+        if init == "w":
+            std = weight_std if weight_std > 0 else (1.0 / math.sqrt(shape[1]) if len(shape) == 2 else 0.02)
+            a = rng.normal(0.0, std, size=shape)
+        elif init == "one":
+            a = 1.0 + (rng.normal(0.0, 0.1, size=shape) if randomize_norm else np.zeros(shape))
+        else:
+            a = rng.normal(0.0, 0.1, size=shape) if randomize_norm else np.zeros(shape)
+        params[name] = round_storage(a, c.dtype)
+    x = rng.normal(size=(c.global_batch, c.height, c.width, c.in_ch))
+    if c.in_ch == 8:
+        x[..., 3:] = 0.0
+    return {"params": params, "x": round_storage(x, c.dtype)}
 
 
 def make_encoder_inputs(c: EncoderConfig, seed: int = 0, randomize_ln: bool = False):
