@@ -55,6 +55,23 @@ def encoder_flops_per_sample(c):
     return float(per_layer * c.n_layers)
 
 
+def image_encoder_flops_per_sample(c):
+    """2 * pixels * c_out * 9 c_in per 3x3 convolution, 2mnk per 1x1 convolution, 4 * pixels^2 * c for the attention block."""
+    h, w, fl = c.height, c.width, 0.0
+    for (kind, ci, co, st) in c.layers:
+        px = h * w
+        if kind == "conv":
+            h, w = (h - 1) // st + 1, (w - 1) // st + 1
+            fl += 2.0 * h * w * co * 9 * ci
+        elif kind == "resnet":
+            fl += 2.0 * px * co * 9 * ci + 2.0 * px * co * 9 * co + (2.0 * px * co * ci if ci != co else 0.0)
+        elif kind == "attn":
+            fl += 4 * 2.0 * px * ci * ci + 4.0 * px * px * ci
+        else:
+            fl += 2.0 * px * co * 9 * ci
+    return fl
+
+
 def timed(fn, steps, warmup):
     import torch
     for _ in range(warmup):
@@ -100,6 +117,24 @@ def cpu_baseline_stage(cfg):
                       + (" incl. the extra no-grad forward" if cfg.self_cond else "") + f", {t:.1f} s"}
 
 
+def cpu_baseline_image_encoder(cfg):
+    """The fp64 oracle of the image encoder on one sample of the workload (about half a minute)."""
+    import synth_inputs as si
+    from oracle import image_encoder as ie
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    c = cfg.replace(global_batch=1)
+    inp = si.make_image_encoder_inputs(c, seed=0, weight_std=0.0)
+    t0 = time.perf_counter()
+    ie.encoder_fwd(inp["params"], c.layer_dicts(), inp["x"], c.groups, c.gn_eps)
+    t = time.perf_counter() - t0
+    return {"value": 1.0 / t, "unit": "samples/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"1 of {cfg.global_batch} samples of {cfg.name}, one fp64 numpy forward, {t:.1f} s"}
+
+
 # HBM bytes per launch of the dominant kernel measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE),
 # scaled by kernels of known size in the same run (FETCH_SIZE x 2.0, WRITE_SIZE x 1.0); the counter runs and the
 # per-kernel table are in profiles/hbm_traffic_cfg2.md.  Average over the launches of the class in one step.
@@ -108,13 +143,15 @@ PMC_TRAFFIC_BYTES = {
     ("cfg2", "gemm_tn"): 116.6e6,   # 14 launches per step: dW = dy^T x, split-K partial sums included
 }
 
-MFMA_KINDS = {"gemm_nt", "gemm_nn", "gemm_tn", "attn_fwd", "attn_bwd_dq", "attn_bwd_dkv"}
+MFMA_KINDS = {"gemm_nt", "gemm_nn", "gemm_tn", "attn_fwd", "attn_bwd_dq", "attn_bwd_dkv", "conv3x3"}
 KERNEL_NAMES = {"gemm_nt": "dp::gemm_bf16_dtl_kernel<..., A_MC=false, B_MC=false> (y = x W^T; dx = dy W on transposed weight copies)",
                 "gemm_nn": "dp::gemm_bf16_kernel<..., A_MC=false, B_MC=true> (dx = dy W)",
                 "gemm_tn": "dp::gemm_bf16_kernel<..., A_MC=true, B_MC=true> (dW = dy^T x)",
                 "attn_fwd": "dp::attn_fwd_bf16_kernel", "attn_bwd_dq": "dp::attn_bwd_dq_bf16_kernel",
                 "attn_bwd_dkv": "dp::attn_bwd_dkv_bf16_kernel", "ln_fwd": "dp::ln_fwd_kernel", "ln_bwd": "dp::ln_bwd_kernel",
-                "geglu_fwd": "dp::geglu_fwd_kernel", "geglu_bwd": "dp::geglu_bwd_kernel", "reduce": "dp::colsum_kernel"}
+                "geglu_fwd": "dp::geglu_fwd_kernel", "geglu_bwd": "dp::geglu_bwd_kernel", "reduce": "dp::colsum_kernel",
+                "conv3x3": "dp::conv3x3_bf16_kernel (implicit GEMM)", "groupnorm": "dp::gn_partial_kernel + gn_finalize_kernel + gn_apply_kernel",
+                "softmax_rows": "dp::softmax_rows_kernel"}
 
 
 def kernel_roofline(workload, names, si, DeviceStage, DeviceEncoder, passes=3):
@@ -123,6 +160,10 @@ def kernel_roofline(workload, names, si, DeviceStage, DeviceEncoder, passes=3):
     if workload == "cfg5":
         obj = DeviceEncoder(si.CONFIG5, si.make_encoder_inputs(si.CONFIG5, seed=0))
         run = lambda: obj.run_slices(si.CONFIG5.global_batch)
+    elif workload == "cfg6":
+        from paper_2405_01248_amd.harness import DeviceImageEncoder
+        obj = DeviceImageEncoder(si.CONFIG6, si.make_image_encoder_inputs(si.CONFIG6, seed=0, weight_std=0.0))
+        run = lambda: obj.run_slices(si.CONFIG6.global_batch)
     else:
         obj = DeviceStage(names[workload], si.make_stage_inputs(names[workload], seed=0))
         # single-kernel durations: issue the backward's side-stream work in program order
@@ -269,7 +310,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=30)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="cfg2", choices=["cfg2", "cfg3", "cfg4", "cfg5"])
+    ap.add_argument("--workload", default="cfg2", choices=["cfg2", "cfg3", "cfg4", "cfg5", "cfg6"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-others", action="store_true", help="skip the short runs of the other workloads")
     ap.add_argument("--serial", action="store_true",
@@ -319,6 +360,18 @@ def main():
                            "mfma_peak_frac": encoder_flops_per_sample(c) * c.global_batch / sec / MFMA_PEAK}
         return de, out
 
+    def run_image_encoder(steps, warmup):
+        from paper_2405_01248_amd.harness import DeviceImageEncoder
+        c = si.CONFIG6
+        de = DeviceImageEncoder(c, si.make_image_encoder_inputs(c, seed=0, weight_std=0.0))
+        out = {}
+        for b in c.slices:
+            sec = timed(lambda: de.run_slices(b), steps, warmup)
+            out[str(b)] = {"samples_per_s": c.global_batch / sec, "ms_per_global_batch": sec * 1e3,
+                           "ms_per_call": sec * 1e3 * b / c.global_batch,
+                           "mfma_peak_frac": image_encoder_flops_per_sample(c) * c.global_batch / sec / MFMA_PEAK}
+        return de, out
+
     if args.partition:
         print(json.dumps(partition_report(si, DeviceStage)[0]))
         return
@@ -328,7 +381,15 @@ def main():
 
     result = {"n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "higher_is_better": True, "scaling": "weak",
               "vs_baseline": None, "dtype": "bf16", "data": "synthetic"}
-    if args.workload == "cfg5":
+    if args.workload == "cfg6":
+        de, enc = run_image_encoder(max(2, args.steps // 3), max(1, args.warmup // 2))
+        full = enc[str(si.CONFIG6.global_batch)]
+        result.update(metric="image_encoder_fwd_samples_per_sec", value=full["samples_per_s"], unit="samples/s",
+                      ms_per_step=full["ms_per_global_batch"], mfma_peak_frac=full["mfma_peak_frac"],
+                      config={"workload": si.CONFIG6.name, "global_batch": si.CONFIG6.global_batch, "slice_sizes": enc,
+                              "algorithmic_tflop_per_sample": image_encoder_flops_per_sample(si.CONFIG6) / 1e12})
+        del de
+    elif args.workload == "cfg5":
         de, enc = run_encoder(args.steps, args.warmup)
         full = enc[str(si.CONFIG5.global_batch)]
         result.update(metric="encoder_fwd_samples_per_sec", value=full["samples_per_s"], unit="samples/s",
@@ -364,7 +425,7 @@ def main():
     # same launch configuration, with HIP events around every launch on the launch stream.
     result["roofline"], result["kernel_classes"] = kernel_roofline(args.workload, names, si, DeviceStage, DeviceEncoder)
     if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline_stage(names.get(args.workload, si.CONFIG2))
+        result["cpu_baseline"] = cpu_baseline_image_encoder(si.CONFIG6) if args.workload == "cfg6" else cpu_baseline_stage(names.get(args.workload, si.CONFIG2))
     print(json.dumps(result))
 
 

@@ -140,7 +140,8 @@ int encoder_fwd_partial(dp_encoder* enc, const void* const* params, const int32_
  * of component `component` at batch size `batch` (ms, median of reps), its output size O_l
  * (= the forward activation C^f_{l,l+1} sent to the next layer), the backward message
  * C^b_{l+1,l} and the gradient size G_l, in bytes.  component 0 = backbone stage (layer =
- * block index), 1 = text encoder (layer in the index space above; bwd_ms = 0, grad_bytes = 0). */
+ * block index), 1 = text encoder (layer in the index space above; bwd_ms = 0, grad_bytes = 0), 2 = image
+ * encoder (dp_image_encoder_profile). */
 typedef struct {
   int component, layer, batch;
   float fwd_ms, bwd_ms;
@@ -160,6 +161,57 @@ int dp_stage_profile(dp_stage* st, const void* const* params, const void* x, con
 int dp_encoder_profile(dp_encoder* enc, const void* const* params, const int32_t* ids, void* hidden,
                        int global_batch, const int* batches, int n_batches, int reps, void* workspace,
                        size_t workspace_bytes, dp_layer_cost* rows, int max_rows, int* n_rows, void* hip_stream);
+
+/* Frozen image encoder (Sec. 2.1: the image encoders of diffusion models are auto-encoders; Sec. 2.3 and its
+ * execution-time figure: their layers are the moderately long and the extra-long non-trainable layers, which
+ * fit a pipeline bubble only on part of the batch, Sec. 5), forward only, bf16 storage, channels-last tensors
+ * [batch, height, width, channels].  A layer is one of
+ *  DP_IMG_CONV:      y = conv3x3(x; stride 1 or 2, zero padding 1) + b;  parameters w [c_out, 9 * c_in] (taps
+ *                    row-major, channels last: w[o, (3u + v) * c_in + c] multiplies x[i * stride + u - 1, j * stride + v - 1, c]), b
+ *  DP_IMG_RESNET:    h = conv3x3(silu(GN(x))); h = conv3x3(silu(GN(h))); y = skip(x) + h, skip = identity or a 1x1
+ *                    convolution when c_in != c_out;  norm1_g norm1_b conv1_w conv1_b norm2_g norm2_b conv2_w conv2_b
+ *                    [skip_w [c_out, c_in] skip_b]
+ *  DP_IMG_ATTN:      h = GN(x); q, k, v = 1x1 convolutions of h; a = softmax(q k^T / sqrt(c)) v over the pixels of a
+ *                    sample (one head of width c); y = x + 1x1 convolution of a;  norm_g norm_b q_w q_b k_w k_b v_w v_b proj_w proj_b
+ *  DP_IMG_NORM_CONV: y = conv3x3(silu(GN(x))) + b (the output head);  norm_g norm_b w b
+ * GN = GroupNorm with `groups` groups of consecutive channels, biased variance, eps = gn_eps.  Output height
+ * of a stride-s convolution: (height - 1) / s + 1.  Limits: all channel counts multiples of 8 (an RGB image is
+ * padded with zero channels) and of `groups` where a GroupNorm reads them, at most 2048; an attention block
+ * needs height * width to be a multiple of 8, at most 65536.  DP_F32 is not supported (DP_EUNSUPPORTED). */
+typedef struct dp_image_encoder dp_image_encoder; /* opaque, host memory */
+enum dp_image_layer_kind { DP_IMG_CONV = 0, DP_IMG_RESNET = 1, DP_IMG_ATTN = 2, DP_IMG_NORM_CONV = 3 };
+typedef struct { int kind, c_in, c_out, stride; } dp_image_layer;
+typedef struct { int dtype, height, width, in_ch, groups, n_layers; float gn_eps; } dp_image_encoder_desc;
+
+/* layers [host]: n_layers entries, copied.  *out is untouched on error. */
+int dp_image_encoder_create(const dp_image_encoder_desc* desc, const dp_image_layer* layers, dp_image_encoder** out);
+void dp_image_encoder_destroy(dp_image_encoder* enc);
+/* Parameters as a flat array, layer by layer in the orders listed above; names "layer<i>.<tensor>". */
+int dp_image_encoder_param_count(const dp_image_encoder* enc);
+int dp_image_encoder_param_shape(const dp_image_encoder* enc, int idx, int64_t shape[2], const char** name);
+/* hwc = (height, width, channels) of the output of `layer`; layer = -1: the encoder's input. */
+int dp_image_encoder_layer_shape(const dp_image_encoder* enc, int layer, int64_t hwc[3]);
+/* Workspace bytes [device] for a call on layers [layer_begin, layer_end) and at most max_samples samples. */
+size_t dp_image_encoder_workspace_bytes(const dp_image_encoder* enc, int layer_begin, int layer_end, int max_samples);
+
+/* Runs layers [layer_begin, layer_end) on samples [sample_offset, sample_offset + num_samples) of the global
+ * batch: the partial-batch tuple (component, layer, #samples) of Sec. 5.  in [device]: the input of layer
+ * layer_begin for the whole global batch, [global_batch, h, w, c] of dp_image_encoder_layer_shape(layer_begin - 1);
+ * out [device]: the output of layer layer_end - 1, [global_batch, ...]; only the selected samples' rows of `out`
+ * are written, so calls on disjoint sample ranges can be issued in any order or in different bubbles, and a
+ * later call continues from `out` as its `in`.  in and out must be different buffers.  params [host]: all of the
+ * encoder's parameters (only those of the layers in range are read and checked).  num_samples = 0 is a valid
+ * empty slice.  Never allocates or synchronises. */
+int image_encoder_fwd_partial(dp_image_encoder* enc, const void* const* params, const void* in, void* out, int global_batch,
+                              int layer_begin, int layer_end, int sample_offset, int num_samples, void* workspace,
+                              size_t workspace_bytes, void* hip_stream);
+
+/* Times every layer at each requested partial-batch size (samples [0, b); in = the images, out = the last
+ * layer's output buffer); writes n_layers * n_batches rows with component = 2, bwd_ms = 0, grad_bytes = 0.
+ * This call synchronises. */
+int dp_image_encoder_profile(dp_image_encoder* enc, const void* const* params, const void* in, void* out, int global_batch,
+                             const int* batches, int n_batches, int reps, void* workspace, size_t workspace_bytes,
+                             dp_layer_cost* rows, int max_rows, int* n_rows, void* hip_stream);
 
 /* Backbone partitioner (Sec. 4.1, Eq. 1-9; self-conditioning Sec. 4.3, Eq. 17-18), host only: no
  * GPU call is made.  Input is the cost profile of the backbone, rows [host] of component 0 (other
@@ -302,7 +354,7 @@ int dp_op_attention_bwd(int dtype, int B, int H, int Nq, int Nk, int d_head, flo
  * its duration.  kind: 0 GEMM y = x W^T, 1 GEMM dx = dy W, 2 GEMM dW = dy^T x, 3 attention
  * forward, 4 attention dQ, 5 attention dK/dV, 6 LayerNorm forward, 7 LayerNorm backward,
  * 8 GeGLU forward, 9 GeGLU backward, 10 partial-sum reductions, 11 other, 12 fp32 GEMM,
- * 13 fp32 attention.  dp_ktime_begin allocates host-side events (max_records pairs);
+ * 13 fp32 attention, 14 3x3 convolution (2 * pixels * c_out * 9 c_in), 15 GroupNorm, 16 row softmax.  dp_ktime_begin allocates host-side events (max_records pairs);
  * dp_ktime_end synchronises the device, writes up to max records and frees them.  `ms` is the
  * time between a record's two events, which includes the dispatch gap around the kernel (an upper
  * bound of the kernel's duration: a few microseconds above what a kernel trace shows).  For scale,

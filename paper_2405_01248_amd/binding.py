@@ -32,6 +32,17 @@ class EncoderDesc(C.Structure):
                                        "causal")] + [("ln_eps", C.c_float)]
 
 
+class ImageLayer(C.Structure):
+    _fields_ = [(n, C.c_int) for n in ("kind", "c_in", "c_out", "stride")]
+
+
+class ImageEncoderDesc(C.Structure):
+    _fields_ = [(n, C.c_int) for n in ("dtype", "height", "width", "in_ch", "groups", "n_layers")] + [("gn_eps", C.c_float)]
+
+
+IMG_KINDS = {"conv": 0, "resnet": 1, "attn": 2, "norm_conv": 3}
+
+
 class LayerCost(C.Structure):
     _fields_ = [("component", C.c_int), ("layer", C.c_int), ("batch", C.c_int), ("fwd_ms", C.c_float), ("bwd_ms", C.c_float),
                 ("out_bytes", C.c_int64), ("cf_bytes", C.c_int64), ("cb_bytes", C.c_int64), ("grad_bytes", C.c_int64)]
@@ -72,12 +83,14 @@ class KernelTime(C.Structure):
 
 
 KERNEL_KINDS = {0: "gemm_nt", 1: "gemm_nn", 2: "gemm_tn", 3: "attn_fwd", 4: "attn_bwd_dq", 5: "attn_bwd_dkv", 6: "ln_fwd",
-                7: "ln_bwd", 8: "geglu_fwd", 9: "geglu_bwd", 10: "reduce", 11: "other", 12: "gemm_f32", 13: "attn_f32"}
+                7: "ln_bwd", 8: "geglu_fwd", 9: "geglu_bwd", 10: "reduce", 11: "other", 12: "gemm_f32", 13: "attn_f32", 14: "conv3x3", 15: "groupnorm", 16: "softmax_rows"}
 
 EXPORTS = ["dp_stage_create", "dp_stage_destroy", "dp_stage_set_overlap", "dp_stage_set_fusion", "dp_stage_param_count", "dp_stage_param_shape", "dp_stage_workspace_bytes",
            "stage_fwd", "stage_bwd", "dp_encoder_create", "dp_encoder_destroy", "dp_encoder_param_count",
            "dp_encoder_param_shape", "dp_encoder_workspace_bytes", "encoder_fwd_partial", "dp_stage_profile",
-           "dp_encoder_profile", "dp_ktime_begin", "dp_ktime_end", "dp_ktime_event_overhead_ms", "dp_last_error", "dp_op_gemm", "dp_op_gemm_static", "dp_op_gemm_workspace_bytes",
+           "dp_encoder_profile", "dp_image_encoder_create", "dp_image_encoder_destroy", "dp_image_encoder_param_count",
+           "dp_image_encoder_param_shape", "dp_image_encoder_layer_shape", "dp_image_encoder_workspace_bytes", "image_encoder_fwd_partial",
+           "dp_image_encoder_profile", "dp_ktime_begin", "dp_ktime_end", "dp_ktime_event_overhead_ms", "dp_last_error", "dp_op_gemm", "dp_op_gemm_static", "dp_op_gemm_workspace_bytes",
            "dp_op_attention_fwd", "dp_op_attention_bwd", "dp_partition_solve", "dp_bubbles_1f1b", "dp_bubbles_fill"]
 
 
@@ -114,6 +127,14 @@ def load_library():
     lib.encoder_fwd_partial.argtypes = [vp, pp, vp, vp, i, i, i, i, i, vp, sz, vp]
     lib.dp_stage_profile.argtypes = [vp, pp, vp, vp, vp, vp, vp, vp, pp, vp, sz, i, C.POINTER(LayerCost), i, C.POINTER(i), vp]
     lib.dp_encoder_profile.argtypes = [vp, pp, vp, vp, i, C.POINTER(i), i, i, vp, sz, C.POINTER(LayerCost), i, C.POINTER(i), vp]
+    lib.dp_image_encoder_create.argtypes = [C.POINTER(ImageEncoderDesc), C.POINTER(ImageLayer), pp]
+    lib.dp_image_encoder_destroy.argtypes = [vp]; lib.dp_image_encoder_destroy.restype = None
+    lib.dp_image_encoder_param_count.argtypes = [vp]
+    lib.dp_image_encoder_param_shape.argtypes = [vp, i, C.POINTER(C.c_int64), C.POINTER(C.c_char_p)]
+    lib.dp_image_encoder_layer_shape.argtypes = [vp, i, C.POINTER(C.c_int64)]
+    lib.dp_image_encoder_workspace_bytes.argtypes = [vp, i, i, i]; lib.dp_image_encoder_workspace_bytes.restype = sz
+    lib.image_encoder_fwd_partial.argtypes = [vp, pp, vp, vp, i, i, i, i, i, vp, sz, vp]
+    lib.dp_image_encoder_profile.argtypes = [vp, pp, vp, vp, i, C.POINTER(i), i, i, vp, sz, C.POINTER(LayerCost), i, C.POINTER(i), vp]
     f = C.c_float
     lib.dp_op_gemm_workspace_bytes.argtypes = [i, i, i]; lib.dp_op_gemm_workspace_bytes.restype = sz
     lib.dp_op_gemm.argtypes = [i, vp, i, i, vp, i, i, i, i, i, vp, vp, i, i, i, vp, sz, i, vp]
@@ -260,6 +281,42 @@ class Encoder(_Handle):
                                                  len(batches), reps, _ptr(workspace), _nbytes(workspace), rows, len(rows),
                                                  C.byref(n), _stream(stream)))
         return [rows[k].as_dict() for k in range(n.value)]
+
+
+class ImageEncoder(_Handle):
+    """Frozen image encoder; `layers` is a sequence of (kind, c_in, c_out, stride) with kind a key of IMG_KINDS."""
+    _destroy = "dp_image_encoder_destroy"
+
+    def __init__(self, dtype, height, width, in_ch, groups, layers, gn_eps=1e-6):
+        super().__init__()
+        self.n_layers = len(layers)
+        arr = (ImageLayer * len(layers))(*[ImageLayer(IMG_KINDS[k], ci, co, st) for (k, ci, co, st) in layers])
+        desc = ImageEncoderDesc(dtype, height, width, in_ch, groups, len(layers), gn_eps)
+        _check(load_library().dp_image_encoder_create(C.byref(desc), arr, C.byref(self._h)))
+
+    def param_specs(self):
+        return self._specs("dp_image_encoder_param_count", "dp_image_encoder_param_shape")
+
+    def layer_shape(self, layer: int):
+        hwc = (C.c_int64 * 3)()
+        _check(load_library().dp_image_encoder_layer_shape(self._h, layer, hwc))
+        return tuple(int(v) for v in hwc)
+
+    def workspace_bytes(self, layer_begin: int, layer_end: int, max_samples: int) -> int:
+        return load_library().dp_image_encoder_workspace_bytes(self._h, layer_begin, layer_end, max_samples)
+
+    def fwd_partial(self, params, x_in, out, global_batch, layer_begin, layer_end, sample_offset, num_samples, workspace, stream=None):
+        _check(load_library().image_encoder_fwd_partial(self._h, _ptr_array(params), _ptr(x_in), _ptr(out), global_batch, layer_begin, layer_end,
+                                                        sample_offset, num_samples, _ptr(workspace), _nbytes(workspace), _stream(stream)))
+
+    def profile(self, params, x_in, out, global_batch, batches, workspace, reps=5, stream=None):
+        n = self.n_layers * len(batches)
+        rows = (LayerCost * n)()
+        got = C.c_int(0)
+        barr = (C.c_int * len(batches))(*batches)
+        _check(load_library().dp_image_encoder_profile(self._h, _ptr_array(params), _ptr(x_in), _ptr(out), global_batch, barr, len(batches), reps,
+                                                       _ptr(workspace), _nbytes(workspace), rows, n, C.byref(got), _stream(stream)))
+        return [rows[k].as_dict() for k in range(got.value)]
 
 
 def ktime_begin(max_records: int = 65536):

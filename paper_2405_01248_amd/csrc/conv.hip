@@ -1,0 +1,189 @@
+// 3x3 convolution (zero padding 1, stride 1 or 2) of a channels-last bf16 tensor as an implicit GEMM
+// on the MFMA pipeline: out[(b, i, j), o] = sum over (tap, c) of x[b, i * stride + u - 1, j * stride + v - 1, c] *
+// w[o, tap * C_in + c], tap = 3u + v.  Rows of the product are output pixels, its contraction runs over the
+// nine taps times the input channels; the A operand is never materialised: every thread gathers its 16-byte
+// pieces of the input (8 channels of one pixel, which lie inside one tap because C_in is a multiple of 8)
+// straight from the tensor, with zeros where the tap falls into the padding.  Tiles are staged through
+// registers into padded LDS tiles (double buffered) and multiplied with v_mfma_f32_32x32x16_bf16; the
+// epilogue is the GEMM kernels' (bias, optional residual in the storage dtype).  This is the layer class of
+// the frozen image encoder (Sec. 2.1, Sec. 2.3: the non-trainable layers that take tens to hundreds of
+// milliseconds and are cut into partial batches, Sec. 5).
+#include "dp_device.h"
+#include "dp_kernels.h"
+#include "dp_errors.h"
+#include "dp_ktime.h"
+#include "dp_gemm_epilogue.h"
+
+#include <algorithm>
+
+namespace dp {
+
+struct ConvParams {
+  const bf16* x; const bf16* w;
+  int H, W, Cin, Ho, Wo, stride;
+  int M, N, K;                   // output pixels, output channels, 9 * C_in
+  int tiles_m, tiles_n, group_m;
+  int taps_uniform;              // C_in % 64 == 0: a 64-deep k-tile lies inside one filter tap
+  EpiParams<bf16> epi;
+};
+
+template <int BM, int BN, int WGM, int WGN>
+struct ConvSmem {
+  static constexpr int BK = 64, LD = BK + 8;
+  static constexpr int WN = BN / WGN, C_LD = WN + 4;
+  static constexpr size_t TILE_BYTES = 2 * (size_t)(BM + BN) * LD * 2;
+  static constexpr size_t EPI_BYTES = (size_t)WGM * WGN * 32 * C_LD * 4;
+  static constexpr size_t BYTES = TILE_BYTES > EPI_BYTES ? TILE_BYTES : EPI_BYTES;
+};
+
+template <int BM, int BN, int WGM, int WGN>
+__global__ void __launch_bounds__(WGM * WGN * 64) conv3x3_bf16_kernel(const ConvParams p) {
+  using S = ConvSmem<BM, BN, WGM, WGN>;
+  constexpr int BK = S::BK, LD = S::LD, NT = WGM * WGN * 64;
+  constexpr int WM = BM / WGM, WN = BN / WGN, TM = WM / 32, TN = WN / 32;
+  constexpr int A_PER = BM * BK / 8 / NT, B_PER = BN * BK / 8 / NT, ROWS_PER_PASS = NT / 8;
+  static_assert((BM * BK / 8) % NT == 0 && (BN * BK / 8) % NT == 0 && NT % 8 == 0, "tile/threads mismatch");
+
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+  bf16* As = reinterpret_cast<bf16*>(smem_raw);
+  bf16* Bs = As + 2 * BM * LD;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 5, l32 = lane & 31;
+  const int wm0 = (wave / WGN) * WM, wn0 = (wave % WGN) * WN;
+  int tile_m, tile_n;
+  tile_of_block(blockIdx.x, p.tiles_m, p.tiles_n, p.group_m, tile_m, tile_n);
+  const int m0 = tile_m * BM, n0 = tile_n * BN;
+
+  // A thread stages chunk c8 (8 contraction values) of rows tid / 8 + i * ROWS_PER_PASS of both tiles.  The
+  // output pixel behind an A row does not change along the contraction: decode it once.
+  const int c8 = tid & 7, r0 = tid >> 3;
+  int pix_b[A_PER], pix_h[A_PER], pix_w[A_PER];
+  unsigned row_ok = 0;
+#pragma unroll
+  for (int i = 0; i < A_PER; ++i) {
+    const int gm = m0 + r0 + i * ROWS_PER_PASS;
+    row_ok |= (unsigned)(gm < p.M) << i;
+    const int q = min(gm, p.M - 1);
+    const int b = q / (p.Ho * p.Wo), rem = q - b * (p.Ho * p.Wo), ho = rem / p.Wo, wo = rem - ho * p.Wo;
+    pix_b[i] = b; pix_h[i] = ho * p.stride - 1; pix_w[i] = wo * p.stride - 1;
+  }
+
+  bf16x8 ra[A_PER], rb[B_PER];
+  unsigned oka = 0, okb = 0;
+  auto load_global = [&](int kt) {
+    const int k0 = kt * BK, gk = k0 + c8 * 8;
+    int tap, ci;
+    if (p.taps_uniform) { tap = k0 / p.Cin; ci = k0 - tap * p.Cin + c8 * 8; }      // tap: one scalar division per k-tile
+    else { tap = gk / p.Cin; ci = gk - tap * p.Cin; }
+    const bool kok = gk < p.K;
+    tap = min(tap, 8); ci = min(ci, p.Cin - 8);
+    const int u = tap / 3, v = tap - 3 * u;
+    oka = 0; okb = 0;
+#pragma unroll
+    for (int i = 0; i < A_PER; ++i) {
+      const int hi = pix_h[i] + u, wi = pix_w[i] + v;
+      const bool ok = ((row_ok >> i) & 1) && kok && (unsigned)hi < (unsigned)p.H && (unsigned)wi < (unsigned)p.W;
+      const int hc = min(max(hi, 0), p.H - 1), wc = min(max(wi, 0), p.W - 1);      // a valid address in any case
+      ra[i] = *reinterpret_cast<const bf16x8*>(p.x + (((size_t)pix_b[i] * p.H + hc) * p.W + wc) * p.Cin + ci);
+      oka |= (unsigned)ok << i;
+    }
+#pragma unroll
+    for (int i = 0; i < B_PER; ++i) {
+      const int gn = n0 + r0 + i * ROWS_PER_PASS;
+      rb[i] = *reinterpret_cast<const bf16x8*>(p.w + (size_t)min(gn, p.N - 1) * p.K + min(gk, p.K - 8));
+      okb |= (unsigned)(gn < p.N && kok) << i;
+    }
+  };
+  auto store_lds = [&](int buf) {
+    bf16* as = As + buf * BM * LD;
+    bf16* bs = Bs + buf * BN * LD;
+#pragma unroll
+    for (int i = 0; i < A_PER; ++i)
+      *reinterpret_cast<bf16x8*>(as + (r0 + i * ROWS_PER_PASS) * LD + c8 * 8) = ((oka >> i) & 1) ? ra[i] : zero8();
+#pragma unroll
+    for (int i = 0; i < B_PER; ++i)
+      *reinterpret_cast<bf16x8*>(bs + (r0 + i * ROWS_PER_PASS) * LD + c8 * 8) = ((okb >> i) & 1) ? rb[i] : zero8();
+  };
+
+  f32x16 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  const int nkt = (p.K + BK - 1) / BK;
+  load_global(0);
+  store_lds(0);
+  __syncthreads();
+  for (int kt = 0; kt < nkt; ++kt) {
+    const int buf = kt & 1;
+    const bool more = kt + 1 < nkt;
+    if (more) load_global(kt + 1);
+    const bf16* as = As + buf * BM * LD;
+    const bf16* bs = Bs + buf * BN * LD;
+#pragma unroll
+    for (int ks = 0; ks < BK / 16; ++ks) {
+      bf16x8 fa[TM], fb[TN];
+#pragma unroll
+      for (int i = 0; i < TM; ++i) fa[i] = *reinterpret_cast<const bf16x8*>(as + (wm0 + i * 32 + l32) * LD + ks * 16 + 8 * g);
+#pragma unroll
+      for (int j = 0; j < TN; ++j) fb[j] = *reinterpret_cast<const bf16x8*>(bs + (wn0 + j * 32 + l32) * LD + ks * 16 + 8 * g);
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) acc[i][j] = mfma32(fa[i], fb[j], acc[i][j]);
+    }
+    if (more) store_lds(buf ^ 1);
+    __syncthreads();
+  }
+  // the operand tiles are dead past the last barrier: each wave reuses its slice of LDS for the epilogue
+  float* Cw = reinterpret_cast<float*>(smem_raw) + wave * 32 * S::C_LD;
+  wave_epilogue<TM, TN, WN, S::C_LD>(acc, Cw, p.epi, m0 + wm0, n0 + wn0, lane);
+}
+
+template <int BM, int BN, int WGM, int WGN>
+static int launch_conv_cfg(ConvParams& p, hipStream_t s) {
+  using S = ConvSmem<BM, BN, WGM, WGN>;
+  p.tiles_m = (p.M + BM - 1) / BM; p.tiles_n = (p.N + BN - 1) / BN;
+  // whole tile-rows per XCD: the tiles that share a band of input pixels run on one L2
+  const long n = (long)p.tiles_m * p.tiles_n, ppx = (n + 7) / 8;
+  p.group_m = (int)std::max<long>(1, std::min<long>((ppx + p.tiles_n / 2) / p.tiles_n, p.tiles_m));
+  auto kern = conv3x3_bf16_kernel<BM, BN, WGM, WGN>;
+  if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)S::BYTES) != hipSuccess)
+    return set_error(DP_EHIP, "hipFuncSetAttribute(conv) failed");
+  hipLaunchKernelGGL(kern, dim3((unsigned)n), dim3(WGM * WGN * 64), S::BYTES, s, p);
+  return hipGetLastError() == hipSuccess ? DP_OK : set_error(DP_EHIP, "conv launch failed");
+}
+
+int launch_conv3x3(const ConvArgs& a, hipStream_t s) {
+  if (a.dtype != BF16) return set_error(DP_EUNSUPPORTED, "conv3x3: bf16 storage only");
+  if (a.B <= 0 || a.H <= 0 || a.W <= 0 || a.Cin <= 0 || a.Cout <= 0) return set_error(DP_EINVAL, "conv3x3: non-positive size");
+  if (a.stride != 1 && a.stride != 2) return set_error(DP_EUNSUPPORTED, "conv3x3: stride must be 1 or 2");
+  if (a.Cin % 8 || a.Cout % 8) return set_error(DP_EUNSUPPORTED, "conv3x3: channel counts must be multiples of 8");
+  if (!a.x || !a.w || !a.y) return set_error(DP_EINVAL, "conv3x3: null operand");
+  const void* ps[] = {a.x, a.w, a.y, a.bias, a.residual};
+  for (const void* q : ps) if ((uintptr_t)q % 16) return set_error(DP_EALIGN, "conv3x3: operands must be 16-byte aligned");
+  const int Ho = (a.H - 1) / a.stride + 1, Wo = (a.W - 1) / a.stride + 1;
+  const long M = (long)a.B * Ho * Wo;
+  if (M >= (1L << 31) - 512 || (long)9 * a.Cin >= (1L << 24)) return set_error(DP_EUNSUPPORTED, "conv3x3: too many output pixels or input channels");
+  ConvParams p;
+  p.x = (const bf16*)a.x; p.w = (const bf16*)a.w;
+  p.H = a.H; p.W = a.W; p.Cin = a.Cin; p.Ho = Ho; p.Wo = Wo; p.stride = a.stride;
+  p.M = (int)M; p.N = a.Cout; p.K = 9 * a.Cin;
+  p.taps_uniform = a.Cin % 64 == 0;
+  EpiParams<bf16>& e = p.epi;
+  e.M = p.M; e.N = p.N; e.out = (bf16*)a.y; e.ldo = a.Cout;
+  e.out32 = nullptr; e.ldo32 = 0; e.accumulate = 0; e.partial = nullptr;
+  e.bias = (const bf16*)a.bias; e.pre_out = nullptr; e.ld_pre = 0; e.act = 0;
+  e.dact_pre = nullptr; e.ld_dact = 0; e.dact_kind = 0; e.gate = nullptr; e.gate_ld = 0; e.rows_per_batch = 1;
+  e.residual = a.residual; e.ld_res = a.Cout; e.residual_f32 = 0; e.out_fused_f32 = 0;
+  e.geglu = 0; e.geglu_inner = 0; e.geglu_u = nullptr; e.ld_geglu = 0;
+  const double by = 2.0 * ((double)a.B * a.H * a.W * a.Cin + (double)p.N * p.K + (double)M * a.Cout * (a.residual ? 2.0 : 1.0));
+  KScope ks(KK_CONV, 2.0 * (double)M * p.N * p.K, by, s, p.M, p.N, p.K);
+  if (a.Cout <= 64) return launch_conv_cfg<128, 64, 4, 1>(p, s);
+  if (M >= 256L * 256) return launch_conv_cfg<256, 128, 4, 2>(p, s);
+  return launch_conv_cfg<128, 128, 2, 2>(p, s);
+}
+
+}  // namespace dp

@@ -64,6 +64,33 @@ bool gemm_colsum_supported(const GemmArgs& a);
 size_t gemm_splitk_ws_bytes(int M, int N, int K);   // upper bound for out_f32 GEMMs
 size_t gemm_epi_splitk_ws_bytes(int M, int N, int K);   // same for storage-dtype outputs (0: such a GEMM is never split)
 
+// ---------------------------------------------------------------- convolution (frozen image encoder)
+// y[b, i, j, :] = sum_{u, v} x[b, i * stride + u - 1, j * stride + v - 1, :] w[:, 3u + v, :]^T + bias (+ residual),
+// zero padding 1.  Channels-last bf16 tensors: x [B, H, W, Cin], w [Cout, 9 * Cin] (taps row-major, channels
+// last), y and residual [B, Ho, Wo, Cout] with Ho = (H - 1) / stride + 1.  Cin, Cout multiples of 8.
+struct ConvArgs {
+  int dtype;
+  int B, H, W, Cin, Cout, stride;
+  const void* x; const void* w; const void* bias; const void* residual; void* y;
+};
+int launch_conv3x3(const ConvArgs& a, hipStream_t s);
+
+// GroupNorm over channels-last x [B, HW, C]: per (sample, group of C / groups consecutive channels) mean and
+// biased variance over the group's channels at all pixels; y = (x - mean) * rstd * gamma + beta, then SiLU
+// if silu != 0.  Three launches: per-block partial sums, their fixed-order combination (in double) into a
+// per-(sample, channel) scale and shift, and the elementwise pass.  scratch: fp32, gn_scratch_bytes().
+struct GroupNormArgs {
+  int dtype;
+  int B, HW, C, groups; float eps; int silu;
+  const void* x; const void* gamma; const void* beta; void* y;
+  float* scratch; size_t scratch_bytes;
+};
+size_t gn_scratch_bytes(int B, int HW, int C);
+int launch_groupnorm(const GroupNormArgs& a, hipStream_t s);
+
+// p[r, :] = softmax(scale * s[r, :]) for fp32 logits s [rows, cols] (dense), written in the storage dtype.
+int launch_softmax_rows(int dtype, const float* s, void* p, long rows, int cols, float scale, hipStream_t st);
+
 // ---------------------------------------------------------------- attention
 // Per (batch b, head h): O = softmax(Q K^T * scale [+ causal mask]) V.
 // Element (b, n, h, t) of X lives at X + (b * rows_X + n) * ld_X + h * d_head + t, so Q/K/V

@@ -4,6 +4,7 @@
 #include "../../include/dpipe.h"
 #include "dp_kernels.h"
 #include "dp_errors.h"
+#include "dp_host.h"
 
 #include <algorithm>
 #include <cmath>
@@ -27,24 +28,6 @@ int set_errorf(int code, const char* fmt, ...) {
   va_end(ap);
   return code;
 }
-
-#define DP_TRY(expr) do { int _e = (expr); if (_e != DP_OK) return _e; } while (0)
-
-static inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
-
-// Bump planner over the caller's workspace; the same code computes sizes (base = nullptr)
-// and pointers.
-struct Plan {
-  char* base; size_t off = 0;
-  explicit Plan(void* b) : base((char*)b) {}
-  void* take(size_t bytes) {
-    void* p = base ? base + off : nullptr;
-    off += align_up(bytes, 256);
-    return p;
-  }
-};
-
-struct ParamInfo { std::string name; int64_t rows, cols; };
 
 struct ProfileHooks {            // optional per-block event recording
   std::vector<hipEvent_t>* ev = nullptr;
@@ -594,12 +577,6 @@ static int dit_block_bwd(const dp_stage& s, const void* const* P, const void* co
 }
 
 // ============================================================ stage drivers
-static int check_ptr(const void* p, const char* what, size_t align = 16) {
-  if (!p) return set_errorf(DP_EINVAL, "%s is NULL", what);
-  if ((uintptr_t)p % align) return set_errorf(DP_EALIGN, "%s is not %zu-byte aligned", what, align);
-  return DP_OK;
-}
-
 static int check_stage_call(const dp_stage* s, const void* const* params, const void* a, const void* b, const void* c,
                             const void* ws, size_t ws_bytes, int save) {
   if (!s) return set_error(DP_EINVAL, "stage handle is NULL");
@@ -859,12 +836,6 @@ static int check_encoder_call(const dp_encoder* e, const void* const* params, co
   const size_t need = dp_encoder_workspace_bytes(e, n);
   if (ws_bytes < need) return set_errorf(DP_EWORKSPACE, "workspace too small: %zu bytes given, %zu needed", ws_bytes, need);
   return DP_OK;
-}
-
-static float median(std::vector<float>& v) {
-  std::sort(v.begin(), v.end());
-  const size_t n = v.size();
-  return n % 2 ? v[n / 2] : 0.5f * (v[n / 2 - 1] + v[n / 2]);
 }
 
 }  // namespace dp

@@ -100,6 +100,38 @@ class DeviceEncoder:
         return _dev_to_np(self.hidden)
 
 
+class DeviceImageEncoder:
+    """The frozen image encoder with its parameters, the image batch and the output buffer on the GPU."""
+
+    def __init__(self, cfg, inputs, device="cuda:0"):
+        self.cfg, self.device = cfg, device
+        self.enc = B.ImageEncoder(_dp_dtype(cfg.dtype), cfg.height, cfg.width, cfg.in_ch, cfg.groups, cfg.layers, cfg.gn_eps)
+        self.specs = self.enc.param_specs()
+        self.params = [_np_to_dev(inputs["params"][name], cfg.dtype, device) for name, _ in self.specs]
+        for (name, shape), p in zip(self.specs, self.params):
+            assert tuple(p.shape) == tuple(shape), (name, p.shape, shape)
+        self.gb, self.nl = cfg.global_batch, len(cfg.layers)
+        self.x = _np_to_dev(inputs["x"], cfg.dtype, device)
+        self.out = torch.zeros((self.gb,) + self.enc.layer_shape(self.nl - 1), dtype=_torch_dtype(cfg.dtype), device=device)
+        self.ws = torch.empty(max(self.enc.workspace_bytes(0, self.nl, self.gb), 256), dtype=torch.uint8, device=device)
+
+    def buffer(self, layer_end):
+        """A zeroed global-batch buffer for the output of layer layer_end - 1."""
+        return torch.zeros((self.gb,) + self.enc.layer_shape(layer_end - 1), dtype=self.out.dtype, device=self.device)
+
+    def run_slices(self, b, layer_begin=0, layer_end=None, src=None, dst=None):
+        """Cover the global batch with consecutive partial-batch calls of b samples."""
+        le = self.nl if layer_end is None else layer_end
+        src = self.x if src is None else src
+        dst = self.out if dst is None else dst
+        for off in range(0, self.gb, b):
+            self.enc.fwd_partial(self.params, src, dst, self.gb, layer_begin, le, off, min(b, self.gb - off), self.ws)
+        return dst
+
+    def output(self):
+        return _dev_to_np(self.out)
+
+
 def rel_err(gpu: np.ndarray, ref: np.ndarray) -> float:
     """max |gpu - ref| / max |ref| over one tensor (the tolerance metric of the parity tests)."""
     den = float(np.max(np.abs(ref)))

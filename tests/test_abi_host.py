@@ -118,3 +118,39 @@ def test_fusion_mask_range(dp):
 
 def test_last_error_is_never_null(dp):
     assert dp.load_library().dp_last_error() is not None
+
+
+# ------------------------------------------------------------------ image encoder (host side)
+def test_image_encoder_tables_and_shapes_agree_with_input_generator(dp):
+    from paper_2405_01248_amd import binding as B
+    for c in (si.CONFIG6, si.ImageEncoderConfig("t", "bf16", 16, 12, 8, 4, si.vae_encoder_layers(16, (1, 2), 8, 8), 3)):
+        enc = B.ImageEncoder(B.DP_BF16, c.height, c.width, c.in_ch, c.groups, c.layers, c.gn_eps)
+        assert enc.param_specs() == [(n, tuple(s)) for n, s, _ in si.image_encoder_param_specs(c)]
+        assert enc.layer_shape(-1) == (c.height, c.width, c.in_ch)
+        for l in range(len(c.layers)):
+            assert enc.layer_shape(l) == c.out_shape(l + 1)
+        nl = len(c.layers)
+        assert enc.workspace_bytes(0, nl, 4) > enc.workspace_bytes(0, nl, 1) > 0
+        assert enc.workspace_bytes(nl - 1, nl, 1) < enc.workspace_bytes(0, nl, 1)
+        assert enc.workspace_bytes(0, nl + 1, 1) == 0 and enc.workspace_bytes(2, 2, 1) == 0
+
+
+@pytest.mark.parametrize("layers, kw, code", [
+    ((("conv", 8, 16, 3),), {}, -1),                         # stride 3
+    ((("resnet", 8, 16, 2),), {}, -1),                       # only a plain convolution may stride
+    ((("conv", 16, 16, 1),), {}, -1),                        # c_in does not match the 8 input channels
+    ((("conv", 8, 12, 1),), {}, -2),                         # c_out not a multiple of 8
+    ((("conv", 8, 16, 1), ("attn", 16, 24, 1)), {}, -1),     # attention changes the width
+    ((("conv", 8, 24, 1), ("resnet", 24, 24, 1)), {"groups": 16}, -1),
+    ((("conv", 8, 16, 1),), {"in_ch": 3}, -2),               # unpadded RGB
+    ((("conv", 8, 16, 1),), {"dtype": 0}, -2),               # fp32 storage
+    ((("conv", 8, 16, 1),), {"gn_eps": 0.0}, -1),
+    ((("conv", 8, 16, 1), ("attn", 16, 16, 1)), {"height": 3, "width": 3}, -2),   # 9 pixels: not a multiple of 8
+])
+def test_bad_image_encoder_descriptors_are_rejected(dp, layers, kw, code):
+    from paper_2405_01248_amd import binding as B
+    a = dict(dtype=B.DP_BF16, height=8, width=8, in_ch=8, groups=4, gn_eps=1e-6)
+    a.update(kw)
+    with pytest.raises(B.DpipeError) as ei:
+        B.ImageEncoder(a["dtype"], a["height"], a["width"], a["in_ch"], a["groups"], layers, a["gn_eps"])
+    assert ei.value.code == code
