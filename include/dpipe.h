@@ -239,6 +239,8 @@ typedef struct {
   double p2p_gbps, p2p_latency_ms;   /* R_p2p, L_p2p */
   double ar_gbps, ar_latency_ms;     /* R_ar, L_ar */
   double self_cond_prob;             /* p; 0 = Eq. 1 alone */
+  int exact_stages;                  /* > 0: partition into exactly this many stages (one point of the search of Sec. 3,
+                                        dp_schedule_search); 0: the best stage count up to max_stages */
 } dp_partition_opts;
 typedef struct {
   int n_stages;
@@ -301,6 +303,42 @@ typedef struct {
 } dp_fill_summary;
 int dp_bubbles_fill(const dp_bubble* bubbles, int n_bubbles, const dp_layer_cost* rows, int n_rows, const int* dep_pairs,
                     int n_dep_pairs, int batch, int n_devices, dp_fill* fills, int max_fills, dp_fill_summary* summary);
+
+/* Search over the pipeline hyper-parameters (Sec. 3, workflow steps 2-5; Table "Pipeline training
+ * hyper-parameters": S stages, M micro-batches, D devices per pipeline-parallel group, world size = D x
+ * data-parallel degree), host only.  For every D of group_sizes that divides world_size, every M of
+ * micro_batch_counts and every S = 1..min(L, D, max_stages): a pipeline group trains training_batch * D /
+ * world_size samples per iteration in M micro-batches of B samples (combinations where these are not
+ * integers are skipped); the backbone (rows of component 0) is partitioned into exactly S stages
+ * (dp_partition_solve; skipped when infeasible); the FIFO-1F1B iteration of that plan is simulated
+ * (dp_bubbles_1f1b) with per-stage forward time (1 + p) sum P^f at the stage's local batch B / r, backward
+ * time sum P^b, transfers C / R_p2p + L_p2p between stages and the gradient synchronisation sum G / R_ar +
+ * L_ar (Eq. 4) after a stage's last backward; its bubbles (at least min_bubble_ms long) are filled with the
+ * non-trainable components (rows of component >= 1; dp_bubbles_fill with the group's batch and D devices;
+ * dep_pairs as there).  iteration_ms = pipeline_ms + leftover_ms (the frozen layers that fit no bubble, run
+ * after the pipeline on the group's devices).  Candidates are written in the order walked (group_sizes, then
+ * micro_batch_counts, then S ascending); *best is the index of the least iteration_ms, the earlier one on
+ * ties.  *n_cands is the number of feasible combinations, also when it exceeds max_cands (DP_EWORKSPACE; the
+ * first max_cands are written and *best refers to them).  DP_EUNSUPPORTED when no combination is feasible. */
+typedef struct {
+  int world_size, training_batch;
+  const int* group_sizes; int n_group_sizes;                 /* candidate D [host] */
+  const int* micro_batch_counts; int n_micro_batch_counts;   /* candidate M [host] */
+  int max_stages;                                            /* 0: up to min(L, D) */
+  int uniform_replication;
+  double p2p_gbps, p2p_latency_ms, ar_gbps, ar_latency_ms, self_cond_prob;
+  double min_bubble_ms;
+  const int* dep_pairs; int n_dep_pairs;
+} dp_search_opts;
+typedef struct {
+  int n_stages, n_micro_batches, group_size, micro_batch;    /* S, M, D, B */
+  double pipeline_ms, leftover_ms, iteration_ms;
+  double bubble_ratio;           /* idle device-time / (D x pipeline_ms), before filling */
+  double bubble_ratio_filled;    /* unfilled idle device-time / (D x iteration_ms) */
+  dp_partition_plan plan;
+} dp_search_candidate;
+int dp_schedule_search(const dp_layer_cost* rows, int n_rows, const dp_search_opts* opts, dp_search_candidate* cands, int max_cands,
+                       int* n_cands, int* best);
 
 /* Operator-level entry points: the same kernels the stage calls, exposed one by one for unit
  * tests and per-kernel measurement (the cost profile of Sec. 4 is per layer; these go one

@@ -56,6 +56,7 @@ class Options:
     self_cond_prob: float = 0.0      # p of Sec. 4.3 (0: Eq. 1 alone)
     max_stages: int = 0              # 0: up to min(L, D)
     uniform_replication: bool = False  # every stage on the same number of devices (the paper's evaluation setting)
+    exact_stages: int = 0            # S fixed (one point of the hyper-parameter search of Sec. 3); 0: best S up to max_stages
 
 
 @dataclass
@@ -117,7 +118,9 @@ def solve(prof: Profile, o: Options) -> Plan:
     s_max = min(L, D) if o.max_stages <= 0 else min(L, D, o.max_stages)
     tf = feedback_ms(prof, o)
     best = Plan()
-    for S in range(1, s_max + 1):
+    for S in ([o.exact_stages] if o.exact_stages > 0 else range(1, s_max + 1)):
+        if S > s_max:
+            break
         # table[(l, s, r, d)] = (W, W_sc, Y, parent key or None)
         table = {}
         for d in range(1, D + 1):
@@ -187,7 +190,9 @@ def brute_force(prof: Profile, o: Options):
     L, D = prof.n_layers, o.n_devices
     s_max = min(L, D) if o.max_stages <= 0 else min(L, D, o.max_stages)
     best = (math.inf, None, None)
-    for S in range(1, s_max + 1):
+    for S in ([o.exact_stages] if o.exact_stages > 0 else range(1, s_max + 1)):
+        if S > s_max:
+            break
         for inner in itertools.combinations(range(1, L), S - 1):
             cuts = (0,) + inner
             for reps in itertools.product(range(1, D + 1), repeat=S):

@@ -56,13 +56,27 @@ DP_MAX_STAGES = 64
 
 class PartitionOpts(C.Structure):
     _fields_ = [(n, C.c_int) for n in ("micro_batch", "n_micro_batches", "n_devices", "max_stages", "uniform_replication")] + \
-               [(n, C.c_double) for n in ("p2p_gbps", "p2p_latency_ms", "ar_gbps", "ar_latency_ms", "self_cond_prob")]
+               [(n, C.c_double) for n in ("p2p_gbps", "p2p_latency_ms", "ar_gbps", "ar_latency_ms", "self_cond_prob")] + [("exact_stages", C.c_int)]
 
 
 class PartitionPlan(C.Structure):
     _fields_ = [("n_stages", C.c_int), ("first_layer", C.c_int * DP_MAX_STAGES), ("n_layers", C.c_int * DP_MAX_STAGES),
                 ("replicas", C.c_int * DP_MAX_STAGES)] + \
                [(n, C.c_double) for n in ("t0_ms", "t0_sc_ms", "gap_ms", "tf_ms", "t_max_ms")]
+
+
+class SearchOpts(C.Structure):
+    _fields_ = [("world_size", C.c_int), ("training_batch", C.c_int), ("group_sizes", C.POINTER(C.c_int)), ("n_group_sizes", C.c_int),
+                ("micro_batch_counts", C.POINTER(C.c_int)), ("n_micro_batch_counts", C.c_int), ("max_stages", C.c_int),
+                ("uniform_replication", C.c_int)] + \
+               [(n, C.c_double) for n in ("p2p_gbps", "p2p_latency_ms", "ar_gbps", "ar_latency_ms", "self_cond_prob", "min_bubble_ms")] + \
+               [("dep_pairs", C.POINTER(C.c_int)), ("n_dep_pairs", C.c_int)]
+
+
+class SearchCandidate(C.Structure):
+    _fields_ = [(n, C.c_int) for n in ("n_stages", "n_micro_batches", "group_size", "micro_batch")] + \
+               [(n, C.c_double) for n in ("pipeline_ms", "leftover_ms", "iteration_ms", "bubble_ratio", "bubble_ratio_filled")] + \
+               [("plan", PartitionPlan)]
 
 
 class Bubble(C.Structure):
@@ -91,7 +105,7 @@ EXPORTS = ["dp_stage_create", "dp_stage_destroy", "dp_stage_set_overlap", "dp_st
            "dp_encoder_profile", "dp_image_encoder_create", "dp_image_encoder_destroy", "dp_image_encoder_param_count",
            "dp_image_encoder_param_shape", "dp_image_encoder_layer_shape", "dp_image_encoder_workspace_bytes", "image_encoder_fwd_partial",
            "dp_image_encoder_profile", "dp_ktime_begin", "dp_ktime_end", "dp_ktime_event_overhead_ms", "dp_last_error", "dp_op_gemm", "dp_op_gemm_static", "dp_op_gemm_workspace_bytes",
-           "dp_op_attention_fwd", "dp_op_attention_bwd", "dp_partition_solve", "dp_bubbles_1f1b", "dp_bubbles_fill"]
+           "dp_op_attention_fwd", "dp_op_attention_bwd", "dp_partition_solve", "dp_bubbles_1f1b", "dp_bubbles_fill", "dp_schedule_search"]
 
 
 def library_path() -> str:
@@ -145,6 +159,7 @@ def load_library():
     dptr = C.POINTER(C.c_double)
     lib.dp_bubbles_1f1b.argtypes = [i, dptr, dptr, C.POINTER(i), i, dptr, dptr, dptr, C.c_double, C.POINTER(Bubble), i, C.POINTER(i), dptr]
     lib.dp_bubbles_fill.argtypes = [C.POINTER(Bubble), i, C.POINTER(LayerCost), i, C.POINTER(i), i, i, i, C.POINTER(FillRow), i, C.POINTER(FillSummary)]
+    lib.dp_schedule_search.argtypes = [C.POINTER(LayerCost), i, C.POINTER(SearchOpts), C.POINTER(SearchCandidate), i, C.POINTER(i), C.POINTER(i)]
     lib.dp_ktime_begin.argtypes = [i]
     lib.dp_ktime_event_overhead_ms.restype = C.c_float
     lib.dp_ktime_end.argtypes = [C.POINTER(KernelTime), i, C.POINTER(i)]
@@ -338,7 +353,7 @@ def ktime_event_overhead_ms() -> float:
 
 
 def partition_solve(rows, micro_batch, n_micro_batches, n_devices, p2p_gbps, p2p_latency_ms, ar_gbps, ar_latency_ms,
-                    self_cond_prob=0.0, max_stages=0, uniform_replication=False):
+                    self_cond_prob=0.0, max_stages=0, uniform_replication=False, exact_stages=0):
     """rows: sequence of LayerCost or of dicts with its fields (host data).  Returns a dict with the plan."""
     arr = (LayerCost * len(rows))()
     for i, r in enumerate(rows):
@@ -346,7 +361,7 @@ def partition_solve(rows, micro_batch, n_micro_batches, n_devices, p2p_gbps, p2p
         for n, _ in LayerCost._fields_:
             setattr(arr[i], n, d[n])
     opts = PartitionOpts(micro_batch, n_micro_batches, n_devices, max_stages, int(uniform_replication), p2p_gbps, p2p_latency_ms,
-                         ar_gbps, ar_latency_ms, self_cond_prob)
+                         ar_gbps, ar_latency_ms, self_cond_prob, exact_stages)
     plan = PartitionPlan()
     lib = load_library()
     _check(lib.dp_partition_solve(arr, len(rows), C.byref(opts), C.byref(plan)))
@@ -354,6 +369,38 @@ def partition_solve(rows, micro_batch, n_micro_batches, n_devices, p2p_gbps, p2p
     return {"n_stages": n, "first_layer": list(plan.first_layer[:n]), "n_layers": list(plan.n_layers[:n]),
             "replicas": list(plan.replicas[:n]), "t0_ms": plan.t0_ms, "t0_sc_ms": plan.t0_sc_ms, "gap_ms": plan.gap_ms,
             "tf_ms": plan.tf_ms, "t_max_ms": plan.t_max_ms}
+
+
+def _rows_array(rows):
+    arr = (LayerCost * len(rows))()
+    for i, r in enumerate(rows):
+        d = r if isinstance(r, dict) else r.as_dict()
+        for n, _ in LayerCost._fields_:
+            setattr(arr[i], n, d[n])
+    return arr
+
+
+def schedule_search(rows, world_size, training_batch, group_sizes, micro_batch_counts, p2p_gbps, p2p_latency_ms, ar_gbps, ar_latency_ms,
+                    self_cond_prob=0.0, max_stages=0, uniform_replication=True, min_bubble_ms=0.0, deps=(), max_cands=4096):
+    """Returns (list of candidate dicts in walking order, index of the best)."""
+    gs = (C.c_int * len(group_sizes))(*group_sizes)
+    ms = (C.c_int * len(micro_batch_counts))(*micro_batch_counts)
+    flat = [x for pair in deps for x in pair]
+    dp = (C.c_int * max(len(flat), 1))(*flat)
+    opts = SearchOpts(world_size, training_batch, gs, len(group_sizes), ms, len(micro_batch_counts), max_stages, int(uniform_replication),
+                      p2p_gbps, p2p_latency_ms, ar_gbps, ar_latency_ms, self_cond_prob, min_bubble_ms, dp, len(deps))
+    cands = (SearchCandidate * max_cands)()
+    n, best = C.c_int(0), C.c_int(-1)
+    _check(load_library().dp_schedule_search(_rows_array(rows), len(rows), C.byref(opts), cands, max_cands, C.byref(n), C.byref(best)))
+    out = []
+    for k in range(n.value):
+        c = cands[k]
+        ns = c.plan.n_stages
+        out.append({"n_stages": c.n_stages, "n_micro_batches": c.n_micro_batches, "group_size": c.group_size, "micro_batch": c.micro_batch,
+                    "pipeline_ms": c.pipeline_ms, "leftover_ms": c.leftover_ms, "iteration_ms": c.iteration_ms, "bubble_ratio": c.bubble_ratio,
+                    "bubble_ratio_filled": c.bubble_ratio_filled, "first_layer": list(c.plan.first_layer[:ns]),
+                    "n_layers": list(c.plan.n_layers[:ns]), "replicas": list(c.plan.replicas[:ns]), "t_max_ms": c.plan.t_max_ms})
+    return out, best.value
 
 
 def _darr(v):

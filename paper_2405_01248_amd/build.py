@@ -8,7 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libdpipe.so")
-SOURCES = ["gemm.hip", "attention.hip", "elementwise.hip", "stage.hip", "ktime.hip", "partition.hip", "bubbles.hip", "noalloc.hip", "conv.hip", "image_encoder.hip"]
+SOURCES = ["gemm.hip", "attention.hip", "elementwise.hip", "stage.hip", "ktime.hip", "partition.hip", "bubbles.hip", "noalloc.hip", "conv.hip", "image_encoder.hip", "search.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 

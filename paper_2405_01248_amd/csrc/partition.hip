@@ -44,8 +44,8 @@ extern "C" int dp_partition_solve(const dp_layer_cost* rows, int n_rows, const d
   using dp::set_error;
   if (!rows || n_rows <= 0 || !opts || !plan) return set_error(DP_EINVAL, "dp_partition_solve: null argument");
   const dp_partition_opts& o = *opts;
-  if (o.micro_batch <= 0 || o.n_micro_batches <= 0 || o.n_devices <= 0 || o.n_devices > DP_MAX_STAGES || o.max_stages < 0)
-    return set_error(DP_EINVAL, "dp_partition_solve: micro_batch, n_micro_batches > 0; 1 <= n_devices <= DP_MAX_STAGES; max_stages >= 0");
+  if (o.micro_batch <= 0 || o.n_micro_batches <= 0 || o.n_devices <= 0 || o.n_devices > DP_MAX_STAGES || o.max_stages < 0 || o.exact_stages < 0)
+    return set_error(DP_EINVAL, "dp_partition_solve: micro_batch, n_micro_batches > 0; 1 <= n_devices <= DP_MAX_STAGES; max_stages, exact_stages >= 0");
   if (!(o.p2p_gbps > 0.0) || !(o.ar_gbps > 0.0) || o.p2p_latency_ms < 0.0 || o.ar_latency_ms < 0.0 || o.self_cond_prob < 0.0 ||
       o.self_cond_prob > 1.0)
     return set_error(DP_EINVAL, "dp_partition_solve: bandwidths > 0, latencies >= 0, 0 <= self_cond_prob <= 1");
@@ -121,7 +121,7 @@ extern "C" int dp_partition_solve(const dp_layer_cost* rows, int n_rows, const d
   best.n_stages = 0;
   auto idx = [&](int s, int d, int r, int l) { return (((size_t)(s - 1) * (D + 1) + d) * (D + 1) + r) * (L + 1) + l; };
   std::vector<State> tab;
-  for (int S = 1; S <= s_max; ++S) {
+  for (int S = o.exact_stages > 0 ? o.exact_stages : 1; S <= (o.exact_stages > 0 ? std::min(o.exact_stages, s_max) : s_max); ++S) {
     tab.assign((size_t)S * (D + 1) * (D + 1) * (L + 1), State{0, 0, 0, -1, -1, false});
     for (int d = 1; d <= D; ++d)
       for (int l = 1; l <= L; ++l) {

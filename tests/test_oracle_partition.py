@@ -116,3 +116,23 @@ def test_uniform_backbone_closed_forms():
     plan = P.solve(prof1, o1)
     assert plan.replicas == [1, 1, 1] and sorted(plan.n_layers) == [2, 3, 3]
     assert plan.t_max_ms == pytest.approx((6 + 2 * 3 - 2) * 3 * 2 * c)
+
+
+@pytest.mark.parametrize("seed", range(10))
+def test_exact_stage_count_against_brute_force_over_that_count(seed):
+    # the point (S, M, D) of the hyper-parameter search (Sec. 3): S is given, not chosen
+    rng = random.Random(300 + seed)
+    L, D = rng.randint(3, 6), rng.randint(2, 4)
+    prof = make_profile(L, [12, 6, 4, 3], rng, bwd=False, grads=False, comm_scale=rng.choice([0.1, 5.0]))
+    for S in range(1, min(L, D) + 1):
+        o = P.Options(micro_batch=12, n_micro_batches=rng.randint(1, 8), n_devices=D, ar_latency_ms=0.0, exact_stages=S)
+        plan, bf = P.solve(prof, o), P.brute_force(prof, o)
+        if bf[1] is None:
+            assert plan.n_stages == 0
+            continue
+        assert plan.n_stages == S == len(bf[1]) and plan.t_max_ms == pytest.approx(bf[0], rel=1e-12)
+    # the unrestricted programme takes the best of the exact ones
+    o = P.Options(micro_batch=12, n_micro_batches=4, n_devices=D, ar_latency_ms=0.0)
+    exact = [P.solve(prof, P.Options(micro_batch=12, n_micro_batches=4, n_devices=D, ar_latency_ms=0.0, exact_stages=S)).t_max_ms
+             for S in range(1, min(L, D) + 1)]
+    assert P.solve(prof, o).t_max_ms == pytest.approx(min(exact), rel=1e-12)
