@@ -250,6 +250,28 @@ typedef struct {
 } dp_partition_plan;
 int dp_partition_solve(const dp_layer_cost* rows, int n_rows, const dp_partition_opts* opts, dp_partition_plan* plan);
 
+/* Two backbones of a cascaded model trained on the same devices, pipelined in opposite directions (Sec. 4.2,
+ * Eq. 10-16), host only.  rows_down / rows_up: the cost profiles of the two backbones (rows of component 0 of
+ * each array).  Both backbones are cut into the same number S of stages; position i of the device chain (low
+ * rank first) holds stage i of the down backbone and stage S - 1 - i of the up backbone, both replicated on
+ * the same replicas[i] devices.  State (l_d, l_u, s, r, d): the first l_d layers of the down backbone and the
+ * last l_u layers of the up backbone in s stages on devices 1..d (the text words the sub-problem the other
+ * way round; the two labelings are mirror images); W = max over both backbones' stages of T_0(s) with the
+ * communication time of Eq. 3 doubled, Y likewise of T_0^{S-C}(s); the plan minimises (M_CDM + 2S - 2) W + Y
+ * (Eq. 12, 13) with M_CDM = opts->n_micro_batches (the paper gives M_CDM no formula).  opts->self_cond_prob
+ * must be 0; max_stages, exact_stages and uniform_replication as in dp_partition_solve.  first_layer_up is in
+ * the up backbone's own layer numbering.  DP_EUNSUPPORTED when nothing is feasible or the problem is too
+ * large (stages x devices^3 x (layers_down x layers_up)^2 > 1.6e10; at most 256 layers per backbone). */
+typedef struct {
+  int n_stages;
+  int first_layer_down[DP_MAX_STAGES], n_layers_down[DP_MAX_STAGES], first_layer_up[DP_MAX_STAGES], n_layers_up[DP_MAX_STAGES],
+      replicas[DP_MAX_STAGES];
+  double t0_ms, gap_ms;     /* T_0,CDM (Eq. 10) and T_0,CDM^{S-C} (Eq. 11) of the chosen partition */
+  double t_max_ms;          /* Eq. 12 */
+} dp_bidir_plan;
+int dp_partition_solve_bidirectional(const dp_layer_cost* rows_down, int n_down, const dp_layer_cost* rows_up, int n_up,
+                                     const dp_partition_opts* opts, dp_bidir_plan* plan);
+
 /* Pipeline bubbles and their filling (Sec. 5, Algorithms 1 and 2), host only: no GPU call is made.
  *
  * dp_bubbles_1f1b simulates one iteration of the FIFO-1F1B schedule of n_stages stages and

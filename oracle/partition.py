@@ -21,6 +21,15 @@ T_S - T_C is clamped at zero (a synchronisation that ends inside the compensatio
 window adds nothing to the bound); ties are broken towards the earlier candidate in
 the loop order (fewer stages, smaller r, smaller l, smaller r').
 
+Sec. 4.2 (two backbones of a cascaded model, pipelined in opposite directions over the same devices):
+`solve_bidirectional`, Eq. 10-16.  Readings: the text names the sub-problem's layers "the last L_d and the
+first L_u"; with the down pipeline entering the device chain at rank 1 (its definition of "down"), the
+devices 1..d hold the FIRST layers of the down backbone and the LAST layers of the up backbone, which is
+what the state below holds (the two labelings are mirror images of one another).  M_CDM ("the number of
+paired forward and backward stages between the down and up pipelines") is given no formula: it is an input
+(n_micro_batches).  Both backbones are cut into the same number of stages; a chain position holds one
+stage of each, replicated on the same r devices; self-conditioning is not combined with it.
+
 Units: times in ms, sizes in bytes, bandwidths in GB/s (1e9 bytes per second).
 """
 from __future__ import annotations
@@ -201,4 +210,140 @@ def brute_force(prof: Profile, o: Options):
                 sc = score(prof, o, cuts, reps)
                 if sc is not None and sc[3] < best[0]:
                     best = (sc[3], cuts, reps)
+    return best
+
+
+# ------------------------------------------------------------------ two backbones, bidirectional pipelining (Sec. 4.2)
+@dataclass
+class BidirPlan:
+    n_stages: int = 0
+    first_layer_down: list = field(default_factory=list)   # per position along the device chain, low rank first
+    n_layers_down: list = field(default_factory=list)
+    first_layer_up: list = field(default_factory=list)     # in the up backbone's own layer numbering
+    n_layers_up: list = field(default_factory=list)
+    replicas: list = field(default_factory=list)
+    t0_ms: float = math.inf          # W = T_0,CDM (Eq. 10)
+    gap_ms: float = math.inf         # Y = T_0,CDM^{S-C} (Eq. 11)
+    t_max_ms: float = math.inf       # Eq. 12
+
+
+def bidir_stage_terms(prof: Profile, o: Options, lo: int, hi: int, r: int, incoming):
+    """(T_0(s), T_0^{S-C}(s)) of one backbone's stage [lo, hi) on r devices as in Eq. 3-6, with the
+    communication time doubled (Sec. 4.2: the two directions compete for the links).  `incoming` is the
+    index of the layer boundary the stage receives its input over, or None for the backbone's first stage."""
+    if o.micro_batch % r:
+        return None
+    b = o.micro_batch // r
+    if b not in prof.fwd_ms:
+        return None
+    pf, pb = sum(prof.fwd_ms[b][lo:hi]), sum(prof.bwd_ms[b][lo:hi])
+    comm = 0.0
+    if incoming is not None:
+        comm = 2.0 * (_ms(prof.cf_bytes[b][incoming] + prof.cb_bytes[b][incoming], o.p2p_gbps) + 2 * o.p2p_latency_ms)
+    ts = _ms(sum(prof.grad_bytes[lo:hi]), o.ar_gbps) + o.ar_latency_ms
+    return max(pf + pb, comm), max(ts - pb, 0.0)
+
+
+def _bidir_pair(down: Profile, up: Profile, o: Options, ld0: int, ld1: int, lu0: int, lu1: int, r: int):
+    """Terms of the device group that holds down layers [ld0, ld1) and, counted from the END of the up
+    backbone, its layers [lu0, lu1) (the up pipeline enters the chain at the other end, so the low-rank
+    devices hold its last layers): (max T_0, max T_0^{S-C}) over the two stages."""
+    td = bidir_stage_terms(down, o, ld0, ld1, r, ld0 - 1 if ld0 > 0 else None)
+    Lu = up.n_layers
+    a, b = Lu - lu1, Lu - lu0                       # the same stage in the up backbone's own numbering
+    tu = bidir_stage_terms(up, o, a, b, r, a - 1 if a > 0 else None)
+    if td is None or tu is None:
+        return None
+    return max(td[0], tu[0]), max(td[1], tu[1])
+
+
+def solve_bidirectional(down: Profile, up: Profile, o: Options) -> BidirPlan:
+    """Eq. 13-16: state (l_d, l_u, s, r, d) = the first l_d layers of the down backbone and the last l_u
+    layers of the up backbone in s stages on devices 1..d, the stage pair at the high-rank end on r devices.
+    o.n_micro_batches is M_CDM.  One run per total stage count S; a state keeps the (W, Y) of the candidate
+    with the least (M_CDM + 2S - 2) W + Y."""
+    Ld, Lu, D = down.n_layers, up.n_layers, o.n_devices
+    s_cap = min(Ld, Lu, D) if o.max_stages <= 0 else min(Ld, Lu, D, o.max_stages)
+    best = BidirPlan()
+    for S in ([o.exact_stages] if o.exact_stages > 0 else range(1, s_cap + 1)):
+        if S > s_cap:
+            break
+        obj = lambda w, y: (o.n_micro_batches + 2 * S - 2) * w + y
+        table = {}
+        for d in range(1, D + 1):
+            for ld in range(1, Ld + 1):
+                for lu in range(1, Lu + 1):
+                    t = _bidir_pair(down, up, o, 0, ld, 0, lu, d)
+                    if t is not None:
+                        table[(ld, lu, 1, d, d)] = (t[0], t[1], None)
+        for s in range(2, S + 1):
+            for d in range(s, D + 1):
+                for r in range(1, d - (s - 1) + 1):
+                    for ld in range(s, Ld + 1):
+                        for lu in range(s, Lu + 1):
+                            pick = None
+                            for pd in range(s - 1, ld):              # Eq. 16: l_d, l_u, r'
+                                for pu in range(s - 1, lu):
+                                    t = _bidir_pair(down, up, o, pd, ld, pu, lu, r)
+                                    if t is None:
+                                        continue
+                                    for rp in range(1, d - r + 1):
+                                        if o.uniform_replication and rp != r:
+                                            continue
+                                        sub = table.get((pd, pu, s - 1, rp, d - r))
+                                        if sub is None:
+                                            continue
+                                        w, y = max(sub[0], t[0]), max(sub[1], t[1])      # Eq. 14, 15
+                                        if pick is None or obj(w, y) < pick[0]:
+                                            pick = (obj(w, y), w, y, (pd, pu, s - 1, rp, d - r))
+                            if pick is not None:
+                                table[(ld, lu, s, r, d)] = pick[1:]
+        for r in range(1, D + 1):                                    # Eq. 13
+            st = table.get((Ld, Lu, S, r, D))
+            if st is None or obj(st[0], st[1]) >= best.t_max_ms:
+                continue
+            plan = BidirPlan(n_stages=S, t0_ms=st[0], gap_ms=st[1], t_max_ms=obj(st[0], st[1]))
+            key, stages = (Ld, Lu, S, r, D), []
+            while key is not None:
+                parent = table[key][2]
+                pd, pu = (parent[0], parent[1]) if parent is not None else (0, 0)
+                stages.append((pd, key[0] - pd, Lu - key[1], key[1] - pu, key[3]))
+                key = parent
+            stages.reverse()
+            plan.first_layer_down = [x[0] for x in stages]; plan.n_layers_down = [x[1] for x in stages]
+            plan.first_layer_up = [x[2] for x in stages]; plan.n_layers_up = [x[3] for x in stages]
+            plan.replicas = [x[4] for x in stages]
+            best = plan
+    return best
+
+
+def score_bidirectional(down: Profile, up: Profile, o: Options, cuts_down, cuts_up_from_end, replicas):
+    """(W, Y, T_max) of an explicit pair of partitions from the definitions (Eq. 10-12): cuts_down = first
+    down layer of every chain position, cuts_up_from_end = the same for the up backbone counted from its end."""
+    S = len(replicas)
+    bd, bu = list(cuts_down) + [down.n_layers], list(cuts_up_from_end) + [up.n_layers]
+    w = y = 0.0
+    for i in range(S):
+        t = _bidir_pair(down, up, o, bd[i], bd[i + 1], bu[i], bu[i + 1], replicas[i])
+        if t is None:
+            return None
+        w, y = max(w, t[0]), max(y, t[1])
+    return w, y, (o.n_micro_batches + 2 * S - 2) * w + y
+
+
+def brute_force_bidirectional(down: Profile, up: Profile, o: Options):
+    Ld, Lu, D = down.n_layers, up.n_layers, o.n_devices
+    s_cap = min(Ld, Lu, D) if o.max_stages <= 0 else min(Ld, Lu, D, o.max_stages)
+    best = (math.inf, None, None, None)
+    for S in ([o.exact_stages] if o.exact_stages > 0 else range(1, s_cap + 1)):
+        if S > s_cap:
+            break
+        for cd in itertools.combinations(range(1, Ld), S - 1):
+            for cu in itertools.combinations(range(1, Lu), S - 1):
+                for reps in itertools.product(range(1, D + 1), repeat=S):
+                    if sum(reps) != D or (o.uniform_replication and len(set(reps)) != 1):
+                        continue
+                    sc = score_bidirectional(down, up, o, (0,) + cd, (0,) + cu, reps)
+                    if sc is not None and sc[2] < best[0]:
+                        best = (sc[2], (0,) + cd, (0,) + cu, reps)
     return best

@@ -65,6 +65,12 @@ class PartitionPlan(C.Structure):
                [(n, C.c_double) for n in ("t0_ms", "t0_sc_ms", "gap_ms", "tf_ms", "t_max_ms")]
 
 
+class BidirPlan(C.Structure):
+    _fields_ = [("n_stages", C.c_int)] + [(n, C.c_int * DP_MAX_STAGES) for n in ("first_layer_down", "n_layers_down", "first_layer_up",
+                                                                                   "n_layers_up", "replicas")] + \
+               [(n, C.c_double) for n in ("t0_ms", "gap_ms", "t_max_ms")]
+
+
 class SearchOpts(C.Structure):
     _fields_ = [("world_size", C.c_int), ("training_batch", C.c_int), ("group_sizes", C.POINTER(C.c_int)), ("n_group_sizes", C.c_int),
                 ("micro_batch_counts", C.POINTER(C.c_int)), ("n_micro_batch_counts", C.c_int), ("max_stages", C.c_int),
@@ -105,7 +111,7 @@ EXPORTS = ["dp_stage_create", "dp_stage_destroy", "dp_stage_set_overlap", "dp_st
            "dp_encoder_profile", "dp_image_encoder_create", "dp_image_encoder_destroy", "dp_image_encoder_param_count",
            "dp_image_encoder_param_shape", "dp_image_encoder_layer_shape", "dp_image_encoder_workspace_bytes", "image_encoder_fwd_partial",
            "dp_image_encoder_profile", "dp_ktime_begin", "dp_ktime_end", "dp_ktime_event_overhead_ms", "dp_last_error", "dp_op_gemm", "dp_op_gemm_static", "dp_op_gemm_workspace_bytes",
-           "dp_op_attention_fwd", "dp_op_attention_bwd", "dp_partition_solve", "dp_bubbles_1f1b", "dp_bubbles_fill", "dp_schedule_search"]
+           "dp_op_attention_fwd", "dp_op_attention_bwd", "dp_partition_solve", "dp_partition_solve_bidirectional", "dp_bubbles_1f1b", "dp_bubbles_fill", "dp_schedule_search"]
 
 
 def library_path() -> str:
@@ -159,6 +165,7 @@ def load_library():
     dptr = C.POINTER(C.c_double)
     lib.dp_bubbles_1f1b.argtypes = [i, dptr, dptr, C.POINTER(i), i, dptr, dptr, dptr, C.c_double, C.POINTER(Bubble), i, C.POINTER(i), dptr]
     lib.dp_bubbles_fill.argtypes = [C.POINTER(Bubble), i, C.POINTER(LayerCost), i, C.POINTER(i), i, i, i, C.POINTER(FillRow), i, C.POINTER(FillSummary)]
+    lib.dp_partition_solve_bidirectional.argtypes = [C.POINTER(LayerCost), i, C.POINTER(LayerCost), i, C.POINTER(PartitionOpts), C.POINTER(BidirPlan)]
     lib.dp_schedule_search.argtypes = [C.POINTER(LayerCost), i, C.POINTER(SearchOpts), C.POINTER(SearchCandidate), i, C.POINTER(i), C.POINTER(i)]
     lib.dp_ktime_begin.argtypes = [i]
     lib.dp_ktime_event_overhead_ms.restype = C.c_float
@@ -378,6 +385,19 @@ def _rows_array(rows):
         for n, _ in LayerCost._fields_:
             setattr(arr[i], n, d[n])
     return arr
+
+
+def partition_solve_bidirectional(rows_down, rows_up, micro_batch, n_paired_micro_batches, n_devices, p2p_gbps, p2p_latency_ms, ar_gbps,
+                                  ar_latency_ms, max_stages=0, uniform_replication=False, exact_stages=0):
+    opts = PartitionOpts(micro_batch, n_paired_micro_batches, n_devices, max_stages, int(uniform_replication), p2p_gbps, p2p_latency_ms,
+                         ar_gbps, ar_latency_ms, 0.0, exact_stages)
+    plan = BidirPlan()
+    _check(load_library().dp_partition_solve_bidirectional(_rows_array(rows_down), len(rows_down), _rows_array(rows_up), len(rows_up),
+                                                           C.byref(opts), C.byref(plan)))
+    n = plan.n_stages
+    out = {k: list(getattr(plan, k)[:n]) for k in ("first_layer_down", "n_layers_down", "first_layer_up", "n_layers_up", "replicas")}
+    out.update(n_stages=n, t0_ms=plan.t0_ms, gap_ms=plan.gap_ms, t_max_ms=plan.t_max_ms)
+    return out
 
 
 def schedule_search(rows, world_size, training_batch, group_sizes, micro_batch_counts, p2p_gbps, p2p_latency_ms, ar_gbps, ar_latency_ms,

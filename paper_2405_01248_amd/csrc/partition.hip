@@ -172,3 +172,159 @@ extern "C" int dp_partition_solve(const dp_layer_cost* rows, int n_rows, const d
   *plan = best;
   return DP_OK;
 }
+
+
+// ------------------------------------------------------------------ two backbones, bidirectional pipelining (Sec. 4.2, Eq. 10-16)
+namespace {
+
+struct Rows {                                      // one backbone's profile: batch -> rows by layer
+  std::map<int, std::vector<const dp_layer_cost*>> by_batch;
+  int L = 0;
+};
+
+int collect_rows(const dp_layer_cost* rows, int n_rows, Rows& out, const char* who) {
+  using dp::set_errorf;
+  for (int i = 0; i < n_rows; ++i)
+    if (rows[i].component == 0) {
+      if (rows[i].layer < 0 || rows[i].batch <= 0) return set_errorf(DP_EINVAL, "%s: bad layer or batch in a row", who);
+      out.L = std::max(out.L, rows[i].layer + 1);
+    }
+  if (out.L == 0) return set_errorf(DP_EINVAL, "%s: no rows of component 0", who);
+  if (out.L > 256) return set_errorf(DP_EUNSUPPORTED, "%s: more than 256 layers", who);
+  for (int i = 0; i < n_rows; ++i) {
+    if (rows[i].component != 0) continue;
+    auto& v = out.by_batch[rows[i].batch];
+    if (v.empty()) v.assign(out.L, nullptr);
+    if (v[rows[i].layer]) return set_errorf(DP_EINVAL, "%s: duplicate (layer, batch) row", who);
+    if (!(rows[i].fwd_ms >= 0.f) || !(rows[i].bwd_ms >= 0.f) || rows[i].cf_bytes < 0 || rows[i].cb_bytes < 0 || rows[i].grad_bytes < 0)
+      return set_errorf(DP_EINVAL, "%s: negative or NaN cost in a row", who);
+    v[rows[i].layer] = &rows[i];
+  }
+  for (auto& kv : out.by_batch)
+    for (const dp_layer_cost* r : kv.second)
+      if (!r) return set_errorf(DP_EINVAL, "%s: a batch size lacks rows for some layers", who);
+  return DP_OK;
+}
+
+struct PairTerms { double t0, gap; bool ok; };
+
+// (T_0, T_0^{S-C}) of every stage [lo, hi) of one backbone at replication r, communication time doubled
+void fill_bidir_terms(const Rows& R, const dp_partition_opts& o, int r, std::vector<PairTerms>& t) {
+  const int L = R.L;
+  t.assign((size_t)(L + 1) * (L + 1), PairTerms{0, 0, false});
+  if (o.micro_batch % r) return;
+  auto it = R.by_batch.find(o.micro_batch / r);
+  if (it == R.by_batch.end()) return;
+  const auto& lay = it->second;
+  for (int lo = 0; lo < L; ++lo) {
+    double pf = 0.0, pbk = 0.0, g = 0.0, comm = 0.0;
+    if (lo > 0) comm = 2.0 * (bytes_ms((double)lay[lo - 1]->cf_bytes + (double)lay[lo - 1]->cb_bytes, o.p2p_gbps) + 2 * o.p2p_latency_ms);
+    for (int hi = lo + 1; hi <= L; ++hi) {
+      pf += (double)lay[hi - 1]->fwd_ms; pbk += (double)lay[hi - 1]->bwd_ms; g += (double)lay[hi - 1]->grad_bytes;
+      PairTerms& x = t[(size_t)lo * (L + 1) + hi];
+      x.t0 = std::max(pf + pbk, comm);
+      x.gap = std::max(bytes_ms(g, o.ar_gbps) + o.ar_latency_ms - pbk, 0.0);
+      x.ok = true;
+    }
+  }
+}
+
+struct BState { double w, y; int pd, pu, pr; bool ok; };
+
+}  // namespace
+
+extern "C" int dp_partition_solve_bidirectional(const dp_layer_cost* rows_down, int n_down, const dp_layer_cost* rows_up, int n_up,
+                                                const dp_partition_opts* opts, dp_bidir_plan* plan) {
+  using dp::set_error;
+  if (!rows_down || n_down <= 0 || !rows_up || n_up <= 0 || !opts || !plan) return set_error(DP_EINVAL, "dp_partition_solve_bidirectional: null argument");
+  const dp_partition_opts& o = *opts;
+  if (o.micro_batch <= 0 || o.n_micro_batches <= 0 || o.n_devices <= 0 || o.n_devices > DP_MAX_STAGES || o.max_stages < 0 || o.exact_stages < 0)
+    return set_error(DP_EINVAL, "dp_partition_solve_bidirectional: micro_batch, n_micro_batches > 0; 1 <= n_devices <= DP_MAX_STAGES; max_stages, exact_stages >= 0");
+  if (!(o.p2p_gbps > 0.0) || !(o.ar_gbps > 0.0) || o.p2p_latency_ms < 0.0 || o.ar_latency_ms < 0.0)
+    return set_error(DP_EINVAL, "dp_partition_solve_bidirectional: bandwidths > 0, latencies >= 0");
+  if (o.self_cond_prob != 0.0) return set_error(DP_EUNSUPPORTED, "dp_partition_solve_bidirectional: self-conditioning is not combined with bidirectional pipelining");
+  try {
+    Rows Rd, Ru;
+    if (int e = collect_rows(rows_down, n_down, Rd, "dp_partition_solve_bidirectional (down)")) return e;
+    if (int e = collect_rows(rows_up, n_up, Ru, "dp_partition_solve_bidirectional (up)")) return e;
+    const int Ld = Rd.L, Lu = Ru.L, D = o.n_devices;
+    const int s_cap = std::min(std::min(std::min(Ld, Lu), D), o.max_stages > 0 ? o.max_stages : DP_MAX_STAGES);
+    // work ~ S x D^3 x (Ld Lu)^2 / 4, memory ~ S x D^2 x Ld Lu states
+    const double work = (double)s_cap * D * D * D * (double)Ld * Ld * Lu * Lu / 4.0, mem = (double)s_cap * (D + 1) * (D + 1) * (Ld + 1) * (Lu + 1);
+    if (work > 4e9 || mem > 5e7) return set_error(DP_EUNSUPPORTED, "dp_partition_solve_bidirectional: problem too large (stages x devices^3 x (layers_down x layers_up)^2 > 1.6e10)");
+    std::vector<std::vector<PairTerms>> td(D), tu(D);
+    for (int r = 1; r <= D; ++r) { fill_bidir_terms(Rd, o, r, td[r - 1]); fill_bidir_terms(Ru, o, r, tu[r - 1]); }
+    // the chain position holding down layers [d0, d1) and the up layers [u0, u1) counted from the up backbone's end
+    auto pair = [&](int r, int d0, int d1, int u0, int u1, double& t0, double& gap) {
+      const PairTerms& a = td[r - 1][(size_t)d0 * (Ld + 1) + d1];
+      const PairTerms& b = tu[r - 1][(size_t)(Lu - u1) * (Lu + 1) + (Lu - u0)];
+      if (!a.ok || !b.ok) return false;
+      t0 = std::max(a.t0, b.t0); gap = std::max(a.gap, b.gap);
+      return true;
+    };
+    const double inf = std::numeric_limits<double>::infinity();
+    double best_val = inf;
+    dp_bidir_plan best;
+    best.n_stages = 0;
+    std::vector<BState> tab;
+    for (int S = o.exact_stages > 0 ? o.exact_stages : 1; S <= (o.exact_stages > 0 ? std::min(o.exact_stages, s_cap) : s_cap); ++S) {
+      auto idx = [&](int s, int d, int r, int ld, int lu) { return ((((size_t)(s - 1) * (D + 1) + d) * (D + 1) + r) * (Ld + 1) + ld) * (Lu + 1) + lu; };
+      auto obj = [&](double w, double y) { return (o.n_micro_batches + 2 * S - 2) * w + y; };
+      tab.assign((size_t)S * (D + 1) * (D + 1) * (Ld + 1) * (Lu + 1), BState{0, 0, -1, -1, -1, false});
+      for (int d = 1; d <= D; ++d)
+        for (int ld = 1; ld <= Ld; ++ld)
+          for (int lu = 1; lu <= Lu; ++lu) {
+            double t0, gap;
+            if (pair(d, 0, ld, 0, lu, t0, gap)) tab[idx(1, d, d, ld, lu)] = BState{t0, gap, -1, -1, -1, true};
+          }
+      for (int s = 2; s <= S; ++s)
+        for (int d = s; d <= D; ++d)
+          for (int r = 1; r <= d - (s - 1); ++r)
+            for (int ld = s; ld <= Ld; ++ld)
+              for (int lu = s; lu <= Lu; ++lu) {
+                BState pick{0, 0, -1, -1, -1, false};
+                double pick_val = inf;
+                for (int pd = s - 1; pd < ld; ++pd)                       // Eq. 16
+                  for (int pu = s - 1; pu < lu; ++pu) {
+                    double t0, gap;
+                    if (!pair(r, pd, ld, pu, lu, t0, gap)) continue;
+                    for (int rp = 1; rp <= d - r; ++rp) {
+                      if (o.uniform_replication && rp != r) continue;
+                      const BState& sub = tab[idx(s - 1, d - r, rp, pd, pu)];
+                      if (!sub.ok) continue;
+                      const double w = std::max(sub.w, t0), y = std::max(sub.y, gap);   // Eq. 14, 15
+                      const double val = obj(w, y);
+                      if (!pick.ok || val < pick_val) { pick = BState{w, y, pd, pu, rp, true}; pick_val = val; }
+                    }
+                  }
+                if (pick.ok) tab[idx(s, d, r, ld, lu)] = pick;
+              }
+      for (int r = 1; r <= D; ++r) {                                      // Eq. 13
+        const BState& st = tab[idx(S, D, r, Ld, Lu)];
+        if (!st.ok) continue;
+        const double val = obj(st.w, st.y);
+        if (val < best_val) {
+          best_val = val;
+          best.n_stages = S; best.t0_ms = st.w; best.gap_ms = st.y; best.t_max_ms = val;
+          int s = S, d = D, rr = r, ld = Ld, lu = Lu;
+          while (s >= 1) {
+            const BState& cur = tab[idx(s, d, rr, ld, lu)];
+            const int pd = s > 1 ? cur.pd : 0, pu = s > 1 ? cur.pu : 0;
+            best.first_layer_down[s - 1] = pd; best.n_layers_down[s - 1] = ld - pd;
+            best.first_layer_up[s - 1] = Lu - lu; best.n_layers_up[s - 1] = lu - pu;
+            best.replicas[s - 1] = rr;
+            const int nd = d - rr, nr = cur.pr;
+            ld = pd; lu = pu; d = nd; rr = nr; --s;
+          }
+        }
+      }
+    }
+    if (best.n_stages == 0) return set_error(DP_EUNSUPPORTED, "dp_partition_solve_bidirectional: no feasible partition (micro_batch / replicas must be a profiled batch size of both backbones)");
+    for (int i = best.n_stages; i < DP_MAX_STAGES; ++i)
+      best.first_layer_down[i] = best.n_layers_down[i] = best.first_layer_up[i] = best.n_layers_up[i] = best.replicas[i] = 0;
+    *plan = best;
+  } catch (...) {
+    return set_error(DP_EINVAL, "dp_partition_solve_bidirectional: out of host memory");
+  }
+  return DP_OK;
+}
