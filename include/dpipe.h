@@ -150,14 +150,21 @@ typedef struct {
 
 /* Times every block's forward and backward (reps >= 1 repetitions each, hipEvents on the
  * stream; this call synchronises).  Same buffers as stage_fwd / stage_bwd; dparams are
- * overwritten.  Writes n_blocks rows. */
+ * overwritten.  Writes n_blocks rows.  The passes run as stage_fwd / stage_bwd run them, side stream included
+ * (dp_stage_set_overlap), but the caller's stream waits for a block's side-stream work before the next block's
+ * time stamp: a block's weight-gradient kernels are charged to that block, and sum_l (P^f_l + P^b_l) is the
+ * time of the step up to what the per-block joins cost (Eq. 3 adds layer times up).  Two things are charged
+ * to a neighbour: the context K/V projections of all U-Net blocks (issued at the start of the forward, in
+ * block 0's span) and a block's weight transposes (issued one block ahead in the backward). */
 int dp_stage_profile(dp_stage* st, const void* const* params, const void* x, const void* ctx_or_cond, void* y,
                      const void* dy, void* dx, void* d_cond, void* const* dparams, void* workspace,
                      size_t workspace_bytes, int reps, dp_layer_cost* rows, int max_rows, int* n_rows,
                      void* hip_stream);
 
-/* Times every encoder layer at each requested partial-batch size (samples [0, b)).
- * Writes (n_layers + 2) * n_batches rows. */
+/* Times every encoder layer at each requested partial-batch size (samples [0, b)), in the launch sequence of
+ * an ordinary encoder_fwd_partial call over all layers: where a layer's last reduction pass also computes
+ * the LayerNorm that opens the next layer (or the final one), that work is charged to the earlier layer and
+ * the final LayerNorm's own row can be (almost) empty.  Writes (n_layers + 2) * n_batches rows. */
 int dp_encoder_profile(dp_encoder* enc, const void* const* params, const int32_t* ids, void* hidden,
                        int global_batch, const int* batches, int n_batches, int reps, void* workspace,
                        size_t workspace_bytes, dp_layer_cost* rows, int max_rows, int* n_rows, void* hip_stream);

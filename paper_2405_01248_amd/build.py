@@ -8,7 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libdpipe.so")
-SOURCES = ["gemm.hip", "attention.hip", "elementwise.hip", "stage.hip", "ktime.hip", "partition.hip", "bubbles.hip", "noalloc.hip", "conv.hip", "image_encoder.hip", "search.hip"]
+SOURCES = ["gemm.hip", "attention.hip", "elementwise.hip", "stage.hip", "ktime.hip", "partition.hip", "bubbles.hip", "noalloc.hip", "conv.hip", "image_encoder.hip", "search.hip", "errors.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 
@@ -45,6 +45,24 @@ def _wait(procs, verbose):
             raise RuntimeError(f"hipcc failed on {src}")
         if verbose and out.strip():
             print(out)
+
+
+# The sources that make no GPU call (partitioner, bubble filler, schedule search, error message): they also
+# compile as plain C++, which is how the sanitizer build of the tests takes them.
+HOST_ONLY_SOURCES = ["partition.hip", "bubbles.hip", "search.hip", "errors.hip"]
+
+
+def build_host_sanitized(driver_cpp: str, out_path: str) -> str:
+    """Builds `driver_cpp` together with the host-only sources as one executable under AddressSanitizer and
+    UndefinedBehaviorSanitizer (g++; no GPU code is involved)."""
+    cxx = os.environ.get("CXX", "g++")
+    cmd = [cxx, "-std=c++17", "-O1", "-g", "-fno-omit-frame-pointer", "-fsanitize=address,undefined", "-fno-sanitize-recover=undefined",
+           "-Wall", driver_cpp]
+    for src in HOST_ONLY_SOURCES:
+        cmd += ["-x", "c++", os.path.join(CSRC, src)]
+    cmd += ["-o", out_path]
+    subprocess.run(cmd, check=True)
+    return out_path
 
 
 if __name__ == "__main__":

@@ -4,7 +4,7 @@
 // and cuts the idle time into bubbles (start, end, idle devices).  dp_bubbles_fill walks the bubbles in
 // chronological order; for each it lists the whole-batch candidates of the ready components (Algorithm 2),
 // extends every candidate by at most one partial-batch layer with the largest regular sample count that
-// fits (Algorithm 1), and keeps the longest.  A layer begun on part of the batch stays the first ready layer
+// fits (Algorithm 1), and keeps the longest.  The candidates are walked by an odometer over prefix-time tables.  A layer begun on part of the batch stays the first ready layer
 // of its component and counts as a whole-batch layer on the remaining samples.  No device code here.
 #include "../../include/dpipe.h"
 #include "dp_errors.h"
@@ -63,35 +63,66 @@ double full_time(const std::vector<Comp>& cs, const State& st, int i, int j, int
   return layer_time(cs[i], st.u[i] + j, ceil_div(n, d));
 }
 
-// Algorithm 2
-void ffc(const std::vector<Comp>& cs, const State& st, const std::vector<int>& ready, double t_b, int d, size_t pos,
-         std::vector<int>& prefix, std::vector<std::vector<int>>& out) {
-  const int i = ready[pos];
-  double t = 0.0;
-  int k0 = 0;
-  while (st.u[i] + k0 < cs[i].n_layers && t + full_time(cs, st, i, k0, d) <= t_b) { t += full_time(cs, st, i, k0, d); ++k0; }
-  if (pos + 1 == ready.size()) {
-    prefix.push_back(k0); out.push_back(prefix); prefix.pop_back();
-    return;
+// Whole-batch packings of a bubble, the candidate set of Algorithm 2: the layer counts (k_0 .. k_{n-1}) of the
+// ready components whose summed whole-batch time fits the bubble, every component before the last one walked from
+// its largest feasible count down to zero (for the time its predecessors leave) and the last one always at its
+// largest count.  Instead of recursing, an odometer runs over per-component tables of prefix times: digit x counts
+// layers of component x; after a visit the right-most non-zero digit (the last one excepted) is decreased and the
+// digits to its right are reset to their maxima for the new remainder -- the same order as the recursive listing,
+// which matters because the first of several equally long candidates is kept.
+struct PrefixTimes { std::vector<double> t; };     // t[k] = time of the component's first k unfinished layers, whole batch
+
+std::vector<PrefixTimes> prefix_times(const std::vector<Comp>& cs, const State& st, const std::vector<int>& ready, int d) {
+  std::vector<PrefixTimes> out(ready.size());
+  for (size_t x = 0; x < ready.size(); ++x) {
+    const int i = ready[x], left = cs[i].n_layers - st.u[i];
+    out[x].t.assign(1, 0.0);
+    for (int j = 0; j < left; ++j) out[x].t.push_back(out[x].t.back() + full_time(cs, st, i, j, d));
   }
-  for (int k = k0; k >= 0; --k) {
-    double used = 0.0;
-    for (int h = 0; h < k; ++h) used += full_time(cs, st, i, h, d);
-    prefix.push_back(k);
-    ffc(cs, st, ready, t_b - used, d, pos + 1, prefix, out);
-    prefix.pop_back();
+  return out;
+}
+
+// largest k whose prefix time fits the budget (prefix times are non-decreasing)
+inline int largest_fit(const PrefixTimes& p, double budget) {
+  int k = 0;
+  while (k + 1 < (int)p.t.size() && p.t[k + 1] <= budget) ++k;
+  return k;
+}
+
+constexpr long kMaxPackings = 1000000;   // a bubble with more candidates than this is refused, not enumerated
+
+// Calls visit(k) for every packing; false if there are more than kMaxPackings.
+template <class Visit>
+bool for_each_packing(const std::vector<PrefixTimes>& tab, double t_b, Visit visit) {
+  const int n = (int)tab.size();
+  std::vector<int> k(n, 0);
+  std::vector<double> budget(n, 0.0);
+  budget[0] = t_b;
+  k[0] = largest_fit(tab[0], t_b);
+  long count = 0;
+  for (int from = 0;;) {
+    for (int x = from; x + 1 < n; ++x) {
+      budget[x + 1] = budget[x] - tab[x].t[k[x]];
+      k[x + 1] = largest_fit(tab[x + 1], budget[x + 1]);
+    }
+    if (++count > kMaxPackings) return false;
+    visit(k);
+    int x = n - 2;
+    while (x >= 0 && k[x] == 0) --x;
+    if (x < 0) return true;
+    --k[x];
+    from = x;
   }
 }
 
-struct Pick { std::vector<int> k; int ph = -1, player = -1, pb = 0; double t = -1.0; bool ok = false; };
+struct Pick { std::vector<int> k; int ph = -1, player = -1, pb = 0; double t = -1.0; bool ok = false; bool too_many = false; };
 
-// Algorithm 1
+// Algorithm 1: every packing, alone or extended by one partial-batch layer (the next layer of one ready component
+// on the largest regular sample count that still fits); the candidate that runs longest wins, the first on ties.
 Pick fill_one(const std::vector<Comp>& cs, const State& st, const std::vector<int>& ready, double t_b, int d) {
-  std::vector<std::vector<int>> K;
-  std::vector<int> prefix;
-  ffc(cs, st, ready, t_b, d, 0, prefix, K);
+  const std::vector<PrefixTimes> tab = prefix_times(cs, st, ready, d);
   Pick best;
-  for (const auto& k : K) {
+  const bool all = for_each_packing(tab, t_b, [&](const std::vector<int>& k) {
     double t_full = 0.0;
     for (size_t x = 0; x < ready.size(); ++x)
       for (int j = 0; j < k[x]; ++j) t_full += full_time(cs, st, ready[x], j, d);
@@ -109,13 +140,14 @@ Pick fill_one(const std::vector<Comp>& cs, const State& st, const std::vector<in
       const double t = t_full + layer_time(cs[h], layer, b_best / d);
       if (t > best.t) { best.k = k; best.ph = h; best.player = layer; best.pb = b_best; best.t = t; }
     }
-  }
+  });
+  best.too_many = !all;
   return best;
 }
 
 }  // namespace
 
-extern "C" int dp_bubbles_1f1b(int n_stages, const double* fwd_ms, const double* bwd_ms, const int* replicas, int n_micro_batches,
+static int bubbles_1f1b_impl(int n_stages, const double* fwd_ms, const double* bwd_ms, const int* replicas, int n_micro_batches,
                                const double* comm_fwd_ms, const double* comm_bwd_ms, const double* tail_ms, double min_ms,
                                dp_bubble* out, int max_out, int* n_out, double* iteration_ms) {
   if (!fwd_ms || !bwd_ms || !replicas || !n_out || (max_out > 0 && !out)) return set_error(DP_EINVAL, "dp_bubbles_1f1b: null argument");
@@ -199,7 +231,7 @@ extern "C" int dp_bubbles_1f1b(int n_stages, const double* fwd_ms, const double*
   return DP_OK;
 }
 
-extern "C" int dp_bubbles_fill(const dp_bubble* bubbles, int n_bubbles, const dp_layer_cost* rows, int n_rows, const int* dep_pairs,
+static int bubbles_fill_impl(const dp_bubble* bubbles, int n_bubbles, const dp_layer_cost* rows, int n_rows, const int* dep_pairs,
                                int n_dep_pairs, int batch, int n_devices, dp_fill* fills, int max_fills, dp_fill_summary* summary) {
   if ((n_bubbles > 0 && !bubbles) || !rows || n_rows <= 0 || !summary || (max_fills > 0 && !fills) || (n_dep_pairs > 0 && !dep_pairs))
     return set_error(DP_EINVAL, "dp_bubbles_fill: null argument");
@@ -258,6 +290,7 @@ extern "C" int dp_bubbles_fill(const dp_bubble* bubbles, int n_bubbles, const dp
     }
     if (ready.empty()) continue;
     const Pick p = fill_one(cs, st, ready, len, bub.n_devices);
+    if (p.too_many) return set_error(DP_EUNSUPPORTED, "dp_bubbles_fill: a bubble has more than a million whole-batch packings");
     if (!p.ok || !(p.t > 0.0)) continue;
     for (size_t x = 0; x < ready.size(); ++x) {
       const int i = ready[x];
@@ -278,4 +311,26 @@ extern "C" int dp_bubbles_fill(const dp_bubble* bubbles, int n_bubbles, const dp
   *summary = sum;
   if (n > max_fills) return set_error(DP_EWORKSPACE, "dp_bubbles_fill: more fill rows than max_fills (summary.n_fills holds the count)");
   return DP_OK;
+}
+
+
+// No C++ exception crosses the C boundary: an allocation failure becomes an error code.
+extern "C" int dp_bubbles_1f1b(int n_stages, const double* fwd_ms, const double* bwd_ms, const int* replicas, int n_micro_batches,
+                               const double* comm_fwd_ms, const double* comm_bwd_ms, const double* tail_ms, double min_ms, dp_bubble* out,
+                               int max_out, int* n_out, double* iteration_ms) {
+  try {
+    return bubbles_1f1b_impl(n_stages, fwd_ms, bwd_ms, replicas, n_micro_batches, comm_fwd_ms, comm_bwd_ms, tail_ms, min_ms, out, max_out, n_out,
+                             iteration_ms);
+  } catch (...) {
+    return set_error(DP_EINVAL, "dp_bubbles_1f1b: out of host memory");
+  }
+}
+
+extern "C" int dp_bubbles_fill(const dp_bubble* bubbles, int n_bubbles, const dp_layer_cost* rows, int n_rows, const int* dep_pairs,
+                               int n_dep_pairs, int batch, int n_devices, dp_fill* fills, int max_fills, dp_fill_summary* summary) {
+  try {
+    return bubbles_fill_impl(bubbles, n_bubbles, rows, n_rows, dep_pairs, n_dep_pairs, batch, n_devices, fills, max_fills, summary);
+  } catch (...) {
+    return set_error(DP_EINVAL, "dp_bubbles_fill: out of host memory");
+  }
 }

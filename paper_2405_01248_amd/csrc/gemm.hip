@@ -15,6 +15,7 @@
 #include "dp_gemm_epilogue.h"
 
 #include <algorithm>
+#include <atomic>
 #include <cmath>
 
 namespace dp {
@@ -839,11 +840,11 @@ static int launch_bf16_cfg(const GemmArgs& a, hipStream_t s) {
   dim3 grid(p.tiles_m * p.tiles_n, 1, splits);
   const size_t smem = S::BYTES;
   auto kern = gemm_bf16_kernel<BM, BN, BK, WGM, WGN, A_MC, B_MC>;
-  static bool attr_set = false;
-  if (!attr_set) {
+  static std::atomic<bool> attr_set{false};   // setting it twice is harmless; the flag only saves the call
+  if (!attr_set.load(std::memory_order_acquire)) {
     if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) != hipSuccess)
       return set_error(DP_EHIP, "hipFuncSetAttribute(gemm) failed");
-    attr_set = true;
+    attr_set.store(true, std::memory_order_release);
   }
   {
     // the timing scope brackets the GEMM kernel alone (the split-K reduction is its own class)
@@ -889,11 +890,11 @@ static int launch_dtl_cfg(const GemmArgs& a, hipStream_t s) {
   dim3 grid(p.tiles_m * p.tiles_n, 1, splits);
   const size_t smem = S::BYTES;
   auto kern = gemm_bf16_dtl_kernel<BM, BN, BK, STAGES, WGM, WGN, A_MC, B_MC>;
-  static bool attr_set = false;
-  if (!attr_set) {
+  static std::atomic<bool> attr_set{false};   // setting it twice is harmless; the flag only saves the call
+  if (!attr_set.load(std::memory_order_acquire)) {
     if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) != hipSuccess)
       return set_error(DP_EHIP, "hipFuncSetAttribute(gemm) failed");
-    attr_set = true;
+    attr_set.store(true, std::memory_order_release);
   }
   {
     // the timing scope brackets the GEMM kernel alone (the split-K reduction is its own class)
@@ -937,11 +938,11 @@ static int launch_dtl16(const GemmArgs& a, hipStream_t s) {
   p.b_bytes = (uint32_t)operand_extent_bytes(a.N, a.K, a.ldb);
   p.k_tiles_per_split = a.K / 64;
   auto kern = gemm_bf16_dtl16_kernel<BM, BN, 3, WGM, WGN>;
-  static bool attr_set = false;
-  if (!attr_set) {
+  static std::atomic<bool> attr_set{false};   // setting it twice is harmless; the flag only saves the call
+  if (!attr_set.load(std::memory_order_acquire)) {
     if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)S::BYTES) != hipSuccess)
       return set_error(DP_EHIP, "hipFuncSetAttribute(gemm) failed");
-    attr_set = true;
+    attr_set.store(true, std::memory_order_release);
   }
   KScope ks(KK_GEMM_NT, 2.0 * a.M * a.N * a.K, gemm_tensor_bytes(a), s, a.M, a.N, a.K);
   hipLaunchKernelGGL(kern, dim3(p.tiles_m * p.tiles_n), dim3(WGM * WGN * 64), S::BYTES, s, p);

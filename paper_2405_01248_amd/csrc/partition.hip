@@ -40,7 +40,18 @@ struct State { double w, w_sc, y; int parent_l, parent_r; bool ok; };
 
 }  // namespace
 
+static int partition_solve_impl(const dp_layer_cost* rows, int n_rows, const dp_partition_opts* opts, dp_partition_plan* plan);
+
+// No C++ exception crosses the C boundary: an allocation failure becomes an error code.
 extern "C" int dp_partition_solve(const dp_layer_cost* rows, int n_rows, const dp_partition_opts* opts, dp_partition_plan* plan) {
+  try {
+    return partition_solve_impl(rows, n_rows, opts, plan);
+  } catch (...) {
+    return dp::set_error(DP_EINVAL, "dp_partition_solve: out of host memory");
+  }
+}
+
+static int partition_solve_impl(const dp_layer_cost* rows, int n_rows, const dp_partition_opts* opts, dp_partition_plan* plan) {
   using dp::set_error;
   if (!rows || n_rows <= 0 || !opts || !plan) return set_error(DP_EINVAL, "dp_partition_solve: null argument");
   const dp_partition_opts& o = *opts;
@@ -76,7 +87,9 @@ extern "C" int dp_partition_solve(const dp_layer_cost* rows, int n_rows, const d
 
   const int D = o.n_devices;
   const int s_max = std::min(std::min(L, D), o.max_stages > 0 ? o.max_stages : DP_MAX_STAGES);
-  if ((double)s_max * D * D * L > 64e6) return set_error(DP_EUNSUPPORTED, "dp_partition_solve: problem too large (stages x devices^2 x layers > 64M)");
+  // what is allocated (stage terms: D x (L + 1)^2 entries; states: S x D^2 x L) and what is looped over (S^2 x D^3 x L^2 / 4)
+  if ((double)s_max * D * D * L > 64e6 || (double)D * (L + 1) * (L + 1) > 8e6 || (double)s_max * s_max * D * D * D * L * L / 4.0 > 2e10)
+    return set_error(DP_EUNSUPPORTED, "dp_partition_solve: problem too large (stages x devices^2 x layers > 64M, devices x layers^2 > 8M, or stages^2 x devices^3 x layers^2 > 8e10)");
 
   double tf = 0.0;                                        // T_F = O_L(B) / R_p2p + L_p2p   (Sec. 4.3)
   if (o.self_cond_prob > 0.0) {

@@ -16,21 +16,23 @@
 
 namespace dp {
 
-static thread_local char g_err[512] = "";
-int set_error(int code, const char* msg) {
-  snprintf(g_err, sizeof(g_err), "%s", msg);
-  return code;
-}
-int set_errorf(int code, const char* fmt, ...) {
-  va_list ap;
-  va_start(ap, fmt);
-  vsnprintf(g_err, sizeof(g_err), fmt, ap);
-  va_end(ap);
-  return code;
-}
-
 struct ProfileHooks {            // optional per-block event recording
   std::vector<hipEvent_t>* ev = nullptr;
+};
+
+// Timing events of the profile entry points, destroyed on every way out.
+struct EventSet {
+  std::vector<hipEvent_t> ev;
+  int create(size_t n) {
+    ev.reserve(n);
+    for (size_t i = 0; i < n; ++i) {
+      hipEvent_t e;
+      if (hipEventCreate(&e) != hipSuccess) return set_error(DP_EHIP, "hipEventCreate failed");
+      ev.push_back(e);
+    }
+    return DP_OK;
+  }
+  ~EventSet() { for (auto& e : ev) (void)hipEventDestroy(e); }
 };
 
 }  // namespace dp
@@ -794,15 +796,17 @@ static int encoder_run(const dp_encoder& e, const void* const* params, const int
     DP_TRY(mark(l));
     DP_TRY(launch_cast_to_f32(dt, x, w.res, (size_t)R * d, st));
     // A layer's last reduction pass may also compute the LayerNorm that follows it (the next layer's first, or
-    // the final one straight into `hidden`); not while layers are being timed one by one.
+    // the final one straight into `hidden`), also while layers are being timed one by one: the cost profile
+    // then describes the launch sequence of an ordinary call, with a folded LayerNorm charged to the layer
+    // whose reduction pass computes it.
     bool h_ready = false;
     for (; l < tl_end; ++l) {
       if (l != (lb == 0 ? 1 : lb)) DP_TRY(mark(l));
       const void* const* P = params + 2 + (size_t)(l - 1) * E_PER_LAYER;
       const void *ng = nullptr, *nb = nullptr;
       void* nout = nullptr;
-      if (!ev && l + 1 < tl_end) { ng = P[E_PER_LAYER + E_LN1_G]; nb = P[E_PER_LAYER + E_LN1_B]; nout = w.h; }
-      else if (!ev && l == nl && final_ln) { ng = params[2 + (size_t)nl * E_PER_LAYER]; nb = params[2 + (size_t)nl * E_PER_LAYER + 1]; nout = x; }
+      if (l + 1 < tl_end) { ng = P[E_PER_LAYER + E_LN1_G]; nb = P[E_PER_LAYER + E_LN1_B]; nout = w.h; }
+      else if (l == nl && final_ln) { ng = params[2 + (size_t)nl * E_PER_LAYER]; nb = params[2 + (size_t)nl * E_PER_LAYER + 1]; nout = x; }
       bool done = false;
       DP_TRY(encoder_block(e, P, w.res, n, w, st, h_ready, ng, nb, nout, &done));
       h_ready = done && l + 1 < tl_end;
@@ -810,6 +814,7 @@ static int encoder_run(const dp_encoder& e, const void* const* params, const int
     }
     if (!final_ln) DP_TRY(launch_cast_from_f32(dt, w.res, x, (size_t)R * d, st));
   }
+  if (final_ln && final_done) DP_TRY(mark(nl + 1));     // folded into the last layer's reduction pass: its own span is empty
   if (final_ln && !final_done) {
     DP_TRY(mark(nl + 1));
     const void* const* P = params + 2 + (size_t)nl * E_PER_LAYER;
@@ -843,7 +848,6 @@ static int check_encoder_call(const dp_encoder* e, const void* const* params, co
 // ============================================================ extern "C"
 extern "C" {
 
-const char* dp_last_error(void) { return dp::g_err; }
 
 int dp_stage_create(const dp_stage_desc* desc, dp_stage** out) {
   if (!desc || !out) return set_error(DP_EINVAL, "dp_stage_create: NULL argument");
@@ -1014,10 +1018,10 @@ int dp_stage_profile(dp_stage* st, const void* const* params, const void* x, con
   const int nb = st->d.n_blocks;
   if (reps < 1 || max_rows < nb) return set_error(DP_EINVAL, "dp_stage_profile: reps < 1 or too few rows");
   hipStream_t s = (hipStream_t)hip_stream;
-  std::vector<hipEvent_t> ef(nb + 1), eb(nb + 1);
-  for (auto* v : {&ef, &eb})
-    for (auto& e : *v)
-      if (hipEventCreate(&e) != hipSuccess) return set_error(DP_EHIP, "hipEventCreate failed");
+  EventSet esf, esb;
+  DP_TRY(esf.create(nb + 1)); DP_TRY(esb.create(nb + 1));
+  std::vector<hipEvent_t>& ef = esf.ev;
+  std::vector<hipEvent_t>& eb = esb.ev;
   std::vector<std::vector<float>> tf(nb), tb(nb);
   int rc = DP_OK;
   for (int r = 0; r < reps && rc == DP_OK; ++r) {
@@ -1035,8 +1039,6 @@ int dp_stage_profile(dp_stage* st, const void* const* params, const void* x, con
       tb[b].push_back(ms);
     }
   }
-  for (auto* v : {&ef, &eb})
-    for (auto& e : *v) (void)hipEventDestroy(e);
   if (rc != DP_OK) return rc;
   const int64_t act = (int64_t)st->T * st->d.d_model * st->es;
   for (int b = 0; b < nb; ++b) {
@@ -1062,9 +1064,9 @@ int dp_encoder_profile(dp_encoder* enc, const void* const* params, const int32_t
     DP_TRY(check_encoder_call(enc, params, ids, hidden, global_batch, 0, nl, 0, batches[i], workspace, workspace_bytes));
   }
   hipStream_t s = (hipStream_t)hip_stream;
-  std::vector<hipEvent_t> ev(nl + 1);
-  for (auto& e : ev)
-    if (hipEventCreate(&e) != hipSuccess) return set_error(DP_EHIP, "hipEventCreate failed");
+  EventSet es;
+  DP_TRY(es.create(nl + 1));
+  std::vector<hipEvent_t>& ev = es.ev;
   int rc = DP_OK, out = 0;
   for (int bi = 0; bi < n_batches && rc == DP_OK; ++bi) {
     const int n = batches[bi];
@@ -1083,7 +1085,6 @@ int dp_encoder_profile(dp_encoder* enc, const void* const* params, const int32_t
     const int64_t act = (int64_t)n * enc->d.seq * enc->d.d_model * enc->es;
     for (int l = 0; l < nl && rc == DP_OK; ++l) rows[out++] = dp_layer_cost{1, l, n, median(t[l]), 0.f, act, act, 0, 0};
   }
-  for (auto& e : ev) (void)hipEventDestroy(e);
   if (rc != DP_OK) return rc;
   *n_rows = out;
   return DP_OK;

@@ -220,6 +220,32 @@ def test_stage_cost_profile_rows(cfg):
         assert np.array_equal(got["grads"][k], want["grads"][k]), k
 
 
+@pytest.mark.parametrize("cfg", [si.CONFIG2.replace(name="cfg2_blocks", batch=4), si.CONFIG4.replace(name="cfg4_3blocks", n_blocks=3, batch=16, self_cond=False)],
+                         ids=lambda c: c.name)
+def test_stage_profile_rows_add_up_to_the_step(cfg):
+    """The partitioner adds per-layer times up (Eq. 3): the sum of the profiled P^f_l + P^b_l of a stage's
+    blocks must be the time of the stage's step, up to what the per-block joins of the side stream cost."""
+    import time
+    import torch
+    from paper_2405_01248_amd.harness import DeviceStage
+    ds = DeviceStage(cfg, si.make_stage_inputs(cfg, seed=0))
+    for _ in range(3):
+        ds.step()
+    torch.cuda.synchronize()
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+    steps = []
+    for _ in range(7):
+        ev[0].record(); ds.step(); ev[1].record()
+        torch.cuda.synchronize()
+        steps.append(ev[0].elapsed_time(ev[1]))
+    step_ms = float(np.median(steps))
+    rows = ds.stage.profile(ds.params, ds.x, ds.cc, ds.y, ds.dy, ds.dx, ds.d_cond, ds.dparams, ds.ws, reps=7)
+    torch.cuda.synchronize()
+    total = sum(r["fwd_ms"] + r["bwd_ms"] for r in rows)
+    print(f"\n[{cfg.name}] sum of profiled block times {total:.3f} ms, measured step {step_ms:.3f} ms, ratio {total / step_ms:.3f}", flush=True)
+    assert 0.9 <= total / step_ms <= 1.15, (total, step_ms)
+
+
 def test_partitioner_on_measured_stage_profiles():
     """Closes the loop of Sec. 4: cost rows measured on the GPU at the local batch sizes B / r feed the library's
     partitioner, whose plan must be the oracle's plan for the same rows (host arithmetic, compared exactly)."""
@@ -270,7 +296,9 @@ def test_encoder_cost_profile_rows():
         for l in range(nl):
             r = rows[j * nl + l]
             assert (r["component"], r["layer"], r["batch"]) == (1, l, b)
-            assert 0.0 < r["fwd_ms"] < 1e3 and r["bwd_ms"] == 0.0 and r["grad_bytes"] == 0 and r["cb_bytes"] == 0
+            # the final LayerNorm (l = nl - 1) may be folded into the last layer's reduction pass: its own span is then empty
+            assert (0.0 <= r["fwd_ms"] if l == nl - 1 else 0.0 < r["fwd_ms"]) and r["fwd_ms"] < 1e3
+            assert r["bwd_ms"] == 0.0 and r["grad_bytes"] == 0 and r["cb_bytes"] == 0
             assert r["out_bytes"] == b * cfg.seq * cfg.d_model * 2 and r["cf_bytes"] == r["out_bytes"]
 
 
