@@ -142,6 +142,177 @@ __global__ void __launch_bounds__(WGM * WGN * 64) conv3x3_bf16_kernel(const Conv
   wave_epilogue<TM, TN, WN, S::C_LD>(acc, Cw, p.epi, m0 + wm0, n0 + wn0, lane);
 }
 
+
+// ------------------------------------------------------------------ direct-to-LDS pipeline
+// The same product with the GEMM kernels' copy pipeline: tiles travel global -> LDS without passing through
+// registers (buffer_load ... lds, 16 bytes per lane, every lane with an address of its own, so the gather of
+// the input pixels costs nothing extra), three 64-deep k-tiles in flight, fragments fetched one k-step ahead,
+// one fence-free barrier per k-tile.  A k-tile lies inside one filter tap (C_in a multiple of 64): its source
+// address is the output pixel's base address plus an offset that is the same for the whole wave, and a lane
+// whose tap falls into the padding aims its copy past the end of the buffer, which the hardware answers with
+// zeros.  256 x 128 output tile, eight waves of 64 x 64.  LDS tiles are unpadded with permuted 16-byte
+// chunks, as in the GEMM kernels: chunk c of tile row r sits at position c ^ ((r >> 1) & 7).
+struct ConvDtlSmem {
+  static constexpr int BM = 256, BN = 128, BK = 64, STAGES = 3, WGM = 4, WGN = 2;
+  static constexpr int A_BYTES = BM * BK * 2, B_BYTES = BN * BK * 2, STAGE = A_BYTES + B_BYTES;
+  static constexpr int WN = BN / WGN, C_LD = WN + 4;
+  static constexpr size_t TILE_BYTES = (size_t)STAGES * STAGE;
+  static constexpr size_t EPI_BYTES = (size_t)WGM * WGN * 32 * C_LD * 4;
+  static constexpr size_t BYTES = TILE_BYTES > EPI_BYTES ? TILE_BYTES : EPI_BYTES;
+};
+
+__global__ void __launch_bounds__(512) conv3x3_dtl_kernel(const ConvParams p, uint32_t x_bytes, uint32_t w_bytes) {
+  using S = ConvDtlSmem;
+  constexpr int BM = S::BM, BN = S::BN, BK = S::BK, STAGES = S::STAGES, WGN = S::WGN, NW = S::WGM * S::WGN, KS = BK / 16, CPR = BK / 8;
+  constexpr int WM = BM / S::WGM, WN = BN / WGN, TM = WM / 32, TN = WN / 32;
+  constexpr int A_LOADS = S::A_BYTES / 1024 / NW, B_LOADS = S::B_BYTES / 1024 / NW, LOADS = A_LOADS + B_LOADS, PART_LAST = LOADS / KS;
+  static_assert(S::A_BYTES % (1024 * NW) == 0 && S::B_BYTES % (1024 * NW) == 0 && STAGES == 3 && KS == 4, "pipeline shape");
+  constexpr uint32_t OUTSIDE = 0xFFFFFFF0u;          // an offset past any buffer this kernel accepts: the copy delivers zeros
+
+  extern __shared__ __attribute__((aligned(1024))) unsigned char smem_raw[];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 5, l32 = lane & 31;
+  const int wm0 = (wave / WGN) * WM, wn0 = (wave % WGN) * WN;
+  int tile_m, tile_n;
+  tile_of_block(blockIdx.x, p.tiles_m, p.tiles_n, p.group_m, tile_m, tile_n);
+  const int m0 = tile_m * BM, n0 = tile_n * BN;
+  const int nk = p.K / BK;
+
+  const rsrc_t rx = make_rsrc(p.x, x_bytes), rw = make_rsrc(p.w, w_bytes);
+  // per A piece of this wave: byte offset of the output pixel's own input pixel (tap centre) plus this lane's
+  // chunk, and the 9-bit set of taps that fall inside the image for that pixel (empty for rows past M)
+  int a_base[A_LOADS];
+  unsigned a_taps[A_LOADS];
+#pragma unroll
+  for (int j = 0; j < A_LOADS; ++j) {
+    const int r = (wave * A_LOADS + j) * (512 / BK) + lane / CPR, pc = lane % CPR, c = pc ^ ((r >> 1) & 7);
+    const int gm = m0 + r, q = min(gm, p.M - 1);
+    const int b = q / (p.Ho * p.Wo), rem = q - b * (p.Ho * p.Wo), ho = rem / p.Wo, wo = rem - ho * p.Wo;
+    const int hc = ho * p.stride, wc = wo * p.stride;
+    a_base[j] = (int)(2u * ((uint32_t)((b * p.H + hc) * p.W + wc) * (uint32_t)p.Cin + (uint32_t)c * 8u));
+    unsigned m = 0;
+#pragma unroll
+    for (int tap = 0; tap < 9; ++tap) {
+      const int hi = hc + tap / 3 - 1, wi = wc + tap % 3 - 1;
+      m |= (unsigned)((unsigned)hi < (unsigned)p.H && (unsigned)wi < (unsigned)p.W) << tap;
+    }
+    a_taps[j] = gm < p.M ? m : 0u;
+  }
+  uint32_t vb[B_LOADS];
+#pragma unroll
+  for (int j = 0; j < B_LOADS; ++j) {
+    const int r = (wave * B_LOADS + j) * (512 / BK) + lane / CPR, pc = lane % CPR, c = pc ^ ((r >> 1) & 7);
+    vb[j] = 2u * ((uint32_t)min(n0 + r, p.N - 1) * (uint32_t)p.K + (uint32_t)c * 8u);
+  }
+  // the k-tile whose copies are being issued: its tap and its wave-uniform source offset relative to the tap centre
+  int it_tap = 0, it_c0 = 0, cur_tap = 0, cur_off = 0;
+  auto next_tile = [&]() {
+    const int u = (it_tap * 11) >> 5, v = it_tap - 3 * u;          // tap / 3, tap % 3 for tap < 9
+    cur_tap = it_tap;
+    cur_off = 2 * (((u - 1) * p.W + (v - 1)) * p.Cin + it_c0);
+    it_c0 += BK;
+    if (it_c0 == p.Cin) { it_c0 = 0; ++it_tap; }
+  };
+#define DPC_ISSUE_PART(t_, part_, parts_)                                                                             \
+  {                                                                                                                   \
+    unsigned char* st_ = smem_raw + ((t_) % STAGES) * S::STAGE;                                                       \
+    _Pragma("unroll") for (int j = 0; j < A_LOADS; ++j)                                                               \
+      if (j % (parts_) == (part_)) {                                                                                  \
+        const uint32_t off_ = ((a_taps[j] >> cur_tap) & 1u) ? (uint32_t)(a_base[j] + cur_off) : OUTSIDE;              \
+        async_copy_16B_buf(rx, off_, 0u, st_ + (wave * A_LOADS + j) * 1024);                                          \
+      }                                                                                                               \
+    _Pragma("unroll") for (int j = 0; j < B_LOADS; ++j)                                                               \
+      if ((A_LOADS + j) % (parts_) == (part_))                                                                        \
+        async_copy_16B_buf(rw, vb[j], (uint32_t)(t_) * (2u * BK), st_ + S::A_BYTES + (wave * B_LOADS + j) * 1024);    \
+  }
+
+  f32x16 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  bf16x8 fa[2][TM], fb[2][TN];
+#define DPC_FRAGS(st_, ks_, set_)                                                                                     \
+  {                                                                                                                   \
+    const bf16* as = reinterpret_cast<const bf16*>(smem_raw + (st_) * S::STAGE);                                      \
+    const bf16* bs = reinterpret_cast<const bf16*>(smem_raw + (st_) * S::STAGE + S::A_BYTES);                         \
+    _Pragma("unroll") for (int i = 0; i < TM; ++i) {                                                                  \
+      const int r = wm0 + i * 32 + l32;                                                                               \
+      fa[set_][i] = *reinterpret_cast<const bf16x8*>(as + r * BK + (((2 * (ks_) + g) ^ ((r >> 1) & 7)) * 8));         \
+    }                                                                                                                 \
+    _Pragma("unroll") for (int j2 = 0; j2 < TN; ++j2) {                                                               \
+      const int r = wn0 + j2 * 32 + l32;                                                                              \
+      fb[set_][j2] = *reinterpret_cast<const bf16x8*>(bs + r * BK + (((2 * (ks_) + g) ^ ((r >> 1) & 7)) * 8));        \
+    }                                                                                                                 \
+  }
+#define DPC_MFMAS(set_)                                                                                               \
+  _Pragma("unroll") for (int i = 0; i < TM; ++i)                                                                      \
+    _Pragma("unroll") for (int j2 = 0; j2 < TN; ++j2) acc[i][j2] = mfma32(fa[set_][i], fb[set_][j2], acc[i][j2]);
+
+  // pipeline: as in the GEMM kernels (all three buffers filled up front; k-tile t + 2 is copied, a few pieces per
+  // k-step, while k-tile t is multiplied; every wait names exactly the copies it needs)
+  for (int t = 0; t < STAGES && t < nk; ++t) { next_tile(); DPC_ISSUE_PART(t, 0, 1); }
+  {
+    const int y = min(nk, STAGES) - 1;
+    if (y == 2) wait_vmcnt<2 * LOADS>();
+    else if (y == 1) wait_vmcnt<LOADS>();
+    else wait_vmcnt<0>();
+  }
+  barrier_nofence();
+  DPC_FRAGS(0, 0, 0);
+  for (int t = 0; t + 1 < nk; ++t) {
+    const int st = t % STAGES;
+    const bool refill = t >= 1 && t - 1 + STAGES < nk;
+    if (refill) next_tile();
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      if (ks + 1 < KS) {
+        DPC_FRAGS(st, ks + 1, (ks + 1) & 1);
+      } else {
+        wait_lgkmcnt0();
+        if (nk - 2 - t >= 1) wait_vmcnt<LOADS - PART_LAST>();
+        else wait_vmcnt<0>();
+        barrier_nofence();
+        DPC_FRAGS((t + 1) % STAGES, 0, 0);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+      DPC_MFMAS(ks & 1);
+      __builtin_amdgcn_sched_barrier(0);
+      if (refill) DPC_ISSUE_PART(t - 1 + STAGES, ks, KS);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  }
+  {
+    const int st = (nk - 1) % STAGES;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      if (ks + 1 < KS) DPC_FRAGS(st, ks + 1, (ks + 1) & 1);
+      __builtin_amdgcn_sched_barrier(0);
+      DPC_MFMAS(ks & 1);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  }
+#undef DPC_FRAGS
+#undef DPC_MFMAS
+#undef DPC_ISSUE_PART
+  __syncthreads();   // every wave is done with the operand tiles before they are reused below
+  float* Cw = reinterpret_cast<float*>(smem_raw) + wave * 32 * S::C_LD;
+  wave_epilogue<TM, TN, WN, S::C_LD>(acc, Cw, p.epi, m0 + wm0, n0 + wn0, lane);
+}
+
+static int launch_conv_dtl(ConvParams& p, size_t x_bytes, size_t w_bytes, hipStream_t s) {
+  using S = ConvDtlSmem;
+  p.tiles_m = (p.M + S::BM - 1) / S::BM; p.tiles_n = (p.N + S::BN - 1) / S::BN;
+  const long n = (long)p.tiles_m * p.tiles_n, ppx = (n + 7) / 8;
+  p.group_m = (int)std::max<long>(1, std::min<long>((ppx + p.tiles_n / 2) / p.tiles_n, p.tiles_m));
+  if (hipFuncSetAttribute((const void*)conv3x3_dtl_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)S::BYTES) != hipSuccess)
+    return set_error(DP_EHIP, "hipFuncSetAttribute(conv) failed");
+  hipLaunchKernelGGL(conv3x3_dtl_kernel, dim3((unsigned)n), dim3(512), S::BYTES, s, p, (uint32_t)x_bytes, (uint32_t)w_bytes);
+  return hipGetLastError() == hipSuccess ? DP_OK : set_error(DP_EHIP, "conv launch failed");
+}
+
 template <int BM, int BN, int WGM, int WGN>
 static int launch_conv_cfg(ConvParams& p, hipStream_t s) {
   using S = ConvSmem<BM, BN, WGM, WGN>;
@@ -181,6 +352,10 @@ int launch_conv3x3(const ConvArgs& a, hipStream_t s) {
   e.geglu = 0; e.geglu_inner = 0; e.geglu_u = nullptr; e.ld_geglu = 0;
   const double by = 2.0 * ((double)a.B * a.H * a.W * a.Cin + (double)p.N * p.K + (double)M * a.Cout * (a.residual ? 2.0 : 1.0));
   KScope ks(KK_CONV, 2.0 * (double)M * p.N * p.K, by, s, p.M, p.N, p.K);
+  // the direct-to-LDS kernel: k-tiles inside one tap, 32-bit byte offsets with room for the "outside" marker
+  const size_t x_bytes = 2 * (size_t)a.B * a.H * a.W * a.Cin, w_bytes = 2 * (size_t)p.N * p.K;
+  if (a.Cin % 64 == 0 && a.Cout >= 64 && M >= 2048 && x_bytes < (1ull << 31) && w_bytes < (1ull << 31) && !a.force_staged)
+    return launch_conv_dtl(p, x_bytes, w_bytes, s);
   if (a.Cout <= 64) return launch_conv_cfg<128, 64, 4, 1>(p, s);
   if (M >= 256L * 256) return launch_conv_cfg<256, 128, 4, 2>(p, s);
   return launch_conv_cfg<128, 128, 2, 2>(p, s);

@@ -72,6 +72,7 @@ struct ConvArgs {
   int dtype;
   int B, H, W, Cin, Cout, stride;
   const void* x; const void* w; const void* bias; const void* residual; void* y;
+  int force_staged;   // 1: always the register-staged kernel (measurement and tests of that path)
 };
 int launch_conv3x3(const ConvArgs& a, hipStream_t s);
 

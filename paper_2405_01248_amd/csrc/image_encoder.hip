@@ -225,7 +225,7 @@ static void plan_image(const dp_image_encoder& e, void* base, int lb, int le, in
   b.gn_bytes = gn; b.gn = gn ? (float*)p.take(gn) : nullptr;
   if (attn_rows) {
     const size_t qb = attn_rows * attn_c * 2;
-    b.q = p.take(qb); b.k = p.take(qb); b.v = p.take(qb); b.a = p.take(qb);
+    b.q = p.take(qb); b.k = p.take(qb); b.v = p.take((size_t)attn_px * attn_c * 2); b.a = p.take(qb);   // v: one sample's values, transposed
     b.scores = (float*)p.take(attn_px * attn_px * 4); b.probs = p.take(attn_px * attn_px * 2);
   } else { b.q = b.k = b.v = b.a = b.probs = nullptr; b.scores = nullptr; }
   b.bytes = p.off;
@@ -274,18 +274,19 @@ static int image_layer(const dp_image_encoder& e, int l, const void* const* P, c
       DP_TRY(gn(src, ci, P[0], P[1], 0, w.t1));
       DP_TRY(launch_gemm(linear(w.t1, R, ci, P[2], ci, P[3], w.q), st));
       DP_TRY(launch_gemm(linear(w.t1, R, ci, P[4], ci, P[5], w.k), st));
-      DP_TRY(launch_gemm(linear(w.t1, R, ci, P[6], ci, P[7], w.v), st));
       const float scale = 1.0f / sqrtf((float)ci);
       for (int s = 0; s < n; ++s) {
         const size_t off = (size_t)s * HW * ci * 2;
+        // The values are produced transposed, v^T [c, HW] = W_v h_s^T (the weight as the row operand), so that the
+        // product with the probabilities contracts over a contiguous index on both sides.  Their bias is added after
+        // the attention instead: every row of the probabilities sums to one, so P (V + 1 b^T) = P V + 1 b^T.
+        DP_TRY(launch_gemm(linear(P[6], ci, ci, (const char*)w.t1 + off, HW, nullptr, w.v), st));
         GemmArgs g; memset(&g, 0, sizeof(g));          // scores = q_s k_s^T, fp32
         g.dtype = BF16; g.A = (const char*)w.q + off; g.B = (const char*)w.k + off; g.M = HW; g.N = HW; g.K = ci; g.lda = ci; g.ldb = ci;
         g.out_f32 = w.scores; g.ldo32 = HW;
         DP_TRY(launch_gemm(g, st));
         DP_TRY(launch_softmax_rows(BF16, w.scores, w.probs, HW, HW, scale, st));
-        memset(&g, 0, sizeof(g));                       // a_s = probs v_s
-        g.dtype = BF16; g.A = w.probs; g.B = (const char*)w.v + off; g.M = HW; g.N = ci; g.K = HW; g.lda = HW; g.ldb = ci; g.b_mc = 1;
-        g.out = (char*)w.a + off; g.ldo = ci;
+        g = linear(w.probs, HW, HW, w.v, ci, P[7], (char*)w.a + off);      // a_s = probs v_s + b_v
         DP_TRY(launch_gemm(g, st));
       }
       GemmArgs g = linear(w.a, R, ci, P[8], ci, P[9], dst);

@@ -29,6 +29,13 @@ SINGLE_LAYERS = [
     _one_layer("conv", 24, 8, 1, (5, 5)),                    # taps not aligned with k-tiles; the 8-channel output head width
     _one_layer("conv", 128, 128, 2, (34, 33), batch=1),
     _one_layer("conv", 16, 16, 1, (1, 1)),                   # a single pixel: only the centre tap is inside
+    # large enough for the direct-to-LDS kernel (C_in a multiple of 64, at least 2048 output pixels): padding taps
+    # answered by out-of-range copies, ragged pixel and channel tiles, stride 2, a half-empty channel tile
+    _one_layer("conv", 64, 128, 1, (48, 50)),
+    _one_layer("conv", 64, 192, 2, (65, 70)),
+    _one_layer("conv", 128, 64, 1, (33, 32)),
+    _one_layer("conv", 192, 72, 1, (47, 45), batch=1),
+    _one_layer("resnet", 64, 128, 1, (40, 40)),
     _one_layer("resnet", 32, 32, 1, (12, 10)),
     _one_layer("resnet", 32, 72, 1, (7, 9), groups=8),       # with the 1x1 skip convolution
     _one_layer("attn", 64, 64, 1, (8, 9), batch=3),          # 72 pixels: ragged tiles of the score and value products
