@@ -5,7 +5,8 @@ A step is one pass of the whole hot path over one micro-batch of synthetic input
 already resident in HBM: stage forward (saving activations) + stage backward, preceded by
 the extra no-grad forward for the self-conditioned DiT workload; for the text-encoder
 workload a step covers the 64-sample global batch with partial-batch calls.
-Prints ONE JSON line ("Measurement").
+`value` is the mean over exactly --steps steps between two device synchronisations (wall clock); the median of the
+per-step times taken with events on the launch stream is reported beside it.  Prints ONE JSON line.
 """
 from __future__ import annotations
 
@@ -72,16 +73,25 @@ def image_encoder_flops_per_sample(c):
     return fl
 
 
-def timed(fn, steps, warmup):
+def timed(fn, steps, warmup, median_out=None):
+    """Mean wall-clock seconds per step over exactly `steps` steps between two device synchronisations.  The same steps
+    are bracketed one by one with events on the stream the work is launched on; median_out["ms"] receives their median."""
     import torch
     for _ in range(warmup):
         fn()
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(steps):
+    ev[0].record()
+    for i in range(steps):
         fn()
+        ev[i + 1].record()
     torch.cuda.synchronize()
-    return (time.perf_counter() - t0) / steps
+    sec = (time.perf_counter() - t0) / steps
+    if median_out is not None:
+        per = sorted(ev[i].elapsed_time(ev[i + 1]) for i in range(steps))
+        median_out["ms"] = per[len(per) // 2] if steps % 2 else 0.5 * (per[steps // 2 - 1] + per[steps // 2])
+    return sec
 
 
 def cpu_baseline_stage(cfg):
@@ -135,13 +145,20 @@ def cpu_baseline_image_encoder(cfg):
             "sample": f"1 of {cfg.global_batch} samples of {cfg.name}, one fp64 numpy forward, {t:.1f} s"}
 
 
-# HBM bytes per launch of the dominant kernel measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE),
-# scaled by kernels of known size in the same run (FETCH_SIZE x 2.0, WRITE_SIZE x 1.0); the counter runs and the
-# per-kernel table are in profiles/hbm_traffic_cfg2.md.  Average over the launches of the class in one step.
-PMC_TRAFFIC_BYTES = {
-    ("cfg2", "gemm_nt"): 81.8e6,    # 26 launches per step: forward projections and dx = dy W on transposed weight copies
-    ("cfg2", "gemm_tn"): 116.6e6,   # 14 launches per step: dW = dy^T x, split-K partial sums included
-}
+def pmc_traffic_bytes(workload, kind):
+    """HBM bytes per launch of a kernel class as measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (two counter runs,
+    scaled by kernels of known size): read from the class table of profiles/hbm_traffic_<workload>.md, which also holds the
+    commands.  None (with the reason) when that summary or that class is not there."""
+    import re
+    path = os.path.join(ROOT, "profiles", f"hbm_traffic_{workload}.md")
+    if not os.path.exists(path):
+        return None, f"profiles/hbm_traffic_{workload}.md is missing"
+    for line in open(path):
+        m = re.match(r"\|\s*`class:([a-z0-9_]+)`\s*\|\s*(\d+)\s*\|\s*([0-9.]+)\s*\|", line)
+        if m and m.group(1) == kind:
+            return float(m.group(3)) * 1e6, f"profiles/hbm_traffic_{workload}.md, class {kind}, {m.group(2)} dispatches"
+    return None, f"profiles/hbm_traffic_{workload}.md has no row for class {kind}"
+
 
 MFMA_KINDS = {"gemm_nt", "gemm_nn", "gemm_tn", "attn_fwd", "attn_bwd_dq", "attn_bwd_dkv", "conv3x3"}
 KERNEL_NAMES = {"gemm_nt": "dp::gemm_bf16_dtl_kernel<..., A_MC=false, B_MC=false> (y = x W^T; dx = dy W on transposed weight copies)",
@@ -198,10 +215,11 @@ def kernel_roofline(workload, names, si, DeviceStage, DeviceEncoder, passes=3):
     else:
         ach = a["bytes"] / (a["ms"] * 1e-3) / 1e9
         roof = {"bound": "hbm", "achieved": ach, "peak": HBM_PEAK / 1e9, "unit": "GB/s", "frac": ach / (HBM_PEAK / 1e9)}
-    roof.update(traffic=PMC_TRAFFIC_BYTES.get((workload, dom)), kernel=KERNEL_NAMES.get(dom, dom),
+    traffic, traffic_src = pmc_traffic_bytes(workload, dom)
+    roof.update(traffic=traffic, traffic_source=traffic_src, kernel=KERNEL_NAMES.get(dom, dom),
                 note="durations from a pass with the backward's side stream disabled (kernels run one at a time); "
                      "HIP events around every launch, dispatch gap included (rocprofv3's kernel-only averages are in "
-                     "profiles/kernels_cfg2_serial.md; an empty event pair reads event_pair_overhead_us)",
+                     f"profiles/kernels_{workload}_serial.md; an empty event pair reads event_pair_overhead_us)",
                 event_pair_overhead_us=event_overhead_us,
                 avg_launch_us=1e3 * a["ms"] / a["launches"], launches_per_step=a["launches"] / passes,
                 algorithmic_per_launch=(a["flops"] if dom in MFMA_KINDS else a["bytes"]) / a["launches"],
@@ -308,8 +326,8 @@ def bubble_report(si, DeviceStage, DeviceEncoder):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=30)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="cfg2", choices=["cfg2", "cfg3", "cfg4", "cfg5", "cfg6"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-others", action="store_true", help="skip the short runs of the other workloads")
@@ -344,9 +362,10 @@ def main():
             ds.stage.set_overlap(False)
         if args.fusion is not None:
             ds.stage.set_fusion(args.fusion)
-        sec = timed(ds.step, steps, warmup)
+        med = {}
+        sec = timed(ds.step, steps, warmup, med)
         fl = stage_flops(cfg)
-        return ds, {"samples_per_s": cfg.batch / sec, "ms_per_step": sec * 1e3, "tflops": fl / sec / 1e12,
+        return ds, {"samples_per_s": cfg.batch / sec, "ms_per_step": sec * 1e3, "median_ms_per_step": med["ms"], "tflops": fl / sec / 1e12,
                     "mfma_peak_frac": fl / sec / MFMA_PEAK}
 
     def run_encoder(steps, warmup):
@@ -400,7 +419,8 @@ def main():
         cfg = names[args.workload]
         ds, r = run_stage(cfg, args.steps, args.warmup)
         result.update(metric="stage_fwd_bwd_samples_per_sec", value=r["samples_per_s"], unit="samples/s",
-                      ms_per_step=r["ms_per_step"], mfma_peak_frac=r["mfma_peak_frac"], achieved_tflops=r["tflops"],
+                      ms_per_step=r["ms_per_step"], median_ms_per_step=r["median_ms_per_step"], mfma_peak_frac=r["mfma_peak_frac"],
+                      achieved_tflops=r["tflops"],
                       config={"workload": cfg.name, "micro_batch": cfg.batch, "tokens": cfg.tokens, "d_model": cfg.d_model,
                               "n_blocks": cfg.n_blocks, "self_conditioning": cfg.self_cond,
                               "algorithmic_tflop_per_step": stage_flops(cfg) / 1e12})
