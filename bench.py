@@ -229,6 +229,45 @@ def kernel_roofline(workload, names, si, DeviceStage, DeviceEncoder, passes=3):
     return roof, classes
 
 
+def fp8_report():
+    """The FP8 (OCP E4M3) projection GEMM beside the bf16 one on the projection shapes of the DiT stage, the text encoder
+    at 16 and 64 samples and one large square problem: microseconds per launch (events on the launch stream) and
+    algorithmic TFLOP/s; the fp8 figure is against the 5.0 PFLOP/s fp8 peak."""
+    import torch
+    from paper_2405_01248_amd import binding as B
+    dev = "cuda:0"
+
+    def t(f, iters=30):
+        for _ in range(3):
+            f()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(iters):
+            f()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / iters * 1e3
+
+    rows = []
+    for (M, N, K) in [(8192, 4608, 1152), (8192, 1152, 4608), (8192, 3456, 1152), (4928, 3072, 768), (1232, 3072, 768), (8192, 8192, 8192)]:
+        A = torch.randn((M, K), device=dev, dtype=torch.bfloat16)
+        W = torch.randn((N, K), device=dev, dtype=torch.bfloat16) * 0.05
+        Cc = torch.empty((M, N), device=dev, dtype=torch.bfloat16)
+        ws = torch.empty(max(B.op_gemm_workspace_bytes(M, N, K), 256), dtype=torch.uint8, device=dev)
+        qa = torch.zeros((M, K), dtype=torch.uint8, device=dev)
+        qw = torch.zeros((N, K), dtype=torch.uint8, device=dev)
+        sa, sw = float(A.abs().max()) / 448.0, float(W.abs().max()) / 448.0
+        B.op_quantize_fp8(A, K, qa, K, M, K, sa)
+        B.op_quantize_fp8(W, K, qw, K, N, K, sw)
+        us16 = t(lambda: B.op_gemm(B.DP_BF16, A, K, 0, W, K, 0, M, N, K, None, Cc, N, False, False, ws, 0))
+        us8 = t(lambda: B.op_gemm_fp8(qa, K, qw, K, M, N, K, sa * sw, None, Cc, N))
+        usq = t(lambda: B.op_quantize_fp8(A, K, qa, K, M, K, sa))
+        fl = 2.0 * M * N * K
+        rows.append({"M": M, "N": N, "K": K, "bf16_us": us16, "bf16_tflops": fl / us16 / 1e6, "fp8_us": us8, "fp8_tflops": fl / us8 / 1e6,
+                     "fp8_peak_frac": fl / us8 / 1e6 / 5000.0, "speedup": us16 / us8, "quantize_activations_us": usq})
+    return {"metric": "fp8_vs_bf16_projection_gemm", "dtype": "fp8_e4m3", "shapes": rows}
+
+
 def partition_report(si, DeviceStage):
     """Partitioner (Sec. 4.1 / 4.3) on cost rows measured here: the 7 identical-shape DiT blocks of cfg4 are profiled at
     local batch 32 / r for r = 1, 2, 4, 8 and tiled 4x to the 28 layers of the whole backbone; link figures are one xGMI
@@ -339,6 +378,8 @@ def main():
     ap.add_argument("--bubbles", action="store_true",
                     help="instead of the step benchmark: --partition's plan for cfg4, its 1F1B bubbles, and their filling with "
                          "the text encoder profiled here at the regular partial-batch sizes (library and oracle)")
+    ap.add_argument("--fp8", action="store_true",
+                    help="instead of the step benchmark: the FP8 (E4M3) projection GEMM beside the bf16 one on the workloads' projection shapes")
     ap.add_argument("--partition", action="store_true",
                     help="instead of the step benchmark: profile the DiT stage's blocks at local batch sizes 32, 16, 8, 4 on this "
                          "GPU, tile them to a 28-layer backbone and run the partitioner (library and oracle) for 8 devices")
@@ -391,6 +432,9 @@ def main():
                            "mfma_peak_frac": image_encoder_flops_per_sample(c) * c.global_batch / sec / MFMA_PEAK}
         return de, out
 
+    if args.fp8:
+        print(json.dumps(fp8_report()))
+        return
     if args.partition:
         print(json.dumps(partition_report(si, DeviceStage)[0]))
         return

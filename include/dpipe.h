@@ -388,6 +388,20 @@ int dp_op_gemm(int dtype, const void* A, int lda, int a_kmajor, const void* B, i
                const void* bias, void* C, int ldc, int out_is_f32, int accumulate, void* workspace, size_t workspace_bytes,
                int tile_cfg, void* hip_stream);
 
+/* FP8 variant of the projection GEMM, an extension for MI355X (whose matrix pipe runs 8-bit operands at twice the
+ * bf16 rate): meant for the frozen, forward-only components (Sec. 2.1), whose projections need no gradient.
+ * Format: OCP E4M3 (1 sign, 4 exponent bits with bias 7, 3 mantissa bits; subnormals; largest finite value 448; no
+ * infinities), one scale per tensor.
+ * dp_op_quantize_fp8: q[i, j] = e4m3(clamp(x[i, j] * (1 / scale), -448, 448)), the product formed in fp32 (1 / scale
+ * rounded to fp32 first), conversion to the nearest E4M3 value, ties to even.  x [device]: bf16 [rows, cols], row
+ * stride ldx elements; q [device]: bytes [rows, cols], row stride ldq; cols, ldx, ldq multiples of 8.
+ * dp_op_gemm_fp8: C[M, N] (bf16, row stride ldc) = out_scale * sum_k A[m, k] B[n, k] (+ bias[n], bf16), A [M, K] and
+ * B [N, K] E4M3 bytes with row strides lda, ldb (multiples of 16), fp32 accumulation; out_scale is the product of the
+ * two tensors' scales.  K a multiple of 128, N and ldc of 8; operands below 4 GiB. */
+int dp_op_quantize_fp8(const void* x, int ldx, void* q, int ldq, int rows, int cols, float scale, void* hip_stream);
+int dp_op_gemm_fp8(const void* A, int lda, const void* B, int ldb, int M, int N, int K, float out_scale, const void* bias, void* C,
+                   int ldc, void* hip_stream);
+
 /* dp_op_gemm for callers that cannot allocate device memory: code under HIP graph capture, tight serving
  * loops, harnesses that forbid hipMalloc.  Same operation, arguments and results as dp_op_gemm (bit for bit
  * those of dp_op_gemm given a workspace of dp_op_gemm_workspace_bytes), but the split-K partial sums live in
@@ -421,7 +435,7 @@ int dp_op_attention_bwd(int dtype, int B, int H, int Nq, int Nk, int d_head, flo
  * its duration.  kind: 0 GEMM y = x W^T, 1 GEMM dx = dy W, 2 GEMM dW = dy^T x, 3 attention
  * forward, 4 attention dQ, 5 attention dK/dV, 6 LayerNorm forward, 7 LayerNorm backward,
  * 8 GeGLU forward, 9 GeGLU backward, 10 partial-sum reductions, 11 other, 12 fp32 GEMM,
- * 13 fp32 attention, 14 3x3 convolution (2 * pixels * c_out * 9 c_in), 15 GroupNorm, 16 row softmax.  dp_ktime_begin allocates host-side events (max_records pairs);
+ * 13 fp32 attention, 14 3x3 convolution (2 * pixels * c_out * 9 c_in), 15 GroupNorm, 16 row softmax, 17 fp8 GEMM.  dp_ktime_begin allocates host-side events (max_records pairs);
  * dp_ktime_end synchronises the device, writes up to max records and frees them.  `ms` is the
  * time between a record's two events, which includes the dispatch gap around the kernel (an upper
  * bound of the kernel's duration: a few microseconds above what a kernel trace shows).  For scale,

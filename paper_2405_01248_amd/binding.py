@@ -103,14 +103,14 @@ class KernelTime(C.Structure):
 
 
 KERNEL_KINDS = {0: "gemm_nt", 1: "gemm_nn", 2: "gemm_tn", 3: "attn_fwd", 4: "attn_bwd_dq", 5: "attn_bwd_dkv", 6: "ln_fwd",
-                7: "ln_bwd", 8: "geglu_fwd", 9: "geglu_bwd", 10: "reduce", 11: "other", 12: "gemm_f32", 13: "attn_f32", 14: "conv3x3", 15: "groupnorm", 16: "softmax_rows"}
+                7: "ln_bwd", 8: "geglu_fwd", 9: "geglu_bwd", 10: "reduce", 11: "other", 12: "gemm_f32", 13: "attn_f32", 14: "conv3x3", 15: "groupnorm", 16: "softmax_rows", 17: "gemm_fp8"}
 
 EXPORTS = ["dp_stage_create", "dp_stage_destroy", "dp_stage_set_overlap", "dp_stage_set_fusion", "dp_stage_param_count", "dp_stage_param_shape", "dp_stage_workspace_bytes",
            "stage_fwd", "stage_bwd", "dp_encoder_create", "dp_encoder_destroy", "dp_encoder_param_count",
            "dp_encoder_param_shape", "dp_encoder_workspace_bytes", "encoder_fwd_partial", "dp_stage_profile",
            "dp_encoder_profile", "dp_image_encoder_create", "dp_image_encoder_destroy", "dp_image_encoder_param_count",
            "dp_image_encoder_param_shape", "dp_image_encoder_layer_shape", "dp_image_encoder_workspace_bytes", "image_encoder_fwd_partial",
-           "dp_image_encoder_profile", "dp_ktime_begin", "dp_ktime_end", "dp_ktime_event_overhead_ms", "dp_last_error", "dp_op_gemm", "dp_op_gemm_static", "dp_op_gemm_workspace_bytes",
+           "dp_image_encoder_profile", "dp_ktime_begin", "dp_ktime_end", "dp_ktime_event_overhead_ms", "dp_last_error", "dp_op_gemm", "dp_op_gemm_fp8", "dp_op_quantize_fp8", "dp_op_gemm_static", "dp_op_gemm_workspace_bytes",
            "dp_op_attention_fwd", "dp_op_attention_bwd", "dp_partition_solve", "dp_partition_solve_bidirectional", "dp_bubbles_1f1b", "dp_bubbles_fill", "dp_schedule_search"]
 
 
@@ -158,6 +158,8 @@ def load_library():
     f = C.c_float
     lib.dp_op_gemm_workspace_bytes.argtypes = [i, i, i]; lib.dp_op_gemm_workspace_bytes.restype = sz
     lib.dp_op_gemm.argtypes = [i, vp, i, i, vp, i, i, i, i, i, vp, vp, i, i, i, vp, sz, i, vp]
+    lib.dp_op_quantize_fp8.argtypes = [vp, i, vp, i, i, i, f, vp]
+    lib.dp_op_gemm_fp8.argtypes = [vp, i, vp, i, i, i, i, f, vp, vp, i, vp]
     lib.dp_op_gemm_static.argtypes = [i, vp, i, i, vp, i, i, i, i, i, vp, vp, i, i, i, i, vp]
     lib.dp_op_attention_fwd.argtypes = [i, i, i, i, i, i, i, f, vp, i, vp, i, vp, i, vp, i, vp, vp]
     lib.dp_op_attention_bwd.argtypes = [i, i, i, i, i, i, f, vp, i, vp, i, vp, i, vp, i, vp, vp, i, vp, vp, i, vp, i, vp, i, vp]
@@ -476,6 +478,14 @@ def op_gemm_static(dtype, A, lda, a_kmajor, B, ldb, b_kmajor, M, N, K, bias, Cou
                    tile_cfg=0, stream=None):
     _check(load_library().dp_op_gemm_static(dtype, _ptr(A), lda, int(a_kmajor), _ptr(B), ldb, int(b_kmajor), M, N, K, _ptr(bias),
                                             _ptr(Cout), ldc, int(out_is_f32), int(accumulate), tile_cfg, _stream(stream)))
+
+
+def op_quantize_fp8(x, ldx, q, ldq, rows, cols, scale, stream=None):
+    _check(load_library().dp_op_quantize_fp8(_ptr(x), ldx, _ptr(q), ldq, rows, cols, scale, _stream(stream)))
+
+
+def op_gemm_fp8(A, lda, B, ldb, M, N, K, out_scale, bias, Cout, ldc, stream=None):
+    _check(load_library().dp_op_gemm_fp8(_ptr(A), lda, _ptr(B), ldb, M, N, K, out_scale, _ptr(bias), _ptr(Cout), ldc, _stream(stream)))
 
 
 def op_gemm_workspace_bytes(M, N, K):

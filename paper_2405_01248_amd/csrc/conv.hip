@@ -349,7 +349,7 @@ int launch_conv3x3(const ConvArgs& a, hipStream_t s) {
   e.bias = (const bf16*)a.bias; e.pre_out = nullptr; e.ld_pre = 0; e.act = 0;
   e.dact_pre = nullptr; e.ld_dact = 0; e.dact_kind = 0; e.gate = nullptr; e.gate_ld = 0; e.rows_per_batch = 1;
   e.residual = a.residual; e.ld_res = a.Cout; e.residual_f32 = 0; e.out_fused_f32 = 0;
-  e.geglu = 0; e.geglu_inner = 0; e.geglu_u = nullptr; e.ld_geglu = 0;
+  e.geglu = 0; e.geglu_inner = 0; e.geglu_u = nullptr; e.ld_geglu = 0; e.out_scale = 1.0f;
   const double by = 2.0 * ((double)a.B * a.H * a.W * a.Cin + (double)p.N * p.K + (double)M * a.Cout * (a.residual ? 2.0 : 1.0));
   KScope ks(KK_CONV, 2.0 * (double)M * p.N * p.K, by, s, p.M, p.N, p.K);
   // the direct-to-LDS kernel: k-tiles inside one tap, 32-bit byte offsets with room for the "outside" marker

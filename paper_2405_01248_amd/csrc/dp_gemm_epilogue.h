@@ -20,6 +20,7 @@ struct EpiParams {
   const T* gate; int gate_ld; int rows_per_batch;
   const void* residual; int ld_res; int residual_f32; int out_fused_f32;
   int geglu, geglu_inner; const T* geglu_u; int ld_geglu;
+  float out_scale;                // the accumulators are multiplied by this before anything else (1 except for fp8 operands)
 };
 
 // Scalar epilogue (fp32 path).
@@ -54,6 +55,10 @@ __device__ __forceinline__ void epi_vec8(const EpiParams<bf16>& e, int m, int n,
     *reinterpret_cast<f32x4*>(o) = *reinterpret_cast<const f32x4*>(&v[0]);
     *reinterpret_cast<f32x4*>(o + 4) = *reinterpret_cast<const f32x4*>(&v[4]);
     return;
+  }
+  if (e.out_scale != 1.0f) {
+#pragma unroll
+    for (int t = 0; t < 8; ++t) v[t] *= e.out_scale;
   }
   if (e.bias) {
     const bf16x8 bv = *reinterpret_cast<const bf16x8*>(e.bias + n);

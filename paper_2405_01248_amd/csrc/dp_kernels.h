@@ -64,6 +64,17 @@ bool gemm_colsum_supported(const GemmArgs& a);
 size_t gemm_splitk_ws_bytes(int M, int N, int K);   // upper bound for out_f32 GEMMs
 size_t gemm_epi_splitk_ws_bytes(int M, int N, int K);   // same for storage-dtype outputs (0: such a GEMM is never split)
 
+// ---------------------------------------------------------------- FP8 (OCP E4M3) projection GEMM
+// q[i, j] = e4m3(clamp(x[i, j] * inv_scale, -448, 448)), round to nearest even; x [rows, cols] in bf16 (row stride ldx
+// elements), q bytes (row stride ldq).  cols a multiple of 8.
+int launch_quantize_fp8(const void* x, int ldx, void* q, int ldq, int rows, int cols, float inv_scale, hipStream_t s);
+// out[M, N] (bf16) = out_scale * sum_k A[m, k] B[n, k] (+ bias[n]) for E4M3 operands A [M, K], B [N, K] (row strides in
+// bytes), fp32 accumulation on v_mfma_f32_32x32x64_f8f6f4.  K a multiple of 128, N of 8.
+struct Fp8GemmArgs {
+  const void* A; int lda; const void* B; int ldb; int M, N, K; float out_scale; const void* bias; void* out; int ldo;
+};
+int launch_gemm_fp8(const Fp8GemmArgs& a, hipStream_t s);
+
 // ---------------------------------------------------------------- convolution (frozen image encoder)
 // y[b, i, j, :] = sum_{u, v} x[b, i * stride + u - 1, j * stride + v - 1, :] w[:, 3u + v, :]^T + bias (+ residual),
 // zero padding 1.  Channels-last bf16 tensors: x [B, H, W, Cin], w [Cout, 9 * Cin] (taps row-major, channels

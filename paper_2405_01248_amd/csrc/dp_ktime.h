@@ -9,7 +9,7 @@ namespace dp {
 enum KernelKind {
   KK_GEMM_NT = 0, KK_GEMM_NN = 1, KK_GEMM_TN = 2, KK_ATTN_FWD = 3, KK_ATTN_BWD_DQ = 4, KK_ATTN_BWD_DKV = 5,
   KK_LN_FWD = 6, KK_LN_BWD = 7, KK_GEGLU_FWD = 8, KK_GEGLU_BWD = 9, KK_REDUCE = 10, KK_OTHER = 11, KK_GEMM_F32 = 12,
-  KK_ATTN_F32 = 13, KK_CONV = 14, KK_GROUPNORM = 15, KK_SOFTMAX = 16
+  KK_ATTN_F32 = 13, KK_CONV = 14, KK_GROUPNORM = 15, KK_SOFTMAX = 16, KK_GEMM_FP8 = 17
 };
 
 bool ktime_enabled();

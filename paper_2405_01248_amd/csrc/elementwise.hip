@@ -692,6 +692,38 @@ int launch_cast_to_f32(int dtype, const void* in, float* out, size_t n, hipStrea
   return hipGetLastError() == hipSuccess ? DP_OK : set_error(DP_EHIP, "cast launch failed");
 }
 
+// bf16 -> OCP E4M3 with a per-tensor scale: the product with 1 / scale is formed in fp32, clamped to the format's
+// largest finite value (+-448) and converted by the hardware's round-to-nearest-even conversion; 8 values per thread.
+__global__ void __launch_bounds__(256) quantize_fp8_kernel(const bf16* __restrict__ x, int ldx, unsigned char* __restrict__ q, int ldq,
+                                                           int rows, int cols, float inv_scale) {
+  const size_t i = blockIdx.x * (size_t)256 + threadIdx.x;
+  const int per_row = cols / 8;
+  if (i >= (size_t)rows * per_row) return;
+  const size_t r = i / per_row; const int c = (int)(i % per_row) * 8;
+  const bf16x8 v = *reinterpret_cast<const bf16x8*>(x + r * ldx + c);
+  float f[8];
+#pragma unroll
+  for (int t = 0; t < 8; ++t) f[t] = fminf(fmaxf((float)v[t] * inv_scale, -448.0f), 448.0f);
+  int lo = 0, hi = 0;
+  lo = __builtin_amdgcn_cvt_pk_fp8_f32(f[0], f[1], lo, false);
+  lo = __builtin_amdgcn_cvt_pk_fp8_f32(f[2], f[3], lo, true);
+  hi = __builtin_amdgcn_cvt_pk_fp8_f32(f[4], f[5], hi, false);
+  hi = __builtin_amdgcn_cvt_pk_fp8_f32(f[6], f[7], hi, true);
+  u32x2 o = {(uint32_t)lo, (uint32_t)hi};
+  *reinterpret_cast<u32x2*>(q + r * ldq + c) = o;
+}
+int launch_quantize_fp8(const void* x, int ldx, void* q, int ldq, int rows, int cols, float inv_scale, hipStream_t s) {
+  if (rows <= 0 || cols <= 0 || !x || !q) return set_error(DP_EINVAL, "quantize_fp8: bad arguments");
+  if (cols % 8 || ldx % 8 || ldq % 8 || ldx < cols || ldq < cols) return set_error(DP_EUNSUPPORTED, "quantize_fp8: cols and leading dims must be multiples of 8");
+  if (((uintptr_t)x % 16) || ((uintptr_t)q % 8)) return set_error(DP_EALIGN, "quantize_fp8: operands must be 16- / 8-byte aligned");
+  if (!(inv_scale > 0.f) || !(inv_scale < INFINITY)) return set_error(DP_EINVAL, "quantize_fp8: the scale must be positive and finite");
+  const size_t n = (size_t)rows * (cols / 8);
+  if ((n + 255) / 256 > 0x7fffffffull) return set_error(DP_EUNSUPPORTED, "quantize_fp8: tensor too large");
+  KScope ks(KK_OTHER, 0.0, 3.0 * (double)rows * cols, s, rows, cols, 0);
+  hipLaunchKernelGGL(quantize_fp8_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, (const bf16*)x, ldx, (unsigned char*)q, ldq, rows, cols, inv_scale);
+  return hipGetLastError() == hipSuccess ? DP_OK : set_error(DP_EHIP, "quantize_fp8 launch failed");
+}
+
 // One wave per token row.  Token ids outside [0, vocab) are clamped (ids live on the device
 // and cannot be validated on the host); the sum is rounded once to the storage type.
 template <typename T>

@@ -17,6 +17,7 @@
 #include <algorithm>
 #include <atomic>
 #include <cmath>
+#include <cstring>
 
 namespace dp {
 
@@ -245,11 +246,19 @@ struct DtlSmem {
 // reads by 16 consecutive rows.  BK = 32: 4 chunks, key (r >> 2) & 3; BK = 64: 8 chunks, key (r >> 1) & 7.
 template <int BK> __device__ __forceinline__ int kc_key(int r) { return BK == 32 ? ((r >> 2) & 3) : ((r >> 1) & 7); }
 
-template <int BM, int BN, int BK, int STAGES, int WGM, int WGN, bool A_MC, bool B_MC>
+// FP8: the operands are OCP E4M3 bytes.  The copy pipeline only moves bytes, so an fp8 row of K bytes is handled as a
+// row of K / 2 two-byte elements (all sizes and strides in the parameters are given in those units); what changes is the
+// k-step (64 bytes instead of 32: two 16-byte chunks per lane) and the instruction, v_mfma_f32_32x32x64_f8f6f4 with both
+// block scales at 2^0.  Any assignment of the 64 bytes of a k-step to lanes and byte slots gives the right product as
+// long as it is the same for both operands, which it is by symmetry.
+typedef __attribute__((ext_vector_type(8))) int i32x8;
+
+template <int BM, int BN, int BK, int STAGES, int WGM, int WGN, bool A_MC, bool B_MC, bool FP8 = false>
 __global__ void __launch_bounds__(WGM * WGN * 64)
 gemm_bf16_dtl_kernel(const GemmBf16Params p) {
   using S = DtlSmem<BM, BN, BK, STAGES, WGM, WGN>;
-  constexpr int NW = WGM * WGN, KS = BK / 16, CPR = BK / 8;      // k-steps per tile, chunks per K-contiguous row
+  constexpr int NW = WGM * WGN, KS = FP8 ? BK / 32 : BK / 16, CPR = BK / 8;      // k-steps per tile, chunks per K-contiguous row
+  static_assert(!FP8 || (!A_MC && !B_MC && BK == 64), "the fp8 variant takes contraction-contiguous operands and 128-byte k-tiles");
   constexpr int WM = BM / WGM, WN = BN / WGN;
   constexpr int TM = WM / 32, TN = WN / 32;
   constexpr int A_LOADS = S::A_BYTES / 1024 / NW, B_LOADS = S::B_BYTES / 1024 / NW, LOADS = A_LOADS + B_LOADS;
@@ -322,8 +331,24 @@ gemm_bf16_dtl_kernel(const GemmBf16Params p) {
 
   // Fragment fetch of k-step ks_ of the k-tile in stage st_ into register set set_.
   bf16x8 fa[2][TM], fb[2][TN];
+  i32x8 qa[2][FP8 ? TM : 1], qb[2][FP8 ? TN : 1];     // fp8: 32 bytes per lane and fragment
 #define DP_DTL_FRAGS(st_, ks_, set_)                                                                                  \
-  {                                                                                                                   \
+  { if (FP8) {                                                                                                        \
+    const unsigned char* as = smem_raw + (st_) * S::STAGE;                                                            \
+    const unsigned char* bs = smem_raw + (st_) * S::STAGE + S::A_BYTES;                                               \
+    _Pragma("unroll") for (int i = 0; i < (FP8 ? TM : 0); ++i) {                                                      \
+      const int r = wm0 + i * 32 + l32, c0 = 4 * (ks_) + 2 * g, key = kc_key<BK>(r);                                  \
+      const u32x4 lo = *reinterpret_cast<const u32x4*>(as + r * (2 * BK) + ((c0 ^ key) * 16));                        \
+      const u32x4 hi = *reinterpret_cast<const u32x4*>(as + r * (2 * BK) + (((c0 + 1) ^ key) * 16));                  \
+      qa[set_][i] = __builtin_bit_cast(i32x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));              \
+    }                                                                                                                 \
+    _Pragma("unroll") for (int j2 = 0; j2 < (FP8 ? TN : 0); ++j2) {                                                   \
+      const int r = wn0 + j2 * 32 + l32, c0 = 4 * (ks_) + 2 * g, key = kc_key<BK>(r);                                 \
+      const u32x4 lo = *reinterpret_cast<const u32x4*>(bs + r * (2 * BK) + ((c0 ^ key) * 16));                        \
+      const u32x4 hi = *reinterpret_cast<const u32x4*>(bs + r * (2 * BK) + (((c0 + 1) ^ key) * 16));                  \
+      qb[set_][j2] = __builtin_bit_cast(i32x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));             \
+    }                                                                                                                 \
+  } else {                                                                                                            \
     const bf16* as = reinterpret_cast<const bf16*>(smem_raw + (st_) * S::STAGE);                                      \
     const bf16* bs = reinterpret_cast<const bf16*>(smem_raw + (st_) * S::STAGE + S::A_BYTES);                         \
     _Pragma("unroll") for (int i = 0; i < TM; ++i) {                                                                  \
@@ -342,10 +367,13 @@ gemm_bf16_dtl_kernel(const GemmBf16Params p) {
         fb[set_][j2] = *reinterpret_cast<const bf16x8*>(bs + r * BK + (((2 * (ks_) + g) ^ kc_key<BK>(r)) * 8));       \
       }                                                                                                               \
     }                                                                                                                 \
-  }
+  } }
 #define DP_DTL_MFMAS(set_)                                                                                            \
   _Pragma("unroll") for (int i = 0; i < TM; ++i)                                                                      \
-    _Pragma("unroll") for (int j2 = 0; j2 < TN; ++j2) acc[i][j2] = mfma32(fa[set_][i], fb[set_][j2], acc[i][j2]);
+    _Pragma("unroll") for (int j2 = 0; j2 < TN; ++j2) {                                                               \
+      if (FP8) acc[i][j2] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(qa[set_][FP8 ? i : 0], qb[set_][FP8 ? j2 : 0], acc[i][j2], 0, 0, 0, 127, 0, 127); \
+      else acc[i][j2] = mfma32(fa[set_][i], fb[set_][j2], acc[i][j2]);                                                \
+    }
 
   // Software pipeline.  All STAGES buffers are filled up front.  Fragments are fetched one k-step
   // ahead of the MFMAs that use them, also across the k-tile boundary: before the last MFMA group
@@ -668,6 +696,7 @@ static EpiParams<T> make_epi(const GemmArgs& a) {
   e.gate = (const T*)a.gate; e.gate_ld = a.gate_ld; e.rows_per_batch = a.rows_per_batch > 0 ? a.rows_per_batch : 1;
   e.residual = a.residual; e.ld_res = a.ld_res; e.residual_f32 = a.residual_f32; e.out_fused_f32 = a.out_fused_f32;
   e.geglu = a.geglu; e.geglu_inner = a.geglu_inner; e.geglu_u = (const T*)a.geglu_u; e.ld_geglu = a.ld_geglu;
+  e.out_scale = 1.0f;
   return e;
 }
 
@@ -921,6 +950,48 @@ static int launch_dtl_cfg(const GemmArgs& a, hipStream_t s) {
     return launch_reduce_partials(a.splitk_ws, splits, (size_t)a.M * a.N, a.out_f32, a.accumulate, s);
   }
   return DP_OK;
+}
+
+// C = out_scale * (A_q B_q^T) (+ bias) for OCP E4M3 operands A_q [M, K], B_q [N, K] (bytes, contraction contiguous), storage-dtype
+// (bf16) output.  The kernel sees the operands as two-byte elements: K / 2 of them per row.
+template <int BM, int BN, int WGM, int WGN>
+static int launch_fp8_cfg(const Fp8GemmArgs& a, hipStream_t s) {
+  constexpr int BK = 64, STAGES = 3;
+  using S = DtlSmem<BM, BN, BK, STAGES, WGM, WGN>;
+  GemmBf16Params p;
+  memset(&p, 0, sizeof(p));
+  p.A = (const bf16*)a.A; p.B = (const bf16*)a.B;
+  p.M = a.M; p.N = a.N; p.K = a.K / 2; p.lda = a.lda / 2; p.ldb = a.ldb / 2;
+  EpiParams<bf16>& e = p.epi;
+  e.M = a.M; e.N = a.N; e.out = (bf16*)a.out; e.ldo = a.ldo; e.bias = (const bf16*)a.bias; e.rows_per_batch = 1; e.out_scale = a.out_scale;
+  p.tiles_m = (a.M + BM - 1) / BM; p.tiles_n = (a.N + BN - 1) / BN;
+  GemmArgs shape; memset(&shape, 0, sizeof(shape)); shape.M = a.M; shape.N = a.N;
+  p.group_m = choose_group_m(shape, p.tiles_m, p.tiles_n);
+  p.a_bytes = (uint32_t)((size_t)(a.M - 1) * a.lda + a.K);
+  p.b_bytes = (uint32_t)((size_t)(a.N - 1) * a.ldb + a.K);
+  p.k_tiles_per_split = p.K / BK;
+  auto kern = gemm_bf16_dtl_kernel<BM, BN, BK, STAGES, WGM, WGN, false, false, true>;
+  if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)S::BYTES) != hipSuccess)
+    return set_error(DP_EHIP, "hipFuncSetAttribute(gemm fp8) failed");
+  KScope ks(KK_GEMM_FP8, 2.0 * a.M * a.N * a.K, (double)a.M * a.K + (double)a.N * a.K + 2.0 * a.M * a.N, s, a.M, a.N, a.K);
+  hipLaunchKernelGGL(kern, dim3(p.tiles_m * p.tiles_n, 1, 1), dim3(WGM * WGN * 64), S::BYTES, s, p);
+  return hipGetLastError() == hipSuccess ? DP_OK : set_error(DP_EHIP, "gemm fp8 launch failed");
+}
+
+int launch_gemm_fp8(const Fp8GemmArgs& a, hipStream_t s) {
+  if (a.M <= 0 || a.N <= 0 || a.K <= 0) return set_error(DP_EINVAL, "gemm fp8: non-positive size");
+  if (!a.A || !a.B || !a.out) return set_error(DP_EINVAL, "gemm fp8: null operand");
+  if (a.K % 128) return set_error(DP_EUNSUPPORTED, "gemm fp8: K must be a multiple of 128");
+  if (a.lda % 16 || a.ldb % 16 || a.lda < a.K || a.ldb < a.K) return set_error(DP_EUNSUPPORTED, "gemm fp8: leading dims must be multiples of 16 bytes and at least K");
+  if (a.N % 8 || a.ldo % 8 || a.ldo < a.N) return set_error(DP_EUNSUPPORTED, "gemm fp8: N and ldc must be multiples of 8, ldc >= N");
+  if (!(a.out_scale > 0.f)) return set_error(DP_EINVAL, "gemm fp8: the output scale must be positive");
+  const void* ps[] = {a.A, a.B, a.out, a.bias};
+  for (const void* q : ps) if ((uintptr_t)q % 16) return set_error(DP_EALIGN, "gemm fp8: operands must be 16-byte aligned");
+  if ((size_t)(a.M - 1) * a.lda + a.K >= (1ull << 32) || (size_t)(a.N - 1) * a.ldb + a.K >= (1ull << 32))
+    return set_error(DP_EUNSUPPORTED, "gemm fp8: operand larger than 4 GiB");
+  const long t256 = (long)((a.M + 255) / 256) * ((a.N + 127) / 128);
+  if (t256 >= kCUs / 2) return launch_fp8_cfg<256, 128, 4, 2>(a, s);
+  return launch_fp8_cfg<128, 128, 4, 2>(a, s);
 }
 
 template <int BM, int BN, int WGM, int WGN>

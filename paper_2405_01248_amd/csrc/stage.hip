@@ -1114,6 +1114,17 @@ int dp_op_gemm(int dtype, const void* A, int lda, int a_kmajor, const void* B, i
   return launch_gemm(g, (hipStream_t)hip_stream);
 }
 
+int dp_op_quantize_fp8(const void* x, int ldx, void* q, int ldq, int rows, int cols, float scale, void* hip_stream) {
+  if (!(scale > 0.f) || !(scale < INFINITY)) return set_error(DP_EINVAL, "dp_op_quantize_fp8: the scale must be positive and finite");
+  return launch_quantize_fp8(x, ldx, q, ldq, rows, cols, 1.0f / scale, (hipStream_t)hip_stream);
+}
+
+int dp_op_gemm_fp8(const void* A, int lda, const void* B, int ldb, int M, int N, int K, float out_scale, const void* bias, void* C,
+                   int ldc, void* hip_stream) {
+  Fp8GemmArgs a{A, lda, B, ldb, M, N, K, out_scale, bias, C, ldc};
+  return launch_gemm_fp8(a, (hipStream_t)hip_stream);
+}
+
 int dp_op_attention_fwd(int dtype, int B, int H, int Nq, int Nk, int d_head, int causal, float scale, const void* q, int ldq,
                         const void* k, int ldk, const void* v, int ldv, void* o, int ldo, float* lse, void* hip_stream) {
   if (dtype != DP_F32 && dtype != DP_BF16) return set_error(DP_EINVAL, "unknown dtype");

@@ -155,3 +155,73 @@ def test_attention_forward_and_backward(case):
     errs = {"dq": rel_err(_dev_to_np(gq), rq), "dk": rel_err(_dev_to_np(gk), rk), "dv": rel_err(_dev_to_np(gv), rv)}
     print(f"[attention bwd {_attn_id(case)}] {errs}", flush=True)
     assert max(errs.values()) <= TOL_BF16, errs
+
+
+# ------------------------------------------------------------------ FP8 (OCP E4M3) projection GEMM
+def test_fp8_quantisation_is_bit_exact():
+    """The 8-bit codes are integers decided by floating point: both sides take the decision in fp32 (bf16 input times
+    the fp32 reciprocal of the scale), so the codes must agree bit for bit -- normal and subnormal range, ties,
+    saturation, both signs."""
+    import torch
+    from oracle import fp8
+    from paper_2405_01248_amd import binding as B
+    from paper_2405_01248_amd.harness import _np_to_dev
+    rng = np.random.default_rng(0)
+    rows, cols = 67, 136
+    x = rng.standard_normal((rows, cols)) * np.exp(rng.uniform(-9, 7, size=(rows, cols)))       # 2^-13 .. 2^10 in magnitude
+    table = fp8.e4m3_decode(np.arange(0x7F, dtype=np.uint8))
+    mids = 0.5 * (table[1:] + table[:-1])
+    x[0, :len(mids)] = mids                       # exact ties (the midpoints are bf16-representable: 5 significant bits)
+    x[1, :len(mids)] = -mids
+    x = si.round_bf16(x)
+    for scale in (1.0, 0.3, 7.25):
+        dx = _np_to_dev(x, "bf16")
+        q = torch.zeros((rows, cols), dtype=torch.uint8, device="cuda:0")
+        B.op_quantize_fp8(dx, cols, q, cols, rows, cols, scale)
+        torch.cuda.synchronize()
+        _, want = fp8.quantize(x, scale)
+        got = q.cpu().numpy()
+        bad = np.argwhere(got != want)
+        assert bad.size == 0, (scale, bad[:5], got[tuple(bad[0])], want[tuple(bad[0])], x[tuple(bad[0])])
+
+
+@pytest.mark.parametrize("M,N,K", [(333, 392, 384), (77, 768, 3072), (1300, 136, 128), (2048, 1152, 1152)])
+def test_fp8_gemm_matches_oracle(M, N, K):
+    import torch
+    from oracle import fp8
+    from paper_2405_01248_amd import binding as B
+    from paper_2405_01248_amd.harness import _np_to_dev, _dev_to_np, rel_err
+    rng = np.random.default_rng(M + K)
+    x = si.round_bf16(rng.standard_normal((M, K)))
+    w = si.round_bf16(rng.standard_normal((N, K)) * 0.05)
+    bias = si.round_bf16(rng.standard_normal(N))
+    sx, sw = float(np.abs(x).max()) / 448.0, float(np.abs(w).max()) / 448.0          # per-tensor scales: the largest value maps to 448
+    qx = torch.zeros((M, K), dtype=torch.uint8, device="cuda:0")
+    qw = torch.zeros((N, K), dtype=torch.uint8, device="cuda:0")
+    B.op_quantize_fp8(_np_to_dev(x, "bf16"), K, qx, K, M, K, sx)
+    B.op_quantize_fp8(_np_to_dev(w, "bf16"), K, qw, K, N, K, sw)
+    out = torch.zeros((M, N), dtype=torch.bfloat16, device="cuda:0")
+    out_scale = float(np.float32(sx) * np.float32(sw))
+    B.op_gemm_fp8(qx, K, qw, K, M, N, K, out_scale, _np_to_dev(bias, "bf16"), out, N)
+    torch.cuda.synchronize()
+    (ax, cx), (aw, cw) = fp8.quantize(x, sx), fp8.quantize(w, sw)
+    assert np.array_equal(qx.cpu().numpy(), cx) and np.array_equal(qw.cpu().numpy(), cw)
+    ref = fp8.gemm(ax, aw, out_scale, bias)
+    e = rel_err(_dev_to_np(out), ref)
+    # what the 8-bit operands cost against the unquantised product (reported, not a bar: it is the format's error)
+    e_fmt = rel_err(ref, x @ w.T + bias)
+    print(f"\n[gemm fp8 {M}x{N}x{K}] rel err vs fp8 oracle {e:.2e}; quantisation error of the product itself {e_fmt:.2e}", flush=True)
+    assert e <= TOL_BF16
+
+
+def test_fp8_unsupported_shapes_are_errors():
+    import torch
+    from paper_2405_01248_amd import binding as B
+    a = torch.zeros((64, 192), dtype=torch.uint8, device="cuda:0")
+    o = torch.zeros((64, 64), dtype=torch.bfloat16, device="cuda:0")
+    with pytest.raises(B.DpipeError) as ei:
+        B.op_gemm_fp8(a, 192, a, 192, 64, 64, 192, 1.0, None, o, 64)         # K not a multiple of 128
+    assert ei.value.code == -2
+    with pytest.raises(B.DpipeError) as ei:
+        B.op_gemm_fp8(a, 192, a, 192, 64, 64, 128, 0.0, None, o, 64)
+    assert ei.value.code == -1
