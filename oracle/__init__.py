@@ -8,6 +8,14 @@ layers).  The paper treats each layer as a black box, so the arithmetic here is
 the textbook definition of the named architectures, written out without
 blocking, fusion or reordering.
 
+Further modules, each with its own header and pins:
+  partition.py      backbone partitioning, single (Sec. 4.1 Eq. 1-9, Sec. 4.3 Eq. 17-18) and bidirectional
+                    (Sec. 4.2 Eq. 10-16; the expression for M_CDM is an input: "parity unpinned"), brute force
+  bubbles.py        1F1B bubbles and their filling (Sec. 5, Algorithms 1-2)
+  search.py         the walk over (S, M, D) (Sec. 3, steps 2-5)
+  image_encoder.py  3x3 convolution, GroupNorm, residual and attention blocks of the frozen image encoder
+  fp8.py            OCP E4M3 quantisation and the FP8 projection product (an extension beyond the paper)
+
 Only tests, the smoke check and the bench's cpu_baseline leg may import this
 package.  It shares no code with the HIP path and imports nothing from it.
 
