@@ -184,6 +184,7 @@ static void plan_bwd_scratch(Plan& p, const dp_stage& s, BwdScratch& b) {
 struct StagePlan {
   std::vector<UnetBuf> ub; std::vector<DitBuf> db;
   void *pp0 = nullptr, *pp1 = nullptr, *pp2 = nullptr, *sc_in = nullptr;   // pp*: fp32 block inputs of a no-save forward
+  std::vector<void*> mods;   // DiT, no-save forward: one modulation buffer per block (they are all computed up front)
   BwdScratch bs{};
   size_t bytes = 0;
 };
@@ -199,6 +200,10 @@ static void make_plan(const dp_stage& s, void* base, bool save, StagePlan& sp) {
   else {
     const size_t rb = (size_t)s.T * s.d.d_model * 4;
     sp.pp0 = p.take(rb); sp.pp1 = p.take(rb); sp.pp2 = p.take(rb);
+    if (!unet) {
+      sp.mods.resize(s.d.n_blocks);
+      for (int i = 0; i < s.d.n_blocks; ++i) sp.mods[i] = p.take((size_t)s.d.batch * 6 * s.d.d_model * s.es);
+    }
   }
   sp.bytes = p.off;
 }
@@ -463,11 +468,14 @@ static int unet_block_bwd(const dp_stage& s, const void* const* P, const void* c
 
 // ============================================================ DiT stage
 // save = false (the self-conditioning pass) skips the tensors only the backward reads.
+// mod_side: the modulation vectors of this block (they depend on the conditioning and the weights only) were
+// issued on the side stream as batch mod_batch of *mod_side; otherwise they are computed here.
 static int dit_block_fwd(const dp_stage& s, const void* const* P, const float* x, const void* sc_in, void* y, bool y_is_out,
-                         bool save, DitBuf& u, hipStream_t st) {
+                         bool save, DitBuf& u, hipStream_t st, Side* mod_side = nullptr, int mod_batch = 0) {
   const int dt = s.d.dtype, T = s.T, d = s.d.d_model, ff = s.d.ff_inner, B = s.d.batch, N = s.d.tokens;
   const size_t es = s.es;
-  DP_TRY(launch_gemm(gemm_fwd(dt, sc_in, B, d, P[D_ADA_W], 6 * d, P[D_ADA_B], u.m), st));
+  if (mod_side) mod_side->wait(mod_batch);
+  else DP_TRY(launch_gemm(gemm_fwd(dt, sc_in, B, d, P[D_ADA_W], 6 * d, P[D_ADA_B], u.m), st));
   LnArgs ln; memset(&ln, 0, sizeof(ln));
   ln.dtype = dt; ln.rows = T; ln.d = d; ln.eps = s.d.ln_eps; ln.mod_ld = 6 * d; ln.rows_per_batch = N; ln.x_f32 = 1;
   ln.x = x; ln.y = u.h1; ln.shift = u.m; ln.scale = at(u.m, d, es); ln.mean = u.mean1; ln.rstd = u.rstd1;
@@ -613,17 +621,26 @@ static int run_stage_fwd(dp_stage* s, const void* const* params, const void* x, 
   float* cur = (float*)(save ? (unet ? sp.ub[0].xin : sp.db[0].xin) : sp.pp2);
   // U-Net, saving pass (one K/V buffer per block): the context projections of all blocks run on the
   // side stream while the main stream works through block 0's self-attention
+  // DiT: likewise the modulation vectors m = SiLU(cond) W_ada^T + b_ada of all blocks (32 rows each: latency, not work);
+  // not while profiling, where each block's row has to hold its own projection
   Side sd;
-  sd.main = st; sd.on = s->overlap && unet && save;
+  sd.main = st; sd.on = s->overlap && (unet ? save != 0 : ph == nullptr);
   int kv_batch = 0;
+  std::vector<int> mod_batch((size_t)nb, 0);
   if (sd.on) {
     DP_TRY(ensure_side_stream(s));
     sd.side = s->side; sd.ev = &s->events;
     hipStream_t q = sd.begin();
-    for (int b = 0; b < nb; ++b)
-      DP_TRY(launch_gemm(gemm_fwd(s->d.dtype, cc, s->Tc, s->d.ctx_dim, params[(size_t)b * s->per_block + U_WKV2], 2 * s->d.d_model, nullptr,
-                                  sp.ub[b].kv2), q));
-    kv_batch = sd.end();
+    for (int b = 0; b < nb; ++b) {
+      const void* const* P = params + (size_t)b * s->per_block;
+      if (unet) DP_TRY(launch_gemm(gemm_fwd(s->d.dtype, cc, s->Tc, s->d.ctx_dim, P[U_WKV2], 2 * s->d.d_model, nullptr, sp.ub[b].kv2), q));
+      else {
+        DP_TRY(launch_gemm(gemm_fwd(s->d.dtype, sp.sc_in, s->d.batch, s->d.d_model, P[D_ADA_W], 6 * s->d.d_model, P[D_ADA_B],
+                                    save ? sp.db[b].m : sp.mods[b]), q));
+        mod_batch[b] = sd.end();      // a block waits for its own vectors only
+      }
+    }
+    if (unet) kv_batch = sd.end();
   }
   DP_TRY(launch_cast_to_f32(s->d.dtype, x, cur, act, st));
   for (int b = 0; b < nb; ++b) {
@@ -636,7 +653,11 @@ static int run_stage_fwd(dp_stage* s, const void* const* params, const void* x, 
     else out = (b & 1) ? sp.pp1 : sp.pp0;
     const int slot = save ? b : 0;
     if (unet) DP_TRY(unet_block_fwd(*s, P, cur, cc, out, last, sp.ub[slot], st, sd.on ? &sd : nullptr, kv_batch));
-    else DP_TRY(dit_block_fwd(*s, P, cur, sp.sc_in, out, last, save != 0, sp.db[slot], st));
+    else {
+      DitBuf ub = sp.db[slot];
+      if (!save) ub.m = sp.mods[b];
+      DP_TRY(dit_block_fwd(*s, P, cur, sp.sc_in, out, last, save != 0, ub, st, sd.on ? &sd : nullptr, mod_batch[b]));
+    }
     cur = (float*)out;
   }
   sd.wait(sd.issued);
