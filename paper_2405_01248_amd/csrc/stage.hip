@@ -80,7 +80,7 @@ struct GradPair { float* f; void* h; };
 struct BwdScratch {
   GradPair r[2];
   void *dh, *da, *dqkv, *dq2, *dkv2, *dg, *dg2, *du, *dm_t;
-  float *delta, *dm, *dcond_pre, *partial, *partial_side; size_t partial_bytes;
+  float *delta, *dmv[2], *dcond_pre, *partial, *partial_side; size_t partial_bytes;   // dmv: modulation gradients, alternating by block
   float* dkv_ws; size_t dkv_ws_bytes;     // query-split partials of the cross-attention dK/dV kernel
   void* wt;                               // transposed copies of every block's weight matrices (bf16 stages only)
   float* ln_partial[3]; size_t ln_partial_bytes;   // U-Net: column partials of the three LayerNorm backward kernels (reduced on the side stream)
@@ -164,7 +164,7 @@ static void plan_bwd_scratch(Plan& p, const dp_stage& s, BwdScratch& b) {
     b.dkv_ws_bytes = attn_dkv_ws_bytes(s.d.batch, s.d.n_heads, s.d.ctx_tokens, s.d.d_head);
     b.dkv_ws = (float*)p.take(b.dkv_ws_bytes);
     b.dg = p.take(T * ff * es); b.du = p.take(T * 2 * ff * es); b.dg2 = nullptr;
-    b.dm_t = nullptr; b.dm = nullptr; b.dcond_pre = nullptr;
+    b.dm_t = nullptr; b.dmv[0] = b.dmv[1] = nullptr; b.dcond_pre = nullptr;
     b.ln_partial_bytes = ln_bwd_partial_bytes((int)T, (int)d, (int)T);
     for (int i = 0; i < 3; ++i) b.ln_partial[i] = (float*)p.take(b.ln_partial_bytes);
   } else {
@@ -173,7 +173,8 @@ static void plan_bwd_scratch(Plan& p, const dp_stage& s, BwdScratch& b) {
     b.dg = p.take(T * d * es);          // gated-branch gradients: df2 ...
     b.dg2 = p.take(T * d * es);         // ... and do (separate, so the side stream can still read df2)
     b.du = p.take(T * ff * es);         // df1
-    b.dm = (float*)p.take(B * 6 * d * 4); b.dm_t = p.take(B * 6 * d * es); b.dcond_pre = (float*)p.take(B * d * 4);
+    for (int i = 0; i < 2; ++i) b.dmv[i] = (float*)p.take(B * 6 * d * 4);
+    b.dm_t = p.take(B * 6 * d * es); b.dcond_pre = (float*)p.take(B * d * 4);
   }
   b.wt = s.es == 2 ? p.take((size_t)s.d.n_blocks * wt_block_elems(s) * s.es) : nullptr;
   b.partial_bytes = partial_need(s);
@@ -274,7 +275,7 @@ struct Side {
 };
 
 // Last side batch that reads each reusable backward buffer.
-struct SideReads { int pair[2] = {0, 0}; int du = 0, dq2 = 0, dqkv = 0, dg = 0, dg2 = 0, dm_t = 0; int lnp[3] = {0, 0, 0}; };
+struct SideReads { int pair[2] = {0, 0}; int du = 0, dq2 = 0, dqkv = 0, dg = 0, dg2 = 0; int dmv[2] = {0, 0}; int lnp[3] = {0, 0, 0}; };
 
 static AttnArgs attn_base(const dp_stage& s) {
   AttnArgs a;
@@ -503,7 +504,7 @@ static int dit_block_fwd(const dp_stage& s, const void* const* P, const float* x
 
 // dy lives in pair c; dx1 goes to pair c ^ 1 and the block's dx back to pair c (or dx_final).
 static int dit_block_bwd(const dp_stage& s, const void* const* P, const void* const* WT, void* const* G, int acc, const void* cond, const void* sc_in,
-                         GradPair dy, int c, void* dx_final, float* d_cond, int dcond_acc, DitBuf& u, BwdScratch& b, Side& sd,
+                         GradPair dy, int c, void* dx_final, float* d_cond, int dcond_acc, int par, DitBuf& u, BwdScratch& b, Side& sd,
                          SideReads& rd) {
   const int dt = s.d.dtype, T = s.T, d = s.d.d_model, ff = s.d.ff_inner, B = s.d.batch, N = s.d.tokens;
   const size_t es = s.es;
@@ -521,9 +522,13 @@ static int dit_block_bwd(const dp_stage& s, const void* const* P, const void* co
     DP_TRY(launch_gemm(g, q));
     return db(gy, N, M, pb, q);
   };
+  // modulation gradients of this block: the buffer alternates with the block parity `par`, because the
+  // conditioning path that reads it runs on the side stream while the next block already writes its own
+  float* const dm = b.dmv[par];
+  sd.wait(rd.dmv[par]);
   // ---- MLP branch
   sd.wait(rd.dg);
-  DP_TRY(launch_gate_bwd(dt, dy.f, u.f2, at(u.m, 5 * d, es), 6 * d, b.dg, b.dm + 5 * d, 6 * d, B, N, d, st));
+  DP_TRY(launch_gate_bwd(dt, dy.f, u.f2, at(u.m, 5 * d, es), 6 * d, b.dg, dm + 5 * d, 6 * d, B, N, d, st));
   {
     hipStream_t q = sd.begin();
     DP_TRY(dwb(b.dg, T, d, u.f, ff, D_FC2_W, D_FC2_B, q));
@@ -543,11 +548,11 @@ static int dit_block_bwd(const dp_stage& s, const void* const* P, const void* co
   lb.dtype = dt; lb.rows = T; lb.d = d; lb.partial = b.partial; lb.partial_bytes = b.partial_bytes;
   lb.mod_ld = 6 * d; lb.rows_per_batch = N; lb.dmod_ld = 6 * d;
   lb.dy = b.dh; lb.x = u.x1; lb.mean = u.mean2; lb.rstd = u.rstd2; lb.scale = at(u.m, 4 * d, es); lb.dres = dy.f; set_dx(lb, dx1);
-  lb.dscale = b.dm + 4 * d; lb.dshift = b.dm + 3 * d;
+  lb.dscale = dm + 4 * d; lb.dshift = dm + 3 * d;
   DP_TRY(launch_ln_bwd(lb, st));
   // ---- attention branch
   sd.wait(rd.dg2);
-  DP_TRY(launch_gate_bwd(dt, dx1.f, u.o, at(u.m, 2 * d, es), 6 * d, b.dg2, b.dm + 2 * d, 6 * d, B, N, d, st));
+  DP_TRY(launch_gate_bwd(dt, dx1.f, u.o, at(u.m, 2 * d, es), 6 * d, b.dg2, dm + 2 * d, 6 * d, B, N, d, st));
   {
     hipStream_t q = sd.begin();
     DP_TRY(dwb(b.dg2, T, d, u.a, d, D_WO, D_BO, q));
@@ -568,21 +573,21 @@ static int dit_block_bwd(const dp_stage& s, const void* const* P, const void* co
   DP_TRY(launch_gemm(gemm_dx(dt, b.dqkv, T, 3 * d, P[D_WQKV], WT[D_WQKV], d, b.dh), st));
   lb.dy = b.dh; lb.x = u.xin; lb.mean = u.mean1; lb.rstd = u.rstd1; lb.scale = at(u.m, d, es); lb.dres = dx1.f;
   if (dx_final) { lb.dx = dx_final; lb.dx32 = nullptr; } else set_dx(lb, out);
-  lb.dscale = b.dm + d; lb.dshift = b.dm;
+  lb.dscale = dm + d; lb.dshift = dm;
   DP_TRY(launch_ln_bwd(lb, st));
-  // ---- conditioning path: m = SiLU(cond) W_ada^T + b_ada
-  sd.wait(rd.dm_t);
-  DP_TRY(launch_cast_from_f32(dt, b.dm, b.dm_t, (size_t)B * 6 * d, st));
+  // ---- conditioning path: m = SiLU(cond) W_ada^T + b_ada.  Nothing on the main stream reads its results (d W_ada, d b_ada and
+  // d cond, accumulated over the blocks in issue order), so all of it runs on the side stream.
   {
     hipStream_t q = sd.begin();
+    DP_TRY(launch_cast_from_f32(dt, dm, b.dm_t, (size_t)B * 6 * d, q));
     DP_TRY(dwb(b.dm_t, B, 6 * d, sc_in, d, D_ADA_W, D_ADA_B, q));
-    rd.dm_t = sd.end();
+    g = gemm_base(dt);
+    g.A = b.dm_t; g.B = P[D_ADA_W]; g.M = B; g.N = d; g.K = 6 * d; g.lda = 6 * d; g.ldb = d; g.b_mc = 1;
+    g.out_f32 = b.dcond_pre; g.ldo32 = d; g.accumulate = 0; g.splitk_ws = b.partial_side; g.splitk_ws_bytes = b.partial_bytes;
+    DP_TRY(launch_gemm(g, q));
+    DP_TRY(launch_silu_bwd(dt, b.dcond_pre, cond, d_cond, dcond_acc, (size_t)B * d, q));
+    rd.dmv[par] = sd.end();
   }
-  g = gemm_base(dt);
-  g.A = b.dm_t; g.B = P[D_ADA_W]; g.M = B; g.N = d; g.K = 6 * d; g.lda = 6 * d; g.ldb = d; g.b_mc = 1;
-  g.out_f32 = b.dcond_pre; g.ldo32 = d; g.accumulate = 0; g.splitk_ws = b.partial; g.splitk_ws_bytes = b.partial_bytes;
-  DP_TRY(launch_gemm(g, st));
-  DP_TRY(launch_silu_bwd(dt, b.dcond_pre, cond, d_cond, dcond_acc, (size_t)B * d, st));
   return sd.err;
 }
 
@@ -720,7 +725,7 @@ static int run_stage_bwd(dp_stage* s, const void* const* params, const void* dy,
       ci ^= 1;
       cur = bs.r[ci];
     } else {
-      DP_TRY(dit_block_bwd(*s, P, WT, G, acc, cc, sp.sc_in, cur, ci, dx_final, (float*)d_cond, b != nb - 1, sp.db[b], bs, sd, rd));
+      DP_TRY(dit_block_bwd(*s, P, WT, G, acc, cc, sp.sc_in, cur, ci, dx_final, (float*)d_cond, b != nb - 1, b & 1, sp.db[b], bs, sd, rd));
       cur = bs.r[ci];
     }
     if (ph && ph->ev) sd.wait(sd.issued);      // per-block timing: charge a block's side work to that block
