@@ -83,7 +83,7 @@ struct BwdScratch {
   float *delta, *dmv[2], *dcond_pre, *partial, *partial_side; size_t partial_bytes;   // dmv: modulation gradients, alternating by block
   float* dkv_ws; size_t dkv_ws_bytes;     // query-split partials of the cross-attention dK/dV kernel
   void* wt;                               // transposed copies of every block's weight matrices (bf16 stages only)
-  float* ln_partial[3]; size_t ln_partial_bytes;   // U-Net: column partials of the three LayerNorm backward kernels (reduced on the side stream)
+  float* ln_partial[4]; size_t ln_partial_bytes;   // column partials of the LayerNorm backward kernels, reduced on the side stream (U-Net: one per LayerNorm; DiT: [2 * block parity + LayerNorm])
 };
 
 static void plan_unet_block(Plan& p, const dp_stage& s, UnetBuf& u, bool with_xin) {
@@ -167,9 +167,11 @@ static void plan_bwd_scratch(Plan& p, const dp_stage& s, BwdScratch& b) {
     b.dm_t = nullptr; b.dmv[0] = b.dmv[1] = nullptr; b.dcond_pre = nullptr;
     b.ln_partial_bytes = ln_bwd_partial_bytes((int)T, (int)d, (int)T);
     for (int i = 0; i < 3; ++i) b.ln_partial[i] = (float*)p.take(b.ln_partial_bytes);
+    b.ln_partial[3] = nullptr;
   } else {
     b.dq2 = nullptr; b.dkv2 = nullptr; b.dkv_ws = nullptr; b.dkv_ws_bytes = 0;
-    b.ln_partial_bytes = 0; b.ln_partial[0] = b.ln_partial[1] = b.ln_partial[2] = nullptr;
+    b.ln_partial_bytes = ln_bwd_partial_bytes((int)T, (int)d, s.d.tokens);
+    for (int i = 0; i < 4; ++i) b.ln_partial[i] = (float*)p.take(b.ln_partial_bytes);
     b.dg = p.take(T * d * es);          // gated-branch gradients: df2 ...
     b.dg2 = p.take(T * d * es);         // ... and do (separate, so the side stream can still read df2)
     b.du = p.take(T * ff * es);         // df1
@@ -549,7 +551,10 @@ static int dit_block_bwd(const dp_stage& s, const void* const* P, const void* co
   lb.mod_ld = 6 * d; lb.rows_per_batch = N; lb.dmod_ld = 6 * d;
   lb.dy = b.dh; lb.x = u.x1; lb.mean = u.mean2; lb.rstd = u.rstd2; lb.scale = at(u.m, 4 * d, es); lb.dres = dy.f; set_dx(lb, dx1);
   lb.dscale = dm + 4 * d; lb.dshift = dm + 3 * d;
+  // the sums of the column partials into d scale / d shift feed the conditioning path only: they run with it on the side stream
+  lb.partial = b.ln_partial[2 * par + 1]; lb.partial_bytes = b.ln_partial_bytes; lb.defer_reduce = 1;
   DP_TRY(launch_ln_bwd(lb, st));
+  const LnBwdArgs lb2 = lb;
   // ---- attention branch
   sd.wait(rd.dg2);
   DP_TRY(launch_gate_bwd(dt, dx1.f, u.o, at(u.m, 2 * d, es), 6 * d, b.dg2, dm + 2 * d, 6 * d, B, N, d, st));
@@ -574,11 +579,14 @@ static int dit_block_bwd(const dp_stage& s, const void* const* P, const void* co
   lb.dy = b.dh; lb.x = u.xin; lb.mean = u.mean1; lb.rstd = u.rstd1; lb.scale = at(u.m, d, es); lb.dres = dx1.f;
   if (dx_final) { lb.dx = dx_final; lb.dx32 = nullptr; } else set_dx(lb, out);
   lb.dscale = dm + d; lb.dshift = dm;
+  lb.partial = b.ln_partial[2 * par];
   DP_TRY(launch_ln_bwd(lb, st));
   // ---- conditioning path: m = SiLU(cond) W_ada^T + b_ada.  Nothing on the main stream reads its results (d W_ada, d b_ada and
   // d cond, accumulated over the blocks in issue order), so all of it runs on the side stream.
   {
     hipStream_t q = sd.begin();
+    DP_TRY(launch_ln_bwd_reduce(lb2, q));
+    DP_TRY(launch_ln_bwd_reduce(lb, q));
     DP_TRY(launch_cast_from_f32(dt, dm, b.dm_t, (size_t)B * 6 * d, q));
     DP_TRY(dwb(b.dm_t, B, 6 * d, sc_in, d, D_ADA_W, D_ADA_B, q));
     g = gemm_base(dt);
