@@ -28,6 +28,7 @@ struct GemmBf16Params {
   int k_tiles_per_split;
   int tiles_m, tiles_n;
   int group_m;                 // tile-rows per group of the workgroup-to-tile map (choose_group_m)
+  int split_major;             // register-staged kernel, 1-D grid of tiles x splits: all tiles of one split on one XCD
   // Column sums of the A operand over the contraction (register-staged kernel, contraction-strided A only: the
   // bias gradient next to a weight gradient).  colsum[blockIdx.z * colsum_stride + m]; colsum_acc: add to what is there.
   float* colsum; int colsum_stride; int colsum_acc;
@@ -77,12 +78,23 @@ gemm_bf16_kernel(const GemmBf16Params p) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int g = lane >> 5, l32 = lane & 31;
   const int wm0 = (wave / WGN) * WM, wn0 = (wave % WGN) * WN;
+  // Split-K launches with a multiple of 8 splits come as a 1-D grid: the hardware deals consecutive workgroups
+  // round-robin to the 8 XCDs, so workgroup L takes tile j % T of split (L % 8) + 8 * (j / T), j = L / 8.  All
+  // tiles of a split then run on one XCD, and its slice of both operands is fetched into one L2 only.
+  int bx = blockIdx.x, split = blockIdx.z;
+  if (p.split_major) {
+    const int T = p.tiles_m * p.tiles_n, j = (int)blockIdx.x >> 3;
+    split = ((int)blockIdx.x & 7) + 8 * (j / T);
+    bx = j % T;
+  }
   int tile_m, tile_n;
-  tile_of_block(blockIdx.x, p.tiles_m, p.tiles_n, p.group_m, tile_m, tile_n);
+  tile_of_block(bx, p.tiles_m, p.tiles_n, p.group_m, tile_m, tile_n);
   const int m0 = tile_m * BM, n0 = tile_n * BN;
+  EpiParams<bf16> epi = p.epi;
+  if (p.split_major && epi.partial) epi.partial += (size_t)split * p.M * p.N;   // blockIdx.z is 0 in the 1-D grid
 
   const int total_kt = (p.K + BK - 1) / BK;
-  const int kt_begin = blockIdx.z * p.k_tiles_per_split;
+  const int kt_begin = split * p.k_tiles_per_split;
   const int kt_end = min(total_kt, kt_begin + p.k_tiles_per_split);
 
   // staged tile chunks; out-of-range chunks are loaded from a clamped (valid) address and
@@ -203,13 +215,13 @@ gemm_bf16_kernel(const GemmBf16Params p) {
     if (tid < BM && m0 + tid < p.M) {
       float sum = 0.f;
       for (int g2 = 0; g2 < GROUPS; ++g2) sum += red[g2 * BM + tid];
-      float* o = p.colsum + (size_t)blockIdx.z * p.colsum_stride + m0 + tid;
+      float* o = p.colsum + (size_t)split * p.colsum_stride + m0 + tid;
       *o = p.colsum_acc ? *o + sum : sum;
     }
     __syncthreads();
   }
   float* Cw = reinterpret_cast<float*>(smem_raw) + wave * 32 * S::C_LD;
-  wave_epilogue<TM, TN, WN, S::C_LD>(acc, Cw, p.epi, m0 + wm0, n0 + wn0, lane);
+  wave_epilogue<TM, TN, WN, S::C_LD>(acc, Cw, epi, m0 + wm0, n0 + wn0, lane);
 }
 
 #undef DP_GEMM_LOAD_GLOBAL
@@ -853,7 +865,7 @@ static int launch_bf16_cfg(const GemmArgs& a, hipStream_t s) {
   using S = GemmSmem<BM, BN, BK, WGM, WGN, A_MC, B_MC>;
   GemmBf16Params p;
   p.A = (const bf16*)a.A; p.B = (const bf16*)a.B;
-  p.M = a.M; p.N = a.N; p.K = a.K; p.lda = a.lda; p.ldb = a.ldb;
+  p.M = a.M; p.N = a.N; p.K = a.K; p.lda = a.lda; p.ldb = a.ldb; p.split_major = 0;
   p.epi = make_epi<bf16>(a);
   p.tiles_m = (a.M + BM - 1) / BM; p.tiles_n = (a.N + BN - 1) / BN;
   p.group_m = choose_group_m(a, p.tiles_m, p.tiles_n);
@@ -877,6 +889,8 @@ static int launch_bf16_cfg(const GemmArgs& a, hipStream_t s) {
     else { p.colsum = a.colsum_out; p.colsum_acc = a.accumulate; }
   }
   dim3 grid(p.tiles_m * p.tiles_n, 1, splits);
+  p.split_major = 0;
+  if (splits >= 8 && splits % 8 == 0) { p.split_major = 1; grid = dim3(p.tiles_m * p.tiles_n * splits, 1, 1); }
   const size_t smem = S::BYTES;
   auto kern = gemm_bf16_kernel<BM, BN, BK, WGM, WGN, A_MC, B_MC>;
   static std::atomic<bool> attr_set{false};   // setting it twice is harmless; the flag only saves the call
@@ -905,7 +919,7 @@ static int launch_dtl_cfg(const GemmArgs& a, hipStream_t s) {
   using S = DtlSmem<BM, BN, BK, STAGES, WGM, WGN>;
   GemmBf16Params p;
   p.A = (const bf16*)a.A; p.B = (const bf16*)a.B;
-  p.M = a.M; p.N = a.N; p.K = a.K; p.lda = a.lda; p.ldb = a.ldb;
+  p.M = a.M; p.N = a.N; p.K = a.K; p.lda = a.lda; p.ldb = a.ldb; p.split_major = 0;
   p.epi = make_epi<bf16>(a);
   p.tiles_m = (a.M + BM - 1) / BM; p.tiles_n = (a.N + BN - 1) / BN;
   p.group_m = choose_group_m(a, p.tiles_m, p.tiles_n);
@@ -1011,7 +1025,7 @@ static int launch_dtl16(const GemmArgs& a, hipStream_t s) {
   if (!dtl_addressable(a)) return set_error(DP_EUNSUPPORTED, "gemm: operand too large for the forced direct-to-LDS configuration");
   GemmBf16Params p;
   p.A = (const bf16*)a.A; p.B = (const bf16*)a.B;
-  p.M = a.M; p.N = a.N; p.K = a.K; p.lda = a.lda; p.ldb = a.ldb;
+  p.M = a.M; p.N = a.N; p.K = a.K; p.lda = a.lda; p.ldb = a.ldb; p.split_major = 0;
   p.epi = make_epi<bf16>(a);
   p.tiles_m = (a.M + BM - 1) / BM; p.tiles_n = (a.N + BN - 1) / BN;
   p.group_m = choose_group_m(a, p.tiles_m, p.tiles_n);
