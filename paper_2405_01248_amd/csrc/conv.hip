@@ -24,6 +24,7 @@ struct ConvParams {
   int M, N, K;                   // output pixels, output channels, 9 * C_in
   int tiles_m, tiles_n, group_m;
   int taps_uniform;              // C_in % 64 == 0: a 64-deep k-tile lies inside one filter tap
+  float* gn_partial;             // direct-to-LDS kernel: per-(256-pixel block, channel) sum and sum of squares of the output, or nullptr
   EpiParams<bf16> epi;
 };
 
@@ -152,8 +153,9 @@ __global__ void __launch_bounds__(WGM * WGN * 64) conv3x3_bf16_kernel(const Conv
 // whose tap falls into the padding aims its copy past the end of the buffer, which the hardware answers with
 // zeros.  256 x 128 output tile, eight waves of 64 x 64.  LDS tiles are unpadded with permuted 16-byte
 // chunks, as in the GEMM kernels: chunk c of tile row r sits at position c ^ ((r >> 1) & 7).
+template <int BK_>
 struct ConvDtlSmem {
-  static constexpr int BM = 256, BN = 128, BK = 64, STAGES = 3, WGM = 4, WGN = 2;
+  static constexpr int BM = 256, BN = 128, BK = BK_, STAGES = 3, WGM = 4, WGN = 2;
   static constexpr int A_BYTES = BM * BK * 2, B_BYTES = BN * BK * 2, STAGE = A_BYTES + B_BYTES;
   static constexpr int WN = BN / WGN, C_LD = WN + 4;
   static constexpr size_t TILE_BYTES = (size_t)STAGES * STAGE;
@@ -161,12 +163,19 @@ struct ConvDtlSmem {
   static constexpr size_t BYTES = TILE_BYTES > EPI_BYTES ? TILE_BYTES : EPI_BYTES;
 };
 
-__global__ void __launch_bounds__(512) conv3x3_dtl_kernel(const ConvParams p, uint32_t x_bytes, uint32_t w_bytes) {
-  using S = ConvDtlSmem;
+// Chunk permutation of a tile row (BK / 8 chunks of 16 bytes): BK = 64: key (r >> 1) & 7; BK = 32: (r >> 2) & 3.
+template <int BK> __device__ __forceinline__ int conv_key(int r) { return BK == 32 ? ((r >> 2) & 3) : ((r >> 1) & 7); }
+
+// BK = 64: 144 KB of LDS, one workgroup per CU.  BK = 32: 72 KB, two workgroups per CU (MINW = 4 waves per SIMD), which hide
+// each other's prologue and epilogue where the contraction is short (C_in = 128 .. 256).
+template <int BK_, int MINW>
+__global__ void __launch_bounds__(512, MINW) conv3x3_dtl_kernel(const ConvParams p, uint32_t x_bytes, uint32_t w_bytes) {
+  using S = ConvDtlSmem<BK_>;
   constexpr int BM = S::BM, BN = S::BN, BK = S::BK, STAGES = S::STAGES, WGN = S::WGN, NW = S::WGM * S::WGN, KS = BK / 16, CPR = BK / 8;
   constexpr int WM = BM / S::WGM, WN = BN / WGN, TM = WM / 32, TN = WN / 32;
   constexpr int A_LOADS = S::A_BYTES / 1024 / NW, B_LOADS = S::B_BYTES / 1024 / NW, LOADS = A_LOADS + B_LOADS, PART_LAST = LOADS / KS;
-  static_assert(S::A_BYTES % (1024 * NW) == 0 && S::B_BYTES % (1024 * NW) == 0 && STAGES == 3 && KS == 4, "pipeline shape");
+  static_assert(S::A_BYTES % (1024 * NW) == 0 && S::B_BYTES % (1024 * NW) == 0 && STAGES == 3 && KS % 2 == 0, "pipeline shape");
+  constexpr bool INTERLEAVE = BK == 64;
   constexpr uint32_t OUTSIDE = 0xFFFFFFF0u;          // an offset past any buffer this kernel accepts: the copy delivers zeros
 
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem_raw[];
@@ -184,7 +193,7 @@ __global__ void __launch_bounds__(512) conv3x3_dtl_kernel(const ConvParams p, ui
   unsigned a_taps[A_LOADS];
 #pragma unroll
   for (int j = 0; j < A_LOADS; ++j) {
-    const int r = (wave * A_LOADS + j) * (512 / BK) + lane / CPR, pc = lane % CPR, c = pc ^ ((r >> 1) & 7);
+    const int r = (wave * A_LOADS + j) * (512 / BK) + lane / CPR, pc = lane % CPR, c = pc ^ conv_key<BK>(r);
     const int gm = m0 + r, q = min(gm, p.M - 1);
     const int b = q / (p.Ho * p.Wo), rem = q - b * (p.Ho * p.Wo), ho = rem / p.Wo, wo = rem - ho * p.Wo;
     const int hc = ho * p.stride, wc = wo * p.stride;
@@ -200,7 +209,7 @@ __global__ void __launch_bounds__(512) conv3x3_dtl_kernel(const ConvParams p, ui
   uint32_t vb[B_LOADS];
 #pragma unroll
   for (int j = 0; j < B_LOADS; ++j) {
-    const int r = (wave * B_LOADS + j) * (512 / BK) + lane / CPR, pc = lane % CPR, c = pc ^ ((r >> 1) & 7);
+    const int r = (wave * B_LOADS + j) * (512 / BK) + lane / CPR, pc = lane % CPR, c = pc ^ conv_key<BK>(r);
     vb[j] = 2u * ((uint32_t)min(n0 + r, p.N - 1) * (uint32_t)p.K + (uint32_t)c * 8u);
   }
   // the k-tile whose copies are being issued: its tap and its wave-uniform source offset relative to the tap centre
@@ -240,11 +249,11 @@ __global__ void __launch_bounds__(512) conv3x3_dtl_kernel(const ConvParams p, ui
     const bf16* bs = reinterpret_cast<const bf16*>(smem_raw + (st_) * S::STAGE + S::A_BYTES);                         \
     _Pragma("unroll") for (int i = 0; i < TM; ++i) {                                                                  \
       const int r = wm0 + i * 32 + l32;                                                                               \
-      fa[set_][i] = *reinterpret_cast<const bf16x8*>(as + r * BK + (((2 * (ks_) + g) ^ ((r >> 1) & 7)) * 8));         \
+      fa[set_][i] = *reinterpret_cast<const bf16x8*>(as + r * BK + (((2 * (ks_) + g) ^ conv_key<BK>(r)) * 8));         \
     }                                                                                                                 \
     _Pragma("unroll") for (int j2 = 0; j2 < TN; ++j2) {                                                               \
       const int r = wn0 + j2 * 32 + l32;                                                                              \
-      fb[set_][j2] = *reinterpret_cast<const bf16x8*>(bs + r * BK + (((2 * (ks_) + g) ^ ((r >> 1) & 7)) * 8));        \
+      fb[set_][j2] = *reinterpret_cast<const bf16x8*>(bs + r * BK + (((2 * (ks_) + g) ^ conv_key<BK>(r)) * 8));        \
     }                                                                                                                 \
   }
 #define DPC_MFMAS(set_)                                                                                               \
@@ -277,7 +286,14 @@ __global__ void __launch_bounds__(512) conv3x3_dtl_kernel(const ConvParams p, ui
         barrier_nofence();
         DPC_FRAGS((t + 1) % STAGES, 0, 0);
       }
-      __builtin_amdgcn_sched_barrier(0);
+      if (INTERLEAVE && ks + 1 < KS) {
+        _Pragma("unroll") for (int q_ = 0; q_ < TM * TN; ++q_) {     // one fragment read behind each MFMA, as in the GEMM kernel
+          __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+          __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        }
+      } else {
+        __builtin_amdgcn_sched_barrier(0);
+      }
       DPC_MFMAS(ks & 1);
       __builtin_amdgcn_sched_barrier(0);
       if (refill) DPC_ISSUE_PART(t - 1 + STAGES, ks, KS);
@@ -299,17 +315,87 @@ __global__ void __launch_bounds__(512) conv3x3_dtl_kernel(const ConvParams p, ui
 #undef DPC_ISSUE_PART
   __syncthreads();   // every wave is done with the operand tiles before they are reused below
   float* Cw = reinterpret_cast<float*>(smem_raw) + wave * 32 * S::C_LD;
-  wave_epilogue<TM, TN, WN, S::C_LD>(acc, Cw, p.epi, m0 + wm0, n0 + wn0, lane);
+  if (!p.gn_partial) {
+    wave_epilogue<TM, TN, WN, S::C_LD>(acc, Cw, p.epi, m0 + wm0, n0 + wn0, lane);
+    return;
+  }
+  // Epilogue with the next GroupNorm's first pass folded in: bias, optional residual, bf16 store, and per channel the sum
+  // and the sum of squares of the stored (rounded) values over this tile's 256 pixels.  A lane owns the same 8 columns in
+  // every pass over the rows; the 8 lanes with equal lane % 8 are added by a butterfly, the four waves of a column in
+  // ascending order: nothing depends on timing.
+  static_assert(WN == 64 && S::BYTES >= S::EPI_BYTES + NW * 2 * 64 * 4, "statistics slab");
+  const EpiParams<bf16>& e = p.epi;
+  float cs[8], cq[8];
+#pragma unroll
+  for (int t = 0; t < 8; ++t) { cs[t] = 0.f; cq[t] = 0.f; }
+  const int lc = (lane & 7) * 8, n = n0 + wn0 + lc;
+  bf16x8 bv;
+#pragma unroll
+  for (int t = 0; t < 8; ++t) bv[t] = (bf16)0.f;
+  if (e.bias && n < e.N) bv = *reinterpret_cast<const bf16x8*>(e.bias + n);
+#pragma unroll
+  for (int i = 0; i < TM; ++i) {
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) Cw[(8 * (r >> 2) + 4 * g + (r & 3)) * S::C_LD + j * 32 + l32] = acc[i][j][r];
+    asm volatile("" ::: "memory");
+#pragma unroll 1
+    for (int it = 0; it < 4; ++it) {
+      const int lr = it * 8 + (lane >> 3), m = m0 + wm0 + i * 32 + lr;
+      if (m < e.M && n < e.N) {
+        float v[8];
+        *reinterpret_cast<f32x4*>(&v[0]) = *reinterpret_cast<const f32x4*>(&Cw[lr * S::C_LD + lc]);
+        *reinterpret_cast<f32x4*>(&v[4]) = *reinterpret_cast<const f32x4*>(&Cw[lr * S::C_LD + lc + 4]);
+#pragma unroll
+        for (int t = 0; t < 8; ++t) v[t] += (float)bv[t];
+        if (e.residual) {
+          const bf16x8 rv = *reinterpret_cast<const bf16x8*>((const bf16*)e.residual + (size_t)m * e.ld_res + n);
+#pragma unroll
+          for (int t = 0; t < 8; ++t) v[t] += (float)rv[t];
+        }
+        bf16x8 o;
+#pragma unroll
+        for (int t = 0; t < 8; ++t) {
+          o[t] = (bf16)v[t];
+          const float f = (float)o[t];
+          cs[t] += f; cq[t] = fmaf(f, f, cq[t]);
+        }
+        *reinterpret_cast<bf16x8*>(e.out + (size_t)m * e.ldo + n) = o;
+      }
+    }
+    asm volatile("" ::: "memory");
+  }
+#pragma unroll
+  for (int t = 0; t < 8; ++t) {
+#pragma unroll
+    for (int o = 8; o < 64; o <<= 1) { cs[t] += __shfl_xor(cs[t], o, 64); cq[t] += __shfl_xor(cq[t], o, 64); }
+  }
+  float* stat = reinterpret_cast<float*>(smem_raw + S::EPI_BYTES);      // [wave][sum | sum of squares][64 columns], past the slabs
+  if (lane < 8) {
+#pragma unroll
+    for (int t = 0; t < 8; ++t) { stat[(wave * 2) * 64 + lane * 8 + t] = cs[t]; stat[(wave * 2 + 1) * 64 + lane * 8 + t] = cq[t]; }
+  }
+  __syncthreads();
+  if (tid < 2 * BN) {
+    const int which = tid / BN, c = tid % BN, wcol = c / 64, cc = c % 64;
+    float sum = 0.f;
+#pragma unroll
+    for (int wr = 0; wr < S::WGM; ++wr) sum += stat[((wr * WGN + wcol) * 2 + which) * 64 + cc];
+    if (n0 + c < e.N) p.gn_partial[((size_t)tile_m * e.N + n0 + c) * 2 + which] = sum;
+  }
 }
 
+template <int BK, int MINW>
 static int launch_conv_dtl(ConvParams& p, size_t x_bytes, size_t w_bytes, hipStream_t s) {
-  using S = ConvDtlSmem;
+  using S = ConvDtlSmem<BK>;
   p.tiles_m = (p.M + S::BM - 1) / S::BM; p.tiles_n = (p.N + S::BN - 1) / S::BN;
   const long n = (long)p.tiles_m * p.tiles_n, ppx = (n + 7) / 8;
   p.group_m = (int)std::max<long>(1, std::min<long>((ppx + p.tiles_n / 2) / p.tiles_n, p.tiles_m));
-  if (hipFuncSetAttribute((const void*)conv3x3_dtl_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)S::BYTES) != hipSuccess)
+  auto kern = conv3x3_dtl_kernel<BK, MINW>;
+  if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)S::BYTES) != hipSuccess)
     return set_error(DP_EHIP, "hipFuncSetAttribute(conv) failed");
-  hipLaunchKernelGGL(conv3x3_dtl_kernel, dim3((unsigned)n), dim3(512), S::BYTES, s, p, (uint32_t)x_bytes, (uint32_t)w_bytes);
+  hipLaunchKernelGGL(kern, dim3((unsigned)n), dim3(512), S::BYTES, s, p, (uint32_t)x_bytes, (uint32_t)w_bytes);
   return hipGetLastError() == hipSuccess ? DP_OK : set_error(DP_EHIP, "conv launch failed");
 }
 
@@ -343,6 +429,9 @@ int launch_conv3x3(const ConvArgs& a, hipStream_t s) {
   p.H = a.H; p.W = a.W; p.Cin = a.Cin; p.Ho = Ho; p.Wo = Wo; p.stride = a.stride;
   p.M = (int)M; p.N = a.Cout; p.K = 9 * a.Cin;
   p.taps_uniform = a.Cin % 64 == 0;
+  p.gn_partial = nullptr;
+  if (a.gn_applied) *a.gn_applied = 0;
+  if (a.gn_partial && !a.gn_applied) return set_error(DP_EINVAL, "conv3x3: gn_partial comes with gn_applied");
   EpiParams<bf16>& e = p.epi;
   e.M = p.M; e.N = p.N; e.out = (bf16*)a.y; e.ldo = a.Cout;
   e.out32 = nullptr; e.ldo32 = 0; e.accumulate = 0; e.partial = nullptr;
@@ -354,8 +443,12 @@ int launch_conv3x3(const ConvArgs& a, hipStream_t s) {
   KScope ks(KK_CONV, 2.0 * (double)M * p.N * p.K, by, s, p.M, p.N, p.K);
   // the direct-to-LDS kernel: k-tiles inside one tap, 32-bit byte offsets with room for the "outside" marker
   const size_t x_bytes = 2 * (size_t)a.B * a.H * a.W * a.Cin, w_bytes = 2 * (size_t)p.N * p.K;
-  if (a.Cin % 64 == 0 && a.Cout >= 64 && M >= 2048 && x_bytes < (1ull << 31) && w_bytes < (1ull << 31) && !a.force_staged)
-    return launch_conv_dtl(p, x_bytes, w_bytes, s);
+  if (a.Cin % 64 == 0 && a.Cout >= 64 && M >= 2048 && x_bytes < (1ull << 31) && w_bytes < (1ull << 31) && !a.force_staged) {
+    if (a.gn_partial && (Ho * Wo) % 256 == 0 && ((uintptr_t)a.gn_partial % 16) == 0) { p.gn_partial = a.gn_partial; *a.gn_applied = 1; }
+    // measured on the layers of the 512 x 512 encoder: C_in = 128 at stride 1 runs 18 % faster (C_out = 256: 7 %) on the
+    // two-workgroups-per-CU variant; from C_in = 256 on, and at stride 2, the deeper k-tile wins
+    return (a.Cin <= 128 && a.stride == 1) ? launch_conv_dtl<32, 4>(p, x_bytes, w_bytes, s) : launch_conv_dtl<64, 2>(p, x_bytes, w_bytes, s);
+  }
   if (a.Cout <= 64) return launch_conv_cfg<128, 64, 4, 1>(p, s);
   if (M >= 256L * 256) return launch_conv_cfg<256, 128, 4, 2>(p, s);
   return launch_conv_cfg<128, 128, 2, 2>(p, s);

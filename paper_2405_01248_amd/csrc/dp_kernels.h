@@ -84,6 +84,11 @@ struct ConvArgs {
   int B, H, W, Cin, Cout, stride;
   const void* x; const void* w; const void* bias; const void* residual; void* y;
   int force_staged;   // 1: always the register-staged kernel (measurement and tests of that path)
+  // Optional: per-channel sums and sums of squares of the output (as rounded to bf16) per block of 256 output pixels, in
+  // the layout of GroupNorm's first pass, gn_partial[((b * (HoWo / 256) + block) * Cout + c) * 2 + {0, 1}], so that a
+  // GroupNorm of y can skip that pass.  Only when Ho * Wo is a multiple of 256 and the direct-to-LDS kernel runs:
+  // *gn_applied (required with gn_partial) tells whether they were written.
+  float* gn_partial; int* gn_applied;
 };
 int launch_conv3x3(const ConvArgs& a, hipStream_t s);
 
@@ -96,6 +101,8 @@ struct GroupNormArgs {
   int B, HW, C, groups; float eps; int silu;
   const void* x; const void* gamma; const void* beta; void* y;
   float* scratch; size_t scratch_bytes;
+  // partial sums already produced by the convolution that wrote x (ConvArgs::gn_partial): ready_blocks blocks per sample
+  const float* ready_partial; int ready_blocks;
 };
 size_t gn_scratch_bytes(int B, int HW, int C);
 int launch_groupnorm(const GroupNormArgs& a, hipStream_t s);

@@ -136,10 +136,11 @@ int launch_groupnorm(const GroupNormArgs& a, hipStream_t s) {
   float* partial = a.scratch;
   float* ab = (float*)((char*)a.scratch + align_up((size_t)a.B * nb * a.C * 2 * sizeof(float), 256));
   const double bytes = 2.0 * 2.0 * (double)a.B * a.HW * a.C + 2.0 * (double)a.B * a.HW * a.C;   // x read twice, y written once
-  KScope ks(KK_GROUPNORM, 0.0, bytes, s, a.B * a.HW, a.C, a.groups);
-  hipLaunchKernelGGL(gn_partial_kernel, dim3(nb, a.B), dim3(GN_THREADS), 0, s, (const bf16*)a.x, a.HW, a.C, ppb, partial);
-  hipLaunchKernelGGL(gn_finalize_kernel, dim3((a.B * a.groups + 3) / 4), dim3(256), 0, s, partial, nb, a.HW, a.C, a.groups, a.eps,
-                     (const bf16*)a.gamma, (const bf16*)a.beta, ab, a.B);
+  const bool ready = a.ready_partial != nullptr && a.ready_blocks > 0;
+  KScope ks(KK_GROUPNORM, 0.0, ready ? bytes - 2.0 * (double)a.B * a.HW * a.C : bytes, s, a.B * a.HW, a.C, a.groups);
+  if (!ready) hipLaunchKernelGGL(gn_partial_kernel, dim3(nb, a.B), dim3(GN_THREADS), 0, s, (const bf16*)a.x, a.HW, a.C, ppb, partial);
+  hipLaunchKernelGGL(gn_finalize_kernel, dim3((a.B * a.groups + 3) / 4), dim3(256), 0, s, ready ? a.ready_partial : partial, ready ? a.ready_blocks : nb,
+                     a.HW, a.C, a.groups, a.eps, (const bf16*)a.gamma, (const bf16*)a.beta, ab, a.B);
   const size_t chunks = (size_t)a.B * a.HW * (a.C / 8);
   hipLaunchKernelGGL(gn_apply_kernel, dim3((unsigned)((chunks + 255) / 256)), dim3(256), 0, s, (const bf16*)a.x, (bf16*)a.y, ab, (size_t)a.HW,
                      a.C, chunks, a.silu);
@@ -204,6 +205,8 @@ namespace dp {
 struct ImgBuf {
   void *ping, *pong, *t1, *t2, *t3, *q, *k, *v, *a, *probs;
   float *scores, *gn; size_t gn_bytes; size_t bytes;
+  // GroupNorm partial sums written by the convolution that produced tensor stat_of (stat_blocks blocks of 256 pixels per sample)
+  float* gnc; size_t gnc_bytes; const void* stat_of; int stat_blocks;
 };
 
 static size_t layer_act_elems(const dp_image_encoder& e, int l, int n) {
@@ -214,15 +217,17 @@ static size_t layer_act_elems(const dp_image_encoder& e, int l, int n) {
 
 static void plan_image(const dp_image_encoder& e, void* base, int lb, int le, int n, ImgBuf& b) {
   Plan p(base);
-  size_t maxact = 0, gn = 0, attn_rows = 0, attn_px = 0; int attn_c = 0;
+  size_t maxact = 0, gn = 0, gnc = 0, attn_rows = 0, attn_px = 0; int attn_c = 0;
   for (int l = lb; l < le; ++l) {
     maxact = std::max(maxact, layer_act_elems(e, l, n));
+    gnc = std::max(gnc, (size_t)n * ((size_t)e.h[l + 1] * e.w[l + 1] / 256 + 1) * e.c[l + 1] * 2 * sizeof(float));
     const int HW = e.h[l] * e.w[l];
     if (e.layers[l].kind != DP_IMG_CONV) gn = std::max(gn, std::max(gn_scratch_bytes(n, HW, e.c[l]), gn_scratch_bytes(n, HW, e.c[l + 1])));
     if (e.layers[l].kind == DP_IMG_ATTN) { attn_rows = std::max(attn_rows, (size_t)n * HW); attn_px = std::max(attn_px, (size_t)HW); attn_c = std::max(attn_c, e.c[l]); }
   }
   b.ping = p.take(maxact * 2); b.pong = p.take(maxact * 2); b.t1 = p.take(maxact * 2); b.t2 = p.take(maxact * 2); b.t3 = p.take(maxact * 2);
   b.gn_bytes = gn; b.gn = gn ? (float*)p.take(gn) : nullptr;
+  b.gnc_bytes = gnc; b.gnc = (float*)p.take(gnc); b.stat_of = nullptr; b.stat_blocks = 0;
   if (attn_rows) {
     const size_t qb = attn_rows * attn_c * 2;
     b.q = p.take(qb); b.k = p.take(qb); b.v = p.take((size_t)attn_px * attn_c * 2); b.a = p.take(qb);   // v: one sample's values, transposed
@@ -244,12 +249,20 @@ static int image_layer(const dp_image_encoder& e, int l, const void* const* P, c
   auto conv = [&](const void* x, int cin, int cout, int stride, const void* wt, const void* bias, const void* res, void* y) {
     ConvArgs a; memset(&a, 0, sizeof(a));
     a.dtype = BF16; a.B = n; a.H = H; a.W = W; a.Cin = cin; a.Cout = cout; a.stride = stride; a.x = x; a.w = wt; a.bias = bias; a.residual = res; a.y = y;
-    return launch_conv3x3(a, st);
+    // the convolution's epilogue can produce the first pass of a GroupNorm over its output
+    const int out_px = ((H - 1) / stride + 1) * ((W - 1) / stride + 1);
+    int applied = 0;
+    if (w.gnc && (size_t)n * (out_px / 256 + 1) * cout * 2 * sizeof(float) <= w.gnc_bytes) { a.gn_partial = w.gnc; a.gn_applied = &applied; }
+    w.stat_of = nullptr;
+    const int rc = launch_conv3x3(a, st);
+    if (rc == DP_OK && applied) { w.stat_of = y; w.stat_blocks = out_px / 256; }
+    return rc;
   };
   auto gn = [&](const void* x, int ch, const void* gamma, const void* beta, int silu, void* y) {
     GroupNormArgs a; memset(&a, 0, sizeof(a));
     a.dtype = BF16; a.B = n; a.HW = HW; a.C = ch; a.groups = e.d.groups; a.eps = e.d.gn_eps; a.silu = silu;
     a.x = x; a.gamma = gamma; a.beta = beta; a.y = y; a.scratch = w.gn; a.scratch_bytes = w.gn_bytes;
+    if (w.stat_of == x && w.stat_blocks > 0) { a.ready_partial = w.gnc; a.ready_blocks = w.stat_blocks; }
     return launch_groupnorm(a, st);
   };
   switch (L.kind) {
@@ -291,6 +304,7 @@ static int image_layer(const dp_image_encoder& e, int l, const void* const* P, c
       }
       GemmArgs g = linear(w.a, R, ci, P[8], ci, P[9], dst);
       g.residual = src; g.ld_res = ci;
+      w.stat_of = nullptr;          // dst is written by a GEMM: no statistics come with it
       return launch_gemm(g, st);
     }
     default: return set_error(DP_EINVAL, "unknown image layer kind");
