@@ -368,6 +368,9 @@ def main():
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="cfg2", choices=["cfg2", "cfg3", "cfg4", "cfg5", "cfg6"])
+    ap.add_argument("--slices", default=None,
+                    help="encoder workloads (cfg5, cfg6): comma-separated slice sizes to time instead of all of the configuration's "
+                         "(the full global batch is always included); keeps counter-collection runs short")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-others", action="store_true", help="skip the short runs of the other workloads")
     ap.add_argument("--serial", action="store_true",
@@ -409,11 +412,20 @@ def main():
         return ds, {"samples_per_s": cfg.batch / sec, "ms_per_step": sec * 1e3, "median_ms_per_step": med["ms"], "tflops": fl / sec / 1e12,
                     "mfma_peak_frac": fl / sec / MFMA_PEAK}
 
+    def slice_list(c):
+        if not args.slices:
+            return c.slices
+        want = sorted({int(v) for v in args.slices.split(",")} | {c.global_batch})
+        bad = [b for b in want if b <= 0 or c.global_batch % b]
+        if bad:
+            raise SystemExit(f"--slices: {bad} do not divide the global batch {c.global_batch}")
+        return tuple(want)
+
     def run_encoder(steps, warmup):
         c = si.CONFIG5
         de = DeviceEncoder(c, si.make_encoder_inputs(c, seed=0))
         out = {}
-        for b in c.slices:
+        for b in slice_list(c):
             sec = timed(lambda: de.run_slices(b), steps, warmup)
             out[str(b)] = {"samples_per_s": c.global_batch / sec, "ms_per_global_batch": sec * 1e3,
                            "ms_per_call": sec * 1e3 * b / c.global_batch,
@@ -425,7 +437,7 @@ def main():
         c = si.CONFIG6
         de = DeviceImageEncoder(c, si.make_image_encoder_inputs(c, seed=0, weight_std=0.0))
         out = {}
-        for b in c.slices:
+        for b in slice_list(c):
             sec = timed(lambda: de.run_slices(b), steps, warmup)
             out[str(b)] = {"samples_per_s": c.global_batch / sec, "ms_per_global_batch": sec * 1e3,
                            "ms_per_call": sec * 1e3 * b / c.global_batch,
