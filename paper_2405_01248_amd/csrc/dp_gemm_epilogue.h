@@ -201,16 +201,22 @@ __device__ __forceinline__ void wave_epilogue(const f32x16 (&acc)[TM][TN], float
 // to the 8 XCDs; the remap gives each XCD a contiguous range of tiles, ordered in groups of
 // `group_m` tile-rows (walked down the rows, then to the next column) so that concurrently running
 // tiles share A and B panels in that XCD's L2.
-__device__ __forceinline__ void tile_of_block(int pid, int tiles_m, int tiles_n, int group_m, int& tm, int& tn) {
-  const int n = tiles_m * tiles_n;
+// First half: position of workgroup pid in an order of n items in which every XCD owns a contiguous range.
+__device__ __forceinline__ int xcd_contiguous_id(int pid, int n) {
   const int ppx = (n + 7) / 8, tall = n % 8;
   const int xcd = pid % 8, local = pid / 8;
-  const int id = (tall == 0 || xcd < tall) ? xcd * ppx + local : tall * ppx + (xcd - tall) * (ppx - 1) + local;
+  return (tall == 0 || xcd < tall) ? xcd * ppx + local : tall * ppx + (xcd - tall) * (ppx - 1) + local;
+}
+// Second half: tile of position id in the grouped order.
+__device__ __forceinline__ void tile_of_id(int id, int tiles_m, int tiles_n, int group_m, int& tm, int& tn) {
   const int in_group = group_m * tiles_n;
   const int first_m = (id / in_group) * group_m;
   const int gsz = min(tiles_m - first_m, group_m);
   tm = first_m + (id % in_group) % gsz;
   tn = (id % in_group) / gsz;
+}
+__device__ __forceinline__ void tile_of_block(int pid, int tiles_m, int tiles_n, int group_m, int& tm, int& tn) {
+  tile_of_id(xcd_contiguous_id(pid, tiles_m * tiles_n), tiles_m, tiles_n, group_m, tm, tn);
 }
 
 }  // namespace dp

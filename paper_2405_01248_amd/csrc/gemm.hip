@@ -28,7 +28,7 @@ struct GemmBf16Params {
   int k_tiles_per_split;
   int tiles_m, tiles_n;
   int group_m;                 // tile-rows per group of the workgroup-to-tile map (choose_group_m)
-  int split_major;             // register-staged kernel, 1-D grid of tiles x splits: all tiles of one split on one XCD
+  int split_major;             // register-staged kernel: number of splits of a 1-D grid over (split, tile) pairs, 0 = plain grid of tiles
   // Column sums of the A operand over the contraction (register-staged kernel, contraction-strided A only: the
   // bias gradient next to a weight gradient).  colsum[blockIdx.z * colsum_stride + m]; colsum_acc: add to what is there.
   float* colsum; int colsum_stride; int colsum_acc;
@@ -78,17 +78,18 @@ gemm_bf16_kernel(const GemmBf16Params p) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int g = lane >> 5, l32 = lane & 31;
   const int wm0 = (wave / WGN) * WM, wn0 = (wave % WGN) * WN;
-  // Split-K launches with a multiple of 8 splits come as a 1-D grid: the hardware deals consecutive workgroups
-  // round-robin to the 8 XCDs, so workgroup L takes tile j % T of split (L % 8) + 8 * (j / T), j = L / 8.  All
-  // tiles of a split then run on one XCD, and its slice of both operands is fetched into one L2 only.
-  int bx = blockIdx.x, split = blockIdx.z;
+  // Split-K launches come as a 1-D grid over (split, tile) pairs in split-major order, of which every XCD takes a
+  // contiguous range (the hardware deals consecutive workgroups round-robin to the 8 XCDs): the tiles of one split,
+  // which read the same slice of both operands, run on one or two XCDs instead of all eight.
+  int split = 0, tile_m, tile_n;
   if (p.split_major) {
-    const int T = p.tiles_m * p.tiles_n, j = (int)blockIdx.x >> 3;
-    split = ((int)blockIdx.x & 7) + 8 * (j / T);
-    bx = j % T;
+    const int T = p.tiles_m * p.tiles_n;
+    const int id = xcd_contiguous_id(blockIdx.x, T * p.split_major);
+    split = id / T;
+    tile_of_id(id % T, p.tiles_m, p.tiles_n, p.group_m, tile_m, tile_n);
+  } else {
+    tile_of_block(blockIdx.x, p.tiles_m, p.tiles_n, p.group_m, tile_m, tile_n);
   }
-  int tile_m, tile_n;
-  tile_of_block(bx, p.tiles_m, p.tiles_n, p.group_m, tile_m, tile_n);
   const int m0 = tile_m * BM, n0 = tile_n * BN;
   EpiParams<bf16> epi = p.epi;
   if (p.split_major && epi.partial) epi.partial += (size_t)split * p.M * p.N;   // blockIdx.z is 0 in the 1-D grid
@@ -890,7 +891,7 @@ static int launch_bf16_cfg(const GemmArgs& a, hipStream_t s) {
   }
   dim3 grid(p.tiles_m * p.tiles_n, 1, splits);
   p.split_major = 0;
-  if (splits >= 8 && splits % 8 == 0) { p.split_major = 1; grid = dim3(p.tiles_m * p.tiles_n * splits, 1, 1); }
+  if (splits > 1) { p.split_major = splits; grid = dim3(p.tiles_m * p.tiles_n * splits, 1, 1); }
   const size_t smem = S::BYTES;
   auto kern = gemm_bf16_kernel<BM, BN, BK, WGM, WGN, A_MC, B_MC>;
   static std::atomic<bool> attr_set{false};   // setting it twice is harmless; the flag only saves the call
