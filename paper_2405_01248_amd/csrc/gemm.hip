@@ -799,7 +799,7 @@ static int choose_splits_epi(long tiles, int kt) {
 
 size_t gemm_epi_splitk_ws_bytes(int M, int N, int K) {
   size_t worst = 0;
-  const int shapes[][2] = {{128, 128}, {256, 128}, {256, 256}};
+  const int shapes[][2] = {{64, 64}, {128, 128}, {256, 128}, {256, 256}};
   for (const auto& t : shapes) {
     const long tiles = (long)((M + t[0] - 1) / t[0]) * ((N + t[1] - 1) / t[1]);
     const int sp = choose_splits_epi(tiles, K / 64);
@@ -828,6 +828,11 @@ static int choose_cfg(int M, int N, int K, bool a_mc, bool b_mc, bool dtl_ok) {
     // and L1 bytes per FLOP; 256x160 (16x16x32 MFMA tiles) exists for widths that leave the others
     // with padded columns or a badly filled last round (N = 320, 1152, 2560).  A 192x128 tile for
     // N = 640 (215 instead of 160 workgroups) won 5 % on bare GEMMs and lost 2 % inside the stage.
+    // A few hundred rows and a short contraction (the frozen encoder's projections on a partial batch): 64x64 tiles give
+    // 4x the workgroups of 128x128 ones, each with a quarter of the work per k-tile, and no split-K pass is needed.
+    // Measured on the text encoder (samples/s at slices of 1 / 4 / 16): 1538 / 5617 / 19148 -> 1733 / 6490 / 20040; with more
+    // 128x128 tiles than the limits below the larger tiles win again (16 samples, K = 3072: -6 % with 64x64 tiles).
+    if (dtl64 && (long)((M + 127) / 128) * ((N + 127) / 128) <= (K <= 1024 ? 100 : 24)) return 15;
     struct Cand { int idx, bm, bn; float eff; bool need64; };
     // Two 256x128 workgroups per CU (configuration 12, three 32-deep buffers) hide each other's prologue,
     // epilogue and barrier stalls: the shorter the contraction and the more tiles per CU, the more it pays.
@@ -1105,7 +1110,7 @@ int launch_gemm(const GemmArgs& a, hipStream_t s) {
           return set_error(DP_EINVAL, "gemm: bad fused GeGLU backward arguments");
       }
     }
-    int cfg = (a.force_cfg > 0 && a.force_cfg <= kNumCfgs + 9) ? a.force_cfg - 1 : choose_cfg(a.M, a.N, a.K, a.a_mc != 0, a.b_mc != 0, dtl_addressable(a));
+    int cfg = (a.force_cfg > 0 && a.force_cfg <= kNumCfgs + 11) ? a.force_cfg - 1 : choose_cfg(a.M, a.N, a.K, a.a_mc != 0, a.b_mc != 0, dtl_addressable(a));
     if (a.geglu == 1 && (cfg < 6 || cfg > 14 || cfg == 11)) {   // cfg 11 has no column permutation in its loader either
       // the column permutation lives in the direct-to-LDS loader
       const long t256x256 = (long)((a.M + 255) / 256) * ((a.N + 255) / 256);
@@ -1126,6 +1131,12 @@ int launch_gemm(const GemmArgs& a, hipStream_t s) {
       case 12: return launch_dtl_layout<256, 128, 32, 3, 4, 2>(a, s);   // 72 KB of LDS: two workgroups per CU
       case 13: return launch_dtl_layout<128, 128, 64, 3, 4, 2>(a, s);   // eight waves on a 128x128 tile
       case 14: return launch_dtl_layout<128, 128, 32, 4, 4, 2>(a, s);
+      // small tiles: many workgroups for problems of a few hundred rows (contraction-contiguous operands only: the chunk
+      // permutation of a contraction-strided tile needs at least 128 columns)
+      case 15:
+      case 16:
+        if (a.a_mc || a.b_mc || a.K % 64) return set_error(DP_EUNSUPPORTED, "gemm: the forced 64-row configurations need contraction-contiguous operands and K % 64 == 0");
+        return cfg == 15 ? launch_dtl_cfg<64, 64, 64, 3, 2, 2, false, false>(a, s) : launch_dtl_cfg<64, 128, 64, 3, 2, 2, false, false>(a, s);
       default: break;
     }
     return launch_bf16_layout<128, 128, 64, 2, 2>(a, s);
