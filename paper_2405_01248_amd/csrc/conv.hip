@@ -443,14 +443,15 @@ int launch_conv3x3(const ConvArgs& a, hipStream_t s) {
   KScope ks(KK_CONV, 2.0 * (double)M * p.N * p.K, by, s, p.M, p.N, p.K);
   // the direct-to-LDS kernel: k-tiles inside one tap, 32-bit byte offsets with room for the "outside" marker
   const size_t x_bytes = 2 * (size_t)a.B * a.H * a.W * a.Cin, w_bytes = 2 * (size_t)p.N * p.K;
-  if (a.Cin % 64 == 0 && a.Cout >= 64 && M >= 2048 && x_bytes < (1ull << 31) && w_bytes < (1ull << 31) && !a.force_staged) {
+  // (the choice depends on one sample's pixel count, not on the number of samples: a slice of any size takes the same kernel)
+  if (a.Cin % 64 == 0 && a.Cout >= 64 && (long)Ho * Wo >= 1024 && x_bytes < (1ull << 31) && w_bytes < (1ull << 31) && !a.force_staged) {
     if (a.gn_partial && (Ho * Wo) % 256 == 0 && ((uintptr_t)a.gn_partial % 16) == 0) { p.gn_partial = a.gn_partial; *a.gn_applied = 1; }
     // measured on the layers of the 512 x 512 encoder: C_in = 128 at stride 1 runs 18 % faster (C_out = 256: 7 %) on the
     // two-workgroups-per-CU variant; from C_in = 256 on, and at stride 2, the deeper k-tile wins
     return (a.Cin <= 128 && a.stride == 1) ? launch_conv_dtl<32, 4>(p, x_bytes, w_bytes, s) : launch_conv_dtl<64, 2>(p, x_bytes, w_bytes, s);
   }
   if (a.Cout <= 64) return launch_conv_cfg<128, 64, 4, 1>(p, s);
-  if (M >= 256L * 256) return launch_conv_cfg<256, 128, 4, 2>(p, s);
+  if ((long)Ho * Wo >= 16384) return launch_conv_cfg<256, 128, 4, 2>(p, s);
   return launch_conv_cfg<128, 128, 2, 2>(p, s);
 }
 

@@ -59,6 +59,8 @@ struct GemmArgs {
   const void* ln_gamma; const void* ln_beta; void* ln_out; float ln_eps; int* ln_applied;
 };
 int launch_gemm(const GemmArgs& a, hipStream_t s);
+// Index (as force_cfg - 1) of the tile configuration launch_gemm would choose for y = x W^T with M rows, contraction-contiguous bf16 operands.
+int gemm_choose_cfg(int M, int N, int K);
 bool gemm_geglu_fwd_supported(const GemmArgs& a);
 bool gemm_colsum_supported(const GemmArgs& a);
 size_t gemm_splitk_ws_bytes(int M, int N, int K);   // upper bound for out_f32 GEMMs

@@ -1079,6 +1079,8 @@ bool gemm_geglu_fwd_supported(const GemmArgs& a) {
          a.N == 2 * a.geglu_inner && a.ldo >= a.geglu_inner && (!a.pre_out || a.ld_pre >= a.N) && dtl_addressable(a);
 }
 
+int gemm_choose_cfg(int M, int N, int K) { return choose_cfg(M, N, K, false, false, true); }
+
 int launch_gemm(const GemmArgs& a, hipStream_t s) {
   if (a.ln_applied) *a.ln_applied = 0;
   if (a.M <= 0 || a.N <= 0 || a.K <= 0) return set_error(DP_EINVAL, "gemm: non-positive size");

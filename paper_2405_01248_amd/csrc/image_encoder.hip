@@ -112,7 +112,8 @@ __global__ void __launch_bounds__(256) gn_apply_kernel(const bf16* __restrict__ 
 
 static int gn_blocks(int B, int HW, int C, int* pix_per_block) {
   const int C8 = C / 8, PPB = GN_THREADS / C8;
-  long want = std::max<long>(1, std::min<long>(HW / std::max(1, PPB * 4), std::max(1, 2048 / std::max(1, B))));
+  // (the block count per sample does not depend on the number of samples: a sample's sums are grouped the same way in every slice)
+  long want = std::max<long>(1, std::min<long>(HW / std::max(1, PPB * 4), 256));
   const int ppb = (int)((HW + want - 1) / want);
   if (pix_per_block) *pix_per_block = ppb;
   return (HW + ppb - 1) / ppb;
@@ -236,9 +237,12 @@ static void plan_image(const dp_image_encoder& e, void* base, int lb, int le, in
   b.bytes = p.off;
 }
 
-static GemmArgs linear(const void* x, long M, int K, const void* W, int N, const void* bias, void* y) {
+// y = x W^T + bias on M rows.  rows_per_sample > 0: the tile configuration is chosen for one sample's rows, so that the
+// arithmetic behind a sample's outputs is the same whatever the number of samples in the call.
+static GemmArgs linear(const void* x, long M, int K, const void* W, int N, const void* bias, void* y, int rows_per_sample = 0) {
   GemmArgs g; memset(&g, 0, sizeof(g));
   g.dtype = BF16; g.A = x; g.B = W; g.M = (int)M; g.N = N; g.K = K; g.lda = K; g.ldb = K; g.out = y; g.ldo = N; g.bias = bias;
+  if (rows_per_sample > 0) g.force_cfg = 1 + gemm_choose_cfg(rows_per_sample, N, K);
   return g;
 }
 
@@ -277,7 +281,7 @@ static int image_layer(const dp_image_encoder& e, int l, const void* const* P, c
       DP_TRY(gn(w.t2, co, P[4], P[5], 1, w.t1));
       const void* skip = src;
       if (ci != co) {
-        DP_TRY(launch_gemm(linear(src, (long)n * HW, ci, P[8], co, P[9], w.t3), st));
+        DP_TRY(launch_gemm(linear(src, (long)n * HW, ci, P[8], co, P[9], w.t3, HW), st));
         skip = w.t3;
       }
       return conv(w.t1, co, co, 1, P[6], P[7], skip, dst);
@@ -285,8 +289,8 @@ static int image_layer(const dp_image_encoder& e, int l, const void* const* P, c
     case DP_IMG_ATTN: {
       const long R = (long)n * HW;
       DP_TRY(gn(src, ci, P[0], P[1], 0, w.t1));
-      DP_TRY(launch_gemm(linear(w.t1, R, ci, P[2], ci, P[3], w.q), st));
-      DP_TRY(launch_gemm(linear(w.t1, R, ci, P[4], ci, P[5], w.k), st));
+      DP_TRY(launch_gemm(linear(w.t1, R, ci, P[2], ci, P[3], w.q, HW), st));
+      DP_TRY(launch_gemm(linear(w.t1, R, ci, P[4], ci, P[5], w.k, HW), st));
       const float scale = 1.0f / sqrtf((float)ci);
       for (int s = 0; s < n; ++s) {
         const size_t off = (size_t)s * HW * ci * 2;
@@ -302,7 +306,7 @@ static int image_layer(const dp_image_encoder& e, int l, const void* const* P, c
         g = linear(w.probs, HW, HW, w.v, ci, P[7], (char*)w.a + off);      // a_s = probs v_s + b_v
         DP_TRY(launch_gemm(g, st));
       }
-      GemmArgs g = linear(w.a, R, ci, P[8], ci, P[9], dst);
+      GemmArgs g = linear(w.a, R, ci, P[8], ci, P[9], dst, HW);
       g.residual = src; g.ld_res = ci;
       w.stat_of = nullptr;          // dst is written by a GEMM: no statistics come with it
       return launch_gemm(g, st);

@@ -29,7 +29,7 @@ SINGLE_LAYERS = [
     _one_layer("conv", 24, 8, 1, (5, 5)),                    # taps not aligned with k-tiles; the 8-channel output head width
     _one_layer("conv", 128, 128, 2, (34, 33), batch=1),
     _one_layer("conv", 16, 16, 1, (1, 1)),                   # a single pixel: only the centre tap is inside
-    # large enough for the direct-to-LDS kernel (C_in a multiple of 64, at least 2048 output pixels): padding taps
+    # large enough for the direct-to-LDS kernel (C_in a multiple of 64, at least 1024 output pixels per sample): padding taps
     # answered by out-of-range copies, ragged pixel and channel tiles, stride 2, a half-empty channel tile
     _one_layer("conv", 64, 128, 1, (48, 50)),
     _one_layer("conv", 64, 192, 2, (65, 70)),
@@ -40,7 +40,17 @@ SINGLE_LAYERS = [
     _one_layer("resnet", 32, 72, 1, (7, 9), groups=8),       # with the 1x1 skip convolution
     _one_layer("attn", 64, 64, 1, (8, 9), batch=3),          # 72 pixels: ragged tiles of the score and value products
     _one_layer("norm_conv", 64, 8, 1, (10, 6)),
+    # pixel counts per sample that are multiples of 256 on the direct-to-LDS convolution: its epilogue also produces the
+    # statistics pass of the GroupNorm that follows (inside the residual block: the second norm reads them)
+    _one_layer("resnet", 64, 128, 1, (32, 48)),              # 64-deep k-tiles; with the 1x1 skip convolution
+    _one_layer("resnet", 128, 128, 1, (32, 32), batch=2, groups=32),   # 32-deep k-tiles, two workgroups per CU
+    _one_layer("resnet", 64, 192, 1, (32, 32), batch=3, groups=8),     # a half-empty output-channel tile; odd sample count
 ]
+
+# The statistics handed from one layer to the next: a stride-2 convolution (the norm of the residual block that follows
+# reads the sums its epilogue wrote, at the halved resolution), then a block whose last convolution feeds the output head's norm.
+CHAIN = si.ImageEncoderConfig("chain_conv_resnet_head", "bf16", 64, 64, 64, 8,
+                              (("conv", 64, 64, 2), ("resnet", 64, 128, 1), ("norm_conv", 128, 8, 1)), 3)
 
 
 @pytest.mark.parametrize("cfg", SINGLE_LAYERS, ids=lambda c: c.name)
@@ -56,6 +66,24 @@ def test_single_layers_match_oracle(cfg):
     e = rel_err(got, ref)
     print(f"\n[{cfg.name}] rel err {e:.2e}, rel L2 {rel_l2(got, ref):.2e}", flush=True)
     assert np.isfinite(got).all() and e <= TOL
+
+
+def test_statistics_pass_from_layer_to_layer():
+    import torch
+    from paper_2405_01248_amd.harness import DeviceImageEncoder, rel_err, rel_l2
+    inp = si.make_image_encoder_inputs(CHAIN, seed=11, randomize_norm=True, weight_std=0.0)
+    de = DeviceImageEncoder(CHAIN, inp)
+    de.run_slices(CHAIN.global_batch)
+    torch.cuda.synchronize()
+    whole = de.output()
+    ref = _oracle(CHAIN, inp)
+    e = rel_err(whole, ref)
+    print(f"\n[{CHAIN.name}] rel err {e:.2e}, rel L2 {rel_l2(whole, ref):.2e}", flush=True)
+    assert np.isfinite(whole).all() and e <= TOL
+    # one sample at a time gives the same bits: the sums are taken per sample and per tile, in a fixed order
+    de.run_slices(1)
+    torch.cuda.synchronize()
+    assert np.array_equal(de.output(), whole)
 
 
 SMALL = si.ImageEncoderConfig("small_img_enc_bf16", "bf16", 24, 16, 8, 4, si.vae_encoder_layers(16, (1, 2, 2), 8, 8), 5)
