@@ -121,7 +121,14 @@ int dp_encoder_create(const dp_encoder_desc* desc, dp_encoder** out);
 void dp_encoder_destroy(dp_encoder* enc);
 int dp_encoder_param_count(const dp_encoder* enc);
 int dp_encoder_param_shape(const dp_encoder* enc, int idx, int64_t shape[2], const char** name);
-/* Workspace bytes for a call on at most max_samples samples. */
+/* Batch-invariant mode (off by default).  on = 1: tile shapes and split-K factors of every projection are chosen
+ * for one sample's rows instead of the slice's, so that a sample's result is bit-identical for every num_samples --
+ * what the partial-batch scheme of Sec. 5 (a layer's samples spread over bubbles of different sizes, outputs
+ * concatenated) needs if the concatenation has to equal the full-batch result bit for bit.  Large slices then run
+ * slower (the choice that suits 77 rows does not suit 4928) and the workspace grows: set the mode before asking
+ * for the workspace size. */
+int dp_encoder_set_batch_invariant(dp_encoder* enc, int on);
+/* Workspace bytes for a call on at most max_samples samples (in the encoder's current mode). */
 size_t dp_encoder_workspace_bytes(const dp_encoder* enc, int max_samples);
 
 /* Runs layers [layer_begin, layer_end) on samples [sample_offset, sample_offset + num_samples)
@@ -133,10 +140,11 @@ size_t dp_encoder_workspace_bytes(const dp_encoder* enc, int max_samples);
  * sample ranges can be issued in any order or in different bubbles.  num_samples = 0 is a valid
  * empty slice: arguments are still checked, nothing is launched.
  * Invariance: a sample's result is bit-identical run to run and for equal num_samples, whatever the
- * offset and the other samples hold.  It is NOT bit-identical across different num_samples (the
+ * offset and the other samples hold.  By default it is NOT bit-identical across different num_samples (the
  * projections split their contraction by a factor chosen from the row count, which re-associates fp32
  * sums: relative L2 difference of the bf16 output about 4e-3, maximum below 2^-7 of its range), nor across
- * a layer range cut into two calls (the hidden state is rounded to the storage type at the cut). */
+ * a layer range cut into two calls (the hidden state is rounded to the storage type at the cut).
+ * dp_encoder_set_batch_invariant(enc, 1) restores bit-identity across num_samples at a cost in speed. */
 int encoder_fwd_partial(dp_encoder* enc, const void* const* params, const int32_t* ids, void* hidden,
                         int global_batch, int layer_begin, int layer_end, int sample_offset, int num_samples,
                         void* workspace, size_t workspace_bytes, void* hip_stream);

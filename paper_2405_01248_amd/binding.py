@@ -105,7 +105,7 @@ class KernelTime(C.Structure):
 KERNEL_KINDS = {0: "gemm_nt", 1: "gemm_nn", 2: "gemm_tn", 3: "attn_fwd", 4: "attn_bwd_dq", 5: "attn_bwd_dkv", 6: "ln_fwd",
                 7: "ln_bwd", 8: "geglu_fwd", 9: "geglu_bwd", 10: "reduce", 11: "other", 12: "gemm_f32", 13: "attn_f32", 14: "conv3x3", 15: "groupnorm", 16: "softmax_rows", 17: "gemm_fp8"}
 
-EXPORTS = ["dp_stage_create", "dp_stage_destroy", "dp_stage_set_overlap", "dp_stage_set_fusion", "dp_stage_param_count", "dp_stage_param_shape", "dp_stage_workspace_bytes",
+EXPORTS = ["dp_stage_create", "dp_stage_destroy", "dp_stage_set_overlap", "dp_stage_set_fusion", "dp_encoder_set_batch_invariant", "dp_stage_param_count", "dp_stage_param_shape", "dp_stage_workspace_bytes",
            "stage_fwd", "stage_bwd", "dp_encoder_create", "dp_encoder_destroy", "dp_encoder_param_count",
            "dp_encoder_param_shape", "dp_encoder_workspace_bytes", "encoder_fwd_partial", "dp_stage_profile",
            "dp_encoder_profile", "dp_image_encoder_create", "dp_image_encoder_destroy", "dp_image_encoder_param_count",
@@ -134,6 +134,7 @@ def load_library():
     lib.dp_stage_destroy.argtypes = [vp]; lib.dp_stage_destroy.restype = None
     lib.dp_stage_set_overlap.argtypes = [vp, i]
     lib.dp_stage_set_fusion.argtypes = [vp, i]
+    lib.dp_encoder_set_batch_invariant.argtypes = [vp, i]
     lib.dp_stage_param_count.argtypes = [vp]
     lib.dp_stage_param_shape.argtypes = [vp, i, C.POINTER(C.c_int64), C.POINTER(C.c_char_p)]
     lib.dp_stage_workspace_bytes.argtypes = [vp, i]; lib.dp_stage_workspace_bytes.restype = sz
@@ -286,6 +287,9 @@ class Encoder(_Handle):
 
     def param_specs(self):
         return self._specs("dp_encoder_param_count", "dp_encoder_param_shape")
+
+    def set_batch_invariant(self, on: bool):
+        _check(load_library().dp_encoder_set_batch_invariant(self._h, int(on)))
 
     def workspace_bytes(self, max_samples: int) -> int:
         return load_library().dp_encoder_workspace_bytes(self._h, max_samples)

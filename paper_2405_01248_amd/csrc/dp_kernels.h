@@ -43,6 +43,8 @@ struct GemmArgs {
   // bias gradient, from the tiles the kernel stages anyway.  Only where gemm_colsum_supported() says so.
   float* colsum_out;
   int force_cfg;             // 0 = choose by shape; 1 + index forces a tile configuration (measurement only)
+  int choice_rows;           // > 0: tile configuration and split-K factor are chosen as if the problem had this many rows
+                             // (a caller whose rows are independent samples gets the same arithmetic per row for any M)
   // GeGLU fused into the epilogue (bf16 only; bias is the only other epilogue term allowed):
   //   geglu = 1 (forward): B [2 * geglu_inner, K] and bias are the [value | gate] projection, N = 2 * geglu_inner.
   //     pre_out [M, N] (optional) receives the projection u, out [M, geglu_inner] = value * gelu(gate), both taken
@@ -65,6 +67,7 @@ bool gemm_geglu_fwd_supported(const GemmArgs& a);
 bool gemm_colsum_supported(const GemmArgs& a);
 size_t gemm_splitk_ws_bytes(int M, int N, int K);   // upper bound for out_f32 GEMMs
 size_t gemm_epi_splitk_ws_bytes(int M, int N, int K);   // same for storage-dtype outputs (0: such a GEMM is never split)
+size_t gemm_epi_splitk_ws_bytes_for(int M, int N, int K, int choice_rows);   // with GemmArgs::choice_rows
 
 // ---------------------------------------------------------------- FP8 (OCP E4M3) projection GEMM
 // q[i, j] = e4m3(clamp(x[i, j] * inv_scale, -448, 448)), round to nearest even; x [rows, cols] in bf16 (row stride ldx

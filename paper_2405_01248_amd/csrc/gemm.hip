@@ -797,6 +797,18 @@ static int choose_splits_epi(long tiles, int kt) {
   return s;
 }
 
+// The same when the choice is made for `choice_rows` rows (GemmArgs::choice_rows) but M rows are computed.
+size_t gemm_epi_splitk_ws_bytes_for(int M, int N, int K, int choice_rows) {
+  size_t worst = 0;
+  const int shapes[][2] = {{64, 64}, {128, 128}, {256, 128}, {256, 256}};
+  for (const auto& t : shapes) {
+    const long tiles = (long)((choice_rows + t[0] - 1) / t[0]) * ((N + t[1] - 1) / t[1]);
+    const int sp = choose_splits_epi(tiles, K / 64);
+    if (sp > 1) worst = std::max(worst, (size_t)sp * M * N * sizeof(float));
+  }
+  return worst;
+}
+
 size_t gemm_epi_splitk_ws_bytes(int M, int N, int K) {
   size_t worst = 0;
   const int shapes[][2] = {{64, 64}, {128, 128}, {256, 128}, {256, 256}};
@@ -937,11 +949,16 @@ static int launch_dtl_cfg(const GemmArgs& a, hipStream_t s) {
   if (a.out_f32) {
     splits = choose_splits((long)p.tiles_m * p.tiles_n, kt * BK / 64, S::BYTES <= 80 * 1024 ? 2 * kCUs : kCUs);
   } else if (a.splitk_ws && a.geglu != 1) {
-    splits = choose_splits_epi((long)p.tiles_m * p.tiles_n, kt * BK / 64);
+    const long rows_for_choice = a.choice_rows > 0 ? a.choice_rows : a.M;
+    splits = choose_splits_epi(((rows_for_choice + BM - 1) / BM) * p.tiles_n, kt * BK / 64);
   }
   if (splits > 1) {
     const size_t need = (size_t)splits * a.M * a.N * sizeof(float);
-    if (!a.splitk_ws || a.splitk_ws_bytes < need) splits = 1;
+    if (!a.splitk_ws || a.splitk_ws_bytes < need) {
+      // with choice_rows the split is part of what the caller asked for: running unsplit would silently change the sums
+      if (a.choice_rows > 0) return set_error(DP_EWORKSPACE, "gemm: split-K workspace too small for the split chosen from choice_rows");
+      splits = 1;
+    }
   }
   p.k_tiles_per_split = (kt + splits - 1) / splits;
   splits = (kt + p.k_tiles_per_split - 1) / p.k_tiles_per_split;
@@ -1112,7 +1129,7 @@ int launch_gemm(const GemmArgs& a, hipStream_t s) {
           return set_error(DP_EINVAL, "gemm: bad fused GeGLU backward arguments");
       }
     }
-    int cfg = (a.force_cfg > 0 && a.force_cfg <= kNumCfgs + 11) ? a.force_cfg - 1 : choose_cfg(a.M, a.N, a.K, a.a_mc != 0, a.b_mc != 0, dtl_addressable(a));
+    int cfg = (a.force_cfg > 0 && a.force_cfg <= kNumCfgs + 11) ? a.force_cfg - 1 : choose_cfg(a.choice_rows > 0 ? a.choice_rows : a.M, a.N, a.K, a.a_mc != 0, a.b_mc != 0, dtl_addressable(a));
     if (a.geglu == 1 && (cfg < 6 || cfg > 14 || cfg == 11)) {   // cfg 11 has no column permutation in its loader either
       // the column permutation lives in the direct-to-LDS loader
       const long t256x256 = (long)((a.M + 255) / 256) * ((a.N + 255) / 256);

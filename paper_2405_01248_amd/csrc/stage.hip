@@ -58,6 +58,7 @@ struct dp_encoder {
   dp_encoder_desc d;
   std::vector<ParamInfo> params;
   size_t es;
+  int batch_invariant = 0;   // tile shapes and split-K factors chosen for one sample's rows, whatever the slice size
 };
 
 namespace dp {
@@ -754,8 +755,8 @@ static void plan_encoder(const dp_encoder& e, void* base, int samples, EncBuf& b
   b.res = (float*)p.take(R * d * 4);
   // partial sums of the projections that are split along the contraction on small batches
   const int Ri = (int)R, di = e.d.d_model, ff = e.d.ff_inner;
-  b.splitk_bytes = std::max(std::max(gemm_epi_splitk_ws_bytes(Ri, 3 * di, di), gemm_epi_splitk_ws_bytes(Ri, di, di)),
-                            std::max(gemm_epi_splitk_ws_bytes(Ri, ff, di), gemm_epi_splitk_ws_bytes(Ri, di, ff)));
+  auto sk = [&](int N, int K) { return e.batch_invariant ? gemm_epi_splitk_ws_bytes_for(Ri, N, K, e.d.seq) : gemm_epi_splitk_ws_bytes(Ri, N, K); };
+  b.splitk_bytes = std::max(std::max(sk(3 * di, di), sk(di, di)), std::max(sk(ff, di), sk(di, ff)));
   b.splitk = b.splitk_bytes ? (float*)p.take(b.splitk_bytes) : nullptr;
   b.bytes = p.off;
 }
@@ -773,8 +774,9 @@ static int encoder_block(const dp_encoder& e, const void* const* P, float* x, in
   ln.dtype = dt; ln.rows = R; ln.d = d; ln.eps = e.d.ln_eps; ln.x_f32 = 1;
   ln.x = x; ln.y = w.h; ln.gamma = P[E_LN1_G]; ln.beta = P[E_LN1_B];
   if (!h_ready) DP_TRY(launch_ln_fwd(ln, st));
+  const int choice_rows = e.batch_invariant ? seq : 0;
   GemmArgs g = gemm_fwd(dt, w.h, R, d, P[E_WQKV], 3 * d, P[E_BQKV], w.qkv);
-  g.splitk_ws = w.splitk; g.splitk_ws_bytes = w.splitk_bytes;
+  g.splitk_ws = w.splitk; g.splitk_ws_bytes = w.splitk_bytes; g.choice_rows = choice_rows;
   DP_TRY(launch_gemm(g, st));
   AttnArgs a; memset(&a, 0, sizeof(a));
   a.dtype = dt; a.B = n; a.H = e.d.n_heads; a.Nq = seq; a.Nk = seq; a.d_head = e.d.d_head; a.causal = e.d.causal;
@@ -783,7 +785,7 @@ static int encoder_block(const dp_encoder& e, const void* const* P, float* x, in
   DP_TRY(launch_attn_fwd(a, st));
   int ln_applied = 0;
   g = gemm_fwd(dt, w.a, R, d, P[E_WO], d, P[E_BO], x);
-  g.splitk_ws = w.splitk; g.splitk_ws_bytes = w.splitk_bytes;
+  g.splitk_ws = w.splitk; g.splitk_ws_bytes = w.splitk_bytes; g.choice_rows = choice_rows;
   g.residual = x; g.ld_res = d; g.residual_f32 = 1; g.out_fused_f32 = 1;
   if (fuse_ln) { g.ln_gamma = P[E_LN2_G]; g.ln_beta = P[E_LN2_B]; g.ln_out = w.h; g.ln_eps = e.d.ln_eps; g.ln_applied = &ln_applied; }
   DP_TRY(launch_gemm(g, st));
@@ -792,12 +794,12 @@ static int encoder_block(const dp_encoder& e, const void* const* P, float* x, in
     DP_TRY(launch_ln_fwd(ln, st));
   }
   g = gemm_fwd(dt, w.h, R, d, P[E_FC1_W], ff, P[E_FC1_B], w.f);
-  g.splitk_ws = w.splitk; g.splitk_ws_bytes = w.splitk_bytes;
+  g.splitk_ws = w.splitk; g.splitk_ws_bytes = w.splitk_bytes; g.choice_rows = choice_rows;
   g.act = 3;
   DP_TRY(launch_gemm(g, st));
   ln_applied = 0;
   g = gemm_fwd(dt, w.f, R, ff, P[E_FC2_W], d, P[E_FC2_B], x);
-  g.splitk_ws = w.splitk; g.splitk_ws_bytes = w.splitk_bytes;
+  g.splitk_ws = w.splitk; g.splitk_ws_bytes = w.splitk_bytes; g.choice_rows = choice_rows;
   g.residual = x; g.ld_res = d; g.residual_f32 = 1; g.out_fused_f32 = 1;
   if (fuse_ln && next_gamma) { g.ln_gamma = next_gamma; g.ln_beta = next_beta; g.ln_out = next_out; g.ln_eps = e.d.ln_eps; g.ln_applied = &ln_applied; }
   DP_TRY(launch_gemm(g, st));
@@ -938,6 +940,12 @@ void dp_stage_destroy(dp_stage* st) {
 int dp_stage_set_overlap(dp_stage* st, int enabled) {
   if (!st) return set_error(DP_EINVAL, "stage handle is NULL");
   st->overlap = enabled != 0;
+  return DP_OK;
+}
+
+int dp_encoder_set_batch_invariant(dp_encoder* enc, int on) {
+  if (!enc) return set_error(DP_EINVAL, "encoder handle is NULL");
+  enc->batch_invariant = on != 0;
   return DP_OK;
 }
 

@@ -505,3 +505,44 @@ def test_encoder_full_size_all_slice_sizes():
         print(f"[{cfg.name}] slice {b} vs slice {cfg.slices[0]}: max {e_sl:.2e}, rel L2 {l2_sl:.2e}, "
               f"{100.0 * np.mean(out == first):.1f} % of elements identical", flush=True)
         assert e_sl <= 2.0 ** -7 and l2_sl <= 6e-3, (e_sl, l2_sl)
+
+
+def test_encoder_batch_invariant_mode_is_bitwise_across_slice_sizes():
+    # dp_encoder_set_batch_invariant: tile shapes and split-K factors chosen for one sample's rows, so the
+    # concatenation of partial batches of any sizes (Sec. 5) equals the full-batch result bit for bit
+    import torch
+    from paper_2405_01248_amd.harness import DeviceEncoder, rel_err
+    cfg = si.CONFIG5
+    inp = si.make_encoder_inputs(cfg, seed=0)
+    ref = _oracle_encoder(cfg, inp)
+    de = DeviceEncoder(cfg, inp)
+    de.enc.set_batch_invariant(True)
+    de.ws = torch.empty(de.enc.workspace_bytes(de.gb), dtype=torch.uint8, device=de.device)     # the mode changes the workspace size
+    first = None
+    for b in cfg.slices:
+        de.hidden.zero_()
+        de.run_slices(b)
+        torch.cuda.synchronize()
+        out = de.output()
+        e = rel_err(out, ref)
+        print(f"\n[{cfg.name}, batch-invariant] slice {b}: rel err {e:.3e}", flush=True)
+        assert e <= TOL[cfg.dtype]
+        if first is None:
+            first = out
+        assert np.array_equal(out, first), f"slice {b} differs from slice {cfg.slices[0]}"
+    # mixed slice sizes and a layer range continued by a call of another size, all in one buffer
+    de.hidden.zero_()
+    le = cfg.n_layers + 2
+    for off, n in ((0, 16), (16, 1), (17, 4), (21, 43)):
+        de.enc.fwd_partial(de.params, de.ids, de.hidden, de.gb, 0, le, off, n, de.ws)
+    torch.cuda.synchronize()
+    assert np.array_equal(de.output(), first)
+    # a workspace sized for the default mode is refused rather than silently changing the sums
+    from paper_2405_01248_amd import binding as B
+    de.enc.set_batch_invariant(False)
+    small = torch.empty(de.enc.workspace_bytes(de.gb), dtype=torch.uint8, device=de.device)
+    de.enc.set_batch_invariant(True)
+    if small.numel() < de.ws.numel():
+        with pytest.raises(B.DpipeError) as ei:
+            de.enc.fwd_partial(de.params, de.ids, de.hidden, de.gb, 0, le, 0, de.gb, small)
+        assert ei.value.code < 0
