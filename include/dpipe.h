@@ -121,13 +121,15 @@ int dp_encoder_create(const dp_encoder_desc* desc, dp_encoder** out);
 void dp_encoder_destroy(dp_encoder* enc);
 int dp_encoder_param_count(const dp_encoder* enc);
 int dp_encoder_param_shape(const dp_encoder* enc, int idx, int64_t shape[2], const char** name);
-/* Batch-invariant mode (off by default).  on = 1: tile shapes and split-K factors of every projection are chosen
- * for one sample's rows instead of the slice's, so that a sample's result is bit-identical for every num_samples --
- * what the partial-batch scheme of Sec. 5 (a layer's samples spread over bubbles of different sizes, outputs
- * concatenated) needs if the concatenation has to equal the full-batch result bit for bit.  Large slices then run
- * slower (the choice that suits 77 rows does not suit 4928) and the workspace grows: set the mode before asking
- * for the workspace size. */
-int dp_encoder_set_batch_invariant(dp_encoder* enc, int on);
+/* Batch-invariant modes (mode 0, the default, is off).  In modes 1 and 2 a sample's result is bit-identical for
+ * every num_samples -- what the partial-batch scheme of Sec. 5 (a layer's samples spread over bubbles of different
+ * sizes, outputs concatenated) needs if the concatenation has to equal the full-batch result bit for bit.
+ *   mode 1: tile shapes and split-K factors of every projection are chosen for one sample's rows instead of the
+ *           slice's.  Full speed on slices of up to 4 samples, 12 % slower at 16, 33 % at 64; larger workspace.
+ *   mode 2: no split-K, and only tiles built on the 32x32x16 matrix instruction (their shape does not change the
+ *           order in which an output element's products are added).  Full speed at 64 samples, 20 % slower on small slices.
+ * Set the mode before asking for the workspace size; any other value is DP_EINVAL. */
+int dp_encoder_set_batch_invariant(dp_encoder* enc, int mode);
 /* Workspace bytes for a call on at most max_samples samples (in the encoder's current mode). */
 size_t dp_encoder_workspace_bytes(const dp_encoder* enc, int max_samples);
 
@@ -144,7 +146,7 @@ size_t dp_encoder_workspace_bytes(const dp_encoder* enc, int max_samples);
  * projections split their contraction by a factor chosen from the row count, which re-associates fp32
  * sums: relative L2 difference of the bf16 output about 4e-3, maximum below 2^-7 of its range), nor across
  * a layer range cut into two calls (the hidden state is rounded to the storage type at the cut).
- * dp_encoder_set_batch_invariant(enc, 1) restores bit-identity across num_samples at a cost in speed. */
+ * dp_encoder_set_batch_invariant restores bit-identity across num_samples at a cost in speed. */
 int encoder_fwd_partial(dp_encoder* enc, const void* const* params, const int32_t* ids, void* hidden,
                         int global_batch, int layer_begin, int layer_end, int sample_offset, int num_samples,
                         void* workspace, size_t workspace_bytes, void* hip_stream);

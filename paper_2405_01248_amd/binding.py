@@ -288,7 +288,7 @@ class Encoder(_Handle):
     def param_specs(self):
         return self._specs("dp_encoder_param_count", "dp_encoder_param_shape")
 
-    def set_batch_invariant(self, on: bool):
+    def set_batch_invariant(self, on):
         _check(load_library().dp_encoder_set_batch_invariant(self._h, int(on)))
 
     def workspace_bytes(self, max_samples: int) -> int:

@@ -44,7 +44,8 @@ struct GemmArgs {
   float* colsum_out;
   int force_cfg;             // 0 = choose by shape; 1 + index forces a tile configuration (measurement only)
   int choice_rows;           // > 0: tile configuration and split-K factor are chosen as if the problem had this many rows
-                             // (a caller whose rows are independent samples gets the same arithmetic per row for any M)
+                             // (a caller whose rows are independent samples gets the same arithmetic per row for any M);
+                             // < 0: the same guarantee by other means: no split-K and 32x32x16 tiles only, shape chosen from M
   // GeGLU fused into the epilogue (bf16 only; bias is the only other epilogue term allowed):
   //   geglu = 1 (forward): B [2 * geglu_inner, K] and bias are the [value | gate] projection, N = 2 * geglu_inner.
   //     pre_out [M, N] (optional) receives the projection u, out [M, geglu_inner] = value * gelu(gate), both taken

@@ -828,7 +828,7 @@ size_t gemm_epi_splitk_ws_bytes(int M, int N, int K) {
 //    direct-to-LDS tiles when they fill the CUs, else the register-staged kernel;
 //  - dW = dy^T x (both operands read through the transposing LDS load): register-staged 128x128 tiles,
 //    two workgroups per CU; 256x256 direct-to-LDS tiles for large M and N.
-static int choose_cfg(int M, int N, int K, bool a_mc, bool b_mc, bool dtl_ok) {
+static int choose_cfg(int M, int N, int K, bool a_mc, bool b_mc, bool dtl_ok, bool allow16 = true) {
   const long t256x256 = (long)((M + 255) / 256) * ((N + 255) / 256);
   const long t256x128 = (long)((M + 255) / 256) * ((N + 127) / 128);
   const bool dtl32 = dtl_ok && K % 32 == 0, dtl64 = dtl_ok && K % 64 == 0;
@@ -855,6 +855,7 @@ static int choose_cfg(int M, int N, int K, bool a_mc, bool b_mc, bool dtl_ok) {
     float best_cost = 0.f;
     for (const Cand& c : cands) {
       if (c.need64 ? !dtl64 : !dtl32) continue;
+      if (c.idx == 11 && !allow16) continue;       // the 16x16x32 instruction sums a k-step of 32 at once: other bits than the 32x32x16 tiles
       const long tiles = (long)((M + c.bm - 1) / c.bm) * ((N + c.bn - 1) / c.bn);
       const float cost = (float)((tiles + kCUs - 1) / kCUs) * (float)(c.bm * c.bn) / c.eff;
       if (best < 0 || cost < best_cost) { best = c.idx; best_cost = cost; }
@@ -950,7 +951,7 @@ static int launch_dtl_cfg(const GemmArgs& a, hipStream_t s) {
     splits = choose_splits((long)p.tiles_m * p.tiles_n, kt * BK / 64, S::BYTES <= 80 * 1024 ? 2 * kCUs : kCUs);
   } else if (a.splitk_ws && a.geglu != 1) {
     const long rows_for_choice = a.choice_rows > 0 ? a.choice_rows : a.M;
-    splits = choose_splits_epi(((rows_for_choice + BM - 1) / BM) * p.tiles_n, kt * BK / 64);
+    splits = a.choice_rows < 0 ? 1 : choose_splits_epi(((rows_for_choice + BM - 1) / BM) * p.tiles_n, kt * BK / 64);
   }
   if (splits > 1) {
     const size_t need = (size_t)splits * a.M * a.N * sizeof(float);
@@ -1129,7 +1130,7 @@ int launch_gemm(const GemmArgs& a, hipStream_t s) {
           return set_error(DP_EINVAL, "gemm: bad fused GeGLU backward arguments");
       }
     }
-    int cfg = (a.force_cfg > 0 && a.force_cfg <= kNumCfgs + 11) ? a.force_cfg - 1 : choose_cfg(a.choice_rows > 0 ? a.choice_rows : a.M, a.N, a.K, a.a_mc != 0, a.b_mc != 0, dtl_addressable(a));
+    int cfg = (a.force_cfg > 0 && a.force_cfg <= kNumCfgs + 11) ? a.force_cfg - 1 : choose_cfg(a.choice_rows > 0 ? a.choice_rows : a.M, a.N, a.K, a.a_mc != 0, a.b_mc != 0, dtl_addressable(a), a.choice_rows >= 0);
     if (a.geglu == 1 && (cfg < 6 || cfg > 14 || cfg == 11)) {   // cfg 11 has no column permutation in its loader either
       // the column permutation lives in the direct-to-LDS loader
       const long t256x256 = (long)((a.M + 255) / 256) * ((a.N + 255) / 256);

@@ -58,7 +58,7 @@ struct dp_encoder {
   dp_encoder_desc d;
   std::vector<ParamInfo> params;
   size_t es;
-  int batch_invariant = 0;   // tile shapes and split-K factors chosen for one sample's rows, whatever the slice size
+  int batch_invariant = 0;   // 1: tile shapes and split-K factors chosen for one sample's rows; 2: no split-K, 32x32x16 tiles only
 };
 
 namespace dp {
@@ -755,7 +755,7 @@ static void plan_encoder(const dp_encoder& e, void* base, int samples, EncBuf& b
   b.res = (float*)p.take(R * d * 4);
   // partial sums of the projections that are split along the contraction on small batches
   const int Ri = (int)R, di = e.d.d_model, ff = e.d.ff_inner;
-  auto sk = [&](int N, int K) { return e.batch_invariant ? gemm_epi_splitk_ws_bytes_for(Ri, N, K, e.d.seq) : gemm_epi_splitk_ws_bytes(Ri, N, K); };
+  auto sk = [&](int N, int K) { return e.batch_invariant == 1 ? gemm_epi_splitk_ws_bytes_for(Ri, N, K, e.d.seq) : gemm_epi_splitk_ws_bytes(Ri, N, K); };
   b.splitk_bytes = std::max(std::max(sk(3 * di, di), sk(di, di)), std::max(sk(ff, di), sk(di, ff)));
   b.splitk = b.splitk_bytes ? (float*)p.take(b.splitk_bytes) : nullptr;
   b.bytes = p.off;
@@ -774,7 +774,7 @@ static int encoder_block(const dp_encoder& e, const void* const* P, float* x, in
   ln.dtype = dt; ln.rows = R; ln.d = d; ln.eps = e.d.ln_eps; ln.x_f32 = 1;
   ln.x = x; ln.y = w.h; ln.gamma = P[E_LN1_G]; ln.beta = P[E_LN1_B];
   if (!h_ready) DP_TRY(launch_ln_fwd(ln, st));
-  const int choice_rows = e.batch_invariant ? seq : 0;
+  const int choice_rows = e.batch_invariant == 1 ? seq : (e.batch_invariant == 2 ? -1 : 0);
   GemmArgs g = gemm_fwd(dt, w.h, R, d, P[E_WQKV], 3 * d, P[E_BQKV], w.qkv);
   g.splitk_ws = w.splitk; g.splitk_ws_bytes = w.splitk_bytes; g.choice_rows = choice_rows;
   DP_TRY(launch_gemm(g, st));
@@ -943,9 +943,10 @@ int dp_stage_set_overlap(dp_stage* st, int enabled) {
   return DP_OK;
 }
 
-int dp_encoder_set_batch_invariant(dp_encoder* enc, int on) {
+int dp_encoder_set_batch_invariant(dp_encoder* enc, int mode) {
   if (!enc) return set_error(DP_EINVAL, "encoder handle is NULL");
-  enc->batch_invariant = on != 0;
+  if (mode < 0 || mode > 2) return set_error(DP_EINVAL, "batch-invariant mode must be 0, 1 or 2");
+  enc->batch_invariant = mode;
   return DP_OK;
 }
 

@@ -97,6 +97,15 @@ def test_null_misaligned_and_small_workspace_are_rejected_before_launch(dp):
     call = lambda **k: lib.encoder_fwd_partial(enc._h, eg, x, x, k.get("gb", 8), k.get("lb", 0), k.get("le", 4), k.get("off", 0),
                                                k.get("n", 4), ws, k.get("wsb", wsb), None)
     assert call(off=6) == -1            # range leaves the global batch
+    # batch-invariant modes: 0..2 accepted, anything else refused; mode 1 asks for a larger workspace (its split-K
+    # factors come from one sample's rows) and a call with the smaller one is refused before any launch
+    assert lib.dp_encoder_set_batch_invariant(enc._h, 3) == -1 and lib.dp_encoder_set_batch_invariant(None, 1) == -1
+    big = dp.Encoder(1, 2, 768, 12, 64, 77, 1000, 3072)
+    w0 = big.workspace_bytes(64)
+    big.set_batch_invariant(1)
+    w1 = big.workspace_bytes(64)
+    big.set_batch_invariant(2)
+    assert w1 > w0 and big.workspace_bytes(64) == w0
     assert call(n=0) == 0               # an empty slice is valid: checked, then nothing is launched (no GPU needed)
     assert call(n=0, off=8) == 0        # ... also at the very end of the batch
     assert call(n=0, off=9) == -1
