@@ -153,6 +153,7 @@ struct LnArgs {
   const void* gamma; const void* beta;
   const void* scale; const void* shift; int mod_ld; int rows_per_batch;
   float* mean; float* rstd;
+  float* x32_out;               // optional, storage-dtype x only: the rows of x widened to fp32 (the stage input entering the fp32 residual stream)
 };
 int launch_ln_fwd(const LnArgs& a, hipStream_t s);
 // x[r, :] += sum_z partial[z][r, :] (+ bias), then y[r, :] = LN(x[r, :]; gamma, beta, eps) in bf16: the split-K

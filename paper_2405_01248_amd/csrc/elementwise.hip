@@ -43,7 +43,8 @@ template <typename TX, typename T>
 __global__ void __launch_bounds__(256) ln_fwd_kernel(int rows, int d, float eps, const TX* __restrict__ x, T* __restrict__ y,
                                                      const T* __restrict__ gamma, const T* __restrict__ beta,
                                                      const T* __restrict__ scale, const T* __restrict__ shift, int mod_ld,
-                                                     int rows_per_batch, float* __restrict__ mean, float* __restrict__ rstd) {
+                                                     int rows_per_batch, float* __restrict__ mean, float* __restrict__ rstd,
+                                                     float* __restrict__ x32_out) {
   constexpr int V = Vec<T>::N;
   const int lane = threadIdx.x & 63, row = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (row >= rows) return;
@@ -56,6 +57,7 @@ __global__ void __launch_bounds__(256) ln_fwd_kernel(int rows, int d, float eps,
     if (col < d) {
       if (sizeof(TX) == 4) load_f32<V>(reinterpret_cast<const float*>(xr + col), v[c]);
       else load_vec<T>(reinterpret_cast<const T*>(xr + col), v[c]);
+      if (sizeof(TX) != 4 && x32_out) store_f32<V>(x32_out + (size_t)row * d + col, v[c]);
 #pragma unroll
       for (int i = 0; i < V; ++i) s += v[c][i];
     }
@@ -104,7 +106,7 @@ template <typename TX, typename T>
 static int ln_fwd_t(const LnArgs& a, hipStream_t s) {
   hipLaunchKernelGGL((ln_fwd_kernel<TX, T>), dim3((a.rows + 3) / 4), dim3(256), 0, s, a.rows, a.d, a.eps, (const TX*)a.x, (T*)a.y,
                      (const T*)a.gamma, (const T*)a.beta, (const T*)a.scale, (const T*)a.shift, a.mod_ld,
-                     a.rows_per_batch > 0 ? a.rows_per_batch : a.rows, a.mean, a.rstd);
+                     a.rows_per_batch > 0 ? a.rows_per_batch : a.rows, a.mean, a.rstd, a.x32_out);
   return hipGetLastError() == hipSuccess ? DP_OK : set_error(DP_EHIP, "ln_fwd launch failed");
 }
 
@@ -190,7 +192,8 @@ int launch_ln_fwd(const LnArgs& a, hipStream_t s) {
   if (int e = check_ln_dim(a.dtype, a.d)) return e;
   if ((a.gamma == nullptr) != (a.beta == nullptr) || (a.scale == nullptr) != (a.shift == nullptr))
     return set_error(DP_EINVAL, "ln_fwd: gamma/beta and scale/shift come in pairs");
-  KScope ks(KK_LN_FWD, 0.0, a.rows * (double)a.d * (dtype_size(a.dtype) + (a.x_f32 ? 4 : dtype_size(a.dtype))) + 8.0 * a.rows, s, a.rows, a.d);
+  if (a.x32_out && (a.x_f32 || a.dtype != BF16 || ((uintptr_t)a.x32_out % 16))) return set_error(DP_EINVAL, "ln_fwd: the widened copy goes with a bf16 input and a 16-byte aligned destination");
+  KScope ks(KK_LN_FWD, 0.0, a.rows * (double)a.d * (dtype_size(a.dtype) + (a.x_f32 ? 4 : dtype_size(a.dtype)) + (a.x32_out ? 4 : 0)) + 8.0 * a.rows, s, a.rows, a.d);
   if (a.dtype == BF16) return a.x_f32 ? ln_fwd_t<float, bf16>(a, s) : ln_fwd_t<bf16, bf16>(a, s);
   return ln_fwd_t<float, float>(a, s);
 }

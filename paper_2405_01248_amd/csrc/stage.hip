@@ -302,15 +302,19 @@ static int record(ProfileHooks* ph, int idx, hipStream_t st) {
 // x: fp32 block input.  y: fp32 (next block's input) unless y_is_out (storage dtype, the stage output).
 // kv_side: the context K/V projection of this block was issued on the side stream as batch kv_batch
 // of *kv_side (it depends on the context and the weights only); otherwise it is computed here.
+// x_storage (first block of a bf16 stage): the stage input in the storage dtype; the first LayerNorm reads it and
+// writes its rows widened to fp32 into x on the way, which saves a conversion pass over the input.
 static int unet_block_fwd(const dp_stage& s, const void* const* P, const float* x, const void* ctx, void* y, bool y_is_out,
-                          UnetBuf& u, hipStream_t st, Side* kv_side = nullptr, int kv_batch = 0) {
+                          UnetBuf& u, hipStream_t st, Side* kv_side = nullptr, int kv_batch = 0, const void* x_storage = nullptr) {
   const int dt = s.d.dtype, T = s.T, Tc = s.Tc, d = s.d.d_model, inner = s.d.ff_inner, dc = s.d.ctx_dim;
   const size_t es = s.es;
   LnArgs ln; memset(&ln, 0, sizeof(ln));
   ln.dtype = dt; ln.rows = T; ln.d = d; ln.eps = s.d.ln_eps; ln.x_f32 = 1;
   // self-attention
   ln.x = x; ln.y = u.h1; ln.gamma = P[U_LN1_G]; ln.beta = P[U_LN1_B]; ln.mean = u.mean1; ln.rstd = u.rstd1;
+  if (x_storage) { ln.x = x_storage; ln.x_f32 = 0; ln.x32_out = const_cast<float*>(x); }
   DP_TRY(launch_ln_fwd(ln, st));
+  ln.x_f32 = 1; ln.x32_out = nullptr;
   DP_TRY(launch_gemm(gemm_fwd(dt, u.h1, T, d, P[U_WQKV], 3 * d, nullptr, u.qkv), st));
   AttnArgs a = attn_base(s);
   a.Nk = s.d.tokens; a.q = u.qkv; a.k = at(u.qkv, d, es); a.v = at(u.qkv, 2 * d, es); a.ldq = a.ldk = a.ldv = 3 * d;
@@ -475,7 +479,7 @@ static int unet_block_bwd(const dp_stage& s, const void* const* P, const void* c
 // mod_side: the modulation vectors of this block (they depend on the conditioning and the weights only) were
 // issued on the side stream as batch mod_batch of *mod_side; otherwise they are computed here.
 static int dit_block_fwd(const dp_stage& s, const void* const* P, const float* x, const void* sc_in, void* y, bool y_is_out,
-                         bool save, DitBuf& u, hipStream_t st, Side* mod_side = nullptr, int mod_batch = 0) {
+                         bool save, DitBuf& u, hipStream_t st, Side* mod_side = nullptr, int mod_batch = 0, const void* x_storage = nullptr) {
   const int dt = s.d.dtype, T = s.T, d = s.d.d_model, ff = s.d.ff_inner, B = s.d.batch, N = s.d.tokens;
   const size_t es = s.es;
   if (mod_side) mod_side->wait(mod_batch);
@@ -483,7 +487,9 @@ static int dit_block_fwd(const dp_stage& s, const void* const* P, const float* x
   LnArgs ln; memset(&ln, 0, sizeof(ln));
   ln.dtype = dt; ln.rows = T; ln.d = d; ln.eps = s.d.ln_eps; ln.mod_ld = 6 * d; ln.rows_per_batch = N; ln.x_f32 = 1;
   ln.x = x; ln.y = u.h1; ln.shift = u.m; ln.scale = at(u.m, d, es); ln.mean = u.mean1; ln.rstd = u.rstd1;
+  if (x_storage) { ln.x = x_storage; ln.x_f32 = 0; ln.x32_out = const_cast<float*>(x); }     // see unet_block_fwd
   DP_TRY(launch_ln_fwd(ln, st));
+  ln.x_f32 = 1; ln.x32_out = nullptr;
   DP_TRY(launch_gemm(gemm_fwd(dt, u.h1, T, d, P[D_WQKV], 3 * d, P[D_BQKV], u.qkv), st));
   AttnArgs a = attn_base(s);
   a.Nk = N; a.q = u.qkv; a.k = at(u.qkv, d, es); a.v = at(u.qkv, 2 * d, es); a.ldq = a.ldk = a.ldv = 3 * d;
@@ -656,7 +662,9 @@ static int run_stage_fwd(dp_stage* s, const void* const* params, const void* x, 
     }
     if (unet) kv_batch = sd.end();
   }
-  DP_TRY(launch_cast_to_f32(s->d.dtype, x, cur, act, st));
+  // bf16 stages: the first block's first LayerNorm widens the input on its way (one pass less over it)
+  const bool widen_in_ln = s->d.dtype == DP_BF16;
+  if (!widen_in_ln) DP_TRY(launch_cast_to_f32(s->d.dtype, x, cur, act, st));
   for (int b = 0; b < nb; ++b) {
     DP_TRY(record(ph, b, st));
     const void* const* P = params + (size_t)b * s->per_block;
@@ -666,11 +674,12 @@ static int run_stage_fwd(dp_stage* s, const void* const* params, const void* x, 
     else if (save) out = unet ? sp.ub[b + 1].xin : sp.db[b + 1].xin;
     else out = (b & 1) ? sp.pp1 : sp.pp0;
     const int slot = save ? b : 0;
-    if (unet) DP_TRY(unet_block_fwd(*s, P, cur, cc, out, last, sp.ub[slot], st, sd.on ? &sd : nullptr, kv_batch));
+    const void* xs = (b == 0 && widen_in_ln) ? x : nullptr;
+    if (unet) DP_TRY(unet_block_fwd(*s, P, cur, cc, out, last, sp.ub[slot], st, sd.on ? &sd : nullptr, kv_batch, xs));
     else {
       DitBuf ub = sp.db[slot];
       if (!save) ub.m = sp.mods[b];
-      DP_TRY(dit_block_fwd(*s, P, cur, sp.sc_in, out, last, save != 0, ub, st, sd.on ? &sd : nullptr, mod_batch[b]));
+      DP_TRY(dit_block_fwd(*s, P, cur, sp.sc_in, out, last, save != 0, ub, st, sd.on ? &sd : nullptr, mod_batch[b], xs));
     }
     cur = (float*)out;
   }
