@@ -314,6 +314,57 @@ def partition_report(si, DeviceStage):
     return out, prof, rows
 
 
+def bidirectional_report(si, DeviceStage):
+    """Bidirectional partitioning of two backbones (Sec. 4.2, Eq. 10-16) on cost rows measured here: the U-Net blocks of
+    cfg2 (32x32 latents, d = 640) as the backbone pipelined down the device chain and those of cfg3 (64x64 latents,
+    d = 320) as the one pipelined up, each profiled at local batch 8 / 4 / 2 and tiled to 6 layers; 4 devices, micro-batch
+    8, M_CDM = 8 (an input: the paper prints no expression for it), one xGMI link for p2p, 7 links for the all-reduce."""
+    import torch
+    from paper_2405_01248_amd import binding
+    from oracle import partition as P      # timed beside the library as the CPU baseline of this row
+    tiles, profs, all_rows = 3, [], []
+    for base in (si.CONFIG2, si.CONFIG3):
+        rows = []
+        for b in (8, 4, 2):
+            cfg = base.replace(batch=b, name=f"{base.name}_b{b}")
+            ds = DeviceStage(cfg, si.make_stage_inputs(cfg, seed=0))
+            ds.step()
+            blk = ds.stage.profile(ds.params, ds.x, ds.cc, ds.y, ds.dy, ds.dx, ds.d_cond, ds.dparams, ds.ws, reps=10)
+            torch.cuda.synchronize()
+            for rep in range(tiles):
+                rows += [dict(r, layer=r["layer"] + rep * cfg.n_blocks) for r in blk]
+            del ds
+            torch.cuda.empty_cache()
+        L = tiles * base.n_blocks
+        prof = P.Profile(L, {}, {}, {}, {}, [0] * L, {})
+        for r in rows:
+            for name, tab in (("fwd_ms", prof.fwd_ms), ("bwd_ms", prof.bwd_ms), ("cf_bytes", prof.cf_bytes), ("cb_bytes", prof.cb_bytes)):
+                tab.setdefault(r["batch"], [0] * L)[r["layer"]] = r[name]
+            prof.grad_bytes[r["layer"]] = r["grad_bytes"]
+            if r["layer"] == L - 1:
+                prof.out_bytes[r["batch"]] = r["out_bytes"]
+        profs.append(prof); all_rows.append(rows)
+    link = dict(p2p_gbps=153.0, p2p_latency_ms=0.01, ar_gbps=7 * 153.0 / 2, ar_latency_ms=0.05)
+    out = {"workload": "down: cfg2 blocks x3 (6 layers), up: cfg3 blocks x3 (6 layers), B=8, M_CDM=8, D=4", "links": link,
+           "per_layer_ms": {n: {str(b): {"fwd": pr.fwd_ms[b][0], "bwd": pr.bwd_ms[b][0]} for b in sorted(pr.fwd_ms)} for n, pr in zip(("down", "up"), profs)},
+           "plans": []}
+    for uni in (False, True):
+        t0 = time.perf_counter()
+        for _ in range(5):
+            got = binding.partition_solve_bidirectional(all_rows[0], all_rows[1], 8, 8, 4, uniform_replication=uni, **link)
+        t_lib = (time.perf_counter() - t0) / 5
+        o = P.Options(micro_batch=8, n_micro_batches=8, n_devices=4, uniform_replication=uni, **link)
+        t0 = time.perf_counter()
+        ref = P.solve_bidirectional(profs[0], profs[1], o)
+        t_or = time.perf_counter() - t0
+        same = (got["first_layer_down"], got["first_layer_up"], got["replicas"]) == (ref.first_layer_down, ref.first_layer_up, ref.replicas) \
+            and abs(got["t_max_ms"] - ref.t_max_ms) <= 1e-9 * ref.t_max_ms
+        out["plans"].append({"uniform_replication": uni, "layers_down": got["n_layers_down"], "layers_up": got["n_layers_up"], "replicas": got["replicas"],
+                             "t0_ms": got["t0_ms"], "gap_ms": got["gap_ms"], "t_max_ms": got["t_max_ms"], "solve_ms_library": t_lib * 1e3,
+                             "solve_ms_oracle": t_or * 1e3, "matches_oracle": same})
+    return out
+
+
 def bubble_report(si, DeviceStage, DeviceEncoder):
     """Bubble filling (Sec. 5) on measured profiles: the partition of --partition (self-conditioning off), one 1F1B
     iteration simulated from the measured stage times, and the frozen text encoder (profiled here at local batch 4..64,
@@ -383,6 +434,8 @@ def main():
                          "the text encoder profiled here at the regular partial-batch sizes (library and oracle)")
     ap.add_argument("--fp8", action="store_true",
                     help="instead of the step benchmark: the FP8 (E4M3) projection GEMM beside the bf16 one on the workloads' projection shapes")
+    ap.add_argument("--bidirectional", action="store_true",
+                    help="instead of the step benchmark: the bidirectional partitioner (Sec. 4.2) on profiles of two backbones at different resolutions measured on this GPU")
     ap.add_argument("--partition", action="store_true",
                     help="instead of the step benchmark: profile the DiT stage's blocks at local batch sizes 32, 16, 8, 4 on this "
                          "GPU, tile them to a 28-layer backbone and run the partitioner (library and oracle) for 8 devices")
@@ -446,6 +499,9 @@ def main():
 
     if args.fp8:
         print(json.dumps(fp8_report()))
+        return
+    if args.bidirectional:
+        print(json.dumps(bidirectional_report(si, DeviceStage)))
         return
     if args.partition:
         print(json.dumps(partition_report(si, DeviceStage)[0]))
