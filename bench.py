@@ -413,6 +413,42 @@ def bubble_report(si, DeviceStage, DeviceEncoder):
             "solve_ms_library": t_lib * 1e3, "solve_ms_oracle": t_or * 1e3, "matches_oracle": same}
 
 
+def search_report(si, DeviceStage, DeviceEncoder):
+    """The search over stages, micro-batches and group size (Sec. 3, steps 2-5) on profiles measured here: the DiT backbone of
+    --partition (28 layers, profiled at local batch 32 / 16 / 8 / 4) with self-conditioning at p = 0.5 and the frozen text
+    encoder as the non-trainable part; 8 devices, training batch 256; group sizes 2 / 4 / 8, micro-batch counts 2 / 4 / 8 / 16."""
+    import torch
+    from paper_2405_01248_amd import binding
+    from oracle import bubbles as Bu, search as S
+    part, prof, rows = partition_report(si, DeviceStage)
+    cfg = si.CONFIG5
+    de = DeviceEncoder(cfg, si.make_encoder_inputs(cfg, seed=0))
+    batches = [4, 8, 12, 16, 24, 32, 48, 64]
+    enc_rows = de.enc.profile(de.params, de.ids, de.hidden, de.gb, batches, de.ws, reps=5)
+    torch.cuda.synchronize()
+    link = part["links"]
+    kw = dict(world_size=8, training_batch=256, group_sizes=(2, 4, 8), micro_batch_counts=(2, 4, 8, 16), self_cond_prob=0.5,
+              uniform_replication=True, min_bubble_ms=0.1, **link)
+    t0 = time.perf_counter()
+    cands, best = binding.schedule_search(rows + enc_rows, **kw)
+    t_lib = time.perf_counter() - t0
+    comp = Bu.Component(cfg.n_layers + 2, {b: [r["fwd_ms"] for r in enc_rows if r["batch"] == b] for b in batches})
+    t0 = time.perf_counter()
+    ref, ref_best = S.search(prof, [comp], S.SearchOptions(**kw))
+    t_or = time.perf_counter() - t0
+    same = len(cands) == len(ref) and best == ref_best and all(
+        (c["n_stages"], c["n_micro_batches"], c["group_size"]) == (r.n_stages, r.n_micro_batches, r.group_size)
+        and abs(c["iteration_ms"] - r.iteration_ms) <= 1e-9 * r.iteration_ms for c, r in zip(cands, ref))
+    pick = lambda c: {k: c[k] for k in ("n_stages", "n_micro_batches", "group_size", "micro_batch", "n_layers", "replicas", "pipeline_ms", "leftover_ms",
+                                        "iteration_ms", "bubble_ratio", "bubble_ratio_filled")}
+    # iteration time is per pipeline group; a group of D devices trains 256 D / 8 samples per iteration
+    rate = lambda c: 256.0 * c["group_size"] / 8 / c["iteration_ms"] * 1e3 * (8 / c["group_size"])
+    ranked = sorted(range(len(cands)), key=lambda i: cands[i]["iteration_ms"])
+    return {"workload": part["workload"] + ", world 8, training batch 256, p = 0.5", "n_candidates": len(cands), "best": pick(cands[best]),
+            "best_samples_per_s_all_groups": rate(cands[best]), "runners_up": [pick(cands[i]) for i in ranked[1:4]],
+            "solve_ms_library": t_lib * 1e3, "solve_ms_oracle": t_or * 1e3, "matches_oracle": same}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -434,6 +470,8 @@ def main():
                          "the text encoder profiled here at the regular partial-batch sizes (library and oracle)")
     ap.add_argument("--fp8", action="store_true",
                     help="instead of the step benchmark: the FP8 (E4M3) projection GEMM beside the bf16 one on the workloads' projection shapes")
+    ap.add_argument("--search", action="store_true",
+                    help="instead of the step benchmark: the search over stages, micro-batches and group size (Sec. 3) on profiles measured on this GPU")
     ap.add_argument("--bidirectional", action="store_true",
                     help="instead of the step benchmark: the bidirectional partitioner (Sec. 4.2) on profiles of two backbones at different resolutions measured on this GPU")
     ap.add_argument("--partition", action="store_true",
@@ -499,6 +537,9 @@ def main():
 
     if args.fp8:
         print(json.dumps(fp8_report()))
+        return
+    if args.search:
+        print(json.dumps(search_report(si, DeviceStage, DeviceEncoder)))
         return
     if args.bidirectional:
         print(json.dumps(bidirectional_report(si, DeviceStage)))
