@@ -261,6 +261,166 @@ __global__ void __launch_bounds__(256, (QT == 1 && DHP == 64) ? 3 : 2) attn_fwd_
   }
 }
 
+// The same forward for d_head = 64 with the K and V tiles copied global -> LDS directly (no register
+// staging: 16 fewer registers per lane, no LDS stores in the loop).  A [64 x 64] bf16 tile is 64 rows of
+// eight 16-byte chunks with no padding; a wave copies 8 rows per instruction, lane = 8 * row + position,
+// and the chunk a position holds is position ^ key(row), so that the fragment reads stay conflict-free:
+// K (rows read as MFMA A fragments, lanes vary in the row): key = row & 7;
+// V (read by the transposing load, 4 rows x 64 bytes per half-wave): key = 4 * ((row >> 1) & 1).
+// Rows past the end of the keys come back as zeros from the buffer descriptor's range check.
+__device__ __forceinline__ int attn_kkey(int row) { return row & 7; }
+__device__ __forceinline__ int attn_vkey(int row) { return 4 * ((row >> 1) & 1); }
+
+template <bool CAUSAL>
+__global__ void __launch_bounds__(256, 4) attn_fwd_dtl_kernel(const AttnK p) {
+  constexpr int KC = 4, DT = 2, BQ = 128, TILE = 64 * 64;
+  __shared__ __attribute__((aligned(1024))) bf16 Ks[2][TILE];
+  __shared__ __attribute__((aligned(1024))) bf16 Vs[2][TILE];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 5, l32 = lane & 31;
+  int qtile, bh;
+  attn_block_map(blockIdx.x, (p.Nq + BQ - 1) / BQ, p.B * p.H, qtile, bh);
+  const int b = bh / p.H, h = bh % p.H;
+  const int q0 = qtile * BQ + wave * 32;
+  const bf16* qb = (const bf16*)p.q + (size_t)b * p.Nq * p.ldq + h * 64;
+  const bf16* kb = (const bf16*)p.k + (size_t)b * p.Nk * p.ldk + h * 64;
+  const bf16* vb = (const bf16*)p.v + (size_t)b * p.Nk * p.ldv + h * 64;
+  const rsrc_t kr = make_rsrc(kb, (uint32_t)(((size_t)(p.Nk - 1) * p.ldk + 64) * 2));
+  const rsrc_t vr = make_rsrc(vb, (uint32_t)(((size_t)(p.Nk - 1) * p.ldv + 64) * 2));
+
+  bf16x8 qf[KC];
+#pragma unroll
+  for (int c = 0; c < KC; ++c) {
+    const int qi = q0 + l32;
+    qf[c] = ld8(qb + (size_t)qi * p.ldq + 16 * c + 8 * g, qi < p.Nq);
+  }
+  f32x16 oacc[DT];
+  float m = -INFINITY, lsum = 0.f;
+#pragma unroll
+  for (int i = 0; i < DT; ++i)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) oacc[i][r] = 0.f;
+
+  int nkt = (p.Nk + 63) / 64;
+  if (CAUSAL) nkt = min(nkt, (min(p.Nq, qtile * BQ + BQ) + 63) / 64);
+
+  // this wave's share of a tile: rows 16 * wave .. + 15 of K and of V, two 8-row pieces each
+  uint32_t ko[2], vo[2];
+#pragma unroll
+  for (int j = 0; j < 2; ++j) {
+    const int row = 16 * wave + 8 * j + (lane >> 3), pc = lane & 7;
+    ko[j] = (uint32_t)(row * p.ldk + 8 * (pc ^ attn_kkey(row))) * 2u;
+    vo[j] = (uint32_t)(row * p.ldv + 8 * (pc ^ attn_vkey(row))) * 2u;
+  }
+  auto copy_tile = [&](int kt, int st) {
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      // the tile's offset goes into the per-lane offset: only that one is range-checked
+      async_copy_16B_buf(kr, ko[j] + (uint32_t)kt * 64u * (uint32_t)p.ldk * 2u, 0, &Ks[st][(16 * wave + 8 * j) * 64]);
+      async_copy_16B_buf(vr, vo[j] + (uint32_t)kt * 64u * (uint32_t)p.ldv * 2u, 0, &Vs[st][(16 * wave + 8 * j) * 64]);
+    }
+  };
+  copy_tile(0, 0);
+  wait_vmcnt<0>();
+  __syncthreads();
+
+  for (int kt = 0; kt < nkt; ++kt) {
+    const int buf = kt & 1;
+    // every wave left stage buf ^ 1 at the barrier that ended the previous iteration
+    if (kt + 1 < nkt) copy_tile(kt + 1, buf ^ 1);
+    f32x16 s[2];
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) s[t][r] = 0.f;
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+      for (int c = 0; c < KC; ++c) {
+        const int row = 32 * t + l32;
+        const bf16x8 a = *reinterpret_cast<const bf16x8*>(&Ks[buf][row * 64 + 8 * ((2 * c + g) ^ attn_kkey(row))]);
+        s[t] = mfma32(a, qf[c], s[t]);
+      }
+    const int qi = q0 + l32;
+    const bool edge = kt * 64 + 64 > p.Nk || (CAUSAL && kt * 64 + 63 > q0);
+    if (edge) {
+#pragma unroll
+      for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int key = kt * 64 + 32 * t + acc_row(r, g);
+          const bool dead = key >= p.Nk || (CAUSAL && key > qi);
+          s[t][r] = dead ? -INFINITY : s[t][r];
+        }
+    }
+    // online softmax with a lazily moved reference point, as in attn_fwd_bf16_kernel
+    float mx = -INFINITY;
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[t][r]);
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    mx = fmaxf(m, mx * p.scale_log2);
+    const bool bump = __any(mx > m + 8.0f);
+    mx = bump ? mx : m;
+    const float mref = (mx == -INFINITY) ? 0.f : mx;
+    float rs = 0.f;
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const float e = __builtin_amdgcn_exp2f(fmaf(s[t][r], p.scale_log2, -mref));
+        s[t][r] = e;
+        rs += e;
+      }
+    rs += __shfl_xor(rs, 32, 64);
+    if (bump) {
+      const float alpha = __builtin_amdgcn_exp2f(m - mref);
+      lsum *= alpha;
+#pragma unroll
+      for (int i = 0; i < DT; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) oacc[i][r] *= alpha;
+    }
+    lsum += rs;
+    m = mx;
+    // O^T += V^T P^T; the transposing load takes, per lane, 4 consecutive channels of one key row
+    const int vb4 = lane >> 4, vj = lane & 15;
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+      for (int cc = 0; cc < 2; ++cc) {
+        const bf16x8 pf = pack8(s[t], 8 * cc);
+#pragma unroll
+        for (int i = 0; i < DT; ++i) {
+          const int row = 32 * t + 16 * cc + 4 * (vb4 >> 1) + (vj >> 2);       // and row + 8 (same key)
+          const int chunk = 4 * i + 2 * (vb4 & 1) + ((vj & 3) >> 1);
+          const bf16* a0 = &Vs[buf][row * 64 + 8 * (chunk ^ attn_vkey(row)) + 4 * (vj & 1)];
+          const bf16x4 lo = lds_read_tr(a0);
+          const bf16x4 hi = lds_read_tr(a0 + 8 * 64);
+          oacc[i] = mfma32(__builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7), pf, oacc[i]);
+        }
+      }
+    wait_vmcnt<0>();      // this wave's pieces of the next tile have landed
+    __syncthreads();      // ... and everybody's; all reads of stage buf are done
+  }
+
+  const int qi = q0 + l32;
+  if (qi < p.Nq) {
+    const float inv = lsum > 0.f ? 1.0f / lsum : 0.f;
+    bf16* ob = (bf16*)p.o + ((size_t)b * p.Nq + qi) * p.ldo + h * 64;
+#pragma unroll
+    for (int i = 0; i < DT; ++i)
+#pragma unroll
+      for (int r4 = 0; r4 < 4; ++r4) {
+        bf16x4 o;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) o[u] = (bf16)(oacc[i][4 * r4 + u] * inv);
+        *reinterpret_cast<bf16x4*>(ob + 32 * i + 8 * r4 + 4 * g) = o;
+      }
+    if (p.lse && g == 0) p.lse[((size_t)b * p.H + h) * p.Nq + qi] = m * LN2 + logf(lsum);
+  }
+}
+
 // ------------------------------------------------------------------ delta = rowsum(dO * O)
 // 8 lanes per (token, head) pair.
 template <typename T>
@@ -728,7 +888,13 @@ int launch_attn_fwd(const AttnArgs& a, hipStream_t s) {
     // (the kernel is bound by the softmax arithmetic, not by LDS), so one tile per wave is used
     const bool qt2 = false;
     dim3 grid(((a.Nq + (qt2 ? 255 : 127)) / (qt2 ? 256 : 128)) * a.B * a.H);
-    if (a.d_head <= 64) {
+    // d_head = 64 (every stage and encoder of the workloads but the DiT's 72): K / V copied straight to LDS;
+    // the copies address a (batch, head) slice with 32-bit byte offsets
+    const bool dtl = a.d_head == 64 && (size_t)a.Nk * std::max(a.ldk, a.ldv) * 2 < (1ull << 31);
+    if (dtl) {
+      if (a.causal) hipLaunchKernelGGL((attn_fwd_dtl_kernel<true>), grid, dim3(256), 0, s, k);
+      else hipLaunchKernelGGL((attn_fwd_dtl_kernel<false>), grid, dim3(256), 0, s, k);
+    } else if (a.d_head <= 64) {
       if (qt2) {
         if (a.causal) hipLaunchKernelGGL((attn_fwd_bf16_kernel<64, true, 2>), grid, dim3(256), 0, s, k);
         else hipLaunchKernelGGL((attn_fwd_bf16_kernel<64, false, 2>), grid, dim3(256), 0, s, k);
