@@ -712,6 +712,302 @@ __global__ void __launch_bounds__(256, DHP == 64 ? 2 : 1) attn_bwd_dkv_bf16_kern
   }
 }
 
+// ------------------------------------------------------------------ backward for d_head = 64, tiles copied global -> LDS
+// Both backward kernels read a streamed tile two ways (by rows as an MFMA A operand, and through the
+// transposing load), so one chunk permutation has to keep both conflict-free: position = chunk ^ key,
+// key = row bits (0, 2, 1) -- a bijection of row & 7 (8 consecutive rows of a row-fragment read land in
+// 8 different positions) whose bit 2 is row bit 1 (the 4 rows of a transposing read fall into 4
+// different 64-byte bank groups).
+__device__ __forceinline__ int attn_ukey(int row) { return (row & 1) | ((row & 4) >> 1) | ((row & 2) << 1); }
+
+// This wave's share of a [64 x 64] tile copy: rows 16 * wave .. + 15 in two 8-row pieces.
+struct AttnTileCopy {
+  uint32_t off[2];
+  __device__ __forceinline__ void init(int wave, int lane, int ld) {
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      const int row = 16 * wave + 8 * j + (lane >> 3);
+      off[j] = (uint32_t)(row * ld + 8 * ((lane & 7) ^ attn_ukey(row))) * 2u;
+    }
+  }
+  // rows row0 .. row0 + 63 of the (batch, head) slice behind r; rows past its end read as zeros
+  __device__ __forceinline__ void issue(rsrc_t r, int row0, int ld, bf16* stage, int wave) const {
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+      async_copy_16B_buf(r, off[j] + (uint32_t)row0 * (uint32_t)ld * 2u, 0, stage + (16 * wave + 8 * j) * 64);
+  }
+};
+// Per-lane element offsets of the fragment reads, computed once: a row fragment of rows 32 * t + l32 is at
+// row[c] + 32 * 64 * t, a transposed fragment (the slot order of frag_from_mc_accorder) of rows r0 .. r0 + 15
+// (r0 a multiple of 16, which leaves the keys alone), columns 32 * i .. + 31, at tr[i] + 64 * r0 and 8 rows below.
+struct AttnFragOff {
+  int row[4], tr[2];
+  __device__ __forceinline__ void init(int lane) {
+    const int g = lane >> 5, l32 = lane & 31, b = lane >> 4, j = lane & 15;
+#pragma unroll
+    for (int c = 0; c < 4; ++c) row[c] = l32 * 64 + 8 * ((2 * c + g) ^ attn_ukey(l32));
+    const int r = 4 * (b >> 1) + (j >> 2);
+#pragma unroll
+    for (int i = 0; i < 2; ++i) tr[i] = r * 64 + 8 * ((4 * i + 2 * (b & 1) + ((j & 3) >> 1)) ^ attn_ukey(r)) + 4 * (j & 1);
+  }
+};
+__device__ __forceinline__ bf16x8 attn_row_frag(const bf16* tile, const AttnFragOff& f, int t, int c) {
+  return *reinterpret_cast<const bf16x8*>(tile + f.row[c] + 32 * 64 * t);
+}
+__device__ __forceinline__ bf16x8 attn_tr_frag(const bf16* tile, const AttnFragOff& f, int r0, int i) {
+  const bf16* a0 = tile + f.tr[i] + 64 * r0;
+  const bf16x4 lo = lds_read_tr(a0);
+  const bf16x4 hi = lds_read_tr(a0 + 8 * 64);
+  return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+}
+
+__global__ void __launch_bounds__(256, 3) attn_bwd_dq_dtl_kernel(const AttnK p) {
+  constexpr int KC = 4, DT = 2, TILE = 64 * 64;
+  __shared__ __attribute__((aligned(1024))) bf16 Ks[2][TILE];
+  __shared__ __attribute__((aligned(1024))) bf16 Vs[2][TILE];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 5, l32 = lane & 31;
+  int qtile, bh;
+  attn_block_map(blockIdx.x, (p.Nq + 127) / 128, p.B * p.H, qtile, bh);
+  const int b = bh / p.H, h = bh % p.H;
+  const int qi = qtile * 128 + wave * 32 + l32;
+  const bool qok = qi < p.Nq;
+  const bf16* kb = (const bf16*)p.k + (size_t)b * p.Nk * p.ldk + h * 64;
+  const bf16* vb = (const bf16*)p.v + (size_t)b * p.Nk * p.ldv + h * 64;
+  const rsrc_t kr = make_rsrc(kb, (uint32_t)(((size_t)(p.Nk - 1) * p.ldk + 64) * 2));
+  const rsrc_t vr = make_rsrc(vb, (uint32_t)(((size_t)(p.Nk - 1) * p.ldv + 64) * 2));
+  const bf16* qrow = (const bf16*)p.q + ((size_t)b * p.Nq + qi) * p.ldq + h * 64;
+  const bf16* dorow = (const bf16*)p.dout + ((size_t)b * p.Nq + qi) * p.lddo + h * 64;
+
+  AttnFragOff fo;
+  fo.init(lane);
+  AttnTileCopy ck, cv;
+  ck.init(wave, lane, p.ldk);
+  cv.init(wave, lane, p.ldv);
+  ck.issue(kr, 0, p.ldk, Ks[0], wave);
+  cv.issue(vr, 0, p.ldv, Vs[0], wave);
+
+  bf16x8 qf[KC], dof[KC];
+#pragma unroll
+  for (int c = 0; c < KC; ++c) {
+    qf[c] = ld8(qrow + 16 * c + 8 * g, qok);
+    dof[c] = ld8(dorow + 16 * c + 8 * g, qok);
+  }
+  const size_t sidx = ((size_t)b * p.H + h) * p.Nq + qi;
+  const float lse2 = qok ? p.lse[sidx] * LOG2E : INFINITY;
+  // delta = rowsum(dO * O) from the dO fragments the lane holds (lane ^ 32 has the other half of the
+  // head dimension); stored for the dK/dV kernel, which runs after this one on the same stream
+  float dlt = 0.f;
+  {
+    const bf16* orow = (const bf16*)p.o + ((size_t)b * p.Nq + qi) * p.ldo + h * 64;
+#pragma unroll
+    for (int c = 0; c < KC; ++c) {
+      const bf16x8 of = ld8(orow + 16 * c + 8 * g, qok);
+#pragma unroll
+      for (int u = 0; u < 8; ++u) dlt = fmaf((float)of[u], (float)dof[c][u], dlt);
+    }
+    dlt += __shfl_xor(dlt, 32, 64);
+    if (qok && g == 0) p.delta[sidx] = dlt;
+  }
+  f32x16 acc[DT];
+#pragma unroll
+  for (int i = 0; i < DT; ++i)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
+
+  const int nkt = (p.Nk + 63) / 64;
+  wait_vmcnt<0>();
+  __syncthreads();
+  for (int kt = 0; kt < nkt; ++kt) {
+    const int buf = kt & 1;
+    if (kt + 1 < nkt) {      // stage buf ^ 1 was left by every wave at the barrier ending the previous iteration
+      ck.issue(kr, (kt + 1) * 64, p.ldk, Ks[buf ^ 1], wave);
+      cv.issue(vr, (kt + 1) * 64, p.ldv, Vs[buf ^ 1], wave);
+    }
+    // keys past Nk need no masking: their K and V rows are zero in LDS, so dP = 0 and the finite dS
+    // they get multiplies a zero K row in the dQ product
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+      f32x16 s, dp;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) { s[r] = 0.f; dp[r] = 0.f; }
+#pragma unroll
+      for (int c = 0; c < KC; ++c) {
+        s = mfma32(attn_row_frag(Ks[buf], fo, t, c), qf[c], s);
+        dp = mfma32(attn_row_frag(Vs[buf], fo, t, c), dof[c], dp);
+      }
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const float pr = __builtin_amdgcn_exp2f(fmaf(s[r], p.scale_log2, -lse2));
+        s[r] = pr * (dp[r] - dlt);
+      }
+#pragma unroll
+      for (int cc = 0; cc < 2; ++cc) {
+        const bf16x8 dsf = pack8(s, 8 * cc);
+#pragma unroll
+        for (int i = 0; i < DT; ++i) acc[i] = mfma32(attn_tr_frag(Ks[buf], fo, 32 * t + 16 * cc, i), dsf, acc[i]);
+      }
+    }
+    wait_vmcnt<0>();
+    __syncthreads();
+  }
+  if (qok) {
+    bf16* ob = (bf16*)p.dq + ((size_t)b * p.Nq + qi) * p.lddq + h * 64;
+#pragma unroll
+    for (int i = 0; i < DT; ++i)
+#pragma unroll
+      for (int r4 = 0; r4 < 4; ++r4) {
+        bf16x4 o;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) o[u] = (bf16)(acc[i][4 * r4 + u] * p.scale);
+        *reinterpret_cast<bf16x4*>(ob + 32 * i + 8 * r4 + 4 * g) = o;
+      }
+  }
+}
+
+__global__ void __launch_bounds__(256, 2) attn_bwd_dkv_dtl_kernel(const AttnK p) {
+  constexpr int KC = 4, DT = 2, TILE = 64 * 64;
+  __shared__ __attribute__((aligned(1024))) bf16 Qs[2][TILE];
+  __shared__ __attribute__((aligned(1024))) bf16 Ds[2][TILE];
+  __shared__ __attribute__((aligned(16))) float lse_s[2][64];
+  __shared__ __attribute__((aligned(16))) float dlt_s[2][64];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 5, l32 = lane & 31;
+  int ktile, bh;
+  const int qs = blockIdx.x % p.qsplits;
+  attn_block_map(blockIdx.x / p.qsplits, (p.Nk + 127) / 128, p.B * p.H, ktile, bh);
+  const int b = bh / p.H, h = bh % p.H;
+  const int ki = ktile * 128 + wave * 32 + l32;
+  const bool kok = ki < p.Nk;
+  const bf16* qb = (const bf16*)p.q + (size_t)b * p.Nq * p.ldq + h * 64;
+  const bf16* dob = (const bf16*)p.dout + (size_t)b * p.Nq * p.lddo + h * 64;
+  const rsrc_t qr = make_rsrc(qb, (uint32_t)(((size_t)(p.Nq - 1) * p.ldq + 64) * 2));
+  const rsrc_t dr = make_rsrc(dob, (uint32_t)(((size_t)(p.Nq - 1) * p.lddo + 64) * 2));
+  const bf16* krow = (const bf16*)p.k + ((size_t)b * p.Nk + ki) * p.ldk + h * 64;
+  const bf16* vrow = (const bf16*)p.v + ((size_t)b * p.Nk + ki) * p.ldv + h * 64;
+  const float* lse_b = p.lse + ((size_t)b * p.H + h) * p.Nq;
+  const float* dlt_b = p.delta + ((size_t)b * p.H + h) * p.Nq;
+
+  // this workgroup's share of the 64-query tiles
+  const int nqt_all = (p.Nq + 63) / 64, tps = (nqt_all + p.qsplits - 1) / p.qsplits;
+  const int qt0 = qs * tps, nqt = min(nqt_all, qt0 + tps);
+  AttnFragOff fo;
+  fo.init(lane);
+  AttnTileCopy cq, cd;
+  cq.init(wave, lane, p.ldq);
+  cd.init(wave, lane, p.lddo);
+  if (qt0 < nqt) {
+    cq.issue(qr, qt0 * 64, p.ldq, Qs[0], wave);
+    cd.issue(dr, qt0 * 64, p.lddo, Ds[0], wave);
+  }
+  float r_lse = 0.f, r_dlt = 0.f;
+  auto load_stats = [&](int qt) {
+    if (tid < 64) {
+      const int qi = qt * 64 + tid;
+      r_lse = qi < p.Nq ? lse_b[qi] * LOG2E : INFINITY;
+      r_dlt = qi < p.Nq ? dlt_b[qi] : 0.f;
+    }
+  };
+  auto store_stats = [&](int buf) {
+    if (tid < 64) { lse_s[buf][tid] = r_lse; dlt_s[buf][tid] = r_dlt; }
+  };
+  load_stats(qt0);
+
+  bf16x8 kf[KC], vf[KC];
+#pragma unroll
+  for (int c = 0; c < KC; ++c) {
+    kf[c] = ld8(krow + 16 * c + 8 * g, kok);
+    vf[c] = ld8(vrow + 16 * c + 8 * g, kok);
+  }
+  f32x16 dkacc[DT], dvacc[DT];
+#pragma unroll
+  for (int i = 0; i < DT; ++i)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) { dkacc[i][r] = 0.f; dvacc[i][r] = 0.f; }
+
+  store_stats(0);
+  wait_vmcnt<0>();
+  __syncthreads();
+
+  for (int qt = qt0; qt < nqt; ++qt) {
+    const int buf = (qt - qt0) & 1;
+    const bool more = qt + 1 < nqt;
+    if (more) {
+      cq.issue(qr, (qt + 1) * 64, p.ldq, Qs[buf ^ 1], wave);
+      cd.issue(dr, (qt + 1) * 64, p.lddo, Ds[buf ^ 1], wave);
+      load_stats(qt + 1);
+    }
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+      f32x16 s, dp;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) { s[r] = 0.f; dp[r] = 0.f; }
+#pragma unroll
+      for (int c = 0; c < KC; ++c) {
+        s = mfma32(attn_row_frag(Qs[buf], fo, t, c), kf[c], s);
+        dp = mfma32(attn_row_frag(Ds[buf], fo, t, c), vf[c], dp);
+      }
+      f32x16 ds;
+#pragma unroll
+      for (int r4 = 0; r4 < 4; ++r4) {
+        const f32x4 l4 = *reinterpret_cast<const f32x4*>(&lse_s[buf][32 * t + 8 * r4 + 4 * g]);
+        const f32x4 d4 = *reinterpret_cast<const f32x4*>(&dlt_s[buf][32 * t + 8 * r4 + 4 * g]);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          const int r = 4 * r4 + u;
+          // a lane whose key is past Nk computes garbage that stays in its own accumulator columns,
+          // which are never stored; queries past Nq have lse = +inf, hence pr = 0
+          const float pr = __builtin_amdgcn_exp2f(fmaf(s[r], p.scale_log2, -l4[u]));
+          s[r] = pr;
+          ds[r] = pr * (dp[r] - d4[u]);
+        }
+      }
+#pragma unroll
+      for (int cc = 0; cc < 2; ++cc) {
+        const bf16x8 pf = pack8(s, 8 * cc);
+        const bf16x8 dsf = pack8(ds, 8 * cc);
+#pragma unroll
+        for (int i = 0; i < DT; ++i) {
+          dvacc[i] = mfma32(attn_tr_frag(Ds[buf], fo, 32 * t + 16 * cc, i), pf, dvacc[i]);
+          dkacc[i] = mfma32(attn_tr_frag(Qs[buf], fo, 32 * t + 16 * cc, i), dsf, dkacc[i]);
+        }
+      }
+    }
+    if (more) store_stats(buf ^ 1);
+    wait_vmcnt<0>();
+    __syncthreads();
+  }
+  if (kok && p.qsplits > 1) {
+    // fp32 partial sums of this query range; reduced in a fixed order by attn_dkv_reduce_kernel
+    const size_t hd = (size_t)p.H * 64, rows = (size_t)p.B * p.Nk;
+    float* pk = p.dkv_partial + ((size_t)qs * rows + (size_t)b * p.Nk + ki) * hd + h * 64;
+    float* pv = pk + (size_t)p.qsplits * rows * hd;
+#pragma unroll
+    for (int i = 0; i < DT; ++i)
+#pragma unroll
+      for (int r4 = 0; r4 < 4; ++r4) {
+        const int col = 32 * i + 8 * r4 + 4 * g;
+        f32x4 ok_, ov;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) { ok_[u] = dkacc[i][4 * r4 + u] * p.scale; ov[u] = dvacc[i][4 * r4 + u]; }
+        *reinterpret_cast<f32x4*>(pk + col) = ok_;
+        *reinterpret_cast<f32x4*>(pv + col) = ov;
+      }
+  } else if (kok) {
+    bf16* dkb = (bf16*)p.dk + ((size_t)b * p.Nk + ki) * p.lddk + h * 64;
+    bf16* dvb = (bf16*)p.dv + ((size_t)b * p.Nk + ki) * p.lddv + h * 64;
+#pragma unroll
+    for (int i = 0; i < DT; ++i)
+#pragma unroll
+      for (int r4 = 0; r4 < 4; ++r4) {
+        const int col = 32 * i + 8 * r4 + 4 * g;
+        bf16x4 ok_, ov;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) { ok_[u] = (bf16)(dkacc[i][4 * r4 + u] * p.scale); ov[u] = (bf16)dvacc[i][4 * r4 + u]; }
+        *reinterpret_cast<bf16x4*>(dkb + col) = ok_;
+        *reinterpret_cast<bf16x4*>(dvb + col) = ov;
+      }
+  }
+}
+
 // dk[row, col] = sum_qs partial_k[qs][row][col] (ascending qs), same for dv; 4 columns per thread.
 __global__ void attn_dkv_reduce_kernel(const float* __restrict__ partial, int qsplits, size_t rows, int hd, bf16* __restrict__ dk, int lddk,
                                        bf16* __restrict__ dv, int lddv) {
@@ -922,9 +1218,12 @@ int launch_attn_bwd(const AttnArgs& a, hipStream_t s) {
     // algorithmic backward work = 2x forward, split evenly between the two kernels for accounting
     const double fl = 4.0 * a.B * a.H * (double)a.Nq * a.Nk * a.d_head;
     const double by = 2.0 * (double)a.B * a.H * a.d_head * (3.0 * a.Nq + 2.0 * a.Nk);
+    // d_head = 64: streamed tiles copied straight to LDS; a (batch, head) slice is addressed with 32-bit byte offsets
+    const bool dtl = a.d_head == 64 && (size_t)std::max(a.Nq, a.Nk) * std::max(std::max(a.ldq, a.lddo), std::max(a.ldk, a.ldv)) * 2 < (1ull << 31);
     {
       KScope ks(KK_ATTN_BWD_DQ, fl, by, s, a.Nq, a.Nk, a.d_head);
-      if (a.d_head <= 64) hipLaunchKernelGGL(attn_bwd_dq_bf16_kernel<64>, gq, dim3(256), 0, s, k);
+      if (dtl) hipLaunchKernelGGL(attn_bwd_dq_dtl_kernel, gq, dim3(256), 0, s, k);
+      else if (a.d_head <= 64) hipLaunchKernelGGL(attn_bwd_dq_bf16_kernel<64>, gq, dim3(256), 0, s, k);
       else hipLaunchKernelGGL(attn_bwd_dq_bf16_kernel<96>, gq, dim3(256), 0, s, k);
     }
     {
@@ -940,7 +1239,8 @@ int launch_attn_bwd(const AttnArgs& a, hipStream_t s) {
       dim3 gk2(gk.x * qsplit);
       {
         KScope ks(KK_ATTN_BWD_DKV, fl, by, s, a.Nq, a.Nk, a.d_head);
-        if (a.d_head <= 64) hipLaunchKernelGGL(attn_bwd_dkv_bf16_kernel<64>, gk2, dim3(256), 0, s, k2);
+        if (dtl) hipLaunchKernelGGL(attn_bwd_dkv_dtl_kernel, gk2, dim3(256), 0, s, k2);
+        else if (a.d_head <= 64) hipLaunchKernelGGL(attn_bwd_dkv_bf16_kernel<64>, gk2, dim3(256), 0, s, k2);
         else hipLaunchKernelGGL(attn_bwd_dkv_bf16_kernel<96>, gk2, dim3(256), 0, s, k2);
       }
       if (qsplit > 1) {
