@@ -10,6 +10,8 @@
 // contraction index moved (V, and K/Q/dO in the backward) is read from its row-major
 // LDS tile with the transposing LDS load.  The backward is split into a dQ kernel and
 // a dK/dV kernel so that no floating-point atomics are needed (run-to-run identical).
+// For d_head = 64 the streamed tiles are copied global -> LDS directly (the *_dtl_kernel variants);
+// other head widths stage them through registers.
 //
 // fp32 path: one wave per query (or key) row, plain FMA; used by the small fp32
 // configuration only.
