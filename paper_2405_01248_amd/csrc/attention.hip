@@ -10,8 +10,8 @@
 // contraction index moved (V, and K/Q/dO in the backward) is read from its row-major
 // LDS tile with the transposing LDS load.  The backward is split into a dQ kernel and
 // a dK/dV kernel so that no floating-point atomics are needed (run-to-run identical).
-// For d_head = 64 the streamed tiles are copied global -> LDS directly (the *_dtl_kernel variants);
-// other head widths stage them through registers.
+// The streamed tiles are copied global -> LDS directly (`buffer_load ... lds`) into unpadded tiles whose
+// 16-byte chunks are permuted per row, so that both ways of reading a tile stay free of bank conflicts.
 //
 // fp32 path: one wave per query (or key) row, plain FMA; used by the small fp32
 // configuration only.
@@ -44,30 +44,83 @@ struct AttnK {
 constexpr float LOG2E = 1.4426950408889634f;
 constexpr float LN2 = 0.6931471805599453f;
 
-// Copies a [64 x DHP] tile (rows row0.., zero-filled outside [0,nrows) x [0,dh)) into registers / LDS.
-template <int DHP, int NT>
-struct TileLoader {
-  static constexpr int CHUNKS = 64 * DHP / 8;
-  static constexpr int PER = (CHUNKS + NT - 1) / NT;
-  bf16x8 r[PER];
-  __device__ __forceinline__ void load(const bf16* base, int ld, int row0, int nrows, int dh, int tid) {
+// Layout of a streamed [64 x DHP] bf16 tile in LDS: 64 rows of DHP / 8 16-byte chunks, no padding; the chunk
+// at position pos of a row is chunk pos ^ key(row).  A tile is read two ways -- by rows as an MFMA A operand
+// (16 consecutive rows, one chunk each, per 256 bytes of LDS bandwidth) and through the transposing load (4
+// consecutive rows x 64 bytes) -- and the key keeps both conflict-free:
+//   DHP = 64 (128-byte rows): key = row bits (0, 2, 1): a bijection of row & 7 whose bit 2 is row bit 1, so
+//     8 consecutive rows land in 8 different positions and the 4 rows of a transposing read in 4 different
+//     64-byte bank groups;
+//   DHP = 96 (192-byte rows): consecutive rows already start 192 bytes apart, i.e. in different 64-byte groups;
+//     rows r and r + 4 share one, so key = (row >> 2) & 3 moves them apart inside the group.
+template <int DHP> struct AttnTile;
+template <> struct AttnTile<64> {
+  static constexpr int PIECES = 2;     // 1 KB copy instructions per wave and tile (16 rows)
+  static __device__ __forceinline__ int key(int row) { return (row & 1) | ((row & 4) >> 1) | ((row & 2) << 1); }
+};
+template <> struct AttnTile<96> {
+  static constexpr int PIECES = 3;
+  static __device__ __forceinline__ int key(int row) { return (row >> 2) & 3; }
+};
+
+// Global -> LDS copy of one tile (`buffer_load ... lds`: the wave's 64 x 16 bytes land contiguously in LDS).
+// A wave owns rows 16 * wave .. + 15; each lane keeps the byte offset, inside the (batch, head) slice, of the
+// chunk that belongs at its LDS position.  Chunks past d_head get an offset of 2^31, which stays outside the
+// buffer descriptor's range whatever tile offset is added: they, like rows past the end of the slice, arrive
+// as zeros without touching memory.
+template <int DHP>
+struct AttnTileCopy {
+  using T = AttnTile<DHP>;
+  uint32_t off[T::PIECES];
+  __device__ __forceinline__ void init(int wave, int lane, int ld, int dh) {
 #pragma unroll
-    for (int i = 0; i < PER; ++i) {
-      const int id = tid + i * NT;
-      const int row = id / (DHP / 8), c = (id % (DHP / 8)) * 8;
-      const bool ok = (CHUNKS % NT == 0 || id < CHUNKS) && row0 + row < nrows && c < dh;
-      r[i] = ld8(base + (size_t)(row0 + row) * ld + c, ok);
+    for (int j = 0; j < T::PIECES; ++j) {
+      const int o = 1024 * j + 16 * lane;                     // byte inside the wave's 16-row block
+      const int row = 16 * wave + o / (2 * DHP), pos = (o % (2 * DHP)) / 16;
+      const int chunk = pos ^ T::key(row);
+      off[j] = 8 * chunk < dh ? (uint32_t)(row * ld + 8 * chunk) * 2u : 0x80000000u;
     }
   }
-  __device__ __forceinline__ void store(bf16* tile, int tld, int tid) const {
+  // rows row0 .. row0 + 63 of the slice behind r (the tile offset goes into the per-lane offset: only that
+  // one is range-checked)
+  __device__ __forceinline__ void issue(rsrc_t r, int row0, int ld, bf16* stage, int wave) const {
 #pragma unroll
-    for (int i = 0; i < PER; ++i) {
-      const int id = tid + i * NT;
-      const int row = id / (DHP / 8), c = (id % (DHP / 8)) * 8;
-      if (CHUNKS % NT == 0 || id < CHUNKS) *reinterpret_cast<bf16x8*>(tile + row * tld + c) = r[i];
-    }
+    for (int j = 0; j < T::PIECES; ++j)
+      async_copy_16B_buf(r, off[j] + (uint32_t)row0 * (uint32_t)ld * 2u, 0, stage + 16 * wave * DHP + 512 * j);
   }
 };
+
+// Per-lane element offsets of the fragment reads, computed once.  A row fragment (rows 32 * t + l32, k-chunk
+// c) is at row[c] + 32 * DHP * t.  A transposed fragment in the slot order of frag_from_mc_accorder (rows
+// r0 .. r0 + 15 with r0 a multiple of 16, which leaves the keys alone; columns 32 * i .. + 31) is read as two
+// halves at tr_lo[i] + DHP * r0 and tr_hi[i] + DHP * r0 (8 rows apart).
+template <int DHP>
+struct AttnFragOff {
+  using T = AttnTile<DHP>;
+  int row[DHP / 16], tr_lo[DHP / 32], tr_hi[DHP / 32];
+  __device__ __forceinline__ void init(int lane) {
+    const int g = lane >> 5, l32 = lane & 31, b = lane >> 4, j = lane & 15;
+#pragma unroll
+    for (int c = 0; c < DHP / 16; ++c) row[c] = l32 * DHP + 8 * ((2 * c + g) ^ T::key(l32));
+    const int r = 4 * (b >> 1) + (j >> 2);
+#pragma unroll
+    for (int i = 0; i < DHP / 32; ++i) {
+      const int chunk = 4 * i + 2 * (b & 1) + ((j & 3) >> 1);
+      tr_lo[i] = r * DHP + 8 * (chunk ^ T::key(r)) + 4 * (j & 1);
+      tr_hi[i] = (r + 8) * DHP + 8 * (chunk ^ T::key(r + 8)) + 4 * (j & 1);
+    }
+  }
+  __device__ __forceinline__ bf16x8 row_frag(const bf16* tile, int t, int c) const {
+    return *reinterpret_cast<const bf16x8*>(tile + row[c] + 32 * DHP * t);
+  }
+  __device__ __forceinline__ bf16x8 tr_frag(const bf16* tile, int r0, int i) const {
+    const bf16x4 lo = lds_read_tr(tile + tr_lo[i] + DHP * r0);
+    const bf16x4 hi = lds_read_tr(tile + tr_hi[i] + DHP * r0);
+    return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+  }
+};
+// byte extent of a (batch, head) slice of n rows with leading dimension ld (elements), d_head columns
+__device__ __forceinline__ uint32_t attn_slice_bytes(int n, int ld, int dh) { return (uint32_t)(((size_t)(n - 1) * ld + dh) * 2); }
 
 __device__ __forceinline__ bf16x8 pack8(const f32x16& v, int off) {
   bf16x8 o;
@@ -93,208 +146,35 @@ __device__ __forceinline__ void attn_block_map(int id, int ntiles, int BH, int& 
 }
 
 // ------------------------------------------------------------------ forward (bf16)
-// A wave owns QT tiles of 32 queries; every K / V fragment fetched from LDS is used for all of
-// them (QT = 2 halves the LDS traffic per FLOP, and the MFMAs of one query tile can overlap the
-// softmax arithmetic of the other).  A workgroup covers 128 * QT queries.
-template <int DHP, bool CAUSAL, int QT>
-__global__ void __launch_bounds__(256, (QT == 1 && DHP == 64) ? 3 : 2) attn_fwd_bf16_kernel(const AttnK p) {
-  constexpr int KC = DHP / 16, DT = DHP / 32, BQ = 128 * QT;
-  constexpr int K_LD = DHP + 8, V_LD = DHP + 16;
-  __shared__ __attribute__((aligned(16))) bf16 Ks[2][64 * K_LD];
-  __shared__ __attribute__((aligned(16))) bf16 Vs[2][64 * V_LD];
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 5, l32 = lane & 31;
-  int qtile, bh;
-  attn_block_map(blockIdx.x, (p.Nq + BQ - 1) / BQ, p.B * p.H, qtile, bh);
-  const int b = bh / p.H, h = bh % p.H;
-  const int q0 = qtile * BQ + wave * 32 * QT;          // first query of this wave
-  const bf16* qb = (const bf16*)p.q + (size_t)b * p.Nq * p.ldq + h * p.dh;
-  const bf16* kb = (const bf16*)p.k + (size_t)b * p.Nk * p.ldk + h * p.dh;
-  const bf16* vb = (const bf16*)p.v + (size_t)b * p.Nk * p.ldv + h * p.dh;
-
-  bf16x8 qf[QT][KC];
-#pragma unroll
-  for (int j = 0; j < QT; ++j)
-#pragma unroll
-    for (int c = 0; c < KC; ++c) {
-      const int qi = q0 + 32 * j + l32;
-      qf[j][c] = ld8(qb + (size_t)qi * p.ldq + 16 * c + 8 * g, qi < p.Nq && 16 * c + 8 * g < p.dh);
-    }
-
-  f32x16 oacc[QT][DT];
-  float m[QT], lsum[QT];
-#pragma unroll
-  for (int j = 0; j < QT; ++j) {
-    m[j] = -INFINITY; lsum[j] = 0.f;
-#pragma unroll
-    for (int i = 0; i < DT; ++i)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) oacc[j][i][r] = 0.f;
-  }
-
-  int nkt = (p.Nk + 63) / 64;
-  if (CAUSAL) nkt = min(nkt, (min(p.Nq, qtile * BQ + BQ) + 63) / 64);
-
-  TileLoader<DHP, 256> lk, lv;
-  lk.load(kb, p.ldk, 0, p.Nk, p.dh, tid);
-  lv.load(vb, p.ldv, 0, p.Nk, p.dh, tid);
-  lk.store(Ks[0], K_LD, tid);
-  lv.store(Vs[0], V_LD, tid);
-  __syncthreads();
-
-  for (int kt = 0; kt < nkt; ++kt) {
-    const int buf = kt & 1;
-    const bool more = kt + 1 < nkt;
-    if (more) {
-      lk.load(kb, p.ldk, (kt + 1) * 64, p.Nk, p.dh, tid);
-      lv.load(vb, p.ldv, (kt + 1) * 64, p.Nk, p.dh, tid);
-    }
-    // S^T = K Q^T for the wave's QT query tiles: K fragments are fetched once
-    f32x16 s[QT][2];
-#pragma unroll
-    for (int j = 0; j < QT; ++j)
-#pragma unroll
-      for (int t = 0; t < 2; ++t)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) s[j][t][r] = 0.f;
-#pragma unroll
-    for (int t = 0; t < 2; ++t)
-#pragma unroll
-      for (int c = 0; c < KC; ++c) {
-        const bf16x8 a = *reinterpret_cast<const bf16x8*>(&Ks[buf][(32 * t + l32) * K_LD + 16 * c + 8 * g]);
-#pragma unroll
-        for (int j = 0; j < QT; ++j) s[j][t] = mfma32(a, qf[j][c], s[j][t]);
-      }
-    // online softmax, one query column per lane (shared with lane ^ 32)
-    const bool key_edge = kt * 64 + 64 > p.Nk;
-#pragma unroll
-    for (int j = 0; j < QT; ++j) {
-      const int qi = q0 + 32 * j + l32;
-      const bool edge = key_edge || (CAUSAL && kt * 64 + 63 > q0 + 32 * j);
-      // masking only in tiles that cross the end of the keys or the causal diagonal (one wave-uniform
-      // branch around a block of selects; a test per element would be compiled into a branch per element)
-      if (edge) {
-#pragma unroll
-        for (int t = 0; t < 2; ++t)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            const int key = kt * 64 + 32 * t + acc_row(r, g);
-            const bool dead = key >= p.Nk || (CAUSAL && key > qi);
-            s[j][t][r] = dead ? -INFINITY : s[j][t][r];
-          }
-      }
-      // running maximum over raw scores (the scale is positive, so it commutes with max)
-      float mx = -INFINITY;
-#pragma unroll
-      for (int t = 0; t < 2; ++t)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[j][t][r]);
-      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-      mx = fmaxf(m[j], mx * p.scale_log2);                 // m[j] is kept in the scaled (log2) domain
-      // The reference point only has to bound the exponents, not equal the maximum: it is moved (and the
-      // accumulators rescaled) when some query of the wave has outgrown it by 2^8; until then the
-      // probabilities of this tile are taken relative to the old one (at most 256, exact in the final
-      // O = acc / sum and LSE = ref + log sum).  Wave-uniform, so the rescale is skipped for most tiles.
-      const bool bump = __any(mx > m[j] + 8.0f);
-      mx = bump ? mx : m[j];
-      const float mref = (mx == -INFINITY) ? 0.f : mx;
-      float rs = 0.f;
-#pragma unroll
-      for (int t = 0; t < 2; ++t)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const float e = __builtin_amdgcn_exp2f(fmaf(s[j][t][r], p.scale_log2, -mref));
-          s[j][t][r] = e;
-          rs += e;
-        }
-      rs += __shfl_xor(rs, 32, 64);
-      if (bump) {
-        const float alpha = __builtin_amdgcn_exp2f(m[j] - mref);
-        lsum[j] *= alpha;
-#pragma unroll
-        for (int i = 0; i < DT; ++i)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) oacc[j][i][r] *= alpha;
-      }
-      lsum[j] += rs;
-      m[j] = mx;
-    }
-    // O^T += V^T P^T: V fragments are fetched once for all query tiles
-#pragma unroll
-    for (int t = 0; t < 2; ++t)
-#pragma unroll
-      for (int cc = 0; cc < 2; ++cc) {
-        bf16x8 pf[QT];
-#pragma unroll
-        for (int j = 0; j < QT; ++j) pf[j] = pack8(s[j][t], 8 * cc);
-#pragma unroll
-        for (int i = 0; i < DT; ++i) {
-          const bf16x8 a = frag_from_mc_accorder(&Vs[buf][(32 * t + 16 * cc) * V_LD + 32 * i], V_LD, lane);
-#pragma unroll
-          for (int j = 0; j < QT; ++j) oacc[j][i] = mfma32(a, pf[j], oacc[j][i]);
-        }
-      }
-    if (more) {
-      lk.store(Ks[buf ^ 1], K_LD, tid);
-      lv.store(Vs[buf ^ 1], V_LD, tid);
-    }
-    __syncthreads();
-  }
-
-#pragma unroll
-  for (int j = 0; j < QT; ++j) {
-    const int qi = q0 + 32 * j + l32;
-    if (qi < p.Nq) {
-      const float inv = lsum[j] > 0.f ? 1.0f / lsum[j] : 0.f;
-      bf16* ob = (bf16*)p.o + ((size_t)b * p.Nq + qi) * p.ldo + h * p.dh;
-#pragma unroll
-      for (int i = 0; i < DT; ++i)
-#pragma unroll
-        for (int r4 = 0; r4 < 4; ++r4) {
-          const int col = 32 * i + 8 * r4 + 4 * g;
-          if (col < p.dh) {
-            bf16x4 o;
-#pragma unroll
-            for (int u = 0; u < 4; ++u) o[u] = (bf16)(oacc[j][i][4 * r4 + u] * inv);
-            *reinterpret_cast<bf16x4*>(ob + col) = o;
-          }
-        }
-      if (p.lse && g == 0) p.lse[((size_t)b * p.H + h) * p.Nq + qi] = m[j] * LN2 + logf(lsum[j]);
-    }
-  }
-}
-
-// The same forward for d_head = 64 with the K and V tiles copied global -> LDS directly (no register
-// staging: 16 fewer registers per lane, no LDS stores in the loop).  A [64 x 64] bf16 tile is 64 rows of
-// eight 16-byte chunks with no padding; a wave copies 8 rows per instruction, lane = 8 * row + position,
-// and the chunk a position holds is position ^ key(row), so that the fragment reads stay conflict-free:
-// K (rows read as MFMA A fragments, lanes vary in the row): key = row & 7;
-// V (read by the transposing load, 4 rows x 64 bytes per half-wave): key = 4 * ((row >> 1) & 1).
-// Rows past the end of the keys come back as zeros from the buffer descriptor's range check.
-__device__ __forceinline__ int attn_kkey(int row) { return row & 7; }
-__device__ __forceinline__ int attn_vkey(int row) { return 4 * ((row >> 1) & 1); }
-
-template <bool CAUSAL>
-__global__ void __launch_bounds__(256, 4) attn_fwd_dtl_kernel(const AttnK p) {
-  constexpr int KC = 4, DT = 2, BQ = 128, TILE = 64 * 64;
+// A workgroup covers 128 queries (32 per wave) and walks the keys in 64-row tiles, two LDS stages.
+template <int DHP, bool CAUSAL>
+__global__ void __launch_bounds__(256, DHP == 64 ? 4 : 3) attn_fwd_bf16_kernel(const AttnK p) {
+  constexpr int KC = DHP / 16, DT = DHP / 32, BQ = 128, TILE = 64 * DHP;
   __shared__ __attribute__((aligned(1024))) bf16 Ks[2][TILE];
   __shared__ __attribute__((aligned(1024))) bf16 Vs[2][TILE];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 5, l32 = lane & 31;
   int qtile, bh;
   attn_block_map(blockIdx.x, (p.Nq + BQ - 1) / BQ, p.B * p.H, qtile, bh);
   const int b = bh / p.H, h = bh % p.H;
-  const int q0 = qtile * BQ + wave * 32;
-  const bf16* qb = (const bf16*)p.q + (size_t)b * p.Nq * p.ldq + h * 64;
-  const bf16* kb = (const bf16*)p.k + (size_t)b * p.Nk * p.ldk + h * 64;
-  const bf16* vb = (const bf16*)p.v + (size_t)b * p.Nk * p.ldv + h * 64;
-  const rsrc_t kr = make_rsrc(kb, (uint32_t)(((size_t)(p.Nk - 1) * p.ldk + 64) * 2));
-  const rsrc_t vr = make_rsrc(vb, (uint32_t)(((size_t)(p.Nk - 1) * p.ldv + 64) * 2));
+  const int q0 = qtile * BQ + wave * 32;               // first query of this wave
+  const int qi = q0 + l32;
+  const bf16* qb = (const bf16*)p.q + (size_t)b * p.Nq * p.ldq + h * p.dh;
+  const bf16* kb = (const bf16*)p.k + (size_t)b * p.Nk * p.ldk + h * p.dh;
+  const bf16* vb = (const bf16*)p.v + (size_t)b * p.Nk * p.ldv + h * p.dh;
+  const rsrc_t kr = make_rsrc(kb, attn_slice_bytes(p.Nk, p.ldk, p.dh));
+  const rsrc_t vr = make_rsrc(vb, attn_slice_bytes(p.Nk, p.ldv, p.dh));
+
+  AttnFragOff<DHP> fo;
+  fo.init(lane);
+  AttnTileCopy<DHP> ck, cv;
+  ck.init(wave, lane, p.ldk, p.dh);
+  cv.init(wave, lane, p.ldv, p.dh);
+  ck.issue(kr, 0, p.ldk, Ks[0], wave);
+  cv.issue(vr, 0, p.ldv, Vs[0], wave);
 
   bf16x8 qf[KC];
 #pragma unroll
-  for (int c = 0; c < KC; ++c) {
-    const int qi = q0 + l32;
-    qf[c] = ld8(qb + (size_t)qi * p.ldq + 16 * c + 8 * g, qi < p.Nq);
-  }
+  for (int c = 0; c < KC; ++c) qf[c] = ld8(qb + (size_t)qi * p.ldq + 16 * c + 8 * g, qi < p.Nq && 16 * c + 8 * g < p.dh);
   f32x16 oacc[DT];
   float m = -INFINITY, lsum = 0.f;
 #pragma unroll
@@ -304,31 +184,16 @@ __global__ void __launch_bounds__(256, 4) attn_fwd_dtl_kernel(const AttnK p) {
 
   int nkt = (p.Nk + 63) / 64;
   if (CAUSAL) nkt = min(nkt, (min(p.Nq, qtile * BQ + BQ) + 63) / 64);
-
-  // this wave's share of a tile: rows 16 * wave .. + 15 of K and of V, two 8-row pieces each
-  uint32_t ko[2], vo[2];
-#pragma unroll
-  for (int j = 0; j < 2; ++j) {
-    const int row = 16 * wave + 8 * j + (lane >> 3), pc = lane & 7;
-    ko[j] = (uint32_t)(row * p.ldk + 8 * (pc ^ attn_kkey(row))) * 2u;
-    vo[j] = (uint32_t)(row * p.ldv + 8 * (pc ^ attn_vkey(row))) * 2u;
-  }
-  auto copy_tile = [&](int kt, int st) {
-#pragma unroll
-    for (int j = 0; j < 2; ++j) {
-      // the tile's offset goes into the per-lane offset: only that one is range-checked
-      async_copy_16B_buf(kr, ko[j] + (uint32_t)kt * 64u * (uint32_t)p.ldk * 2u, 0, &Ks[st][(16 * wave + 8 * j) * 64]);
-      async_copy_16B_buf(vr, vo[j] + (uint32_t)kt * 64u * (uint32_t)p.ldv * 2u, 0, &Vs[st][(16 * wave + 8 * j) * 64]);
-    }
-  };
-  copy_tile(0, 0);
   wait_vmcnt<0>();
   __syncthreads();
 
   for (int kt = 0; kt < nkt; ++kt) {
     const int buf = kt & 1;
-    // every wave left stage buf ^ 1 at the barrier that ended the previous iteration
-    if (kt + 1 < nkt) copy_tile(kt + 1, buf ^ 1);
+    if (kt + 1 < nkt) {      // every wave left stage buf ^ 1 at the barrier that ended the previous iteration
+      ck.issue(kr, (kt + 1) * 64, p.ldk, Ks[buf ^ 1], wave);
+      cv.issue(vr, (kt + 1) * 64, p.ldv, Vs[buf ^ 1], wave);
+    }
+    // S^T = K Q^T
     f32x16 s[2];
 #pragma unroll
     for (int t = 0; t < 2; ++t)
@@ -337,12 +202,10 @@ __global__ void __launch_bounds__(256, 4) attn_fwd_dtl_kernel(const AttnK p) {
 #pragma unroll
     for (int t = 0; t < 2; ++t)
 #pragma unroll
-      for (int c = 0; c < KC; ++c) {
-        const int row = 32 * t + l32;
-        const bf16x8 a = *reinterpret_cast<const bf16x8*>(&Ks[buf][row * 64 + 8 * ((2 * c + g) ^ attn_kkey(row))]);
-        s[t] = mfma32(a, qf[c], s[t]);
-      }
-    const int qi = q0 + l32;
+      for (int c = 0; c < KC; ++c) s[t] = mfma32(fo.row_frag(Ks[buf], t, c), qf[c], s[t]);
+    // online softmax, one query column per lane (shared with lane ^ 32).  Masking only in tiles that cross the
+    // end of the keys or the causal diagonal (one wave-uniform branch around a block of selects; a test per
+    // element would be compiled into a branch per element)
     const bool edge = kt * 64 + 64 > p.Nk || (CAUSAL && kt * 64 + 63 > q0);
     if (edge) {
 #pragma unroll
@@ -354,14 +217,18 @@ __global__ void __launch_bounds__(256, 4) attn_fwd_dtl_kernel(const AttnK p) {
           s[t][r] = dead ? -INFINITY : s[t][r];
         }
     }
-    // online softmax with a lazily moved reference point, as in attn_fwd_bf16_kernel
+    // running maximum over raw scores (the scale is positive, so it commutes with max)
     float mx = -INFINITY;
 #pragma unroll
     for (int t = 0; t < 2; ++t)
 #pragma unroll
       for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[t][r]);
     mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-    mx = fmaxf(m, mx * p.scale_log2);
+    mx = fmaxf(m, mx * p.scale_log2);                    // m is kept in the scaled (log2) domain
+    // The reference point only has to bound the exponents, not equal the maximum: it is moved (and the
+    // accumulators rescaled) when some query of the wave has outgrown it by 2^8; until then the
+    // probabilities of this tile are taken relative to the old one (at most 256, exact in the final
+    // O = acc / sum and LSE = ref + log sum).  Wave-uniform, so the rescale is skipped for most tiles.
     const bool bump = __any(mx > m + 8.0f);
     mx = bump ? mx : m;
     const float mref = (mx == -INFINITY) ? 0.f : mx;
@@ -385,39 +252,33 @@ __global__ void __launch_bounds__(256, 4) attn_fwd_dtl_kernel(const AttnK p) {
     }
     lsum += rs;
     m = mx;
-    // O^T += V^T P^T; the transposing load takes, per lane, 4 consecutive channels of one key row
-    const int vb4 = lane >> 4, vj = lane & 15;
+    // O^T += V^T P^T
 #pragma unroll
     for (int t = 0; t < 2; ++t)
 #pragma unroll
       for (int cc = 0; cc < 2; ++cc) {
         const bf16x8 pf = pack8(s[t], 8 * cc);
 #pragma unroll
-        for (int i = 0; i < DT; ++i) {
-          const int row = 32 * t + 16 * cc + 4 * (vb4 >> 1) + (vj >> 2);       // and row + 8 (same key)
-          const int chunk = 4 * i + 2 * (vb4 & 1) + ((vj & 3) >> 1);
-          const bf16* a0 = &Vs[buf][row * 64 + 8 * (chunk ^ attn_vkey(row)) + 4 * (vj & 1)];
-          const bf16x4 lo = lds_read_tr(a0);
-          const bf16x4 hi = lds_read_tr(a0 + 8 * 64);
-          oacc[i] = mfma32(__builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7), pf, oacc[i]);
-        }
+        for (int i = 0; i < DT; ++i) oacc[i] = mfma32(fo.tr_frag(Vs[buf], 32 * t + 16 * cc, i), pf, oacc[i]);
       }
     wait_vmcnt<0>();      // this wave's pieces of the next tile have landed
     __syncthreads();      // ... and everybody's; all reads of stage buf are done
   }
 
-  const int qi = q0 + l32;
   if (qi < p.Nq) {
     const float inv = lsum > 0.f ? 1.0f / lsum : 0.f;
-    bf16* ob = (bf16*)p.o + ((size_t)b * p.Nq + qi) * p.ldo + h * 64;
+    bf16* ob = (bf16*)p.o + ((size_t)b * p.Nq + qi) * p.ldo + h * p.dh;
 #pragma unroll
     for (int i = 0; i < DT; ++i)
 #pragma unroll
       for (int r4 = 0; r4 < 4; ++r4) {
-        bf16x4 o;
+        const int col = 32 * i + 8 * r4 + 4 * g;
+        if (col < p.dh) {
+          bf16x4 o;
 #pragma unroll
-        for (int u = 0; u < 4; ++u) o[u] = (bf16)(oacc[i][4 * r4 + u] * inv);
-        *reinterpret_cast<bf16x4*>(ob + 32 * i + 8 * r4 + 4 * g) = o;
+          for (int u = 0; u < 4; ++u) o[u] = (bf16)(oacc[i][4 * r4 + u] * inv);
+          *reinterpret_cast<bf16x4*>(ob + col) = o;
+        }
       }
     if (p.lse && g == 0) p.lse[((size_t)b * p.H + h) * p.Nq + qi] = m * LN2 + logf(lsum);
   }
@@ -448,11 +309,10 @@ __global__ void attn_delta_kernel(const T* __restrict__ o, int ldo, const T* __r
 
 // ------------------------------------------------------------------ dQ (bf16)
 template <int DHP>
-__global__ void __launch_bounds__(256, DHP == 64 ? 3 : 2) attn_bwd_dq_bf16_kernel(const AttnK p) {
-  constexpr int KC = DHP / 16, DT = DHP / 32;
-  constexpr int LD = DHP + 8;
-  __shared__ __attribute__((aligned(16))) bf16 Ks[2][64 * LD];
-  __shared__ __attribute__((aligned(16))) bf16 Vs[2][64 * LD];
+__global__ void __launch_bounds__(256, DHP == 64 ? 4 : 2) attn_bwd_dq_bf16_kernel(const AttnK p) {
+  constexpr int KC = DHP / 16, DT = DHP / 32, TILE = 64 * DHP;
+  __shared__ __attribute__((aligned(1024))) bf16 Ks[2][TILE];
+  __shared__ __attribute__((aligned(1024))) bf16 Vs[2][TILE];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 5, l32 = lane & 31;
   int qtile, bh;
   attn_block_map(blockIdx.x, (p.Nq + 127) / 128, p.B * p.H, qtile, bh);
@@ -461,8 +321,18 @@ __global__ void __launch_bounds__(256, DHP == 64 ? 3 : 2) attn_bwd_dq_bf16_kerne
   const bool qok = qi < p.Nq;
   const bf16* kb = (const bf16*)p.k + (size_t)b * p.Nk * p.ldk + h * p.dh;
   const bf16* vb = (const bf16*)p.v + (size_t)b * p.Nk * p.ldv + h * p.dh;
+  const rsrc_t kr = make_rsrc(kb, attn_slice_bytes(p.Nk, p.ldk, p.dh));
+  const rsrc_t vr = make_rsrc(vb, attn_slice_bytes(p.Nk, p.ldv, p.dh));
   const bf16* qrow = (const bf16*)p.q + ((size_t)b * p.Nq + qi) * p.ldq + h * p.dh;
   const bf16* dorow = (const bf16*)p.dout + ((size_t)b * p.Nq + qi) * p.lddo + h * p.dh;
+
+  AttnFragOff<DHP> fo;
+  fo.init(lane);
+  AttnTileCopy<DHP> ck, cv;
+  ck.init(wave, lane, p.ldk, p.dh);
+  cv.init(wave, lane, p.ldv, p.dh);
+  ck.issue(kr, 0, p.ldk, Ks[0], wave);
+  cv.issue(vr, 0, p.ldv, Vs[0], wave);
 
   bf16x8 qf[KC], dof[KC];
 #pragma unroll
@@ -496,19 +366,13 @@ __global__ void __launch_bounds__(256, DHP == 64 ? 3 : 2) attn_bwd_dq_bf16_kerne
     for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
 
   const int nkt = (p.Nk + 63) / 64;
-  TileLoader<DHP, 256> lk, lv;
-  lk.load(kb, p.ldk, 0, p.Nk, p.dh, tid);
-  lv.load(vb, p.ldv, 0, p.Nk, p.dh, tid);
-  lk.store(Ks[0], LD, tid);
-  lv.store(Vs[0], LD, tid);
+  wait_vmcnt<0>();
   __syncthreads();
-
   for (int kt = 0; kt < nkt; ++kt) {
     const int buf = kt & 1;
-    const bool more = kt + 1 < nkt;
-    if (more) {
-      lk.load(kb, p.ldk, (kt + 1) * 64, p.Nk, p.dh, tid);
-      lv.load(vb, p.ldv, (kt + 1) * 64, p.Nk, p.dh, tid);
+    if (kt + 1 < nkt) {      // every wave left stage buf ^ 1 at the barrier that ended the previous iteration
+      ck.issue(kr, (kt + 1) * 64, p.ldk, Ks[buf ^ 1], wave);
+      cv.issue(vr, (kt + 1) * 64, p.ldv, Vs[buf ^ 1], wave);
     }
     // Keys past Nk need no masking here: their K and V rows are zero in LDS, so dP = 0 and the
     // finite dS they get multiplies a zero K row in the dQ product.
@@ -519,10 +383,8 @@ __global__ void __launch_bounds__(256, DHP == 64 ? 3 : 2) attn_bwd_dq_bf16_kerne
       for (int r = 0; r < 16; ++r) { s[r] = 0.f; dp[r] = 0.f; }
 #pragma unroll
       for (int c = 0; c < KC; ++c) {
-        bf16x8 ka = *reinterpret_cast<const bf16x8*>(&Ks[buf][(32 * t + l32) * LD + 16 * c + 8 * g]);
-        bf16x8 va = *reinterpret_cast<const bf16x8*>(&Vs[buf][(32 * t + l32) * LD + 16 * c + 8 * g]);
-        s = mfma32(ka, qf[c], s);
-        dp = mfma32(va, dof[c], dp);
+        s = mfma32(fo.row_frag(Ks[buf], t, c), qf[c], s);
+        dp = mfma32(fo.row_frag(Vs[buf], t, c), dof[c], dp);
       }
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
@@ -533,16 +395,10 @@ __global__ void __launch_bounds__(256, DHP == 64 ? 3 : 2) attn_bwd_dq_bf16_kerne
       for (int cc = 0; cc < 2; ++cc) {
         const bf16x8 dsf = pack8(s, 8 * cc);
 #pragma unroll
-        for (int i = 0; i < DT; ++i) {
-          bf16x8 a = frag_from_mc_accorder(&Ks[buf][(32 * t + 16 * cc) * LD + 32 * i], LD, lane);
-          acc[i] = mfma32(a, dsf, acc[i]);
-        }
+        for (int i = 0; i < DT; ++i) acc[i] = mfma32(fo.tr_frag(Ks[buf], 32 * t + 16 * cc, i), dsf, acc[i]);
       }
     }
-    if (more) {
-      lk.store(Ks[buf ^ 1], LD, tid);
-      lv.store(Vs[buf ^ 1], LD, tid);
-    }
+    wait_vmcnt<0>();
     __syncthreads();
   }
   if (qok) {
@@ -563,13 +419,12 @@ __global__ void __launch_bounds__(256, DHP == 64 ? 3 : 2) attn_bwd_dq_bf16_kerne
 }
 
 // ------------------------------------------------------------------ dK, dV (bf16)
-// grid.x = ceil(Nk / 128); each wave owns 32 keys and walks all query tiles.
+// grid.x = ceil(Nk / 128) * qsplits; each wave owns 32 keys and walks its share of the query tiles.
 template <int DHP>
-__global__ void __launch_bounds__(256, DHP == 64 ? 2 : 1) attn_bwd_dkv_bf16_kernel(const AttnK p) {
-  constexpr int KC = DHP / 16, DT = DHP / 32;
-  constexpr int LD = DHP + 8;
-  __shared__ __attribute__((aligned(16))) bf16 Qs[2][64 * LD];
-  __shared__ __attribute__((aligned(16))) bf16 Ds[2][64 * LD];
+__global__ void __launch_bounds__(256, 2) attn_bwd_dkv_bf16_kernel(const AttnK p) {
+  constexpr int KC = DHP / 16, DT = DHP / 32, TILE = 64 * DHP;
+  __shared__ __attribute__((aligned(1024))) bf16 Qs[2][TILE];
+  __shared__ __attribute__((aligned(1024))) bf16 Ds[2][TILE];
   __shared__ __attribute__((aligned(16))) float lse_s[2][64];
   __shared__ __attribute__((aligned(16))) float dlt_s[2][64];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 5, l32 = lane & 31;
@@ -581,10 +436,37 @@ __global__ void __launch_bounds__(256, DHP == 64 ? 2 : 1) attn_bwd_dkv_bf16_kern
   const bool kok = ki < p.Nk;
   const bf16* qb = (const bf16*)p.q + (size_t)b * p.Nq * p.ldq + h * p.dh;
   const bf16* dob = (const bf16*)p.dout + (size_t)b * p.Nq * p.lddo + h * p.dh;
+  const rsrc_t qr = make_rsrc(qb, attn_slice_bytes(p.Nq, p.ldq, p.dh));
+  const rsrc_t dr = make_rsrc(dob, attn_slice_bytes(p.Nq, p.lddo, p.dh));
   const bf16* krow = (const bf16*)p.k + ((size_t)b * p.Nk + ki) * p.ldk + h * p.dh;
   const bf16* vrow = (const bf16*)p.v + ((size_t)b * p.Nk + ki) * p.ldv + h * p.dh;
   const float* lse_b = p.lse + ((size_t)b * p.H + h) * p.Nq;
   const float* dlt_b = p.delta + ((size_t)b * p.H + h) * p.Nq;
+
+  // this workgroup's share of the 64-query tiles
+  const int nqt_all = (p.Nq + 63) / 64, tps = (nqt_all + p.qsplits - 1) / p.qsplits;
+  const int qt0 = qs * tps, nqt = min(nqt_all, qt0 + tps);
+  AttnFragOff<DHP> fo;
+  fo.init(lane);
+  AttnTileCopy<DHP> cq, cd;
+  cq.init(wave, lane, p.ldq, p.dh);
+  cd.init(wave, lane, p.lddo, p.dh);
+  if (qt0 < nqt) {
+    cq.issue(qr, qt0 * 64, p.ldq, Qs[0], wave);
+    cd.issue(dr, qt0 * 64, p.lddo, Ds[0], wave);
+  }
+  float r_lse = 0.f, r_dlt = 0.f;
+  auto load_stats = [&](int qt) {
+    if (tid < 64) {
+      const int qi = qt * 64 + tid;
+      r_lse = qi < p.Nq ? lse_b[qi] * LOG2E : INFINITY;
+      r_dlt = qi < p.Nq ? dlt_b[qi] : 0.f;
+    }
+  };
+  auto store_stats = [&](int buf) {
+    if (tid < 64) { lse_s[buf][tid] = r_lse; dlt_s[buf][tid] = r_dlt; }
+  };
+  load_stats(qt0);
 
   bf16x8 kf[KC], vf[KC];
 #pragma unroll
@@ -599,35 +481,16 @@ __global__ void __launch_bounds__(256, DHP == 64 ? 2 : 1) attn_bwd_dkv_bf16_kern
 #pragma unroll
     for (int r = 0; r < 16; ++r) { dkacc[i][r] = 0.f; dvacc[i][r] = 0.f; }
 
-  // this workgroup's share of the 64-query tiles
-  const int nqt_all = (p.Nq + 63) / 64, tps = (nqt_all + p.qsplits - 1) / p.qsplits;
-  const int qt0 = qs * tps, nqt = min(nqt_all, qt0 + tps);
-  TileLoader<DHP, 256> lq, ld_;
-  float r_lse = 0.f, r_dlt = 0.f;
-  auto load_stats = [&](int qt) {
-    if (tid < 64) {
-      const int qi = qt * 64 + tid;
-      r_lse = qi < p.Nq ? lse_b[qi] * LOG2E : INFINITY;
-      r_dlt = qi < p.Nq ? dlt_b[qi] : 0.f;
-    }
-  };
-  auto store_stats = [&](int buf) {
-    if (tid < 64) { lse_s[buf][tid] = r_lse; dlt_s[buf][tid] = r_dlt; }
-  };
-  lq.load(qb, p.ldq, qt0 * 64, p.Nq, p.dh, tid);
-  ld_.load(dob, p.lddo, qt0 * 64, p.Nq, p.dh, tid);
-  load_stats(qt0);
-  lq.store(Qs[0], LD, tid);
-  ld_.store(Ds[0], LD, tid);
   store_stats(0);
+  wait_vmcnt<0>();
   __syncthreads();
 
   for (int qt = qt0; qt < nqt; ++qt) {
     const int buf = (qt - qt0) & 1;
     const bool more = qt + 1 < nqt;
     if (more) {
-      lq.load(qb, p.ldq, (qt + 1) * 64, p.Nq, p.dh, tid);
-      ld_.load(dob, p.lddo, (qt + 1) * 64, p.Nq, p.dh, tid);
+      cq.issue(qr, (qt + 1) * 64, p.ldq, Qs[buf ^ 1], wave);
+      cd.issue(dr, (qt + 1) * 64, p.lddo, Ds[buf ^ 1], wave);
       load_stats(qt + 1);
     }
 #pragma unroll
@@ -637,10 +500,8 @@ __global__ void __launch_bounds__(256, DHP == 64 ? 2 : 1) attn_bwd_dkv_bf16_kern
       for (int r = 0; r < 16; ++r) { s[r] = 0.f; dp[r] = 0.f; }
 #pragma unroll
       for (int c = 0; c < KC; ++c) {
-        bf16x8 qa = *reinterpret_cast<const bf16x8*>(&Qs[buf][(32 * t + l32) * LD + 16 * c + 8 * g]);
-        bf16x8 da = *reinterpret_cast<const bf16x8*>(&Ds[buf][(32 * t + l32) * LD + 16 * c + 8 * g]);
-        s = mfma32(qa, kf[c], s);
-        dp = mfma32(da, vf[c], dp);
+        s = mfma32(fo.row_frag(Qs[buf], t, c), kf[c], s);
+        dp = mfma32(fo.row_frag(Ds[buf], t, c), vf[c], dp);
       }
       f32x16 ds;
 #pragma unroll
@@ -663,18 +524,13 @@ __global__ void __launch_bounds__(256, DHP == 64 ? 2 : 1) attn_bwd_dkv_bf16_kern
         const bf16x8 dsf = pack8(ds, 8 * cc);
 #pragma unroll
         for (int i = 0; i < DT; ++i) {
-          bf16x8 da = frag_from_mc_accorder(&Ds[buf][(32 * t + 16 * cc) * LD + 32 * i], LD, lane);
-          bf16x8 qa = frag_from_mc_accorder(&Qs[buf][(32 * t + 16 * cc) * LD + 32 * i], LD, lane);
-          dvacc[i] = mfma32(da, pf, dvacc[i]);
-          dkacc[i] = mfma32(qa, dsf, dkacc[i]);
+          dvacc[i] = mfma32(fo.tr_frag(Ds[buf], 32 * t + 16 * cc, i), pf, dvacc[i]);
+          dkacc[i] = mfma32(fo.tr_frag(Qs[buf], 32 * t + 16 * cc, i), dsf, dkacc[i]);
         }
       }
     }
-    if (more) {
-      lq.store(Qs[buf ^ 1], LD, tid);
-      ld_.store(Ds[buf ^ 1], LD, tid);
-      store_stats(buf ^ 1);
-    }
+    if (more) store_stats(buf ^ 1);
+    wait_vmcnt<0>();
     __syncthreads();
   }
   if (kok && p.qsplits > 1) {
@@ -710,302 +566,6 @@ __global__ void __launch_bounds__(256, DHP == 64 ? 2 : 1) attn_bwd_dkv_bf16_kern
           *reinterpret_cast<bf16x4*>(dkb + col) = ok_;
           *reinterpret_cast<bf16x4*>(dvb + col) = ov;
         }
-      }
-  }
-}
-
-// ------------------------------------------------------------------ backward for d_head = 64, tiles copied global -> LDS
-// Both backward kernels read a streamed tile two ways (by rows as an MFMA A operand, and through the
-// transposing load), so one chunk permutation has to keep both conflict-free: position = chunk ^ key,
-// key = row bits (0, 2, 1) -- a bijection of row & 7 (8 consecutive rows of a row-fragment read land in
-// 8 different positions) whose bit 2 is row bit 1 (the 4 rows of a transposing read fall into 4
-// different 64-byte bank groups).
-__device__ __forceinline__ int attn_ukey(int row) { return (row & 1) | ((row & 4) >> 1) | ((row & 2) << 1); }
-
-// This wave's share of a [64 x 64] tile copy: rows 16 * wave .. + 15 in two 8-row pieces.
-struct AttnTileCopy {
-  uint32_t off[2];
-  __device__ __forceinline__ void init(int wave, int lane, int ld) {
-#pragma unroll
-    for (int j = 0; j < 2; ++j) {
-      const int row = 16 * wave + 8 * j + (lane >> 3);
-      off[j] = (uint32_t)(row * ld + 8 * ((lane & 7) ^ attn_ukey(row))) * 2u;
-    }
-  }
-  // rows row0 .. row0 + 63 of the (batch, head) slice behind r; rows past its end read as zeros
-  __device__ __forceinline__ void issue(rsrc_t r, int row0, int ld, bf16* stage, int wave) const {
-#pragma unroll
-    for (int j = 0; j < 2; ++j)
-      async_copy_16B_buf(r, off[j] + (uint32_t)row0 * (uint32_t)ld * 2u, 0, stage + (16 * wave + 8 * j) * 64);
-  }
-};
-// Per-lane element offsets of the fragment reads, computed once: a row fragment of rows 32 * t + l32 is at
-// row[c] + 32 * 64 * t, a transposed fragment (the slot order of frag_from_mc_accorder) of rows r0 .. r0 + 15
-// (r0 a multiple of 16, which leaves the keys alone), columns 32 * i .. + 31, at tr[i] + 64 * r0 and 8 rows below.
-struct AttnFragOff {
-  int row[4], tr[2];
-  __device__ __forceinline__ void init(int lane) {
-    const int g = lane >> 5, l32 = lane & 31, b = lane >> 4, j = lane & 15;
-#pragma unroll
-    for (int c = 0; c < 4; ++c) row[c] = l32 * 64 + 8 * ((2 * c + g) ^ attn_ukey(l32));
-    const int r = 4 * (b >> 1) + (j >> 2);
-#pragma unroll
-    for (int i = 0; i < 2; ++i) tr[i] = r * 64 + 8 * ((4 * i + 2 * (b & 1) + ((j & 3) >> 1)) ^ attn_ukey(r)) + 4 * (j & 1);
-  }
-};
-__device__ __forceinline__ bf16x8 attn_row_frag(const bf16* tile, const AttnFragOff& f, int t, int c) {
-  return *reinterpret_cast<const bf16x8*>(tile + f.row[c] + 32 * 64 * t);
-}
-__device__ __forceinline__ bf16x8 attn_tr_frag(const bf16* tile, const AttnFragOff& f, int r0, int i) {
-  const bf16* a0 = tile + f.tr[i] + 64 * r0;
-  const bf16x4 lo = lds_read_tr(a0);
-  const bf16x4 hi = lds_read_tr(a0 + 8 * 64);
-  return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-}
-
-__global__ void __launch_bounds__(256, 3) attn_bwd_dq_dtl_kernel(const AttnK p) {
-  constexpr int KC = 4, DT = 2, TILE = 64 * 64;
-  __shared__ __attribute__((aligned(1024))) bf16 Ks[2][TILE];
-  __shared__ __attribute__((aligned(1024))) bf16 Vs[2][TILE];
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 5, l32 = lane & 31;
-  int qtile, bh;
-  attn_block_map(blockIdx.x, (p.Nq + 127) / 128, p.B * p.H, qtile, bh);
-  const int b = bh / p.H, h = bh % p.H;
-  const int qi = qtile * 128 + wave * 32 + l32;
-  const bool qok = qi < p.Nq;
-  const bf16* kb = (const bf16*)p.k + (size_t)b * p.Nk * p.ldk + h * 64;
-  const bf16* vb = (const bf16*)p.v + (size_t)b * p.Nk * p.ldv + h * 64;
-  const rsrc_t kr = make_rsrc(kb, (uint32_t)(((size_t)(p.Nk - 1) * p.ldk + 64) * 2));
-  const rsrc_t vr = make_rsrc(vb, (uint32_t)(((size_t)(p.Nk - 1) * p.ldv + 64) * 2));
-  const bf16* qrow = (const bf16*)p.q + ((size_t)b * p.Nq + qi) * p.ldq + h * 64;
-  const bf16* dorow = (const bf16*)p.dout + ((size_t)b * p.Nq + qi) * p.lddo + h * 64;
-
-  AttnFragOff fo;
-  fo.init(lane);
-  AttnTileCopy ck, cv;
-  ck.init(wave, lane, p.ldk);
-  cv.init(wave, lane, p.ldv);
-  ck.issue(kr, 0, p.ldk, Ks[0], wave);
-  cv.issue(vr, 0, p.ldv, Vs[0], wave);
-
-  bf16x8 qf[KC], dof[KC];
-#pragma unroll
-  for (int c = 0; c < KC; ++c) {
-    qf[c] = ld8(qrow + 16 * c + 8 * g, qok);
-    dof[c] = ld8(dorow + 16 * c + 8 * g, qok);
-  }
-  const size_t sidx = ((size_t)b * p.H + h) * p.Nq + qi;
-  const float lse2 = qok ? p.lse[sidx] * LOG2E : INFINITY;
-  // delta = rowsum(dO * O) from the dO fragments the lane holds (lane ^ 32 has the other half of the
-  // head dimension); stored for the dK/dV kernel, which runs after this one on the same stream
-  float dlt = 0.f;
-  {
-    const bf16* orow = (const bf16*)p.o + ((size_t)b * p.Nq + qi) * p.ldo + h * 64;
-#pragma unroll
-    for (int c = 0; c < KC; ++c) {
-      const bf16x8 of = ld8(orow + 16 * c + 8 * g, qok);
-#pragma unroll
-      for (int u = 0; u < 8; ++u) dlt = fmaf((float)of[u], (float)dof[c][u], dlt);
-    }
-    dlt += __shfl_xor(dlt, 32, 64);
-    if (qok && g == 0) p.delta[sidx] = dlt;
-  }
-  f32x16 acc[DT];
-#pragma unroll
-  for (int i = 0; i < DT; ++i)
-#pragma unroll
-    for (int r = 0; r < 16; ++r) acc[i][r] = 0.f;
-
-  const int nkt = (p.Nk + 63) / 64;
-  wait_vmcnt<0>();
-  __syncthreads();
-  for (int kt = 0; kt < nkt; ++kt) {
-    const int buf = kt & 1;
-    if (kt + 1 < nkt) {      // stage buf ^ 1 was left by every wave at the barrier ending the previous iteration
-      ck.issue(kr, (kt + 1) * 64, p.ldk, Ks[buf ^ 1], wave);
-      cv.issue(vr, (kt + 1) * 64, p.ldv, Vs[buf ^ 1], wave);
-    }
-    // keys past Nk need no masking: their K and V rows are zero in LDS, so dP = 0 and the finite dS
-    // they get multiplies a zero K row in the dQ product
-#pragma unroll
-    for (int t = 0; t < 2; ++t) {
-      f32x16 s, dp;
-#pragma unroll
-      for (int r = 0; r < 16; ++r) { s[r] = 0.f; dp[r] = 0.f; }
-#pragma unroll
-      for (int c = 0; c < KC; ++c) {
-        s = mfma32(attn_row_frag(Ks[buf], fo, t, c), qf[c], s);
-        dp = mfma32(attn_row_frag(Vs[buf], fo, t, c), dof[c], dp);
-      }
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const float pr = __builtin_amdgcn_exp2f(fmaf(s[r], p.scale_log2, -lse2));
-        s[r] = pr * (dp[r] - dlt);
-      }
-#pragma unroll
-      for (int cc = 0; cc < 2; ++cc) {
-        const bf16x8 dsf = pack8(s, 8 * cc);
-#pragma unroll
-        for (int i = 0; i < DT; ++i) acc[i] = mfma32(attn_tr_frag(Ks[buf], fo, 32 * t + 16 * cc, i), dsf, acc[i]);
-      }
-    }
-    wait_vmcnt<0>();
-    __syncthreads();
-  }
-  if (qok) {
-    bf16* ob = (bf16*)p.dq + ((size_t)b * p.Nq + qi) * p.lddq + h * 64;
-#pragma unroll
-    for (int i = 0; i < DT; ++i)
-#pragma unroll
-      for (int r4 = 0; r4 < 4; ++r4) {
-        bf16x4 o;
-#pragma unroll
-        for (int u = 0; u < 4; ++u) o[u] = (bf16)(acc[i][4 * r4 + u] * p.scale);
-        *reinterpret_cast<bf16x4*>(ob + 32 * i + 8 * r4 + 4 * g) = o;
-      }
-  }
-}
-
-__global__ void __launch_bounds__(256, 2) attn_bwd_dkv_dtl_kernel(const AttnK p) {
-  constexpr int KC = 4, DT = 2, TILE = 64 * 64;
-  __shared__ __attribute__((aligned(1024))) bf16 Qs[2][TILE];
-  __shared__ __attribute__((aligned(1024))) bf16 Ds[2][TILE];
-  __shared__ __attribute__((aligned(16))) float lse_s[2][64];
-  __shared__ __attribute__((aligned(16))) float dlt_s[2][64];
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 5, l32 = lane & 31;
-  int ktile, bh;
-  const int qs = blockIdx.x % p.qsplits;
-  attn_block_map(blockIdx.x / p.qsplits, (p.Nk + 127) / 128, p.B * p.H, ktile, bh);
-  const int b = bh / p.H, h = bh % p.H;
-  const int ki = ktile * 128 + wave * 32 + l32;
-  const bool kok = ki < p.Nk;
-  const bf16* qb = (const bf16*)p.q + (size_t)b * p.Nq * p.ldq + h * 64;
-  const bf16* dob = (const bf16*)p.dout + (size_t)b * p.Nq * p.lddo + h * 64;
-  const rsrc_t qr = make_rsrc(qb, (uint32_t)(((size_t)(p.Nq - 1) * p.ldq + 64) * 2));
-  const rsrc_t dr = make_rsrc(dob, (uint32_t)(((size_t)(p.Nq - 1) * p.lddo + 64) * 2));
-  const bf16* krow = (const bf16*)p.k + ((size_t)b * p.Nk + ki) * p.ldk + h * 64;
-  const bf16* vrow = (const bf16*)p.v + ((size_t)b * p.Nk + ki) * p.ldv + h * 64;
-  const float* lse_b = p.lse + ((size_t)b * p.H + h) * p.Nq;
-  const float* dlt_b = p.delta + ((size_t)b * p.H + h) * p.Nq;
-
-  // this workgroup's share of the 64-query tiles
-  const int nqt_all = (p.Nq + 63) / 64, tps = (nqt_all + p.qsplits - 1) / p.qsplits;
-  const int qt0 = qs * tps, nqt = min(nqt_all, qt0 + tps);
-  AttnFragOff fo;
-  fo.init(lane);
-  AttnTileCopy cq, cd;
-  cq.init(wave, lane, p.ldq);
-  cd.init(wave, lane, p.lddo);
-  if (qt0 < nqt) {
-    cq.issue(qr, qt0 * 64, p.ldq, Qs[0], wave);
-    cd.issue(dr, qt0 * 64, p.lddo, Ds[0], wave);
-  }
-  float r_lse = 0.f, r_dlt = 0.f;
-  auto load_stats = [&](int qt) {
-    if (tid < 64) {
-      const int qi = qt * 64 + tid;
-      r_lse = qi < p.Nq ? lse_b[qi] * LOG2E : INFINITY;
-      r_dlt = qi < p.Nq ? dlt_b[qi] : 0.f;
-    }
-  };
-  auto store_stats = [&](int buf) {
-    if (tid < 64) { lse_s[buf][tid] = r_lse; dlt_s[buf][tid] = r_dlt; }
-  };
-  load_stats(qt0);
-
-  bf16x8 kf[KC], vf[KC];
-#pragma unroll
-  for (int c = 0; c < KC; ++c) {
-    kf[c] = ld8(krow + 16 * c + 8 * g, kok);
-    vf[c] = ld8(vrow + 16 * c + 8 * g, kok);
-  }
-  f32x16 dkacc[DT], dvacc[DT];
-#pragma unroll
-  for (int i = 0; i < DT; ++i)
-#pragma unroll
-    for (int r = 0; r < 16; ++r) { dkacc[i][r] = 0.f; dvacc[i][r] = 0.f; }
-
-  store_stats(0);
-  wait_vmcnt<0>();
-  __syncthreads();
-
-  for (int qt = qt0; qt < nqt; ++qt) {
-    const int buf = (qt - qt0) & 1;
-    const bool more = qt + 1 < nqt;
-    if (more) {
-      cq.issue(qr, (qt + 1) * 64, p.ldq, Qs[buf ^ 1], wave);
-      cd.issue(dr, (qt + 1) * 64, p.lddo, Ds[buf ^ 1], wave);
-      load_stats(qt + 1);
-    }
-#pragma unroll
-    for (int t = 0; t < 2; ++t) {
-      f32x16 s, dp;
-#pragma unroll
-      for (int r = 0; r < 16; ++r) { s[r] = 0.f; dp[r] = 0.f; }
-#pragma unroll
-      for (int c = 0; c < KC; ++c) {
-        s = mfma32(attn_row_frag(Qs[buf], fo, t, c), kf[c], s);
-        dp = mfma32(attn_row_frag(Ds[buf], fo, t, c), vf[c], dp);
-      }
-      f32x16 ds;
-#pragma unroll
-      for (int r4 = 0; r4 < 4; ++r4) {
-        const f32x4 l4 = *reinterpret_cast<const f32x4*>(&lse_s[buf][32 * t + 8 * r4 + 4 * g]);
-        const f32x4 d4 = *reinterpret_cast<const f32x4*>(&dlt_s[buf][32 * t + 8 * r4 + 4 * g]);
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-          const int r = 4 * r4 + u;
-          // a lane whose key is past Nk computes garbage that stays in its own accumulator columns,
-          // which are never stored; queries past Nq have lse = +inf, hence pr = 0
-          const float pr = __builtin_amdgcn_exp2f(fmaf(s[r], p.scale_log2, -l4[u]));
-          s[r] = pr;
-          ds[r] = pr * (dp[r] - d4[u]);
-        }
-      }
-#pragma unroll
-      for (int cc = 0; cc < 2; ++cc) {
-        const bf16x8 pf = pack8(s, 8 * cc);
-        const bf16x8 dsf = pack8(ds, 8 * cc);
-#pragma unroll
-        for (int i = 0; i < DT; ++i) {
-          dvacc[i] = mfma32(attn_tr_frag(Ds[buf], fo, 32 * t + 16 * cc, i), pf, dvacc[i]);
-          dkacc[i] = mfma32(attn_tr_frag(Qs[buf], fo, 32 * t + 16 * cc, i), dsf, dkacc[i]);
-        }
-      }
-    }
-    if (more) store_stats(buf ^ 1);
-    wait_vmcnt<0>();
-    __syncthreads();
-  }
-  if (kok && p.qsplits > 1) {
-    // fp32 partial sums of this query range; reduced in a fixed order by attn_dkv_reduce_kernel
-    const size_t hd = (size_t)p.H * 64, rows = (size_t)p.B * p.Nk;
-    float* pk = p.dkv_partial + ((size_t)qs * rows + (size_t)b * p.Nk + ki) * hd + h * 64;
-    float* pv = pk + (size_t)p.qsplits * rows * hd;
-#pragma unroll
-    for (int i = 0; i < DT; ++i)
-#pragma unroll
-      for (int r4 = 0; r4 < 4; ++r4) {
-        const int col = 32 * i + 8 * r4 + 4 * g;
-        f32x4 ok_, ov;
-#pragma unroll
-        for (int u = 0; u < 4; ++u) { ok_[u] = dkacc[i][4 * r4 + u] * p.scale; ov[u] = dvacc[i][4 * r4 + u]; }
-        *reinterpret_cast<f32x4*>(pk + col) = ok_;
-        *reinterpret_cast<f32x4*>(pv + col) = ov;
-      }
-  } else if (kok) {
-    bf16* dkb = (bf16*)p.dk + ((size_t)b * p.Nk + ki) * p.lddk + h * 64;
-    bf16* dvb = (bf16*)p.dv + ((size_t)b * p.Nk + ki) * p.lddv + h * 64;
-#pragma unroll
-    for (int i = 0; i < DT; ++i)
-#pragma unroll
-      for (int r4 = 0; r4 < 4; ++r4) {
-        const int col = 32 * i + 8 * r4 + 4 * g;
-        bf16x4 ok_, ov;
-#pragma unroll
-        for (int u = 0; u < 4; ++u) { ok_[u] = (bf16)(dkacc[i][4 * r4 + u] * p.scale); ov[u] = (bf16)dvacc[i][4 * r4 + u]; }
-        *reinterpret_cast<bf16x4*>(dkb + col) = ok_;
-        *reinterpret_cast<bf16x4*>(dvb + col) = ov;
       }
   }
 }
@@ -1166,6 +726,9 @@ static int check_attn(const AttnArgs& a, bool bwd) {
     for (int x : lds) if (x % 8) return set_error(DP_EUNSUPPORTED, "attention(bf16): leading dims must be multiples of 8");
     const void* ps[] = {a.q, a.k, a.v, a.o, bwd ? a.dout : a.q, bwd ? a.dq : a.q, bwd ? a.dk : a.q, bwd ? a.dv : a.q};
     for (const void* x : ps) if ((uintptr_t)x % 16) return set_error(DP_EALIGN, "attention(bf16): operands must be 16-byte aligned");
+    // the tile copies address one (batch, head) slice with 32-bit byte offsets and keep bit 31 for "no data"
+    const size_t maxld = (size_t)std::max(std::max(a.ldq, a.ldk), std::max(a.ldv, bwd ? a.lddo : 8));
+    if ((size_t)std::max(a.Nq, a.Nk) * maxld * 2 >= (1ull << 31)) return set_error(DP_EUNSUPPORTED, "attention(bf16): one batch element's q / k / v rows must span less than 2 GiB");
   } else {
     if (a.d_head > F32_MAX_DH) return set_error(DP_EUNSUPPORTED, "attention(fp32): d_head > 256");
     if ((size_t)a.Nk * 4 > 60000 || (bwd && (size_t)a.Nq * 8 > 60000)) return set_error(DP_EUNSUPPORTED, "attention(fp32): sequence too long for the fp32 path");
@@ -1182,27 +745,13 @@ int launch_attn_fwd(const AttnArgs& a, hipStream_t s) {
   const double by = dtype_size(a.dtype) * (double)a.B * a.H * a.d_head * (2.0 * a.Nq + 2.0 * a.Nk);
   KScope ks(a.dtype == BF16 ? KK_ATTN_FWD : KK_ATTN_F32, fl, by, s, a.Nq, a.Nk, a.d_head);
   if (a.dtype == BF16) {
-    // two query tiles per wave halve the LDS traffic but cost occupancy; measured slower on MI355X
-    // (the kernel is bound by the softmax arithmetic, not by LDS), so one tile per wave is used
-    const bool qt2 = false;
-    dim3 grid(((a.Nq + (qt2 ? 255 : 127)) / (qt2 ? 256 : 128)) * a.B * a.H);
-    // d_head = 64 (every stage and encoder of the workloads but the DiT's 72): K / V copied straight to LDS;
-    // the copies address a (batch, head) slice with 32-bit byte offsets
-    const bool dtl = a.d_head == 64 && (size_t)a.Nk * std::max(a.ldk, a.ldv) * 2 < (1ull << 31);
-    if (dtl) {
-      if (a.causal) hipLaunchKernelGGL((attn_fwd_dtl_kernel<true>), grid, dim3(256), 0, s, k);
-      else hipLaunchKernelGGL((attn_fwd_dtl_kernel<false>), grid, dim3(256), 0, s, k);
-    } else if (a.d_head <= 64) {
-      if (qt2) {
-        if (a.causal) hipLaunchKernelGGL((attn_fwd_bf16_kernel<64, true, 2>), grid, dim3(256), 0, s, k);
-        else hipLaunchKernelGGL((attn_fwd_bf16_kernel<64, false, 2>), grid, dim3(256), 0, s, k);
-      } else {
-        if (a.causal) hipLaunchKernelGGL((attn_fwd_bf16_kernel<64, true, 1>), grid, dim3(256), 0, s, k);
-        else hipLaunchKernelGGL((attn_fwd_bf16_kernel<64, false, 1>), grid, dim3(256), 0, s, k);
-      }
+    dim3 grid(((a.Nq + 127) / 128) * a.B * a.H);
+    if (a.d_head <= 64) {
+      if (a.causal) hipLaunchKernelGGL((attn_fwd_bf16_kernel<64, true>), grid, dim3(256), 0, s, k);
+      else hipLaunchKernelGGL((attn_fwd_bf16_kernel<64, false>), grid, dim3(256), 0, s, k);
     } else {
-      if (a.causal) hipLaunchKernelGGL((attn_fwd_bf16_kernel<96, true, 1>), grid, dim3(256), 0, s, k);
-      else hipLaunchKernelGGL((attn_fwd_bf16_kernel<96, false, 1>), grid, dim3(256), 0, s, k);
+      if (a.causal) hipLaunchKernelGGL((attn_fwd_bf16_kernel<96, true>), grid, dim3(256), 0, s, k);
+      else hipLaunchKernelGGL((attn_fwd_bf16_kernel<96, false>), grid, dim3(256), 0, s, k);
     }
   } else {
     hipLaunchKernelGGL(attn_fwd_f32_kernel, dim3(a.Nq, a.B * a.H), dim3(64), (size_t)a.Nk * sizeof(float), s, k, a.causal);
@@ -1220,12 +769,9 @@ int launch_attn_bwd(const AttnArgs& a, hipStream_t s) {
     // algorithmic backward work = 2x forward, split evenly between the two kernels for accounting
     const double fl = 4.0 * a.B * a.H * (double)a.Nq * a.Nk * a.d_head;
     const double by = 2.0 * (double)a.B * a.H * a.d_head * (3.0 * a.Nq + 2.0 * a.Nk);
-    // d_head = 64: streamed tiles copied straight to LDS; a (batch, head) slice is addressed with 32-bit byte offsets
-    const bool dtl = a.d_head == 64 && (size_t)std::max(a.Nq, a.Nk) * std::max(std::max(a.ldq, a.lddo), std::max(a.ldk, a.ldv)) * 2 < (1ull << 31);
     {
       KScope ks(KK_ATTN_BWD_DQ, fl, by, s, a.Nq, a.Nk, a.d_head);
-      if (dtl) hipLaunchKernelGGL(attn_bwd_dq_dtl_kernel, gq, dim3(256), 0, s, k);
-      else if (a.d_head <= 64) hipLaunchKernelGGL(attn_bwd_dq_bf16_kernel<64>, gq, dim3(256), 0, s, k);
+      if (a.d_head <= 64) hipLaunchKernelGGL(attn_bwd_dq_bf16_kernel<64>, gq, dim3(256), 0, s, k);
       else hipLaunchKernelGGL(attn_bwd_dq_bf16_kernel<96>, gq, dim3(256), 0, s, k);
     }
     {
@@ -1241,8 +787,7 @@ int launch_attn_bwd(const AttnArgs& a, hipStream_t s) {
       dim3 gk2(gk.x * qsplit);
       {
         KScope ks(KK_ATTN_BWD_DKV, fl, by, s, a.Nq, a.Nk, a.d_head);
-        if (dtl) hipLaunchKernelGGL(attn_bwd_dkv_dtl_kernel, gk2, dim3(256), 0, s, k2);
-        else if (a.d_head <= 64) hipLaunchKernelGGL(attn_bwd_dkv_bf16_kernel<64>, gk2, dim3(256), 0, s, k2);
+        if (a.d_head <= 64) hipLaunchKernelGGL(attn_bwd_dkv_bf16_kernel<64>, gk2, dim3(256), 0, s, k2);
         else hipLaunchKernelGGL(attn_bwd_dkv_bf16_kernel<96>, gk2, dim3(256), 0, s, k2);
       }
       if (qsplit > 1) {

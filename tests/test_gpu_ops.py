@@ -93,6 +93,9 @@ ATTN_CASES = [
     (2, 3, 200, 77, 64, False, 1.0, 0.0),       # cross-attention to the 77-token context
     (2, 2, 256, 256, 72, False, 1.0, 0.0),      # DiT head width (not a multiple of the MFMA depth)
     (1, 2, 130, 130, 32, False, 1.0, 0.0),
+    (2, 1, 70, 200, 40, False, 1.0, 0.0),        # head widths that leave part of a tile row empty
+    (1, 2, 150, 90, 96, False, 1.0, 0.0),
+    (1, 3, 90, 150, 88, True, 1.0, 0.0),
     (3, 4, 77, 77, 64, True, 1.0, 0.0),         # text encoder: causal, forward only
     (2, 2, 200, 200, 64, True, 1.0, 0.0),       # causal over several key tiles: the diagonal mask meets full tiles
     # sharp softmax: logits spread over tens of log2 units, a per-row shift of up to +-80, row maxima
