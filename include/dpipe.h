@@ -438,7 +438,10 @@ int dp_op_gemm_static(int dtype, const void* A, int lda, int a_kmajor, const voi
 /* dp_op_attention_fwd / _bwd: per (batch, head) O = softmax(Q K^T * scale [causal]) V.
  * Element (b, n, h, t) of a tensor X is X[(b * rows + n) * ldX + h * d_head + t], so Q, K, V may
  * be column blocks of one fused projection output.  lse: fp32 [B, H, Nq] (written by fwd, read
- * by bwd).  delta: fp32 [B, H, Nq] scratch.  The backward does not support the causal mask. */
+ * by bwd).  delta: fp32 [B, H, Nq] scratch.  The backward does not support the causal mask.
+ * bf16: d_head a multiple of 8, at most 96; leading dimensions multiples of 8; operands 16-byte aligned;
+ * one batch element's rows of any operand span less than 2 GiB (max(Nq, Nk) * ld * 2 < 2^31), else
+ * DP_EUNSUPPORTED.  All of this is checked before anything is launched. */
 int dp_op_attention_fwd(int dtype, int B, int H, int Nq, int Nk, int d_head, int causal, float scale, const void* q, int ldq,
                         const void* k, int ldk, const void* v, int ldv, void* o, int ldo, float* lse, void* hip_stream);
 int dp_op_attention_bwd(int dtype, int B, int H, int Nq, int Nk, int d_head, float scale, const void* q, int ldq, const void* k,

@@ -116,6 +116,24 @@ def test_null_misaligned_and_small_workspace_are_rejected_before_launch(dp):
     assert call(n=8, wsb=wsb) == -3     # workspace sized for 4 samples
 
 
+def test_attention_arguments_are_checked_before_launch(dp):
+    """The bf16 attention kernels address one batch element's rows with 32-bit byte offsets: a slice of 2 GiB
+    or more, a head width they do not cover, a leading dimension or pointer off the 16-byte grid are all
+    refused by the host check (no GPU needed: nothing is launched)."""
+    lib = dp.load_library()
+    p = C.c_void_p(0x10000)
+    lse = C.c_void_p(0x20000)
+    fwd = lambda **k: lib.dp_op_attention_fwd(dp.DP_BF16, 1, k.get("H", 2), k.get("Nq", 128), k.get("Nk", 128), k.get("dh", 64), 0, C.c_float(0.125),
+                                              k.get("q", p), k.get("ld", 128), p, k.get("ld", 128), p, k.get("ld", 128), p, k.get("ld", 128), lse, None)
+    assert fwd(dh=104, ld=208) == -2 and fwd(dh=60, ld=120) == -2          # head width
+    assert fwd(ld=132) == -2                                                # leading dimension not a multiple of 8
+    assert fwd(ld=120) == -1                                                # ... or smaller than heads * d_head
+    assert fwd(q=C.c_void_p(0x10008)) == -4                                 # alignment
+    assert fwd(Nk=1 << 22, ld=256) == -2                                    # 2^22 rows * 256 * 2 bytes = 2 GiB
+    assert b"2 GiB" in lib.dp_last_error()
+    assert fwd(Nq=0) == -1
+
+
 def test_fusion_mask_range(dp):
     st = dp.Stage(0, 1, 1, 1, 64, 64, 1, 64, 8, 64, 64)
     for m in (0, 1, 2, 3):
