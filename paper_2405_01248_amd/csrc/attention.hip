@@ -420,8 +420,9 @@ __global__ void __launch_bounds__(256, DHP == 64 ? 4 : 2) attn_bwd_dq_bf16_kerne
 
 // ------------------------------------------------------------------ dK, dV (bf16)
 // grid.x = ceil(Nk / 128) * qsplits; each wave owns 32 keys and walks its share of the query tiles.
-template <int DHP>
-__global__ void __launch_bounds__(256, 2) attn_bwd_dkv_bf16_kernel(const AttnK p) {
+// MINW: waves per SIMD the register allocation aims at (3 costs d_head 64 a few spilled address registers).
+template <int DHP, int MINW>
+__global__ void __launch_bounds__(256, MINW) attn_bwd_dkv_bf16_kernel(const AttnK p) {
   constexpr int KC = DHP / 16, DT = DHP / 32, TILE = 64 * DHP;
   __shared__ __attribute__((aligned(1024))) bf16 Qs[2][TILE];
   __shared__ __attribute__((aligned(1024))) bf16 Ds[2][TILE];
@@ -787,8 +788,12 @@ int launch_attn_bwd(const AttnArgs& a, hipStream_t s) {
       dim3 gk2(gk.x * qsplit);
       {
         KScope ks(KK_ATTN_BWD_DKV, fl, by, s, a.Nq, a.Nk, a.d_head);
-        if (a.d_head <= 64) hipLaunchKernelGGL(attn_bwd_dkv_bf16_kernel<64>, gk2, dim3(256), 0, s, k2);
-        else hipLaunchKernelGGL(attn_bwd_dkv_bf16_kernel<96>, gk2, dim3(256), 0, s, k2);
+        // Two workgroups per CU hold 512 at a time; a larger grid gains more from a third resident workgroup
+        // than the tighter register budget costs (1024 tokens, 640 workgroups: 120 -> 110 us for the whole
+        // backward), a smaller one only pays for it (77 keys: 43 -> 46 us)
+        if (a.d_head <= 64 && qsplit == 1 && gk.x > 2 * 256) hipLaunchKernelGGL((attn_bwd_dkv_bf16_kernel<64, 3>), gk2, dim3(256), 0, s, k2);
+        else if (a.d_head <= 64) hipLaunchKernelGGL((attn_bwd_dkv_bf16_kernel<64, 2>), gk2, dim3(256), 0, s, k2);
+        else hipLaunchKernelGGL((attn_bwd_dkv_bf16_kernel<96, 2>), gk2, dim3(256), 0, s, k2);
       }
       if (qsplit > 1) {
         const size_t rows = (size_t)a.B * a.Nk; const int hd = a.H * a.d_head;
