@@ -57,28 +57,34 @@ __device__ __forceinline__ double wave_sum_f64(double v) {
   return v;
 }
 
-// Pass 2: one wave per (sample, group) adds the partial sums of the group's channels over all blocks in
-// double precision (lane-strided, then a fixed butterfly) and writes, per channel, the scale and shift of
-// the normalisation: y = x * ab[0] + ab[1] with ab[0] = rstd * gamma, ab[1] = beta - mean * rstd * gamma.
+// Pass 2: one workgroup per (sample, group) adds the partial sums of the group's channels over all blocks in
+// double precision (thread-strided, a fixed butterfly inside each wave, the four waves in ascending order) and
+// writes, per channel, the scale and shift of the normalisation: y = x * ab[0] + ab[1] with
+// ab[0] = rstd * gamma, ab[1] = beta - mean * rstd * gamma.  (A single wave per pair left the 256 pairs of an
+// 8-sample call with one wave per CU walking up to 64 dependent strided loads each: 12 us on average.)
 __global__ void __launch_bounds__(256) gn_finalize_kernel(const float* __restrict__ partial, int nblocks, int HW, int C, int groups,
                                                           float eps, const bf16* __restrict__ gamma, const bf16* __restrict__ beta,
                                                           float* __restrict__ ab, int B) {
-  const int lane = threadIdx.x & 63, wg = blockIdx.x * 4 + (threadIdx.x >> 6);
-  if (wg >= B * groups) return;
+  __shared__ double red[2][4];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, wg = blockIdx.x;
   const int b = wg / groups, g = wg % groups, cpg = C / groups;
   double s = 0.0, q = 0.0;
   const int n = nblocks * cpg;
-  for (int i = lane; i < n; i += 64) {
+  for (int i = tid; i < n; i += 256) {
     const int blk = i / cpg, c = g * cpg + i % cpg;
     const float* pp = partial + (((size_t)b * nblocks + blk) * C + c) * 2;
     s += (double)pp[0]; q += (double)pp[1];
   }
   s = wave_sum_f64(s); q = wave_sum_f64(q);
+  if (lane == 0) { red[0][wave] = s; red[1][wave] = q; }
+  __syncthreads();
+  s = ((red[0][0] + red[0][1]) + red[0][2]) + red[0][3];
+  q = ((red[1][0] + red[1][1]) + red[1][2]) + red[1][3];
   const double cnt = (double)HW * cpg, mean = s / cnt;
   double var = q / cnt - mean * mean;
   var = var > 0.0 ? var : 0.0;
   const double rstd = 1.0 / sqrt(var + (double)eps);
-  for (int c = lane; c < cpg; c += 64) {
+  for (int c = tid; c < cpg; c += 256) {
     const int ch = g * cpg + c;
     const double a = rstd * (double)(float)gamma[ch];
     ab[((size_t)b * C + ch) * 2] = (float)a;
@@ -140,7 +146,7 @@ int launch_groupnorm(const GroupNormArgs& a, hipStream_t s) {
   const bool ready = a.ready_partial != nullptr && a.ready_blocks > 0;
   KScope ks(KK_GROUPNORM, 0.0, ready ? bytes - 2.0 * (double)a.B * a.HW * a.C : bytes, s, a.B * a.HW, a.C, a.groups);
   if (!ready) hipLaunchKernelGGL(gn_partial_kernel, dim3(nb, a.B), dim3(GN_THREADS), 0, s, (const bf16*)a.x, a.HW, a.C, ppb, partial);
-  hipLaunchKernelGGL(gn_finalize_kernel, dim3((a.B * a.groups + 3) / 4), dim3(256), 0, s, ready ? a.ready_partial : partial, ready ? a.ready_blocks : nb,
+  hipLaunchKernelGGL(gn_finalize_kernel, dim3(a.B * a.groups), dim3(256), 0, s, ready ? a.ready_partial : partial, ready ? a.ready_blocks : nb,
                      a.HW, a.C, a.groups, a.eps, (const bf16*)a.gamma, (const bf16*)a.beta, ab, a.B);
   const size_t chunks = (size_t)a.B * a.HW * (a.C / 8);
   hipLaunchKernelGGL(gn_apply_kernel, dim3((unsigned)((chunks + 255) / 256)), dim3(256), 0, s, (const bf16*)a.x, (bf16*)a.y, ab, (size_t)a.HW,
