@@ -51,6 +51,21 @@ __global__ void __launch_bounds__(256) ln_fwd_kernel(int rows, int d, float eps,
   const TX* xr = x + (size_t)row * d;
   float v[LN_MAXCH][V];
   float s = 0.f;
+  // gain and shift are fetched together with the row, not after the two reductions: on a few rows the kernel's
+  // time is its chain of memory round trips
+  using VT = typename Vec<T>::type;
+  VT ga[LN_MAXCH], sh[LN_MAXCH];
+  const size_t mrow = scale ? (size_t)(row / rows_per_batch) * mod_ld : 0;
+  const T* gsrc = scale ? scale + mrow : gamma;
+  const T* ssrc = scale ? shift + mrow : beta;
+#pragma unroll
+  for (int c = 0; c < LN_MAXCH; ++c) {
+    const int col = (c * 64 + lane) * V;
+    if (col < d && gsrc) {
+      ga[c] = *reinterpret_cast<const VT*>(gsrc + col);
+      sh[c] = *reinterpret_cast<const VT*>(ssrc + col);
+    }
+  }
 #pragma unroll
   for (int c = 0; c < LN_MAXCH; ++c) {
     const int col = (c * 64 + lane) * V;
@@ -77,22 +92,17 @@ __global__ void __launch_bounds__(256) ln_fwd_kernel(int rows, int d, float eps,
     if (mean) mean[row] = mu;
     if (rstd) rstd[row] = rs;
   }
-  const size_t mrow = scale ? (size_t)(row / rows_per_batch) * mod_ld : 0;
 #pragma unroll
   for (int c = 0; c < LN_MAXCH; ++c) {
     const int col = (c * 64 + lane) * V;
     if (col < d) {
-      float o[V], a[V], b[V];
+      float o[V];
       if (scale) {
-        load_vec<T>(scale + mrow + col, a);
-        load_vec<T>(shift + mrow + col, b);
 #pragma unroll
-        for (int i = 0; i < V; ++i) o[i] = v[c][i] * rs * (1.0f + a[i]) + b[i];
+        for (int i = 0; i < V; ++i) o[i] = v[c][i] * rs * (1.0f + to_f<T>(ga[c][i])) + to_f<T>(sh[c][i]);
       } else if (gamma) {
-        load_vec<T>(gamma + col, a);
-        load_vec<T>(beta + col, b);
 #pragma unroll
-        for (int i = 0; i < V; ++i) o[i] = v[c][i] * rs * a[i] + b[i];
+        for (int i = 0; i < V; ++i) o[i] = v[c][i] * rs * to_f<T>(ga[c][i]) + to_f<T>(sh[c][i]);
       } else {
 #pragma unroll
         for (int i = 0; i < V; ++i) o[i] = v[c][i] * rs;
@@ -111,6 +121,8 @@ static int ln_fwd_t(const LnArgs& a, hipStream_t s) {
 }
 
 // Split-K reduction onto the fp32 residual stream fused with the LayerNorm that follows (bf16 storage).
+// NCH: number of 512-column chunks a row spans.
+template <int NCH>
 __global__ void __launch_bounds__(256) reduce_residual_ln_kernel(int rows, int d, float eps, const float* __restrict__ partial, int splits,
                                                                  const bf16* __restrict__ bias, float* __restrict__ x, bf16* __restrict__ y,
                                                                  const bf16* __restrict__ gamma, const bf16* __restrict__ beta) {
@@ -118,37 +130,78 @@ __global__ void __launch_bounds__(256) reduce_residual_ln_kernel(int rows, int d
   const int lane = threadIdx.x & 63, row = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (row >= rows) return;
   const size_t plane = (size_t)rows * d;
-  float v[LN_MAXCH][V];
-  float s = 0.f;
+  // The partial sums are added in ascending split order (fixed summation order), but their loads are issued four
+  // planes at a time for all of the row's chunks: on a slice of a few samples the kernel runs on a few dozen
+  // workgroups and its time is the chain of memory round trips, one per plane when load and add alternate.
+  float v[NCH][V], acc[NCH][V];
+  bf16x8 bi[NCH], ga[NCH], be[NCH];     // fetched with the row, used after the reductions
+  const float* prow = partial + (size_t)row * d;
 #pragma unroll
-  for (int c = 0; c < LN_MAXCH; ++c) {
+  for (int c = 0; c < NCH; ++c) {
     const int col = (c * 64 + lane) * V;
     if (col < d) {
-      float* xr = x + (size_t)row * d + col;
-      load_f32<V>(xr, v[c]);
-      float acc[V];
-      load_f32<V>(partial + (size_t)row * d + col, acc);
-      for (int z = 1; z < splits; ++z) {                  // ascending split order: fixed summation order
-        float t[V];
-        load_f32<V>(partial + z * plane + (size_t)row * d + col, t);
+      load_f32<V>(x + (size_t)row * d + col, v[c]);
+      load_f32<V>(prow + col, acc[c]);
+      if (bias) bi[c] = *reinterpret_cast<const bf16x8*>(bias + col);
+      ga[c] = *reinterpret_cast<const bf16x8*>(gamma + col);
+      be[c] = *reinterpret_cast<const bf16x8*>(beta + col);
+    }
+  }
+  int z = 1;
+  for (; z + 3 < splits; z += 4) {
+    float t[4][NCH][V];
 #pragma unroll
-        for (int i = 0; i < V; ++i) acc[i] += t[i];
+    for (int u = 0; u < 4; ++u)
+#pragma unroll
+      for (int c = 0; c < NCH; ++c) {
+        const int col = (c * 64 + lane) * V;
+        if (col < d) load_f32<V>(prow + (size_t)(z + u) * plane + col, t[u][c]);
       }
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+#pragma unroll
+      for (int c = 0; c < NCH; ++c) {
+        const int col = (c * 64 + lane) * V;
+        if (col < d) {
+#pragma unroll
+          for (int i = 0; i < V; ++i) acc[c][i] += t[u][c][i];
+        }
+      }
+  }
+  for (; z < splits; ++z) {
+    float t[NCH][V];
+#pragma unroll
+    for (int c = 0; c < NCH; ++c) {
+      const int col = (c * 64 + lane) * V;
+      if (col < d) load_f32<V>(prow + (size_t)z * plane + col, t[c]);
+    }
+#pragma unroll
+    for (int c = 0; c < NCH; ++c) {
+      const int col = (c * 64 + lane) * V;
+      if (col < d) {
+#pragma unroll
+        for (int i = 0; i < V; ++i) acc[c][i] += t[c][i];
+      }
+    }
+  }
+  float s = 0.f;
+#pragma unroll
+  for (int c = 0; c < NCH; ++c) {
+    const int col = (c * 64 + lane) * V;
+    if (col < d) {
       if (bias) {
-        float b[V];
-        load_vec<bf16>(bias + col, b);
 #pragma unroll
-        for (int i = 0; i < V; ++i) acc[i] += b[i];
+        for (int i = 0; i < V; ++i) acc[c][i] += (float)bi[c][i];
       }
 #pragma unroll
-      for (int i = 0; i < V; ++i) { v[c][i] += acc[i]; s += v[c][i]; }
-      store_f32<V>(xr, v[c]);
+      for (int i = 0; i < V; ++i) { v[c][i] += acc[c][i]; s += v[c][i]; }
+      store_f32<V>(x + (size_t)row * d + col, v[c]);
     }
   }
   const float mu = wave_sum(s) / d;
   float q = 0.f;
 #pragma unroll
-  for (int c = 0; c < LN_MAXCH; ++c) {
+  for (int c = 0; c < NCH; ++c) {
     const int col = (c * 64 + lane) * V;
     if (col < d) {
 #pragma unroll
@@ -157,14 +210,12 @@ __global__ void __launch_bounds__(256) reduce_residual_ln_kernel(int rows, int d
   }
   const float rs = rsqrtf(wave_sum(q) / d + eps);
 #pragma unroll
-  for (int c = 0; c < LN_MAXCH; ++c) {
+  for (int c = 0; c < NCH; ++c) {
     const int col = (c * 64 + lane) * V;
     if (col < d) {
-      float o[V], a[V], b[V];
-      load_vec<bf16>(gamma + col, a);
-      load_vec<bf16>(beta + col, b);
+      float o[V];
 #pragma unroll
-      for (int i = 0; i < V; ++i) o[i] = v[c][i] * rs * a[i] + b[i];
+      for (int i = 0; i < V; ++i) o[i] = v[c][i] * rs * (float)ga[c][i] + (float)be[c][i];
       store_vec<bf16>(y + (size_t)row * d + col, o);
     }
   }
@@ -175,8 +226,16 @@ int launch_reduce_residual_ln(const float* partial, int splits, int rows, int d,
   if (!partial || splits < 1 || rows <= 0 || !x || !y || !gamma || !beta) return set_error(DP_EINVAL, "reduce_residual_ln: bad arguments");
   if (d <= 0 || d % 8 || d > 64 * LN_MAXCH * 8) return set_error(DP_EUNSUPPORTED, "reduce_residual_ln: d must be a multiple of 8, at most 2048");
   KScope ks(KK_REDUCE, 0.0, (double)rows * d * (4.0 * splits + 8.0 + 2.0), s, rows, d, splits);
-  hipLaunchKernelGGL(reduce_residual_ln_kernel, dim3((rows + 3) / 4), dim3(256), 0, s, rows, d, eps, partial, splits, (const bf16*)bias, x,
-                     (bf16*)y, (const bf16*)gamma, (const bf16*)beta);
+  const dim3 grid((rows + 3) / 4);
+#define DP_RRLN(n_) hipLaunchKernelGGL(reduce_residual_ln_kernel<n_>, grid, dim3(256), 0, s, rows, d, eps, partial, splits, (const bf16*)bias, x, \
+                                       (bf16*)y, (const bf16*)gamma, (const bf16*)beta)
+  switch ((d + 511) / 512) {
+    case 1: DP_RRLN(1); break;
+    case 2: DP_RRLN(2); break;
+    case 3: DP_RRLN(3); break;
+    default: DP_RRLN(4); break;
+  }
+#undef DP_RRLN
   return hipGetLastError() == hipSuccess ? DP_OK : set_error(DP_EHIP, "reduce_residual_ln launch failed");
 }
 
