@@ -51,7 +51,18 @@ __global__ void __launch_bounds__(256) ln_fwd_kernel(int rows, int d, float eps,
   const TX* xr = x + (size_t)row * d;
   float v[LN_MAXCH][V];
   float s = 0.f;
-  // gain and shift are fetched together with the row, not after the two reductions: on a few rows the kernel's
+#pragma unroll
+  for (int c = 0; c < LN_MAXCH; ++c) {
+    const int col = (c * 64 + lane) * V;
+    if (col < d) {
+      if (sizeof(TX) == 4) load_f32<V>(reinterpret_cast<const float*>(xr + col), v[c]);
+      else load_vec<T>(reinterpret_cast<const T*>(xr + col), v[c]);
+      if (sizeof(TX) != 4 && x32_out) store_f32<V>(x32_out + (size_t)row * d + col, v[c]);
+#pragma unroll
+      for (int i = 0; i < V; ++i) s += v[c][i];
+    }
+  }
+  // gain and shift are fetched right behind the row, not after the two reductions: on a few rows the kernel's
   // time is its chain of memory round trips
   using VT = typename Vec<T>::type;
   VT ga[LN_MAXCH], sh[LN_MAXCH];
@@ -64,17 +75,6 @@ __global__ void __launch_bounds__(256) ln_fwd_kernel(int rows, int d, float eps,
     if (col < d && gsrc) {
       ga[c] = *reinterpret_cast<const VT*>(gsrc + col);
       sh[c] = *reinterpret_cast<const VT*>(ssrc + col);
-    }
-  }
-#pragma unroll
-  for (int c = 0; c < LN_MAXCH; ++c) {
-    const int col = (c * 64 + lane) * V;
-    if (col < d) {
-      if (sizeof(TX) == 4) load_f32<V>(reinterpret_cast<const float*>(xr + col), v[c]);
-      else load_vec<T>(reinterpret_cast<const T*>(xr + col), v[c]);
-      if (sizeof(TX) != 4 && x32_out) store_f32<V>(x32_out + (size_t)row * d + col, v[c]);
-#pragma unroll
-      for (int i = 0; i < V; ++i) s += v[c][i];
     }
   }
   const float mu = wave_sum(s) / d;
