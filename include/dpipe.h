@@ -224,9 +224,10 @@ size_t dp_image_encoder_workspace_bytes(const dp_image_encoder* enc, int layer_b
  * later call continues from `out` as its `in`.  in and out must be different buffers.  params [host]: all of the
  * encoder's parameters (only those of the layers in range are read and checked).  num_samples = 0 is a valid
  * empty slice.  Never allocates or synchronises.  A sample's result is bit-identical for every slice size and
- * offset: kernels, tile shapes and the grouping of every sum are chosen from one sample's shape, never from the
- * number of samples (as long as a layer's input for the slice stays below 2 GiB, the range of the convolution's
- * 32-bit offsets; beyond it another kernel takes over). */
+ * offset: kernels and the grouping of every sum are chosen from one sample's shape, never from the number of
+ * samples; the one choice that follows the slice size, the convolution's tile width, is between two shapes that
+ * add in the same order and give the same bits (as long as a layer's input for the slice stays below 2 GiB, the
+ * range of the convolution's 32-bit offsets; beyond it another kernel takes over). */
 int image_encoder_fwd_partial(dp_image_encoder* enc, const void* const* params, const void* in, void* out, int global_batch,
                               int layer_begin, int layer_end, int sample_offset, int num_samples, void* workspace,
                               size_t workspace_bytes, void* hip_stream);

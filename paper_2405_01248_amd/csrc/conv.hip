@@ -151,11 +151,11 @@ __global__ void __launch_bounds__(WGM * WGN * 64) conv3x3_bf16_kernel(const Conv
 // one fence-free barrier per k-tile.  A k-tile lies inside one filter tap (C_in a multiple of 64): its source
 // address is the output pixel's base address plus an offset that is the same for the whole wave, and a lane
 // whose tap falls into the padding aims its copy past the end of the buffer, which the hardware answers with
-// zeros.  256 x 128 output tile, eight waves of 64 x 64.  LDS tiles are unpadded with permuted 16-byte
+// zeros.  256 x 128 output tile, eight waves of 64 x 64 (or 256 x 256, eight waves of 128 x 64).  LDS tiles are unpadded with permuted 16-byte
 // chunks, as in the GEMM kernels: chunk c of tile row r sits at position c ^ ((r >> 1) & 7).
-template <int BK_>
+template <int BK_, int BN_ = 128>
 struct ConvDtlSmem {
-  static constexpr int BM = 256, BN = 128, BK = BK_, STAGES = 3, WGM = 4, WGN = 2;
+  static constexpr int BM = 256, BN = BN_, BK = BK_, STAGES = 3, WGM = BN_ == 256 ? 2 : 4, WGN = BN_ == 256 ? 4 : 2;
   static constexpr int A_BYTES = BM * BK * 2, B_BYTES = BN * BK * 2, STAGE = A_BYTES + B_BYTES;
   static constexpr int WN = BN / WGN, C_LD = WN + 4;
   static constexpr size_t TILE_BYTES = (size_t)STAGES * STAGE;
@@ -168,9 +168,11 @@ template <int BK> __device__ __forceinline__ int conv_key(int r) { return BK == 
 
 // BK = 64: 144 KB of LDS, one workgroup per CU.  BK = 32: 72 KB, two workgroups per CU (MINW = 4 waves per SIMD), which hide
 // each other's prologue and epilogue where the contraction is short (C_in = 128 .. 256).
-template <int BK_, int MINW>
+// BN = 256 (BK = 32, 96 KB, eight waves of 128 x 64): half the weight-tile copies and A-fragment reads per FLOP, for layers
+// with at least 256 output channels.
+template <int BK_, int MINW, int BN_ = 128>
 __global__ void __launch_bounds__(512, MINW) conv3x3_dtl_kernel(const ConvParams p, uint32_t x_bytes, uint32_t w_bytes) {
-  using S = ConvDtlSmem<BK_>;
+  using S = ConvDtlSmem<BK_, BN_>;
   constexpr int BM = S::BM, BN = S::BN, BK = S::BK, STAGES = S::STAGES, WGN = S::WGN, NW = S::WGM * S::WGN, KS = BK / 16, CPR = BK / 8;
   constexpr int WM = BM / S::WGM, WN = BN / WGN, TM = WM / 32, TN = WN / 32;
   constexpr int A_LOADS = S::A_BYTES / 1024 / NW, B_LOADS = S::B_BYTES / 1024 / NW, LOADS = A_LOADS + B_LOADS, PART_LAST = LOADS / KS;
@@ -321,13 +323,15 @@ __global__ void __launch_bounds__(512, MINW) conv3x3_dtl_kernel(const ConvParams
   }
   // Epilogue with the next GroupNorm's first pass folded in: bias, optional residual, bf16 store, and per channel the sum
   // and the sum of squares of the stored (rounded) values over this tile's 256 pixels.  A lane owns the same 8 columns in
-  // every pass over the rows; the 8 lanes with equal lane % 8 are added by a butterfly, the four waves of a column in
-  // ascending order: nothing depends on timing.
-  static_assert(WN == 64 && S::BYTES >= S::EPI_BYTES + NW * 2 * 64 * 4, "statistics slab");
+  // every pass over the rows.  The sums are formed per 64-row band (one band per wave in the 256 x 128 tile, two in the
+  // 256 x 256 one): the lane's rows in order, the 8 lanes with equal lane % 8 by a butterfly, the four bands of a column in
+  // ascending order.  Nothing depends on timing, and both tile shapes associate the additions the same way, so they
+  // produce the same bits.
+  constexpr int NH = WM / 64;       // 64-row bands per wave
+  static_assert(WN == 64 && WM % 64 == 0 && S::BYTES >= S::EPI_BYTES + (size_t)S::WGM * NH * WGN * 2 * 64 * 4, "statistics slab");
   const EpiParams<bf16>& e = p.epi;
+  float* stat = reinterpret_cast<float*>(smem_raw + S::EPI_BYTES);      // [band][wave column][sum | sum of squares][64 columns], past the slabs
   float cs[8], cq[8];
-#pragma unroll
-  for (int t = 0; t < 8; ++t) { cs[t] = 0.f; cq[t] = 0.f; }
   const int lc = (lane & 7) * 8, n = n0 + wn0 + lc;
   bf16x8 bv;
 #pragma unroll
@@ -335,6 +339,10 @@ __global__ void __launch_bounds__(512, MINW) conv3x3_dtl_kernel(const ConvParams
   if (e.bias && n < e.N) bv = *reinterpret_cast<const bf16x8*>(e.bias + n);
 #pragma unroll
   for (int i = 0; i < TM; ++i) {
+    if (i % 2 == 0) {
+#pragma unroll
+      for (int t = 0; t < 8; ++t) { cs[t] = 0.f; cq[t] = 0.f; }
+    }
 #pragma unroll
     for (int j = 0; j < TN; ++j)
 #pragma unroll
@@ -365,34 +373,40 @@ __global__ void __launch_bounds__(512, MINW) conv3x3_dtl_kernel(const ConvParams
       }
     }
     asm volatile("" ::: "memory");
-  }
+    if (i % 2 == 1) {
+      // the band is complete: lanes with equal lane % 8 hold the same columns
 #pragma unroll
-  for (int t = 0; t < 8; ++t) {
+      for (int t = 0; t < 8; ++t) {
 #pragma unroll
-    for (int o = 8; o < 64; o <<= 1) { cs[t] += __shfl_xor(cs[t], o, 64); cq[t] += __shfl_xor(cq[t], o, 64); }
-  }
-  float* stat = reinterpret_cast<float*>(smem_raw + S::EPI_BYTES);      // [wave][sum | sum of squares][64 columns], past the slabs
-  if (lane < 8) {
+        for (int o = 8; o < 64; o <<= 1) { cs[t] += __shfl_xor(cs[t], o, 64); cq[t] += __shfl_xor(cq[t], o, 64); }
+      }
+      const int band = (wave / WGN) * NH + i / 2, wcol = wave % WGN;
+      if (lane < 8) {
 #pragma unroll
-    for (int t = 0; t < 8; ++t) { stat[(wave * 2) * 64 + lane * 8 + t] = cs[t]; stat[(wave * 2 + 1) * 64 + lane * 8 + t] = cq[t]; }
+        for (int t = 0; t < 8; ++t) {
+          stat[((band * WGN + wcol) * 2) * 64 + lane * 8 + t] = cs[t];
+          stat[((band * WGN + wcol) * 2 + 1) * 64 + lane * 8 + t] = cq[t];
+        }
+      }
+    }
   }
   __syncthreads();
   if (tid < 2 * BN) {
     const int which = tid / BN, c = tid % BN, wcol = c / 64, cc = c % 64;
     float sum = 0.f;
 #pragma unroll
-    for (int wr = 0; wr < S::WGM; ++wr) sum += stat[((wr * WGN + wcol) * 2 + which) * 64 + cc];
+    for (int band = 0; band < S::WGM * NH; ++band) sum += stat[((band * WGN + wcol) * 2 + which) * 64 + cc];
     if (n0 + c < e.N) p.gn_partial[((size_t)tile_m * e.N + n0 + c) * 2 + which] = sum;
   }
 }
 
-template <int BK, int MINW>
+template <int BK, int MINW, int BN = 128>
 static int launch_conv_dtl(ConvParams& p, size_t x_bytes, size_t w_bytes, hipStream_t s) {
-  using S = ConvDtlSmem<BK>;
+  using S = ConvDtlSmem<BK, BN>;
   p.tiles_m = (p.M + S::BM - 1) / S::BM; p.tiles_n = (p.N + S::BN - 1) / S::BN;
   const long n = (long)p.tiles_m * p.tiles_n, ppx = (n + 7) / 8;
   p.group_m = (int)std::max<long>(1, std::min<long>((ppx + p.tiles_n / 2) / p.tiles_n, p.tiles_m));
-  auto kern = conv3x3_dtl_kernel<BK, MINW>;
+  auto kern = conv3x3_dtl_kernel<BK, MINW, BN>;
   if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)S::BYTES) != hipSuccess)
     return set_error(DP_EHIP, "hipFuncSetAttribute(conv) failed");
   hipLaunchKernelGGL(kern, dim3((unsigned)n), dim3(512), S::BYTES, s, p, (uint32_t)x_bytes, (uint32_t)w_bytes);
@@ -443,11 +457,18 @@ int launch_conv3x3(const ConvArgs& a, hipStream_t s) {
   KScope ks(KK_CONV, 2.0 * (double)M * p.N * p.K, by, s, p.M, p.N, p.K);
   // the direct-to-LDS kernel: k-tiles inside one tap, 32-bit byte offsets with room for the "outside" marker
   const size_t x_bytes = 2 * (size_t)a.B * a.H * a.W * a.Cin, w_bytes = 2 * (size_t)p.N * p.K;
-  // (the choice depends on one sample's pixel count, not on the number of samples: a slice of any size takes the same kernel)
+  // (whether this kernel is taken depends on one sample's pixel count, not on the number of samples)
   if (a.Cin % 64 == 0 && a.Cout >= 64 && (long)Ho * Wo >= 1024 && x_bytes < (1ull << 31) && w_bytes < (1ull << 31) && !a.force_staged) {
     if (a.gn_partial && (Ho * Wo) % 256 == 0 && ((uintptr_t)a.gn_partial % 16) == 0) { p.gn_partial = a.gn_partial; *a.gn_applied = 1; }
     // measured on the layers of the 512 x 512 encoder: C_in = 128 at stride 1 runs 18 % faster (C_out = 256: 7 %) on the
     // two-workgroups-per-CU variant; from C_in = 256 on, and at stride 2, the deeper k-tile wins
+    // 256 x 256 tiles for at least 256 output channels when they load the CUs no worse than the 256 x 128 ones: a CU's time
+    // is its number of tiles times the tile's cost, and a 256 x 128 tile costs about 0.6 of a 256 x 256 one.  This choice may
+    // depend on the number of samples: the two tile shapes produce the same bits, statistics included.
+    if (a.Cout % 256 == 0 && a.Cin >= 128) {
+      const long tw = ((M + 255) / 256) * (a.Cout / 256), cus = 256;
+      if ((double)((tw + cus - 1) / cus) <= 0.6 * (double)((2 * tw + cus - 1) / cus)) return launch_conv_dtl<32, 2, 256>(p, x_bytes, w_bytes, s);
+    }
     return (a.Cin <= 128 && a.stride == 1) ? launch_conv_dtl<32, 4>(p, x_bytes, w_bytes, s) : launch_conv_dtl<64, 2>(p, x_bytes, w_bytes, s);
   }
   if (a.Cout <= 64) return launch_conv_cfg<128, 64, 4, 1>(p, s);

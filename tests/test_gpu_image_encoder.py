@@ -45,6 +45,8 @@ SINGLE_LAYERS = [
     _one_layer("resnet", 64, 128, 1, (32, 48)),              # 64-deep k-tiles; with the 1x1 skip convolution
     _one_layer("resnet", 128, 128, 1, (32, 32), batch=2, groups=32),   # 32-deep k-tiles, two workgroups per CU
     _one_layer("resnet", 64, 192, 1, (32, 32), batch=3, groups=8),     # a half-empty output-channel tile; odd sample count
+    _one_layer("resnet", 256, 256, 1, (32, 32), batch=2, groups=32),   # 256 output channels: the 256-wide tile, two samples in one tile row
+    _one_layer("resnet", 256, 512, 1, (32, 40), batch=1, groups=32),   # ... two tiles across, ragged pixel count, 1x1 skip
 ]
 
 # The statistics handed from one layer to the next: a stride-2 convolution (the norm of the residual block that follows
@@ -84,6 +86,27 @@ def test_statistics_pass_from_layer_to_layer():
     de.run_slices(1)
     torch.cuda.synchronize()
     assert np.array_equal(de.output(), whole)
+
+
+def test_both_convolution_tile_shapes_give_the_same_bits():
+    """With 256 output channels the convolution takes 256 x 256 tiles when they load the CUs at least as well as 256 x 128
+    ones, which depends on how many samples a call covers: 16 samples of 64 x 64 pixels make 256 wide tiles (taken), 4 make
+    64 and 1 makes 16 (not taken).  Both shapes accumulate in the same order and form the GroupNorm sums per 64-row band,
+    so every slicing of the batch has to give the same bits (the second norm of the block reads the sums)."""
+    import torch
+    from paper_2405_01248_amd.harness import DeviceImageEncoder
+    cfg = si.ImageEncoderConfig("wide_and_narrow_tiles", "bf16", 64, 64, 256, 32, (("resnet", 256, 256, 1), ("resnet", 256, 512, 1)), 16)
+    inp = si.make_image_encoder_inputs(cfg, seed=5, randomize_norm=True, weight_std=0.0)
+    de = DeviceImageEncoder(cfg, inp)
+    de.run_slices(16)
+    torch.cuda.synchronize()
+    whole = de.output()
+    assert np.isfinite(whole).all() and float(np.abs(whole).max()) > 0.0
+    for b in (4, 1):
+        de.out.zero_()
+        de.run_slices(b)
+        torch.cuda.synchronize()
+        assert np.array_equal(de.output(), whole), b
 
 
 SMALL = si.ImageEncoderConfig("small_img_enc_bf16", "bf16", 24, 16, 8, 4, si.vae_encoder_layers(16, (1, 2, 2), 8, 8), 5)
